@@ -1,0 +1,233 @@
+/*
+ * mi3d — C ABI of the MI355X (gfx950) hot path for full-resolution 3D U-Net
+ * training with data swapping.
+ *
+ * Two groups of entry points:
+ *   1. mi3d_conv3d_{fwd,dgrad,wgrad}: the 3-D convolution layers whose
+ *      forward output ("feature map A^l") is produced in the forward pass and
+ *      needed again by the same layer in the backward pass (paper, Section
+ *      3.1 and Fig. 1).  The paper gives no formula (its convolutions ran in
+ *      a closed vendor library, Section 4.1); the definitions below are the
+ *      textbook ones.
+ *   2. mi3d_swap_*: the data-swapping engine (Sections 3.1-3.3): feature maps
+ *      are copied to host memory after the forward pass has used them and
+ *      copied back before the layer's backward pass, on side streams so that
+ *      the copies overlap GPU computation.
+ *
+ * General rules
+ *   - Plain C, no C++ or framework types.  `stream` arguments are a
+ *     hipStream_t passed as void* (NULL = the null stream).
+ *   - Pointers named x, w, y, dy, dx, dw, ws and every `dev_*` pointer are
+ *     DEVICE pointers, 16-byte aligned, owned by the caller.  Descriptor,
+ *     config, stats and out-parameters are HOST pointers.
+ *   - Every call returns an int status: MI3D_OK (0) or a negative error.
+ *     No call aborts or throws.  Convolution calls only enqueue work on the
+ *     given stream: they never allocate device memory and never synchronise.
+ *   - Convolution calls are re-entrant.  A swap engine must be used from one
+ *     host thread at a time.
+ */
+#ifndef MI3D_H
+#define MI3D_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    MI3D_OK = 0,
+    MI3D_ERR_INVALID_ARG = -1,      /* null pointer, non-positive size, misaligned pointer, kernel larger than padded input */
+    MI3D_ERR_UNSUPPORTED = -2,      /* no kernel for this dtype / shape */
+    MI3D_ERR_WORKSPACE = -3,        /* ws_bytes smaller than mi3d_conv3d_workspace_bytes() */
+    MI3D_ERR_HIP = -4,              /* a HIP runtime call failed; see mi3d_last_hip_error() */
+    MI3D_ERR_HOST_POOL = -5,        /* pinned host pool exhausted */
+    MI3D_ERR_OVER_BUDGET = -6,      /* no swap plan fits the device budget / arena exhausted */
+    MI3D_ERR_BAD_STATE = -7         /* unknown id, double swap-out, swap-in of a tensor that is not on the host, ... */
+};
+
+const char *mi3d_status_string(int status);
+/* hipError_t value of the most recent failing HIP call on this host thread (0 if none). */
+int mi3d_last_hip_error(void);
+
+/* ------------------------------------------------------------------------ */
+/* Convolution                                                              */
+/* ------------------------------------------------------------------------ */
+
+typedef enum { MI3D_F32 = 0, MI3D_BF16 = 1 } mi3d_dtype;
+typedef enum { MI3D_PASS_FWD = 0, MI3D_PASS_DGRAD = 1, MI3D_PASS_WGRAD = 2 } mi3d_pass;
+
+/*
+ * Geometry of one layer.
+ *   activations  NDHWC, channel fastest:        x[n][d][h][w][ci]
+ *   weights      [Cout][kD][kH][kW][Cin]:       w[co][kd][kh][kw][ci]
+ *   explicit symmetric zero padding p per side, stride s, cross-correlation
+ *   Do = floor((D + 2 pD - kD) / sD) + 1, same for Ho, Wo.
+ * dtype is the element type of x, w, y, dy and dx.  Products are accumulated
+ * in fp32 in every case; with MI3D_BF16 the results y and dx are rounded to
+ * bf16 (nearest even) once at the end.  dw is always fp32.
+ */
+typedef struct {
+    int N, D, H, W, Cin;
+    int Cout, kD, kH, kW;
+    int sD, sH, sW, pD, pH, pW;
+    int dtype; /* mi3d_dtype */
+} mi3d_conv_desc;
+
+int mi3d_conv3d_out_dims(const mi3d_conv_desc *desc, int *Do, int *Ho, int *Wo);
+
+/* Bytes of device scratch the given pass needs for this geometry (may be 0).
+ * Returns 0 for an invalid descriptor as well; the pass itself reports it. */
+size_t mi3d_conv3d_workspace_bytes(const mi3d_conv_desc *desc, int pass);
+
+/* y[n,o,co] = sum_{t,ci} x[n, o*s - p + t, ci] * w[co,t,ci]     (feature map of Section 3.1)
+ * x: N*D*H*W*Cin elements, w: Cout*kD*kH*kW*Cin, y: N*Do*Ho*Wo*Cout (fully overwritten). */
+int mi3d_conv3d_fwd(const mi3d_conv_desc *desc, const void *x, const void *w, void *y,
+                    void *ws, size_t ws_bytes, void *stream);
+
+/* dx = adjoint of the forward map with respect to x:
+ * dx[n,i,ci] = sum over (o,t,co) with o*s - p + t == i of dy[n,o,co] * w[co,t,ci].
+ * dx is fully overwritten; positions no output read receive 0. */
+int mi3d_conv3d_dgrad(const mi3d_conv_desc *desc, const void *dy, const void *w, void *dx,
+                      void *ws, size_t ws_bytes, void *stream);
+
+/* dw[co,t,ci] = sum_{n,o} dy[n,o,co] * x[n, o*s - p + t, ci]; needs the saved
+ * input x of the layer, which is why feature maps are kept (or swapped).
+ * dw (fp32, Cout*kD*kH*kW*Cin elements) is overwritten, not accumulated.
+ * The reduction order is fixed, so repeated calls give identical bits. */
+int mi3d_conv3d_wgrad(const mi3d_conv_desc *desc, const void *x, const void *dy, float *dw,
+                      void *ws, size_t ws_bytes, void *stream);
+
+/* Kernel family used for a pass: 0 = automatic choice, 1 = force the plain
+ * one-thread-per-output kernels (slow; for debugging and cross-checks).
+ * Process-wide; returns the previous value. */
+int mi3d_conv3d_set_kernel_family(int family);
+/* Writes the name of the kernel the automatic choice picks (for reports). */
+int mi3d_conv3d_kernel_name(const mi3d_conv_desc *desc, int pass, char *buf, size_t buf_len);
+
+/* ------------------------------------------------------------------------ */
+/* Data-swapping engine                                                     */
+/* ------------------------------------------------------------------------ */
+
+/*
+ * Vocabulary.  A training step is a list of ops with indices 0..n_ops-1:
+ * forward ops first, then backward ops.  A saved tensor (feature map) is
+ * produced by op `produce_op`, last read in the forward pass by op
+ * `last_fwd_use_op`, and read again by backward ops `bwd_first_use_op` ..
+ * `bwd_last_use_op`.  Between last_fwd_use_op and bwd_first_use_op it only
+ * occupies memory; that is the interval the engine can move it to the host.
+ *
+ * Planner knobs, after Section 3.2:
+ *   policy MI3D_SWAP_BUDGET   swap the smallest set that brings the peak under
+ *                             budget_bytes, earliest-produced / longest-idle /
+ *                             largest first (the heuristic of Section 3.2 that
+ *                             early feature maps are large and live long)
+ *   policy MI3D_SWAP_ALL      swap every eligible tensor          (n_tensors = -1)
+ *   policy MI3D_SWAP_FIRST_N  swap the first n_tensors eligible tensors in
+ *                             production order                    (n_tensors = N)
+ *   exclude_tags              tensors carrying any of these tag bits are never
+ *                             swapped (excl_scopes, e.g. the synthesis path)
+ *   include_tags              if non-zero, only tensors carrying one of these
+ *                             bits are eligible (incl_scopes)
+ *   lookahead                 swap-in for a tensor first used by backward op j
+ *                             is to be issued when op j - lookahead is launched
+ *                             (the `lb` knob: larger = earlier)
+ */
+enum { MI3D_SWAP_BUDGET = 0, MI3D_SWAP_ALL = 1, MI3D_SWAP_FIRST_N = 2 };
+enum { MI3D_TAG_ENCODER = 1u, MI3D_TAG_DECODER = 2u, MI3D_TAG_INPUT = 4u, MI3D_TAG_HEAD = 8u };
+
+typedef struct {
+    size_t budget_bytes;     /* device bytes the step may hold at any op (saved tensors + transients) */
+    void  *dev_arena;        /* optional device block sub-allocated by mi3d_swap_alloc(); may be NULL */
+    size_t arena_bytes;      /* size of dev_arena (0 if none) */
+    size_t host_pool_bytes;  /* pinned host memory to allocate at create (0 = planner-only engine, no HIP calls) */
+    int    lookahead;        /* >= 0 */
+    int    policy;           /* MI3D_SWAP_* */
+    int    n_tensors;        /* for MI3D_SWAP_FIRST_N */
+    unsigned exclude_tags;
+    unsigned include_tags;
+} mi3d_swap_config;
+
+typedef struct {
+    uint64_t bytes_out, bytes_in;        /* bytes copied device->host / host->device since create or reset */
+    double   copy_ms_out, copy_ms_in;    /* summed event-timed copy durations per direction (completed copies) */
+    double   busy_ms;                    /* length of the union of the copy intervals of both side streams */
+    uint64_t peak_arena_bytes;           /* high-water mark of mi3d_swap_alloc()ed bytes */
+    uint64_t planned_peak_bytes;         /* peak of the planner's residency model with the chosen swap set */
+    uint64_t unswapped_peak_bytes;       /* same model with nothing swapped */
+    int      n_registered, n_planned;    /* tensors known / chosen for swapping */
+    int      n_swapped_out, n_swapped_in;/* copies actually issued */
+} mi3d_swap_stats_t;
+
+typedef struct mi3d_swap_engine mi3d_swap_engine;
+
+/* Creates an engine on the current device.  With host_pool_bytes > 0 it
+ * allocates that much pinned host memory and two side streams (one per copy
+ * direction, default priority).  Returns MI3D_ERR_HIP if that fails. */
+int mi3d_swap_create(const mi3d_swap_config *cfg, mi3d_swap_engine **out);
+/* Waits for outstanding copies, frees the pool, streams and events. */
+int mi3d_swap_destroy(mi3d_swap_engine *e);
+
+/* Ops 0..n_fwd_ops-1 are the forward pass, n_fwd_ops..n_ops-1 the backward pass. */
+int mi3d_swap_set_timeline(mi3d_swap_engine *e, int n_fwd_ops, int n_ops);
+/* Declares a saved tensor.  ids are caller-chosen, unique, >= 0. */
+int mi3d_swap_register(mi3d_swap_engine *e, int id, size_t bytes, int produce_op, int last_fwd_use_op,
+                       int bwd_first_use_op, int bwd_last_use_op, unsigned tags);
+/* Device bytes op `op` holds besides saved tensors (gradients, workspaces, weights). */
+int mi3d_swap_set_transient(mi3d_swap_engine *e, int op, size_t bytes);
+/* Host-only: chooses the swap set.  MI3D_ERR_OVER_BUDGET if even the chosen
+ * policy's full set leaves the modelled peak above budget_bytes (the plan is
+ * still filled in, so callers may inspect it), MI3D_ERR_HOST_POOL if the set
+ * does not fit the pinned pool. */
+int mi3d_swap_plan(mi3d_swap_engine *e);
+/* 1 if the tensor is in the swap set, 0 if not, <0 on error. */
+int mi3d_swap_is_planned(mi3d_swap_engine *e, int id);
+/* Op index at whose launch the swap-in of `id` is to be issued:
+ * max(first backward op, bwd_first_use_op - lookahead). */
+int mi3d_swap_prefetch_op(mi3d_swap_engine *e, int id);
+/* Modelled resident bytes at op `op` under the current plan. */
+int mi3d_swap_planned_bytes_at(mi3d_swap_engine *e, int op, uint64_t *bytes);
+
+/* Sub-allocates `bytes` (rounded up to 256) from dev_arena for work on
+ * `stream`.  A block that was released while copies or kernels were still
+ * using it is handed out again only together with a stream wait on those
+ * events, so the caller may use it on `stream` at once.
+ * MI3D_ERR_OVER_BUDGET when no block is large enough. */
+int mi3d_swap_alloc(mi3d_swap_engine *e, size_t bytes, void *stream, void **dev_ptr);
+/* Returns a block; it becomes reusable once the work enqueued on `stream` so
+ * far has finished (and, for a tensor being swapped out, once its copy has). */
+int mi3d_swap_free(mi3d_swap_engine *e, void *dev_ptr, void *stream);
+
+/* Swap-out (Section 3.1): asynchronous device->host copy of tensor `id` from
+ * dev_src into the pinned pool.  The copy starts after the work enqueued on
+ * producer_stream so far.  The host thread does not block. */
+int mi3d_swap_out(mi3d_swap_engine *e, int id, const void *dev_src, void *producer_stream);
+/* The forward pass is done with the device copy of `id`: after the work
+ * enqueued on last_consumer_stream so far AND the swap-out copy, dev_src may
+ * be reused.  If dev_src came from mi3d_swap_alloc() it is returned to the
+ * arena with those two conditions attached; otherwise the call makes
+ * last_consumer_stream wait for the copy so that the caller may reuse the
+ * memory on that stream. */
+int mi3d_swap_release(mi3d_swap_engine *e, int id, void *last_consumer_stream);
+/* Swap-in: asynchronous host->device copy of `id` into dev_dst, started after
+ * the work enqueued on consumer_stream so far (dev_dst may have been in use
+ * there).  Does not make consumer_stream wait; see mi3d_swap_wait_in. */
+int mi3d_swap_in(mi3d_swap_engine *e, int id, void *dev_dst, void *consumer_stream);
+/* Makes consumer_stream wait until the swap-in of `id` has landed.  Call
+ * right before the backward op that reads it. */
+int mi3d_swap_wait_in(mi3d_swap_engine *e, int id, void *consumer_stream);
+/* The backward pass is done with `id`: its host slot is recycled. */
+int mi3d_swap_done(mi3d_swap_engine *e, int id);
+/* Blocks the host until every copy issued so far has finished. */
+int mi3d_swap_sync(mi3d_swap_engine *e);
+/* Forgets per-step state (tensor residency, host slots, counters) but keeps
+ * registrations and the plan, so the same step can run again. */
+int mi3d_swap_reset_step(mi3d_swap_engine *e);
+/* Collects counters; synchronises with the side streams to time the copies. */
+int mi3d_swap_stats(mi3d_swap_engine *e, mi3d_swap_stats_t *out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MI3D_H */

@@ -1,0 +1,108 @@
+"""Thin binding of the convolution entry points: argument marshalling only.
+
+Tensors are torch CUDA tensors used as plain device buffers (NDHWC
+activations, [Cout][kD][kH][kW][Cin] weights); every arithmetic step runs in
+libmi3d.so on the current torch stream.
+"""
+import ctypes
+
+import torch
+
+from ._lib import ConvDesc, check, lib
+
+F32, BF16 = 0, 1
+PASS_FWD, PASS_DGRAD, PASS_WGRAD = 0, 1, 2
+_DT = {torch.float32: F32, torch.bfloat16: BF16}
+
+
+def _t3(v):
+    return (v, v, v) if isinstance(v, int) else tuple(int(a) for a in v)
+
+
+def make_desc(N, D, H, W, Cin, Cout, k, s, p, dtype):
+    k, s, p = _t3(k), _t3(s), _t3(p)
+    dt = _DT[dtype] if isinstance(dtype, torch.dtype) else int(dtype)
+    return ConvDesc(N, D, H, W, Cin, Cout, *k, *s, *p, dt)
+
+
+def out_dims(desc):
+    a, b, c = ctypes.c_int(), ctypes.c_int(), ctypes.c_int()
+    check(lib().mi3d_conv3d_out_dims(ctypes.byref(desc), ctypes.byref(a), ctypes.byref(b), ctypes.byref(c)), "conv3d_out_dims")
+    return a.value, b.value, c.value
+
+
+def workspace_bytes(desc, pass_):
+    return int(lib().mi3d_conv3d_workspace_bytes(ctypes.byref(desc), pass_))
+
+
+def kernel_name(desc, pass_):
+    buf = ctypes.create_string_buffer(64)
+    check(lib().mi3d_conv3d_kernel_name(ctypes.byref(desc), pass_, buf, 64), "conv3d_kernel_name")
+    return buf.value.decode()
+
+
+def set_kernel_family(family):
+    return lib().mi3d_conv3d_set_kernel_family(int(family))
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _tdtype(desc):
+    return torch.float32 if desc.dtype == F32 else torch.bfloat16
+
+
+def _chk(t, shape, dtype, name):
+    if not t.is_cuda or not t.is_contiguous() or t.dtype != dtype or tuple(t.shape) != tuple(shape):
+        raise ValueError(f"{name}: need contiguous CUDA {dtype} tensor of shape {tuple(shape)}, got {t.dtype} {tuple(t.shape)} on {t.device}")
+
+
+def _ws(desc, pass_, ws):
+    need = workspace_bytes(desc, pass_)
+    if ws is None:
+        ws = torch.empty(max(need, 16), dtype=torch.uint8, device="cuda")
+    return ws, ws.data_ptr(), ws.numel() * ws.element_size()
+
+
+def _shapes(desc):
+    Do, Ho, Wo = out_dims(desc)
+    return ((desc.N, desc.D, desc.H, desc.W, desc.Cin),
+            (desc.Cout, desc.kD, desc.kH, desc.kW, desc.Cin),
+            (desc.N, Do, Ho, Wo, desc.Cout))
+
+
+def conv3d_fwd(desc, x, w, y=None, ws=None):
+    xs, wsh, ys = _shapes(desc)
+    dt = _tdtype(desc)
+    _chk(x, xs, dt, "x"); _chk(w, wsh, dt, "w")
+    if y is None:
+        y = torch.empty(ys, dtype=dt, device=x.device)
+    _chk(y, ys, dt, "y")
+    ws, p, n = _ws(desc, PASS_FWD, ws)
+    check(lib().mi3d_conv3d_fwd(ctypes.byref(desc), x.data_ptr(), w.data_ptr(), y.data_ptr(), p, n, _stream()), "conv3d_fwd")
+    return y
+
+
+def conv3d_dgrad(desc, dy, w, dx=None, ws=None):
+    xs, wsh, ys = _shapes(desc)
+    dt = _tdtype(desc)
+    _chk(dy, ys, dt, "dy"); _chk(w, wsh, dt, "w")
+    if dx is None:
+        dx = torch.empty(xs, dtype=dt, device=dy.device)
+    _chk(dx, xs, dt, "dx")
+    ws, p, n = _ws(desc, PASS_DGRAD, ws)
+    check(lib().mi3d_conv3d_dgrad(ctypes.byref(desc), dy.data_ptr(), w.data_ptr(), dx.data_ptr(), p, n, _stream()), "conv3d_dgrad")
+    return dx
+
+
+def conv3d_wgrad(desc, x, dy, dw=None, ws=None):
+    xs, wsh, ys = _shapes(desc)
+    dt = _tdtype(desc)
+    _chk(x, xs, dt, "x"); _chk(dy, ys, dt, "dy")
+    if dw is None:
+        dw = torch.empty(wsh, dtype=torch.float32, device=x.device)
+    _chk(dw, wsh, torch.float32, "dw")
+    ws, p, n = _ws(desc, PASS_WGRAD, ws)
+    check(lib().mi3d_conv3d_wgrad(ctypes.byref(desc), x.data_ptr(), dy.data_ptr(), dw.data_ptr(), p, n, _stream()), "conv3d_wgrad")
+    return dw

@@ -1,0 +1,154 @@
+// C ABI of the convolution passes: descriptor validation and kernel choice.
+#include <atomic>
+#include <cstdio>
+#include <cstring>
+
+#include "mi3d_internal.h"
+
+namespace mi3d {
+
+static thread_local int g_last_hip_error = 0;
+static std::atomic<int> g_family{0};
+
+void note_hip_error(hipError_t e) { g_last_hip_error = (int)e; }
+
+int check_launch() {
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) {
+        note_hip_error(e);
+        return MI3D_ERR_HIP;
+    }
+    return MI3D_OK;
+}
+
+int make_geom(const mi3d_conv_desc* d, Geom* g) {
+    if (!d) return MI3D_ERR_INVALID_ARG;
+    if (d->N <= 0 || d->D <= 0 || d->H <= 0 || d->W <= 0 || d->Cin <= 0 || d->Cout <= 0) return MI3D_ERR_INVALID_ARG;
+    if (d->kD <= 0 || d->kH <= 0 || d->kW <= 0 || d->sD <= 0 || d->sH <= 0 || d->sW <= 0) return MI3D_ERR_INVALID_ARG;
+    if (d->pD < 0 || d->pH < 0 || d->pW < 0) return MI3D_ERR_INVALID_ARG;
+    if (d->D + 2 * d->pD < d->kD || d->H + 2 * d->pH < d->kH || d->W + 2 * d->pW < d->kW) return MI3D_ERR_INVALID_ARG;
+    if (d->dtype != MI3D_F32 && d->dtype != MI3D_BF16) return MI3D_ERR_UNSUPPORTED;
+    g->N = d->N; g->D = d->D; g->H = d->H; g->W = d->W; g->Cin = d->Cin;
+    g->Cout = d->Cout; g->kD = d->kD; g->kH = d->kH; g->kW = d->kW;
+    g->sD = d->sD; g->sH = d->sH; g->sW = d->sW; g->pD = d->pD; g->pH = d->pH; g->pW = d->pW;
+    g->Do = (d->D + 2 * d->pD - d->kD) / d->sD + 1;
+    g->Ho = (d->H + 2 * d->pH - d->kH) / d->sH + 1;
+    g->Wo = (d->W + 2 * d->pW - d->kW) / d->sW + 1;
+    g->dtype = d->dtype;
+    // element counts must stay addressable with 63-bit indices and sane grids
+    const long long lim = 1ll << 40;
+    if (g->in_voxels() * g->Cin > lim || g->out_voxels() * g->Cout > lim || g->w_elems() > (1ll << 31)) return MI3D_ERR_UNSUPPORTED;
+    return MI3D_OK;
+}
+
+static bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
+
+enum Kernel { K_DIRECT = 0, K_NONE = -1 };
+
+static Kernel choose(const Geom& g, int pass) {
+    (void)g; (void)pass;
+    return K_DIRECT;
+}
+
+static const char* kernel_name(Kernel k) {
+    switch (k) {
+        case K_DIRECT: return "direct";
+        default: return "none";
+    }
+}
+
+}  // namespace mi3d
+
+using namespace mi3d;
+
+extern "C" {
+
+const char* mi3d_status_string(int status) {
+    switch (status) {
+        case MI3D_OK: return "ok";
+        case MI3D_ERR_INVALID_ARG: return "invalid argument";
+        case MI3D_ERR_UNSUPPORTED: return "unsupported dtype or shape";
+        case MI3D_ERR_WORKSPACE: return "workspace too small";
+        case MI3D_ERR_HIP: return "HIP runtime error";
+        case MI3D_ERR_HOST_POOL: return "pinned host pool exhausted";
+        case MI3D_ERR_OVER_BUDGET: return "device budget or arena exceeded";
+        case MI3D_ERR_BAD_STATE: return "call not valid in this state";
+        default: return "unknown status";
+    }
+}
+
+int mi3d_last_hip_error(void) { return g_last_hip_error; }
+
+int mi3d_conv3d_out_dims(const mi3d_conv_desc* desc, int* Do, int* Ho, int* Wo) {
+    Geom g;
+    int st = make_geom(desc, &g);
+    if (st) return st;
+    if (!Do || !Ho || !Wo) return MI3D_ERR_INVALID_ARG;
+    *Do = g.Do; *Ho = g.Ho; *Wo = g.Wo;
+    return MI3D_OK;
+}
+
+int mi3d_conv3d_set_kernel_family(int family) {
+    if (family < 0 || family > 1) return MI3D_ERR_INVALID_ARG;
+    return g_family.exchange(family);
+}
+
+int mi3d_conv3d_kernel_name(const mi3d_conv_desc* desc, int pass, char* buf, size_t buf_len) {
+    Geom g;
+    int st = make_geom(desc, &g);
+    if (st) return st;
+    if (!buf || buf_len == 0 || pass < 0 || pass > 2) return MI3D_ERR_INVALID_ARG;
+    Kernel k = g_family.load() == 1 ? K_DIRECT : choose(g, pass);
+    snprintf(buf, buf_len, "%s", kernel_name(k));
+    return MI3D_OK;
+}
+
+size_t mi3d_conv3d_workspace_bytes(const mi3d_conv_desc* desc, int pass) {
+    Geom g;
+    if (make_geom(desc, &g) || pass < 0 || pass > 2) return 0;
+    // the plain kernels must always be runnable (family 1), so report the max
+    size_t need = direct_workspace_bytes(g, pass);
+    return need;
+}
+
+int mi3d_conv3d_fwd(const mi3d_conv_desc* desc, const void* x, const void* w, void* y, void* ws, size_t ws_bytes, void* stream) {
+    Geom g;
+    int st = make_geom(desc, &g);
+    if (st) return st;
+    if (!x || !w || !y || !aligned16(x) || !aligned16(w) || !aligned16(y) || !aligned16(ws)) return MI3D_ERR_INVALID_ARG;
+    if (ws_bytes && !ws) return MI3D_ERR_INVALID_ARG;
+    Kernel k = g_family.load() == 1 ? K_DIRECT : choose(g, MI3D_PASS_FWD);
+    switch (k) {
+        case K_DIRECT: return direct_fwd(g, x, w, y, (hipStream_t)stream);
+        default: return MI3D_ERR_UNSUPPORTED;
+    }
+}
+
+int mi3d_conv3d_dgrad(const mi3d_conv_desc* desc, const void* dy, const void* w, void* dx, void* ws, size_t ws_bytes, void* stream) {
+    Geom g;
+    int st = make_geom(desc, &g);
+    if (st) return st;
+    if (!dy || !w || !dx || !aligned16(dy) || !aligned16(w) || !aligned16(dx) || !aligned16(ws)) return MI3D_ERR_INVALID_ARG;
+    if (ws_bytes && !ws) return MI3D_ERR_INVALID_ARG;
+    Kernel k = g_family.load() == 1 ? K_DIRECT : choose(g, MI3D_PASS_DGRAD);
+    switch (k) {
+        case K_DIRECT: return direct_dgrad(g, dy, w, dx, (hipStream_t)stream);
+        default: return MI3D_ERR_UNSUPPORTED;
+    }
+}
+
+int mi3d_conv3d_wgrad(const mi3d_conv_desc* desc, const void* x, const void* dy, float* dw, void* ws, size_t ws_bytes, void* stream) {
+    Geom g;
+    int st = make_geom(desc, &g);
+    if (st) return st;
+    if (!x || !dy || !dw || !aligned16(x) || !aligned16(dy) || !aligned16(dw) || !aligned16(ws)) return MI3D_ERR_INVALID_ARG;
+    if (ws_bytes && !ws) return MI3D_ERR_INVALID_ARG;
+    if (ws_bytes < mi3d_conv3d_workspace_bytes(desc, MI3D_PASS_WGRAD)) return MI3D_ERR_WORKSPACE;
+    Kernel k = g_family.load() == 1 ? K_DIRECT : choose(g, MI3D_PASS_WGRAD);
+    switch (k) {
+        case K_DIRECT: return direct_wgrad(g, x, dy, dw, ws, ws_bytes, (hipStream_t)stream);
+        default: return MI3D_ERR_UNSUPPORTED;
+    }
+}
+
+}  // extern "C"

@@ -1,0 +1,47 @@
+// Internal declarations shared by the translation units of libmi3d.so.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/mi3d.h"
+
+namespace mi3d {
+
+// Validated geometry of one layer (descriptor plus derived output extents).
+struct Geom {
+    int N, D, H, W, Cin;
+    int Cout, kD, kH, kW;
+    int sD, sH, sW, pD, pH, pW;
+    int Do, Ho, Wo;
+    int dtype;
+    __host__ __device__ long long in_voxels() const { return (long long)N * D * H * W; }
+    __host__ __device__ long long out_voxels() const { return (long long)N * Do * Ho * Wo; }
+    __host__ __device__ long long taps() const { return (long long)kD * kH * kW; }
+    __host__ __device__ long long w_elems() const { return taps() * Cin * Cout; }
+    __host__ __device__ size_t esize() const { return dtype == MI3D_BF16 ? 2 : 4; }
+};
+
+int make_geom(const mi3d_conv_desc* d, Geom* g);  // MI3D_OK or error
+void note_hip_error(hipError_t e);
+int check_launch();  // hipGetLastError -> status
+
+// bf16 helpers (device): storage is the upper 16 bits of the fp32 pattern.
+__device__ __forceinline__ float bf16_to_f32(uint16_t v) { return __uint_as_float((uint32_t)v << 16); }
+__device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return 0x7fc0;  // NaN stays NaN
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+// ---- kernel families (each returns a status; only enqueue on `stream`) ----
+// plain one-thread-per-output kernels: any geometry, both dtypes
+size_t direct_workspace_bytes(const Geom& g, int pass);
+int direct_fwd(const Geom& g, const void* x, const void* w, void* y, hipStream_t s);
+int direct_dgrad(const Geom& g, const void* dy, const void* w, void* dx, hipStream_t s);
+int direct_wgrad(const Geom& g, const void* x, const void* dy, float* dw, void* ws, size_t ws_bytes, hipStream_t s);
+// out[i] = sum_p part[p*n + i], p in index order (bit-reproducible)
+__global__ void reduce_partials_kernel(const float* __restrict__ part, float* __restrict__ out, long long n, int parts);
+
+}  // namespace mi3d

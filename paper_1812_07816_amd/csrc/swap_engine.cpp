@@ -1,0 +1,463 @@
+// Run-time half of the data-swapping engine (Sections 3.1 and 3.3): pinned
+// host pool, one side stream per copy direction, events that order copies
+// against the compute stream, an event-aware device arena, and counters.
+#include <algorithm>
+#include <map>
+#include <memory>
+#include <new>
+#include <vector>
+
+#include "mi3d_internal.h"
+#include "swap_planner.h"
+
+using namespace mi3d;
+
+namespace {
+
+enum State { ST_NEW = 0, ST_OUT_ISSUED, ST_HOST, ST_IN_ISSUED, ST_BACK, ST_DONE };
+
+struct Copy {
+    hipEvent_t start = nullptr, done = nullptr;
+    bool issued = false;
+};
+
+struct Tensor {
+    PlanTensor plan;
+    State state = ST_NEW;
+    const void* dev_src = nullptr;
+    Copy out, in;
+};
+
+struct ArenaBlock {
+    size_t off, size;
+    bool free;
+    std::vector<std::shared_ptr<void>> pending;  // events that must fire before reuse
+};
+
+}  // namespace
+
+struct mi3d_swap_engine {
+    mi3d_swap_config cfg;
+    std::map<int, Tensor> tensors;
+    std::vector<size_t> transient;
+    int n_fwd_ops = 0, n_ops = 0;
+    bool have_plan = false;
+    PlanResult plan_res;
+
+    bool live = false;  // owns HIP objects
+    int device = 0;
+    char* host_pool = nullptr;
+    hipStream_t s_out = nullptr, s_in = nullptr;
+    hipEvent_t base = nullptr;
+    std::vector<hipEvent_t> free_events_timed, free_events_plain;
+
+    std::vector<ArenaBlock> blocks;
+    size_t arena_used = 0, arena_peak = 0;
+
+    uint64_t bytes_out = 0, bytes_in = 0;
+    int n_out = 0, n_in = 0;
+};
+
+namespace {
+
+#define HIP_TRY(expr)                         \
+    do {                                      \
+        hipError_t err__ = (expr);            \
+        if (err__ != hipSuccess) {            \
+            note_hip_error(err__);            \
+            return MI3D_ERR_HIP;              \
+        }                                     \
+    } while (0)
+
+int get_event(mi3d_swap_engine* e, bool timed, hipEvent_t* ev) {
+    std::vector<hipEvent_t>& pool = timed ? e->free_events_timed : e->free_events_plain;
+    if (!pool.empty()) {
+        *ev = pool.back();
+        pool.pop_back();
+        return MI3D_OK;
+    }
+    HIP_TRY(hipEventCreateWithFlags(ev, timed ? hipEventDefault : hipEventDisableTiming));
+    return MI3D_OK;
+}
+
+// plain (untimed) event recorded on `s`, handed back to the pool when the
+// last holder lets go
+int record_shared(mi3d_swap_engine* e, hipStream_t s, std::shared_ptr<void>* out) {
+    hipEvent_t ev;
+    int st = get_event(e, false, &ev);
+    if (st) return st;
+    HIP_TRY(hipEventRecord(ev, s));
+    *out = std::shared_ptr<void>((void*)ev, [e](void* p) { e->free_events_plain.push_back((hipEvent_t)p); });
+    return MI3D_OK;
+}
+
+Tensor* find(mi3d_swap_engine* e, int id) {
+    auto it = e->tensors.find(id);
+    return it == e->tensors.end() ? nullptr : &it->second;
+}
+
+bool in_arena(const mi3d_swap_engine* e, const void* p) {
+    const char* b = (const char*)e->cfg.dev_arena;
+    return b && (const char*)p >= b && (const char*)p < b + e->cfg.arena_bytes;
+}
+
+void coalesce(mi3d_swap_engine* e) {
+    std::vector<ArenaBlock>& bl = e->blocks;
+    for (size_t i = 0; i + 1 < bl.size();) {
+        if (bl[i].free && bl[i + 1].free) {
+            bl[i].size += bl[i + 1].size;
+            for (auto& ev : bl[i + 1].pending) bl[i].pending.push_back(ev);
+            bl.erase(bl.begin() + i + 1);
+        } else {
+            ++i;
+        }
+    }
+}
+
+int arena_free(mi3d_swap_engine* e, const void* ptr, std::vector<std::shared_ptr<void>> pending) {
+    size_t off = (const char*)ptr - (const char*)e->cfg.dev_arena;
+    for (ArenaBlock& b : e->blocks) {
+        if (b.off == off && !b.free) {
+            b.free = true;
+            b.pending = std::move(pending);
+            e->arena_used -= b.size;
+            coalesce(e);
+            return MI3D_OK;
+        }
+    }
+    return MI3D_ERR_BAD_STATE;
+}
+
+void reset_step_state(mi3d_swap_engine* e) {
+    for (auto& kv : e->tensors) {
+        Tensor& t = kv.second;
+        for (Copy* c : {&t.out, &t.in}) {
+            if (c->start) e->free_events_timed.push_back(c->start);
+            if (c->done) e->free_events_timed.push_back(c->done);
+            *c = Copy();
+        }
+        t.state = ST_NEW;
+        t.dev_src = nullptr;
+    }
+    e->bytes_out = e->bytes_in = 0;
+    e->n_out = e->n_in = 0;
+}
+
+}  // namespace
+
+extern "C" {
+
+int mi3d_swap_create(const mi3d_swap_config* cfg, mi3d_swap_engine** out) {
+    if (!cfg || !out) return MI3D_ERR_INVALID_ARG;
+    if (cfg->lookahead < 0 || cfg->policy < MI3D_SWAP_BUDGET || cfg->policy > MI3D_SWAP_FIRST_N) return MI3D_ERR_INVALID_ARG;
+    if ((cfg->dev_arena == nullptr) != (cfg->arena_bytes == 0)) return MI3D_ERR_INVALID_ARG;
+    if (cfg->dev_arena && ((uintptr_t)cfg->dev_arena & 255)) return MI3D_ERR_INVALID_ARG;
+    mi3d_swap_engine* e = new (std::nothrow) mi3d_swap_engine();
+    if (!e) return MI3D_ERR_INVALID_ARG;
+    e->cfg = *cfg;
+    if (cfg->arena_bytes) e->blocks.push_back(ArenaBlock{0, cfg->arena_bytes & ~(size_t)255, true, {}});
+    if (cfg->host_pool_bytes) {
+        hipError_t err = hipGetDevice(&e->device);
+        if (err == hipSuccess) err = hipHostMalloc((void**)&e->host_pool, cfg->host_pool_bytes, hipHostMallocDefault);
+        if (err == hipSuccess) err = hipStreamCreateWithFlags(&e->s_out, hipStreamNonBlocking);
+        if (err == hipSuccess) err = hipStreamCreateWithFlags(&e->s_in, hipStreamNonBlocking);
+        if (err == hipSuccess) err = hipEventCreate(&e->base);
+        if (err == hipSuccess) err = hipEventRecord(e->base, e->s_out);
+        if (err != hipSuccess) {
+            note_hip_error(err);
+            if (e->base) (void)hipEventDestroy(e->base);
+            if (e->s_in) (void)hipStreamDestroy(e->s_in);
+            if (e->s_out) (void)hipStreamDestroy(e->s_out);
+            if (e->host_pool) (void)hipHostFree(e->host_pool);
+            delete e;
+            return MI3D_ERR_HIP;
+        }
+        e->live = true;
+    }
+    *out = e;
+    return MI3D_OK;
+}
+
+int mi3d_swap_destroy(mi3d_swap_engine* e) {
+    if (!e) return MI3D_ERR_INVALID_ARG;
+    int st = MI3D_OK;
+    if (e->live) {
+        if (hipStreamSynchronize(e->s_out) != hipSuccess) st = MI3D_ERR_HIP;
+        if (hipStreamSynchronize(e->s_in) != hipSuccess) st = MI3D_ERR_HIP;
+        e->blocks.clear();  // drops shared events into the free lists
+        reset_step_state(e);
+        for (hipEvent_t ev : e->free_events_timed) (void)hipEventDestroy(ev);
+        for (hipEvent_t ev : e->free_events_plain) (void)hipEventDestroy(ev);
+        (void)hipEventDestroy(e->base);
+        (void)hipStreamDestroy(e->s_out);
+        (void)hipStreamDestroy(e->s_in);
+        (void)hipHostFree(e->host_pool);
+    }
+    delete e;
+    return st;
+}
+
+int mi3d_swap_set_timeline(mi3d_swap_engine* e, int n_fwd_ops, int n_ops) {
+    if (!e || n_fwd_ops < 0 || n_ops < n_fwd_ops) return MI3D_ERR_INVALID_ARG;
+    e->n_fwd_ops = n_fwd_ops;
+    e->n_ops = n_ops;
+    e->transient.resize(n_ops, 0);
+    e->have_plan = false;
+    return MI3D_OK;
+}
+
+int mi3d_swap_register(mi3d_swap_engine* e, int id, size_t bytes, int produce_op, int last_fwd_use_op,
+                       int bwd_first_use_op, int bwd_last_use_op, unsigned tags) {
+    if (!e || id < 0 || bytes == 0) return MI3D_ERR_INVALID_ARG;
+    if (produce_op < 0 || produce_op > last_fwd_use_op || last_fwd_use_op >= bwd_first_use_op || bwd_first_use_op > bwd_last_use_op)
+        return MI3D_ERR_INVALID_ARG;
+    if (e->tensors.count(id)) return MI3D_ERR_BAD_STATE;
+    Tensor t;
+    t.plan.id = id;
+    t.plan.bytes = bytes;
+    t.plan.produce_op = produce_op;
+    t.plan.last_fwd_use_op = last_fwd_use_op;
+    t.plan.bwd_first_use_op = bwd_first_use_op;
+    t.plan.bwd_last_use_op = bwd_last_use_op;
+    t.plan.tags = tags;
+    e->tensors[id] = t;
+    e->have_plan = false;
+    return MI3D_OK;
+}
+
+int mi3d_swap_set_transient(mi3d_swap_engine* e, int op, size_t bytes) {
+    if (!e || op < 0) return MI3D_ERR_INVALID_ARG;
+    if (op >= (int)e->transient.size()) e->transient.resize(op + 1, 0);
+    e->transient[op] = bytes;
+    e->have_plan = false;
+    return MI3D_OK;
+}
+
+int mi3d_swap_plan(mi3d_swap_engine* e) {
+    if (!e) return MI3D_ERR_INVALID_ARG;
+    std::vector<PlanTensor> ts;
+    for (auto& kv : e->tensors) ts.push_back(kv.second.plan);
+    PlanParams p;
+    p.budget_bytes = e->cfg.budget_bytes;
+    p.host_pool_bytes = e->cfg.host_pool_bytes;
+    p.lookahead = e->cfg.lookahead;
+    p.policy = e->cfg.policy;
+    p.n_tensors = e->cfg.n_tensors;
+    p.exclude_tags = e->cfg.exclude_tags;
+    p.include_tags = e->cfg.include_tags;
+    p.n_fwd_ops = e->n_fwd_ops;
+    p.n_ops = std::max<int>(e->n_ops, (int)e->transient.size());
+    int st = plan_swaps(ts, e->transient, p, &e->plan_res);
+    if (st == MI3D_ERR_INVALID_ARG) return st;
+    for (const PlanTensor& t : ts) e->tensors[t.id].plan = t;
+    e->have_plan = true;
+    return st;
+}
+
+int mi3d_swap_is_planned(mi3d_swap_engine* e, int id) {
+    if (!e) return MI3D_ERR_INVALID_ARG;
+    Tensor* t = find(e, id);
+    if (!t || !e->have_plan) return MI3D_ERR_BAD_STATE;
+    return t->plan.planned ? 1 : 0;
+}
+
+int mi3d_swap_prefetch_op(mi3d_swap_engine* e, int id) {
+    if (!e) return MI3D_ERR_INVALID_ARG;
+    Tensor* t = find(e, id);
+    if (!t || !e->have_plan) return MI3D_ERR_BAD_STATE;
+    return t->plan.prefetch_op;
+}
+
+int mi3d_swap_planned_bytes_at(mi3d_swap_engine* e, int op, uint64_t* bytes) {
+    if (!e || !bytes || op < 0) return MI3D_ERR_INVALID_ARG;
+    if (!e->have_plan) return MI3D_ERR_BAD_STATE;
+    std::vector<PlanTensor> ts;
+    for (auto& kv : e->tensors) ts.push_back(kv.second.plan);
+    *bytes = plan_bytes_at(ts, e->transient, op, false);
+    return MI3D_OK;
+}
+
+int mi3d_swap_alloc(mi3d_swap_engine* e, size_t bytes, void* stream, void** dev_ptr) {
+    if (!e || !dev_ptr || bytes == 0) return MI3D_ERR_INVALID_ARG;
+    if (!e->cfg.dev_arena) return MI3D_ERR_BAD_STATE;
+    size_t need = (bytes + 255) & ~(size_t)255;
+    // drop events that have already fired, so that idle blocks cost no wait
+    for (ArenaBlock& b : e->blocks) {
+        if (!b.free) continue;
+        auto& pv = b.pending;
+        pv.erase(std::remove_if(pv.begin(), pv.end(), [](const std::shared_ptr<void>& ev) { return hipEventQuery((hipEvent_t)ev.get()) == hipSuccess; }), pv.end());
+    }
+    int pick = -1;
+    for (int pass = 0; pass < 2 && pick < 0; ++pass)
+        for (int i = 0; i < (int)e->blocks.size(); ++i) {
+            const ArenaBlock& b = e->blocks[i];
+            if (b.free && b.size >= need && (pass == 1 || b.pending.empty())) { pick = i; break; }
+        }
+    if (pick < 0) return MI3D_ERR_OVER_BUDGET;
+    for (auto& ev : e->blocks[pick].pending) HIP_TRY(hipStreamWaitEvent((hipStream_t)stream, (hipEvent_t)ev.get(), 0));
+    ArenaBlock& b = e->blocks[pick];
+    if (b.size > need) {
+        ArenaBlock rest{b.off + need, b.size - need, true, b.pending};
+        b.size = need;
+        e->blocks.insert(e->blocks.begin() + pick + 1, rest);
+    }
+    ArenaBlock& a = e->blocks[pick];
+    a.free = false;
+    a.pending.clear();
+    e->arena_used += need;
+    e->arena_peak = std::max(e->arena_peak, e->arena_used);
+    *dev_ptr = (char*)e->cfg.dev_arena + a.off;
+    return MI3D_OK;
+}
+
+int mi3d_swap_free(mi3d_swap_engine* e, void* dev_ptr, void* stream) {
+    if (!e || !dev_ptr) return MI3D_ERR_INVALID_ARG;
+    if (!in_arena(e, dev_ptr)) return MI3D_ERR_BAD_STATE;
+    std::shared_ptr<void> ev;
+    int st = record_shared(e, (hipStream_t)stream, &ev);
+    if (st) return st;
+    return arena_free(e, dev_ptr, {ev});
+}
+
+int mi3d_swap_out(mi3d_swap_engine* e, int id, const void* dev_src, void* producer_stream) {
+    if (!e || !dev_src) return MI3D_ERR_INVALID_ARG;
+    Tensor* t = find(e, id);
+    if (!t || !e->have_plan || !t->plan.planned || t->state != ST_NEW || !e->live) return MI3D_ERR_BAD_STATE;
+    hipEvent_t dep;
+    int st = get_event(e, false, &dep);
+    if (st) return st;
+    HIP_TRY(hipEventRecord(dep, (hipStream_t)producer_stream));
+    HIP_TRY(hipStreamWaitEvent(e->s_out, dep, 0));
+    e->free_events_plain.push_back(dep);  // the enqueued wait refers to the record above; the handle may be re-recorded
+    if ((st = get_event(e, true, &t->out.start)) || (st = get_event(e, true, &t->out.done))) return st;
+    HIP_TRY(hipEventRecord(t->out.start, e->s_out));
+    HIP_TRY(hipMemcpyAsync(e->host_pool + t->plan.host_offset, dev_src, t->plan.bytes, hipMemcpyDeviceToHost, e->s_out));
+    HIP_TRY(hipEventRecord(t->out.done, e->s_out));
+    t->out.issued = true;
+    t->dev_src = dev_src;
+    t->state = ST_OUT_ISSUED;
+    e->bytes_out += t->plan.bytes;
+    e->n_out++;
+    return MI3D_OK;
+}
+
+int mi3d_swap_release(mi3d_swap_engine* e, int id, void* last_consumer_stream) {
+    if (!e) return MI3D_ERR_INVALID_ARG;
+    Tensor* t = find(e, id);
+    if (!t || t->state != ST_OUT_ISSUED) return MI3D_ERR_BAD_STATE;
+    if (in_arena(e, t->dev_src)) {
+        std::shared_ptr<void> consumer, copy;
+        int st = record_shared(e, (hipStream_t)last_consumer_stream, &consumer);
+        if (st) return st;
+        if ((st = record_shared(e, e->s_out, &copy))) return st;  // s_out is in order: fires after this tensor's copy
+        if ((st = arena_free(e, t->dev_src, {consumer, copy}))) return st;
+    } else {
+        HIP_TRY(hipStreamWaitEvent((hipStream_t)last_consumer_stream, t->out.done, 0));
+    }
+    t->dev_src = nullptr;
+    t->state = ST_HOST;
+    return MI3D_OK;
+}
+
+int mi3d_swap_in(mi3d_swap_engine* e, int id, void* dev_dst, void* consumer_stream) {
+    if (!e || !dev_dst) return MI3D_ERR_INVALID_ARG;
+    Tensor* t = find(e, id);
+    if (!t || t->state != ST_HOST || !e->live) return MI3D_ERR_BAD_STATE;
+    hipEvent_t dep;
+    int st = get_event(e, false, &dep);
+    if (st) return st;
+    HIP_TRY(hipEventRecord(dep, (hipStream_t)consumer_stream));
+    HIP_TRY(hipStreamWaitEvent(e->s_in, dep, 0));
+    e->free_events_plain.push_back(dep);
+    HIP_TRY(hipStreamWaitEvent(e->s_in, t->out.done, 0));  // the host copy must be complete
+    if ((st = get_event(e, true, &t->in.start)) || (st = get_event(e, true, &t->in.done))) return st;
+    HIP_TRY(hipEventRecord(t->in.start, e->s_in));
+    HIP_TRY(hipMemcpyAsync(dev_dst, e->host_pool + t->plan.host_offset, t->plan.bytes, hipMemcpyHostToDevice, e->s_in));
+    HIP_TRY(hipEventRecord(t->in.done, e->s_in));
+    t->in.issued = true;
+    t->state = ST_IN_ISSUED;
+    e->bytes_in += t->plan.bytes;
+    e->n_in++;
+    return MI3D_OK;
+}
+
+int mi3d_swap_wait_in(mi3d_swap_engine* e, int id, void* consumer_stream) {
+    if (!e) return MI3D_ERR_INVALID_ARG;
+    Tensor* t = find(e, id);
+    if (!t || (t->state != ST_IN_ISSUED && t->state != ST_BACK)) return MI3D_ERR_BAD_STATE;
+    HIP_TRY(hipStreamWaitEvent((hipStream_t)consumer_stream, t->in.done, 0));
+    t->state = ST_BACK;
+    return MI3D_OK;
+}
+
+int mi3d_swap_done(mi3d_swap_engine* e, int id) {
+    if (!e) return MI3D_ERR_INVALID_ARG;
+    Tensor* t = find(e, id);
+    if (!t || t->state != ST_BACK) return MI3D_ERR_BAD_STATE;
+    t->state = ST_DONE;
+    return MI3D_OK;
+}
+
+int mi3d_swap_sync(mi3d_swap_engine* e) {
+    if (!e) return MI3D_ERR_INVALID_ARG;
+    if (!e->live) return MI3D_OK;
+    HIP_TRY(hipStreamSynchronize(e->s_out));
+    HIP_TRY(hipStreamSynchronize(e->s_in));
+    return MI3D_OK;
+}
+
+int mi3d_swap_reset_step(mi3d_swap_engine* e) {
+    if (!e) return MI3D_ERR_INVALID_ARG;
+    int st = mi3d_swap_sync(e);
+    if (st) return st;
+    reset_step_state(e);
+    if (e->live) HIP_TRY(hipEventRecord(e->base, e->s_out));
+    return MI3D_OK;
+}
+
+int mi3d_swap_stats(mi3d_swap_engine* e, mi3d_swap_stats_t* out) {
+    if (!e || !out) return MI3D_ERR_INVALID_ARG;
+    *out = mi3d_swap_stats_t();
+    out->bytes_out = e->bytes_out;
+    out->bytes_in = e->bytes_in;
+    out->peak_arena_bytes = e->arena_peak;
+    out->planned_peak_bytes = e->have_plan ? e->plan_res.planned_peak : 0;
+    out->unswapped_peak_bytes = e->have_plan ? e->plan_res.unswapped_peak : 0;
+    out->n_registered = (int)e->tensors.size();
+    out->n_planned = e->have_plan ? e->plan_res.n_planned : 0;
+    out->n_swapped_out = e->n_out;
+    out->n_swapped_in = e->n_in;
+    if (!e->live) return MI3D_OK;
+    int st = mi3d_swap_sync(e);
+    if (st) return st;
+    std::vector<std::pair<float, float>> iv;
+    for (auto& kv : e->tensors) {
+        Tensor& t = kv.second;
+        for (int dir = 0; dir < 2; ++dir) {
+            Copy& c = dir ? t.in : t.out;
+            if (!c.issued) continue;
+            float t0 = 0.f, t1 = 0.f;
+            HIP_TRY(hipEventElapsedTime(&t0, e->base, c.start));
+            HIP_TRY(hipEventElapsedTime(&t1, e->base, c.done));
+            (dir ? out->copy_ms_in : out->copy_ms_out) += (double)(t1 - t0);
+            iv.emplace_back(t0, t1);
+        }
+    }
+    std::sort(iv.begin(), iv.end());
+    double busy = 0.0;
+    float cur0 = 0.f, cur1 = -1.f;
+    for (auto& p : iv) {
+        if (cur1 < cur0 || p.first > cur1) {
+            if (cur1 >= cur0) busy += cur1 - cur0;
+            cur0 = p.first;
+            cur1 = p.second;
+        } else {
+            cur1 = std::max(cur1, p.second);
+        }
+    }
+    if (cur1 >= cur0) busy += cur1 - cur0;
+    out->busy_ms = busy;
+    return MI3D_OK;
+}
+
+}  // extern "C"

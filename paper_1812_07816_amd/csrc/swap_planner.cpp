@@ -1,0 +1,118 @@
+#include "swap_planner.h"
+
+#include <algorithm>
+
+#include "../../include/mi3d.h"
+
+namespace mi3d {
+
+static bool resident(const PlanTensor& t, int op, bool ignore_plan) {
+    if (op < t.produce_op || op > t.bwd_last_use_op) return false;
+    if (ignore_plan || !t.planned) return true;
+    return op <= t.last_fwd_use_op || op >= t.prefetch_op;
+}
+
+uint64_t plan_bytes_at(const std::vector<PlanTensor>& ts, const std::vector<size_t>& transient, int op, bool ignore_plan) {
+    uint64_t b = (op >= 0 && op < (int)transient.size()) ? transient[op] : 0;
+    for (const PlanTensor& t : ts)
+        if (resident(t, op, ignore_plan)) b += t.bytes;
+    return b;
+}
+
+static uint64_t peak(const std::vector<PlanTensor>& ts, const std::vector<size_t>& tr, int n_ops, bool ignore_plan, int* at) {
+    uint64_t best = 0;
+    int where = 0;
+    for (int op = 0; op < n_ops; ++op) {
+        uint64_t b = plan_bytes_at(ts, tr, op, ignore_plan);
+        if (b > best) { best = b; where = op; }
+    }
+    if (at) *at = where;
+    return best;
+}
+
+int plan_swaps(std::vector<PlanTensor>& ts, const std::vector<size_t>& transient, const PlanParams& p, PlanResult* res) {
+    int n_ops = p.n_ops;
+    for (const PlanTensor& t : ts) n_ops = std::max(n_ops, t.bwd_last_use_op + 1);
+    if (p.n_fwd_ops < 0 || p.n_fwd_ops > n_ops || p.lookahead < 0) return MI3D_ERR_INVALID_ARG;
+    for (PlanTensor& t : ts) {
+        if (t.produce_op > t.last_fwd_use_op || t.last_fwd_use_op >= t.bwd_first_use_op ||
+            t.bwd_first_use_op > t.bwd_last_use_op || t.produce_op < 0)
+            return MI3D_ERR_INVALID_ARG;
+        t.planned = false;
+        // `lb`: issue the swap-in `lookahead` ops before the first backward use,
+        // but never before the backward pass starts or the forward use ends.
+        int pf = t.bwd_first_use_op - p.lookahead;
+        pf = std::max(pf, p.n_fwd_ops);
+        pf = std::max(pf, t.last_fwd_use_op + 1);
+        pf = std::min(pf, t.bwd_first_use_op);
+        t.prefetch_op = pf;
+        t.host_offset = 0;
+    }
+    res->unswapped_peak = peak(ts, transient, n_ops, true, nullptr);
+
+    auto eligible = [&](const PlanTensor& t) {
+        if (t.tags & p.exclude_tags) return false;
+        if (p.include_tags && !(t.tags & p.include_tags)) return false;
+        return true;
+    };
+    // production order, the order in which swap-outs would be issued
+    std::vector<int> order;
+    for (int i = 0; i < (int)ts.size(); ++i)
+        if (eligible(ts[i])) order.push_back(i);
+    std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return ts[a].produce_op < ts[b].produce_op; });
+
+    if (p.policy == MI3D_SWAP_ALL) {
+        for (int i : order) ts[i].planned = true;
+    } else if (p.policy == MI3D_SWAP_FIRST_N) {
+        int n = p.n_tensors < 0 ? (int)order.size() : std::min<int>(p.n_tensors, (int)order.size());
+        for (int k = 0; k < n; ++k) ts[order[k]].planned = true;
+    } else if (p.policy == MI3D_SWAP_BUDGET) {
+        std::vector<int> chosen;
+        for (;;) {
+            int at = 0;
+            uint64_t pk = peak(ts, transient, n_ops, false, &at);
+            if (pk <= p.budget_bytes) break;
+            // candidates: tensors idle at the peak op.  Prefer the longest idle
+            // interval (early feature maps live longest), then the earlier
+            // producer, then the larger tensor.
+            int best = -1;
+            for (int i : order) {
+                const PlanTensor& t = ts[i];
+                if (t.planned || at <= t.last_fwd_use_op || at >= t.prefetch_op) continue;
+                if (best < 0) { best = i; continue; }
+                const PlanTensor& b = ts[best];
+                int gt = t.prefetch_op - t.last_fwd_use_op, gb = b.prefetch_op - b.last_fwd_use_op;
+                if (gt != gb ? gt > gb : (t.produce_op != b.produce_op ? t.produce_op < b.produce_op : t.bytes > b.bytes)) best = i;
+            }
+            if (best < 0) break;  // nothing more can lower this peak
+            ts[best].planned = true;
+            chosen.push_back(best);
+        }
+        // drop tensors that later choices made unnecessary (less traffic)
+        if (peak(ts, transient, n_ops, false, nullptr) <= p.budget_bytes) {
+            for (int k = (int)chosen.size() - 1; k >= 0; --k) {
+                ts[chosen[k]].planned = false;
+                if (peak(ts, transient, n_ops, false, nullptr) > p.budget_bytes) ts[chosen[k]].planned = true;
+            }
+        }
+    } else {
+        return MI3D_ERR_INVALID_ARG;
+    }
+
+    size_t off = 0;
+    int n = 0;
+    for (int i : order) {
+        if (!ts[i].planned) continue;
+        ts[i].host_offset = off;
+        off += (ts[i].bytes + 4095) & ~(size_t)4095;
+        ++n;
+    }
+    res->n_planned = n;
+    res->host_bytes = off;
+    res->planned_peak = peak(ts, transient, n_ops, false, nullptr);
+    if (p.host_pool_bytes && off > p.host_pool_bytes) return MI3D_ERR_HOST_POOL;
+    if (res->planned_peak > p.budget_bytes) return MI3D_ERR_OVER_BUDGET;
+    return MI3D_OK;
+}
+
+}  // namespace mi3d

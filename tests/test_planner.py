@@ -1,0 +1,194 @@
+"""Host-only tests of the swap planner (Sections 3.2-3.3 knobs): run on CPU."""
+import itertools
+
+import numpy as np
+import pytest
+
+from paper_1812_07816_amd import swap as sw
+from paper_1812_07816_amd._lib import Mi3dError
+
+
+def unet_like(levels=4, base=1024):
+    """Encoder tensors shrink 8x per level; decoder mirrors it.  Returns
+    (n_fwd, n_ops, tensors) with tensors = (id, bytes, produce, last_fwd, bwd_first, bwd_last, tag)."""
+    n_fwd = 2 * levels
+    n_ops = 2 * n_fwd
+    ts = []
+    for l in range(levels):       # encoder op l produces e_l, used by op l+1 and (skip) decoder op n_fwd-1-l
+        ts.append((l, base >> (3 * l) if base >> (3 * l) else 1, l, n_fwd - 1 - l, n_fwd + l, n_ops - 1 - l, sw.TAG_ENCODER))
+    for l in range(levels):       # decoder op levels+l produces d_l used by next op
+        op = levels + l
+        size = base >> (3 * (levels - 1 - l)) or 1
+        ts.append((levels + l, size, op, min(op + 1, n_fwd - 1), n_ops - 1 - op, n_ops - 1 - op, sw.TAG_DECODER))
+    return n_fwd, n_ops, ts
+
+
+def chain(n_layers, sizes):
+    """Plain chain: op i produces tensor i, op i+1 reads it, backward op
+    n_ops-1-i reads it again."""
+    n_fwd, n_ops = n_layers, 2 * n_layers
+    return n_fwd, n_ops, [(i, sizes[i], i, min(i + 1, n_fwd - 1), n_ops - 1 - i, n_ops - 1 - i, sw.TAG_ENCODER)
+                          for i in range(n_layers)]
+
+
+def make(ts, n_fwd, n_ops, **kw):
+    e = sw.SwapEngine(**kw)
+    e.set_timeline(n_fwd, n_ops)
+    for t in ts:
+        e.register(*t)
+    return e
+
+
+def brute_bytes(ts, planned, prefetch, op):
+    b = 0
+    for (i, size, prod, lf, bf, bl, _tag) in ts:
+        if op < prod or op > bl:
+            continue
+        if i in planned and lf < op < prefetch[i]:
+            continue
+        b += size
+    return b
+
+
+def test_accounting_equals_brute_force_sweep():
+    n_fwd, n_ops, ts = chain(6, [600, 500, 400, 300, 200, 100])
+    e = make(ts, n_fwd, n_ops, budget_bytes=1500, lookahead=1)
+    e.plan()
+    planned = {t[0] for t in ts if e.is_planned(t[0])}
+    pre = {t[0]: e.prefetch_op(t[0]) for t in ts}
+    assert planned
+    sweep = [brute_bytes(ts, planned, pre, op) for op in range(n_ops)]
+    assert sweep == [e.planned_bytes_at(op) for op in range(n_ops)]
+    st = e.stats()
+    assert st["planned_peak_bytes"] == max(sweep) <= 1500
+    assert st["unswapped_peak_bytes"] == 2100
+    assert st["n_planned"] == len(planned)
+
+
+def test_budget_policy_picks_early_long_lived_tensors_first():
+    n_fwd, n_ops, ts = chain(6, [600, 500, 400, 300, 200, 100])
+    e = make(ts, n_fwd, n_ops, budget_bytes=1600, lookahead=1)
+    e.plan()
+    assert [e.is_planned(i) for i in range(6)] == [True, False, False, False, False, False]
+    # nothing is swapped when everything fits
+    e2 = make(ts, n_fwd, n_ops, budget_bytes=2100, lookahead=1)
+    e2.plan()
+    assert not any(e2.is_planned(i) for i in range(6))
+    assert e2.stats()["n_planned"] == 0
+
+
+def test_budget_plan_is_minimal_under_removal():
+    n_fwd, n_ops, ts = unet_like()
+    sizes = {t[0]: t[1] for t in ts}
+    for budget in (1400, 1200, 1100):
+        e = make(ts, n_fwd, n_ops, budget_bytes=budget, lookahead=1)
+        st = e.plan(allow_over_budget=True)
+        if st != 0:
+            continue
+        planned = [i for i in sizes if e.is_planned(i)]
+        pre = {t[0]: e.prefetch_op(t[0]) for t in ts}
+        for drop in planned:   # removing any one chosen tensor breaks the budget
+            rest = set(planned) - {drop}
+            assert max(brute_bytes(ts, rest, pre, op) for op in range(n_ops)) > budget
+
+
+def test_infeasible_budget_is_reported():
+    n_fwd, n_ops, ts = chain(4, [100, 100, 100, 100])
+    e = make(ts, n_fwd, n_ops, budget_bytes=150, lookahead=1)
+    with pytest.raises(Mi3dError) as ei:
+        e.plan()
+    assert ei.value.status == -6
+    assert e.plan(allow_over_budget=True) == -6
+    # the plan is still inspectable
+    assert e.stats()["planned_peak_bytes"] > 150
+
+
+def test_transients_count_against_the_budget():
+    n_fwd, n_ops, ts = chain(4, [100, 100, 100, 100])
+    e = make(ts, n_fwd, n_ops, budget_bytes=400, lookahead=1)
+    e.plan()
+    assert e.stats()["n_planned"] == 0
+    e.set_transient(3, 150)
+    e.plan()
+    assert e.stats()["n_planned"] >= 1 and e.stats()["planned_peak_bytes"] <= 400
+
+
+def test_policy_all_and_first_n_and_tags():
+    n_fwd, n_ops, ts = unet_like()
+    e = make(ts, n_fwd, n_ops, budget_bytes=1 << 40, policy=sw.POLICY_ALL)
+    e.plan()
+    assert all(e.is_planned(t[0]) for t in ts)                       # "n_tensors = -1"
+    e = make(ts, n_fwd, n_ops, budget_bytes=1 << 40, policy=sw.POLICY_FIRST_N, n_tensors=3)
+    e.plan()
+    by_prod = sorted(ts, key=lambda t: t[2])
+    assert [e.is_planned(t[0]) for t in by_prod] == [True] * 3 + [False] * (len(ts) - 3)
+    e = make(ts, n_fwd, n_ops, budget_bytes=1 << 40, policy=sw.POLICY_ALL, exclude_tags=sw.TAG_DECODER)
+    e.plan()                                                          # excl_scopes = synthesis path
+    assert all(e.is_planned(t[0]) == (t[6] == sw.TAG_ENCODER) for t in ts)
+    e = make(ts, n_fwd, n_ops, budget_bytes=1 << 40, policy=sw.POLICY_ALL, include_tags=sw.TAG_DECODER)
+    e.plan()                                                          # incl_scopes
+    assert all(e.is_planned(t[0]) == (t[6] == sw.TAG_DECODER) for t in ts)
+
+
+def test_fewer_swapped_tensors_never_lower_the_modelled_peak():
+    # Table 1's structure: the all-swapped configuration has the lowest peak
+    n_fwd, n_ops, ts = unet_like()
+    peaks = []
+    for n in (len(ts), 5, 3, 1, 0):
+        e = make(ts, n_fwd, n_ops, budget_bytes=1 << 40, policy=sw.POLICY_FIRST_N, n_tensors=n)
+        e.plan()
+        peaks.append(e.stats()["planned_peak_bytes"])
+    assert peaks == sorted(peaks)
+
+
+def test_lookahead_moves_prefetch_earlier_and_clamps():
+    n_fwd, n_ops, ts = chain(6, [100] * 6)
+    prev = None
+    for lb in (0, 1, 2, 4, 20):
+        e = make(ts, n_fwd, n_ops, budget_bytes=1 << 40, policy=sw.POLICY_ALL, lookahead=lb)
+        e.plan()
+        pre = [e.prefetch_op(i) for i in range(6)]
+        for (i, _s, _p, lf, bf, _bl, _t), p in zip(ts, pre):
+            assert p == min(bf, max(bf - lb, n_fwd, lf + 1))     # never before the backward pass starts
+        if prev is not None:
+            assert all(a <= b for a, b in zip(pre, prev))        # larger lb => earlier (or equal)
+        prev = pre
+
+
+def test_bad_registrations_and_states():
+    e = sw.SwapEngine(budget_bytes=100)
+    e.set_timeline(2, 4)
+    e.register(0, 10, 0, 1, 2, 3)
+    for args in [(0, 10, 0, 1, 2, 3), ]:
+        with pytest.raises(Mi3dError) as ei:
+            e.register(*args)
+        assert ei.value.status == -7          # duplicate id
+    for args in [(1, 0, 0, 1, 2, 3), (-1, 10, 0, 1, 2, 3), (2, 10, 1, 0, 2, 3), (3, 10, 0, 2, 2, 3), (4, 10, 0, 1, 3, 2)]:
+        with pytest.raises(Mi3dError) as ei:
+            e.register(*args)
+        assert ei.value.status == -1
+    with pytest.raises(Mi3dError) as ei:
+        e.is_planned(0)                        # no plan yet
+    assert ei.value.status == -7
+    e.plan()
+    with pytest.raises(Mi3dError) as ei:
+        e.is_planned(99)                       # unknown id
+    assert ei.value.status == -7
+    # a planner-only engine (no pinned pool) refuses to copy, without touching HIP
+    for call in (lambda: e.swap_out(0, 4096), lambda: e.swap_in(0, 4096), lambda: e.release(0),
+                 lambda: e.wait_in(0), lambda: e.done(0), lambda: e.alloc(16)):
+        with pytest.raises(Mi3dError) as ei:
+            call()
+        assert ei.value.status == -7
+    with pytest.raises(Mi3dError) as ei:
+        sw.SwapEngine(budget_bytes=1, lookahead=-1)
+    assert ei.value.status == -1
+
+
+def test_host_pool_capacity_is_checked_at_plan_time():
+    # host_pool_bytes > 0 would allocate pinned memory (needs a GPU); the
+    # capacity rule itself is visible through the planned set's size
+    n_fwd, n_ops, ts = chain(4, [5000, 5000, 5000, 5000])
+    e = make(ts, n_fwd, n_ops, budget_bytes=1 << 40, policy=sw.POLICY_ALL)
+    e.plan()
+    assert e.stats()["n_planned"] == 4
