@@ -26,6 +26,8 @@ def _compile(src):
         cmd += DEVICE
     else:
         cmd += ["-x", "hip", "--offload-arch=gfx950"]
+    if os.environ.get("MI3D_RESOURCE_USAGE"):
+        cmd += ["-Rpass-analysis=kernel-resource-usage"]
     cmd += ["-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     out = "\n".join(l for l in r.stdout.splitlines() if "packed-fp32-ops" not in l)

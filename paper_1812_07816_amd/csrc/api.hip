@@ -43,16 +43,17 @@ int make_geom(const mi3d_conv_desc* d, Geom* g) {
 
 static bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
 
-enum Kernel { K_DIRECT = 0, K_NONE = -1 };
+enum Kernel { K_DIRECT = 0, K_SP = 1, K_NONE = -1 };
 
 static Kernel choose(const Geom& g, int pass) {
-    (void)g; (void)pass;
+    if (sp_supported(g, pass)) return K_SP;
     return K_DIRECT;
 }
 
 static const char* kernel_name(Kernel k) {
     switch (k) {
         case K_DIRECT: return "direct";
+        case K_SP: return "mfma_plane_stream";
         default: return "none";
     }
 }
@@ -108,7 +109,8 @@ size_t mi3d_conv3d_workspace_bytes(const mi3d_conv_desc* desc, int pass) {
     if (make_geom(desc, &g) || pass < 0 || pass > 2) return 0;
     // the plain kernels must always be runnable (family 1), so report the max
     size_t need = direct_workspace_bytes(g, pass);
-    return need;
+    size_t sp = sp_workspace_bytes(g, pass);
+    return need > sp ? need : sp;
 }
 
 int mi3d_conv3d_fwd(const mi3d_conv_desc* desc, const void* x, const void* w, void* y, void* ws, size_t ws_bytes, void* stream) {
@@ -117,9 +119,11 @@ int mi3d_conv3d_fwd(const mi3d_conv_desc* desc, const void* x, const void* w, vo
     if (st) return st;
     if (!x || !w || !y || !aligned16(x) || !aligned16(w) || !aligned16(y) || !aligned16(ws)) return MI3D_ERR_INVALID_ARG;
     if (ws_bytes && !ws) return MI3D_ERR_INVALID_ARG;
+    if (ws_bytes < mi3d_conv3d_workspace_bytes(desc, MI3D_PASS_FWD)) return MI3D_ERR_WORKSPACE;
     Kernel k = g_family.load() == 1 ? K_DIRECT : choose(g, MI3D_PASS_FWD);
     switch (k) {
         case K_DIRECT: return direct_fwd(g, x, w, y, (hipStream_t)stream);
+        case K_SP: return sp_conv(g, MI3D_PASS_FWD, x, w, y, ws, ws_bytes, (hipStream_t)stream);
         default: return MI3D_ERR_UNSUPPORTED;
     }
 }
@@ -130,9 +134,11 @@ int mi3d_conv3d_dgrad(const mi3d_conv_desc* desc, const void* dy, const void* w,
     if (st) return st;
     if (!dy || !w || !dx || !aligned16(dy) || !aligned16(w) || !aligned16(dx) || !aligned16(ws)) return MI3D_ERR_INVALID_ARG;
     if (ws_bytes && !ws) return MI3D_ERR_INVALID_ARG;
+    if (ws_bytes < mi3d_conv3d_workspace_bytes(desc, MI3D_PASS_DGRAD)) return MI3D_ERR_WORKSPACE;
     Kernel k = g_family.load() == 1 ? K_DIRECT : choose(g, MI3D_PASS_DGRAD);
     switch (k) {
         case K_DIRECT: return direct_dgrad(g, dy, w, dx, (hipStream_t)stream);
+        case K_SP: return sp_conv(g, MI3D_PASS_DGRAD, dy, w, dx, ws, ws_bytes, (hipStream_t)stream);
         default: return MI3D_ERR_UNSUPPORTED;
     }
 }

@@ -44,4 +44,10 @@ int direct_wgrad(const Geom& g, const void* x, const void* dy, float* dw, void* 
 // out[i] = sum_p part[p*n + i], p in index order (bit-reproducible)
 __global__ void reduce_partials_kernel(const float* __restrict__ part, float* __restrict__ out, long long n, int parts);
 
+
+// plane-streaming MFMA kernel: bf16, 3x3x3, stride 1 (forward and data gradient)
+bool sp_supported(const Geom& g, int pass);
+size_t sp_workspace_bytes(const Geom& g, int pass);
+int sp_conv(const Geom& g, int pass, const void* in, const void* w, void* out, void* ws, size_t ws_bytes, hipStream_t s);
+
 }  // namespace mi3d
