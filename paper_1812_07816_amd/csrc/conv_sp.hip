@@ -44,41 +44,104 @@ __device__ __forceinline__ f32x16 mfma(bf16x8 a, bf16x8 b, f32x16 c) {
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }
 
-template <int PH>
-__device__ __forceinline__ void plane_compute(f32x16 (&acc)[3][RH], const char* in_lds, const char* w_lds, int kdmask,
-                                              int lane, int wave) {
-    const int row0 = wave * RH;
+typedef __attribute__((__vector_size__(2 * sizeof(float)))) float f32x2;
+typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
+
+// Register fragments.  x: input rows row0 .. row0+RH+1 at one (kw, k16)
+// position (double buffered); w: the 3 kh taps of one kd group.
+struct XFrag { bf16x8 v[RH + 2]; };
+struct WFrag { bf16x8 v[3]; };
+
+template <int SUB>
+__device__ __forceinline__ void load_x(XFrag& f, const char* in_lane) {
+    constexpr int kw = SUB / 2, kk = SUB % 2;
 #pragma unroll
-    for (int kw = 0; kw < 3; ++kw) {
+    for (int r = 0; r < RH + 2; ++r) f.v[r] = *(const bf16x8*)(in_lane + (2 * kk * NV + r * COLS + kw) * 16);
+}
+template <int SUB, int KD>
+__device__ __forceinline__ void load_w(WFrag& f, const char* w_lane) {
+    constexpr int kw = SUB / 2, kk = SUB % 2;
 #pragma unroll
-        for (int kk = 0; kk < 2; ++kk) {
-            bf16x8 xin[RH + 2];
-            const int c = 2 * kk + (lane >> 5);
+    for (int kh = 0; kh < 3; ++kh) f.v[kh] = *(const bf16x8*)(w_lane + (((kw * 3 + KD) * 3 + kh) * 2 + kk) * 1024);
+}
+
+// The 12 MFMAs of one kd group at one (kw, k16) position.  The accumulator
+// set of output plane od = j - kd is (PH - kd) mod 3.  The kd = 0 set starts a
+// new output plane: its first contribution (SUB 0, kh 0) accumulates onto zero.
+template <int PH, int SUB, int KD>
+__device__ __forceinline__ void group_mfma(f32x16 (&acc)[3][RH], const XFrag& x, const WFrag& w) {
 #pragma unroll
-            for (int r = 0; r < RH + 2; ++r)
-                xin[r] = *(const bf16x8*)(in_lds + (c * NV + (row0 + r) * COLS + (lane & 31) + kw) * 16);
+    for (int kh = 0; kh < 3; ++kh) {
 #pragma unroll
-            for (int kd = 0; kd < 3; ++kd) {
-                if (kdmask & (1 << kd)) {
-#pragma unroll
-                    for (int kh = 0; kh < 3; ++kh) {
-                        bf16x8 wf = *(const bf16x8*)(w_lds + ((((kw * 3 + kd) * 3 + kh) * 2 + kk) * 64 + lane) * 16);
-#pragma unroll
-                        for (int r = 0; r < RH; ++r)
-                            acc[(PH + 3 - kd) % 3][r] = mfma(wf, xin[r + kh], acc[(PH + 3 - kd) % 3][r]);
-                    }
-                }
+        for (int r = 0; r < RH; ++r) {
+            f32x16& a = acc[(PH + 3 - KD) % 3][r];
+            if (KD == 0 && SUB == 0 && kh == 0) {
+                f32x16 z = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+                a = mfma(w.v[kh], x.v[r + kh], z);
+            } else {
+                a = mfma(w.v[kh], x.v[r + kh], a);
             }
         }
     }
 }
 
-__device__ __forceinline__ uint32_t pack2(float a, float b) {
-    return (uint32_t)f32_to_bf16_rne(a) | ((uint32_t)f32_to_bf16_rne(b) << 16);
+__device__ __forceinline__ void convert_rows(const f32x16 (&a)[RH], uint32_t (&o)[RH][8]);
+
+#define SP_FENCE() __builtin_amdgcn_sched_barrier(0)
+
+// One (kw, k16) position: kd groups 2, 1, 0 (oldest output plane first), with
+// the LDS reads of the next position issued between the groups so that they
+// are in flight for at least one group of MFMAs.
+template <int PH, int SUB>
+__device__ __forceinline__ void sub_step(f32x16 (&acc)[3][RH], XFrag& xc, XFrag& xn, WFrag& w2, WFrag& w1, WFrag& w0,
+                                         const char* in_lane, const char* w_lane, uint32_t (&outp)[RH][8]) {
+    constexpr bool last = SUB == 5;
+    load_w<SUB, 0>(w0, w_lane);
+    group_mfma<PH, SUB, 2>(acc, xc, w2);
+    SP_FENCE();
+    if (!last) load_x<last ? 0 : SUB + 1>(xn, in_lane);
+    if (last) convert_rows(acc[(PH + 1) % 3], outp);
+    group_mfma<PH, SUB, 1>(acc, xc, w1);
+    SP_FENCE();
+    if (!last) load_w<last ? 0 : SUB + 1, 2>(w2, w_lane);
+    group_mfma<PH, SUB, 0>(acc, xc, w0);
+    SP_FENCE();
+    if (!last) load_w<last ? 0 : SUB + 1, 1>(w1, w_lane);
 }
 
-__device__ __forceinline__ void store_rows(f32x16 (&a)[RH], uint16_t* yplane, int oh0, int ow, int Ho, int Wo, int Cout,
-                                           int co0, int lane) {
+// All 216 MFMAs of one staged input plane.  Steps at the ends of a segment
+// also run in full: what they add to output planes outside the segment lands
+// in accumulator sets that are never stored and are restarted from zero.
+template <int PH>
+__device__ __forceinline__ void plane_compute(f32x16 (&acc)[3][RH], const char* in_lane, const char* w_lane,
+                                              uint32_t (&outp)[RH][8]) {
+    XFrag xa, xb;
+    WFrag w2, w1, w0;
+    load_x<0>(xa, in_lane);
+    load_w<0, 2>(w2, w_lane);
+    load_w<0, 1>(w1, w_lane);
+    sub_step<PH, 0>(acc, xa, xb, w2, w1, w0, in_lane, w_lane, outp);
+    sub_step<PH, 1>(acc, xb, xa, w2, w1, w0, in_lane, w_lane, outp);
+    sub_step<PH, 2>(acc, xa, xb, w2, w1, w0, in_lane, w_lane, outp);
+    sub_step<PH, 3>(acc, xb, xa, w2, w1, w0, in_lane, w_lane, outp);
+    sub_step<PH, 4>(acc, xa, xb, w2, w1, w0, in_lane, w_lane, outp);
+    sub_step<PH, 5>(acc, xb, xa, w2, w1, w0, in_lane, w_lane, outp);
+}
+
+// fp32 accumulators of one finished output plane -> packed bf16 (RNE)
+__device__ __forceinline__ void convert_rows(const f32x16 (&a)[RH], uint32_t (&o)[RH][8]) {
+#pragma unroll
+    for (int r = 0; r < RH; ++r)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            f32x2 v = {a[r][2 * i], a[r][2 * i + 1]};
+            bf16x2 b = __builtin_convertvector(v, bf16x2);
+            o[r][i] = __builtin_bit_cast(uint32_t, b);
+        }
+}
+
+__device__ __forceinline__ void store_rows(const uint32_t (&o)[RH][8], uint16_t* yplane, int oh0, int ow, int Ho, int Wo,
+                                           int Cout, int co0, int lane) {
 #pragma unroll
     for (int r = 0; r < RH; ++r) {
         int oh = oh0 + r;
@@ -86,14 +149,10 @@ __device__ __forceinline__ void store_rows(f32x16 (&a)[RH], uint16_t* yplane, in
             uint16_t* p = yplane + ((long long)oh * Wo + ow) * Cout + co0 + 4 * (lane >> 5);
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
-                uint2 v;
-                v.x = pack2(a[r][4 * g + 0], a[r][4 * g + 1]);
-                v.y = pack2(a[r][4 * g + 2], a[r][4 * g + 3]);
+                uint2 v = {o[r][2 * g], o[r][2 * g + 1]};
                 *(uint2*)(p + 8 * g) = v;
             }
         }
-#pragma unroll
-        for (int i = 0; i < 16; ++i) a[r][i] = 0.f;
     }
 }
 
@@ -110,24 +169,20 @@ __global__ void __launch_bounds__(256, 1) sp_conv_kernel(SpParams P) {
     if ((P.nwg & 7) == 0) g = (g & 7) * (P.nwg >> 3) + (g >> 3);
     long long u0 = P.units * g / P.nwg, u1 = P.units * (g + 1) / P.nwg;
 
-    // per-thread load plan for one plane patch (does not depend on the plane)
-    int lds_off[NLOAD], rowcol[NLOAD];
+    // per-thread load plan for one plane patch: thread t moves the 16-byte
+    // pieces q = t + 256 i; piece q is channels 8c..8c+7 of voxel q / 4
+    int lds_off[NLOAD];
 #pragma unroll
     for (int i = 0; i < NLOAD; ++i) {
         int q = t + 256 * i;
         int v = q >> 2, c = q & 3;
-        int row = v / IN_COLS, col = v - row * IN_COLS;
+        int row = (v * 241) >> 13, col = v - row * IN_COLS;  // v / 34 for v < 700
         lds_off[i] = (c * NV + row * COLS + col) * 16;
-        rowcol[i] = (q < IN_ROWS * IN_COLS * 4) ? ((row << 16) | (col << 4) | (c << 1) | 1) : 0;
     }
-
+    constexpr int NPIECE = IN_ROWS * IN_COLS * 4;
     f32x16 acc[3][RH];
-#pragma unroll
-    for (int s = 0; s < 3; ++s)
-#pragma unroll
-        for (int r = 0; r < RH; ++r)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) acc[s][r][i] = 0.f;
+    const int lane_in_off = ((lane >> 5) * NV + wave * RH * COLS + (lane & 31)) * 16;
+    const char* w_lane = w_lds + lane * 16;
 
     int cur_ct = -1;
     while (u0 < u1) {
@@ -151,9 +206,11 @@ __global__ void __launch_bounds__(256, 1) sp_conv_kernel(SpParams P) {
         unsigned valid = 0;
 #pragma unroll
         for (int i = 0; i < NLOAD; ++i) {
-            int row = rowcol[i] >> 16, col = (rowcol[i] >> 4) & 0xfff, c = (rowcol[i] >> 1) & 7;
+            int q = t + 256 * i;
+            int v = q >> 2, c = q & 3;
+            int row = (v * 241) >> 13, col = v - row * IN_COLS;
             int gh = h0 - P.pH + row, gw = w0 - P.pW + col;
-            bool ok = (rowcol[i] & 1) && gh >= 0 && gh < P.H && gw >= 0 && gw < P.W;
+            bool ok = q < NPIECE && gh >= 0 && gh < P.H && gw >= 0 && gw < P.W;
             goff[i] = ok ? (gh * P.W + gw) * P.Cin + c * 8 : 0;
             valid |= (ok ? 1u : 0u) << i;
         }
@@ -163,52 +220,63 @@ __global__ void __launch_bounds__(256, 1) sp_conv_kernel(SpParams P) {
         const int nJ = od_end - od_start + 2;
         uint4 pre[NLOAD];
 
+        // a plane outside [0, D) is zero padding: stage zeros.  Loads are
+        // unconditional (masked pieces read element 0 of a valid plane) and
+        // zeroed afterwards, so that the piece registers never pass through memory.
         auto load_plane = [&](int ip) {
-            const uint16_t* base = xn + (long long)ip * plane_elems;
+            const bool inside = ip >= 0 && ip < P.D;
+            const uint16_t* base = xn + (long long)(inside ? ip : 0) * plane_elems;
+            const unsigned vm = inside ? valid : 0u;
 #pragma unroll
             for (int i = 0; i < NLOAD; ++i) {
-                uint4 z = {0, 0, 0, 0};
-                pre[i] = ((valid >> i) & 1) ? *(const uint4*)(base + goff[i]) : z;
+                uint4 v = *(const uint4*)(base + goff[i]);
+                const bool ok = (vm >> i) & 1;
+                pre[i].x = ok ? v.x : 0u;
+                pre[i].y = ok ? v.y : 0u;
+                pre[i].z = ok ? v.z : 0u;
+                pre[i].w = ok ? v.w : 0u;
             }
         };
         auto write_plane = [&](int buf) {
+            char* dst = in_lds + buf * STAGE_BYTES;
 #pragma unroll
             for (int i = 0; i < NLOAD; ++i)
-                if (rowcol[i] & 1) *(uint4*)(in_lds + buf * STAGE_BYTES + lds_off[i]) = pre[i];
+                if (t + 256 * i < NPIECE) *(uint4*)(dst + lds_off[i]) = pre[i];
         };
 
-        {
-            int ip = od_start - P.pD;
-            if (ip >= 0 && ip < P.D) { load_plane(ip); write_plane(0); }
-        }
+        // every segment starts from cleared accumulators (keeps them dead across segments)
+#pragma unroll
+        for (int s = 0; s < 3; ++s)
+#pragma unroll
+            for (int r = 0; r < RH; ++r)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) acc[s][r][i] = 0.f;
+
+        load_plane(od_start - P.pD);
+        write_plane(0);
         __syncthreads();
 
-#define SP_STEP(PHASE, JJ)                                                                      \
+        // step jj stages input plane ip = od_start + jj - pD; it completes output plane od_start + jj - 2
+#define SP_STEP(PHASE)                                                                          \
         {                                                                                       \
-            const int jj_ = (JJ);                                                               \
-            const int j_ = od_start + jj_;                                                      \
-            const int ip_ = j_ - P.pD;                                                          \
-            const bool valid_ = ip_ >= 0 && ip_ < P.D;                                          \
-            const bool validn_ = (jj_ + 1 < nJ) && (ip_ + 1 >= 0) && (ip_ + 1 < P.D);           \
-            if (validn_) load_plane(ip_ + 1);                                                   \
-            if (valid_) {                                                                       \
-                int m_ = 0;                                                                     \
-                for (int kd = 0; kd < 3; ++kd)                                                  \
-                    if (j_ - kd >= od_start && j_ - kd < od_end) m_ |= 1 << kd;                 \
-                plane_compute<PHASE>(acc, in_lds + (jj_ & 1) * STAGE_BYTES, w_lds, m_, lane, wave); \
-            }                                                                                   \
-            if (validn_) write_plane((jj_ + 1) & 1);                                            \
-            __syncthreads();                                                                    \
-            if (jj_ >= 2) {                                                                     \
-                const int od_ = j_ - 2;                                                         \
-                store_rows(acc[((PHASE) + 1) % 3], yn + (long long)od_ * P.Ho * P.Wo * P.Cout,  \
+            const int j_ = od_start + jj;                                                       \
+            const bool more_ = jj + 1 < nJ;                                                     \
+            if (more_) load_plane(j_ + 1 - P.pD);                                               \
+            uint32_t outp_[RH][8];                                                              \
+            plane_compute<PHASE>(acc, in_lds + (jj & 1) * STAGE_BYTES + lane_in_off, w_lane, outp_); \
+            if (more_) write_plane((jj + 1) & 1);                                               \
+            if (jj >= 2)                                                                        \
+                store_rows(outp_, yn + (long long)(j_ - 2) * P.Ho * P.Wo * P.Cout,              \
                            h0 + wave * RH, w0 + (lane & 31), P.Ho, P.Wo, P.Cout, ct * 32, lane); \
-            }                                                                                   \
+            __syncthreads();                                                                    \
         }
-        for (int jj = 0; jj < nJ; jj += 3) {
-            SP_STEP(0, jj)
-            if (jj + 1 < nJ) SP_STEP(1, jj + 1)
-            if (jj + 2 < nJ) SP_STEP(2, jj + 2)
+        for (int jj = 0;;) {
+            SP_STEP(0)
+            if (++jj >= nJ) break;
+            SP_STEP(1)
+            if (++jj >= nJ) break;
+            SP_STEP(2)
+            if (++jj >= nJ) break;
         }
 #undef SP_STEP
     }
