@@ -140,18 +140,26 @@ __device__ __forceinline__ void convert_rows(const f32x16 (&a)[RH], uint32_t (&o
         }
 }
 
+// Lanes l and l+32 hold the two interleaved halves of a voxel's 32 couts
+// (4 couts of every group of 8).  Swapping between the lane halves gives each
+// lane 16 consecutive couts, stored as two 16-byte pieces.
 __device__ __forceinline__ void store_rows(const uint32_t (&o)[RH][8], uint16_t* yplane, int oh0, int ow, int Ho, int Wo,
                                            int Cout, int co0, int lane) {
+    typedef __attribute__((ext_vector_type(2))) unsigned u32x2;
 #pragma unroll
     for (int r = 0; r < RH; ++r) {
+        uint4 c[2];
+#pragma unroll
+        for (int k = 0; k < 2; ++k) {  // k = 0: cout groups 0 and 2, k = 1: groups 1 and 3
+            u32x2 s0 = __builtin_amdgcn_permlane32_swap(o[r][2 * k], o[r][2 * k + 4], false, false);
+            u32x2 s1 = __builtin_amdgcn_permlane32_swap(o[r][2 * k + 1], o[r][2 * k + 5], false, false);
+            c[k].x = s0[0]; c[k].y = s1[0]; c[k].z = s0[1]; c[k].w = s1[1];
+        }
         int oh = oh0 + r;
         if (oh < Ho && ow < Wo) {
-            uint16_t* p = yplane + ((long long)oh * Wo + ow) * Cout + co0 + 4 * (lane >> 5);
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                uint2 v = {o[r][2 * g], o[r][2 * g + 1]};
-                *(uint2*)(p + 8 * g) = v;
-            }
+            uint16_t* p = yplane + ((long long)oh * Wo + ow) * Cout + co0 + 16 * (lane >> 5);
+            *(uint4*)p = c[0];
+            *(uint4*)(p + 8) = c[1];
         }
     }
 }
@@ -223,25 +231,28 @@ __global__ void __launch_bounds__(256, 1) sp_conv_kernel(SpParams P) {
         // a plane outside [0, D) is zero padding: stage zeros.  Loads are
         // unconditional (masked pieces read element 0 of a valid plane) and
         // zeroed afterwards, so that the piece registers never pass through memory.
+        unsigned pre_mask = 0;
         auto load_plane = [&](int ip) {
             const bool inside = ip >= 0 && ip < P.D;
             const uint16_t* base = xn + (long long)(inside ? ip : 0) * plane_elems;
-            const unsigned vm = inside ? valid : 0u;
+            pre_mask = inside ? valid : 0u;
 #pragma unroll
-            for (int i = 0; i < NLOAD; ++i) {
-                uint4 v = *(const uint4*)(base + goff[i]);
-                const bool ok = (vm >> i) & 1;
-                pre[i].x = ok ? v.x : 0u;
-                pre[i].y = ok ? v.y : 0u;
-                pre[i].z = ok ? v.z : 0u;
-                pre[i].w = ok ? v.w : 0u;
-            }
+            for (int i = 0; i < NLOAD; ++i) pre[i] = *(const uint4*)(base + goff[i]);
         };
+        // the zeroing of masked pieces happens here, after the MFMA work, so
+        // that nothing waits for the global loads before the compute starts
         auto write_plane = [&](int buf) {
             char* dst = in_lds + buf * STAGE_BYTES;
 #pragma unroll
-            for (int i = 0; i < NLOAD; ++i)
-                if (t + 256 * i < NPIECE) *(uint4*)(dst + lds_off[i]) = pre[i];
+            for (int i = 0; i < NLOAD; ++i) {
+                const bool ok = (pre_mask >> i) & 1;
+                uint4 v;
+                v.x = ok ? pre[i].x : 0u;
+                v.y = ok ? pre[i].y : 0u;
+                v.z = ok ? pre[i].z : 0u;
+                v.w = ok ? pre[i].w : 0u;
+                if (t + 256 * i < NPIECE) *(uint4*)(dst + lds_off[i]) = v;
+            }
         };
 
         // every segment starts from cleared accumulators (keeps them dead across segments)
@@ -257,18 +268,21 @@ __global__ void __launch_bounds__(256, 1) sp_conv_kernel(SpParams P) {
         __syncthreads();
 
         // step jj stages input plane ip = od_start + jj - pD; it completes output plane od_start + jj - 2
+#ifndef SP_EXP
+#define SP_EXP 0
+#endif
 #define SP_STEP(PHASE)                                                                          \
         {                                                                                       \
             const int j_ = od_start + jj;                                                       \
             const bool more_ = jj + 1 < nJ;                                                     \
-            if (more_) load_plane(j_ + 1 - P.pD);                                               \
+            if (more_ && !(SP_EXP & 1)) load_plane(j_ + 1 - P.pD);                                               \
             uint32_t outp_[RH][8];                                                              \
             plane_compute<PHASE>(acc, in_lds + (jj & 1) * STAGE_BYTES + lane_in_off, w_lane, outp_); \
-            if (more_) write_plane((jj + 1) & 1);                                               \
-            if (jj >= 2)                                                                        \
+            if (more_ && !(SP_EXP & 1)) write_plane((jj + 1) & 1);                                               \
+            if (jj >= 2 && (!(SP_EXP & 2) || P.N == 12345))                                                                        \
                 store_rows(outp_, yn + (long long)(j_ - 2) * P.Ho * P.Wo * P.Cout,              \
                            h0 + wave * RH, w0 + (lane & 31), P.Ho, P.Wo, P.Cout, ct * 32, lane); \
-            __syncthreads();                                                                    \
+            if (!(SP_EXP & 4)) __syncthreads();                                                                    \
         }
         for (int jj = 0;;) {
             SP_STEP(0)
