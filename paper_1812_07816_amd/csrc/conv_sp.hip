@@ -92,19 +92,22 @@ __device__ __forceinline__ void convert_rows(const f32x16 (&a)[RH], uint32_t (&o
 // One (kw, k16) position: kd groups 2, 1, 0 (oldest output plane first), with
 // the LDS reads of the next position issued between the groups so that they
 // are in flight for at least one group of MFMAs.
-template <int PH, int SUB>
+template <int PH, int SUB, class Hook>
 __device__ __forceinline__ void sub_step(f32x16 (&acc)[3][RH], XFrag& xc, XFrag& xn, WFrag& w2, WFrag& w1, WFrag& w0,
-                                         const char* in_lane, const char* w_lane, uint32_t (&outp)[RH][8]) {
+                                         const char* in_lane, const char* w_lane, uint32_t (&outp)[RH][8], Hook&& hook) {
     constexpr bool last = SUB == 5;
     load_w<SUB, 0>(w0, w_lane);
     group_mfma<PH, SUB, 2>(acc, xc, w2);
+    hook(3 * SUB + 0);
     SP_FENCE();
     if (!last) load_x<last ? 0 : SUB + 1>(xn, in_lane);
     if (last) convert_rows(acc[(PH + 1) % 3], outp);
     group_mfma<PH, SUB, 1>(acc, xc, w1);
+    hook(3 * SUB + 1);
     SP_FENCE();
     if (!last) load_w<last ? 0 : SUB + 1, 2>(w2, w_lane);
     group_mfma<PH, SUB, 0>(acc, xc, w0);
+    hook(3 * SUB + 2);
     SP_FENCE();
     if (!last) load_w<last ? 0 : SUB + 1, 1>(w1, w_lane);
 }
@@ -112,20 +115,23 @@ __device__ __forceinline__ void sub_step(f32x16 (&acc)[3][RH], XFrag& xc, XFrag&
 // All 216 MFMAs of one staged input plane.  Steps at the ends of a segment
 // also run in full: what they add to output planes outside the segment lands
 // in accumulator sets that are never stored and are restarted from zero.
-template <int PH>
+// hook(k), k = 0..17, is called once per group of 12 MFMAs: the caller spreads
+// its global loads and stores over the step with it, so that no wave ever
+// queues a burst of vector-memory instructions.
+template <int PH, class Hook>
 __device__ __forceinline__ void plane_compute(f32x16 (&acc)[3][RH], const char* in_lane, const char* w_lane,
-                                              uint32_t (&outp)[RH][8]) {
+                                              uint32_t (&outp)[RH][8], Hook&& hook) {
     XFrag xa, xb;
     WFrag w2, w1, w0;
     load_x<0>(xa, in_lane);
     load_w<0, 2>(w2, w_lane);
     load_w<0, 1>(w1, w_lane);
-    sub_step<PH, 0>(acc, xa, xb, w2, w1, w0, in_lane, w_lane, outp);
-    sub_step<PH, 1>(acc, xb, xa, w2, w1, w0, in_lane, w_lane, outp);
-    sub_step<PH, 2>(acc, xa, xb, w2, w1, w0, in_lane, w_lane, outp);
-    sub_step<PH, 3>(acc, xb, xa, w2, w1, w0, in_lane, w_lane, outp);
-    sub_step<PH, 4>(acc, xa, xb, w2, w1, w0, in_lane, w_lane, outp);
-    sub_step<PH, 5>(acc, xb, xa, w2, w1, w0, in_lane, w_lane, outp);
+    sub_step<PH, 0>(acc, xa, xb, w2, w1, w0, in_lane, w_lane, outp, hook);
+    sub_step<PH, 1>(acc, xb, xa, w2, w1, w0, in_lane, w_lane, outp, hook);
+    sub_step<PH, 2>(acc, xa, xb, w2, w1, w0, in_lane, w_lane, outp, hook);
+    sub_step<PH, 3>(acc, xb, xa, w2, w1, w0, in_lane, w_lane, outp, hook);
+    sub_step<PH, 4>(acc, xa, xb, w2, w1, w0, in_lane, w_lane, outp, hook);
+    sub_step<PH, 5>(acc, xb, xa, w2, w1, w0, in_lane, w_lane, outp, hook);
 }
 
 // fp32 accumulators of one finished output plane -> packed bf16 (RNE)
@@ -143,24 +149,18 @@ __device__ __forceinline__ void convert_rows(const f32x16 (&a)[RH], uint32_t (&o
 // Lanes l and l+32 hold the two interleaved halves of a voxel's 32 couts
 // (4 couts of every group of 8).  Swapping between the lane halves gives each
 // lane 16 consecutive couts, stored as two 16-byte pieces.
-__device__ __forceinline__ void store_rows(const uint32_t (&o)[RH][8], uint16_t* yplane, int oh0, int ow, int Ho, int Wo,
-                                           int Cout, int co0, int lane) {
+__device__ __forceinline__ void store_row(const uint32_t (&o)[8], uint16_t* p, bool ok) {
     typedef __attribute__((ext_vector_type(2))) unsigned u32x2;
+    uint4 c[2];
 #pragma unroll
-    for (int r = 0; r < RH; ++r) {
-        uint4 c[2];
-#pragma unroll
-        for (int k = 0; k < 2; ++k) {  // k = 0: cout groups 0 and 2, k = 1: groups 1 and 3
-            u32x2 s0 = __builtin_amdgcn_permlane32_swap(o[r][2 * k], o[r][2 * k + 4], false, false);
-            u32x2 s1 = __builtin_amdgcn_permlane32_swap(o[r][2 * k + 1], o[r][2 * k + 5], false, false);
-            c[k].x = s0[0]; c[k].y = s1[0]; c[k].z = s0[1]; c[k].w = s1[1];
-        }
-        int oh = oh0 + r;
-        if (oh < Ho && ow < Wo) {
-            uint16_t* p = yplane + ((long long)oh * Wo + ow) * Cout + co0 + 16 * (lane >> 5);
-            *(uint4*)p = c[0];
-            *(uint4*)(p + 8) = c[1];
-        }
+    for (int k = 0; k < 2; ++k) {  // k = 0: cout groups 0 and 2, k = 1: groups 1 and 3
+        u32x2 s0 = __builtin_amdgcn_permlane32_swap(o[2 * k], o[2 * k + 4], false, false);
+        u32x2 s1 = __builtin_amdgcn_permlane32_swap(o[2 * k + 1], o[2 * k + 5], false, false);
+        c[k].x = s0[0]; c[k].y = s1[0]; c[k].z = s0[1]; c[k].w = s1[1];
+    }
+    if (ok) {
+        *(uint4*)p = c[0];
+        *(uint4*)(p + 8) = c[1];
     }
 }
 
@@ -232,13 +232,13 @@ __global__ void __launch_bounds__(256, 1) sp_conv_kernel(SpParams P) {
         // unconditional (masked pieces read element 0 of a valid plane) and
         // zeroed afterwards, so that the piece registers never pass through memory.
         unsigned pre_mask = 0;
-        auto load_plane = [&](int ip) {
+        const uint16_t* pre_base = xn;
+        auto begin_plane = [&](int ip) {
             const bool inside = ip >= 0 && ip < P.D;
-            const uint16_t* base = xn + (long long)(inside ? ip : 0) * plane_elems;
+            pre_base = xn + (long long)(inside ? ip : 0) * plane_elems;
             pre_mask = inside ? valid : 0u;
-#pragma unroll
-            for (int i = 0; i < NLOAD; ++i) pre[i] = *(const uint4*)(base + goff[i]);
         };
+        auto load_piece = [&](int i) { pre[i] = *(const uint4*)(pre_base + goff[i]); };
         // the zeroing of masked pieces happens here, after the MFMA work, so
         // that nothing waits for the global loads before the compute starts
         auto write_plane = [&](int buf) {
@@ -254,6 +254,15 @@ __global__ void __launch_bounds__(256, 1) sp_conv_kernel(SpParams P) {
                 if (t + 256 * i < NPIECE) *(uint4*)(dst + lds_off[i]) = v;
             }
         };
+        // finished rows wait in outp[] and are stored during the next step
+        uint32_t outp[RH][8];
+        uint16_t* st_ptr = yn;    // address of row 0 of the pending plane for this lane
+        bool st_pending = false;
+        const int ow_ = w0 + (lane & 31);
+        const long long row_pitch = (long long)P.Wo * P.Cout;
+        auto store_piece = [&](int r) {
+            store_row(outp[r], st_ptr + r * row_pitch, st_pending && ow_ < P.Wo && h0 + wave * RH + r < P.Ho);
+        };
 
         // every segment starts from cleared accumulators (keeps them dead across segments)
 #pragma unroll
@@ -263,26 +272,28 @@ __global__ void __launch_bounds__(256, 1) sp_conv_kernel(SpParams P) {
 #pragma unroll
                 for (int i = 0; i < 16; ++i) acc[s][r][i] = 0.f;
 
-        load_plane(od_start - P.pD);
+        begin_plane(od_start - P.pD);
+#pragma unroll
+        for (int i = 0; i < NLOAD; ++i) load_piece(i);
         write_plane(0);
         __syncthreads();
 
-        // step jj stages input plane ip = od_start + jj - pD; it completes output plane od_start + jj - 2
-#ifndef SP_EXP
-#define SP_EXP 0
-#endif
+        // step jj stages input plane ip = od_start + jj - pD; it completes output plane od_start + jj - 2.
+        // Hook slots 0..9 issue the loads of the next plane, slots 10..13 the stores of the plane finished
+        // by the previous step (they must precede slot 15, where outp[] is overwritten).
 #define SP_STEP(PHASE)                                                                          \
         {                                                                                       \
             const int j_ = od_start + jj;                                                       \
             const bool more_ = jj + 1 < nJ;                                                     \
-            if (more_ && !(SP_EXP & 1)) load_plane(j_ + 1 - P.pD);                                               \
-            uint32_t outp_[RH][8];                                                              \
-            plane_compute<PHASE>(acc, in_lds + (jj & 1) * STAGE_BYTES + lane_in_off, w_lane, outp_); \
-            if (more_ && !(SP_EXP & 1)) write_plane((jj + 1) & 1);                                               \
-            if (jj >= 2 && (!(SP_EXP & 2) || P.N == 12345))                                                                        \
-                store_rows(outp_, yn + (long long)(j_ - 2) * P.Ho * P.Wo * P.Cout,              \
-                           h0 + wave * RH, w0 + (lane & 31), P.Ho, P.Wo, P.Cout, ct * 32, lane); \
-            if (!(SP_EXP & 4)) __syncthreads();                                                                    \
+            begin_plane(j_ + 1 - P.pD);                                                         \
+            plane_compute<PHASE>(acc, in_lds + (jj & 1) * STAGE_BYTES + lane_in_off, w_lane, outp, [&](int k) { \
+                if (k < NLOAD) { if (more_) load_piece(k); }                   \
+                else if (k < NLOAD + RH) store_piece(k - NLOAD);         \
+            });                                                                                 \
+            if (more_) write_plane((jj + 1) & 1);                                               \
+            st_pending = jj >= 2;                                                               \
+            st_ptr = yn + (((long long)(j_ - 2) * P.Ho + h0 + wave * RH) * P.Wo + ow_) * P.Cout + ct * 32 + 16 * (lane >> 5); \
+            __syncthreads();                                                                    \
         }
         for (int jj = 0;;) {
             SP_STEP(0)
@@ -293,6 +304,8 @@ __global__ void __launch_bounds__(256, 1) sp_conv_kernel(SpParams P) {
             if (++jj >= nJ) break;
         }
 #undef SP_STEP
+#pragma unroll
+        for (int r = 0; r < RH; ++r) store_piece(r);  // the last plane of the segment
     }
 }
 
