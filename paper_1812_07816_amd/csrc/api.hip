@@ -43,9 +43,10 @@ int make_geom(const mi3d_conv_desc* d, Geom* g) {
 
 static bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
 
-enum Kernel { K_DIRECT = 0, K_SP = 1, K_NONE = -1 };
+enum Kernel { K_DIRECT = 0, K_SP = 1, K_WGRAD_MFMA = 2, K_NONE = -1 };
 
 static Kernel choose(const Geom& g, int pass) {
+    if (pass == MI3D_PASS_WGRAD && wgrad_mfma_supported(g)) return K_WGRAD_MFMA;
     if (sp_supported(g, pass)) return K_SP;
     return K_DIRECT;
 }
@@ -54,6 +55,7 @@ static const char* kernel_name(Kernel k) {
     switch (k) {
         case K_DIRECT: return "direct";
         case K_SP: return "mfma_plane_stream";
+        case K_WGRAD_MFMA: return "mfma_wgrad_plane_stream";
         default: return "none";
     }
 }
@@ -110,7 +112,12 @@ size_t mi3d_conv3d_workspace_bytes(const mi3d_conv_desc* desc, int pass) {
     // the plain kernels must always be runnable (family 1), so report the max
     size_t need = direct_workspace_bytes(g, pass);
     size_t sp = sp_workspace_bytes(g, pass);
-    return need > sp ? need : sp;
+    if (sp > need) need = sp;
+    if (pass == MI3D_PASS_WGRAD) {
+        size_t wg = wgrad_mfma_workspace_bytes(g);
+        if (wg > need) need = wg;
+    }
+    return need;
 }
 
 int mi3d_conv3d_fwd(const mi3d_conv_desc* desc, const void* x, const void* w, void* y, void* ws, size_t ws_bytes, void* stream) {
@@ -153,6 +160,7 @@ int mi3d_conv3d_wgrad(const mi3d_conv_desc* desc, const void* x, const void* dy,
     Kernel k = g_family.load() == 1 ? K_DIRECT : choose(g, MI3D_PASS_WGRAD);
     switch (k) {
         case K_DIRECT: return direct_wgrad(g, x, dy, dw, ws, ws_bytes, (hipStream_t)stream);
+        case K_WGRAD_MFMA: return wgrad_mfma(g, x, dy, dw, ws, ws_bytes, (hipStream_t)stream);
         default: return MI3D_ERR_UNSUPPORTED;
     }
 }

@@ -1,0 +1,336 @@
+// Weight gradient of 3x3x3 / stride 1 layers on bf16 MFMA
+// (v_mfma_f32_16x16x32_bf16), fp32 accumulation and fp32 output:
+//   dw[co,t,ci] = sum_{n,o} dy[n,o,co] * x[n, o - p + t, ci]
+// the pass that needs the saved input feature map of the layer (Section 3.1).
+//
+// The contraction runs over voxels, which are strided by the channel count in
+// NDHWC, so both MFMA operands need a transposing read: tiles are staged in
+// LDS as [16-channel slab][row][voxel] and fetched with ds_read_b64_tr_b16,
+// which hands each lane 4 consecutive voxels of one channel.
+//
+// Work decomposition
+//   pair    = (32-wide cout tile, 32-wide cin tile); a workgroup serves one pair
+//   column  = (n, 16-row x 32-col patch of the dy plane)
+//   unit    = (column, x plane id); contiguous unit ranges per workgroup.
+//   A step stages one x plane patch with halo (18 x 34 voxels) and keeps a ring
+//   of the three dy plane patches od = id + pD - kd.  Each of the 4 waves owns
+//   a 16x16 (co, ci) quadrant for all 27 taps (27 accumulators of 4 registers)
+//   and walks the 18 x rows: an x fragment (one per kw) meets the 3x3 window
+//   of dy fragments (kd, kh) held in registers, so one LDS fragment feeds 9
+//   MFMAs.  Partial sums go to a per-workgroup slot of the workspace and are
+//   added in slot order by a second kernel, which makes the result
+//   bit-reproducible.
+#include "mi3d_internal.h"
+
+namespace mi3d {
+namespace {
+
+typedef __attribute__((__vector_size__(4 * sizeof(short)))) short s16x4;
+typedef __attribute__((__vector_size__(8 * sizeof(short)))) short s16x8;
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
+
+constexpr int TH = 16, TW = 32;
+constexpr int XR = TH + 2, XC = TW + 2;          // x patch with halo
+constexpr int X_SLAB = XR * XC * 32;             // bytes of one 16-channel slab of the x patch
+constexpr int X_BYTES = 2 * X_SLAB;
+constexpr int DY_SLAB = TH * TW * 32;
+constexpr int DY_BYTES = 2 * DY_SLAB;
+constexpr int NX = (XR * XC * 4 + 255) / 256;    // 16-byte pieces per thread: x patch (10)
+constexpr int NDY = TH * TW * 4 / 256;           // dy patch (8)
+constexpr int XPIECES = XR * XC * 4;
+
+struct WgParams {
+    const uint16_t* x;
+    const uint16_t* dy;
+    float* part;            // [slots][Cout][27][Cin]
+    int N, D, H, W, Cin, Cout, Do, Ho, Wo, pD, pH, pW;
+    int HT, WT, CiT, CoT;
+    long long units;        // per pair: N*HT*WT*D
+    int slots;              // workgroups per pair
+};
+
+__device__ __forceinline__ bf16x8 tr_frag(const char* p) {
+    typedef __attribute__((address_space(3))) s16x4* lptr;
+    s16x4 a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lptr)(p));
+    s16x4 b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lptr)(p + 16 * 32));  // voxels +16
+    s16x8 c = __builtin_shufflevector(a, b, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8, c);
+}
+
+__device__ __forceinline__ f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+}
+
+#define WG_FENCE() __builtin_amdgcn_sched_barrier(0)
+
+// x row R of the patch against the dy rows R - kh.  dyw[kd][slot] is the
+// register window of dy fragments, slot = dy row mod 4; xf holds the three kw
+// shifts of the current row, xn receives those of the next row.
+template <int R, class Hook>
+__device__ __forceinline__ void row_step(f32x4 (&acc)[3][3][3], bf16x8 (&dyw)[3][4], bf16x8 (&xf)[3], bf16x8 (&xn)[3],
+                                         const char* x_lane, const char* const (&dy_lane)[3], Hook&& hook) {
+    // prefetch for row R + 1: its dy fragments (one per kd) and x fragments (one per kw)
+    if (R + 1 < TH) {
+#pragma unroll
+        for (int kd = 0; kd < 3; ++kd) dyw[kd][(R + 1) % 4] = tr_frag(dy_lane[kd] + (R + 1) * TW * 32);
+    }
+    if (R + 1 < XR) {
+#pragma unroll
+        for (int kw = 0; kw < 3; ++kw) xn[kw] = tr_frag(x_lane + ((R + 1) * XC + kw) * 32);
+    }
+#pragma unroll
+    for (int kh = 0; kh < 3; ++kh) {
+        constexpr int dummy = 0; (void)dummy;
+        const int dr = R - kh;  // dy row fed by this x row through tap kh
+        if (dr < 0 || dr >= TH) continue;
+#pragma unroll
+        for (int kd = 0; kd < 3; ++kd)
+#pragma unroll
+            for (int kw = 0; kw < 3; ++kw) acc[kd][kh][kw] = mfma16(dyw[kd][dr % 4], xf[kw], acc[kd][kh][kw]);
+    }
+    hook(R);
+    WG_FENCE();
+}
+
+template <class Hook>
+__device__ __forceinline__ void plane_step(f32x4 (&acc)[3][3][3], const char* x_lane, const char* const (&dy_lane)[3], Hook&& hook) {
+    bf16x8 dyw[3][4], xa[3], xb[3];
+#pragma unroll
+    for (int kd = 0; kd < 3; ++kd) dyw[kd][0] = tr_frag(dy_lane[kd]);
+#pragma unroll
+    for (int kw = 0; kw < 3; ++kw) xa[kw] = tr_frag(x_lane + kw * 32);
+    row_step<0>(acc, dyw, xa, xb, x_lane, dy_lane, hook);
+    row_step<1>(acc, dyw, xb, xa, x_lane, dy_lane, hook);
+    row_step<2>(acc, dyw, xa, xb, x_lane, dy_lane, hook);
+    row_step<3>(acc, dyw, xb, xa, x_lane, dy_lane, hook);
+    row_step<4>(acc, dyw, xa, xb, x_lane, dy_lane, hook);
+    row_step<5>(acc, dyw, xb, xa, x_lane, dy_lane, hook);
+    row_step<6>(acc, dyw, xa, xb, x_lane, dy_lane, hook);
+    row_step<7>(acc, dyw, xb, xa, x_lane, dy_lane, hook);
+    row_step<8>(acc, dyw, xa, xb, x_lane, dy_lane, hook);
+    row_step<9>(acc, dyw, xb, xa, x_lane, dy_lane, hook);
+    row_step<10>(acc, dyw, xa, xb, x_lane, dy_lane, hook);
+    row_step<11>(acc, dyw, xb, xa, x_lane, dy_lane, hook);
+    row_step<12>(acc, dyw, xa, xb, x_lane, dy_lane, hook);
+    row_step<13>(acc, dyw, xb, xa, x_lane, dy_lane, hook);
+    row_step<14>(acc, dyw, xa, xb, x_lane, dy_lane, hook);
+    row_step<15>(acc, dyw, xb, xa, x_lane, dy_lane, hook);
+    row_step<16>(acc, dyw, xa, xb, x_lane, dy_lane, hook);
+    row_step<17>(acc, dyw, xb, xa, x_lane, dy_lane, hook);
+}
+
+__device__ __forceinline__ int mod3(int v) { return ((v % 3) + 3) % 3; }
+
+__global__ void __launch_bounds__(256, 1) wgrad_kernel(WgParams P) {
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+    char* x_lds = lds;                 // one x patch
+    char* dy_lds = lds + X_BYTES;      // ring of three dy patches
+
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const int coh = wave >> 1, cih = wave & 1;   // 16x16 quadrant of the 32x32 (co, ci) tile
+    const int pair = blockIdx.y, slot = blockIdx.x;
+    const int cot = pair / P.CiT, cit = pair % P.CiT;
+    long long u0 = P.units * slot / P.slots, u1 = P.units * (slot + 1) / P.slots;
+
+    // per-lane part of the transposing reads: lane group g covers voxels 4g..4g+3
+    // (and +16 in the second read), lane s within the group supplies row s/4, channels 4(s%4)..
+    const int g = lane >> 4, s = lane & 15;
+    const int lane_off = (4 * g + (s >> 2)) * 32 + (s & 3) * 8;
+    const char* x_lane = x_lds + cih * X_SLAB + lane_off;
+
+    f32x4 acc[3][3][3];
+#pragma unroll
+    for (int a = 0; a < 3; ++a)
+#pragma unroll
+        for (int b = 0; b < 3; ++b)
+#pragma unroll
+            for (int c = 0; c < 3; ++c) acc[a][b][c] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    const long long x_plane = (long long)P.H * P.W * P.Cin;
+    const long long dy_plane = (long long)P.Ho * P.Wo * P.Cout;
+
+    while (u0 < u1) {
+        long long column = u0 / P.D;
+        const int id_start = (int)(u0 - column * P.D);
+        const long long left = u1 - u0;
+        const int id_end = id_start + (int)(left < (long long)(P.D - id_start) ? left : (long long)(P.D - id_start));
+        u0 += id_end - id_start;
+        const int wt = (int)(column % P.WT); column /= P.WT;
+        const int ht = (int)(column % P.HT);
+        const int n = (int)(column / P.HT);
+        const int h0 = ht * TH, w0 = wt * TW;
+
+        // load plans: x piece q = t + 256 i is channels 8c..8c+7 of patch voxel q / 4
+        int gx[NX], gdy[NDY];
+        unsigned vx = 0, vdy = 0;
+#pragma unroll
+        for (int i = 0; i < NX; ++i) {
+            int q = t + 256 * i, v = q >> 2, c = q & 3;
+            int row = (v * 241) >> 13, col = v - row * XC;  // v / 34
+            int gh = h0 - P.pH + row, gw = w0 - P.pW + col;
+            bool ok = q < XPIECES && gh >= 0 && gh < P.H && gw >= 0 && gw < P.W;
+            gx[i] = ok ? (gh * P.W + gw) * P.Cin + cit * 32 + c * 8 : 0;
+            vx |= (ok ? 1u : 0u) << i;
+        }
+#pragma unroll
+        for (int i = 0; i < NDY; ++i) {
+            int q = t + 256 * i, v = q >> 2, c = q & 3;
+            int row = v >> 5, col = v & 31;
+            int gh = h0 + row, gw = w0 + col;
+            bool ok = gh < P.Ho && gw < P.Wo;
+            gdy[i] = ok ? (gh * P.Wo + gw) * P.Cout + cot * 32 + c * 8 : 0;
+            vdy |= (ok ? 1u : 0u) << i;
+        }
+        const uint16_t* xn = P.x + (long long)n * P.D * x_plane;
+        const uint16_t* dyn = P.dy + (long long)n * P.Do * dy_plane;
+
+        uint4 px[NX], pdy[NDY];
+        unsigned mx = 0, mdy = 0;
+        const uint16_t *bx = xn, *bdy = dyn;
+        auto begin_x = [&](int id) {
+            const bool in = id >= 0 && id < P.D;
+            bx = xn + (long long)(in ? id : 0) * x_plane;
+            mx = in ? vx : 0u;
+        };
+        auto begin_dy = [&](int od) {
+            const bool in = od >= 0 && od < P.Do;
+            bdy = dyn + (long long)(in ? od : 0) * dy_plane;
+            mdy = in ? vdy : 0u;
+        };
+        auto write_x = [&]() {
+#pragma unroll
+            for (int i = 0; i < NX; ++i) {
+                int q = t + 256 * i, v = q >> 2, c = q & 3;
+                int row = (v * 241) >> 13, col = v - row * XC;
+                const bool ok = (mx >> i) & 1;
+                uint4 w;
+                w.x = ok ? px[i].x : 0u; w.y = ok ? px[i].y : 0u; w.z = ok ? px[i].z : 0u; w.w = ok ? px[i].w : 0u;
+                if (q < XPIECES) *(uint4*)(x_lds + (c >> 1) * X_SLAB + (row * XC + col) * 32 + (c & 1) * 16) = w;
+            }
+        };
+        auto write_dy = [&](int ring) {
+            char* dst = dy_lds + ring * DY_BYTES;
+#pragma unroll
+            for (int i = 0; i < NDY; ++i) {
+                int q = t + 256 * i, v = q >> 2, c = q & 3;
+                const bool ok = (mdy >> i) & 1;
+                uint4 w;
+                w.x = ok ? pdy[i].x : 0u; w.y = ok ? pdy[i].y : 0u; w.z = ok ? pdy[i].z : 0u; w.w = ok ? pdy[i].w : 0u;
+                *(uint4*)(dst + (c >> 1) * DY_SLAB + v * 32 + (c & 1) * 16) = w;
+            }
+        };
+
+        // prologue: x plane id_start and the dy planes of its three kd taps
+        __syncthreads();  // previous segment's readers are done with the LDS
+        begin_x(id_start);
+#pragma unroll
+        for (int i = 0; i < NX; ++i) px[i] = *(const uint4*)(bx + gx[i]);
+        write_x();
+        for (int kd = 0; kd < 3; ++kd) {
+            const int od = id_start + P.pD - kd;
+            begin_dy(od);
+#pragma unroll
+            for (int i = 0; i < NDY; ++i) pdy[i] = *(const uint4*)(bdy + gdy[i]);
+            write_dy(mod3(od));
+        }
+        __syncthreads();
+
+        for (int id = id_start; id < id_end; ++id) {
+            const bool more = id + 1 < id_end;
+            begin_x(id + 1);
+            begin_dy(id + 1 + P.pD);  // the plane that enters the ring for the next step
+            const char* dyl[3];
+#pragma unroll
+            for (int kd = 0; kd < 3; ++kd)
+                dyl[kd] = dy_lds + mod3(id + P.pD - kd) * DY_BYTES + coh * DY_SLAB + lane_off;
+            const char* const dy_lane[3] = {dyl[0], dyl[1], dyl[2]};
+            // one global load per x row: rows 0..9 fetch the next x patch, rows 10..17 the next dy patch
+            plane_step(acc, x_lane, dy_lane, [&](int r) {
+                if (!more) return;
+                if (r < NX) px[r] = *(const uint4*)(bx + gx[r]);
+                else if (r - NX < NDY) pdy[r - NX] = *(const uint4*)(bdy + gdy[r - NX]);
+            });
+            __syncthreads();  // everyone is done reading the x patch and the oldest dy patch
+            if (more) {
+                write_x();
+                write_dy(mod3(id + 1 + P.pD));
+            }
+            __syncthreads();
+        }
+    }
+
+    // partial sums of this workgroup: acc register v of lane l is
+    // (co = 4 (l / 16) + v, ci = l % 16) of the quadrant
+    float* out = P.part + (long long)slot * ((long long)P.Cout * 27 * P.Cin);
+#pragma unroll
+    for (int kd = 0; kd < 3; ++kd)
+#pragma unroll
+        for (int kh = 0; kh < 3; ++kh)
+#pragma unroll
+            for (int kw = 0; kw < 3; ++kw) {
+                const int tap = (kd * 3 + kh) * 3 + kw;
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int co = cot * 32 + coh * 16 + 4 * (lane >> 4) + v;
+                    const int ci = cit * 32 + cih * 16 + (lane & 15);
+                    out[((long long)co * 27 + tap) * P.Cin + ci] = acc[kd][kh][kw][v];
+                }
+            }
+}
+
+}  // namespace
+
+bool wgrad_mfma_supported(const Geom& g) {
+    if (g.dtype != MI3D_BF16 || g.kD != 3 || g.kH != 3 || g.kW != 3) return false;
+    if (g.sD != 1 || g.sH != 1 || g.sW != 1) return false;
+    if (g.pD > 2 || g.pH > 2 || g.pW > 2) return false;
+    return g.Cin % 32 == 0 && g.Cout % 32 == 0;
+}
+
+static int wgrad_slots(const Geom& g) {
+    long long pairs = (long long)(g.Cin / 32) * (g.Cout / 32);
+    long long units = (long long)g.N * ((g.Ho + TH - 1) / TH) * ((g.Wo + TW - 1) / TW) * g.D;
+    long long slots = (256 + pairs - 1) / pairs;   // about one workgroup per CU in total
+    if (slots > units) slots = units;
+    if (slots < 1) slots = 1;
+    return (int)slots;
+}
+
+size_t wgrad_mfma_workspace_bytes(const Geom& g) {
+    if (!wgrad_mfma_supported(g)) return 0;
+    return (size_t)wgrad_slots(g) * g.w_elems() * sizeof(float);
+}
+
+int wgrad_mfma(const Geom& g, const void* x, const void* dy, float* dw, void* ws, size_t ws_bytes, hipStream_t s) {
+    if (ws_bytes < wgrad_mfma_workspace_bytes(g)) return MI3D_ERR_WORKSPACE;
+    WgParams P;
+    P.x = (const uint16_t*)x;
+    P.dy = (const uint16_t*)dy;
+    P.part = (float*)ws;
+    P.N = g.N; P.D = g.D; P.H = g.H; P.W = g.W; P.Cin = g.Cin; P.Cout = g.Cout;
+    P.Do = g.Do; P.Ho = g.Ho; P.Wo = g.Wo; P.pD = g.pD; P.pH = g.pH; P.pW = g.pW;
+    P.HT = (g.Ho + TH - 1) / TH;
+    P.WT = (g.Wo + TW - 1) / TW;
+    P.CiT = g.Cin / 32;
+    P.CoT = g.Cout / 32;
+    P.units = (long long)g.N * P.HT * P.WT * g.D;
+    P.slots = wgrad_slots(g);
+    const int pairs = P.CiT * P.CoT;
+    if (pairs > 65535) return MI3D_ERR_UNSUPPORTED;
+    size_t lds = X_BYTES + 3 * DY_BYTES;
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void*)wgrad_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) { note_hip_error(e); return MI3D_ERR_HIP; }
+        attr_set = true;
+    }
+    wgrad_kernel<<<dim3((unsigned)P.slots, (unsigned)pairs), 256, lds, s>>>(P);
+    int st = check_launch();
+    if (st) return st;
+    long long n = g.w_elems();
+    reduce_partials_kernel<<<(unsigned)((n + 255) / 256), 256, 0, s>>>((const float*)ws, dw, n, P.slots);
+    return check_launch();
+}
+
+}  // namespace mi3d

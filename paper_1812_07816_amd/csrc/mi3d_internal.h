@@ -50,4 +50,10 @@ bool sp_supported(const Geom& g, int pass);
 size_t sp_workspace_bytes(const Geom& g, int pass);
 int sp_conv(const Geom& g, int pass, const void* in, const void* w, void* out, void* ws, size_t ws_bytes, hipStream_t s);
 
+
+// MFMA weight gradient: bf16, 3x3x3, stride 1, channels in multiples of 32
+bool wgrad_mfma_supported(const Geom& g);
+size_t wgrad_mfma_workspace_bytes(const Geom& g);
+int wgrad_mfma(const Geom& g, const void* x, const void* dy, float* dw, void* ws, size_t ws_bytes, hipStream_t s);
+
 }  // namespace mi3d
