@@ -1,0 +1,179 @@
+#!/usr/bin/env python3
+"""Benchmark of the hot path on one MI355X.
+
+A step = forward, data-gradient and weight-gradient passes of the full-size
+first U-Net level (192^3: Conv3D 4->32, 32->32 and the stride-2 32->64) with
+the data-swapping engine moving saved activations to pinned host memory and
+back under a device budget.  Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, published
+HBM_PEAK_GBS = 8000.0
+
+
+def cpu_baseline(seconds_target=15.0):
+    """The fp64 oracle as it stands, timed on this host: fwd + dgrad + wgrad of
+    a 32->32 3x3x3 layer on a cube sized for roughly `seconds_target` of work."""
+    import numpy as np
+    import synth_inputs as si
+    from oracle import conv3d as oc
+    cores = len(os.sched_getaffinity(0))
+    os.environ.setdefault("OMP_NUM_THREADS", str(cores))
+
+    def run(vol):
+        x, w, dy = si.conv_case(3, 10, 1, vol, vol, vol, 32, 32, 3, 1, 1, True)
+        g = oc.shape(1, vol, vol, vol, 32, 32, 3, 1, 1)
+        x, w, dy = (a.astype(np.float64) for a in (x, w, dy))
+        t0 = time.perf_counter()
+        oc.fwd(g, x, w); oc.dgrad(g, dy, w); oc.wgrad(g, x, dy)
+        dt = time.perf_counter() - t0
+        return dt, 3 * 2.0 * vol ** 3 * 27 * 32 * 32
+
+    dt, fl = run(16)                      # calibrate
+    rate = fl / dt
+    vol = int(min(96, max(16, (rate * seconds_target / (3 * 2.0 * 27 * 32 * 32)) ** (1 / 3))))
+    vol -= vol % 4
+    dt, fl = run(vol)
+    threads = int(os.environ.get("OMP_NUM_THREADS", cores))
+    return {"value": fl / dt / 1e12, "unit": "TFLOP/s", "cores": min(threads, cores), "kind": "oracle",
+            "sample": f"fp64 direct-loop fwd+dgrad+wgrad of one 32->32 3x3x3 layer on a {vol}^3 sub-volume of the "
+                      f"workload ({dt:.1f} s)", "seconds": dt}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--vol", type=int, default=192)
+    ap.add_argument("--budget-gib", type=float, default=None,
+                    help="device budget of the step; default: 32 MiB under the unswapped peak, which forces a swap")
+    ap.add_argument("--lookahead", type=int, default=2)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import synth_inputs as si
+    from paper_1812_07816_amd import chain, conv3d as mc, swap as sw
+    from paper_1812_07816_amd._lib import lib
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    vol, N = args.vol, 1
+    layers = [chain.Layer(4, 32), chain.Layer(32, 32), chain.Layer(32, 64, s=2)]
+
+    def dev(a):
+        return torch.from_numpy(si.bf16_bits(a).view(np.int16)).cuda().view(torch.bfloat16).reshape(a.shape)
+
+    x0 = dev(si.normal(3, 0, (N, vol, vol, vol, 4), bf16=True))
+    ws = [dev(si.he_normal_weight(3, 1 + i, ly.Cout, ly.k, ly.Cin, bf16=True)) for i, ly in enumerate(layers)]
+    dy = dev(si.normal(3, 9, (N, vol // 2, vol // 2, vol // 2, 64), bf16=True))
+
+    def timed(step, steps, warmup):
+        for _ in range(warmup):
+            step.run()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            step.run()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / steps
+
+    # unswapped reference run (budget ignored) for the exposed-transfer figure
+    plain = chain.ChainStep(N, vol, layers, ws, x0, dy, swap=False)
+    ms_plain = timed(plain, max(3, args.steps // 2), args.warmup)
+    flops = plain.flops_per_step
+
+    # per-kernel timing with HIP events on the launch stream (torch's current stream)
+    stream = torch.cuda.current_stream()
+    per = []
+    acts = plain.acts
+    for i, ly in enumerate(layers):
+        d = plain.descs[i]
+        calls = {"fwd": lambda: mc.conv3d_fwd(d, acts[i], ws[i], plain.acts[i + 1] if i + 1 < len(layers) else plain.y_last, plain.ws),
+                 "dgrad": lambda: mc.conv3d_dgrad(d, plain.grad[i + 1], ws[i], plain.grad[i], plain.ws),
+                 "wgrad": lambda: mc.conv3d_wgrad(d, acts[i], plain.grad[i + 1], plain.dw[i], plain.ws)}
+        for pi, (pname, fn) in enumerate(calls.items()):
+            fn(); fn()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            reps = 10
+            e0.record(stream)
+            for _ in range(reps):
+                fn()
+            e1.record(stream)
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / reps
+            fl = plain.flops_per_layer[i]
+            in_b = acts[i].numel() * 2 if pname != "dgrad" else plain.grad[i + 1].numel() * 2
+            if pname == "fwd":
+                byt = acts[i].numel() * 2 + ws[i].numel() * 2 + plain.grad[i + 1].numel() * 2
+            elif pname == "dgrad":
+                byt = plain.grad[i + 1].numel() * 2 + ws[i].numel() * 2 + acts[i].numel() * 2
+            else:
+                byt = acts[i].numel() * 2 + plain.grad[i + 1].numel() * 2 + ws[i].numel() * 4
+            per.append({"layer": f"{ly.Cin}->{ly.Cout} s{ly.s}", "pass": pname, "kernel": mc.kernel_name(d, pi),
+                        "ms": ms, "tflops": fl / ms / 1e9, "gbs": byt / ms / 1e6, "flop": fl, "bytes": byt})
+    plain_dw = [d.clone() for d in plain.dw]
+    del plain
+    torch.cuda.empty_cache()
+
+    # the measured step: swapping on
+    probe = chain.ChainStep(N, vol, layers, ws, x0, dy, swap=True)
+    peak = probe.engine.stats()["unswapped_peak_bytes"]
+    probe.close(); del probe
+    torch.cuda.empty_cache()
+    budget = int(args.budget_gib * (1 << 30)) if args.budget_gib is not None else peak - (32 << 20)
+    step = chain.ChainStep(N, vol, layers, ws, x0, dy, swap=True, budget_bytes=budget, lookahead=args.lookahead)
+    ms_step = timed(step, args.steps, args.warmup)
+    st = step.engine.stats()
+    identical = all(torch.equal(a, b) for a, b in zip(plain_dw, step.dw))
+    transfer_ms = st["busy_ms"]
+    exposed_ms = max(0.0, ms_step - ms_plain)
+    hidden = 1.0 - exposed_ms / transfer_ms if transfer_ms > 0 else None
+    link = {"d2h_gbs": st["bytes_out"] / st["copy_ms_out"] / 1e6 if st["copy_ms_out"] else None,
+            "h2d_gbs": st["bytes_in"] / st["copy_ms_in"] / 1e6 if st["copy_ms_in"] else None}
+    step.close()
+
+    dom = max(per, key=lambda r: r["ms"])
+    mfma_bound = dom["flop"] / dom["bytes"] > MFMA_BF16_PEAK_TFLOPS * 1e3 / HBM_PEAK_GBS
+    roof = ({"bound": "mfma", "achieved": dom["tflops"], "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+             "frac": dom["tflops"] / MFMA_BF16_PEAK_TFLOPS} if mfma_bound else
+            {"bound": "hbm", "achieved": dom["gbs"], "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": dom["gbs"] / HBM_PEAK_GBS})
+    roof.update({"traffic": None, "kernel": dom["kernel"], "layer": dom["layer"], "pass": dom["pass"], "ms": dom["ms"]})
+
+    value = flops / ms_step / 1e9
+    out = {
+        "metric": "Conv3D fwd+bwd TFLOP/s (bf16, % MFMA peak); 192^3 U-Net level train-step ms",
+        "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"first U-Net level at {vol}^3, N=1: Conv3D 4->32, 32->32, stride-2 32->64; "
+                               "fwd+dgrad+wgrad of each layer; saved activations swapped under a device budget",
+                   "budget_bytes": budget, "unswapped_peak_bytes": peak, "lookahead": args.lookahead},
+        "pct_mfma_peak": 100.0 * value / MFMA_BF16_PEAK_TFLOPS,
+        "ms_per_step_no_swap": ms_plain,
+        "swap": {"bytes_out": st["bytes_out"], "bytes_in": st["bytes_in"], "n_swapped": st["n_planned"],
+                 "transfer_ms": transfer_ms, "exposed_ms": exposed_ms, "hidden_frac": hidden,
+                 "planned_peak_bytes": st["planned_peak_bytes"], "bit_identical_to_unswapped": identical, **link},
+        "kernels": [{k: (round(v, 4) if isinstance(v, float) else v) for k, v in r.items() if k not in ("flop", "bytes")} for r in per],
+        "roofline": roof,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
