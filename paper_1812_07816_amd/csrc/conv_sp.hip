@@ -68,14 +68,14 @@ __device__ __forceinline__ void load_w(WFrag& f, const char* w_lane) {
 // The 12 MFMAs of one kd group at one (kw, k16) position.  The accumulator
 // set of output plane od = j - kd is (PH - kd) mod 3.  The kd = 0 set starts a
 // new output plane: its first contribution (SUB 0, kh 0) accumulates onto zero.
-template <int PH, int SUB, int KD>
+template <int PH, int SUB, int KD, bool ZERO>
 __device__ __forceinline__ void group_mfma(f32x16 (&acc)[3][RH], const XFrag& x, const WFrag& w) {
 #pragma unroll
     for (int kh = 0; kh < 3; ++kh) {
 #pragma unroll
         for (int r = 0; r < RH; ++r) {
             f32x16& a = acc[(PH + 3 - KD) % 3][r];
-            if (KD == 0 && SUB == 0 && kh == 0) {
+            if (ZERO && KD == 0 && SUB == 0 && kh == 0) {
                 f32x16 z = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
                 a = mfma(w.v[kh], x.v[r + kh], z);
             } else {
@@ -92,21 +92,21 @@ __device__ __forceinline__ void convert_rows(const f32x16 (&a)[RH], uint32_t (&o
 // One (kw, k16) position: kd groups 2, 1, 0 (oldest output plane first), with
 // the LDS reads of the next position issued between the groups so that they
 // are in flight for at least one group of MFMAs.
-template <int PH, int SUB, class Hook>
+template <int PH, int SUB, bool ZERO, bool LAST, class Hook>
 __device__ __forceinline__ void sub_step(f32x16 (&acc)[3][RH], XFrag& xc, XFrag& xn, WFrag& w2, WFrag& w1, WFrag& w0,
                                          const char* in_lane, const char* w_lane, uint32_t (&outp)[RH][8], Hook&& hook) {
     constexpr bool last = SUB == 5;
     load_w<SUB, 0>(w0, w_lane);
-    group_mfma<PH, SUB, 2>(acc, xc, w2);
+    group_mfma<PH, SUB, 2, ZERO>(acc, xc, w2);
     hook(3 * SUB + 0);
     SP_FENCE();
     if (!last) load_x<last ? 0 : SUB + 1>(xn, in_lane);
-    if (last) convert_rows(acc[(PH + 1) % 3], outp);
-    group_mfma<PH, SUB, 1>(acc, xc, w1);
+    if (last && LAST) convert_rows(acc[(PH + 1) % 3], outp);
+    group_mfma<PH, SUB, 1, ZERO>(acc, xc, w1);
     hook(3 * SUB + 1);
     SP_FENCE();
     if (!last) load_w<last ? 0 : SUB + 1, 2>(w2, w_lane);
-    group_mfma<PH, SUB, 0>(acc, xc, w0);
+    group_mfma<PH, SUB, 0, ZERO>(acc, xc, w0);
     hook(3 * SUB + 2);
     SP_FENCE();
     if (!last) load_w<last ? 0 : SUB + 1, 1>(w1, w_lane);
@@ -118,7 +118,10 @@ __device__ __forceinline__ void sub_step(f32x16 (&acc)[3][RH], XFrag& xc, XFrag&
 // hook(k), k = 0..17, is called once per group of 12 MFMAs: the caller spreads
 // its global loads and stores over the step with it, so that no wave ever
 // queues a burst of vector-memory instructions.
-template <int PH, class Hook>
+// ZERO: this stage is the first input-channel chunk of its plane (the new
+// output plane starts from zero); LAST: it is the last chunk (the oldest
+// output plane is complete and is converted to bf16).
+template <int PH, bool ZERO, bool LAST, class Hook>
 __device__ __forceinline__ void plane_compute(f32x16 (&acc)[3][RH], const char* in_lane, const char* w_lane,
                                               uint32_t (&outp)[RH][8], Hook&& hook) {
     XFrag xa, xb;
@@ -126,12 +129,12 @@ __device__ __forceinline__ void plane_compute(f32x16 (&acc)[3][RH], const char* 
     load_x<0>(xa, in_lane);
     load_w<0, 2>(w2, w_lane);
     load_w<0, 1>(w1, w_lane);
-    sub_step<PH, 0>(acc, xa, xb, w2, w1, w0, in_lane, w_lane, outp, hook);
-    sub_step<PH, 1>(acc, xb, xa, w2, w1, w0, in_lane, w_lane, outp, hook);
-    sub_step<PH, 2>(acc, xa, xb, w2, w1, w0, in_lane, w_lane, outp, hook);
-    sub_step<PH, 3>(acc, xb, xa, w2, w1, w0, in_lane, w_lane, outp, hook);
-    sub_step<PH, 4>(acc, xa, xb, w2, w1, w0, in_lane, w_lane, outp, hook);
-    sub_step<PH, 5>(acc, xb, xa, w2, w1, w0, in_lane, w_lane, outp, hook);
+    sub_step<PH, 0, ZERO, LAST>(acc, xa, xb, w2, w1, w0, in_lane, w_lane, outp, hook);
+    sub_step<PH, 1, ZERO, LAST>(acc, xb, xa, w2, w1, w0, in_lane, w_lane, outp, hook);
+    sub_step<PH, 2, ZERO, LAST>(acc, xa, xb, w2, w1, w0, in_lane, w_lane, outp, hook);
+    sub_step<PH, 3, ZERO, LAST>(acc, xb, xa, w2, w1, w0, in_lane, w_lane, outp, hook);
+    sub_step<PH, 4, ZERO, LAST>(acc, xa, xb, w2, w1, w0, in_lane, w_lane, outp, hook);
+    sub_step<PH, 5, ZERO, LAST>(acc, xb, xa, w2, w1, w0, in_lane, w_lane, outp, hook);
 }
 
 // fp32 accumulators of one finished output plane -> packed bf16 (RNE)
@@ -164,10 +167,15 @@ __device__ __forceinline__ void store_row(const uint32_t (&o)[8], uint16_t* p, b
     }
 }
 
+// NC = input-channel chunks of 32 (Cin = 32 NC).  All NC weight chunks of the
+// cout tile stay in LDS.  NC = 1 double-buffers the staged plane; NC = 2 has
+// room for one stage only and takes a second barrier per stage instead.
+template <int NC>
 __global__ void __launch_bounds__(256, 1) sp_conv_kernel(SpParams P) {
     extern __shared__ __attribute__((aligned(16))) char lds[];
+    constexpr int NBUF = NC == 1 ? 2 : 1;
     char* w_lds = lds;
-    char* in_lds = lds + W_BYTES;  // two stages
+    char* in_lds = lds + NC * W_BYTES;
 
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     // XCD-aware placement: hardware deals consecutive workgroup ids round-robin
@@ -205,8 +213,8 @@ __global__ void __launch_bounds__(256, 1) sp_conv_kernel(SpParams P) {
         const int h0 = ht * TH, w0 = wt * TW;
 
         if (ct != cur_ct) {  // (re)load the weights of this cout tile; previous readers passed a barrier
-            const uint4* src = (const uint4*)(P.wpack + (long long)ct * (W_BYTES / 2));
-            for (int i = t; i < W_BYTES / 16; i += 256) ((uint4*)w_lds)[i] = src[i];
+            const uint4* src = (const uint4*)(P.wpack + (long long)ct * NC * (W_BYTES / 2));
+            for (int i = t; i < NC * W_BYTES / 16; i += 256) ((uint4*)w_lds)[i] = src[i];
             cur_ct = ct;
         }
         // global offsets (elements) of this patch relative to the plane base
@@ -233,15 +241,15 @@ __global__ void __launch_bounds__(256, 1) sp_conv_kernel(SpParams P) {
         // zeroed afterwards, so that the piece registers never pass through memory.
         unsigned pre_mask = 0;
         const uint16_t* pre_base = xn;
-        auto begin_plane = [&](int ip) {
+        auto begin_stage = [&](int ip, int chunk) {
             const bool inside = ip >= 0 && ip < P.D;
-            pre_base = xn + (long long)(inside ? ip : 0) * plane_elems;
+            pre_base = xn + (long long)(inside ? ip : 0) * plane_elems + chunk * 32;
             pre_mask = inside ? valid : 0u;
         };
         auto load_piece = [&](int i) { pre[i] = *(const uint4*)(pre_base + goff[i]); };
         // the zeroing of masked pieces happens here, after the MFMA work, so
         // that nothing waits for the global loads before the compute starts
-        auto write_plane = [&](int buf) {
+        auto write_stage = [&](int buf) {
             char* dst = in_lds + buf * STAGE_BYTES;
 #pragma unroll
             for (int i = 0; i < NLOAD; ++i) {
@@ -254,7 +262,7 @@ __global__ void __launch_bounds__(256, 1) sp_conv_kernel(SpParams P) {
                 if (t + 256 * i < NPIECE) *(uint4*)(dst + lds_off[i]) = v;
             }
         };
-        // finished rows wait in outp[] and are stored during the next step
+        // finished rows wait in outp[] and are stored during the next stage
         uint32_t outp[RH][8];
         uint16_t* st_ptr = yn;    // address of row 0 of the pending plane for this lane
         bool st_pending = false;
@@ -272,29 +280,41 @@ __global__ void __launch_bounds__(256, 1) sp_conv_kernel(SpParams P) {
 #pragma unroll
                 for (int i = 0; i < 16; ++i) acc[s][r][i] = 0.f;
 
-        begin_plane(od_start - P.pD);
+        begin_stage(od_start - P.pD, 0);
 #pragma unroll
         for (int i = 0; i < NLOAD; ++i) load_piece(i);
-        write_plane(0);
+        write_stage(0);
         __syncthreads();
 
-        // step jj stages input plane ip = od_start + jj - pD; it completes output plane od_start + jj - 2.
-        // Hook slots 0..9 issue the loads of the next plane, slots 10..13 the stores of the plane finished
-        // by the previous step (they must precede slot 15, where outp[] is overwritten).
-#define SP_STEP(PHASE)                                                                          \
+        // Plane step jj stages input plane ip = od_start + jj - pD, one 32-channel chunk at a time, and
+        // completes output plane od_start + jj - 2.  Hook slots 0..9 issue the loads of the next stage,
+        // slots 10..13 the stores of the plane finished last (before slot 15 overwrites outp[]).
+#define SP_STAGE(PHASE, CHUNK, ZERO, LAST)                                                      \
         {                                                                                       \
             const int j_ = od_start + jj;                                                       \
-            const bool more_ = jj + 1 < nJ;                                                     \
-            begin_plane(j_ + 1 - P.pD);                                                         \
-            plane_compute<PHASE>(acc, in_lds + (jj & 1) * STAGE_BYTES + lane_in_off, w_lane, outp, [&](int k) { \
-                if (k < NLOAD) { if (more_) load_piece(k); }                   \
-                else if (k < NLOAD + RH) store_piece(k - NLOAD);         \
+            const bool more_ = (CHUNK) + 1 < NC || jj + 1 < nJ;                                 \
+            if ((CHUNK) + 1 < NC) begin_stage(j_ - P.pD, (CHUNK) + 1);                          \
+            else begin_stage(j_ + 1 - P.pD, 0);                                                 \
+            const int buf_ = NBUF == 2 ? (jj & 1) : 0;                                          \
+            plane_compute<PHASE, ZERO, LAST>(acc, in_lds + buf_ * STAGE_BYTES + lane_in_off,    \
+                                             w_lane + (CHUNK) * W_BYTES, outp, [&](int k) {     \
+                if (k < NLOAD) { if (more_) load_piece(k); }                                    \
+                else if (k < NLOAD + RH) {                                                      \
+                    store_piece(k - NLOAD);                                                     \
+                    if (k == NLOAD + RH - 1) st_pending = false;                                \
+                }                                                                               \
             });                                                                                 \
-            if (more_) write_plane((jj + 1) & 1);                                               \
-            st_pending = jj >= 2;                                                               \
-            st_ptr = yn + (((long long)(j_ - 2) * P.Ho + h0 + wave * RH) * P.Wo + ow_) * P.Cout + ct * 32 + 16 * (lane >> 5); \
+            if (NBUF == 1) __syncthreads(); /* all waves are done reading the only stage */     \
+            if (more_) write_stage(NBUF == 2 ? ((jj + 1) & 1) : 0);                             \
+            if (LAST) {                                                                         \
+                st_pending = jj >= 2;                                                           \
+                st_ptr = yn + (((long long)(j_ - 2) * P.Ho + h0 + wave * RH) * P.Wo + ow_) * P.Cout + ct * 32 + 16 * (lane >> 5); \
+            }                                                                                   \
             __syncthreads();                                                                    \
         }
+#define SP_STEP(PHASE)                                                                          \
+        if (NC == 1) { SP_STAGE(PHASE, 0, true, true) }                                         \
+        else { SP_STAGE(PHASE, 0, true, false) SP_STAGE(PHASE, 1, false, true) }
         for (int jj = 0;;) {
             SP_STEP(0)
             if (++jj >= nJ) break;
@@ -304,6 +324,7 @@ __global__ void __launch_bounds__(256, 1) sp_conv_kernel(SpParams P) {
             if (++jj >= nJ) break;
         }
 #undef SP_STEP
+#undef SP_STAGE
 #pragma unroll
         for (int r = 0; r < RH; ++r) store_piece(r);  // the last plane of the segment
     }
@@ -343,8 +364,8 @@ bool sp_supported(const Geom& g, int pass) {
     if (g.dtype != MI3D_BF16 || g.kD != 3 || g.kH != 3 || g.kW != 3) return false;
     if (g.sD != 1 || g.sH != 1 || g.sW != 1) return false;
     if (g.pD > 2 || g.pH > 2 || g.pW > 2) return false;
-    if (pass == MI3D_PASS_FWD) return g.Cin == 32 && g.Cout % 32 == 0;
-    if (pass == MI3D_PASS_DGRAD) return g.Cout == 32 && g.Cin % 32 == 0;
+    if (pass == MI3D_PASS_FWD) return (g.Cin == 32 || g.Cin == 64) && g.Cout % 32 == 0;
+    if (pass == MI3D_PASS_DGRAD) return (g.Cout == 32 || g.Cout == 64) && g.Cin % 32 == 0;
     return false;
 }
 
@@ -382,14 +403,20 @@ int sp_conv(const Geom& g, int pass, const void* in, const void* w, void* out, v
     long long nwg = cus;
     if (nwg > P.units) nwg = P.units;
     P.nwg = (int)nwg;
-    size_t lds = W_BYTES + 2 * STAGE_BYTES;
+    const int nc = P.Cin / 32;
+    const size_t lds = nc == 1 ? W_BYTES + 2 * STAGE_BYTES : 2 * W_BYTES + STAGE_BYTES;
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void*)sp_conv_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        hipError_t e = hipFuncSetAttribute((const void*)sp_conv_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           (int)(W_BYTES + 2 * STAGE_BYTES));
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute((const void*)sp_conv_kernel<2>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    (int)(2 * W_BYTES + STAGE_BYTES));
         if (e != hipSuccess) { note_hip_error(e); return MI3D_ERR_HIP; }
         attr_set = true;
     }
-    sp_conv_kernel<<<(unsigned)nwg, 256, lds, s>>>(P);
+    if (nc == 1) sp_conv_kernel<1><<<(unsigned)nwg, 256, lds, s>>>(P);
+    else sp_conv_kernel<2><<<(unsigned)nwg, 256, lds, s>>>(P);
     return check_launch();
 }
 
