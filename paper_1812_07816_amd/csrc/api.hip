@@ -43,11 +43,12 @@ int make_geom(const mi3d_conv_desc* d, Geom* g) {
 
 static bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
 
-enum Kernel { K_DIRECT = 0, K_SP = 1, K_WGRAD_MFMA = 2, K_NONE = -1 };
+enum Kernel { K_DIRECT = 0, K_SP = 1, K_WGRAD_MFMA = 2, K_S2_FWD = 3, K_NONE = -1 };
 
 static Kernel choose(const Geom& g, int pass) {
     if (pass == MI3D_PASS_WGRAD && wgrad_mfma_supported(g)) return K_WGRAD_MFMA;
     if (sp_supported(g, pass)) return K_SP;
+    if (pass == MI3D_PASS_FWD && s2_fwd_supported(g)) return K_S2_FWD;
     return K_DIRECT;
 }
 
@@ -56,6 +57,7 @@ static const char* kernel_name(Kernel k) {
         case K_DIRECT: return "direct";
         case K_SP: return "mfma_plane_stream";
         case K_WGRAD_MFMA: return "mfma_wgrad_plane_stream";
+        case K_S2_FWD: return "mfma_stride2_plane_stream";
         default: return "none";
     }
 }
@@ -113,6 +115,10 @@ size_t mi3d_conv3d_workspace_bytes(const mi3d_conv_desc* desc, int pass) {
     size_t need = direct_workspace_bytes(g, pass);
     size_t sp = sp_workspace_bytes(g, pass);
     if (sp > need) need = sp;
+    if (pass == MI3D_PASS_FWD) {
+        size_t b = s2_fwd_workspace_bytes(g);
+        if (b > need) need = b;
+    }
     if (pass == MI3D_PASS_WGRAD) {
         size_t wg = wgrad_mfma_workspace_bytes(g);
         if (wg > need) need = wg;
@@ -131,6 +137,7 @@ int mi3d_conv3d_fwd(const mi3d_conv_desc* desc, const void* x, const void* w, vo
     switch (k) {
         case K_DIRECT: return direct_fwd(g, x, w, y, (hipStream_t)stream);
         case K_SP: return sp_conv(g, MI3D_PASS_FWD, x, w, y, ws, ws_bytes, (hipStream_t)stream);
+        case K_S2_FWD: return s2_fwd(g, x, w, y, ws, ws_bytes, (hipStream_t)stream);
         default: return MI3D_ERR_UNSUPPORTED;
     }
 }

@@ -1,0 +1,311 @@
+// Forward pass of the 3x3x3 / stride 2 downsampling convolution with 32 input
+// channels on bf16 MFMA (v_mfma_f32_32x32x16_bf16), fp32 accumulation: the
+// layer that leaves a U-Net level (feature maps of Section 3.1).
+//
+// The layer moves 64 bytes of input per 27/8 taps, so it is bound by memory
+// traffic, not by the matrix cores; the kernel's job is to read every input
+// plane once.  Plane streaming as in the stride-1 kernel: a workgroup owns a
+// 4-row x 32-col patch of the output plane for up to two 32-wide cout blocks
+// and walks along D.  Input plane ip = 2 od - pD + kd feeds output plane od
+// through tap kd: planes with even ip + pD feed two output planes (kd 0 and
+// 2), odd ones feed one (kd 1); two output planes are in flight in registers.
+// The staged plane patch (9 x 65 voxels) is split by column parity in LDS, so
+// that the 32 voxels of a fragment (input columns 2 j + kw) are contiguous.
+#include "mi3d_internal.h"
+
+namespace mi3d {
+namespace {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+typedef __attribute__((__vector_size__(2 * sizeof(float)))) float f32x2;
+typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
+
+constexpr int TH = 4, TW = 32, RH = 2;
+constexpr int PR = 2 * TH + 1, PC = 2 * TW + 1;   // staged patch: 9 rows x 65 columns
+constexpr int HALF = 33, PITCH = 2 * HALF;        // row pitch in voxels: even columns, then odd columns
+constexpr int SLAB = PR * PITCH;                  // voxels per 8-channel slab
+constexpr int STAGE_BYTES = 4 * SLAB * 16;
+constexpr int WB_BYTES = 27 * 2 * 1024;           // packed weights of one 32-wide cout block
+constexpr int NPIECE = PR * PC * 4;
+constexpr int NLOAD = (NPIECE + 255) / 256;       // 10
+
+struct S2Params {
+    const uint16_t* x;
+    const uint16_t* wpack;  // [cout block][kw][kd][kh][k16][lane][8]
+    uint16_t* y;
+    int N, D, H, W, Cout, Do, Ho, Wo, pD, pH, pW;
+    int HT, WT, CT, CB;     // tiles per plane, cout tiles, cout blocks per tile (1 or 2)
+    long long units;
+    int nwg;
+};
+
+__device__ __forceinline__ f32x16 mfma(bf16x8 a, bf16x8 b, f32x16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+// All MFMAs of one staged plane for this wave's two output rows.  The
+// accumulator set of output plane m (counted from the segment start) is m % 2.
+//   even step (ip + pD even): kd 2 finishes plane m - 1 (set 1 - S), kd 0 starts plane m (set S)
+//   odd step: kd 1 continues plane m (set S)
+template <int S, bool EVEN>
+__device__ __forceinline__ void plane_compute(f32x16 (&acc)[2][RH], const char* in_lane, const char* w_lane) {
+#pragma unroll
+    for (int kw = 0; kw < 3; ++kw) {
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk) {
+            bf16x8 xr[2 * RH + 1];
+#pragma unroll
+            for (int r = 0; r < 2 * RH + 1; ++r)
+                xr[r] = *(const bf16x8*)(in_lane + (2 * kk * SLAB + r * PITCH + (kw & 1) * HALF + (kw >> 1)) * 16);
+#pragma unroll
+            for (int kdi = 0; kdi < 3; ++kdi) {
+                constexpr int dummy = 0; (void)dummy;
+                const int kd = 2 - kdi;
+                if (EVEN ? (kd == 1) : (kd != 1)) continue;
+                const int set = (kd == 2) ? 1 - S : S;
+#pragma unroll
+                for (int kh = 0; kh < 3; ++kh) {
+                    bf16x8 wf = *(const bf16x8*)(w_lane + (((kw * 3 + kd) * 3 + kh) * 2 + kk) * 1024);
+#pragma unroll
+                    for (int r = 0; r < RH; ++r) {
+                        if (kd == 0 && kw == 0 && kk == 0 && kh == 0) {
+                            f32x16 z = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+                            acc[set][r] = mfma(wf, xr[2 * r + kh], z);
+                        } else {
+                            acc[set][r] = mfma(wf, xr[2 * r + kh], acc[set][r]);
+                        }
+                    }
+                }
+            }
+        }
+    }
+}
+
+__device__ __forceinline__ void store_rows(const f32x16 (&a)[RH], uint16_t* p, long long row_pitch, bool col_ok, int rows_ok) {
+    typedef __attribute__((ext_vector_type(2))) unsigned u32x2;
+#pragma unroll
+    for (int r = 0; r < RH; ++r) {
+        uint32_t o[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            f32x2 v = {a[r][2 * i], a[r][2 * i + 1]};
+            bf16x2 b = __builtin_convertvector(v, bf16x2);
+            o[i] = __builtin_bit_cast(uint32_t, b);
+        }
+        uint4 c[2];
+#pragma unroll
+        for (int k = 0; k < 2; ++k) {
+            u32x2 s0 = __builtin_amdgcn_permlane32_swap(o[2 * k], o[2 * k + 4], false, false);
+            u32x2 s1 = __builtin_amdgcn_permlane32_swap(o[2 * k + 1], o[2 * k + 5], false, false);
+            c[k].x = s0[0]; c[k].y = s1[0]; c[k].z = s0[1]; c[k].w = s1[1];
+        }
+        if (col_ok && r < rows_ok) {
+            *(uint4*)(p + r * row_pitch) = c[0];
+            *(uint4*)(p + r * row_pitch + 8) = c[1];
+        }
+    }
+}
+
+__global__ void __launch_bounds__(256, 1) s2_fwd_kernel(S2Params P) {
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+    char* w_lds = lds;
+    char* in_lds = lds + P.CB * WB_BYTES;
+
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    // CB = 2: waves 0,1 serve cout block 0 and waves 2,3 block 1, two rows each.
+    // CB = 1: all four waves serve the one block; the patch then has 8 output rows.
+    const int cb = P.CB == 2 ? (wave >> 1) : 0;
+    const int rowgrp = P.CB == 2 ? (wave & 1) : wave;
+    const int th = P.CB == 2 ? TH : 2 * TH;          // output rows per workgroup
+
+    int g = blockIdx.x;
+    if ((P.nwg & 7) == 0) g = (g & 7) * (P.nwg >> 3) + (g >> 3);
+    long long u0 = P.units * g / P.nwg, u1 = P.units * (g + 1) / P.nwg;
+
+    f32x16 acc[2][RH];
+
+    int cur_ct = -1;
+    while (u0 < u1) {
+        long long column = u0 / P.Do;
+        const int od_start = (int)(u0 - column * P.Do);
+        const long long left = u1 - u0;
+        const int od_end = od_start + (int)(left < (long long)(P.Do - od_start) ? left : (long long)(P.Do - od_start));
+        u0 += od_end - od_start;
+        const int wt = (int)(column % P.WT); column /= P.WT;
+        const int ht = (int)(column % P.HT); column /= P.HT;
+        const int ct = (int)(column % P.CT);
+        const int n = (int)(column / P.CT);
+        const int h0 = ht * th, w0 = wt * TW;
+
+        if (ct != cur_ct) {
+            const uint4* src = (const uint4*)(P.wpack + (long long)ct * P.CB * (WB_BYTES / 2));
+            for (int i = t; i < P.CB * WB_BYTES / 16; i += 256) ((uint4*)w_lds)[i] = src[i];
+            cur_ct = ct;
+        }
+        // Load plan.  The patch is staged as NG row groups of 9 rows (rows 4 g .. 4 g + 8 of the
+        // patch, i.e. the rows the 4 output rows 4 g .. 4 g + 3 need); with two groups the shared
+        // row is stored twice.  Piece q of a group: channels 8c..8c+7 of voxel q / 4 (row-major 9 x 65).
+        const int ng = P.CB == 2 ? 1 : 2;
+        int goff[2][NLOAD];
+        unsigned valid[2] = {0, 0};
+        int lds_off[NLOAD];
+#pragma unroll
+        for (int i = 0; i < NLOAD; ++i) {
+            const int q = t + 256 * i;
+            const int v = q >> 2, c = q & 3;
+            const int row = (v * 1009) >> 16, col = v - row * PC;  // v / 65
+            lds_off[i] = (c * SLAB + row * PITCH + (col & 1) * HALF + (col >> 1)) * 16;
+#pragma unroll
+            for (int gi = 0; gi < 2; ++gi) {
+                const int gh = 2 * (h0 + gi * TH) - P.pH + row, gw = 2 * w0 - P.pW + col;
+                const bool ok = gi < ng && q < NPIECE && gh >= 0 && gh < P.H && gw >= 0 && gw < P.W;
+                goff[gi][i] = ok ? (gh * P.W + gw) * 32 + c * 8 : 0;
+                valid[gi] |= (ok ? 1u : 0u) << i;
+            }
+        }
+        const long long plane_elems = (long long)P.H * P.W * 32;
+        const uint16_t* xn = P.x + (long long)n * P.D * plane_elems;
+        uint16_t* yn = P.y + (long long)n * P.Do * P.Ho * P.Wo * P.Cout;
+        const int nP = od_end - od_start;
+        const int nT = 2 * nP + 1;     // staged planes tp' = 0 .. 2 nP, input plane ip = 2 od_start - pD + tp'
+
+        uint4 pre[2][NLOAD];
+        bool pre_in = false;
+        auto load_plane = [&](int ip) {
+            pre_in = ip >= 0 && ip < P.D;
+            const uint16_t* base = xn + (long long)(pre_in ? ip : 0) * plane_elems;
+#pragma unroll
+            for (int gi = 0; gi < 2; ++gi)
+                if (gi < ng) {
+#pragma unroll
+                    for (int i = 0; i < NLOAD; ++i) pre[gi][i] = *(const uint4*)(base + goff[gi][i]);
+                }
+        };
+        auto write_plane = [&]() {
+#pragma unroll
+            for (int gi = 0; gi < 2; ++gi)
+                if (gi < ng) {
+#pragma unroll
+                    for (int i = 0; i < NLOAD; ++i) {
+                        const bool ok = pre_in && ((valid[gi] >> i) & 1);
+                        uint4 v;
+                        v.x = ok ? pre[gi][i].x : 0u; v.y = ok ? pre[gi][i].y : 0u;
+                        v.z = ok ? pre[gi][i].z : 0u; v.w = ok ? pre[gi][i].w : 0u;
+                        if (t + 256 * i < NPIECE) *(uint4*)(in_lds + gi * STAGE_BYTES + lds_off[i]) = v;
+                    }
+                }
+        };
+
+#pragma unroll
+        for (int s = 0; s < 2; ++s)
+#pragma unroll
+            for (int r = 0; r < RH; ++r)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) acc[s][r][i] = 0.f;
+
+        __syncthreads();   // previous segment's readers are done with the stage
+        load_plane(2 * od_start - P.pD);
+        write_plane();
+        __syncthreads();
+
+        // this wave: row group (2 rows) within a 9-row staging group, cout block cb
+        const int sg = rowgrp >> 1;            // staging group (0 unless CB == 1 and waves 2,3)
+        const int r0 = (rowgrp & 1) * RH;      // first output row within the group
+        const char* in_lane = in_lds + sg * STAGE_BYTES + ((lane >> 5) * SLAB + 2 * r0 * PITCH + (lane & 31)) * 16;
+        const char* w_lane = w_lds + cb * WB_BYTES + lane * 16;
+        const int oh0 = h0 + sg * TH + r0;
+        const int ow = w0 + (lane & 31);
+        const long long row_pitch = (long long)P.Wo * P.Cout;
+        const int co0 = (ct * P.CB + cb) * 32 + 16 * (lane >> 5);
+
+        // step tq stages plane tp' = tq.  tq even = 2 m': finishes output plane m' - 1, starts m'.
+#define S2_STEP(SET, EVEN)                                                                       \
+        {                                                                                        \
+            const bool more_ = tq + 1 < nT;                                                      \
+            if (more_) load_plane(2 * od_start - P.pD + tq + 1);                                 \
+            plane_compute<SET, EVEN>(acc, in_lane, w_lane);                                      \
+            if ((EVEN) && tq >= 2) {                                                             \
+                const int od_ = od_start + (tq >> 1) - 1;                                        \
+                store_rows(acc[1 - (SET)], yn + ((long long)od_ * P.Ho + oh0) * row_pitch + (long long)ow * P.Cout + co0, \
+                           row_pitch, ow < P.Wo, P.Ho - oh0);                                    \
+            }                                                                                    \
+            __syncthreads();                                                                     \
+            if (more_) write_plane();                                                            \
+            __syncthreads();                                                                     \
+        }
+        for (int tq = 0;;) {
+            S2_STEP(0, true)
+            if (++tq >= nT) break;
+            S2_STEP(0, false)
+            if (++tq >= nT) break;
+            S2_STEP(1, true)
+            if (++tq >= nT) break;
+            S2_STEP(1, false)
+            if (++tq >= nT) break;
+        }
+#undef S2_STEP
+    }
+}
+
+// [Cout][3][3][3][32] -> [cout block][kw][kd][kh][k16][lane][8] MFMA A fragments
+__global__ void __launch_bounds__(256) s2_pack_weights_kernel(const uint16_t* __restrict__ w, uint16_t* __restrict__ wpack, int Cout) {
+    long long total = 27ll * 32 * Cout;
+    long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= total) return;
+    int j = (int)(idx & 7);
+    long long r = idx >> 3;
+    int lane = (int)(r & 63); r >>= 6;
+    int kk = (int)(r & 1); r >>= 1;
+    int kh = (int)(r % 3); r /= 3;
+    int kd = (int)(r % 3); r /= 3;
+    int kw = (int)(r % 3); r /= 3;
+    int blk = (int)r;
+    int co = blk * 32 + (lane & 31);
+    int ci = kk * 16 + 8 * (lane >> 5) + j;
+    wpack[idx] = w[((((long long)co * 3 + kd) * 3 + kh) * 3 + kw) * 32 + ci];
+}
+
+}  // namespace
+
+bool s2_fwd_supported(const Geom& g) {
+    if (g.dtype != MI3D_BF16 || g.kD != 3 || g.kH != 3 || g.kW != 3) return false;
+    if (g.sD != 2 || g.sH != 2 || g.sW != 2) return false;
+    if (g.pD > 1 || g.pH > 1 || g.pW > 1) return false;
+    return g.Cin == 32 && g.Cout % 32 == 0;
+}
+
+size_t s2_fwd_workspace_bytes(const Geom& g) { return s2_fwd_supported(g) ? (size_t)g.w_elems() * 2 : 0; }
+
+int s2_fwd(const Geom& g, const void* x, const void* w, void* y, void* ws, size_t ws_bytes, hipStream_t s) {
+    if (ws_bytes < s2_fwd_workspace_bytes(g)) return MI3D_ERR_WORKSPACE;
+    long long total = g.w_elems();
+    s2_pack_weights_kernel<<<(unsigned)((total + 255) / 256), 256, 0, s>>>((const uint16_t*)w, (uint16_t*)ws, g.Cout);
+    int st = check_launch();
+    if (st) return st;
+    S2Params P;
+    P.x = (const uint16_t*)x; P.wpack = (const uint16_t*)ws; P.y = (uint16_t*)y;
+    P.N = g.N; P.D = g.D; P.H = g.H; P.W = g.W; P.Cout = g.Cout;
+    P.Do = g.Do; P.Ho = g.Ho; P.Wo = g.Wo; P.pD = g.pD; P.pH = g.pH; P.pW = g.pW;
+    P.CB = (g.Cout % 64 == 0) ? 2 : 1;
+    P.CT = g.Cout / (32 * P.CB);
+    const int th = P.CB == 2 ? TH : 2 * TH;
+    P.HT = (g.Ho + th - 1) / th;
+    P.WT = (g.Wo + TW - 1) / TW;
+    P.units = (long long)g.N * P.CT * P.HT * P.WT * g.Do;
+    int dev = 0, cus = 256;
+    if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+    long long nwg = cus < P.units ? cus : P.units;
+    P.nwg = (int)nwg;
+    const size_t lds = (size_t)P.CB * WB_BYTES + (P.CB == 2 ? 1 : 2) * STAGE_BYTES;
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void*)s2_fwd_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 2 * WB_BYTES + STAGE_BYTES);
+        if (e != hipSuccess) { note_hip_error(e); return MI3D_ERR_HIP; }
+        attr_set = true;
+    }
+    s2_fwd_kernel<<<(unsigned)nwg, 256, lds, s>>>(P);
+    return check_launch();
+}
+
+}  // namespace mi3d

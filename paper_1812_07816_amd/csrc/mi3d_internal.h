@@ -56,4 +56,10 @@ bool wgrad_mfma_supported(const Geom& g);
 size_t wgrad_mfma_workspace_bytes(const Geom& g);
 int wgrad_mfma(const Geom& g, const void* x, const void* dy, float* dw, void* ws, size_t ws_bytes, hipStream_t s);
 
+
+// MFMA forward pass of the 3x3x3 stride-2 convolution with 32 input channels
+bool s2_fwd_supported(const Geom& g);
+size_t s2_fwd_workspace_bytes(const Geom& g);
+int s2_fwd(const Geom& g, const void* x, const void* w, void* y, void* ws, size_t ws_bytes, hipStream_t s);
+
 }  // namespace mi3d
