@@ -43,12 +43,14 @@ int make_geom(const mi3d_conv_desc* d, Geom* g) {
 
 static bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
 
-enum Kernel { K_DIRECT = 0, K_SP = 1, K_WGRAD_MFMA = 2, K_S2_FWD = 3, K_NONE = -1 };
+enum Kernel { K_DIRECT = 0, K_SP = 1, K_WGRAD_MFMA = 2, K_S2_FWD = 3, K_EMBED_C = 4, K_EMBED_S = 5, K_NONE = -1 };
 
 static Kernel choose(const Geom& g, int pass) {
     if (pass == MI3D_PASS_WGRAD && wgrad_mfma_supported(g)) return K_WGRAD_MFMA;
     if (sp_supported(g, pass)) return K_SP;
     if (pass == MI3D_PASS_FWD && s2_fwd_supported(g)) return K_S2_FWD;
+    if (embed_c_supported(g, pass)) return K_EMBED_C;
+    if (embed_s_supported(g, pass)) return K_EMBED_S;
     return K_DIRECT;
 }
 
@@ -58,6 +60,8 @@ static const char* kernel_name(Kernel k) {
         case K_SP: return "mfma_plane_stream";
         case K_WGRAD_MFMA: return "mfma_wgrad_plane_stream";
         case K_S2_FWD: return "mfma_stride2_plane_stream";
+        case K_EMBED_C: return "mfma_via_channel_padding";
+        case K_EMBED_S: return "mfma_via_unit_stride";
         default: return "none";
     }
 }
@@ -119,6 +123,12 @@ size_t mi3d_conv3d_workspace_bytes(const mi3d_conv_desc* desc, int pass) {
         size_t b = s2_fwd_workspace_bytes(g);
         if (b > need) need = b;
     }
+    {
+        size_t b = embed_c_workspace_bytes(g, pass);
+        if (b > need) need = b;
+        b = embed_s_workspace_bytes(g, pass);
+        if (b > need) need = b;
+    }
     if (pass == MI3D_PASS_WGRAD) {
         size_t wg = wgrad_mfma_workspace_bytes(g);
         if (wg > need) need = wg;
@@ -138,6 +148,7 @@ int mi3d_conv3d_fwd(const mi3d_conv_desc* desc, const void* x, const void* w, vo
         case K_DIRECT: return direct_fwd(g, x, w, y, (hipStream_t)stream);
         case K_SP: return sp_conv(g, MI3D_PASS_FWD, x, w, y, ws, ws_bytes, (hipStream_t)stream);
         case K_S2_FWD: return s2_fwd(g, x, w, y, ws, ws_bytes, (hipStream_t)stream);
+        case K_EMBED_C: return embed_c_conv(g, MI3D_PASS_FWD, x, w, y, ws, ws_bytes, (hipStream_t)stream);
         default: return MI3D_ERR_UNSUPPORTED;
     }
 }
@@ -153,6 +164,8 @@ int mi3d_conv3d_dgrad(const mi3d_conv_desc* desc, const void* dy, const void* w,
     switch (k) {
         case K_DIRECT: return direct_dgrad(g, dy, w, dx, (hipStream_t)stream);
         case K_SP: return sp_conv(g, MI3D_PASS_DGRAD, dy, w, dx, ws, ws_bytes, (hipStream_t)stream);
+        case K_EMBED_C: return embed_c_conv(g, MI3D_PASS_DGRAD, dy, w, dx, ws, ws_bytes, (hipStream_t)stream);
+        case K_EMBED_S: return embed_s_conv(g, MI3D_PASS_DGRAD, dy, w, dx, ws, ws_bytes, (hipStream_t)stream);
         default: return MI3D_ERR_UNSUPPORTED;
     }
 }
@@ -168,6 +181,8 @@ int mi3d_conv3d_wgrad(const mi3d_conv_desc* desc, const void* x, const void* dy,
     switch (k) {
         case K_DIRECT: return direct_wgrad(g, x, dy, dw, ws, ws_bytes, (hipStream_t)stream);
         case K_WGRAD_MFMA: return wgrad_mfma(g, x, dy, dw, ws, ws_bytes, (hipStream_t)stream);
+        case K_EMBED_C: return embed_c_conv(g, MI3D_PASS_WGRAD, x, dy, dw, ws, ws_bytes, (hipStream_t)stream);
+        case K_EMBED_S: return embed_s_conv(g, MI3D_PASS_WGRAD, x, dy, dw, ws, ws_bytes, (hipStream_t)stream);
         default: return MI3D_ERR_UNSUPPORTED;
     }
 }

@@ -62,4 +62,13 @@ bool s2_fwd_supported(const Geom& g);
 size_t s2_fwd_workspace_bytes(const Geom& g);
 int s2_fwd(const Geom& g, const void* x, const void* w, void* y, void* ws, size_t ws_bytes, hipStream_t s);
 
+
+// fallbacks through the stride-1 MFMA kernels: zero-padded input channels, zero-spread dy
+bool embed_c_supported(const Geom& g, int pass);
+size_t embed_c_workspace_bytes(const Geom& g, int pass);
+int embed_c_conv(const Geom& g, int pass, const void* a, const void* b, void* out, void* ws, size_t ws_bytes, hipStream_t s);
+bool embed_s_supported(const Geom& g, int pass);
+size_t embed_s_workspace_bytes(const Geom& g, int pass);
+int embed_s_conv(const Geom& g, int pass, const void* a, const void* b, void* out, void* ws, size_t ws_bytes, hipStream_t s);
+
 }  // namespace mi3d
