@@ -71,4 +71,10 @@ bool embed_s_supported(const Geom& g, int pass);
 size_t embed_s_workspace_bytes(const Geom& g, int pass);
 int embed_s_conv(const Geom& g, int pass, const void* a, const void* b, void* out, void* ws, size_t ws_bytes, hipStream_t s);
 
+
+// MFMA weight gradient of the 3x3x3 stride-2 convolution, channels in multiples of 32
+bool wgrad_s2_supported(const Geom& g);
+size_t wgrad_s2_workspace_bytes(const Geom& g);
+int wgrad_s2(const Geom& g, const void* x, const void* dy, float* dw, void* ws, size_t ws_bytes, hipStream_t s);
+
 }  // namespace mi3d
