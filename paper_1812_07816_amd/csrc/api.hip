@@ -43,13 +43,15 @@ int make_geom(const mi3d_conv_desc* d, Geom* g) {
 
 static bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
 
-enum Kernel { K_DIRECT = 0, K_SP = 1, K_WGRAD_MFMA = 2, K_S2_FWD = 3, K_EMBED_C = 4, K_EMBED_S = 5, K_WGRAD_S2 = 6, K_NONE = -1 };
+enum Kernel { K_DIRECT = 0, K_SP = 1, K_WGRAD_MFMA = 2, K_S2_FWD = 3, K_EMBED_C = 4, K_EMBED_S = 5, K_WGRAD_S2 = 6, K_C4_FWD = 7, K_C4_WGRAD = 8, K_NONE = -1 };
 
 static Kernel choose(const Geom& g, int pass) {
     if (pass == MI3D_PASS_WGRAD && wgrad_mfma_supported(g)) return K_WGRAD_MFMA;
     if (pass == MI3D_PASS_WGRAD && wgrad_s2_supported(g)) return K_WGRAD_S2;
     if (sp_supported(g, pass)) return K_SP;
     if (pass == MI3D_PASS_FWD && s2_fwd_supported(g)) return K_S2_FWD;
+    if (pass == MI3D_PASS_FWD && c4_fwd_supported(g)) return K_C4_FWD;
+    if (pass == MI3D_PASS_WGRAD && c4_wgrad_supported(g)) return K_C4_WGRAD;
     if (embed_c_supported(g, pass)) return K_EMBED_C;
     if (embed_s_supported(g, pass)) return K_EMBED_S;
     return K_DIRECT;
@@ -62,6 +64,8 @@ static const char* kernel_name(Kernel k) {
         case K_WGRAD_MFMA: return "mfma_wgrad_plane_stream";
         case K_S2_FWD: return "mfma_stride2_plane_stream";
         case K_WGRAD_S2: return "mfma_wgrad_stride2";
+        case K_C4_FWD: return "mfma_cin4_folded_taps";
+        case K_C4_WGRAD: return "mfma_wgrad_cin4_folded_taps";
         case K_EMBED_C: return "mfma_via_channel_padding";
         case K_EMBED_S: return "mfma_via_unit_stride";
         default: return "none";
@@ -124,6 +128,8 @@ size_t mi3d_conv3d_workspace_bytes(const mi3d_conv_desc* desc, int pass) {
     if (pass == MI3D_PASS_FWD) {
         size_t b = s2_fwd_workspace_bytes(g);
         if (b > need) need = b;
+        b = c4_fwd_workspace_bytes(g);
+        if (b > need) need = b;
     }
     {
         size_t b = embed_c_workspace_bytes(g, pass);
@@ -135,6 +141,8 @@ size_t mi3d_conv3d_workspace_bytes(const mi3d_conv_desc* desc, int pass) {
         size_t wg = wgrad_mfma_workspace_bytes(g);
         if (wg > need) need = wg;
         wg = wgrad_s2_workspace_bytes(g);
+        if (wg > need) need = wg;
+        wg = c4_wgrad_workspace_bytes(g);
         if (wg > need) need = wg;
     }
     return need;
@@ -152,6 +160,7 @@ int mi3d_conv3d_fwd(const mi3d_conv_desc* desc, const void* x, const void* w, vo
         case K_DIRECT: return direct_fwd(g, x, w, y, (hipStream_t)stream);
         case K_SP: return sp_conv(g, MI3D_PASS_FWD, x, w, y, ws, ws_bytes, (hipStream_t)stream);
         case K_S2_FWD: return s2_fwd(g, x, w, y, ws, ws_bytes, (hipStream_t)stream);
+        case K_C4_FWD: return c4_fwd(g, x, w, y, ws, ws_bytes, (hipStream_t)stream);
         case K_EMBED_C: return embed_c_conv(g, MI3D_PASS_FWD, x, w, y, ws, ws_bytes, (hipStream_t)stream);
         default: return MI3D_ERR_UNSUPPORTED;
     }
@@ -186,6 +195,7 @@ int mi3d_conv3d_wgrad(const mi3d_conv_desc* desc, const void* x, const void* dy,
         case K_DIRECT: return direct_wgrad(g, x, dy, dw, ws, ws_bytes, (hipStream_t)stream);
         case K_WGRAD_MFMA: return wgrad_mfma(g, x, dy, dw, ws, ws_bytes, (hipStream_t)stream);
         case K_WGRAD_S2: return wgrad_s2(g, x, dy, dw, ws, ws_bytes, (hipStream_t)stream);
+        case K_C4_WGRAD: return c4_wgrad(g, x, dy, dw, ws, ws_bytes, (hipStream_t)stream);
         case K_EMBED_C: return embed_c_conv(g, MI3D_PASS_WGRAD, x, dy, dw, ws, ws_bytes, (hipStream_t)stream);
         case K_EMBED_S: return embed_s_conv(g, MI3D_PASS_WGRAD, x, dy, dw, ws, ws_bytes, (hipStream_t)stream);
         default: return MI3D_ERR_UNSUPPORTED;

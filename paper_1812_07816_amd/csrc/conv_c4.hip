@@ -1,0 +1,383 @@
+// Forward pass of the network's first layer: 3x3x3 / stride 1 convolution
+// with 4 input channels (the four MRI modalities) on bf16 MFMA.
+//
+// With Cin = 4 the layer is bound by writing its output (flop/byte 96 against
+// a ridge of 312), so the kernel is built around few, wide stores, not around
+// MFMA utilisation.  The (kw, ci) pairs of a tap row are folded into the MFMA
+// k dimension: k = 4 kw + ci, 12 used of 16, so one v_mfma_f32_32x32x16_bf16
+// per (kd, kh) covers 32 voxels x 32 couts.  In NDHWC with 4 channels the 8
+// k-values of a lane half are two neighbouring voxels, i.e. 16 contiguous
+// bytes of the staged row: fragments need no im2col.  A workgroup computes a
+// 16 x 32 patch of one output plane from a 3-plane input patch (15 KB of LDS),
+// two workgroups per CU.
+#include "mi3d_internal.h"
+
+namespace mi3d {
+namespace {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+typedef __attribute__((__vector_size__(2 * sizeof(float)))) float f32x2;
+typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
+
+constexpr int TH = 16, TW = 32, RH = 4;
+constexpr int PR = TH + 2, PCOLS = TW + 3, PITCH = 36;  // patch rows, columns read, row pitch (voxels of 8 bytes)
+constexpr int PLANE = PR * PITCH;                        // voxels per staged plane
+constexpr int NVOX = 3 * PR * PCOLS;                     // voxels to load (1890)
+constexpr int NLOAD = (NVOX + 255) / 256;                // 8
+
+struct C4Params {
+    const uint16_t* x;
+    const uint16_t* wpack;  // [cout block][kd][kh][lane][8]
+    uint16_t* y;
+    int N, D, H, W, Cout, Do, Ho, Wo, pD, pH, pW, HT, WT;
+};
+
+__global__ void __launch_bounds__(256, 2) c4_fwd_kernel(C4Params P) {
+    __shared__ __attribute__((aligned(16))) char lds[3 * PLANE * 8];
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    int b = blockIdx.x;
+    const int wt = b % P.WT; b /= P.WT;
+    const int ht = b % P.HT; b /= P.HT;
+    const int od = b % P.Do;
+    const int n = b / P.Do;
+    const int h0 = ht * TH, w0 = wt * TW;
+
+    // stage the 3 x 18 x 35 voxel patch (8 bytes per voxel), zero outside the volume
+#pragma unroll
+    for (int i = 0; i < NLOAD; ++i) {
+        const int q = t + 256 * i;
+        if (q < NVOX) {
+            const int pl = q / (PR * PCOLS), rem = q - pl * (PR * PCOLS);
+            const int row = rem / PCOLS, col = rem - row * PCOLS;
+            const int gd = od - P.pD + pl, gh = h0 - P.pH + row, gw = w0 - P.pW + col;
+            uint2 v = {0u, 0u};
+            if (gd >= 0 && gd < P.D && gh >= 0 && gh < P.H && gw >= 0 && gw < P.W)
+                v = *(const uint2*)(P.x + ((((long long)n * P.D + gd) * P.H + gh) * P.W + gw) * 4);
+            *(uint2*)(lds + (pl * PLANE + row * PITCH + col) * 8) = v;
+        }
+    }
+    __syncthreads();
+
+    // input fragments: lane (voxel n, half h) holds voxels n + 2h and n + 2h + 1 of the row = taps kw 2h, 2h + 1
+    bf16x8 xf[3][RH + 2];
+    const char* xl = lds + (wave * RH * PITCH + (lane & 31) + 2 * (lane >> 5)) * 8;
+#pragma unroll
+    for (int kd = 0; kd < 3; ++kd)
+#pragma unroll
+        for (int r = 0; r < RH + 2; ++r) {
+            const uint2 lo = *(const uint2*)(xl + (kd * PLANE + r * PITCH) * 8);
+            const uint2 hi = *(const uint2*)(xl + (kd * PLANE + r * PITCH + 1) * 8);
+            const uint4 v = {lo.x, lo.y, hi.x, hi.y};
+            xf[kd][r] = __builtin_bit_cast(bf16x8, v);
+        }
+
+    const int ow = w0 + (lane & 31);
+    const int oh0 = h0 + wave * RH;
+    const long long row_pitch = (long long)P.Wo * P.Cout;
+    uint16_t* yrow = P.y + ((((long long)n * P.Do + od) * P.Ho + oh0) * P.Wo + ow) * P.Cout + 16 * (lane >> 5);
+
+    for (int cb = 0; cb < P.Cout / 32; ++cb) {
+        const bf16x8* wp = (const bf16x8*)(P.wpack + (long long)cb * 9 * 512) + lane;
+        bf16x8 wf[9];
+#pragma unroll
+        for (int q = 0; q < 9; ++q) wf[q] = wp[q * 64];
+        f32x16 acc[RH];
+#pragma unroll
+        for (int kd = 0; kd < 3; ++kd)
+#pragma unroll
+            for (int kh = 0; kh < 3; ++kh)
+#pragma unroll
+                for (int r = 0; r < RH; ++r) {
+                    if (kd == 0 && kh == 0) {
+                        f32x16 z = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+                        acc[r] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[0], xf[0][r], z, 0, 0, 0);
+                    } else {
+                        acc[r] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[kd * 3 + kh], xf[kd][r + kh], acc[r], 0, 0, 0);
+                    }
+                }
+        typedef __attribute__((ext_vector_type(2))) unsigned u32x2;
+#pragma unroll
+        for (int r = 0; r < RH; ++r) {
+            uint32_t o[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                f32x2 v = {acc[r][2 * i], acc[r][2 * i + 1]};
+                bf16x2 bb = __builtin_convertvector(v, bf16x2);
+                o[i] = __builtin_bit_cast(uint32_t, bb);
+            }
+            uint4 c[2];
+#pragma unroll
+            for (int k = 0; k < 2; ++k) {
+                u32x2 s0 = __builtin_amdgcn_permlane32_swap(o[2 * k], o[2 * k + 4], false, false);
+                u32x2 s1 = __builtin_amdgcn_permlane32_swap(o[2 * k + 1], o[2 * k + 5], false, false);
+                c[k].x = s0[0]; c[k].y = s1[0]; c[k].z = s0[1]; c[k].w = s1[1];
+            }
+            if (ow < P.Wo && oh0 + r < P.Ho) {
+                uint16_t* p = yrow + r * row_pitch + cb * 32;
+                *(uint4*)p = c[0];
+                *(uint4*)(p + 8) = c[1];
+            }
+        }
+    }
+}
+
+// [Cout][3][3][3][4] -> [cout block][kd][kh][lane][8]: lane (co, half h) holds k = 8h + j = (kw = 2h + j/4, ci = j%4)
+__global__ void __launch_bounds__(256) c4_pack_weights_kernel(const uint16_t* __restrict__ w, uint16_t* __restrict__ wpack, int Cout) {
+    const long long total = (long long)(Cout / 32) * 9 * 512;
+    const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= total) return;
+    const int j = (int)(idx & 7);
+    long long r = idx >> 3;
+    const int lane = (int)(r & 63); r >>= 6;
+    const int kh = (int)(r % 3); r /= 3;
+    const int kd = (int)(r % 3); r /= 3;
+    const int cb = (int)r;
+    const int co = cb * 32 + (lane & 31);
+    const int kw = 2 * (lane >> 5) + (j >> 2), ci = j & 3;
+    wpack[idx] = kw < 3 ? w[((((long long)co * 3 + kd) * 3 + kh) * 3 + kw) * 4 + ci] : (uint16_t)0;
+}
+
+}  // namespace
+
+bool c4_fwd_supported(const Geom& g) {
+    if (g.dtype != MI3D_BF16 || g.kD != 3 || g.kH != 3 || g.kW != 3) return false;
+    if (g.sD != 1 || g.sH != 1 || g.sW != 1) return false;
+    if (g.pD > 2 || g.pH > 2 || g.pW > 2) return false;
+    return g.Cin == 4 && g.Cout % 32 == 0;
+}
+
+size_t c4_fwd_workspace_bytes(const Geom& g) { return c4_fwd_supported(g) ? (size_t)(g.Cout / 32) * 9 * 1024 : 0; }
+
+int c4_fwd(const Geom& g, const void* x, const void* w, void* y, void* ws, size_t ws_bytes, hipStream_t s) {
+    if (ws_bytes < c4_fwd_workspace_bytes(g)) return MI3D_ERR_WORKSPACE;
+    const long long total = (long long)(g.Cout / 32) * 9 * 512;
+    c4_pack_weights_kernel<<<(unsigned)((total + 255) / 256), 256, 0, s>>>((const uint16_t*)w, (uint16_t*)ws, g.Cout);
+    int st = check_launch();
+    if (st) return st;
+    C4Params P;
+    P.x = (const uint16_t*)x; P.wpack = (const uint16_t*)ws; P.y = (uint16_t*)y;
+    P.N = g.N; P.D = g.D; P.H = g.H; P.W = g.W; P.Cout = g.Cout;
+    P.Do = g.Do; P.Ho = g.Ho; P.Wo = g.Wo; P.pD = g.pD; P.pH = g.pH; P.pW = g.pW;
+    P.HT = (g.Ho + TH - 1) / TH;
+    P.WT = (g.Wo + TW - 1) / TW;
+    const long long blocks = (long long)g.N * g.Do * P.HT * P.WT;
+    if (blocks > 0x7fffffffll) return MI3D_ERR_UNSUPPORTED;
+    c4_fwd_kernel<<<(unsigned)blocks, 256, 0, s>>>(P);
+    return check_launch();
+}
+
+}  // namespace mi3d
+
+// ---------------------------------------------------------------------------
+// Weight gradient of the same layer: dw[co,t,ci] = sum_v dy[v,co] * x[v + t - p, ci].
+// The contraction runs over voxels; (kw, ci) is folded into the MFMA n
+// dimension (12 of 16 used), so one v_mfma_f32_16x16x32_bf16 per (kd, kh)
+// covers 16 couts x 32 voxels.  Both operands come from transposing LDS reads;
+// for x each lane passes the address of the voxel shifted by its own kw, so
+// the staged rows need no rearrangement.  A workgroup walks a contiguous range
+// of 16 x 32 dy patches, keeps its 9 accumulators per wave in registers, and
+// writes one partial-sum slot per wave pair; a second kernel adds the slots in
+// index order (bit-reproducible) and drops the padding columns.
+namespace mi3d {
+namespace {
+
+typedef __attribute__((__vector_size__(4 * sizeof(short)))) short s16x4;
+typedef __attribute__((__vector_size__(8 * sizeof(short)))) short s16x8;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
+
+constexpr int WDY_SLAB = TH * TW * 32;          // one 16-cout slab of the dy patch
+constexpr int WDY_BYTES = 2 * WDY_SLAB;         // 32 KB
+constexpr int WX_BYTES = 3 * PLANE * 8;         // 15.2 KB
+constexpr int WNDY = TH * TW * 4 / 256;         // 8 16-byte pieces per thread
+
+struct C4WgParams {
+    const uint16_t* x;
+    const uint16_t* dy;
+    float* part;   // [slot][Cout][9][16]
+    int N, D, H, W, Cout, Do, Ho, Wo, pD, pH, pW, HT, WT;
+    long long tiles;  // N*Do*HT*WT
+    int nwg;
+};
+
+__device__ __forceinline__ bf16x8 tr8(const char* p0, const char* p1) {
+    typedef __attribute__((address_space(3))) s16x4* lptr;
+    s16x4 a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lptr)p0);
+    s16x4 b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lptr)p1);
+    s16x8 c = __builtin_shufflevector(a, b, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8, c);
+}
+
+__global__ void __launch_bounds__(256, 2) c4_wgrad_kernel(C4WgParams P) {
+    __shared__ __attribute__((aligned(16))) char lds[WX_BYTES + WDY_BYTES];
+    char* x_lds = lds;
+    char* dy_lds = lds + WX_BYTES;
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const int coh = wave & 1, rh = wave >> 1;   // 16-cout half, half of the patch rows
+    const int cot = blockIdx.y;
+    const long long t0 = P.tiles * blockIdx.x / P.nwg, t1 = P.tiles * (blockIdx.x + 1) / P.nwg;
+
+    const int g = lane >> 4, s = lane & 15;
+    // dy: lane supplies voxel 4g + s/4 (+16), couts 4(s%4)..+3 of the wave's 16-cout slab
+    const char* dy_lane = dy_lds + coh * WDY_SLAB + (4 * g + (s >> 2)) * 32 + (s & 3) * 8;
+    // x: lane supplies voxel 4g + s/4 (+16) shifted by kw = s%4, all 4 channels
+    const char* x_lane = x_lds + (4 * g + (s >> 2) + (s & 3)) * 8;
+
+    f32x4 acc[3][3];
+#pragma unroll
+    for (int a = 0; a < 3; ++a)
+#pragma unroll
+        for (int b = 0; b < 3; ++b) acc[a][b] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    // patch loads of one tile into registers (zero outside the volume)
+    uint2 px[NLOAD];
+    uint4 pdy[WNDY];
+    auto load_tile = [&](long long tile) {
+        long long b = tile;
+        const int wt = (int)(b % P.WT); b /= P.WT;
+        const int ht = (int)(b % P.HT); b /= P.HT;
+        const int od = (int)(b % P.Do);
+        const int n = (int)(b / P.Do);
+        const int h0 = ht * TH, w0 = wt * TW;
+#pragma unroll
+        for (int i = 0; i < NLOAD; ++i) {
+            const int q = t + 256 * i;
+            const int pl = q / (PR * PCOLS), rem = q - pl * (PR * PCOLS);
+            const int row = rem / PCOLS, col = rem - row * PCOLS;
+            const int gd = od - P.pD + pl, gh = h0 - P.pH + row, gw = w0 - P.pW + col;
+            px[i] = uint2{0u, 0u};
+            if (q < NVOX && gd >= 0 && gd < P.D && gh >= 0 && gh < P.H && gw >= 0 && gw < P.W)
+                px[i] = *(const uint2*)(P.x + ((((long long)n * P.D + gd) * P.H + gh) * P.W + gw) * 4);
+        }
+#pragma unroll
+        for (int i = 0; i < WNDY; ++i) {
+            const int q = t + 256 * i, v = q >> 2, c = q & 3;
+            const int gh = h0 + (v >> 5), gw = w0 + (v & 31);
+            pdy[i] = uint4{0u, 0u, 0u, 0u};
+            if (gh < P.Ho && gw < P.Wo)
+                pdy[i] = *(const uint4*)(P.dy + ((((long long)n * P.Do + od) * P.Ho + gh) * P.Wo + gw) * P.Cout + cot * 32 + c * 8);
+        }
+    };
+    auto write_tile = [&]() {
+#pragma unroll
+        for (int i = 0; i < NLOAD; ++i) {
+            const int q = t + 256 * i;
+            const int pl = q / (PR * PCOLS), rem = q - pl * (PR * PCOLS);
+            const int row = rem / PCOLS, col = rem - row * PCOLS;
+            if (q < NVOX) *(uint2*)(x_lds + (pl * PLANE + row * PITCH + col) * 8) = px[i];
+        }
+#pragma unroll
+        for (int i = 0; i < WNDY; ++i) {
+            const int q = t + 256 * i, v = q >> 2, c = q & 3;
+            *(uint4*)(dy_lds + (c >> 1) * WDY_SLAB + v * 32 + (c & 1) * 16) = pdy[i];
+        }
+    };
+
+    if (t0 < t1) load_tile(t0);
+    for (long long tile = t0; tile < t1; ++tile) {
+        __syncthreads();  // readers of the previous tile are done
+        write_tile();
+        __syncthreads();
+        if (tile + 1 < t1) load_tile(tile + 1);  // in flight during the MFMA work below
+
+        // this wave's 8 dy rows, then every x row that meets them
+        bf16x8 dyf[TH / 2];
+#pragma unroll
+        for (int r = 0; r < TH / 2; ++r) {
+            const char* p = dy_lane + (rh * (TH / 2) + r) * TW * 32;
+            dyf[r] = tr8(p, p + 16 * 32);
+        }
+#pragma unroll
+        for (int kd = 0; kd < 3; ++kd)
+#pragma unroll
+            for (int rr = 0; rr < TH / 2 + 2; ++rr) {
+                const char* p = x_lane + (kd * PLANE + (rh * (TH / 2) + rr) * PITCH) * 8;
+                const bf16x8 xf = tr8(p, p + 16 * 8);
+#pragma unroll
+                for (int kh = 0; kh < 3; ++kh) {
+                    const int dr = rr - kh;
+                    if (dr < 0 || dr >= TH / 2) continue;
+                    acc[kd][kh] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(dyf[dr], xf, acc[kd][kh], 0, 0, 0);
+                }
+            }
+    }
+
+    // add the two row halves (fixed order: upper half onto lower), then one slot per workgroup.
+    // acc register v of lane l: co = 4 (l / 16) + v of the wave's half, n = l % 16 = 4 kw + ci
+    __syncthreads();
+    float* red = (float*)lds;  // [coh][kd*3+kh][v][lane]
+    if (rh == 1) {
+#pragma unroll
+        for (int q = 0; q < 9; ++q)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) red[((coh * 9 + q) * 4 + v) * 64 + lane] = acc[q / 3][q % 3][v];
+    }
+    __syncthreads();
+    if (rh == 0) {
+        float* out = P.part + ((long long)blockIdx.x * P.Cout + cot * 32 + coh * 16) * 144;
+#pragma unroll
+        for (int q = 0; q < 9; ++q)
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+                out[((4 * (lane >> 4) + v) * 9 + q) * 16 + (lane & 15)] = acc[q / 3][q % 3][v] + red[((coh * 9 + q) * 4 + v) * 64 + lane];
+    }
+}
+
+// dw[co][kd][kh][kw][ci] = sum over slots of part[slot][co][kd*3+kh][4 kw + ci]; a block handles 16
+// elements, thread (g, e) adds slots g, g + 16, ...; the 16 group sums are added in index order
+__global__ void __launch_bounds__(256) c4_wgrad_reduce_kernel(const float* __restrict__ part, float* __restrict__ dw, int Cout, int slots) {
+    __shared__ float sm[16][17];
+    const int e = threadIdx.x & 15, g = threadIdx.x >> 4;
+    const int idx = blockIdx.x * 16 + e;
+    const bool ok = idx < Cout * 108;
+    const int ci = idx & 3;
+    int r = idx >> 2;
+    const int kw = r % 3; r /= 3;
+    const int kdh = r % 9;
+    const int co = r / 9;
+    float a = 0.f;
+    if (ok)
+        for (int sl = g; sl < slots; sl += 16) a += part[(((long long)sl * Cout + co) * 9 + kdh) * 16 + 4 * kw + ci];
+    sm[g][e] = a;
+    __syncthreads();
+    if (g == 0 && ok) {
+        float b = 0.f;
+#pragma unroll
+        for (int k = 0; k < 16; ++k) b += sm[k][e];
+        dw[idx] = b;
+    }
+}
+
+}  // namespace
+
+bool c4_wgrad_supported(const Geom& g) { return c4_fwd_supported(g); }
+
+static int c4_wgrad_nwg(const Geom& g) {
+    const long long tiles = (long long)g.N * g.Do * ((g.Ho + TH - 1) / TH) * ((g.Wo + TW - 1) / TW);
+    const long long cap = 512 / (g.Cout / 32) > 0 ? 512 / (g.Cout / 32) : 1;
+    return (int)(tiles < cap ? tiles : cap);
+}
+
+size_t c4_wgrad_workspace_bytes(const Geom& g) {
+    if (!c4_wgrad_supported(g)) return 0;
+    return (size_t)c4_wgrad_nwg(g) * g.Cout * 144 * sizeof(float);
+}
+
+int c4_wgrad(const Geom& g, const void* x, const void* dy, float* dw, void* ws, size_t ws_bytes, hipStream_t s) {
+    if (ws_bytes < c4_wgrad_workspace_bytes(g)) return MI3D_ERR_WORKSPACE;
+    C4WgParams P;
+    P.x = (const uint16_t*)x; P.dy = (const uint16_t*)dy; P.part = (float*)ws;
+    P.N = g.N; P.D = g.D; P.H = g.H; P.W = g.W; P.Cout = g.Cout;
+    P.Do = g.Do; P.Ho = g.Ho; P.Wo = g.Wo; P.pD = g.pD; P.pH = g.pH; P.pW = g.pW;
+    P.HT = (g.Ho + TH - 1) / TH;
+    P.WT = (g.Wo + TW - 1) / TW;
+    P.tiles = (long long)g.N * g.Do * P.HT * P.WT;
+    P.nwg = c4_wgrad_nwg(g);
+    c4_wgrad_kernel<<<dim3((unsigned)P.nwg, (unsigned)(g.Cout / 32)), 256, 0, s>>>(P);
+    int st = check_launch();
+    if (st) return st;
+    c4_wgrad_reduce_kernel<<<(unsigned)((g.Cout * 108 + 15) / 16), 256, 0, s>>>((const float*)ws, dw, g.Cout, P.nwg);
+    return check_launch();
+}
+
+}  // namespace mi3d

@@ -118,15 +118,26 @@ __global__ void __launch_bounds__(256) wgrad_partial_kernel(Geom g, const T* __r
 
 }  // namespace
 
-// Sums `parts` partial tensors of `n` floats each, in index order (fixed
-// order => bit-reproducible).  Shared by every split-K weight-gradient kernel.
+// Sums `parts` partial tensors of `n` floats each in a fixed order
+// (bit-reproducible): a block handles 16 elements; thread (g, e) adds parts
+// g, g + 16, g + 32, ... of element e, then the 16 group sums are added in
+// index order.  Shared by every split-K weight-gradient kernel.
 __global__ void __launch_bounds__(256) reduce_partials_kernel(const float* __restrict__ part, float* __restrict__ out,
                                                               long long n, int parts) {
-    long long i = (long long)blockIdx.x * 256 + threadIdx.x;
-    if (i >= n) return;
+    __shared__ float sm[16][17];
+    const int e = threadIdx.x & 15, g = threadIdx.x >> 4;
+    const long long i = (long long)blockIdx.x * 16 + e;
     float acc = 0.f;
-    for (int p = 0; p < parts; ++p) acc += part[(long long)p * n + i];
-    out[i] = acc;
+    if (i < n)
+        for (int p = g; p < parts; p += 16) acc += part[(long long)p * n + i];
+    sm[g][e] = acc;
+    __syncthreads();
+    if (g == 0 && i < n) {
+        float a = 0.f;
+#pragma unroll
+        for (int k = 0; k < 16; ++k) a += sm[k][e];
+        out[i] = a;
+    }
 }
 
 static void wgrad_chunks(const Geom& g, int* chunks, long long* chunk_len) {
@@ -181,7 +192,7 @@ int direct_wgrad(const Geom& g, const void* x, const void* dy, float* dw, void* 
     int st = check_launch();
     if (st) return st;
     long long n = g.w_elems();
-    reduce_partials_kernel<<<(unsigned)((n + 255) / 256), 256, 0, s>>>(part, dw, n, chunks);
+    reduce_partials_kernel<<<(unsigned)((n + 15) / 16), 256, 0, s>>>(part, dw, n, chunks);
     return check_launch();
 }
 

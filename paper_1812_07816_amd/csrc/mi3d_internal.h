@@ -41,7 +41,7 @@ size_t direct_workspace_bytes(const Geom& g, int pass);
 int direct_fwd(const Geom& g, const void* x, const void* w, void* y, hipStream_t s);
 int direct_dgrad(const Geom& g, const void* dy, const void* w, void* dx, hipStream_t s);
 int direct_wgrad(const Geom& g, const void* x, const void* dy, float* dw, void* ws, size_t ws_bytes, hipStream_t s);
-// out[i] = sum_p part[p*n + i], p in index order (bit-reproducible)
+// out[i] = sum_p part[p*n + i] in a fixed order (bit-reproducible); launch with (n + 15) / 16 blocks of 256
 __global__ void reduce_partials_kernel(const float* __restrict__ part, float* __restrict__ out, long long n, int parts);
 
 
@@ -76,5 +76,14 @@ int embed_s_conv(const Geom& g, int pass, const void* a, const void* b, void* ou
 bool wgrad_s2_supported(const Geom& g);
 size_t wgrad_s2_workspace_bytes(const Geom& g);
 int wgrad_s2(const Geom& g, const void* x, const void* dy, float* dw, void* ws, size_t ws_bytes, hipStream_t s);
+
+
+// first-layer kernels (4 input channels)
+bool c4_fwd_supported(const Geom& g);
+size_t c4_fwd_workspace_bytes(const Geom& g);
+int c4_fwd(const Geom& g, const void* x, const void* w, void* y, void* ws, size_t ws_bytes, hipStream_t s);
+bool c4_wgrad_supported(const Geom& g);
+size_t c4_wgrad_workspace_bytes(const Geom& g);
+int c4_wgrad(const Geom& g, const void* x, const void* dy, float* dw, void* ws, size_t ws_bytes, hipStream_t s);
 
 }  // namespace mi3d
