@@ -43,13 +43,14 @@ int make_geom(const mi3d_conv_desc* d, Geom* g) {
 
 static bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
 
-enum Kernel { K_DIRECT = 0, K_SP = 1, K_WGRAD_MFMA = 2, K_S2_FWD = 3, K_EMBED_C = 4, K_EMBED_S = 5, K_WGRAD_S2 = 6, K_C4_FWD = 7, K_C4_WGRAD = 8, K_NONE = -1 };
+enum Kernel { K_DIRECT = 0, K_SP = 1, K_WGRAD_MFMA = 2, K_S2_FWD = 3, K_EMBED_C = 4, K_EMBED_S = 5, K_WGRAD_S2 = 6, K_C4_FWD = 7, K_C4_WGRAD = 8, K_DGRAD_S2 = 9, K_NONE = -1 };
 
 static Kernel choose(const Geom& g, int pass) {
     if (pass == MI3D_PASS_WGRAD && wgrad_mfma_supported(g)) return K_WGRAD_MFMA;
     if (pass == MI3D_PASS_WGRAD && wgrad_s2_supported(g)) return K_WGRAD_S2;
     if (sp_supported(g, pass)) return K_SP;
     if (pass == MI3D_PASS_FWD && s2_fwd_supported(g)) return K_S2_FWD;
+    if (pass == MI3D_PASS_DGRAD && dgrad_s2_supported(g)) return K_DGRAD_S2;
     if (pass == MI3D_PASS_FWD && c4_fwd_supported(g)) return K_C4_FWD;
     if (pass == MI3D_PASS_WGRAD && c4_wgrad_supported(g)) return K_C4_WGRAD;
     if (embed_c_supported(g, pass)) return K_EMBED_C;
@@ -64,6 +65,7 @@ static const char* kernel_name(Kernel k) {
         case K_WGRAD_MFMA: return "mfma_wgrad_plane_stream";
         case K_S2_FWD: return "mfma_stride2_plane_stream";
         case K_WGRAD_S2: return "mfma_wgrad_stride2";
+        case K_DGRAD_S2: return "mfma_dgrad_stride2_parity";
         case K_C4_FWD: return "mfma_cin4_folded_taps";
         case K_C4_WGRAD: return "mfma_wgrad_cin4_folded_taps";
         case K_EMBED_C: return "mfma_via_channel_padding";
@@ -131,6 +133,10 @@ size_t mi3d_conv3d_workspace_bytes(const mi3d_conv_desc* desc, int pass) {
         b = c4_fwd_workspace_bytes(g);
         if (b > need) need = b;
     }
+    if (pass == MI3D_PASS_DGRAD) {
+        size_t b = dgrad_s2_workspace_bytes(g);
+        if (b > need) need = b;
+    }
     {
         size_t b = embed_c_workspace_bytes(g, pass);
         if (b > need) need = b;
@@ -179,6 +185,7 @@ int mi3d_conv3d_dgrad(const mi3d_conv_desc* desc, const void* dy, const void* w,
         case K_SP: return sp_conv(g, MI3D_PASS_DGRAD, dy, w, dx, ws, ws_bytes, (hipStream_t)stream);
         case K_EMBED_C: return embed_c_conv(g, MI3D_PASS_DGRAD, dy, w, dx, ws, ws_bytes, (hipStream_t)stream);
         case K_EMBED_S: return embed_s_conv(g, MI3D_PASS_DGRAD, dy, w, dx, ws, ws_bytes, (hipStream_t)stream);
+        case K_DGRAD_S2: return dgrad_s2(g, dy, w, dx, ws, ws_bytes, (hipStream_t)stream);
         default: return MI3D_ERR_UNSUPPORTED;
     }
 }

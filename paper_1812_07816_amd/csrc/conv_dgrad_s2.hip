@@ -1,0 +1,308 @@
+// Data gradient of the 3x3x3 / stride 2 convolution (pad 0 or 1 on every
+// axis, Cout <= 64) on bf16 MFMA (v_mfma_f32_32x32x16_bf16), fp32 accumulation:
+//   dx[i,ci] = sum over (o,t) with 2 o - p + t == i of sum_co dy[o,co] * w[co,t,ci]
+//
+// Per axis, input position i = 2 c + e (pair index c, e in {0,1}) receives
+//   tap 0 from dy position c + p      and tap 2 from c + p - 1   if i + p is even  ("E")
+//   tap 1 from dy position c + p - [p == 1]                      if i + p is odd   ("O")
+// so a pair of dx planes / rows / columns needs the two dy positions
+// A = c + p - 1 and B = c + p and nothing else: no accumulator is carried from
+// one plane pair to the next.  A workgroup owns 4 row pairs (one per wave) x 32
+// column pairs and walks along D over plane pairs with a ring of two staged dy
+// plane patches (5 x 33 voxels x Cout); all 27 x Cout x 32 weights of its cin
+// tile stay in LDS.  Each wave holds the 8 accumulator blocks (plane E/O x row
+// E/O x column E/O, 32 cin x 32 column pairs each); the 27 taps are spread over
+// them as 8 + 4 + 4 + 4 + 2 + 2 + 2 + 1.  The layer writes 4x the bytes it
+// reads, so it is bound by its stores: lanes exchange halves so that each lane
+// writes the 64 contiguous bytes of one voxel.
+#include "mi3d_internal.h"
+
+namespace mi3d {
+namespace {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+typedef __attribute__((__vector_size__(2 * sizeof(float)))) float f32x2;
+typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(2))) unsigned u32x2;
+
+constexpr int RP = 4, CP = 32;             // row pairs, column pairs per workgroup
+constexpr int PR = RP + 1, PC = CP + 1;    // staged dy rows, columns
+constexpr int PITCH = 34;                  // row pitch (voxels)
+constexpr int SLABV = PR * PITCH;          // voxels per 8-channel slab
+
+struct Dg2Params {
+    const uint16_t* dy;
+    const uint16_t* wpack;  // [cin tile][kd][kh][kw][k16][lane][8]
+    uint16_t* dx;
+    int N, D, H, W, Cin, Cout, Do, Ho, Wo, p;
+    int QD, HT, WT, CiT;
+    long long units;
+    int nwg;
+};
+
+__device__ __forceinline__ f32x16 mfma(bf16x8 a, bf16x8 b, f32x16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+// per-axis tap table for class e (0 = E, 1 = O): number of taps, tap index, source side (0 = A, 1 = B)
+template <int P> struct Taps {
+    static constexpr int n(int cls) { return cls == 0 ? 2 : 1; }
+    static constexpr int tap(int cls, int k) { return cls == 0 ? (k == 0 ? 0 : 2) : 1; }
+    static constexpr int side(int cls, int k) { return cls == 0 ? (k == 0 ? 1 : 0) : (P == 1 ? 0 : 1); }
+};
+
+// fp32 block -> packed bf16; lane (n, h) ends with cins 16h .. 16h + 15 of its voxel in two uint4
+__device__ __forceinline__ void pack_block(const f32x16& a, uint4 (&c)[2]) {
+    uint32_t o[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        f32x2 v = {a[2 * i], a[2 * i + 1]};
+        bf16x2 b = __builtin_convertvector(v, bf16x2);
+        o[i] = __builtin_bit_cast(uint32_t, b);
+    }
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+        u32x2 s0 = __builtin_amdgcn_permlane32_swap(o[2 * k], o[2 * k + 4], false, false);
+        u32x2 s1 = __builtin_amdgcn_permlane32_swap(o[2 * k + 1], o[2 * k + 5], false, false);
+        c[k].x = s0[0]; c[k].y = s1[0]; c[k].z = s0[1]; c[k].w = s1[1];
+    }
+}
+
+template <int P>
+__global__ void __launch_bounds__(256, 1) dgrad_s2_kernel(Dg2Params G) {
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+    const int KK = G.Cout / 16;                 // k16 steps
+    const int SLABS = G.Cout / 8;
+    const int W_BYTES = 27 * KK * 1024;
+    const int STAGE = SLABS * SLABV * 16;
+    char* w_lds = lds;
+    char* in_lds = lds + W_BYTES;               // two stages, slot = dy plane & 1
+
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    int g = blockIdx.x;
+    if ((G.nwg & 7) == 0) g = (g & 7) * (G.nwg >> 3) + (g >> 3);
+    long long u0 = G.units * g / G.nwg, u1 = G.units * (g + 1) / G.nwg;
+
+    const int NPIECE = PR * PC * SLABS;         // 16-byte pieces of a staged plane (<= 1320)
+    constexpr int NL = 6;
+    int cur_cit = -1;
+
+    while (u0 < u1) {
+        long long column = u0 / G.QD;
+        const int q_start = (int)(u0 - column * G.QD);
+        const long long left = u1 - u0;
+        const int q_end = q_start + (int)(left < (long long)(G.QD - q_start) ? left : (long long)(G.QD - q_start));
+        u0 += q_end - q_start;
+        const int wt = (int)(column % G.WT); column /= G.WT;
+        const int ht = (int)(column % G.HT); column /= G.HT;
+        const int cit = (int)(column % G.CiT);
+        const int n = (int)(column / G.CiT);
+        const int rq0 = ht * RP, cq0 = wt * CP;   // first row pair / column pair
+
+        __syncthreads();  // previous segment's readers are done
+        if (cit != cur_cit) {
+            const uint4* src = (const uint4*)(G.wpack + (long long)cit * (W_BYTES / 2));
+            for (int i = t; i < W_BYTES / 16; i += 256) ((uint4*)w_lds)[i] = src[i];
+            cur_cit = cit;
+        }
+        // load plan: piece q = (voxel v = q / SLABS, slab c = q % SLABS), voxel row-major over 5 x 33
+        int goff[NL], loff[NL];
+        unsigned valid = 0;
+#pragma unroll
+        for (int i = 0; i < NL; ++i) {
+            const int q = t + 256 * i;
+            const int v = q / SLABS, c = q - v * SLABS;
+            const int row = v / PC, col = v - row * PC;
+            const int gh = rq0 + G.p - 1 + row, gw = cq0 + G.p - 1 + col;
+            const bool ok = q < NPIECE && gh >= 0 && gh < G.Ho && gw >= 0 && gw < G.Wo;
+            goff[i] = ok ? (gh * G.Wo + gw) * G.Cout + c * 8 : 0;
+            loff[i] = (c * SLABV + row * PITCH + col) * 16;
+            valid |= (ok ? 1u : 0u) << i;
+        }
+        const long long dy_plane = (long long)G.Ho * G.Wo * G.Cout;
+        const uint16_t* dyn = G.dy + (long long)n * G.Do * dy_plane;
+        uint16_t* dxn = G.dx + (long long)n * G.D * G.H * G.W * G.Cin;
+
+        uint4 pre[NL];
+        unsigned pre_mask = 0;
+        auto load_plane = [&](int m) {
+            const bool in = m >= 0 && m < G.Do;
+            const uint16_t* base = dyn + (long long)(in ? m : 0) * dy_plane;
+            pre_mask = in ? valid : 0u;
+#pragma unroll
+            for (int i = 0; i < NL; ++i) pre[i] = *(const uint4*)(base + goff[i]);
+        };
+        auto write_plane = [&](int slot) {
+            char* dst = in_lds + slot * STAGE;
+#pragma unroll
+            for (int i = 0; i < NL; ++i) {
+                const bool ok = (pre_mask >> i) & 1;
+                uint4 v;
+                v.x = ok ? pre[i].x : 0u; v.y = ok ? pre[i].y : 0u; v.z = ok ? pre[i].z : 0u; v.w = ok ? pre[i].w : 0u;
+                if (t + 256 * i < NPIECE) *(uint4*)(dst + loff[i]) = v;
+            }
+        };
+
+        // planes A = q + p - 1 and B = q + p of the first pair
+        load_plane(q_start + G.p - 1);
+        write_plane((q_start + G.p - 1) & 1);
+        load_plane(q_start + G.p);
+        write_plane((q_start + G.p) & 1);
+        __syncthreads();
+
+        // per-lane fragment addresses: lane (n = column pair, half h) reads slab 2 kk + h, row wave + side, column n + side
+        const int lane_in = ((lane >> 5) * SLABV + wave * PITCH + (lane & 31)) * 16;
+        const char* w_lane = w_lds + lane * 16;
+
+        for (int q = q_start; q < q_end; ++q) {
+            const bool more = q + 1 < q_end;
+            const int mA = q + G.p - 1, mB = q + G.p;
+            if (more) load_plane(mB + 1);
+            const char* plane_base[2] = {in_lds + (mA & 1) * STAGE + lane_in, in_lds + (mB & 1) * STAGE + lane_in};
+
+            f32x16 acc[2][2][2];
+#pragma unroll
+            for (int a = 0; a < 2; ++a)
+#pragma unroll
+                for (int b = 0; b < 2; ++b)
+#pragma unroll
+                    for (int c = 0; c < 2; ++c)
+#pragma unroll
+                        for (int i = 0; i < 16; ++i) acc[a][b][c][i] = 0.f;
+
+            for (int kk = 0; kk < KK; ++kk) {
+                bf16x8 xb[2][2][2];  // [plane side][row side][column side]
+#pragma unroll
+                for (int ps = 0; ps < 2; ++ps)
+#pragma unroll
+                    for (int rs = 0; rs < 2; ++rs)
+#pragma unroll
+                        for (int cs = 0; cs < 2; ++cs)
+                            xb[ps][rs][cs] = *(const bf16x8*)(plane_base[ps] + (2 * kk * SLABV + rs * PITCH + cs) * 16);
+                const char* wk = w_lane + kk * 1024;
+#pragma unroll
+                for (int cd = 0; cd < 2; ++cd)
+#pragma unroll
+                    for (int id = 0; id < Taps<P>::n(cd); ++id)
+#pragma unroll
+                        for (int ch = 0; ch < 2; ++ch)
+#pragma unroll
+                            for (int ih = 0; ih < Taps<P>::n(ch); ++ih)
+#pragma unroll
+                                for (int cw = 0; cw < 2; ++cw)
+#pragma unroll
+                                    for (int iw = 0; iw < Taps<P>::n(cw); ++iw) {
+                                        const int tap = (Taps<P>::tap(cd, id) * 3 + Taps<P>::tap(ch, ih)) * 3 + Taps<P>::tap(cw, iw);
+                                        const bf16x8 wf = *(const bf16x8*)(wk + tap * KK * 1024);
+                                        acc[cd][ch][cw] = mfma(wf, xb[Taps<P>::side(cd, id)][Taps<P>::side(ch, ih)][Taps<P>::side(cw, iw)],
+                                                               acc[cd][ch][cw]);
+                                    }
+            }
+
+            // stores: dx position of class e on an axis is 2 c + (e == 0 ? p : 1 - p)
+            const int cq = cq0 + (lane & 31);
+            const int rq = rq0 + wave;
+#pragma unroll
+            for (int cd = 0; cd < 2; ++cd) {
+                const int id_ = 2 * q + (cd == 0 ? G.p : 1 - G.p);
+#pragma unroll
+                for (int ch = 0; ch < 2; ++ch) {
+                    const int ih_ = 2 * rq + (ch == 0 ? G.p : 1 - G.p);
+                    uint4 be[2], bo[2];
+                    pack_block(acc[cd][ch][0], be);   // class E columns: 2 cq + p
+                    pack_block(acc[cd][ch][1], bo);   // class O columns: 2 cq + 1 - p
+                    // even column = E if p == 0 else O
+                    uint4 (&ev)[2] = (P == 0) ? be : bo;
+                    uint4 (&od)[2] = (P == 0) ? bo : be;
+                    // lower lanes keep the even voxel and fetch its upper 16 cins; upper lanes keep the odd voxel
+                    uint4 first[2], second[2];
+#pragma unroll
+                    for (int k = 0; k < 2; ++k) {
+                        u32x2 a0 = __builtin_amdgcn_permlane32_swap(ev[k].x, od[k].x, false, false);
+                        u32x2 a1 = __builtin_amdgcn_permlane32_swap(ev[k].y, od[k].y, false, false);
+                        u32x2 a2 = __builtin_amdgcn_permlane32_swap(ev[k].z, od[k].z, false, false);
+                        u32x2 a3 = __builtin_amdgcn_permlane32_swap(ev[k].w, od[k].w, false, false);
+                        first[k] = uint4{a0[0], a1[0], a2[0], a3[0]};
+                        second[k] = uint4{a0[1], a1[1], a2[1], a3[1]};
+                    }
+                    const int iw_ = 2 * cq + (lane >> 5);
+                    if (id_ < G.D && ih_ < G.H && iw_ < G.W) {
+                        uint16_t* ptr = dxn + (((long long)id_ * G.H + ih_) * G.W + iw_) * G.Cin + cit * 32;
+                        *(uint4*)(ptr) = first[0];
+                        *(uint4*)(ptr + 8) = first[1];
+                        *(uint4*)(ptr + 16) = second[0];
+                        *(uint4*)(ptr + 24) = second[1];
+                    }
+                }
+            }
+
+            __syncthreads();              // everyone is done reading plane A
+            if (more) write_plane((mB + 1) & 1);
+            __syncthreads();
+        }
+    }
+}
+
+// [Cout][3][3][3][Cin] -> [cin tile][tap][k16][lane][8]: lane (ci = l % 32, half h) holds couts 16 kk + 8 h + j
+__global__ void __launch_bounds__(256) dgrad_s2_pack_kernel(const uint16_t* __restrict__ w, uint16_t* __restrict__ wpack, int Cin, int Cout) {
+    const long long total = 27ll * Cin * Cout;
+    const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= total) return;
+    const int j = (int)(idx & 7);
+    long long r = idx >> 3;
+    const int lane = (int)(r & 63); r >>= 6;
+    const int KK = Cout / 16;
+    const int kk = (int)(r % KK); r /= KK;
+    const int tap = (int)(r % 27);
+    const int cit = (int)(r / 27);
+    const int ci = cit * 32 + (lane & 31);
+    const int co = kk * 16 + 8 * (lane >> 5) + j;
+    wpack[idx] = w[((long long)co * 27 + tap) * Cin + ci];
+}
+
+}  // namespace
+
+bool dgrad_s2_supported(const Geom& g) {
+    if (g.dtype != MI3D_BF16 || g.kD != 3 || g.kH != 3 || g.kW != 3) return false;
+    if (g.sD != 2 || g.sH != 2 || g.sW != 2) return false;
+    if (g.pD != g.pH || g.pD != g.pW || g.pD > 1) return false;
+    return g.Cin % 32 == 0 && (g.Cout == 32 || g.Cout == 64);
+}
+
+size_t dgrad_s2_workspace_bytes(const Geom& g) { return dgrad_s2_supported(g) ? (size_t)g.w_elems() * 2 : 0; }
+
+int dgrad_s2(const Geom& g, const void* dy, const void* w, void* dx, void* ws, size_t ws_bytes, hipStream_t s) {
+    if (ws_bytes < dgrad_s2_workspace_bytes(g)) return MI3D_ERR_WORKSPACE;
+    const long long total = g.w_elems();
+    dgrad_s2_pack_kernel<<<(unsigned)((total + 255) / 256), 256, 0, s>>>((const uint16_t*)w, (uint16_t*)ws, g.Cin, g.Cout);
+    int st = check_launch();
+    if (st) return st;
+    Dg2Params G;
+    G.dy = (const uint16_t*)dy; G.wpack = (const uint16_t*)ws; G.dx = (uint16_t*)dx;
+    G.N = g.N; G.D = g.D; G.H = g.H; G.W = g.W; G.Cin = g.Cin; G.Cout = g.Cout;
+    G.Do = g.Do; G.Ho = g.Ho; G.Wo = g.Wo; G.p = g.pD;
+    G.QD = (g.D + 1) / 2;
+    G.HT = ((g.H + 1) / 2 + RP - 1) / RP;
+    G.WT = ((g.W + 1) / 2 + CP - 1) / CP;
+    G.CiT = g.Cin / 32;
+    G.units = (long long)g.N * G.CiT * G.HT * G.WT * G.QD;
+    int dev = 0, cus = 256;
+    if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+    const long long nwg = cus < G.units ? cus : G.units;
+    G.nwg = (int)nwg;
+    const size_t lds = (size_t)27 * (g.Cout / 16) * 1024 + 2 * (size_t)(g.Cout / 8) * SLABV * 16;
+    static bool attr_set = false;
+    if (!attr_set) {
+        const int max_lds = 27 * 4 * 1024 + 2 * 8 * SLABV * 16;
+        hipError_t e = hipFuncSetAttribute((const void*)dgrad_s2_kernel<0>, hipFuncAttributeMaxDynamicSharedMemorySize, max_lds);
+        if (e == hipSuccess) e = hipFuncSetAttribute((const void*)dgrad_s2_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize, max_lds);
+        if (e != hipSuccess) { note_hip_error(e); return MI3D_ERR_HIP; }
+        attr_set = true;
+    }
+    if (g.pD == 0) dgrad_s2_kernel<0><<<(unsigned)nwg, 256, lds, s>>>(G);
+    else dgrad_s2_kernel<1><<<(unsigned)nwg, 256, lds, s>>>(G);
+    return check_launch();
+}
+
+}  // namespace mi3d

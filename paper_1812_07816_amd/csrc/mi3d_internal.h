@@ -86,4 +86,10 @@ bool c4_wgrad_supported(const Geom& g);
 size_t c4_wgrad_workspace_bytes(const Geom& g);
 int c4_wgrad(const Geom& g, const void* x, const void* dy, float* dw, void* ws, size_t ws_bytes, hipStream_t s);
 
+
+// MFMA data gradient of the 3x3x3 stride-2 convolution (equal pads 0/1, Cout 32 or 64)
+bool dgrad_s2_supported(const Geom& g);
+size_t dgrad_s2_workspace_bytes(const Geom& g);
+int dgrad_s2(const Geom& g, const void* dy, const void* w, void* dx, void* ws, size_t ws_bytes, hipStream_t s);
+
 }  // namespace mi3d
