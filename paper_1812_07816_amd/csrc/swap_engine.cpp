@@ -2,6 +2,7 @@
 // host pool, one side stream per copy direction, events that order copies
 // against the compute stream, an event-aware device arena, and counters.
 #include <algorithm>
+#include <cstring>
 #include <map>
 #include <memory>
 #include <new>
@@ -159,6 +160,8 @@ int mi3d_swap_create(const mi3d_swap_config* cfg, mi3d_swap_engine** out) {
     if (cfg->host_pool_bytes) {
         hipError_t err = hipGetDevice(&e->device);
         if (err == hipSuccess) err = hipHostMalloc((void**)&e->host_pool, cfg->host_pool_bytes, hipHostMallocDefault);
+        // touch every page once: the first DMA into untouched pinned pages runs at a fraction of link speed
+        if (err == hipSuccess) memset(e->host_pool, 0, cfg->host_pool_bytes);
         if (err == hipSuccess) err = hipStreamCreateWithFlags(&e->s_out, hipStreamNonBlocking);
         if (err == hipSuccess) err = hipStreamCreateWithFlags(&e->s_in, hipStreamNonBlocking);
         if (err == hipSuccess) err = hipEventCreate(&e->base);
