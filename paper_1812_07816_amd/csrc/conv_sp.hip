@@ -288,24 +288,25 @@ __global__ void __launch_bounds__(256, 1) sp_conv_kernel(SpParams P) {
 
         // Plane step jj stages input plane ip = od_start + jj - pD, one 32-channel chunk at a time, and
         // completes output plane od_start + jj - 2.  Hook slots 0..9 issue the loads of the next stage,
-        // slots 10..13 the stores of the plane finished last (before slot 15 overwrites outp[]).
+        // slots 10..13 the stores of the plane finished last (before slot 15 overwrites outp[]).  Loads and
+        // LDS writes are unconditional (after the last stage they fetch a valid plane nobody reads): a
+        // condition would hide the load/consumer pairing from the compiler's wait-count insertion.
 #define SP_STAGE(PHASE, CHUNK, ZERO, LAST)                                                      \
         {                                                                                       \
             const int j_ = od_start + jj;                                                       \
-            const bool more_ = (CHUNK) + 1 < NC || jj + 1 < nJ;                                 \
             if ((CHUNK) + 1 < NC) begin_stage(j_ - P.pD, (CHUNK) + 1);                          \
             else begin_stage(j_ + 1 - P.pD, 0);                                                 \
             const int buf_ = NBUF == 2 ? (jj & 1) : 0;                                          \
             plane_compute<PHASE, ZERO, LAST>(acc, in_lds + buf_ * STAGE_BYTES + lane_in_off,    \
                                              w_lane + (CHUNK) * W_BYTES, outp, [&](int k) {     \
-                if (k < NLOAD) { if (more_) load_piece(k); }                                    \
+                if (k < NLOAD) load_piece(k);                                                   \
                 else if (k < NLOAD + RH) {                                                      \
                     store_piece(k - NLOAD);                                                     \
                     if (k == NLOAD + RH - 1) st_pending = false;                                \
                 }                                                                               \
             });                                                                                 \
             if (NBUF == 1) __syncthreads(); /* all waves are done reading the only stage */     \
-            if (more_) write_stage(NBUF == 2 ? ((jj + 1) & 1) : 0);                             \
+            write_stage(NBUF == 2 ? ((jj + 1) & 1) : 0);                                        \
             if (LAST) {                                                                         \
                 st_pending = jj >= 2;                                                           \
                 st_ptr = yn + (((long long)(j_ - 2) * P.Ho + h0 + wave * RH) * P.Wo + ow_) * P.Cout + ct * 32 + 16 * (lane >> 5); \

@@ -245,17 +245,18 @@ __global__ void __launch_bounds__(256, 1) wgrad_kernel(WgParams P) {
             for (int kd = 0; kd < 3; ++kd)
                 dyl[kd] = dy_lds + mod3(id + P.pD - kd) * DY_BYTES + coh * DY_SLAB + lane_off;
             const char* const dy_lane[3] = {dyl[0], dyl[1], dyl[2]};
-            // one global load per x row: rows 0..9 fetch the next x patch, rows 10..17 the next dy patch
+            // one global load per x row: rows 0..9 fetch the next x patch, rows 10..17 the next dy patch.
+            // The loads and the LDS writes below are unconditional (the step after the last one of a segment
+            // fetches a valid plane that is never used): with a condition the compiler cannot pair each
+            // load with its consumer and waits for all outstanding loads before every new one.
+            (void)more;
             plane_step(acc, x_lane, dy_lane, [&](int r) {
-                if (!more) return;
                 if (r < NX) px[r] = *(const uint4*)(bx + gx[r]);
                 else if (r - NX < NDY) pdy[r - NX] = *(const uint4*)(bdy + gdy[r - NX]);
             });
             __syncthreads();  // everyone is done reading the x patch and the oldest dy patch
-            if (more) {
-                write_x();
-                write_dy(mod3(id + 1 + P.pD));
-            }
+            write_x();
+            write_dy(mod3(id + 1 + P.pD));
             __syncthreads();
         }
     }

@@ -213,8 +213,8 @@ __global__ void __launch_bounds__(256, 1) wgrad_s2_kernel(Wg2Params P) {
             const char* d0 = dy_lds + (m & 1) * DY_BYTES + coh * DY_SLAB + lane_off;
             const char* d1 = dy_lds + ((m - 1) & 1) * DY_BYTES + coh * DY_SLAB + lane_off;
             const char* const dy_lane[2] = {d0, d1};
+            // unconditional x loads and LDS writes: see the stride-1 kernel
             auto hook = [&](int r) {
-                if (!more) return;
                 px[r] = *(const uint4*)(bx + gx[r]);
                 if (r + XR < NX) px[r + XR] = *(const uint4*)(bx + gx[r + XR]);  // 18 pieces over 17 rows
                 if (new_dy && r < NDY) pdy[r] = *(const uint4*)(bdy + gdy[r]);
@@ -222,10 +222,8 @@ __global__ void __launch_bounds__(256, 1) wgrad_s2_kernel(Wg2Params P) {
             if (even) plane_step<true>(acc, x_lane, dy_lane, hook);
             else plane_step<false>(acc, x_lane, dy_lane, hook);
             __syncthreads();
-            if (more) {
-                write_x();
-                if (new_dy) write_dy((m + 1) & 1);
-            }
+            write_x();
+            if (new_dy) write_dy((m + 1) & 1);
             __syncthreads();
         }
     }
