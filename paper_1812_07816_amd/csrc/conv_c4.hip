@@ -8,8 +8,8 @@
 // per (kd, kh) covers 32 voxels x 32 couts.  In NDHWC with 4 channels the 8
 // k-values of a lane half are two neighbouring voxels, i.e. 16 contiguous
 // bytes of the staged row: fragments need no im2col.  A workgroup computes a
-// 16 x 32 patch of one output plane from a 3-plane input patch (15 KB of LDS),
-// two workgroups per CU.
+// 16 x 32 patch of one output plane from a 3-plane input patch (15 KB of LDS);
+// two persistent workgroups per CU walk the patches.
 #include "mi3d_internal.h"
 
 namespace mi3d {
@@ -31,93 +31,132 @@ struct C4Params {
     const uint16_t* wpack;  // [cout block][kd][kh][lane][8]
     uint16_t* y;
     int N, D, H, W, Cout, Do, Ho, Wo, pD, pH, pW, HT, WT;
+    long long tiles;        // N*Do*HT*WT
+    int nwg;
 };
 
+// Persistent workgroups walk a contiguous range of (n, od, 16-row, 32-col) tiles; the input patch of
+// the next tile is fetched into registers while the current one is computed and stored.
 __global__ void __launch_bounds__(256, 2) c4_fwd_kernel(C4Params P) {
-    __shared__ __attribute__((aligned(16))) char lds[3 * PLANE * 8];
+    __shared__ __attribute__((aligned(16))) char lds[3 * PLANE * 8 + 4 * RH * 2048];
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
-    int b = blockIdx.x;
-    const int wt = b % P.WT; b /= P.WT;
-    const int ht = b % P.HT; b /= P.HT;
-    const int od = b % P.Do;
-    const int n = b / P.Do;
-    const int h0 = ht * TH, w0 = wt * TW;
+    char* stg = lds + 3 * PLANE * 8 + wave * RH * 2048;  // this wave's store staging: RH rows x 32 voxels x 64 B
+    const long long t0 = P.tiles * blockIdx.x / P.nwg, t1 = P.tiles * (blockIdx.x + 1) / P.nwg;
 
-    // stage the 3 x 18 x 35 voxel patch (8 bytes per voxel), zero outside the volume
+    uint2 px[NLOAD];
+    auto load_tile = [&](long long tile) {  // 3 x 18 x 35 voxels (8 bytes each), zero outside the volume
+        long long b = tile;
+        const int wt = (int)(b % P.WT); b /= P.WT;
+        const int ht = (int)(b % P.HT); b /= P.HT;
+        const int od = (int)(b % P.Do);
+        const int n = (int)(b / P.Do);
 #pragma unroll
-    for (int i = 0; i < NLOAD; ++i) {
-        const int q = t + 256 * i;
-        if (q < NVOX) {
+        for (int i = 0; i < NLOAD; ++i) {
+            const int q = t + 256 * i;
             const int pl = q / (PR * PCOLS), rem = q - pl * (PR * PCOLS);
             const int row = rem / PCOLS, col = rem - row * PCOLS;
-            const int gd = od - P.pD + pl, gh = h0 - P.pH + row, gw = w0 - P.pW + col;
-            uint2 v = {0u, 0u};
-            if (gd >= 0 && gd < P.D && gh >= 0 && gh < P.H && gw >= 0 && gw < P.W)
-                v = *(const uint2*)(P.x + ((((long long)n * P.D + gd) * P.H + gh) * P.W + gw) * 4);
-            *(uint2*)(lds + (pl * PLANE + row * PITCH + col) * 8) = v;
+            const int gd = od - P.pD + pl, gh = ht * TH - P.pH + row, gw = wt * TW - P.pW + col;
+            px[i] = uint2{0u, 0u};
+            if (q < NVOX && gd >= 0 && gd < P.D && gh >= 0 && gh < P.H && gw >= 0 && gw < P.W)
+                px[i] = *(const uint2*)(P.x + ((((long long)n * P.D + gd) * P.H + gh) * P.W + gw) * 4);
         }
-    }
-    __syncthreads();
-
-    // input fragments: lane (voxel n, half h) holds voxels n + 2h and n + 2h + 1 of the row = taps kw 2h, 2h + 1
-    bf16x8 xf[3][RH + 2];
-    const char* xl = lds + (wave * RH * PITCH + (lane & 31) + 2 * (lane >> 5)) * 8;
+    };
+    auto write_tile = [&]() {
 #pragma unroll
-    for (int kd = 0; kd < 3; ++kd)
-#pragma unroll
-        for (int r = 0; r < RH + 2; ++r) {
-            const uint2 lo = *(const uint2*)(xl + (kd * PLANE + r * PITCH) * 8);
-            const uint2 hi = *(const uint2*)(xl + (kd * PLANE + r * PITCH + 1) * 8);
-            const uint4 v = {lo.x, lo.y, hi.x, hi.y};
-            xf[kd][r] = __builtin_bit_cast(bf16x8, v);
+        for (int i = 0; i < NLOAD; ++i) {
+            const int q = t + 256 * i;
+            const int pl = q / (PR * PCOLS), rem = q - pl * (PR * PCOLS);
+            const int row = rem / PCOLS, col = rem - row * PCOLS;
+            if (q < NVOX) *(uint2*)(lds + (pl * PLANE + row * PITCH + col) * 8) = px[i];
         }
+    };
 
-    const int ow = w0 + (lane & 31);
-    const int oh0 = h0 + wave * RH;
-    const long long row_pitch = (long long)P.Wo * P.Cout;
-    uint16_t* yrow = P.y + ((((long long)n * P.Do + od) * P.Ho + oh0) * P.Wo + ow) * P.Cout + 16 * (lane >> 5);
+    if (t0 < t1) load_tile(t0);
+    for (long long tile = t0; tile < t1; ++tile) {
+        long long b = tile;
+        const int wt = (int)(b % P.WT); b /= P.WT;
+        const int ht = (int)(b % P.HT); b /= P.HT;
+        const int od = (int)(b % P.Do);
+        const int n = (int)(b / P.Do);
+        const int h0 = ht * TH, w0 = wt * TW;
+        __syncthreads();  // readers of the previous tile are done
+        write_tile();
+        __syncthreads();
+        if (tile + 1 < t1) load_tile(tile + 1);
 
-    for (int cb = 0; cb < P.Cout / 32; ++cb) {
-        const bf16x8* wp = (const bf16x8*)(P.wpack + (long long)cb * 9 * 512) + lane;
-        bf16x8 wf[9];
-#pragma unroll
-        for (int q = 0; q < 9; ++q) wf[q] = wp[q * 64];
-        f32x16 acc[RH];
+        // input fragments: lane (voxel n, half h) holds voxels n + 2h and n + 2h + 1 of the row = taps kw 2h, 2h + 1
+        bf16x8 xf[3][RH + 2];
+        const char* xl = lds + (wave * RH * PITCH + (lane & 31) + 2 * (lane >> 5)) * 8;
 #pragma unroll
         for (int kd = 0; kd < 3; ++kd)
 #pragma unroll
-            for (int kh = 0; kh < 3; ++kh)
+            for (int r = 0; r < RH + 2; ++r) {
+                const uint2 lo = *(const uint2*)(xl + (kd * PLANE + r * PITCH) * 8);
+                const uint2 hi = *(const uint2*)(xl + (kd * PLANE + r * PITCH + 1) * 8);
+                const uint4 v = {lo.x, lo.y, hi.x, hi.y};
+                xf[kd][r] = __builtin_bit_cast(bf16x8, v);
+            }
+
+        const int oh0 = h0 + wave * RH;
+        const long long row_pitch = (long long)P.Wo * P.Cout;
+        uint16_t* ybase = P.y + ((((long long)n * P.Do + od) * P.Ho + oh0) * P.Wo + w0) * P.Cout;
+
+        for (int cb = 0; cb < P.Cout / 32; ++cb) {
+            const bf16x8* wp = (const bf16x8*)(P.wpack + (long long)cb * 9 * 512) + lane;
+            bf16x8 wf[9];
 #pragma unroll
-                for (int r = 0; r < RH; ++r) {
-                    if (kd == 0 && kh == 0) {
-                        f32x16 z = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-                        acc[r] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[0], xf[0][r], z, 0, 0, 0);
-                    } else {
-                        acc[r] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[kd * 3 + kh], xf[kd][r + kh], acc[r], 0, 0, 0);
+            for (int q = 0; q < 9; ++q) wf[q] = wp[q * 64];
+            f32x16 acc[RH];
+#pragma unroll
+            for (int kd = 0; kd < 3; ++kd)
+#pragma unroll
+                for (int kh = 0; kh < 3; ++kh)
+#pragma unroll
+                    for (int r = 0; r < RH; ++r) {
+                        if (kd == 0 && kh == 0) {
+                            f32x16 z = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+                            acc[r] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[0], xf[0][r], z, 0, 0, 0);
+                        } else {
+                            acc[r] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[kd * 3 + kh], xf[kd][r + kh], acc[r], 0, 0, 0);
+                        }
                     }
+            typedef __attribute__((ext_vector_type(2))) unsigned u32x2;
+            // lane (n, h) ends with couts 16h .. 16h+15 of voxel n; the rows pass through LDS so that
+            // each store instruction writes whole 64-byte voxels of 16 neighbouring voxels
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int r = 0; r < RH; ++r) {
+                uint32_t o[8];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    f32x2 v = {acc[r][2 * i], acc[r][2 * i + 1]};
+                    bf16x2 bb = __builtin_convertvector(v, bf16x2);
+                    o[i] = __builtin_bit_cast(uint32_t, bb);
                 }
-        typedef __attribute__((ext_vector_type(2))) unsigned u32x2;
+                uint4 c[2];
 #pragma unroll
-        for (int r = 0; r < RH; ++r) {
-            uint32_t o[8];
+                for (int k = 0; k < 2; ++k) {
+                    u32x2 s0 = __builtin_amdgcn_permlane32_swap(o[2 * k], o[2 * k + 4], false, false);
+                    u32x2 s1 = __builtin_amdgcn_permlane32_swap(o[2 * k + 1], o[2 * k + 5], false, false);
+                    c[k].x = s0[0]; c[k].y = s1[0]; c[k].z = s0[1]; c[k].w = s1[1];
+                }
+                char* q = stg + r * 2048 + (lane & 31) * 64 + (lane >> 5) * 32;
+                *(uint4*)q = c[0];
+                *(uint4*)(q + 16) = c[1];
+            }
+            // same wave, LDS executes in order: only the compiler must not move the reads above the writes
+            asm volatile("" ::: "memory");
+            __builtin_amdgcn_wave_barrier();
+            asm volatile("" ::: "memory");
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                f32x2 v = {acc[r][2 * i], acc[r][2 * i + 1]};
-                bf16x2 bb = __builtin_convertvector(v, bf16x2);
-                o[i] = __builtin_bit_cast(uint32_t, bb);
-            }
-            uint4 c[2];
+            for (int r = 0; r < RH; ++r)
 #pragma unroll
-            for (int k = 0; k < 2; ++k) {
-                u32x2 s0 = __builtin_amdgcn_permlane32_swap(o[2 * k], o[2 * k + 4], false, false);
-                u32x2 s1 = __builtin_amdgcn_permlane32_swap(o[2 * k + 1], o[2 * k + 5], false, false);
-                c[k].x = s0[0]; c[k].y = s1[0]; c[k].z = s0[1]; c[k].w = s1[1];
-            }
-            if (ow < P.Wo && oh0 + r < P.Ho) {
-                uint16_t* p = yrow + r * row_pitch + cb * 32;
-                *(uint4*)p = c[0];
-                *(uint4*)(p + 8) = c[1];
-            }
+                for (int i = 0; i < 2; ++i) {
+                    const uint4 v = *(const uint4*)(stg + r * 2048 + i * 1024 + lane * 16);
+                    const int vox = i * 16 + (lane >> 2);
+                    if (w0 + vox < P.Wo && oh0 + r < P.Ho)
+                        *(uint4*)(ybase + r * row_pitch + (long long)vox * P.Cout + cb * 32 + (lane & 3) * 8) = v;
+                }
         }
     }
 }
@@ -161,9 +200,9 @@ int c4_fwd(const Geom& g, const void* x, const void* w, void* y, void* ws, size_
     P.Do = g.Do; P.Ho = g.Ho; P.Wo = g.Wo; P.pD = g.pD; P.pH = g.pH; P.pW = g.pW;
     P.HT = (g.Ho + TH - 1) / TH;
     P.WT = (g.Wo + TW - 1) / TW;
-    const long long blocks = (long long)g.N * g.Do * P.HT * P.WT;
-    if (blocks > 0x7fffffffll) return MI3D_ERR_UNSUPPORTED;
-    c4_fwd_kernel<<<(unsigned)blocks, 256, 0, s>>>(P);
+    P.tiles = (long long)g.N * g.Do * P.HT * P.WT;
+    P.nwg = (int)(P.tiles < 512 ? P.tiles : 512);
+    c4_fwd_kernel<<<(unsigned)P.nwg, 256, 0, s>>>(P);
     return check_launch();
 }
 

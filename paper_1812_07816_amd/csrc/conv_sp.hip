@@ -121,9 +121,11 @@ __device__ __forceinline__ void sub_step(f32x16 (&acc)[3][RH], XFrag& xc, XFrag&
 // ZERO: this stage is the first input-channel chunk of its plane (the new
 // output plane starts from zero); LAST: it is the last chunk (the oldest
 // output plane is complete and is converted to bf16).
-template <int PH, bool ZERO, bool LAST, class Hook>
+// phase_end(k), k = 0, 1, is called after the two positions of kw = k (the streamed-weight kernel refills
+// a weight slot and synchronises there).
+template <int PH, bool ZERO, bool LAST, class Hook, class PhaseEnd>
 __device__ __forceinline__ void plane_compute(f32x16 (&acc)[3][RH], const char* in_lane, const char* w_lane,
-                                              uint32_t (&outp)[RH][8], Hook&& hook) {
+                                              uint32_t (&outp)[RH][8], Hook&& hook, PhaseEnd&& phase_end) {
     XFrag xa, xb;
     WFrag w2, w1, w0;
     load_x<0>(xa, in_lane);
@@ -131,8 +133,10 @@ __device__ __forceinline__ void plane_compute(f32x16 (&acc)[3][RH], const char* 
     load_w<0, 1>(w1, w_lane);
     sub_step<PH, 0, ZERO, LAST>(acc, xa, xb, w2, w1, w0, in_lane, w_lane, outp, hook);
     sub_step<PH, 1, ZERO, LAST>(acc, xb, xa, w2, w1, w0, in_lane, w_lane, outp, hook);
+    phase_end(0);
     sub_step<PH, 2, ZERO, LAST>(acc, xa, xb, w2, w1, w0, in_lane, w_lane, outp, hook);
     sub_step<PH, 3, ZERO, LAST>(acc, xb, xa, w2, w1, w0, in_lane, w_lane, outp, hook);
+    phase_end(1);
     sub_step<PH, 4, ZERO, LAST>(acc, xa, xb, w2, w1, w0, in_lane, w_lane, outp, hook);
     sub_step<PH, 5, ZERO, LAST>(acc, xb, xa, w2, w1, w0, in_lane, w_lane, outp, hook);
 }
@@ -167,15 +171,23 @@ __device__ __forceinline__ void store_row(const uint32_t (&o)[8], uint16_t* p, b
     }
 }
 
-// NC = input-channel chunks of 32 (Cin = 32 NC).  All NC weight chunks of the
-// cout tile stay in LDS.  NC = 1 double-buffers the staged plane; NC = 2 has
-// room for one stage only and takes a second barrier per stage instead.
+// NC = input-channel chunks of 32 (Cin = 32 NC).  NC = 1 and 2: all weight
+// chunks of the cout tile stay in LDS; NC = 1 double-buffers the staged plane,
+// NC = 2 has room for one stage only and takes a second barrier per stage.
+// NC = 0: any number of chunks, weights streamed.  LDS holds the weights of
+// ONE chunk as three slots (one per kw, 18 KB each); while the positions of
+// kw = k are computed, the slot of kw = k + 2 (mod 3) is refilled from L2 with
+// the block it needs next, two phases ahead of its use, at the price of a
+// barrier per phase and 54 KB of extra L2 traffic per stage.
 template <int NC>
 __global__ void __launch_bounds__(256, 1) sp_conv_kernel(SpParams P) {
     extern __shared__ __attribute__((aligned(16))) char lds[];
-    constexpr int NBUF = NC == 1 ? 2 : 1;
+    constexpr bool STREAM = NC == 0;
+    constexpr int NBUF = NC == 2 ? 1 : 2;
+    const int nc = STREAM ? P.Cin / 32 : NC;
     char* w_lds = lds;
-    char* in_lds = lds + NC * W_BYTES;
+    char* in_lds = lds + (STREAM ? 1 : NC) * W_BYTES;
+    constexpr int WSLOT = W_BYTES / 3, WPIECES = WSLOT / 16, NWL = (WPIECES + 255) / 256;  // 18 KB, 1152, 5
 
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     // XCD-aware placement: hardware deals consecutive workgroup ids round-robin
@@ -212,11 +224,20 @@ __global__ void __launch_bounds__(256, 1) sp_conv_kernel(SpParams P) {
         int n = (int)(column / P.CT);
         const int h0 = ht * TH, w0 = wt * TW;
 
-        if (ct != cur_ct) {  // (re)load the weights of this cout tile; previous readers passed a barrier
-            const uint4* src = (const uint4*)(P.wpack + (long long)ct * NC * (W_BYTES / 2));
-            for (int i = t; i < NC * W_BYTES / 16; i += 256) ((uint4*)w_lds)[i] = src[i];
+        const char* wct = (const char*)P.wpack + (long long)ct * nc * W_BYTES;  // packed weights of this cout tile
+        if (STREAM) {  // slots kw = 0, 1 of chunk 0; slot 2 follows during the first phase
+            for (int i = t; i < 2 * WPIECES; i += 256) ((uint4*)w_lds)[i] = ((const uint4*)wct)[i];
+        } else if (ct != cur_ct) {  // (re)load the weights of this cout tile; previous readers passed a barrier
+            for (int i = t; i < NC * W_BYTES / 16; i += 256) ((uint4*)w_lds)[i] = ((const uint4*)wct)[i];
             cur_ct = ct;
         }
+        uint4 wreg[NWL];
+        const int wpiece[NWL] = {t, t + 256, t + 512, t + 768, t + 1024 < WPIECES ? t + 1024 : WPIECES - 1};
+        auto write_wslot = [&](int slot) {
+#pragma unroll
+            for (int i = 0; i < NWL; ++i)
+                if (t + 256 * i < WPIECES) *(uint4*)(w_lds + slot * WSLOT + (t + 256 * i) * 16) = wreg[i];
+        };
         // global offsets (elements) of this patch relative to the plane base
         int goff[NLOAD];
         unsigned valid = 0;
@@ -294,28 +315,42 @@ __global__ void __launch_bounds__(256, 1) sp_conv_kernel(SpParams P) {
 #define SP_STAGE(PHASE, CHUNK, ZERO, LAST)                                                      \
         {                                                                                       \
             const int j_ = od_start + jj;                                                       \
-            if ((CHUNK) + 1 < NC) begin_stage(j_ - P.pD, (CHUNK) + 1);                          \
+            const int cnext_ = (CHUNK) + 1 < nc ? (CHUNK) + 1 : 0;                              \
+            if ((CHUNK) + 1 < nc) begin_stage(j_ - P.pD, (CHUNK) + 1);                          \
             else begin_stage(j_ + 1 - P.pD, 0);                                                 \
-            const int buf_ = NBUF == 2 ? (jj & 1) : 0;                                          \
+            const int buf_ = NBUF == 2 ? (sq & 1) : 0;                                          \
+            /* streamed weights: block refilled during phase k = the next user of slot (k + 2) % 3 */ \
+            const char* wsrc_[3] = {wct + ((CHUNK) * 3 + 2) * WSLOT, wct + (cnext_ * 3 + 0) * WSLOT, wct + (cnext_ * 3 + 1) * WSLOT}; \
             plane_compute<PHASE, ZERO, LAST>(acc, in_lds + buf_ * STAGE_BYTES + lane_in_off,    \
-                                             w_lane + (CHUNK) * W_BYTES, outp, [&](int k) {     \
+                                             w_lane + (STREAM ? 0 : (CHUNK) * W_BYTES), outp, [&](int k) { \
+                if (STREAM && k % 6 < NWL) wreg[k % 6] = *(const uint4*)(wsrc_[k / 6] + wpiece[k % 6] * 16); \
                 if (k < NLOAD) load_piece(k);                                                   \
                 else if (k < NLOAD + RH) {                                                      \
                     store_piece(k - NLOAD);                                                     \
                     if (k == NLOAD + RH - 1) st_pending = false;                                \
                 }                                                                               \
+            }, [&](int k) {                                                                     \
+                if (STREAM) { write_wslot((k + 2) % 3); __syncthreads(); }                      \
             });                                                                                 \
+            if (STREAM) write_wslot(1);                                                         \
             if (NBUF == 1) __syncthreads(); /* all waves are done reading the only stage */     \
-            write_stage(NBUF == 2 ? ((jj + 1) & 1) : 0);                                        \
+            write_stage(NBUF == 2 ? ((sq + 1) & 1) : 0);                                        \
             if (LAST) {                                                                         \
                 st_pending = jj >= 2;                                                           \
                 st_ptr = yn + (((long long)(j_ - 2) * P.Ho + h0 + wave * RH) * P.Wo + ow_) * P.Cout + ct * 32 + 16 * (lane >> 5); \
             }                                                                                   \
+            ++sq;                                                                               \
             __syncthreads();                                                                    \
         }
 #define SP_STEP(PHASE)                                                                          \
         if (NC == 1) { SP_STAGE(PHASE, 0, true, true) }                                         \
-        else { SP_STAGE(PHASE, 0, true, false) SP_STAGE(PHASE, 1, false, true) }
+        else if (NC == 2) { SP_STAGE(PHASE, 0, true, false) SP_STAGE(PHASE, 1, false, true) }   \
+        else {                                                                                  \
+            SP_STAGE(PHASE, 0, true, false)                                                     \
+            for (int c_ = 1; c_ + 1 < nc; ++c_) SP_STAGE(PHASE, c_, false, false)               \
+            SP_STAGE(PHASE, nc - 1, false, true)                                                \
+        }
+        int sq = 0;  /* stage counter: selects the input buffer */
         for (int jj = 0;;) {
             SP_STEP(0)
             if (++jj >= nJ) break;
@@ -365,8 +400,8 @@ bool sp_supported(const Geom& g, int pass) {
     if (g.dtype != MI3D_BF16 || g.kD != 3 || g.kH != 3 || g.kW != 3) return false;
     if (g.sD != 1 || g.sH != 1 || g.sW != 1) return false;
     if (g.pD > 2 || g.pH > 2 || g.pW > 2) return false;
-    if (pass == MI3D_PASS_FWD) return (g.Cin == 32 || g.Cin == 64) && g.Cout % 32 == 0;
-    if (pass == MI3D_PASS_DGRAD) return (g.Cout == 32 || g.Cout == 64) && g.Cin % 32 == 0;
+    if (pass == MI3D_PASS_FWD) return g.Cin % 32 == 0 && g.Cout % 32 == 0;
+    if (pass == MI3D_PASS_DGRAD) return g.Cout % 32 == 0 && g.Cin % 32 == 0;
     return false;
 }
 
@@ -405,19 +440,18 @@ int sp_conv(const Geom& g, int pass, const void* in, const void* w, void* out, v
     if (nwg > P.units) nwg = P.units;
     P.nwg = (int)nwg;
     const int nc = P.Cin / 32;
-    const size_t lds = nc == 1 ? W_BYTES + 2 * STAGE_BYTES : 2 * W_BYTES + STAGE_BYTES;
+    const size_t lds1 = W_BYTES + 2 * STAGE_BYTES, lds2 = 2 * W_BYTES + STAGE_BYTES;
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void*)sp_conv_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                           (int)(W_BYTES + 2 * STAGE_BYTES));
-        if (e == hipSuccess)
-            e = hipFuncSetAttribute((const void*)sp_conv_kernel<2>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    (int)(2 * W_BYTES + STAGE_BYTES));
+        hipError_t e = hipFuncSetAttribute((const void*)sp_conv_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds1);
+        if (e == hipSuccess) e = hipFuncSetAttribute((const void*)sp_conv_kernel<2>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds2);
+        if (e == hipSuccess) e = hipFuncSetAttribute((const void*)sp_conv_kernel<0>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds1);
         if (e != hipSuccess) { note_hip_error(e); return MI3D_ERR_HIP; }
         attr_set = true;
     }
-    if (nc == 1) sp_conv_kernel<1><<<(unsigned)nwg, 256, lds, s>>>(P);
-    else sp_conv_kernel<2><<<(unsigned)nwg, 256, lds, s>>>(P);
+    if (nc == 1) sp_conv_kernel<1><<<(unsigned)nwg, 256, lds1, s>>>(P);
+    else if (nc == 2) sp_conv_kernel<2><<<(unsigned)nwg, 256, lds2, s>>>(P);
+    else sp_conv_kernel<0><<<(unsigned)nwg, 256, lds1, s>>>(P);
     return check_launch();
 }
 
