@@ -43,9 +43,10 @@ int make_geom(const mi3d_conv_desc* d, Geom* g) {
 
 static bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
 
-enum Kernel { K_DIRECT = 0, K_SP = 1, K_WGRAD_MFMA = 2, K_S2_FWD = 3, K_EMBED_C = 4, K_EMBED_S = 5, K_WGRAD_S2 = 6, K_C4_FWD = 7, K_C4_WGRAD = 8, K_DGRAD_S2 = 9, K_NONE = -1 };
+enum Kernel { K_DIRECT = 0, K_SP = 1, K_WGRAD_MFMA = 2, K_S2_FWD = 3, K_EMBED_C = 4, K_EMBED_S = 5, K_WGRAD_S2 = 6, K_C4_FWD = 7, K_C4_WGRAD = 8, K_DGRAD_S2 = 9, K_POINTWISE = 10, K_NONE = -1 };
 
 static Kernel choose(const Geom& g, int pass) {
+    if (pointwise_supported(g)) return K_POINTWISE;
     if (pass == MI3D_PASS_WGRAD && wgrad_mfma_supported(g)) return K_WGRAD_MFMA;
     if (pass == MI3D_PASS_WGRAD && wgrad_s2_supported(g)) return K_WGRAD_S2;
     if (sp_supported(g, pass)) return K_SP;
@@ -66,6 +67,7 @@ static const char* kernel_name(Kernel k) {
         case K_S2_FWD: return "mfma_stride2_plane_stream";
         case K_WGRAD_S2: return "mfma_wgrad_stride2";
         case K_DGRAD_S2: return "mfma_dgrad_stride2_parity";
+        case K_POINTWISE: return "valu_pointwise_head";
         case K_C4_FWD: return "mfma_cin4_folded_taps";
         case K_C4_WGRAD: return "mfma_wgrad_cin4_folded_taps";
         case K_EMBED_C: return "mfma_via_channel_padding";
@@ -138,6 +140,10 @@ size_t mi3d_conv3d_workspace_bytes(const mi3d_conv_desc* desc, int pass) {
         if (b > need) need = b;
     }
     {
+        size_t b = pointwise_workspace_bytes(g, pass);
+        if (b > need) need = b;
+    }
+    {
         size_t b = embed_c_workspace_bytes(g, pass);
         if (b > need) need = b;
         b = embed_s_workspace_bytes(g, pass);
@@ -167,6 +173,7 @@ int mi3d_conv3d_fwd(const mi3d_conv_desc* desc, const void* x, const void* w, vo
         case K_SP: return sp_conv(g, MI3D_PASS_FWD, x, w, y, ws, ws_bytes, (hipStream_t)stream);
         case K_S2_FWD: return s2_fwd(g, x, w, y, ws, ws_bytes, (hipStream_t)stream);
         case K_C4_FWD: return c4_fwd(g, x, w, y, ws, ws_bytes, (hipStream_t)stream);
+        case K_POINTWISE: return pointwise_conv(g, MI3D_PASS_FWD, x, w, y, ws, ws_bytes, (hipStream_t)stream);
         case K_EMBED_C: return embed_c_conv(g, MI3D_PASS_FWD, x, w, y, ws, ws_bytes, (hipStream_t)stream);
         default: return MI3D_ERR_UNSUPPORTED;
     }
@@ -186,6 +193,7 @@ int mi3d_conv3d_dgrad(const mi3d_conv_desc* desc, const void* dy, const void* w,
         case K_EMBED_C: return embed_c_conv(g, MI3D_PASS_DGRAD, dy, w, dx, ws, ws_bytes, (hipStream_t)stream);
         case K_EMBED_S: return embed_s_conv(g, MI3D_PASS_DGRAD, dy, w, dx, ws, ws_bytes, (hipStream_t)stream);
         case K_DGRAD_S2: return dgrad_s2(g, dy, w, dx, ws, ws_bytes, (hipStream_t)stream);
+        case K_POINTWISE: return pointwise_conv(g, MI3D_PASS_DGRAD, dy, w, dx, ws, ws_bytes, (hipStream_t)stream);
         default: return MI3D_ERR_UNSUPPORTED;
     }
 }
@@ -203,6 +211,7 @@ int mi3d_conv3d_wgrad(const mi3d_conv_desc* desc, const void* x, const void* dy,
         case K_WGRAD_MFMA: return wgrad_mfma(g, x, dy, dw, ws, ws_bytes, (hipStream_t)stream);
         case K_WGRAD_S2: return wgrad_s2(g, x, dy, dw, ws, ws_bytes, (hipStream_t)stream);
         case K_C4_WGRAD: return c4_wgrad(g, x, dy, dw, ws, ws_bytes, (hipStream_t)stream);
+        case K_POINTWISE: return pointwise_conv(g, MI3D_PASS_WGRAD, x, dy, dw, ws, ws_bytes, (hipStream_t)stream);
         case K_EMBED_C: return embed_c_conv(g, MI3D_PASS_WGRAD, x, dy, dw, ws, ws_bytes, (hipStream_t)stream);
         case K_EMBED_S: return embed_s_conv(g, MI3D_PASS_WGRAD, x, dy, dw, ws, ws_bytes, (hipStream_t)stream);
         default: return MI3D_ERR_UNSUPPORTED;

@@ -1,0 +1,167 @@
+// 1x1x1 convolution to a handful of output channels (the segmentation head:
+// 32 -> 3 classes).  All three passes are bound by streaming the 32-channel
+// tensor once (3 flop/byte), so they are plain vector-ALU kernels built around
+// 16-byte loads and stores:
+//   fwd    y[v,co]  = sum_ci x[v,ci] w[co,ci]      one thread per voxel
+//   dgrad  dx[v,ci] = sum_co dy[v,co] w[co,ci]     one thread per 8 input channels of a voxel
+//   wgrad  dw[co,ci]= sum_v dy[v,co] x[v,ci]       per-thread partial sums over a strided voxel range,
+//                                                  block tree reduction, slots added in fixed order
+// Supported: k = 1, s = 1, p = 0, Cin % 8 == 0, Cin <= 64, Cout <= 4, bf16.
+#include "mi3d_internal.h"
+
+namespace mi3d {
+namespace {
+
+constexpr int MAXCI = 64, MAXCO = 4;
+
+__device__ __forceinline__ void unpack8(const uint4& v, float (&f)[8]) {
+    const uint32_t u[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        f[2 * i] = __uint_as_float(u[i] << 16);
+        f[2 * i + 1] = __uint_as_float(u[i] & 0xffff0000u);
+    }
+}
+
+template <int CO>
+__global__ void __launch_bounds__(256) pw_fwd_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ w,
+                                                     uint16_t* __restrict__ y, long long voxels, int Cin) {
+    __shared__ float ws[MAXCO * MAXCI];
+    for (int i = threadIdx.x; i < CO * Cin; i += 256) ws[i] = bf16_to_f32(w[i]);
+    __syncthreads();
+    const long long v = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (v >= voxels) return;
+    float acc[CO];
+#pragma unroll
+    for (int co = 0; co < CO; ++co) acc[co] = 0.f;
+    for (int c8 = 0; c8 < Cin / 8; ++c8) {
+        float f[8];
+        unpack8(*(const uint4*)(x + v * Cin + c8 * 8), f);
+#pragma unroll
+        for (int co = 0; co < CO; ++co)
+#pragma unroll
+            for (int j = 0; j < 8; ++j) acc[co] = fmaf(f[j], ws[co * Cin + c8 * 8 + j], acc[co]);
+    }
+#pragma unroll
+    for (int co = 0; co < CO; ++co) y[v * CO + co] = f32_to_bf16_rne(acc[co]);
+}
+
+template <int CO>
+__global__ void __launch_bounds__(256) pw_dgrad_kernel(const uint16_t* __restrict__ dy, const uint16_t* __restrict__ w,
+                                                       uint16_t* __restrict__ dx, long long voxels, int Cin) {
+    __shared__ float ws[MAXCO * MAXCI];
+    for (int i = threadIdx.x; i < CO * Cin; i += 256) ws[i] = bf16_to_f32(w[i]);
+    __syncthreads();
+    const int per = Cin / 8;
+    const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= voxels * per) return;
+    const long long v = idx / per;
+    const int c0 = (int)(idx % per) * 8;
+    float g[CO];
+#pragma unroll
+    for (int co = 0; co < CO; ++co) g[co] = bf16_to_f32(dy[v * CO + co]);
+    uint32_t o[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        float a = 0.f, b = 0.f;
+#pragma unroll
+        for (int co = 0; co < CO; ++co) {
+            a = fmaf(g[co], ws[co * Cin + c0 + 2 * j], a);
+            b = fmaf(g[co], ws[co * Cin + c0 + 2 * j + 1], b);
+        }
+        o[j] = (uint32_t)f32_to_bf16_rne(a) | ((uint32_t)f32_to_bf16_rne(b) << 16);
+    }
+    *(uint4*)(dx + v * Cin + c0) = uint4{o[0], o[1], o[2], o[3]};
+}
+
+// block b handles voxels b, b + gridDim.x, ... in chunks; thread (g = t / per, c8 = t % per): voxel lane g
+template <int CO>
+__global__ void __launch_bounds__(256) pw_wgrad_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ dy,
+                                                       float* __restrict__ part, long long voxels, int Cin) {
+    __shared__ float red[256 * 8];
+    const int per = Cin / 8, groups = 256 / per;
+    const int t = threadIdx.x, g = t / per, c8 = t % per;
+    float acc[CO][8];
+#pragma unroll
+    for (int co = 0; co < CO; ++co)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[co][j] = 0.f;
+    if (g < groups)
+        for (long long v = (long long)blockIdx.x * groups + g; v < voxels; v += (long long)gridDim.x * groups) {
+            float f[8];
+            unpack8(*(const uint4*)(x + v * Cin + c8 * 8), f);
+#pragma unroll
+            for (int co = 0; co < CO; ++co) {
+                const float gv = bf16_to_f32(dy[v * CO + co]);
+#pragma unroll
+                for (int j = 0; j < 8; ++j) acc[co][j] = fmaf(gv, f[j], acc[co][j]);
+            }
+        }
+    // fixed-order reduction over the voxel lanes g of the block, one cout at a time
+    for (int co = 0; co < CO; ++co) {
+        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < 8; ++j) red[t * 8 + j] = (g < groups) ? acc[co][j] : 0.f;
+        __syncthreads();
+        if (t < Cin) {
+            const int cc8 = t / 8, j = t % 8;
+            float a = 0.f;
+            for (int gg = 0; gg < groups; ++gg) a += red[(gg * per + cc8) * 8 + j];
+            part[((long long)blockIdx.x * CO + co) * Cin + t] = a;
+        }
+    }
+}
+
+}  // namespace
+
+bool pointwise_supported(const Geom& g) {
+    if (g.dtype != MI3D_BF16 || g.kD != 1 || g.kH != 1 || g.kW != 1) return false;
+    if (g.sD != 1 || g.sH != 1 || g.sW != 1 || g.pD || g.pH || g.pW) return false;
+    return g.Cin % 8 == 0 && g.Cin <= MAXCI && g.Cout <= MAXCO && 256 % (g.Cin / 8) == 0;
+}
+
+static int pw_wgrad_blocks(const Geom& g) {
+    long long groups = 256 / (g.Cin / 8);
+    long long b = (g.in_voxels() + groups - 1) / groups;
+    return (int)(b < 1024 ? b : 1024);
+}
+
+size_t pointwise_workspace_bytes(const Geom& g, int pass) {
+    if (!pointwise_supported(g) || pass != MI3D_PASS_WGRAD) return 0;
+    return (size_t)pw_wgrad_blocks(g) * g.Cout * g.Cin * sizeof(float);
+}
+
+template <int CO>
+static int pw_run(const Geom& g, int pass, const void* a, const void* b, void* out, void* ws, hipStream_t s) {
+    const long long vox = g.in_voxels();
+    if (pass == MI3D_PASS_FWD) {
+        pw_fwd_kernel<CO><<<(unsigned)((vox + 255) / 256), 256, 0, s>>>((const uint16_t*)a, (const uint16_t*)b, (uint16_t*)out, vox, g.Cin);
+        return check_launch();
+    }
+    if (pass == MI3D_PASS_DGRAD) {
+        const long long n = vox * (g.Cin / 8);
+        pw_dgrad_kernel<CO><<<(unsigned)((n + 255) / 256), 256, 0, s>>>((const uint16_t*)a, (const uint16_t*)b, (uint16_t*)out, vox, g.Cin);
+        return check_launch();
+    }
+    const int blocks = pw_wgrad_blocks(g);
+    pw_wgrad_kernel<CO><<<blocks, 256, 0, s>>>((const uint16_t*)a, (const uint16_t*)b, (float*)ws, vox, g.Cin);
+    int st = check_launch();
+    if (st) return st;
+    const long long n = (long long)g.Cout * g.Cin;
+    reduce_partials_kernel<<<(unsigned)((n + 15) / 16), 256, 0, s>>>((const float*)ws, (float*)out, n, blocks);
+    return check_launch();
+}
+
+// fwd: a = x, b = w, out = y.  dgrad: a = dy, b = w, out = dx.  wgrad: a = x, b = dy, out = dw.
+int pointwise_conv(const Geom& g, int pass, const void* a, const void* b, void* out, void* ws, size_t ws_bytes, hipStream_t s) {
+    if (ws_bytes < pointwise_workspace_bytes(g, pass)) return MI3D_ERR_WORKSPACE;
+    if (g.in_voxels() * (g.Cin / 8) / 256 > 0x7fffffffll) return MI3D_ERR_UNSUPPORTED;
+    switch (g.Cout) {
+        case 1: return pw_run<1>(g, pass, a, b, out, ws, s);
+        case 2: return pw_run<2>(g, pass, a, b, out, ws, s);
+        case 3: return pw_run<3>(g, pass, a, b, out, ws, s);
+        default: return pw_run<4>(g, pass, a, b, out, ws, s);
+    }
+}
+
+}  // namespace mi3d

@@ -92,4 +92,10 @@ bool dgrad_s2_supported(const Geom& g);
 size_t dgrad_s2_workspace_bytes(const Geom& g);
 int dgrad_s2(const Geom& g, const void* dy, const void* w, void* dx, void* ws, size_t ws_bytes, hipStream_t s);
 
+
+// 1x1x1 convolution to <= 4 output channels (segmentation head), all passes
+bool pointwise_supported(const Geom& g);
+size_t pointwise_workspace_bytes(const Geom& g, int pass);
+int pointwise_conv(const Geom& g, int pass, const void* a, const void* b, void* out, void* ws, size_t ws_bytes, hipStream_t s);
+
 }  // namespace mi3d
