@@ -43,7 +43,10 @@ int make_geom(const mi3d_conv_desc* d, Geom* g) {
 
 static bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
 
-enum Kernel { K_DIRECT = 0, K_SP = 1, K_WGRAD_MFMA = 2, K_S2_FWD = 3, K_EMBED_C = 4, K_EMBED_S = 5, K_WGRAD_S2 = 6, K_C4_FWD = 7, K_C4_WGRAD = 8, K_DGRAD_S2 = 9, K_POINTWISE = 10, K_NONE = -1 };
+enum Kernel {
+    K_DIRECT = 0, K_SP, K_WGRAD_MFMA, K_S2_FWD, K_WGRAD_S2, K_DGRAD_S2, K_C4_FWD, K_C4_WGRAD, K_POINTWISE,
+    K_EMBED_C, K_EMBED_S, K_EMBED_K2
+};
 
 static Kernel choose(const Geom& g, int pass) {
     if (pointwise_supported(g)) return K_POINTWISE;
@@ -56,6 +59,7 @@ static Kernel choose(const Geom& g, int pass) {
     if (pass == MI3D_PASS_WGRAD && c4_wgrad_supported(g)) return K_C4_WGRAD;
     if (embed_c_supported(g, pass)) return K_EMBED_C;
     if (embed_s_supported(g, pass)) return K_EMBED_S;
+    if (embed_k2_supported(g, pass)) return K_EMBED_K2;
     return K_DIRECT;
 }
 
@@ -72,8 +76,55 @@ static const char* kernel_name(Kernel k) {
         case K_C4_WGRAD: return "mfma_wgrad_cin4_folded_taps";
         case K_EMBED_C: return "mfma_via_channel_padding";
         case K_EMBED_S: return "mfma_via_unit_stride";
+        case K_EMBED_K2: return "mfma_via_k3s2_embedding";
         default: return "none";
     }
+}
+
+static size_t kernel_workspace(Kernel k, const Geom& g, int pass) {
+    switch (k) {
+        case K_DIRECT: return direct_workspace_bytes(g, pass);
+        case K_SP: return sp_workspace_bytes(g, pass);
+        case K_WGRAD_MFMA: return wgrad_mfma_workspace_bytes(g);
+        case K_S2_FWD: return s2_fwd_workspace_bytes(g);
+        case K_WGRAD_S2: return wgrad_s2_workspace_bytes(g);
+        case K_DGRAD_S2: return dgrad_s2_workspace_bytes(g);
+        case K_C4_FWD: return c4_fwd_workspace_bytes(g);
+        case K_C4_WGRAD: return c4_wgrad_workspace_bytes(g);
+        case K_POINTWISE: return pointwise_workspace_bytes(g, pass);
+        case K_EMBED_C: return embed_c_workspace_bytes(g, pass);
+        case K_EMBED_S: return embed_s_workspace_bytes(g, pass);
+        case K_EMBED_K2: return embed_k2_workspace_bytes(g, pass);
+    }
+    return 0;
+}
+
+// a, b, out per pass: fwd (x, w, y), dgrad (dy, w, dx), wgrad (x, dy, dw)
+static int run_kernel(Kernel k, const Geom& g, int pass, const void* a, const void* b, void* out, void* ws, size_t ws_bytes, hipStream_t s) {
+    switch (k) {
+        case K_DIRECT:
+            if (pass == MI3D_PASS_FWD) return direct_fwd(g, a, b, out, s);
+            if (pass == MI3D_PASS_DGRAD) return direct_dgrad(g, a, b, out, s);
+            return direct_wgrad(g, a, b, (float*)out, ws, ws_bytes, s);
+        case K_SP: return sp_conv(g, pass, a, b, out, ws, ws_bytes, s);
+        case K_WGRAD_MFMA: return wgrad_mfma(g, a, b, (float*)out, ws, ws_bytes, s);
+        case K_S2_FWD: return s2_fwd(g, a, b, out, ws, ws_bytes, s);
+        case K_WGRAD_S2: return wgrad_s2(g, a, b, (float*)out, ws, ws_bytes, s);
+        case K_DGRAD_S2: return dgrad_s2(g, a, b, out, ws, ws_bytes, s);
+        case K_C4_FWD: return c4_fwd(g, a, b, out, ws, ws_bytes, s);
+        case K_C4_WGRAD: return c4_wgrad(g, a, b, (float*)out, ws, ws_bytes, s);
+        case K_POINTWISE: return pointwise_conv(g, pass, a, b, out, ws, ws_bytes, s);
+        case K_EMBED_C: return embed_c_conv(g, pass, a, b, out, ws, ws_bytes, s);
+        case K_EMBED_S: return embed_s_conv(g, pass, a, b, out, ws, ws_bytes, s);
+        case K_EMBED_K2: return embed_k2_conv(g, pass, a, b, out, ws, ws_bytes, s);
+    }
+    return MI3D_ERR_UNSUPPORTED;
+}
+
+// automatic choice for a geometry, used by the entry points and by fallbacks that re-enter with a derived geometry
+size_t auto_workspace_bytes(const Geom& g, int pass) { return kernel_workspace(choose(g, pass), g, pass); }
+int auto_conv(const Geom& g, int pass, const void* a, const void* b, void* out, void* ws, size_t ws_bytes, hipStream_t s) {
+    return run_kernel(choose(g, pass), g, pass, a, b, out, ws, ws_bytes, s);
 }
 
 }  // namespace mi3d
@@ -125,97 +176,32 @@ int mi3d_conv3d_kernel_name(const mi3d_conv_desc* desc, int pass, char* buf, siz
 size_t mi3d_conv3d_workspace_bytes(const mi3d_conv_desc* desc, int pass) {
     Geom g;
     if (make_geom(desc, &g) || pass < 0 || pass > 2) return 0;
-    // the plain kernels must always be runnable (family 1), so report the max
-    size_t need = direct_workspace_bytes(g, pass);
-    size_t sp = sp_workspace_bytes(g, pass);
-    if (sp > need) need = sp;
-    if (pass == MI3D_PASS_FWD) {
-        size_t b = s2_fwd_workspace_bytes(g);
-        if (b > need) need = b;
-        b = c4_fwd_workspace_bytes(g);
-        if (b > need) need = b;
-    }
-    if (pass == MI3D_PASS_DGRAD) {
-        size_t b = dgrad_s2_workspace_bytes(g);
-        if (b > need) need = b;
-    }
-    {
-        size_t b = pointwise_workspace_bytes(g, pass);
-        if (b > need) need = b;
-    }
-    {
-        size_t b = embed_c_workspace_bytes(g, pass);
-        if (b > need) need = b;
-        b = embed_s_workspace_bytes(g, pass);
-        if (b > need) need = b;
-    }
-    if (pass == MI3D_PASS_WGRAD) {
-        size_t wg = wgrad_mfma_workspace_bytes(g);
-        if (wg > need) need = wg;
-        wg = wgrad_s2_workspace_bytes(g);
-        if (wg > need) need = wg;
-        wg = c4_wgrad_workspace_bytes(g);
-        if (wg > need) need = wg;
-    }
-    return need;
+    // the plain kernels must stay runnable (kernel family 1), so report the larger of the two
+    size_t plain = direct_workspace_bytes(g, pass), chosen = auto_workspace_bytes(g, pass);
+    return plain > chosen ? plain : chosen;
+}
+
+static int conv_entry(const mi3d_conv_desc* desc, int pass, const void* a, const void* b, void* out, void* ws, size_t ws_bytes, void* stream) {
+    Geom g;
+    int st = make_geom(desc, &g);
+    if (st) return st;
+    if (!a || !b || !out || !aligned16(a) || !aligned16(b) || !aligned16(out) || !aligned16(ws)) return MI3D_ERR_INVALID_ARG;
+    if (ws_bytes && !ws) return MI3D_ERR_INVALID_ARG;
+    if (ws_bytes < mi3d_conv3d_workspace_bytes(desc, pass)) return MI3D_ERR_WORKSPACE;
+    Kernel k = g_family.load() == 1 ? K_DIRECT : choose(g, pass);
+    return run_kernel(k, g, pass, a, b, out, ws, ws_bytes, (hipStream_t)stream);
 }
 
 int mi3d_conv3d_fwd(const mi3d_conv_desc* desc, const void* x, const void* w, void* y, void* ws, size_t ws_bytes, void* stream) {
-    Geom g;
-    int st = make_geom(desc, &g);
-    if (st) return st;
-    if (!x || !w || !y || !aligned16(x) || !aligned16(w) || !aligned16(y) || !aligned16(ws)) return MI3D_ERR_INVALID_ARG;
-    if (ws_bytes && !ws) return MI3D_ERR_INVALID_ARG;
-    if (ws_bytes < mi3d_conv3d_workspace_bytes(desc, MI3D_PASS_FWD)) return MI3D_ERR_WORKSPACE;
-    Kernel k = g_family.load() == 1 ? K_DIRECT : choose(g, MI3D_PASS_FWD);
-    switch (k) {
-        case K_DIRECT: return direct_fwd(g, x, w, y, (hipStream_t)stream);
-        case K_SP: return sp_conv(g, MI3D_PASS_FWD, x, w, y, ws, ws_bytes, (hipStream_t)stream);
-        case K_S2_FWD: return s2_fwd(g, x, w, y, ws, ws_bytes, (hipStream_t)stream);
-        case K_C4_FWD: return c4_fwd(g, x, w, y, ws, ws_bytes, (hipStream_t)stream);
-        case K_POINTWISE: return pointwise_conv(g, MI3D_PASS_FWD, x, w, y, ws, ws_bytes, (hipStream_t)stream);
-        case K_EMBED_C: return embed_c_conv(g, MI3D_PASS_FWD, x, w, y, ws, ws_bytes, (hipStream_t)stream);
-        default: return MI3D_ERR_UNSUPPORTED;
-    }
+    return conv_entry(desc, MI3D_PASS_FWD, x, w, y, ws, ws_bytes, stream);
 }
 
 int mi3d_conv3d_dgrad(const mi3d_conv_desc* desc, const void* dy, const void* w, void* dx, void* ws, size_t ws_bytes, void* stream) {
-    Geom g;
-    int st = make_geom(desc, &g);
-    if (st) return st;
-    if (!dy || !w || !dx || !aligned16(dy) || !aligned16(w) || !aligned16(dx) || !aligned16(ws)) return MI3D_ERR_INVALID_ARG;
-    if (ws_bytes && !ws) return MI3D_ERR_INVALID_ARG;
-    if (ws_bytes < mi3d_conv3d_workspace_bytes(desc, MI3D_PASS_DGRAD)) return MI3D_ERR_WORKSPACE;
-    Kernel k = g_family.load() == 1 ? K_DIRECT : choose(g, MI3D_PASS_DGRAD);
-    switch (k) {
-        case K_DIRECT: return direct_dgrad(g, dy, w, dx, (hipStream_t)stream);
-        case K_SP: return sp_conv(g, MI3D_PASS_DGRAD, dy, w, dx, ws, ws_bytes, (hipStream_t)stream);
-        case K_EMBED_C: return embed_c_conv(g, MI3D_PASS_DGRAD, dy, w, dx, ws, ws_bytes, (hipStream_t)stream);
-        case K_EMBED_S: return embed_s_conv(g, MI3D_PASS_DGRAD, dy, w, dx, ws, ws_bytes, (hipStream_t)stream);
-        case K_DGRAD_S2: return dgrad_s2(g, dy, w, dx, ws, ws_bytes, (hipStream_t)stream);
-        case K_POINTWISE: return pointwise_conv(g, MI3D_PASS_DGRAD, dy, w, dx, ws, ws_bytes, (hipStream_t)stream);
-        default: return MI3D_ERR_UNSUPPORTED;
-    }
+    return conv_entry(desc, MI3D_PASS_DGRAD, dy, w, dx, ws, ws_bytes, stream);
 }
 
 int mi3d_conv3d_wgrad(const mi3d_conv_desc* desc, const void* x, const void* dy, float* dw, void* ws, size_t ws_bytes, void* stream) {
-    Geom g;
-    int st = make_geom(desc, &g);
-    if (st) return st;
-    if (!x || !dy || !dw || !aligned16(x) || !aligned16(dy) || !aligned16(dw) || !aligned16(ws)) return MI3D_ERR_INVALID_ARG;
-    if (ws_bytes && !ws) return MI3D_ERR_INVALID_ARG;
-    if (ws_bytes < mi3d_conv3d_workspace_bytes(desc, MI3D_PASS_WGRAD)) return MI3D_ERR_WORKSPACE;
-    Kernel k = g_family.load() == 1 ? K_DIRECT : choose(g, MI3D_PASS_WGRAD);
-    switch (k) {
-        case K_DIRECT: return direct_wgrad(g, x, dy, dw, ws, ws_bytes, (hipStream_t)stream);
-        case K_WGRAD_MFMA: return wgrad_mfma(g, x, dy, dw, ws, ws_bytes, (hipStream_t)stream);
-        case K_WGRAD_S2: return wgrad_s2(g, x, dy, dw, ws, ws_bytes, (hipStream_t)stream);
-        case K_C4_WGRAD: return c4_wgrad(g, x, dy, dw, ws, ws_bytes, (hipStream_t)stream);
-        case K_POINTWISE: return pointwise_conv(g, MI3D_PASS_WGRAD, x, dy, dw, ws, ws_bytes, (hipStream_t)stream);
-        case K_EMBED_C: return embed_c_conv(g, MI3D_PASS_WGRAD, x, dy, dw, ws, ws_bytes, (hipStream_t)stream);
-        case K_EMBED_S: return embed_s_conv(g, MI3D_PASS_WGRAD, x, dy, dw, ws, ws_bytes, (hipStream_t)stream);
-        default: return MI3D_ERR_UNSUPPORTED;
-    }
+    return conv_entry(desc, MI3D_PASS_WGRAD, x, dy, dw, ws, ws_bytes, stream);
 }
 
 }  // extern "C"

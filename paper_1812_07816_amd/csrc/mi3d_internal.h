@@ -98,4 +98,15 @@ bool pointwise_supported(const Geom& g);
 size_t pointwise_workspace_bytes(const Geom& g, int pass);
 int pointwise_conv(const Geom& g, int pass, const void* a, const void* b, void* out, void* ws, size_t ws_bytes, hipStream_t s);
 
+
+// 2x2x2 stride-2 pad-0 layers (decoder upsampling and its gradients) run as 3x3x3 stride-2 pad-1 layers
+// whose weights sit at taps {1,2}^3 (even extents only)
+bool embed_k2_supported(const Geom& g, int pass);
+size_t embed_k2_workspace_bytes(const Geom& g, int pass);
+int embed_k2_conv(const Geom& g, int pass, const void* a, const void* b, void* out, void* ws, size_t ws_bytes, hipStream_t s);
+
+// automatic kernel choice for a geometry (a, b, out per pass: fwd (x, w, y), dgrad (dy, w, dx), wgrad (x, dy, dw))
+size_t auto_workspace_bytes(const Geom& g, int pass);
+int auto_conv(const Geom& g, int pass, const void* a, const void* b, void* out, void* ws, size_t ws_bytes, hipStream_t s);
+
 }  // namespace mi3d
