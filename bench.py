@@ -48,6 +48,50 @@ def cpu_baseline(seconds_target=15.0):
                       f"workload ({dt:.1f} s)", "seconds": dt}
 
 
+def unet_layer_table(N):
+    """fwd / dgrad / wgrad of all 23 Conv3D layers of the 5-level U-Net at 192^3 (channels 32..320), each
+    timed alone with HIP events on the launch stream; the decoder's transposed convolutions are k2/s2
+    layers with roles swapped (their forward is the dgrad column)."""
+    import torch
+    from paper_1812_07816_amd import conv3d as mc
+    CH, VOL = [32, 64, 128, 256, 320], [192, 96, 48, 24, 12]
+    L = [("enc0.conv1", 192, 4, 32, 3, 1, 1), ("enc0.conv2", 192, 32, 32, 3, 1, 1)]
+    for l in range(1, 5):
+        L += [(f"enc{l}.conv1", VOL[l - 1], CH[l - 1], CH[l], 3, 2, 1), (f"enc{l}.conv2", VOL[l], CH[l], CH[l], 3, 1, 1)]
+    for l in range(3, -1, -1):
+        L += [(f"dec{l}.up", VOL[l], CH[l], CH[l + 1], 2, 2, 0), (f"dec{l}.conv1", VOL[l], 2 * CH[l], CH[l], 3, 1, 1),
+              (f"dec{l}.conv2", VOL[l], CH[l], CH[l], 3, 1, 1)]
+    L.append(("head.1x1", 192, 32, 3, 1, 1, 0))
+    stream = torch.cuda.current_stream()
+    rows, tot_ms, tot_flop = [], 0.0, 0.0
+    for (name, vol, cin, cout, k, s, p) in L:
+        d = mc.make_desc(N, vol, vol, vol, cin, cout, k, s, p, torch.bfloat16)
+        Do, Ho, Wo = mc.out_dims(d)
+        x = torch.randn((N, vol, vol, vol, cin), device="cuda").bfloat16()
+        w = (torch.randn((cout, k, k, k, cin), device="cuda") * 0.05).bfloat16()
+        dy = torch.randn((N, Do, Ho, Wo, cout), device="cuda").bfloat16()
+        y, dx, dw = torch.empty_like(dy), torch.empty_like(x), torch.empty((cout, k, k, k, cin), device="cuda")
+        ws = torch.empty(max(mc.workspace_bytes(d, q) for q in range(3)) + 16, dtype=torch.uint8, device="cuda")
+        flop = 2.0 * N * Do * Ho * Wo * k ** 3 * cin * cout
+        fns = [lambda: mc.conv3d_fwd(d, x, w, y, ws), lambda: mc.conv3d_dgrad(d, dy, w, dx, ws), lambda: mc.conv3d_wgrad(d, x, dy, dw, ws)]
+        row = {"layer": name, "vol": vol, "cin": cin, "cout": cout, "k": k, "s": s, "gflop_per_pass": flop / 1e9}
+        for pi, pname in enumerate(("fwd", "dgrad", "wgrad")):
+            fns[pi](); fns[pi]()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            for _ in range(5):
+                fns[pi]()
+            e1.record(stream)
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / 5
+            row[pname] = {"ms": round(ms, 4), "tflops": round(flop / ms / 1e9, 1), "kernel": mc.kernel_name(d, pi)}
+            tot_ms += ms
+            tot_flop += flop
+        rows.append(row)
+        del x, w, dy, y, dx, dw, ws
+    return {"layers": rows, "total_ms": tot_ms, "total_tflops": tot_flop / tot_ms / 1e9}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -58,6 +102,8 @@ def main():
     ap.add_argument("--no-sweep", action="store_true", help="skip the tighter-budget sweep")
     ap.add_argument("--lookahead", type=int, default=2)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--unet-layers", action="store_true",
+                    help="also time fwd/dgrad/wgrad of every Conv3D layer of the 5-level U-Net at 192^3 (adds ~20 s)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
@@ -197,6 +243,8 @@ def main():
         "kernels": [{k: (round(v, 4) if isinstance(v, float) else v) for k, v in r.items() if k not in ("flop", "bytes")} for r in per],
         "roofline": roof,
     }
+    if args.unet_layers:
+        out["unet_layers"] = unet_layer_table(N)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline()
     print(json.dumps(out))

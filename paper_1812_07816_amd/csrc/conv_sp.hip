@@ -94,27 +94,27 @@ __device__ __forceinline__ void convert_rows(const f32x16 (&a)[RH], uint32_t (&o
 // are in flight for at least one group of MFMAs.
 template <int PH, int SUB, bool ZERO, bool LAST, class Hook>
 __device__ __forceinline__ void sub_step(f32x16 (&acc)[3][RH], XFrag& xc, XFrag& xn, WFrag& w2, WFrag& w1, WFrag& w0,
-                                         const char* in_lane, const char* w_lane, uint32_t (&outp)[RH][8], Hook&& hook) {
+                                         const char* in_lane, const char* w_lane, uint32_t (&outp)[RH][8], int kdmask, Hook&& hook) {
     constexpr bool last = SUB == 5;
     load_w<SUB, 0>(w0, w_lane);
-    group_mfma<PH, SUB, 2, ZERO>(acc, xc, w2);
+    if (kdmask & 4) group_mfma<PH, SUB, 2, ZERO>(acc, xc, w2);
     hook(3 * SUB + 0);
     SP_FENCE();
     if (!last) load_x<last ? 0 : SUB + 1>(xn, in_lane);
     if (last && LAST) convert_rows(acc[(PH + 1) % 3], outp);
-    group_mfma<PH, SUB, 1, ZERO>(acc, xc, w1);
+    if (kdmask & 2) group_mfma<PH, SUB, 1, ZERO>(acc, xc, w1);
     hook(3 * SUB + 1);
     SP_FENCE();
     if (!last) load_w<last ? 0 : SUB + 1, 2>(w2, w_lane);
-    group_mfma<PH, SUB, 0, ZERO>(acc, xc, w0);
+    if (kdmask & 1) group_mfma<PH, SUB, 0, ZERO>(acc, xc, w0);
     hook(3 * SUB + 2);
     SP_FENCE();
     if (!last) load_w<last ? 0 : SUB + 1, 1>(w1, w_lane);
 }
 
-// All 216 MFMAs of one staged input plane.  Steps at the ends of a segment
-// also run in full: what they add to output planes outside the segment lands
-// in accumulator sets that are never stored and are restarted from zero.
+// The MFMAs of one staged input plane.  kdmask bit kd: output plane j - kd lies
+// inside the segment; the groups of the other taps are skipped (first and last
+// two steps of a segment), so no MFMA work is wasted on planes nobody stores.
 // hook(k), k = 0..17, is called once per group of 12 MFMAs: the caller spreads
 // its global loads and stores over the step with it, so that no wave ever
 // queues a burst of vector-memory instructions.
@@ -125,20 +125,20 @@ __device__ __forceinline__ void sub_step(f32x16 (&acc)[3][RH], XFrag& xc, XFrag&
 // a weight slot and synchronises there).
 template <int PH, bool ZERO, bool LAST, class Hook, class PhaseEnd>
 __device__ __forceinline__ void plane_compute(f32x16 (&acc)[3][RH], const char* in_lane, const char* w_lane,
-                                              uint32_t (&outp)[RH][8], Hook&& hook, PhaseEnd&& phase_end) {
+                                              uint32_t (&outp)[RH][8], int kdmask, Hook&& hook, PhaseEnd&& phase_end) {
     XFrag xa, xb;
     WFrag w2, w1, w0;
     load_x<0>(xa, in_lane);
     load_w<0, 2>(w2, w_lane);
     load_w<0, 1>(w1, w_lane);
-    sub_step<PH, 0, ZERO, LAST>(acc, xa, xb, w2, w1, w0, in_lane, w_lane, outp, hook);
-    sub_step<PH, 1, ZERO, LAST>(acc, xb, xa, w2, w1, w0, in_lane, w_lane, outp, hook);
+    sub_step<PH, 0, ZERO, LAST>(acc, xa, xb, w2, w1, w0, in_lane, w_lane, outp, kdmask, hook);
+    sub_step<PH, 1, ZERO, LAST>(acc, xb, xa, w2, w1, w0, in_lane, w_lane, outp, kdmask, hook);
     phase_end(0);
-    sub_step<PH, 2, ZERO, LAST>(acc, xa, xb, w2, w1, w0, in_lane, w_lane, outp, hook);
-    sub_step<PH, 3, ZERO, LAST>(acc, xb, xa, w2, w1, w0, in_lane, w_lane, outp, hook);
+    sub_step<PH, 2, ZERO, LAST>(acc, xa, xb, w2, w1, w0, in_lane, w_lane, outp, kdmask, hook);
+    sub_step<PH, 3, ZERO, LAST>(acc, xb, xa, w2, w1, w0, in_lane, w_lane, outp, kdmask, hook);
     phase_end(1);
-    sub_step<PH, 4, ZERO, LAST>(acc, xa, xb, w2, w1, w0, in_lane, w_lane, outp, hook);
-    sub_step<PH, 5, ZERO, LAST>(acc, xb, xa, w2, w1, w0, in_lane, w_lane, outp, hook);
+    sub_step<PH, 4, ZERO, LAST>(acc, xa, xb, w2, w1, w0, in_lane, w_lane, outp, kdmask, hook);
+    sub_step<PH, 5, ZERO, LAST>(acc, xb, xa, w2, w1, w0, in_lane, w_lane, outp, kdmask, hook);
 }
 
 // fp32 accumulators of one finished output plane -> packed bf16 (RNE)
@@ -321,8 +321,11 @@ __global__ void __launch_bounds__(256, 1) sp_conv_kernel(SpParams P) {
             const int buf_ = NBUF == 2 ? (sq & 1) : 0;                                          \
             /* streamed weights: block refilled during phase k = the next user of slot (k + 2) % 3 */ \
             const char* wsrc_[3] = {wct + ((CHUNK) * 3 + 2) * WSLOT, wct + (cnext_ * 3 + 0) * WSLOT, wct + (cnext_ * 3 + 1) * WSLOT}; \
+            int kdmask_ = 0;                                                                    \
+            for (int kd_ = 0; kd_ < 3; ++kd_)                                                   \
+                if (jj - kd_ >= 0 && jj - kd_ < nJ - 2) kdmask_ |= 1 << kd_;                    \
             plane_compute<PHASE, ZERO, LAST>(acc, in_lds + buf_ * STAGE_BYTES + lane_in_off,    \
-                                             w_lane + (STREAM ? 0 : (CHUNK) * W_BYTES), outp, [&](int k) { \
+                                             w_lane + (STREAM ? 0 : (CHUNK) * W_BYTES), outp, kdmask_, [&](int k) { \
                 if (STREAM && k % 6 < NWL) wreg[k % 6] = *(const uint4*)(wsrc_[k / 6] + wpiece[k % 6] * 16); \
                 if (k < NLOAD) load_piece(k);                                                   \
                 else if (k < NLOAD + RH) {                                                      \
