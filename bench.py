@@ -19,6 +19,22 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, published
 HBM_PEAK_GBS = 8000.0
 
 
+def measured_traffic(kernel):
+    """HBM bytes per launch of `kernel` as counted by rocprofv3 (FETCH_SIZE and WRITE_SIZE runs of this same
+    command, scaled by a copy kernel of known size); the figures are kept, with the commands that produced them,
+    in profiles/hbm_traffic_192_level0.txt as lines `<kernel> <read bytes> <write bytes>`.  None if not recorded."""
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "hbm_traffic_192_level0.txt")
+    try:
+        with open(path) as f:
+            for line in f:
+                p = line.split()
+                if len(p) == 3 and p[0] == kernel:
+                    return float(p[1]) + float(p[2])
+    except OSError:
+        pass
+    return None
+
+
 def cpu_baseline(seconds_target=15.0):
     """The fp64 oracle as it stands, timed on this host: fwd + dgrad + wgrad of
     a 32->32 3x3x3 layer on a cube sized for roughly `seconds_target` of work."""
@@ -220,12 +236,27 @@ def main():
             b = peak - cut
             sweep.append(swapped_run(b, best_lookahead(b), max(3, args.steps // 2), args.warmup))
 
-    dom = max(per, key=lambda r: r["ms"])
-    mfma_bound = dom["flop"] / dom["bytes"] > MFMA_BF16_PEAK_TFLOPS * 1e3 / HBM_PEAK_GBS
-    roof = ({"bound": "mfma", "achieved": dom["tflops"], "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-             "frac": dom["tflops"] / MFMA_BF16_PEAK_TFLOPS} if mfma_bound else
-            {"bound": "hbm", "achieved": dom["gbs"], "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": dom["gbs"] / HBM_PEAK_GBS})
-    roof.update({"traffic": None, "kernel": dom["kernel"], "layer": dom["layer"], "pass": dom["pass"], "ms": dom["ms"]})
+    # dominant kernel = the kernel (by name) with the largest share of the step's kernel time; its
+    # roofline figure is the algorithmic work of all its launches in one step over their summed duration
+    by_name = {}
+    for r in per:
+        a = by_name.setdefault(r["kernel"], {"ms": 0.0, "flop": 0.0, "bytes": 0.0, "launches": []})
+        a["ms"] += r["ms"]; a["flop"] += r["flop"]; a["bytes"] += r["bytes"]
+        a["launches"].append(f'{r["layer"]} {r["pass"]}')
+    dom_name, dom = max(by_name.items(), key=lambda kv: kv[1]["ms"])
+
+    def roofline_of(a):
+        tfl, gbs = a["flop"] / a["ms"] / 1e9, a["bytes"] / a["ms"] / 1e6
+        if a["flop"] / a["bytes"] > MFMA_BF16_PEAK_TFLOPS * 1e3 / HBM_PEAK_GBS:
+            return {"bound": "mfma", "achieved": tfl, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                    "frac": tfl / MFMA_BF16_PEAK_TFLOPS}
+        return {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS}
+
+    roof = roofline_of(dom)
+    roof.update({"traffic": measured_traffic(dom_name), "kernel": dom_name, "launches": dom["launches"],
+                 "ms_per_launch": dom["ms"] / len(dom["launches"]), "share_of_kernel_time": dom["ms"] / sum(r["ms"] for r in per)})
+    for r in per:
+        r["roofline"] = {k: (round(v, 4) if isinstance(v, float) else v) for k, v in roofline_of(r).items()}
 
     value = flops / ms_step / 1e9
     out = {

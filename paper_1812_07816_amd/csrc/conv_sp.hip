@@ -326,7 +326,9 @@ __global__ void __launch_bounds__(256, 1) sp_conv_kernel(SpParams P) {
                 if (jj - kd_ >= 0 && jj - kd_ < nJ - 2) kdmask_ |= 1 << kd_;                    \
             plane_compute<PHASE, ZERO, LAST>(acc, in_lds + buf_ * STAGE_BYTES + lane_in_off,    \
                                              w_lane + (STREAM ? 0 : (CHUNK) * W_BYTES), outp, kdmask_, [&](int k) { \
-                if (STREAM && k % 6 < NWL) wreg[k % 6] = *(const uint4*)(wsrc_[k / 6] + wpiece[k % 6] * 16); \
+                if (STREAM && k % 6 == 0) { /* all pieces of the slot at the start of its phase: a full phase of cover */ \
+                    _Pragma("unroll") for (int i_ = 0; i_ < NWL; ++i_) wreg[i_] = *(const uint4*)(wsrc_[k / 6] + wpiece[i_] * 16); \
+                }                                                                               \
                 if (k < NLOAD) load_piece(k);                                                   \
                 else if (k < NLOAD + RH) {                                                      \
                     store_piece(k - NLOAD);                                                     \
