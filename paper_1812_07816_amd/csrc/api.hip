@@ -44,7 +44,7 @@ int make_geom(const mi3d_conv_desc* d, Geom* g) {
 static bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
 
 enum Kernel {
-    K_DIRECT = 0, K_SP, K_WGRAD_MFMA, K_S2_FWD, K_WGRAD_S2, K_DGRAD_S2, K_C4_FWD, K_C4_WGRAD, K_POINTWISE,
+    K_DIRECT = 0, K_SP, K_WGRAD_MFMA, K_S2_FWD, K_WGRAD_S2, K_DGRAD_S2, K_C4_FWD, K_C4_DGRAD, K_C4_WGRAD, K_POINTWISE,
     K_EMBED_C, K_EMBED_S, K_EMBED_K2
 };
 
@@ -56,6 +56,7 @@ static Kernel choose(const Geom& g, int pass) {
     if (pass == MI3D_PASS_FWD && s2_fwd_supported(g)) return K_S2_FWD;
     if (pass == MI3D_PASS_DGRAD && dgrad_s2_supported(g)) return K_DGRAD_S2;
     if (pass == MI3D_PASS_FWD && c4_fwd_supported(g)) return K_C4_FWD;
+    if (pass == MI3D_PASS_DGRAD && c4_dgrad_supported(g)) return K_C4_DGRAD;
     if (pass == MI3D_PASS_WGRAD && c4_wgrad_supported(g)) return K_C4_WGRAD;
     if (embed_c_supported(g, pass)) return K_EMBED_C;
     if (embed_s_supported(g, pass)) return K_EMBED_S;
@@ -73,6 +74,7 @@ static const char* kernel_name(Kernel k) {
         case K_DGRAD_S2: return "mfma_dgrad_stride2_parity";
         case K_POINTWISE: return "valu_pointwise_head";
         case K_C4_FWD: return "mfma_cin4_folded_taps";
+        case K_C4_DGRAD: return "mfma_dgrad_cin4_folded_taps";
         case K_C4_WGRAD: return "mfma_wgrad_cin4_folded_taps";
         case K_EMBED_C: return "mfma_via_channel_padding";
         case K_EMBED_S: return "mfma_via_unit_stride";
@@ -90,6 +92,7 @@ static size_t kernel_workspace(Kernel k, const Geom& g, int pass) {
         case K_WGRAD_S2: return wgrad_s2_workspace_bytes(g);
         case K_DGRAD_S2: return dgrad_s2_workspace_bytes(g);
         case K_C4_FWD: return c4_fwd_workspace_bytes(g);
+        case K_C4_DGRAD: return c4_dgrad_workspace_bytes(g);
         case K_C4_WGRAD: return c4_wgrad_workspace_bytes(g);
         case K_POINTWISE: return pointwise_workspace_bytes(g, pass);
         case K_EMBED_C: return embed_c_workspace_bytes(g, pass);
@@ -112,6 +115,7 @@ static int run_kernel(Kernel k, const Geom& g, int pass, const void* a, const vo
         case K_WGRAD_S2: return wgrad_s2(g, a, b, (float*)out, ws, ws_bytes, s);
         case K_DGRAD_S2: return dgrad_s2(g, a, b, out, ws, ws_bytes, s);
         case K_C4_FWD: return c4_fwd(g, a, b, out, ws, ws_bytes, s);
+        case K_C4_DGRAD: return c4_dgrad(g, a, b, out, ws, ws_bytes, s);
         case K_C4_WGRAD: return c4_wgrad(g, a, b, (float*)out, ws, ws_bytes, s);
         case K_POINTWISE: return pointwise_conv(g, pass, a, b, out, ws, ws_bytes, s);
         case K_EMBED_C: return embed_c_conv(g, pass, a, b, out, ws, ws_bytes, s);

@@ -82,6 +82,9 @@ int wgrad_s2(const Geom& g, const void* x, const void* dy, float* dw, void* ws, 
 bool c4_fwd_supported(const Geom& g);
 size_t c4_fwd_workspace_bytes(const Geom& g);
 int c4_fwd(const Geom& g, const void* x, const void* w, void* y, void* ws, size_t ws_bytes, hipStream_t s);
+bool c4_dgrad_supported(const Geom& g);
+size_t c4_dgrad_workspace_bytes(const Geom& g);
+int c4_dgrad(const Geom& g, const void* dy, const void* w, void* dx, void* ws, size_t ws_bytes, hipStream_t s);
 bool c4_wgrad_supported(const Geom& g);
 size_t c4_wgrad_workspace_bytes(const Geom& g);
 int c4_wgrad(const Geom& g, const void* x, const void* dy, float* dw, void* ws, size_t ws_bytes, hipStream_t s);

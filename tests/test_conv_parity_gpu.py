@@ -62,6 +62,8 @@ MID = [
     (1, 4, 4, 6, 320, 320, 3, 1, 1),
     (1, 4, 6, 6, 256, 320, 3, 2, 1),
     (2, 12, 20, 36, 4, 32, 3, 1, 1),
+    (1, 5, 19, 45, 4, 32, 3, 1, 0),
+    (1, 4, 16, 33, 4, 32, 3, 1, 2),
     (1, 6, 10, 40, 32, 3, 1, 1, 0),
     (1, 8, 8, 16, 32, 64, 2, 2, 0),
 ]
