@@ -118,6 +118,9 @@ def main():
     ap.add_argument("--no-sweep", action="store_true", help="skip the tighter-budget sweep")
     ap.add_argument("--lookahead", type=int, default=2)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="first run three 256 MiB device-to-device copies: dispatches of known size against which "
+                         "rocprofv3's FETCH_SIZE / WRITE_SIZE readings are scaled")
     ap.add_argument("--unet-layers", action="store_true",
                     help="also time fwd/dgrad/wgrad of every Conv3D layer of the 5-level U-Net at 192^3 (adds ~20 s)")
     args = ap.parse_args()
@@ -134,6 +137,14 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     vol, N = args.vol, 1
+    if args.copy_calibration:
+        src = torch.full((64 << 20,), 1.0, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+        torch.cuda.empty_cache()
     layers = [chain.Layer(4, 32), chain.Layer(32, 32), chain.Layer(32, 64, s=2)]
 
     def dev(a):
@@ -257,6 +268,7 @@ def main():
                  "ms_per_launch": dom["ms"] / len(dom["launches"]), "share_of_kernel_time": dom["ms"] / sum(r["ms"] for r in per)})
     for r in per:
         r["roofline"] = {k: (round(v, 4) if isinstance(v, float) else v) for k, v in roofline_of(r).items()}
+        r["roofline"]["traffic"] = measured_traffic(r["kernel"])
 
     value = flops / ms_step / 1e9
     out = {
