@@ -37,9 +37,17 @@ struct C4Params {
 
 // Persistent workgroups walk a contiguous range of (n, od, 16-row, 32-col) tiles; the input patch of
 // the next tile is fetched into registers while the current one is computed and stored.
+// ONE: Cout == 32, the 9 weight fragments stay in registers for the whole kernel (otherwise they are
+// re-read from L2 for every cout block of every tile, a load latency per tile that nothing hides)
+template <bool ONE>
 __global__ void __launch_bounds__(256, 2) c4_fwd_kernel(C4Params P) {
     __shared__ __attribute__((aligned(16))) char lds[3 * PLANE * 8 + 4 * RH * 2048];
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    bf16x8 wf[9];
+    if (ONE) {
+#pragma unroll
+        for (int q = 0; q < 9; ++q) wf[q] = ((const bf16x8*)P.wpack)[q * 64 + lane];
+    }
     char* stg = lds + 3 * PLANE * 8 + wave * RH * 2048;  // this wave's store staging: RH rows x 32 voxels x 64 B
     const long long t0 = P.tiles * blockIdx.x / P.nwg, t1 = P.tiles * (blockIdx.x + 1) / P.nwg;
 
@@ -101,11 +109,12 @@ __global__ void __launch_bounds__(256, 2) c4_fwd_kernel(C4Params P) {
         const long long row_pitch = (long long)P.Wo * P.Cout;
         uint16_t* ybase = P.y + ((((long long)n * P.Do + od) * P.Ho + oh0) * P.Wo + w0) * P.Cout;
 
-        for (int cb = 0; cb < P.Cout / 32; ++cb) {
-            const bf16x8* wp = (const bf16x8*)(P.wpack + (long long)cb * 9 * 512) + lane;
-            bf16x8 wf[9];
+        for (int cb = 0; cb < (ONE ? 1 : P.Cout / 32); ++cb) {
+            if (!ONE) {
+                const bf16x8* wp = (const bf16x8*)(P.wpack + (long long)cb * 9 * 512) + lane;
 #pragma unroll
-            for (int q = 0; q < 9; ++q) wf[q] = wp[q * 64];
+                for (int q = 0; q < 9; ++q) wf[q] = wp[q * 64];
+            }
             f32x16 acc[RH];
 #pragma unroll
             for (int kd = 0; kd < 3; ++kd)
@@ -202,7 +211,8 @@ int c4_fwd(const Geom& g, const void* x, const void* w, void* y, void* ws, size_
     P.WT = (g.Wo + TW - 1) / TW;
     P.tiles = (long long)g.N * g.Do * P.HT * P.WT;
     P.nwg = (int)(P.tiles < 512 ? P.tiles : 512);
-    c4_fwd_kernel<<<(unsigned)P.nwg, 256, 0, s>>>(P);
+    if (g.Cout == 32) c4_fwd_kernel<true><<<(unsigned)P.nwg, 256, 0, s>>>(P);
+    else c4_fwd_kernel<false><<<(unsigned)P.nwg, 256, 0, s>>>(P);
     return check_launch();
 }
 

@@ -13,8 +13,7 @@
 // tile stay in LDS.  Each wave holds the 8 accumulator blocks (plane E/O x row
 // E/O x column E/O, 32 cin x 32 column pairs each); the 27 taps are spread over
 // them as 8 + 4 + 4 + 4 + 2 + 2 + 2 + 1.  The layer writes 4x the bytes it
-// reads, so it is bound by its stores: lanes exchange halves so that each lane
-// writes the 64 contiguous bytes of one voxel.
+// reads, so it is bound by its stores.
 #include "mi3d_internal.h"
 
 namespace mi3d {
@@ -52,6 +51,38 @@ template <int P> struct Taps {
     static constexpr int side(int cls, int k) { return cls == 0 ? (k == 0 ? 1 : 0) : (P == 1 ? 0 : 1); }
 };
 
+// The 27 taps in issue order: accumulator block (cd, ch, cw), weight tap, source fragment (plane, row,
+// column side).  Blocks have 8, 4, 4, 4, 2, 2, 2, 1 taps; the order interleaves them (most remaining
+// first, never the block just used) so that consecutive MFMAs do not depend on each other.
+template <int P> struct TapList {
+    int blk[27], tap[27], src[27];
+    constexpr TapList() : blk(), tap(), src() {
+        int cnt[8] = {}, tp[8][8] = {}, sr[8][8] = {};
+        for (int cd = 0; cd < 2; ++cd)
+            for (int id = 0; id < Taps<P>::n(cd); ++id)
+                for (int ch = 0; ch < 2; ++ch)
+                    for (int ih = 0; ih < Taps<P>::n(ch); ++ih)
+                        for (int cw = 0; cw < 2; ++cw)
+                            for (int iw = 0; iw < Taps<P>::n(cw); ++iw) {
+                                const int b = cd * 4 + ch * 2 + cw;
+                                tp[b][cnt[b]] = (Taps<P>::tap(cd, id) * 3 + Taps<P>::tap(ch, ih)) * 3 + Taps<P>::tap(cw, iw);
+                                sr[b][cnt[b]] = Taps<P>::side(cd, id) * 4 + Taps<P>::side(ch, ih) * 2 + Taps<P>::side(cw, iw);
+                                ++cnt[b];
+                            }
+        int used[8] = {}, prev = -1;
+        for (int i = 0; i < 27; ++i) {
+            int best = -1;
+            for (int b = 0; b < 8; ++b) {
+                const int rem = cnt[b] - used[b];
+                if (rem > 0 && b != prev && (best < 0 || rem > cnt[best] - used[best])) best = b;
+            }
+            if (best < 0) best = prev;
+            blk[i] = best; tap[i] = tp[best][used[best]]; src[i] = sr[best][used[best]];
+            ++used[best]; prev = best;
+        }
+    }
+};
+
 // fp32 block -> packed bf16; lane (n, h) ends with cins 16h .. 16h + 15 of its voxel in two uint4
 __device__ __forceinline__ void pack_block(const f32x16& a, uint4 (&c)[2]) {
     uint32_t o[8];
@@ -69,13 +100,16 @@ __device__ __forceinline__ void pack_block(const f32x16& a, uint4 (&c)[2]) {
     }
 }
 
-template <int P>
+// KK = Cout / 16 k16 steps.  Every MFMA needs its own 1 KB weight fragment from LDS (a tap is used once
+// per wave and step), so the kernel runs at the LDS rate: the fragment reads are issued two groups of
+// three MFMAs ahead of their use from a ring of three register groups.
+template <int P, int KK>
 __global__ void __launch_bounds__(256, 1) dgrad_s2_kernel(Dg2Params G) {
     extern __shared__ __attribute__((aligned(16))) char lds[];
-    const int KK = G.Cout / 16;                 // k16 steps
-    const int SLABS = G.Cout / 8;
-    const int W_BYTES = 27 * KK * 1024;
-    const int STAGE = SLABS * SLABV * 16;
+    constexpr int SLABS = 2 * KK;
+    constexpr int W_BYTES = 27 * KK * 1024;
+    constexpr int STAGE = SLABS * SLABV * 16;
+    constexpr TapList<P> TL{};
     char* w_lds = lds;
     char* in_lds = lds + W_BYTES;               // two stages, slot = dy plane & 1
 
@@ -156,9 +190,8 @@ __global__ void __launch_bounds__(256, 1) dgrad_s2_kernel(Dg2Params G) {
         const char* w_lane = w_lds + lane * 16;
 
         for (int q = q_start; q < q_end; ++q) {
-            const bool more = q + 1 < q_end;
             const int mA = q + G.p - 1, mB = q + G.p;
-            if (more) load_plane(mB + 1);
+            load_plane(mB + 1);  // unconditional (after the last pair: a plane nobody reads), so that its wait sits at the LDS write
             const char* plane_base[2] = {in_lds + (mA & 1) * STAGE + lane_in, in_lds + (mB & 1) * STAGE + lane_in};
 
             f32x16 acc[2][2][2];
@@ -171,33 +204,32 @@ __global__ void __launch_bounds__(256, 1) dgrad_s2_kernel(Dg2Params G) {
 #pragma unroll
                         for (int i = 0; i < 16; ++i) acc[a][b][c][i] = 0.f;
 
-            for (int kk = 0; kk < KK; ++kk) {
-                bf16x8 xb[2][2][2];  // [plane side][row side][column side]
+            // fragment reads: x of k16 step kk (8 fragments: plane side, row side, column side), weights of MFMA m
+            bf16x8 xb[2][8], wq[3][3];
+            auto load_x = [&](int kk, int f) {
+                xb[kk & 1][f] = *(const bf16x8*)(plane_base[f >> 2] + (2 * kk * SLABV + ((f >> 1) & 1) * PITCH + (f & 1)) * 16);
+            };
+            auto load_wgroup = [&](int gi) {  // group gi = 3 MFMAs: k16 step gi / 9, list positions 3 (gi % 9) ..
 #pragma unroll
-                for (int ps = 0; ps < 2; ++ps)
+                for (int j = 0; j < 3; ++j)
+                    wq[gi % 3][j] = *(const bf16x8*)(w_lane + (TL.tap[3 * (gi % 9) + j] * KK + gi / 9) * 1024);
+            };
 #pragma unroll
-                    for (int rs = 0; rs < 2; ++rs)
+            for (int f = 0; f < 8; ++f) load_x(0, f);
+            load_wgroup(0);
+            load_wgroup(1);
 #pragma unroll
-                        for (int cs = 0; cs < 2; ++cs)
-                            xb[ps][rs][cs] = *(const bf16x8*)(plane_base[ps] + (2 * kk * SLABV + rs * PITCH + cs) * 16);
-                const char* wk = w_lane + kk * 1024;
+            for (int gi = 0; gi < 9 * KK; ++gi) {
+                const int kk = gi / 9, grp = gi % 9;
+                if (gi + 2 < 9 * KK) load_wgroup(gi + 2);
+                if (kk + 1 < KK && grp < 8) load_x(kk + 1, grp);
 #pragma unroll
-                for (int cd = 0; cd < 2; ++cd)
-#pragma unroll
-                    for (int id = 0; id < Taps<P>::n(cd); ++id)
-#pragma unroll
-                        for (int ch = 0; ch < 2; ++ch)
-#pragma unroll
-                            for (int ih = 0; ih < Taps<P>::n(ch); ++ih)
-#pragma unroll
-                                for (int cw = 0; cw < 2; ++cw)
-#pragma unroll
-                                    for (int iw = 0; iw < Taps<P>::n(cw); ++iw) {
-                                        const int tap = (Taps<P>::tap(cd, id) * 3 + Taps<P>::tap(ch, ih)) * 3 + Taps<P>::tap(cw, iw);
-                                        const bf16x8 wf = *(const bf16x8*)(wk + tap * KK * 1024);
-                                        acc[cd][ch][cw] = mfma(wf, xb[Taps<P>::side(cd, id)][Taps<P>::side(ch, ih)][Taps<P>::side(cw, iw)],
-                                                               acc[cd][ch][cw]);
-                                    }
+                for (int j = 0; j < 3; ++j) {
+                    const int i = 3 * grp + j;
+                    f32x16& a = acc[TL.blk[i] >> 2][(TL.blk[i] >> 1) & 1][TL.blk[i] & 1];
+                    a = mfma(wq[gi % 3][j], xb[kk & 1][TL.src[i]], a);
+                }
+                __builtin_amdgcn_sched_barrier(0);
             }
 
             // stores: dx position of class e on an axis is 2 c + (e == 0 ? p : 1 - p)
@@ -215,30 +247,26 @@ __global__ void __launch_bounds__(256, 1) dgrad_s2_kernel(Dg2Params G) {
                     // even column = E if p == 0 else O
                     uint4 (&ev)[2] = (P == 0) ? be : bo;
                     uint4 (&od)[2] = (P == 0) ? bo : be;
-                    // lower lanes keep the even voxel and fetch its upper 16 cins; upper lanes keep the odd voxel
-                    uint4 first[2], second[2];
-#pragma unroll
-                    for (int k = 0; k < 2; ++k) {
-                        u32x2 a0 = __builtin_amdgcn_permlane32_swap(ev[k].x, od[k].x, false, false);
-                        u32x2 a1 = __builtin_amdgcn_permlane32_swap(ev[k].y, od[k].y, false, false);
-                        u32x2 a2 = __builtin_amdgcn_permlane32_swap(ev[k].z, od[k].z, false, false);
-                        u32x2 a3 = __builtin_amdgcn_permlane32_swap(ev[k].w, od[k].w, false, false);
-                        first[k] = uint4{a0[0], a1[0], a2[0], a3[0]};
-                        second[k] = uint4{a0[1], a1[1], a2[1], a3[1]};
-                    }
-                    const int iw_ = 2 * cq + (lane >> 5);
-                    if (id_ < G.D && ih_ < G.H && iw_ < G.W) {
-                        uint16_t* ptr = dxn + (((long long)id_ * G.H + ih_) * G.W + iw_) * G.Cin + cit * 32;
-                        *(uint4*)(ptr) = first[0];
-                        *(uint4*)(ptr + 8) = first[1];
-                        *(uint4*)(ptr + 16) = second[0];
-                        *(uint4*)(ptr + 24) = second[1];
+                    // lane (n, h) writes cins 16 h .. 16 h + 15 of the even and of the odd voxel of its column
+                    // pair: per store instruction the two lane halves fill 32 of a voxel's 64 bytes (measured:
+                    // 5.9 TB/s; giving each lane a whole 64-byte voxel in four 16-byte stores reaches 3.6 TB/s)
+                    const int iw_ = 2 * cq;
+                    if (id_ < G.D && ih_ < G.H) {
+                        uint16_t* ptr = dxn + (((long long)id_ * G.H + ih_) * G.W + iw_) * G.Cin + cit * 32 + 16 * (lane >> 5);
+                        if (iw_ < G.W) {
+                            *(uint4*)(ptr) = ev[0];
+                            *(uint4*)(ptr + 8) = ev[1];
+                        }
+                        if (iw_ + 1 < G.W) {
+                            *(uint4*)(ptr + G.Cin) = od[0];
+                            *(uint4*)(ptr + G.Cin + 8) = od[1];
+                        }
                     }
                 }
             }
 
             __syncthreads();              // everyone is done reading plane A
-            if (more) write_plane((mB + 1) & 1);
+            write_plane((mB + 1) & 1);
             __syncthreads();
         }
     }
@@ -295,13 +323,17 @@ int dgrad_s2(const Geom& g, const void* dy, const void* w, void* dx, void* ws, s
     static bool attr_set = false;
     if (!attr_set) {
         const int max_lds = 27 * 4 * 1024 + 2 * 8 * SLABV * 16;
-        hipError_t e = hipFuncSetAttribute((const void*)dgrad_s2_kernel<0>, hipFuncAttributeMaxDynamicSharedMemorySize, max_lds);
-        if (e == hipSuccess) e = hipFuncSetAttribute((const void*)dgrad_s2_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize, max_lds);
+        hipError_t e = hipFuncSetAttribute((const void*)dgrad_s2_kernel<0, 2>, hipFuncAttributeMaxDynamicSharedMemorySize, max_lds);
+        if (e == hipSuccess) e = hipFuncSetAttribute((const void*)dgrad_s2_kernel<1, 2>, hipFuncAttributeMaxDynamicSharedMemorySize, max_lds);
+        if (e == hipSuccess) e = hipFuncSetAttribute((const void*)dgrad_s2_kernel<0, 4>, hipFuncAttributeMaxDynamicSharedMemorySize, max_lds);
+        if (e == hipSuccess) e = hipFuncSetAttribute((const void*)dgrad_s2_kernel<1, 4>, hipFuncAttributeMaxDynamicSharedMemorySize, max_lds);
         if (e != hipSuccess) { note_hip_error(e); return MI3D_ERR_HIP; }
         attr_set = true;
     }
-    if (g.pD == 0) dgrad_s2_kernel<0><<<(unsigned)nwg, 256, lds, s>>>(G);
-    else dgrad_s2_kernel<1><<<(unsigned)nwg, 256, lds, s>>>(G);
+    if (g.pD == 0 && g.Cout == 32) dgrad_s2_kernel<0, 2><<<(unsigned)nwg, 256, lds, s>>>(G);
+    else if (g.pD == 0) dgrad_s2_kernel<0, 4><<<(unsigned)nwg, 256, lds, s>>>(G);
+    else if (g.Cout == 32) dgrad_s2_kernel<1, 2><<<(unsigned)nwg, 256, lds, s>>>(G);
+    else dgrad_s2_kernel<1, 4><<<(unsigned)nwg, 256, lds, s>>>(G);
     return check_launch();
 }
 
