@@ -22,20 +22,16 @@ typedef __attribute__((__vector_size__(2 * sizeof(float)))) float f32x2;
 typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
 
 constexpr int TH = 4, TW = 32, RH = 2;
-constexpr int PR = 2 * TH + 1, PC = 2 * TW + 1;   // staged patch: 9 rows x 65 columns
+constexpr int PC = 2 * TW + 1;                    // staged columns: 65
 constexpr int HALF = 33, PITCH = 2 * HALF;        // row pitch in voxels: even columns, then odd columns
-constexpr int SLAB = PR * PITCH;                  // voxels per 8-channel slab
-constexpr int STAGE_BYTES = 4 * SLAB * 16;
 constexpr int WB_BYTES = 27 * 2 * 1024;           // packed weights of one 32-wide cout block
-constexpr int NPIECE = PR * PC * 4;
-constexpr int NLOAD = (NPIECE + 255) / 256;       // 10
 
 struct S2Params {
     const uint16_t* x;
     const uint16_t* wpack;  // [cout block][kw][kd][kh][k16][lane][8]
     uint16_t* y;
     int N, D, H, W, Cout, Do, Ho, Wo, pD, pH, pW;
-    int HT, WT, CT, CB;     // tiles per plane, cout tiles, cout blocks per tile (1 or 2)
+    int HT, WT, CT;         // tiles per plane, cout tiles
     long long units;
     int nwg;
 };
@@ -48,37 +44,49 @@ __device__ __forceinline__ f32x16 mfma(bf16x8 a, bf16x8 b, f32x16 c) {
 // accumulator set of output plane m (counted from the segment start) is m % 2.
 //   even step (ip + pD even): kd 2 finishes plane m - 1 (set 1 - S), kd 0 starts plane m (set S)
 //   odd step: kd 1 continues plane m (set S)
-template <int S, bool EVEN>
-__device__ __forceinline__ void plane_compute(f32x16 (&acc)[2][RH], const char* in_lane, const char* w_lane) {
+// The six (kw, k16) positions are software-pipelined: the LDS reads of position
+// pos + 1 (5 input rows, 6 or 3 weight fragments) are issued before the MFMAs of
+// position pos, between scheduling fences; left to itself the compiler emits
+// read -> wait -> two MFMAs.  hook(pos) is called once per position: the caller
+// spreads its global loads over the step with it.
+template <int S, bool EVEN, int SLAB, class Hook>
+__device__ __forceinline__ void plane_compute(f32x16 (&acc)[2][RH], const char* in_lane, const char* w_lane, Hook&& hook) {
+    constexpr int NKD = EVEN ? 2 : 1;
+    bf16x8 xr[2][2 * RH + 1], wf[2][NKD * 3];
+    auto load_pos = [&](int pos, int buf) {
+        const int kw = pos >> 1, kk = pos & 1;
 #pragma unroll
-    for (int kw = 0; kw < 3; ++kw) {
+        for (int r = 0; r < 2 * RH + 1; ++r)
+            xr[buf][r] = *(const bf16x8*)(in_lane + (2 * kk * SLAB + r * PITCH + (kw & 1) * HALF + (kw >> 1)) * 16);
 #pragma unroll
-        for (int kk = 0; kk < 2; ++kk) {
-            bf16x8 xr[2 * RH + 1];
+        for (int a = 0; a < NKD; ++a) {
+            const int kd = EVEN ? (a == 0 ? 2 : 0) : 1;
 #pragma unroll
-            for (int r = 0; r < 2 * RH + 1; ++r)
-                xr[r] = *(const bf16x8*)(in_lane + (2 * kk * SLAB + r * PITCH + (kw & 1) * HALF + (kw >> 1)) * 16);
+            for (int kh = 0; kh < 3; ++kh) wf[buf][a * 3 + kh] = *(const bf16x8*)(w_lane + (((kw * 3 + kd) * 3 + kh) * 2 + kk) * 1024);
+        }
+    };
+    load_pos(0, 0);
 #pragma unroll
-            for (int kdi = 0; kdi < 3; ++kdi) {
-                constexpr int dummy = 0; (void)dummy;
-                const int kd = 2 - kdi;
-                if (EVEN ? (kd == 1) : (kd != 1)) continue;
+    for (int pos = 0; pos < 6; ++pos) {
+        if (pos + 1 < 6) load_pos(pos + 1, (pos + 1) & 1);
+#pragma unroll
+        for (int kh = 0; kh < 3; ++kh)
+#pragma unroll
+            for (int a = 0; a < NKD; ++a) {
+                const int kd = EVEN ? (a == 0 ? 2 : 0) : 1;
                 const int set = (kd == 2) ? 1 - S : S;
 #pragma unroll
-                for (int kh = 0; kh < 3; ++kh) {
-                    bf16x8 wf = *(const bf16x8*)(w_lane + (((kw * 3 + kd) * 3 + kh) * 2 + kk) * 1024);
-#pragma unroll
-                    for (int r = 0; r < RH; ++r) {
-                        if (kd == 0 && kw == 0 && kk == 0 && kh == 0) {
-                            f32x16 z = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-                            acc[set][r] = mfma(wf, xr[2 * r + kh], z);
-                        } else {
-                            acc[set][r] = mfma(wf, xr[2 * r + kh], acc[set][r]);
-                        }
+                for (int r = 0; r < RH; ++r) {
+                    if (kd == 0 && pos == 0 && kh == 0) {
+                        f32x16 z = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+                        acc[set][r] = mfma(wf[pos & 1][a * 3 + kh], xr[pos & 1][2 * r + kh], z);
+                    } else {
+                        acc[set][r] = mfma(wf[pos & 1][a * 3 + kh], xr[pos & 1][2 * r + kh], acc[set][r]);
                     }
                 }
             }
-        }
+        hook(pos);
+        __builtin_amdgcn_sched_barrier(0);
     }
 }
 
@@ -107,23 +115,41 @@ __device__ __forceinline__ void store_rows(const f32x16 (&a)[RH], uint16_t* p, l
     }
 }
 
+// CB = 2 (Cout % 64 == 0): a tile is 4 output rows x 2 cout blocks; waves 0,1 serve block 0 and waves
+// 2,3 block 1, two rows each; the staged patch has 9 rows.  CB = 1: 8 output rows x 1 cout block, one
+// wave per row pair, 17 staged rows.  The layer is bound by HBM reads and one workgroup per CU holds
+// only one plane patch in LDS, so the global loads run two planes ahead of the MFMAs through two
+// register sets (plane tq + 2 is requested during step tq and written to LDS at the end of step
+// tq + 1): with one plane of lookahead the load latency (about 2 us under load) was exposed in every step.
+template <int CB>
 __global__ void __launch_bounds__(256, 1) s2_fwd_kernel(S2Params P) {
     extern __shared__ __attribute__((aligned(16))) char lds[];
+    constexpr int TROWS = CB == 2 ? TH : 2 * TH;      // output rows per workgroup
+    constexpr int PR = 2 * TROWS + 1;                 // staged rows
+    constexpr int SLAB = PR * PITCH;                  // voxels per 8-channel slab
+    constexpr int NPIECE = PR * PC * 4;
+    constexpr int NLOAD = (NPIECE + 255) / 256;       // 10 or 18
+    constexpr int PER_HOOK = (NLOAD + 5) / 6;
     char* w_lds = lds;
-    char* in_lds = lds + P.CB * WB_BYTES;
+    char* in_lds = lds + CB * WB_BYTES;
 
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
-    // CB = 2: waves 0,1 serve cout block 0 and waves 2,3 block 1, two rows each.
-    // CB = 1: all four waves serve the one block; the patch then has 8 output rows.
-    const int cb = P.CB == 2 ? (wave >> 1) : 0;
-    const int rowgrp = P.CB == 2 ? (wave & 1) : wave;
-    const int th = P.CB == 2 ? TH : 2 * TH;          // output rows per workgroup
+    const int cb = CB == 2 ? (wave >> 1) : 0;
+    const int rowgrp = CB == 2 ? (wave & 1) : wave;
 
     int g = blockIdx.x;
     if ((P.nwg & 7) == 0) g = (g & 7) * (P.nwg >> 3) + (g >> 3);
     long long u0 = P.units * g / P.nwg, u1 = P.units * (g + 1) / P.nwg;
 
     f32x16 acc[2][RH];
+    int lds_off[NLOAD];
+#pragma unroll
+    for (int i = 0; i < NLOAD; ++i) {
+        const int q = t + 256 * i;
+        const int v = q >> 2, c = q & 3;
+        const int row = (v * 1009) >> 16, col = v - row * PC;  // v / 65 for v < 1200
+        lds_off[i] = (c * SLAB + row * PITCH + (col & 1) * HALF + (col >> 1)) * 16;
+    }
 
     int cur_ct = -1;
     while (u0 < u1) {
@@ -136,65 +162,54 @@ __global__ void __launch_bounds__(256, 1) s2_fwd_kernel(S2Params P) {
         const int ht = (int)(column % P.HT); column /= P.HT;
         const int ct = (int)(column % P.CT);
         const int n = (int)(column / P.CT);
-        const int h0 = ht * th, w0 = wt * TW;
+        const int h0 = ht * TROWS, w0 = wt * TW;
 
+        __syncthreads();   // previous segment's readers are done with the weights and the stage
         if (ct != cur_ct) {
-            const uint4* src = (const uint4*)(P.wpack + (long long)ct * P.CB * (WB_BYTES / 2));
-            for (int i = t; i < P.CB * WB_BYTES / 16; i += 256) ((uint4*)w_lds)[i] = src[i];
+            const uint4* src = (const uint4*)(P.wpack + (long long)ct * CB * (WB_BYTES / 2));
+            for (int i = t; i < CB * WB_BYTES / 16; i += 256) ((uint4*)w_lds)[i] = src[i];
             cur_ct = ct;
         }
-        // Load plan.  The patch is staged as NG row groups of 9 rows (rows 4 g .. 4 g + 8 of the
-        // patch, i.e. the rows the 4 output rows 4 g .. 4 g + 3 need); with two groups the shared
-        // row is stored twice.  Piece q of a group: channels 8c..8c+7 of voxel q / 4 (row-major 9 x 65).
-        const int ng = P.CB == 2 ? 1 : 2;
-        int goff[2][NLOAD];
-        unsigned valid[2] = {0, 0};
-        int lds_off[NLOAD];
+        // load plan: piece q = channels 8c..8c+7 of voxel q / 4 (row-major PR x 65)
+        int goff[NLOAD];
+        unsigned valid = 0;
 #pragma unroll
         for (int i = 0; i < NLOAD; ++i) {
             const int q = t + 256 * i;
             const int v = q >> 2, c = q & 3;
-            const int row = (v * 1009) >> 16, col = v - row * PC;  // v / 65
-            lds_off[i] = (c * SLAB + row * PITCH + (col & 1) * HALF + (col >> 1)) * 16;
-#pragma unroll
-            for (int gi = 0; gi < 2; ++gi) {
-                const int gh = 2 * (h0 + gi * TH) - P.pH + row, gw = 2 * w0 - P.pW + col;
-                const bool ok = gi < ng && q < NPIECE && gh >= 0 && gh < P.H && gw >= 0 && gw < P.W;
-                goff[gi][i] = ok ? (gh * P.W + gw) * 32 + c * 8 : 0;
-                valid[gi] |= (ok ? 1u : 0u) << i;
-            }
+            const int row = (v * 1009) >> 16, col = v - row * PC;
+            const int gh = 2 * h0 - P.pH + row, gw = 2 * w0 - P.pW + col;
+            const bool ok = q < NPIECE && gh >= 0 && gh < P.H && gw >= 0 && gw < P.W;
+            goff[i] = ok ? (gh * P.W + gw) * 32 + c * 8 : 0;
+            valid |= (ok ? 1u : 0u) << i;
         }
         const long long plane_elems = (long long)P.H * P.W * 32;
         const uint16_t* xn = P.x + (long long)n * P.D * plane_elems;
         uint16_t* yn = P.y + (long long)n * P.Do * P.Ho * P.Wo * P.Cout;
         const int nP = od_end - od_start;
-        const int nT = 2 * nP + 1;     // staged planes tp' = 0 .. 2 nP, input plane ip = 2 od_start - pD + tp'
+        const int nT = 2 * nP + 1;     // staged planes tq = 0 .. 2 nP, input plane ip = 2 od_start - pD + tq
+        const int ip0 = 2 * od_start - P.pD;
 
+        // two register sets; loads are unconditional (a plane outside the volume or past the segment
+        // reads plane 0 and is zeroed / ignored), so that their waits sit at the LDS writes
         uint4 pre[2][NLOAD];
-        bool pre_in = false;
-        auto load_plane = [&](int ip) {
-            pre_in = ip >= 0 && ip < P.D;
-            const uint16_t* base = xn + (long long)(pre_in ? ip : 0) * plane_elems;
-#pragma unroll
-            for (int gi = 0; gi < 2; ++gi)
-                if (gi < ng) {
-#pragma unroll
-                    for (int i = 0; i < NLOAD; ++i) pre[gi][i] = *(const uint4*)(base + goff[gi][i]);
-                }
+        unsigned pre_mask[2] = {0u, 0u};
+        const uint16_t* pre_base[2] = {xn, xn};
+        auto begin_load = [&](int set, int ip) {
+            const bool in = ip >= 0 && ip < P.D;
+            pre_base[set] = xn + (long long)(in ? ip : 0) * plane_elems;
+            pre_mask[set] = in ? valid : 0u;
         };
-        auto write_plane = [&]() {
+        auto load_piece = [&](int set, int i) { pre[set][i] = *(const uint4*)(pre_base[set] + goff[i]); };
+        auto write_plane = [&](int set) {
 #pragma unroll
-            for (int gi = 0; gi < 2; ++gi)
-                if (gi < ng) {
-#pragma unroll
-                    for (int i = 0; i < NLOAD; ++i) {
-                        const bool ok = pre_in && ((valid[gi] >> i) & 1);
-                        uint4 v;
-                        v.x = ok ? pre[gi][i].x : 0u; v.y = ok ? pre[gi][i].y : 0u;
-                        v.z = ok ? pre[gi][i].z : 0u; v.w = ok ? pre[gi][i].w : 0u;
-                        if (t + 256 * i < NPIECE) *(uint4*)(in_lds + gi * STAGE_BYTES + lds_off[i]) = v;
-                    }
-                }
+            for (int i = 0; i < NLOAD; ++i) {
+                const bool ok = (pre_mask[set] >> i) & 1;
+                uint4 v;
+                v.x = ok ? pre[set][i].x : 0u; v.y = ok ? pre[set][i].y : 0u;
+                v.z = ok ? pre[set][i].z : 0u; v.w = ok ? pre[set][i].w : 0u;
+                if (t + 256 * i < NPIECE) *(uint4*)(in_lds + lds_off[i]) = v;
+            }
         };
 
 #pragma unroll
@@ -204,34 +219,40 @@ __global__ void __launch_bounds__(256, 1) s2_fwd_kernel(S2Params P) {
 #pragma unroll
                 for (int i = 0; i < 16; ++i) acc[s][r][i] = 0.f;
 
-        __syncthreads();   // previous segment's readers are done with the stage
-        load_plane(2 * od_start - P.pD);
-        write_plane();
+        begin_load(0, ip0);
+#pragma unroll
+        for (int i = 0; i < NLOAD; ++i) load_piece(0, i);
+        begin_load(1, ip0 + 1);
+#pragma unroll
+        for (int i = 0; i < NLOAD; ++i) load_piece(1, i);
+        write_plane(0);
         __syncthreads();
 
-        // this wave: row group (2 rows) within a 9-row staging group, cout block cb
-        const int sg = rowgrp >> 1;            // staging group (0 unless CB == 1 and waves 2,3)
-        const int r0 = (rowgrp & 1) * RH;      // first output row within the group
-        const char* in_lane = in_lds + sg * STAGE_BYTES + ((lane >> 5) * SLAB + 2 * r0 * PITCH + (lane & 31)) * 16;
+        const int r0 = rowgrp * RH;            // first output row of this wave within the tile
+        const char* in_lane = in_lds + ((lane >> 5) * SLAB + 2 * r0 * PITCH + (lane & 31)) * 16;
         const char* w_lane = w_lds + cb * WB_BYTES + lane * 16;
-        const int oh0 = h0 + sg * TH + r0;
+        const int oh0 = h0 + r0;
         const int ow = w0 + (lane & 31);
         const long long row_pitch = (long long)P.Wo * P.Cout;
-        const int co0 = (ct * P.CB + cb) * 32 + 16 * (lane >> 5);
+        const int co0 = (ct * CB + cb) * 32 + 16 * (lane >> 5);
 
-        // step tq stages plane tp' = tq.  tq even = 2 m': finishes output plane m' - 1, starts m'.
+        // step tq computes staged plane tq (register set tq & 1 is free again: it is refilled with plane
+        // tq + 2), then writes plane tq + 1 from the other set.  tq even = 2 m: finishes output plane m - 1.
 #define S2_STEP(SET, EVEN)                                                                       \
         {                                                                                        \
-            const bool more_ = tq + 1 < nT;                                                      \
-            if (more_) load_plane(2 * od_start - P.pD + tq + 1);                                 \
-            plane_compute<SET, EVEN>(acc, in_lane, w_lane);                                      \
+            constexpr int rs_ = (EVEN) ? 0 : 1;                                                  \
+            begin_load(rs_, ip0 + tq + 2);                                                       \
+            plane_compute<SET, EVEN, SLAB>(acc, in_lane, w_lane, [&](int pos) {                  \
+                _Pragma("unroll") for (int i_ = 0; i_ < PER_HOOK; ++i_)                          \
+                    if (pos * PER_HOOK + i_ < NLOAD) load_piece(rs_, pos * PER_HOOK + i_);       \
+            });                                                                                  \
             if ((EVEN) && tq >= 2) {                                                             \
                 const int od_ = od_start + (tq >> 1) - 1;                                        \
                 store_rows(acc[1 - (SET)], yn + ((long long)od_ * P.Ho + oh0) * row_pitch + (long long)ow * P.Cout + co0, \
                            row_pitch, ow < P.Wo, P.Ho - oh0);                                    \
             }                                                                                    \
             __syncthreads();                                                                     \
-            if (more_) write_plane();                                                            \
+            write_plane(1 - rs_);                                                                \
             __syncthreads();                                                                     \
         }
         for (int tq = 0;;) {
@@ -287,9 +308,9 @@ int s2_fwd(const Geom& g, const void* x, const void* w, void* y, void* ws, size_
     P.x = (const uint16_t*)x; P.wpack = (const uint16_t*)ws; P.y = (uint16_t*)y;
     P.N = g.N; P.D = g.D; P.H = g.H; P.W = g.W; P.Cout = g.Cout;
     P.Do = g.Do; P.Ho = g.Ho; P.Wo = g.Wo; P.pD = g.pD; P.pH = g.pH; P.pW = g.pW;
-    P.CB = (g.Cout % 64 == 0) ? 2 : 1;
-    P.CT = g.Cout / (32 * P.CB);
-    const int th = P.CB == 2 ? TH : 2 * TH;
+    const int CB = (g.Cout % 64 == 0) ? 2 : 1;
+    P.CT = g.Cout / (32 * CB);
+    const int th = CB == 2 ? TH : 2 * TH;
     P.HT = (g.Ho + th - 1) / th;
     P.WT = (g.Wo + TW - 1) / TW;
     P.units = (long long)g.N * P.CT * P.HT * P.WT * g.Do;
@@ -297,14 +318,16 @@ int s2_fwd(const Geom& g, const void* x, const void* w, void* y, void* ws, size_
     if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
     long long nwg = cus < P.units ? cus : P.units;
     P.nwg = (int)nwg;
-    const size_t lds = (size_t)P.CB * WB_BYTES + (P.CB == 2 ? 1 : 2) * STAGE_BYTES;
+    const size_t lds2 = 2 * WB_BYTES + 4 * (2 * TH + 1) * PITCH * 16, lds1 = WB_BYTES + 4 * (4 * TH + 1) * PITCH * 16;
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void*)s2_fwd_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 2 * WB_BYTES + STAGE_BYTES);
+        hipError_t e = hipFuncSetAttribute((const void*)s2_fwd_kernel<2>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds2);
+        if (e == hipSuccess) e = hipFuncSetAttribute((const void*)s2_fwd_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds1);
         if (e != hipSuccess) { note_hip_error(e); return MI3D_ERR_HIP; }
         attr_set = true;
     }
-    s2_fwd_kernel<<<(unsigned)nwg, 256, lds, s>>>(P);
+    if (CB == 2) s2_fwd_kernel<2><<<(unsigned)nwg, 256, lds2, s>>>(P);
+    else s2_fwd_kernel<1><<<(unsigned)nwg, 256, lds1, s>>>(P);
     return check_launch();
 }
 

@@ -56,6 +56,8 @@ MID = [
     (1, 9, 17, 33, 32, 32, 3, 1, 1),
     (1, 8, 16, 32, 64, 32, 3, 1, 1),
     (1, 12, 14, 34, 32, 64, 3, 2, 1),
+    (1, 9, 21, 37, 32, 32, 3, 2, 1),
+    (1, 8, 10, 12, 32, 96, 3, 2, 0),
     (1, 7, 9, 20, 64, 64, 3, 1, 1),
     (1, 6, 6, 12, 128, 64, 3, 1, 1),
     (1, 12, 12, 12, 64, 128, 3, 2, 1),
