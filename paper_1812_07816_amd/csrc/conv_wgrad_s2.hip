@@ -6,8 +6,8 @@
 // 16x16 quadrant per wave, deterministic slot reduction), with the index maps
 // of stride 2: x plane id meets dy plane od through tap kd only when
 // id + pD = 2 od + kd, so planes with even id + pD serve taps 0 and 2 and odd
-// ones tap 1; the same holds for rows (kh).  The staged x patch (17 x 65
-// voxels for 8 x 32 dy voxels) is split by column parity so that the voxels
+// ones tap 1; the same holds for rows (kh).  The staged x patch (9 x 65
+// voxels for 4 x 32 dy voxels) is split by column parity so that the voxels
 // 2 j + kw of a fragment are contiguous in LDS.
 #include "mi3d_internal.h"
 
@@ -19,16 +19,16 @@ typedef __attribute__((__vector_size__(8 * sizeof(short)))) short s16x8;
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
 
-constexpr int TH = 8, TW = 32;
-constexpr int XR = 2 * TH + 1, XC = 2 * TW + 1;  // 17 x 65
+constexpr int TH = 4, TW = 32;
+constexpr int XR = 2 * TH + 1, XC = 2 * TW + 1;  // 9 x 65
 constexpr int XHALF = 33, XPITCH = 2 * XHALF;    // even columns, then odd columns
 constexpr int X_SLAB = XR * XPITCH * 32;
 constexpr int X_BYTES = 2 * X_SLAB;
 constexpr int DY_SLAB = TH * TW * 32;
 constexpr int DY_BYTES = 2 * DY_SLAB;
 constexpr int XPIECES = XR * XC * 4;
-constexpr int NX = (XPIECES + 255) / 256;        // 18
-constexpr int NDY = TH * TW * 4 / 256;           // 4
+constexpr int NX = (XPIECES + 255) / 256;        // 10
+constexpr int NDY = TH * TW * 4 / 256;           // 2
 
 struct Wg2Params {
     const uint16_t* x;
@@ -60,11 +60,19 @@ __device__ __forceinline__ void plane_step(f32x4 (&acc)[3][3][3], const char* x_
     bf16x8 dyw[NKD][3];  // window over dy rows, slot = dr % 3
 #pragma unroll
     for (int k = 0; k < NKD; ++k) dyw[k][0] = tr_frag(dy_lane[k]);
+    // x fragments are read three rows ahead of their use (ring of four); left to the compiler every row is
+    // read -> wait -> MFMAs, and with 3 to 12 MFMAs per row two rows do not cover the LDS latency
+    constexpr int AH = 3;
+    bf16x8 xf[AH + 1][3];
+    auto load_xrow = [&](int R) {
+#pragma unroll
+        for (int kw = 0; kw < 3; ++kw) xf[R % (AH + 1)][kw] = tr_frag(x_lane + (R * XPITCH + (kw & 1) * XHALF + (kw >> 1)) * 32);
+    };
+#pragma unroll
+    for (int R = 0; R < AH; ++R) load_xrow(R);
 #pragma unroll
     for (int R = 0; R < XR; ++R) {
-        bf16x8 xf[3];
-#pragma unroll
-        for (int kw = 0; kw < 3; ++kw) xf[kw] = tr_frag(x_lane + (R * XPITCH + (kw & 1) * XHALF + (kw >> 1)) * 32);
+        if (R + AH < XR) load_xrow(R + AH);
         if ((R & 1) == 0 && R / 2 + 1 < TH) {  // the dy row that the next even x row starts using
 #pragma unroll
             for (int k = 0; k < NKD; ++k) dyw[k][(R / 2 + 1) % 3] = tr_frag(dy_lane[k] + (R / 2 + 1) * TW * 32);
@@ -78,17 +86,18 @@ __device__ __forceinline__ void plane_step(f32x4 (&acc)[3][3][3], const char* x_
             for (int k = 0; k < NKD; ++k) {
                 const int kd = EVEN ? 2 * k : 1;
 #pragma unroll
-                for (int kw = 0; kw < 3; ++kw) acc[kd][kh][kw] = mfma16(dyw[k][dr % 3], xf[kw], acc[kd][kh][kw]);
+                for (int kw = 0; kw < 3; ++kw) acc[kd][kh][kw] = mfma16(dyw[k][dr % 3], xf[R % (AH + 1)][kw], acc[kd][kh][kw]);
             }
         }
         hook(R);
+        __builtin_amdgcn_sched_barrier(0);
     }
 }
 
 __global__ void __launch_bounds__(256, 1) wgrad_s2_kernel(Wg2Params P) {
     extern __shared__ __attribute__((aligned(16))) char lds[];
-    char* x_lds = lds;
-    char* dy_lds = lds + X_BYTES;  // ring of two dy patches, slot = od % 2
+    char* x_lds = lds;                 // two x patches, slot = id % 2
+    char* dy_lds = lds + 2 * X_BYTES;  // ring of two dy patches, slot = od % 2
 
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     const int coh = wave >> 1, cih = wave & 1;
@@ -98,7 +107,20 @@ __global__ void __launch_bounds__(256, 1) wgrad_s2_kernel(Wg2Params P) {
 
     const int g = lane >> 4, s = lane & 15;
     const int lane_off = (4 * g + (s >> 2)) * 32 + (s & 3) * 8;
-    const char* x_lane = x_lds + cih * X_SLAB + lane_off;
+    const int x_lane_off = cih * X_SLAB + lane_off;
+    // LDS offsets of the pieces this thread stages (the same for every tile)
+    int lx[NX], ldy[NDY];
+#pragma unroll
+    for (int i = 0; i < NX; ++i) {
+        const int q = t + 256 * i, v = q >> 2, c = q & 3;
+        const int row = (v * 1009) >> 16, col = v - row * XC;  // v / 65
+        lx[i] = (c >> 1) * X_SLAB + (row * XPITCH + (col & 1) * XHALF + (col >> 1)) * 32 + (c & 1) * 16;
+    }
+#pragma unroll
+    for (int i = 0; i < NDY; ++i) {
+        const int q = t + 256 * i, v = q >> 2, c = q & 3;
+        ldy[i] = (c >> 1) * DY_SLAB + v * 32 + (c & 1) * 16;
+    }
 
     f32x4 acc[3][3][3];
 #pragma unroll
@@ -145,85 +167,116 @@ __global__ void __launch_bounds__(256, 1) wgrad_s2_kernel(Wg2Params P) {
         const uint16_t* xn = P.x + (long long)n * P.D * x_plane;
         const uint16_t* dyn = P.dy + (long long)n * P.Do * dy_plane;
 
-        uint4 px[NX], pdy[NDY];
-        unsigned mx = 0, mdy = 0;
-        const uint16_t *bx = xn, *bdy = dyn;
-        auto begin_x = [&](int id) {
+        // Global loads run two planes ahead of the MFMAs and the LDS writes one plane ahead, both spread
+        // over the rows of the step that is being computed: during step id, piece r of x plane id + 2 is
+        // requested into the register set of its parity, and piece r of plane id + 1 (requested a step
+        // earlier) goes from the other set into the x buffer that step id + 1 will read.  dy plane m + 1 is
+        // requested during the even step 2 m and written during the odd step 2 m + 1 into the ring slot that
+        // only even steps read.  One barrier per step.  (Measured before: with the writes gathered at the
+        // end of the step between two barriers they cost 40 % of the kernel's time.)  Loads and writes are
+        // unconditional; planes outside the volume read plane 0 and are zeroed.
+        uint4 px[2][NX], pdy[NDY];
+        unsigned mx[2] = {0u, 0u}, mdy = 0;
+        const uint16_t* bx[2] = {xn, xn};
+        const uint16_t* bdy = dyn;
+        auto begin_x = [&](int set, int id) {
             const bool in = id >= 0 && id < P.D;
-            bx = xn + (long long)(in ? id : 0) * x_plane;
-            mx = in ? vx : 0u;
+            bx[set] = xn + (long long)(in ? id : 0) * x_plane;
+            mx[set] = in ? vx : 0u;
         };
         auto begin_dy = [&](int od) {
             const bool in = od >= 0 && od < P.Do;
             bdy = dyn + (long long)(in ? od : 0) * dy_plane;
             mdy = in ? vdy : 0u;
         };
-        auto write_x = [&]() {
-#pragma unroll
-            for (int i = 0; i < NX; ++i) {
-                const int q = t + 256 * i, v = q >> 2, c = q & 3;
-                const int row = (v * 1009) >> 16, col = v - row * XC;
-                const bool ok = (mx >> i) & 1;
-                uint4 w;
-                w.x = ok ? px[i].x : 0u; w.y = ok ? px[i].y : 0u; w.z = ok ? px[i].z : 0u; w.w = ok ? px[i].w : 0u;
-                if (q < XPIECES)
-                    *(uint4*)(x_lds + (c >> 1) * X_SLAB + (row * XPITCH + (col & 1) * XHALF + (col >> 1)) * 32 + (c & 1) * 16) = w;
-            }
+        auto write_x_piece = [&](int set, int i, char* dst) {
+            const bool ok = (mx[set] >> i) & 1;
+            uint4 w;
+            w.x = ok ? px[set][i].x : 0u; w.y = ok ? px[set][i].y : 0u; w.z = ok ? px[set][i].z : 0u; w.w = ok ? px[set][i].w : 0u;
+            if (t + 256 * i < XPIECES) *(uint4*)(dst + lx[i]) = w;
         };
-        auto write_dy = [&](int ring) {
-            char* dst = dy_lds + ring * DY_BYTES;
-#pragma unroll
-            for (int i = 0; i < NDY; ++i) {
-                const int q = t + 256 * i, v = q >> 2, c = q & 3;
-                const bool ok = (mdy >> i) & 1;
-                uint4 w;
-                w.x = ok ? pdy[i].x : 0u; w.y = ok ? pdy[i].y : 0u; w.z = ok ? pdy[i].z : 0u; w.w = ok ? pdy[i].w : 0u;
-                *(uint4*)(dst + (c >> 1) * DY_SLAB + v * 32 + (c & 1) * 16) = w;
-            }
+        auto write_dy_piece = [&](int i, char* dst) {
+            const bool ok = (mdy >> i) & 1;
+            uint4 w;
+            w.x = ok ? pdy[i].x : 0u; w.y = ok ? pdy[i].y : 0u; w.z = ok ? pdy[i].z : 0u; w.w = ok ? pdy[i].w : 0u;
+            *(uint4*)(dst + ldy[i]) = w;
         };
         // dy planes an x plane needs: tp = id + pD; even tp: od = tp/2 (kd 0) and tp/2 - 1 (kd 2); odd: (tp-1)/2 (kd 1)
         auto floor_half = [](int v) { return (v - (v & 1)) / 2; };  // floor(v / 2) for negative v too
 
         __syncthreads();
-        begin_x(id_start);
-#pragma unroll
-        for (int i = 0; i < NX; ++i) px[i] = *(const uint4*)(bx + gx[i]);
-        write_x();
-        {
-            const int m = floor_half(id_start + P.pD);
+        const int tp0 = id_start + P.pD;
+        const bool even0 = (tp0 & 1) == 0;
+        {   // first x plane -> LDS (through the set of its parity), second in flight in the other set
+            const int m = floor_half(tp0);
             for (int od = m - 1; od <= m; ++od) {
                 begin_dy(od);
 #pragma unroll
                 for (int i = 0; i < NDY; ++i) pdy[i] = *(const uint4*)(bdy + gdy[i]);
-                write_dy(od & 1);
+#pragma unroll
+                for (int i = 0; i < NDY; ++i) write_dy_piece(i, dy_lds + (od & 1) * DY_BYTES);
+            }
+            begin_dy(m + 1);  // an odd first step writes dy plane m + 1: request it now
+#pragma unroll
+            for (int i = 0; i < NDY; ++i) pdy[i] = *(const uint4*)(bdy + gdy[i]);
+            char* dst = x_lds + (id_start & 1) * X_BYTES;
+            if (even0) {
+                begin_x(0, id_start);
+#pragma unroll
+                for (int i = 0; i < NX; ++i) px[0][i] = *(const uint4*)(bx[0] + gx[i]);
+#pragma unroll
+                for (int i = 0; i < NX; ++i) write_x_piece(0, i, dst);
+                begin_x(1, id_start + 1);
+#pragma unroll
+                for (int i = 0; i < NX; ++i) px[1][i] = *(const uint4*)(bx[1] + gx[i]);
+            } else {
+                begin_x(1, id_start);
+#pragma unroll
+                for (int i = 0; i < NX; ++i) px[1][i] = *(const uint4*)(bx[1] + gx[i]);
+#pragma unroll
+                for (int i = 0; i < NX; ++i) write_x_piece(1, i, dst);
+                begin_x(0, id_start + 1);
+#pragma unroll
+                for (int i = 0; i < NX; ++i) px[0][i] = *(const uint4*)(bx[0] + gx[i]);
             }
         }
         __syncthreads();
 
         for (int id = id_start; id < id_end; ++id) {
-            const bool more = id + 1 < id_end;
             const int tp = id + P.pD;
             const bool even = (tp & 1) == 0;
             const int m = floor_half(tp);
-            begin_x(id + 1);
-            // the next step is even exactly when this one is odd: it then needs dy plane m + 1,
-            // which replaces plane m - 1 in the ring
-            const bool new_dy = more && !even;
-            begin_dy(m + 1);
+            const char* x_lane = x_lds + (id & 1) * X_BYTES + x_lane_off;
+            char* x_next = x_lds + ((id + 1) & 1) * X_BYTES;
             const char* d0 = dy_lds + (m & 1) * DY_BYTES + coh * DY_SLAB + lane_off;
             const char* d1 = dy_lds + ((m - 1) & 1) * DY_BYTES + coh * DY_SLAB + lane_off;
             const char* const dy_lane[2] = {d0, d1};
-            // unconditional x loads and LDS writes: see the stride-1 kernel
-            auto hook = [&](int r) {
-                px[r] = *(const uint4*)(bx + gx[r]);
-                if (r + XR < NX) px[r + XR] = *(const uint4*)(bx + gx[r + XR]);  // 18 pieces over 17 rows
-                if (new_dy && r < NDY) pdy[r] = *(const uint4*)(bdy + gdy[r]);
-            };
-            if (even) plane_step<true>(acc, x_lane, dy_lane, hook);
-            else plane_step<false>(acc, x_lane, dy_lane, hook);
-            __syncthreads();
-            write_x();
-            if (new_dy) write_dy((m + 1) & 1);
+            // hook schedule: loads in rows 0..4 (two pieces each), LDS writes in rows 4..8, so that a piece has
+            // about a step and a half between its request and its write
+            if (even) {
+                // set 0 held this plane: refill it with plane id + 2; set 1 (plane id + 1) goes to LDS
+                begin_x(0, id + 2);
+                begin_dy(m + 1);
+                plane_step<true>(acc, x_lane, dy_lane, [&](int r) {
+#pragma unroll
+                    for (int j = 0; j < 2; ++j) {
+                        if (2 * r + j < NX) px[0][2 * r + j] = *(const uint4*)(bx[0] + gx[2 * r + j]);
+                        if (r >= 4 && 2 * (r - 4) + j < NX) write_x_piece(1, 2 * (r - 4) + j, x_next);
+                    }
+                    if (r < NDY) pdy[r] = *(const uint4*)(bdy + gdy[r]);
+                });
+            } else {
+                char* dy_next = dy_lds + ((m + 1) & 1) * DY_BYTES;
+                begin_x(1, id + 2);
+                plane_step<false>(acc, x_lane, dy_lane, [&](int r) {
+#pragma unroll
+                    for (int j = 0; j < 2; ++j) {
+                        if (2 * r + j < NX) px[1][2 * r + j] = *(const uint4*)(bx[1] + gx[2 * r + j]);
+                        if (r >= 4 && 2 * (r - 4) + j < NX) write_x_piece(0, 2 * (r - 4) + j, x_next);
+                    }
+                    if (r >= XR - NDY) write_dy_piece(r - (XR - NDY), dy_next);  // requested during the previous even step (or before the loop)
+                });
+            }
             __syncthreads();
         }
     }
@@ -282,7 +335,7 @@ int wgrad_s2(const Geom& g, const void* x, const void* dy, float* dw, void* ws, 
     P.slots = wgrad_s2_slots(g);
     const int pairs = P.CiT * P.CoT;
     if (pairs > 65535) return MI3D_ERR_UNSUPPORTED;
-    const size_t lds = X_BYTES + 2 * DY_BYTES;
+    const size_t lds = 2 * X_BYTES + 2 * DY_BYTES;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void*)wgrad_s2_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
