@@ -25,15 +25,18 @@ typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 constexpr int TH = 16, TW = 32, RH = 4;            // output patch per workgroup, rows per wave
 constexpr int IN_ROWS = TH + 2, IN_COLS = TW + 2;  // with halo
 constexpr int COLS = 35;                           // padded row pitch (voxels) in LDS
-constexpr int NV = IN_ROWS * COLS;                 // voxels per 8-channel slab (630: 630 % 8 == 6)
+constexpr int NV = 646;                            // 16-byte positions per 8-channel slab: 18 x 35 = 630 used, room for
+                                                   // ten 64-position loads, slab pitch = 96 bytes mod 256
 constexpr int STAGE_BYTES = 4 * NV * 16;           // 4 slabs of 8 channels, 16 B per voxel
 constexpr int W_BYTES = 27 * 2 * 64 * 16;          // 27 taps x 2 k16 steps x 1 KB fragments
-constexpr int NLOAD = (IN_ROWS * IN_COLS * 4 + 255) / 256;  // 16-byte loads per thread per plane
+constexpr int NLOAD = 10;                          // 16-byte loads per thread per plane
+constexpr unsigned OOB = 0x80000000u;              // buffer offset of a piece that must read as zero
 
 struct SpParams {
     const uint16_t* x;
     const uint16_t* wpack;  // [cout tile][cin chunk][kw][kd][kh][k16][lane][8]
     uint16_t* y;
+    uint16_t* dump;         // 2 KB that masked store lanes write to instead of y
     int N, D, H, W, Cin, Cout, Do, Ho, Wo, pD, pH, pW;
     int HT, WT, CT;         // tiles per plane, cout tiles
     long long units;        // N*CT*HT*WT*Do
@@ -156,7 +159,7 @@ __device__ __forceinline__ void convert_rows(const f32x16 (&a)[RH], uint32_t (&o
 // Lanes l and l+32 hold the two interleaved halves of a voxel's 32 couts
 // (4 couts of every group of 8).  Swapping between the lane halves gives each
 // lane 16 consecutive couts, stored as two 16-byte pieces.
-__device__ __forceinline__ void store_row(const uint32_t (&o)[8], uint16_t* p, bool ok) {
+__device__ __forceinline__ void store_row(const uint32_t (&o)[8], uint16_t* p, bool ok, uint16_t* dump) {
     typedef __attribute__((ext_vector_type(2))) unsigned u32x2;
     uint4 c[2];
 #pragma unroll
@@ -165,10 +168,12 @@ __device__ __forceinline__ void store_row(const uint32_t (&o)[8], uint16_t* p, b
         u32x2 s1 = __builtin_amdgcn_permlane32_swap(o[2 * k + 1], o[2 * k + 5], false, false);
         c[k].x = s0[0]; c[k].y = s1[0]; c[k].z = s0[1]; c[k].w = s1[1];
     }
-    if (ok) {
-        *(uint4*)p = c[0];
-        *(uint4*)(p + 8) = c[1];
-    }
+    // Unconditional stores: lanes outside the tensor (or with nothing pending) write to the dump area.
+    // Behind a branch the compiler cannot count the stores in its vmcnt bookkeeping and makes the next
+    // stage's LDS write wait for vmcnt(0), i.e. for these stores to complete.
+    uint16_t* q = ok ? p : dump;
+    *(uint4*)q = c[0];
+    *(uint4*)(q + 8) = c[1];
 }
 
 // NC = input-channel chunks of 32 (Cin = 32 NC).  NC = 1 and 2: all weight
@@ -197,17 +202,25 @@ __global__ void __launch_bounds__(256, 1) sp_conv_kernel(SpParams P) {
     if ((P.nwg & 7) == 0) g = (g & 7) * (P.nwg >> 3) + (g >> 3);
     long long u0 = P.units * g / P.nwg, u1 = P.units * (g + 1) / P.nwg;
 
-    // per-thread load plan for one plane patch: thread t moves the 16-byte
-    // pieces q = t + 256 i; piece q is channels 8c..8c+7 of voxel q / 4
-    int lds_off[NLOAD];
+    // Staging (double-buffered variants): wave w fills slab w (channels 8w..8w+7 of the chunk) of the next
+    // stage with ten direct-to-LDS buffer loads; load i covers the 64 LDS positions 64 i .. 64 i + 63 of the
+    // slab (position = row * 35 + col), lane l position 64 i + l.  The data never passes through registers:
+    // no ds_write, no wait before it (the LDS write phase at the end of a stage cost about 900 cycles of
+    // 9400), and zero padding comes from the buffer's range check (offset OOB reads as 0).  The NC = 2
+    // variant has one stage buffer only and keeps the register path: piece i of a thread there is channels
+    // 8c..8c+7, c = l / 16, of voxel 16 (4 i + w) + l % 16 of the patch, row-major over 18 x 34.
+    constexpr bool DMA = NC != 2;
+    constexpr int NVOX = IN_ROWS * IN_COLS;
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+    int lds_off[DMA ? 1 : NLOAD];
+    if (!DMA) {
 #pragma unroll
-    for (int i = 0; i < NLOAD; ++i) {
-        int q = t + 256 * i;
-        int v = q >> 2, c = q & 3;
-        int row = (v * 241) >> 13, col = v - row * IN_COLS;  // v / 34 for v < 700
-        lds_off[i] = (c * NV + row * COLS + col) * 16;
+        for (int i = 0; i < NLOAD; ++i) {
+            int v = 16 * (4 * i + wave) + (lane & 15), c = lane >> 4;
+            int row = (v * 241) >> 13, col = v - row * IN_COLS;  // v / 34 for v < 700
+            lds_off[i] = (c * NV + row * COLS + col) * 16;
+        }
     }
-    constexpr int NPIECE = IN_ROWS * IN_COLS * 4;
     f32x16 acc[3][RH];
     const int lane_in_off = ((lane >> 5) * NV + wave * RH * COLS + (lane & 31)) * 16;
     const char* w_lane = w_lds + lane * 16;
@@ -238,39 +251,61 @@ __global__ void __launch_bounds__(256, 1) sp_conv_kernel(SpParams P) {
             for (int i = 0; i < NWL; ++i)
                 if (t + 256 * i < WPIECES) *(uint4*)(w_lds + slot * WSLOT + (t + 256 * i) * 16) = wreg[i];
         };
-        // global offsets (elements) of this patch relative to the plane base
+        // offsets of this thread's pieces relative to the plane base: bytes (DMA) or elements (register path)
         int goff[NLOAD];
         unsigned valid = 0;
 #pragma unroll
         for (int i = 0; i < NLOAD; ++i) {
-            int q = t + 256 * i;
-            int v = q >> 2, c = q & 3;
-            int row = (v * 241) >> 13, col = v - row * IN_COLS;
-            int gh = h0 - P.pH + row, gw = w0 - P.pW + col;
-            bool ok = q < NPIECE && gh >= 0 && gh < P.H && gw >= 0 && gw < P.W;
-            goff[i] = ok ? (gh * P.W + gw) * P.Cin + c * 8 : 0;
+            int row, col, c;
+            bool ok;
+            if (DMA) {
+                const int pos = 64 * i + lane;
+                row = (pos * 1873) >> 16; col = pos - row * COLS;  // pos / 35 for pos < 640
+                c = wave;
+                ok = row < IN_ROWS && col < IN_COLS;
+            } else {
+                const int v = 16 * (4 * i + wave) + (lane & 15);
+                row = (v * 241) >> 13; col = v - row * IN_COLS;
+                c = lane >> 4;
+                ok = v < NVOX;
+            }
+            const int gh = h0 - P.pH + row, gw = w0 - P.pW + col;
+            ok = ok && gh >= 0 && gh < P.H && gw >= 0 && gw < P.W;
+            if (DMA) goff[i] = ok ? ((gh * P.W + gw) * P.Cin + c * 8) * 2 : (int)OOB;
+            else goff[i] = ok ? (gh * P.W + gw) * P.Cin + c * 8 : 0;
             valid |= (ok ? 1u : 0u) << i;
         }
         const long long plane_elems = (long long)P.H * P.W * P.Cin;
         const uint16_t* xn = P.x + (long long)n * P.D * plane_elems;
         uint16_t* yn = P.y + (long long)n * P.Do * P.Ho * P.Wo * P.Cout;
         const int nJ = od_end - od_start + 2;
-        uint4 pre[NLOAD];
+        uint4 pre[DMA ? 1 : NLOAD];
 
-        // a plane outside [0, D) is zero padding: stage zeros.  Loads are
-        // unconditional (masked pieces read element 0 of a valid plane) and
-        // zeroed afterwards, so that the piece registers never pass through memory.
+        // A plane outside [0, D) is zero padding.  DMA: its buffer has zero records, so every piece reads 0.
+        // Register path: loads are unconditional (masked pieces read element 0 of a valid plane) and zeroed
+        // afterwards, so that the piece registers never pass through memory.
         unsigned pre_mask = 0;
         const uint16_t* pre_base = xn;
+        __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)xn, 0, 0, 0x00020000);
         auto begin_stage = [&](int ip, int chunk) {
             const bool inside = ip >= 0 && ip < P.D;
             pre_base = xn + (long long)(inside ? ip : 0) * plane_elems + chunk * 32;
             pre_mask = inside ? valid : 0u;
+            if (DMA) rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)pre_base, 0, inside ? (int)(plane_elems * 2) - chunk * 64 : 0, 0x00020000);
         };
-        auto load_piece = [&](int i) { pre[i] = *(const uint4*)(pre_base + goff[i]); };
-        // the zeroing of masked pieces happens here, after the MFMA work, so
+        // DMA: piece i of the stage begun last goes to stage buffer buf
+        auto load_piece = [&](int i, int buf) {
+            if (DMA) {
+                typedef __attribute__((address_space(3))) void* lds_ptr;
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_ptr)(in_lds + buf * STAGE_BYTES + (wave_u * NV + 64 * i) * 16), 16, goff[i], 0, 0, 0);
+            } else {
+                pre[i] = *(const uint4*)(pre_base + goff[i]);
+            }
+        };
+        // register path only; the zeroing of masked pieces happens here, after the MFMA work, so
         // that nothing waits for the global loads before the compute starts
         auto write_stage = [&](int buf) {
+            if (DMA) return;
             char* dst = in_lds + buf * STAGE_BYTES;
 #pragma unroll
             for (int i = 0; i < NLOAD; ++i) {
@@ -280,17 +315,18 @@ __global__ void __launch_bounds__(256, 1) sp_conv_kernel(SpParams P) {
                 v.y = ok ? pre[i].y : 0u;
                 v.z = ok ? pre[i].z : 0u;
                 v.w = ok ? pre[i].w : 0u;
-                if (t + 256 * i < NPIECE) *(uint4*)(dst + lds_off[i]) = v;
+                if (16 * (4 * i + wave) + (lane & 15) < NVOX) *(uint4*)(dst + lds_off[i]) = v;
             }
         };
         // finished rows wait in outp[] and are stored during the next stage
         uint32_t outp[RH][8];
         uint16_t* st_ptr = yn;    // address of row 0 of the pending plane for this lane
+        uint16_t* dump_lane = P.dump + lane * 16;
         bool st_pending = false;
         const int ow_ = w0 + (lane & 31);
         const long long row_pitch = (long long)P.Wo * P.Cout;
         auto store_piece = [&](int r) {
-            store_row(outp[r], st_ptr + r * row_pitch, st_pending && ow_ < P.Wo && h0 + wave * RH + r < P.Ho);
+            store_row(outp[r], st_ptr + r * row_pitch, st_pending && ow_ < P.Wo && h0 + wave * RH + r < P.Ho, dump_lane);
         };
 
         // every segment starts from cleared accumulators (keeps them dead across segments)
@@ -303,8 +339,9 @@ __global__ void __launch_bounds__(256, 1) sp_conv_kernel(SpParams P) {
 
         begin_stage(od_start - P.pD, 0);
 #pragma unroll
-        for (int i = 0; i < NLOAD; ++i) load_piece(i);
+        for (int i = 0; i < NLOAD; ++i) load_piece(i, 0);
         write_stage(0);
+        if (DMA) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
 
         // Plane step jj stages input plane ip = od_start + jj - pD, one 32-channel chunk at a time, and
@@ -329,7 +366,7 @@ __global__ void __launch_bounds__(256, 1) sp_conv_kernel(SpParams P) {
                 if (STREAM && k % 6 == 0) { /* all pieces of the slot at the start of its phase: a full phase of cover */ \
                     _Pragma("unroll") for (int i_ = 0; i_ < NWL; ++i_) wreg[i_] = *(const uint4*)(wsrc_[k / 6] + wpiece[i_] * 16); \
                 }                                                                               \
-                if (k < NLOAD) load_piece(k);                                                   \
+                if (k < NLOAD) load_piece(k, NBUF == 2 ? ((sq + 1) & 1) : 0);                   \
                 else if (k < NLOAD + RH) {                                                      \
                     store_piece(k - NLOAD);                                                     \
                     if (k == NLOAD + RH - 1) st_pending = false;                                \
@@ -345,6 +382,8 @@ __global__ void __launch_bounds__(256, 1) sp_conv_kernel(SpParams P) {
                 st_ptr = yn + (((long long)(j_ - 2) * P.Ho + h0 + wave * RH) * P.Wo + ow_) * P.Cout + ct * 32 + 16 * (lane >> 5); \
             }                                                                                   \
             ++sq;                                                                               \
+            /* the ten loads into the next stage are complete; the eight stores issued after them may still fly */ \
+            if (DMA) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");                           \
             __syncthreads();                                                                    \
         }
 #define SP_STEP(PHASE)                                                                          \
@@ -405,6 +444,8 @@ bool sp_supported(const Geom& g, int pass) {
     if (g.dtype != MI3D_BF16 || g.kD != 3 || g.kH != 3 || g.kW != 3) return false;
     if (g.sD != 1 || g.sH != 1 || g.sW != 1) return false;
     if (g.pD > 2 || g.pH > 2 || g.pW > 2) return false;
+    // a staged plane is addressed through a buffer resource with 32-bit offsets; 2^31 marks padding
+    if ((long long)g.H * g.W * g.Cin * 2 >= (1ll << 31) || (long long)g.Ho * g.Wo * g.Cout * 2 >= (1ll << 31)) return false;
     if (pass == MI3D_PASS_FWD) return g.Cin % 32 == 0 && g.Cout % 32 == 0;
     if (pass == MI3D_PASS_DGRAD) return g.Cout % 32 == 0 && g.Cin % 32 == 0;
     return false;
@@ -412,7 +453,7 @@ bool sp_supported(const Geom& g, int pass) {
 
 size_t sp_workspace_bytes(const Geom& g, int pass) {
     if (!sp_supported(g, pass)) return 0;
-    return (size_t)g.w_elems() * 2;
+    return (((size_t)g.w_elems() * 2 + 255) & ~(size_t)255) + 2048;  // packed weights + store dump area
 }
 
 // in: activations read (x for fwd, dy for dgrad); out: y or dx
@@ -427,6 +468,7 @@ int sp_conv(const Geom& g, int pass, const void* in, const void* w, void* out, v
     P.x = (const uint16_t*)in;
     P.wpack = (const uint16_t*)ws;
     P.y = (uint16_t*)out;
+    P.dump = (uint16_t*)((char*)ws + (((size_t)g.w_elems() * 2 + 255) & ~(size_t)255));
     P.N = g.N;
     if (!flip) {
         P.D = g.D; P.H = g.H; P.W = g.W; P.Cin = g.Cin; P.Cout = g.Cout;
