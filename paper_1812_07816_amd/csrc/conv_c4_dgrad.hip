@@ -46,6 +46,7 @@ struct C4DgParams {
     const uint16_t* dy;
     const uint16_t* wpack;  // [kd'][kw'][lane][8], flipped taps
     uint16_t* dx;
+    uint16_t* dump;         // 512 B that masked store lanes write to instead of dx
     int N, D, H, W;         // extents of dy (the tensor read)
     int Do, Ho, Wo;         // extents of dx (the tensor written)
     int pD, pH, pW;         // padding of the equivalent forward convolution over dy: 2 - p
@@ -108,7 +109,9 @@ __device__ __forceinline__ float swap_add16(float a, float b) {
 // Output row i = sum over g of U[i + g] in lane group g (group 3 is all zero:
 // its weight rows are padding).  Four rows at a time: after the butterfly lane
 // group g holds output row 4 q + g, each lane the 4 channels of one voxel.
-__device__ __forceinline__ void store_plane(const f32x4 (&U)[UR], uint16_t* p, long long row_pitch, int lane, bool col_ok, int rows_left) {
+// Stores are unconditional (masked lanes write to the dump area): behind a branch the compiler cannot count them
+// and makes the LDS write that follows wait for vmcnt(0), i.e. for the stores themselves.
+__device__ __forceinline__ void store_plane(const f32x4 (&U)[UR], uint16_t* p, long long row_pitch, int lane, bool col_ok, int rows_left, uint16_t* dump) {
     const int g = lane >> 4;
 #pragma unroll
     for (int q = 0; q < WR / 4; ++q) {
@@ -132,7 +135,7 @@ __device__ __forceinline__ void store_plane(const f32x4 (&U)[UR], uint16_t* p, l
         uint2 o;
         o.x = __builtin_bit_cast(uint32_t, __builtin_convertvector(lo, bf16x2));
         o.y = __builtin_bit_cast(uint32_t, __builtin_convertvector(hi, bf16x2));
-        if (col_ok && 4 * q + g < rows_left) *(uint2*)(p + (4 * q + g) * row_pitch) = o;
+        *(uint2*)((col_ok && 4 * q + g < rows_left) ? p + (4 * q + g) * row_pitch : dump) = o;
     }
 }
 
@@ -239,9 +242,8 @@ __global__ void __launch_bounds__(256, 1) c4_dgrad_kernel(C4DgParams P) {
                 if (jj - kd_ >= 0 && jj - kd_ < nJ - 2) kdmask_ |= 1 << kd_;                    \
             plane_compute<PHASE>(acc, in_lds + (sq & 1) * STAGE_BYTES + lane_in_off, wf, kdmask_, \
                                  [&](int r) { load_piece(r); });                                \
-            if (jj >= 2)                                                                        \
-                store_plane(acc[(PHASE + 1) % 3], dxn + (((long long)(j_ - 2) * P.Ho + oh0) * P.Wo + ow) * 4, \
-                            row_pitch, lane, ow < P.Wo, P.Ho - oh0);                            \
+            store_plane(acc[(PHASE + 1) % 3], dxn + (((long long)(j_ - 2) * P.Ho + oh0) * P.Wo + ow) * 4, \
+                        row_pitch, lane, jj >= 2 && ow < P.Wo, P.Ho - oh0, P.dump + lane * 4);  \
             write_stage((sq + 1) & 1);                                                          \
             ++sq;                                                                               \
             __syncthreads();                                                                    \
@@ -280,7 +282,7 @@ bool c4_dgrad_supported(const Geom& g) {
     return g.Cin == 4 && g.Cout == 32;
 }
 
-size_t c4_dgrad_workspace_bytes(const Geom& g) { return c4_dgrad_supported(g) ? 9 * 1024 : 0; }
+size_t c4_dgrad_workspace_bytes(const Geom& g) { return c4_dgrad_supported(g) ? 9 * 1024 + 512 : 0; }
 
 int c4_dgrad(const Geom& g, const void* dy, const void* w, void* dx, void* ws, size_t ws_bytes, hipStream_t s) {
     if (ws_bytes < c4_dgrad_workspace_bytes(g)) return MI3D_ERR_WORKSPACE;
@@ -289,6 +291,7 @@ int c4_dgrad(const Geom& g, const void* dy, const void* w, void* dx, void* ws, s
     if (st) return st;
     C4DgParams P;
     P.dy = (const uint16_t*)dy; P.wpack = (const uint16_t*)ws; P.dx = (uint16_t*)dx;
+    P.dump = (uint16_t*)((char*)ws + 9 * 1024);
     P.N = g.N;
     P.D = g.Do; P.H = g.Ho; P.W = g.Wo;
     P.Do = g.D; P.Ho = g.H; P.Wo = g.W;

@@ -34,6 +34,7 @@ struct Dg2Params {
     const uint16_t* dy;
     const uint16_t* wpack;  // [cin tile][kd][kh][kw][k16][lane][8]
     uint16_t* dx;
+    uint16_t* dump;         // 2 KB that masked store lanes write to instead of dx
     int N, D, H, W, Cin, Cout, Do, Ho, Wo, p;
     int QD, HT, WT, CiT;
     long long units;
@@ -250,18 +251,17 @@ __global__ void __launch_bounds__(256, 1) dgrad_s2_kernel(Dg2Params G) {
                     // lane (n, h) writes cins 16 h .. 16 h + 15 of the even and of the odd voxel of its column
                     // pair: per store instruction the two lane halves fill 32 of a voxel's 64 bytes (measured:
                     // 5.9 TB/s; giving each lane a whole 64-byte voxel in four 16-byte stores reaches 3.6 TB/s)
+                    // Stores are unconditional (masked lanes write to the dump area): behind a branch the compiler
+                    // cannot count them and makes the LDS write that follows wait for the stores to complete.
                     const int iw_ = 2 * cq;
-                    if (id_ < G.D && ih_ < G.H) {
-                        uint16_t* ptr = dxn + (((long long)id_ * G.H + ih_) * G.W + iw_) * G.Cin + cit * 32 + 16 * (lane >> 5);
-                        if (iw_ < G.W) {
-                            *(uint4*)(ptr) = ev[0];
-                            *(uint4*)(ptr + 8) = ev[1];
-                        }
-                        if (iw_ + 1 < G.W) {
-                            *(uint4*)(ptr + G.Cin) = od[0];
-                            *(uint4*)(ptr + G.Cin + 8) = od[1];
-                        }
-                    }
+                    const bool row_ok = id_ < G.D && ih_ < G.H;
+                    uint16_t* ptr = dxn + (((long long)id_ * G.H + ih_) * G.W + iw_) * G.Cin + cit * 32 + 16 * (lane >> 5);
+                    uint16_t* pe = (row_ok && iw_ < G.W) ? ptr : G.dump + lane * 16;
+                    uint16_t* po = (row_ok && iw_ + 1 < G.W) ? ptr + G.Cin : G.dump + lane * 16;
+                    *(uint4*)(pe) = ev[0];
+                    *(uint4*)(pe + 8) = ev[1];
+                    *(uint4*)(po) = od[0];
+                    *(uint4*)(po + 8) = od[1];
                 }
             }
 
@@ -298,7 +298,7 @@ bool dgrad_s2_supported(const Geom& g) {
     return g.Cin % 32 == 0 && (g.Cout == 32 || g.Cout == 64);
 }
 
-size_t dgrad_s2_workspace_bytes(const Geom& g) { return dgrad_s2_supported(g) ? (size_t)g.w_elems() * 2 : 0; }
+size_t dgrad_s2_workspace_bytes(const Geom& g) { return dgrad_s2_supported(g) ? (((size_t)g.w_elems() * 2 + 255) & ~(size_t)255) + 2048 : 0; }
 
 int dgrad_s2(const Geom& g, const void* dy, const void* w, void* dx, void* ws, size_t ws_bytes, hipStream_t s) {
     if (ws_bytes < dgrad_s2_workspace_bytes(g)) return MI3D_ERR_WORKSPACE;
@@ -308,6 +308,7 @@ int dgrad_s2(const Geom& g, const void* dy, const void* w, void* dx, void* ws, s
     if (st) return st;
     Dg2Params G;
     G.dy = (const uint16_t*)dy; G.wpack = (const uint16_t*)ws; G.dx = (uint16_t*)dx;
+    G.dump = (uint16_t*)((char*)ws + (((size_t)g.w_elems() * 2 + 255) & ~(size_t)255));
     G.N = g.N; G.D = g.D; G.H = g.H; G.W = g.W; G.Cin = g.Cin; G.Cout = g.Cout;
     G.Do = g.Do; G.Ho = g.Ho; G.Wo = g.Wo; G.p = g.pD;
     G.QD = (g.D + 1) / 2;

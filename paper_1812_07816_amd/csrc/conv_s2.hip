@@ -30,6 +30,7 @@ struct S2Params {
     const uint16_t* x;
     const uint16_t* wpack;  // [cout block][kw][kd][kh][k16][lane][8]
     uint16_t* y;
+    uint16_t* dump;         // 2 KB that masked store lanes write to instead of y
     int N, D, H, W, Cout, Do, Ho, Wo, pD, pH, pW;
     int HT, WT, CT;         // tiles per plane, cout tiles
     long long units;
@@ -90,7 +91,9 @@ __device__ __forceinline__ void plane_compute(f32x16 (&acc)[2][RH], const char* 
     }
 }
 
-__device__ __forceinline__ void store_rows(const f32x16 (&a)[RH], uint16_t* p, long long row_pitch, bool col_ok, int rows_ok) {
+// Stores are unconditional (masked lanes write to the dump area): behind a branch the compiler cannot count
+// them and makes the LDS write that follows wait for vmcnt(0), i.e. for the stores themselves.
+__device__ __forceinline__ void store_rows(const f32x16 (&a)[RH], uint16_t* p, long long row_pitch, bool col_ok, int rows_ok, uint16_t* dump) {
     typedef __attribute__((ext_vector_type(2))) unsigned u32x2;
 #pragma unroll
     for (int r = 0; r < RH; ++r) {
@@ -108,10 +111,9 @@ __device__ __forceinline__ void store_rows(const f32x16 (&a)[RH], uint16_t* p, l
             u32x2 s1 = __builtin_amdgcn_permlane32_swap(o[2 * k + 1], o[2 * k + 5], false, false);
             c[k].x = s0[0]; c[k].y = s1[0]; c[k].z = s0[1]; c[k].w = s1[1];
         }
-        if (col_ok && r < rows_ok) {
-            *(uint4*)(p + r * row_pitch) = c[0];
-            *(uint4*)(p + r * row_pitch + 8) = c[1];
-        }
+        uint16_t* q = (col_ok && r < rows_ok) ? p + r * row_pitch : dump;
+        *(uint4*)q = c[0];
+        *(uint4*)(q + 8) = c[1];
     }
 }
 
@@ -246,10 +248,10 @@ __global__ void __launch_bounds__(256, 1) s2_fwd_kernel(S2Params P) {
                 _Pragma("unroll") for (int i_ = 0; i_ < PER_HOOK; ++i_)                          \
                     if (pos * PER_HOOK + i_ < NLOAD) load_piece(rs_, pos * PER_HOOK + i_);       \
             });                                                                                  \
-            if ((EVEN) && tq >= 2) {                                                             \
+            if (EVEN) {                                                                          \
                 const int od_ = od_start + (tq >> 1) - 1;                                        \
                 store_rows(acc[1 - (SET)], yn + ((long long)od_ * P.Ho + oh0) * row_pitch + (long long)ow * P.Cout + co0, \
-                           row_pitch, ow < P.Wo, P.Ho - oh0);                                    \
+                           row_pitch, tq >= 2 && ow < P.Wo, P.Ho - oh0, P.dump + lane * 16);     \
             }                                                                                    \
             __syncthreads();                                                                     \
             write_plane(1 - rs_);                                                                \
@@ -296,7 +298,7 @@ bool s2_fwd_supported(const Geom& g) {
     return g.Cin == 32 && g.Cout % 32 == 0;
 }
 
-size_t s2_fwd_workspace_bytes(const Geom& g) { return s2_fwd_supported(g) ? (size_t)g.w_elems() * 2 : 0; }
+size_t s2_fwd_workspace_bytes(const Geom& g) { return s2_fwd_supported(g) ? (((size_t)g.w_elems() * 2 + 255) & ~(size_t)255) + 2048 : 0; }
 
 int s2_fwd(const Geom& g, const void* x, const void* w, void* y, void* ws, size_t ws_bytes, hipStream_t s) {
     if (ws_bytes < s2_fwd_workspace_bytes(g)) return MI3D_ERR_WORKSPACE;
@@ -306,6 +308,7 @@ int s2_fwd(const Geom& g, const void* x, const void* w, void* y, void* ws, size_
     if (st) return st;
     S2Params P;
     P.x = (const uint16_t*)x; P.wpack = (const uint16_t*)ws; P.y = (uint16_t*)y;
+    P.dump = (uint16_t*)((char*)ws + (((size_t)g.w_elems() * 2 + 255) & ~(size_t)255));
     P.N = g.N; P.D = g.D; P.H = g.H; P.W = g.W; P.Cout = g.Cout;
     P.Do = g.Do; P.Ho = g.Ho; P.Wo = g.Wo; P.pD = g.pD; P.pH = g.pH; P.pW = g.pW;
     const int CB = (g.Cout % 64 == 0) ? 2 : 1;
