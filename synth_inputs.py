@@ -61,3 +61,60 @@ def conv_case(config, base_index, N, D, H, W, Cin, Cout, k, s, p, bf16):
     w = he_normal_weight(config, base_index + 1, Cout, (kD, kH, kW), Cin, bf16=bf16)
     dy = normal(config, base_index + 2, (N, Do, Ho, Wo, Cout), bf16=bf16)
     return x, w, dy
+
+
+# ---- whole-network inputs (full training step of the 5-level U-Net) -----------------------------
+
+def unet_weight_shapes(channels, in_ch=4, classes=3):
+    """[(name, (Cout, k, k, k, Cin))] in the fixed order used by every consumer:
+    encoder convs level by level, then per decoder level (deepest first) the
+    up-sampling weights and the two convs, then the 1x1x1 head.  The
+    up-sampling layer is stored as the weights of the 2x2x2 / stride-2
+    convolution whose data gradient it is: [C_deep][2][2][2][C_shallow]."""
+    out = []
+    prev = in_ch
+    for l, c in enumerate(channels):
+        out.append((f"enc{l}.conv1", (c, 3, 3, 3, prev)))
+        out.append((f"enc{l}.conv2", (c, 3, 3, 3, c)))
+        prev = c
+    for l in range(len(channels) - 2, -1, -1):
+        c, deep = channels[l], channels[l + 1]
+        out.append((f"dec{l}.up", (deep, 2, 2, 2, c)))
+        out.append((f"dec{l}.conv1", (c, 3, 3, 3, 2 * c)))
+        out.append((f"dec{l}.conv2", (c, 3, 3, 3, c)))
+    out.append(("head", (classes, 1, 1, 1, channels[0])))
+    return out
+
+
+def unet_weights(config, channels, in_ch=4, classes=3, bf16=True):
+    """He-normal weights (std = sqrt(2 / fan_in); fan_in = k^3 Cin for a
+    convolution, the number of input channels C_deep for the up-sampling layer,
+    where every output voxel sees one tap), tensor indices 100, 101, ..."""
+    ws = []
+    for i, (name, shp) in enumerate(unet_weight_shapes(channels, in_ch, classes)):
+        fan_in = shp[0] if name.endswith(".up") else shp[1] * shp[2] * shp[3] * shp[4]
+        ws.append(normal(config, 100 + i, shp, std=float(np.sqrt(2.0 / fan_in)), bf16=bf16))
+    return ws
+
+
+def ellipsoid_labels(config, tensor_index, N, vol, classes=3):
+    """uint8 [N, vol, vol, vol, classes]: per sample and class the union of 1-8
+    axis-aligned ellipsoids, centres uniform over the volume, per-axis radii
+    uniform in 8..48 voxels at vol = 192 (scaled with vol, at least 1).
+    Classes are drawn independently and may overlap.  Stands in for the tumour
+    sub-region labels of Section 4.1."""
+    g = rng(config, tensor_index)
+    lab = np.zeros((N, vol, vol, vol, classes), dtype=np.uint8)
+    ax = np.arange(vol, dtype=np.float32)
+    lo, hi = max(1, round(8 * vol / 192)), max(2, round(48 * vol / 192))
+    for n in range(N):
+        for c in range(classes):
+            for _ in range(int(g.integers(1, 9))):
+                ctr = g.uniform(0, vol, size=3)
+                rad = g.integers(lo, hi + 1, size=3).astype(np.float32)
+                dz = ((ax - ctr[0]) / rad[0]) ** 2
+                dy = ((ax - ctr[1]) / rad[1]) ** 2
+                dx = ((ax - ctr[2]) / rad[2]) ** 2
+                inside = dz[:, None, None] + dy[None, :, None] + dx[None, None, :] <= 1.0
+                lab[n, ..., c] |= inside.astype(np.uint8)
+    return lab

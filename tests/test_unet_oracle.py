@@ -1,0 +1,86 @@
+"""Pins of the whole-step oracle (oracle/unet.py): the loss against the Dice
+coefficient of Section 4.3 on binary predictions, its gradient and the whole
+backward pass against central finite differences of the forward pass."""
+import numpy as np
+import pytest
+
+import synth_inputs as si
+from oracle import unet as ou
+
+
+def test_soft_dice_reduces_to_dice_coefficient_on_binary_predictions():
+    # logits +-40 give p in {0, 1} to fp64 precision; Dice = |P and T| / ((|P| + |T|) / 2)  (Section 4.3)
+    rng = np.random.default_rng(1)
+    t = (rng.random((2, 4, 5, 6, 3)) < 0.4)
+    pred = (rng.random(t.shape) < 0.5)
+    logits = np.where(pred, 40.0, -40.0)
+    loss, _ = ou.dice_loss(logits, t.astype(np.uint8))
+    dice = [(pred[..., c] & t[..., c]).sum() / ((pred[..., c].sum() + t[..., c].sum()) / 2) for c in range(3)]
+    assert abs(loss - (1.0 - np.mean(dice))) < 1e-6
+
+
+def test_dice_loss_of_perfect_and_of_disjoint_prediction():
+    t = np.zeros((1, 4, 4, 4, 3), dtype=np.uint8)
+    t[:, :2] = 1
+    perfect = np.where(t > 0, 40.0, -40.0)
+    assert ou.dice_loss(perfect, t)[0] < 1e-9
+    assert abs(ou.dice_loss(-perfect, t)[0] - 1.0) < 1e-6
+
+
+def test_dice_gradient_matches_finite_differences():
+    rng = np.random.default_rng(2)
+    logits = rng.standard_normal((2, 3, 4, 5, 3))
+    t = (rng.random(logits.shape) < 0.3).astype(np.uint8)
+    _, g = ou.dice_loss(logits, t)
+    h = 1e-6
+    for idx in [(0, 0, 0, 0, 0), (1, 2, 3, 4, 2), (0, 1, 2, 3, 1), (1, 0, 3, 0, 0)]:
+        a, b = logits.copy(), logits.copy()
+        a[idx] += h; b[idx] -= h
+        fd = (ou.dice_loss(a, t)[0] - ou.dice_loss(b, t)[0]) / (2 * h)
+        assert abs(fd - g[idx]) <= 1e-7 + 1e-5 * abs(g[idx])
+
+
+@pytest.mark.parametrize("channels", [[2, 3], [2, 3, 4]])
+def test_backward_matches_finite_differences_of_forward(channels):
+    # tiny network: every kind of layer (strided conv, up-sampling, concatenation, head) is on the path
+    V = 4 * 2 ** (len(channels) - 1) // 2
+    V = max(V, 2 ** (len(channels) - 1) * 2)
+    rng = np.random.default_rng(3)
+    shapes = si.unet_weight_shapes(channels, in_ch=2, classes=3)
+    ws = [rng.standard_normal(shp) * 0.4 for _, shp in shapes]
+    x = rng.standard_normal((2, V, V, V, 2))
+    t = (rng.random((2, V, V, V, 3)) < 0.4).astype(np.uint8)
+    loss, grads, _ = ou.train_step(x, t, ws, channels, lr=0.0)
+
+    def f(ws_):
+        return ou.dice_loss(ou.forward(x, ws_, channels)[0], t)[0]
+
+    h = 1e-5
+    for k, (name, shp) in enumerate(shapes):
+        for _ in range(2):
+            idx = tuple(int(rng.integers(0, n)) for n in shp)
+            wp = [w.copy() for w in ws]; wm = [w.copy() for w in ws]
+            wp[k][idx] += h; wm[k][idx] -= h
+            fd = (f(wp) - f(wm)) / (2 * h)
+            assert abs(fd - grads[k][idx]) <= 1e-8 + 2e-4 * abs(fd), (name, idx, fd, grads[k][idx])
+
+
+def test_sgd_update_and_weight_order():
+    channels = [2, 3]
+    rng = np.random.default_rng(4)
+    shapes = si.unet_weight_shapes(channels, in_ch=2, classes=3)
+    assert [n for n, _ in shapes] == ["enc0.conv1", "enc0.conv2", "enc1.conv1", "enc1.conv2", "dec0.up", "dec0.conv1", "dec0.conv2", "head"]
+    ws = [rng.standard_normal(shp) * 0.3 for _, shp in shapes]
+    x = rng.standard_normal((1, 4, 4, 4, 2))
+    t = (rng.random((1, 4, 4, 4, 3)) < 0.5).astype(np.uint8)
+    loss, grads, new = ou.train_step(x, t, ws, channels, lr=0.25)
+    for w, g, n in zip(ws, grads, new):
+        assert g.shape == w.shape
+        assert np.allclose(n, w - 0.25 * g, rtol=0, atol=1e-15)
+
+
+def test_label_generator_shape_and_determinism():
+    a = si.ellipsoid_labels(5, 7, 2, 16)
+    b = si.ellipsoid_labels(5, 7, 2, 16)
+    assert a.dtype == np.uint8 and a.shape == (2, 16, 16, 16, 3)
+    assert np.array_equal(a, b) and set(np.unique(a)) <= {0, 1} and a.any()
