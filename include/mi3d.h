@@ -106,6 +106,45 @@ int mi3d_conv3d_set_kernel_family(int family);
 /* Writes the name of the kernel the automatic choice picks (for reports). */
 int mi3d_conv3d_kernel_name(const mi3d_conv_desc *desc, int pass, char *buf, size_t buf_len);
 
+/* ------------------------------------------------------------------------
+ * Steps of the training step around the convolutions (the network of
+ * Section 4.1: LeakyReLU after each 3x3x3 convolution, skip concatenation in
+ * the decoder, sigmoid + soft Dice loss on the Dice coefficient of Section
+ * 4.3, SGD).  Every pointer is a device pointer, 16-byte aligned unless said
+ * otherwise, caller-owned; calls only enqueue work on `stream`.  Element
+ * counts n must be multiples of 8.  Status codes as above.
+ * ---------------------------------------------------------------------- */
+
+/* a[i] <- a[i] > 0 ? a[i] : slope * a[i]  (bf16, in place). */
+int mi3d_leaky_relu_fwd(void *a, size_t n, float slope, void *stream);
+/* da[i] <- da[i] * (a[i] > 0 ? 1 : slope), in place on da; a is the OUTPUT of
+ * the activation (it has the sign of its input, so the input is not kept). */
+int mi3d_leaky_relu_bwd(void *da, const void *a, size_t n, float slope, void *stream);
+/* out[v][0:Ca] = a[v][:], out[v][Ca:Ca+Cb] = b[v][:] over `voxels` voxels
+ * (bf16; Ca, Cb multiples of 8).  The decoder's [upsampled, skip] input. */
+int mi3d_concat_channels(const void *a, int Ca, const void *b, int Cb, void *out, size_t voxels, void *stream);
+/* Inverse of the above: a[v] = in[v][0:Ca], b[v] = in[v][Ca:Ca+Cb]. */
+int mi3d_split_channels(const void *in, int Ca, int Cb, void *a, void *b, size_t voxels, void *stream);
+/* a[i] <- a[i] + b[i]  (bf16 operands, fp32 add, one rounding). */
+int mi3d_add_inplace(void *a, const void *b, size_t n, void *stream);
+
+/* Sigmoid + soft Dice over `voxels` voxels (all samples) of `classes` = 3
+ * channels: p = sigmoid(logit), per class I = sum p t, P = sum p, T = sum t,
+ * loss = 1 - mean_c (2 I + eps) / (P + T + eps).  logits bf16 [voxels][3],
+ * labels uint8 [voxels][3] (8-byte aligned), voxels a multiple of 8.
+ * Writes sums[9] = {I_c, P_c, T_c} and the loss (device fp32); the partial
+ * sums go through ws (mi3d_dice_workspace_bytes) in a fixed order. */
+size_t mi3d_dice_workspace_bytes(int classes);
+int mi3d_dice_loss(const void *logits, const uint8_t *labels, size_t voxels, int classes, float eps,
+                   void *ws, size_t ws_bytes, float *sums, float *loss, void *stream);
+/* dlogits (bf16) = d loss / d logits, from the sums of mi3d_dice_loss. */
+int mi3d_dice_grad(const void *logits, const uint8_t *labels, size_t voxels, int classes, float eps,
+                   const float *sums, void *dlogits, void *stream);
+
+/* w[i] <- w[i] - lr * dw[i] on the fp32 master weights; w_bf16[i] <- the
+ * updated value rounded to bf16 (the copy the convolutions read). */
+int mi3d_sgd_update(float *w, const float *dw, void *w_bf16, size_t n, float lr, void *stream);
+
 /* ------------------------------------------------------------------------ */
 /* Data-swapping engine                                                     */
 /* ------------------------------------------------------------------------ */

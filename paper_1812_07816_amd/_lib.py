@@ -38,6 +38,15 @@ SIGNATURES = {
     "mi3d_status_string": (ctypes.c_char_p, [_i]),
     "mi3d_last_hip_error": (_i, []),
     "mi3d_conv3d_out_dims": (_i, [_pd, _pi, _pi, _pi]),
+    "mi3d_leaky_relu_fwd": (_i, [_vp, _sz, ctypes.c_float, _vp]),
+    "mi3d_leaky_relu_bwd": (_i, [_vp, _vp, _sz, ctypes.c_float, _vp]),
+    "mi3d_concat_channels": (_i, [_vp, _i, _vp, _i, _vp, _sz, _vp]),
+    "mi3d_split_channels": (_i, [_vp, _i, _i, _vp, _vp, _sz, _vp]),
+    "mi3d_add_inplace": (_i, [_vp, _vp, _sz, _vp]),
+    "mi3d_dice_workspace_bytes": (_sz, [_i]),
+    "mi3d_dice_loss": (_i, [_vp, _vp, _sz, _i, ctypes.c_float, _vp, _sz, _vp, _vp, _vp]),
+    "mi3d_dice_grad": (_i, [_vp, _vp, _sz, _i, ctypes.c_float, _vp, _vp, _vp]),
+    "mi3d_sgd_update": (_i, [_vp, _vp, _vp, _sz, ctypes.c_float, _vp]),
     "mi3d_conv3d_workspace_bytes": (_sz, [_pd, _i]),
     "mi3d_conv3d_fwd": (_i, [_pd, _vp, _vp, _vp, _vp, _sz, _vp]),
     "mi3d_conv3d_dgrad": (_i, [_pd, _vp, _vp, _vp, _vp, _sz, _vp]),

@@ -1,0 +1,276 @@
+// Elementwise and reduction steps of the training step around the
+// convolutions (network of Section 4.1): LeakyReLU, channel concatenation of
+// the decoder's skip connections, sigmoid + soft Dice loss (built on the Dice
+// coefficient of Section 4.3) and the SGD update.  All of them move a few
+// bytes per flop, so each is one pass over its tensors with 16-byte accesses;
+// reductions use a fixed partition and a fixed order (bit-reproducible).
+#include "mi3d_internal.h"
+
+
+namespace mi3d {
+namespace {
+
+__device__ __forceinline__ float bf16_to_f32(uint16_t v) { return __builtin_bit_cast(float, (uint32_t)v << 16); }
+__device__ __forceinline__ uint16_t f32_to_bf16(float f) {  // round to nearest even; inputs are finite
+    uint32_t u = __builtin_bit_cast(uint32_t, f);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+__device__ __forceinline__ void unpack8(const uint4& v, float (&f)[8]) {
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        f[2 * i] = __builtin_bit_cast(float, w[i] << 16);
+        f[2 * i + 1] = __builtin_bit_cast(float, w[i] & 0xFFFF0000u);
+    }
+}
+__device__ __forceinline__ uint4 pack8(const float (&f)[8]) {
+    uint32_t w[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) w[i] = (uint32_t)f32_to_bf16(f[2 * i]) | ((uint32_t)f32_to_bf16(f[2 * i + 1]) << 16);
+    return uint4{w[0], w[1], w[2], w[3]};
+}
+
+// a <- a > 0 ? a : slope * a, in place; n8 = number of 16-byte pieces
+__global__ void __launch_bounds__(256) lrelu_fwd_kernel(uint4* __restrict__ a, long long n8, float slope) {
+    for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < n8; i += (long long)gridDim.x * 256) {
+        float f[8];
+        unpack8(a[i], f);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) f[j] = f[j] > 0.f ? f[j] : slope * f[j];
+        a[i] = pack8(f);
+    }
+}
+
+// da <- da * (a > 0 ? 1 : slope), in place on da; a holds the activation's OUTPUT (same sign as its input)
+__global__ void __launch_bounds__(256) lrelu_bwd_kernel(uint4* __restrict__ da, const uint4* __restrict__ a, long long n8, float slope) {
+    for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < n8; i += (long long)gridDim.x * 256) {
+        float g[8], f[8];
+        unpack8(da[i], g);
+        unpack8(a[i], f);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) g[j] = f[j] > 0.f ? g[j] : slope * g[j];
+        da[i] = pack8(g);
+    }
+}
+
+// out[v][0:Ca] = a[v], out[v][Ca:Ca+Cb] = b[v]; channel counts in 16-byte pieces
+__global__ void __launch_bounds__(256) concat_kernel(const uint4* __restrict__ a, int pa, const uint4* __restrict__ b, int pb,
+                                                     uint4* __restrict__ out, long long total) {
+    const int pc = pa + pb;
+    for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < total; i += (long long)gridDim.x * 256) {
+        const long long v = i / pc;
+        const int c = (int)(i - v * pc);
+        out[i] = c < pa ? a[v * pa + c] : b[v * pb + (c - pa)];
+    }
+}
+
+// a[v] = in[v][0:Ca], b[v] = in[v][Ca:Ca+Cb]
+__global__ void __launch_bounds__(256) split_kernel(const uint4* __restrict__ in, int pa, int pb, uint4* __restrict__ a,
+                                                    uint4* __restrict__ b, long long total) {
+    const int pc = pa + pb;
+    for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < total; i += (long long)gridDim.x * 256) {
+        const long long v = i / pc;
+        const int c = (int)(i - v * pc);
+        const uint4 x = in[i];
+        if (c < pa) a[v * pa + c] = x;
+        else b[v * pb + (c - pa)] = x;
+    }
+}
+
+// a <- a + b (fp32 add, one rounding)
+__global__ void __launch_bounds__(256) add_kernel(uint4* __restrict__ a, const uint4* __restrict__ b, long long n8) {
+    for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < n8; i += (long long)gridDim.x * 256) {
+        float f[8], g[8];
+        unpack8(a[i], f);
+        unpack8(b[i], g);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) f[j] += g[j];
+        a[i] = pack8(f);
+    }
+}
+
+__device__ __forceinline__ float sigmoidf(float x) { return 1.f / (1.f + __expf(-x)); }
+
+// Soft Dice, first pass.  A thread takes groups of 8 voxels = 8 C values (C 16-byte pieces of logits, C 8-byte
+// pieces of labels); value e of a group belongs to class e % C.  Per class: sum p t, sum p, sum t.  A block
+// owns a contiguous range of groups; per-thread sums are combined in a fixed tree and written as one partial.
+template <int C>
+__global__ void __launch_bounds__(256) dice_partial_kernel(const uint4* __restrict__ logits, const uint2* __restrict__ labels,
+                                                           long long groups, float* __restrict__ part) {
+    __shared__ float red[3 * C][256];
+    const long long g0 = groups * blockIdx.x / gridDim.x, g1 = groups * (blockIdx.x + 1) / gridDim.x;
+    float s[3 * C];
+#pragma unroll
+    for (int k = 0; k < 3 * C; ++k) s[k] = 0.f;
+    for (long long g = g0 + threadIdx.x; g < g1; g += 256) {
+#pragma unroll
+        for (int q = 0; q < C; ++q) {
+            float x[8];
+            unpack8(logits[g * C + q], x);
+            const uint2 lb = labels[g * C + q];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int cls = (8 * q + j) % C;
+                const float t = (float)(((j < 4 ? lb.x : lb.y) >> (8 * (j & 3))) & 0xFFu);
+                const float p = sigmoidf(x[j]);
+                s[cls] += p * t;
+                s[C + cls] += p;
+                s[2 * C + cls] += t;
+            }
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < 3 * C; ++k) red[k][threadIdx.x] = s[k];
+    __syncthreads();
+    for (int w = 128; w > 0; w >>= 1) {
+        if (threadIdx.x < w) {
+#pragma unroll
+            for (int k = 0; k < 3 * C; ++k) red[k][threadIdx.x] += red[k][threadIdx.x + w];
+        }
+        __syncthreads();
+    }
+    if (threadIdx.x < 3 * C) part[blockIdx.x * 3 * C + threadIdx.x] = red[threadIdx.x][0];
+}
+
+// second pass: partials added in index order in double; sums[3C] and the loss 1 - mean_c (2 I + eps) / (P + T + eps)
+template <int C>
+__global__ void dice_final_kernel(const float* __restrict__ part, int nblocks, float eps, float* __restrict__ sums, float* __restrict__ loss) {
+    __shared__ double tot[3 * C];
+    if (threadIdx.x < 3 * C) {
+        double a = 0.0;
+        for (int b = 0; b < nblocks; ++b) a += (double)part[b * 3 * C + threadIdx.x];
+        tot[threadIdx.x] = a;
+        sums[threadIdx.x] = (float)a;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double d = 0.0;
+        for (int c = 0; c < C; ++c) d += (2.0 * tot[c] + eps) / (tot[C + c] + tot[2 * C + c] + eps);
+        *loss = (float)(1.0 - d / C);
+    }
+}
+
+// dloss/dlogit = -(1/C) (2 t den - (2 I + eps)) / den^2 * p (1 - p), den = P + T + eps
+template <int C>
+__global__ void __launch_bounds__(256) dice_grad_kernel(const uint4* __restrict__ logits, const uint2* __restrict__ labels, long long groups,
+                                                        float eps, const float* __restrict__ sums, uint4* __restrict__ dlogits) {
+    float ka[C], kb[C];  // gradient wrt p = ka * t + kb
+#pragma unroll
+    for (int c = 0; c < C; ++c) {
+        const float den = sums[C + c] + sums[2 * C + c] + eps;
+        ka[c] = -2.f / (den * C);
+        kb[c] = (2.f * sums[c] + eps) / (den * den * C);
+    }
+    for (long long g = (long long)blockIdx.x * 256 + threadIdx.x; g < groups; g += (long long)gridDim.x * 256) {
+#pragma unroll
+        for (int q = 0; q < C; ++q) {
+            float x[8];
+            unpack8(logits[g * C + q], x);
+            const uint2 lb = labels[g * C + q];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int cls = (8 * q + j) % C;
+                const float t = (float)(((j < 4 ? lb.x : lb.y) >> (8 * (j & 3))) & 0xFFu);
+                const float p = sigmoidf(x[j]);
+                x[j] = (ka[cls] * t + kb[cls]) * p * (1.f - p);
+            }
+            dlogits[g * C + q] = pack8(x);
+        }
+    }
+}
+
+// w <- w - lr * dw (fp32 master weights), wb <- bf16(w)
+__global__ void __launch_bounds__(256) sgd_kernel(float* __restrict__ w, const float* __restrict__ dw, uint16_t* __restrict__ wb, long long n, float lr) {
+    for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < n; i += (long long)gridDim.x * 256) {
+        const float v = w[i] - lr * dw[i];
+        w[i] = v;
+        wb[i] = f32_to_bf16(v);
+    }
+}
+
+unsigned grid_for(long long items) {
+    long long b = (items + 255) / 256;
+    return (unsigned)(b < 1 ? 1 : (b > 8192 ? 8192 : b));
+}
+bool al16(const void* p) { return ((uintptr_t)p & 15) == 0; }
+constexpr int DICE_BLOCKS = 1024;
+
+}  // namespace
+}  // namespace mi3d
+
+using namespace mi3d;
+
+extern "C" {
+
+int mi3d_leaky_relu_fwd(void* a, size_t n, float slope, void* stream) {
+    if (!a || !al16(a) || n % 8) return MI3D_ERR_INVALID_ARG;
+    if (n == 0) return MI3D_OK;
+    lrelu_fwd_kernel<<<grid_for(n / 8), 256, 0, (hipStream_t)stream>>>((uint4*)a, (long long)(n / 8), slope);
+    return check_launch();
+}
+
+int mi3d_leaky_relu_bwd(void* da, const void* a, size_t n, float slope, void* stream) {
+    if (!da || !a || !al16(da) || !al16(a) || n % 8) return MI3D_ERR_INVALID_ARG;
+    if (n == 0) return MI3D_OK;
+    lrelu_bwd_kernel<<<grid_for(n / 8), 256, 0, (hipStream_t)stream>>>((uint4*)da, (const uint4*)a, (long long)(n / 8), slope);
+    return check_launch();
+}
+
+int mi3d_concat_channels(const void* a, int Ca, const void* b, int Cb, void* out, size_t voxels, void* stream) {
+    if (!a || !b || !out || !al16(a) || !al16(b) || !al16(out) || Ca <= 0 || Cb <= 0 || Ca % 8 || Cb % 8) return MI3D_ERR_INVALID_ARG;
+    if (voxels == 0) return MI3D_OK;
+    const long long total = (long long)voxels * ((Ca + Cb) / 8);
+    concat_kernel<<<grid_for(total), 256, 0, (hipStream_t)stream>>>((const uint4*)a, Ca / 8, (const uint4*)b, Cb / 8, (uint4*)out, total);
+    return check_launch();
+}
+
+int mi3d_split_channels(const void* in, int Ca, int Cb, void* a, void* b, size_t voxels, void* stream) {
+    if (!a || !b || !in || !al16(a) || !al16(b) || !al16(in) || Ca <= 0 || Cb <= 0 || Ca % 8 || Cb % 8) return MI3D_ERR_INVALID_ARG;
+    if (voxels == 0) return MI3D_OK;
+    const long long total = (long long)voxels * ((Ca + Cb) / 8);
+    split_kernel<<<grid_for(total), 256, 0, (hipStream_t)stream>>>((const uint4*)in, Ca / 8, Cb / 8, (uint4*)a, (uint4*)b, total);
+    return check_launch();
+}
+
+int mi3d_add_inplace(void* a, const void* b, size_t n, void* stream) {
+    if (!a || !b || !al16(a) || !al16(b) || n % 8) return MI3D_ERR_INVALID_ARG;
+    if (n == 0) return MI3D_OK;
+    add_kernel<<<grid_for(n / 8), 256, 0, (hipStream_t)stream>>>((uint4*)a, (const uint4*)b, (long long)(n / 8));
+    return check_launch();
+}
+
+size_t mi3d_dice_workspace_bytes(int classes) { return (size_t)DICE_BLOCKS * 3 * (classes > 0 ? classes : 1) * sizeof(float); }
+
+int mi3d_dice_loss(const void* logits, const uint8_t* labels, size_t voxels, int classes, float eps,
+                   void* ws, size_t ws_bytes, float* sums, float* loss, void* stream) {
+    if (!logits || !labels || !ws || !sums || !loss || !al16(logits) || ((uintptr_t)labels & 7) || voxels == 0 || voxels % 8) return MI3D_ERR_INVALID_ARG;
+    if (classes != 3) return MI3D_ERR_UNSUPPORTED;
+    if (ws_bytes < mi3d_dice_workspace_bytes(classes)) return MI3D_ERR_WORKSPACE;
+    const long long groups = (long long)(voxels / 8);
+    const int blocks = (int)(groups < DICE_BLOCKS ? groups : DICE_BLOCKS);
+    dice_partial_kernel<3><<<blocks, 256, 0, (hipStream_t)stream>>>((const uint4*)logits, (const uint2*)labels, groups, (float*)ws);
+    int st = check_launch();
+    if (st) return st;
+    dice_final_kernel<3><<<1, 64, 0, (hipStream_t)stream>>>((const float*)ws, blocks, eps, sums, loss);
+    return check_launch();
+}
+
+int mi3d_dice_grad(const void* logits, const uint8_t* labels, size_t voxels, int classes, float eps,
+                   const float* sums, void* dlogits, void* stream) {
+    if (!logits || !labels || !sums || !dlogits || !al16(logits) || !al16(dlogits) || ((uintptr_t)labels & 7) || voxels == 0 || voxels % 8)
+        return MI3D_ERR_INVALID_ARG;
+    if (classes != 3) return MI3D_ERR_UNSUPPORTED;
+    const long long groups = (long long)(voxels / 8);
+    dice_grad_kernel<3><<<grid_for(groups), 256, 0, (hipStream_t)stream>>>((const uint4*)logits, (const uint2*)labels, groups, eps, sums, (uint4*)dlogits);
+    return check_launch();
+}
+
+int mi3d_sgd_update(float* w, const float* dw, void* w_bf16, size_t n, float lr, void* stream) {
+    if (!w || !dw || !w_bf16) return MI3D_ERR_INVALID_ARG;
+    if (n == 0) return MI3D_OK;
+    sgd_kernel<<<grid_for((long long)n), 256, 0, (hipStream_t)stream>>>(w, dw, (uint16_t*)w_bf16, (long long)n, lr);
+    return check_launch();
+}
+
+}  // extern "C"

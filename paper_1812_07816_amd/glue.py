@@ -1,0 +1,60 @@
+"""Thin binding of the elementwise / loss / optimiser entry points (marshalling only)."""
+import ctypes
+
+import torch
+
+from ._lib import check, lib
+from .swap import _stream
+
+
+def _p(t):
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def leaky_relu_fwd(a, slope=0.01):
+    check(lib().mi3d_leaky_relu_fwd(_p(a), a.numel(), slope, _stream()), "leaky_relu_fwd")
+
+
+def leaky_relu_bwd(da, a, slope=0.01):
+    assert da.numel() == a.numel()
+    check(lib().mi3d_leaky_relu_bwd(_p(da), _p(a), a.numel(), slope, _stream()), "leaky_relu_bwd")
+
+
+def concat_channels(a, b, out):
+    Ca, Cb = a.shape[-1], b.shape[-1]
+    vox = a.numel() // Ca
+    assert b.numel() // Cb == vox and out.numel() == vox * (Ca + Cb)
+    check(lib().mi3d_concat_channels(_p(a), Ca, _p(b), Cb, _p(out), vox, _stream()), "concat_channels")
+
+
+def split_channels(x, a, b):
+    Ca, Cb = a.shape[-1], b.shape[-1]
+    vox = a.numel() // Ca
+    assert b.numel() // Cb == vox and x.numel() == vox * (Ca + Cb)
+    check(lib().mi3d_split_channels(_p(x), Ca, Cb, _p(a), _p(b), vox, _stream()), "split_channels")
+
+
+def add_inplace(a, b):
+    assert a.numel() == b.numel()
+    check(lib().mi3d_add_inplace(_p(a), _p(b), a.numel(), _stream()), "add_inplace")
+
+
+def dice_workspace(classes=3):
+    return torch.empty(lib().mi3d_dice_workspace_bytes(classes), dtype=torch.uint8, device="cuda")
+
+
+def dice_loss(logits, labels, ws, sums, loss, eps=1e-5):
+    C = logits.shape[-1]
+    vox = logits.numel() // C
+    check(lib().mi3d_dice_loss(_p(logits), _p(labels), vox, C, eps, _p(ws), ws.numel(), _p(sums), _p(loss), _stream()), "dice_loss")
+
+
+def dice_grad(logits, labels, sums, dlogits, eps=1e-5):
+    C = logits.shape[-1]
+    vox = logits.numel() // C
+    check(lib().mi3d_dice_grad(_p(logits), _p(labels), vox, C, eps, _p(sums), _p(dlogits), _stream()), "dice_grad")
+
+
+def sgd_update(w32, dw32, w16, lr):
+    assert w32.numel() == dw32.numel() == w16.numel()
+    check(lib().mi3d_sgd_update(_p(w32), _p(dw32), _p(w16), w32.numel(), lr, _stream()), "sgd_update")

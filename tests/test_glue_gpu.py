@@ -1,0 +1,88 @@
+"""GPU parity of the elementwise / loss / optimiser entry points against the
+fp64 oracle's formulas (oracle/unet.py) on seeded inputs."""
+import numpy as np
+import pytest
+import torch
+
+import synth_inputs as si
+from oracle import unet as ou
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def glue():
+    if not torch.cuda.is_available():
+        pytest.skip("needs a GPU")
+    from paper_1812_07816_amd import glue as g
+    return g
+
+
+def dev(a):
+    return torch.from_numpy(si.bf16_bits(a).view(np.int16)).cuda().view(torch.bfloat16).reshape(a.shape)
+
+
+def host(t):
+    return t.detach().float().cpu().numpy().astype(np.float64)
+
+
+def test_leaky_relu_fwd_bwd(glue):
+    x = si.normal(50, 0, (3, 5, 7, 9, 16), bf16=True)
+    da = si.normal(50, 1, x.shape, bf16=True)
+    a = dev(x)
+    glue.leaky_relu_fwd(a)
+    ref = ou._lrelu(x.astype(np.float64))
+    assert np.max(np.abs(host(a) - ref)) <= 2 ** -8 * np.max(np.abs(ref))
+    g = dev(da)
+    glue.leaky_relu_bwd(g, a)
+    refg = ou._lrelu_grad(x.astype(np.float64), da.astype(np.float64))
+    assert np.max(np.abs(host(g) - refg)) <= 2 ** -8 * np.max(np.abs(refg))
+
+
+def test_concat_split_add(glue):
+    a = si.normal(50, 2, (2, 3, 4, 5, 32), bf16=True)
+    b = si.normal(50, 3, (2, 3, 4, 5, 64), bf16=True)
+    out = torch.empty((2, 3, 4, 5, 96), dtype=torch.bfloat16, device="cuda")
+    glue.concat_channels(dev(a), dev(b), out)
+    assert np.array_equal(host(out), np.concatenate([a, b], axis=-1).astype(np.float64))
+    a2, b2 = torch.empty_like(dev(a)), torch.empty_like(dev(b))
+    glue.split_channels(out, a2, b2)
+    assert np.array_equal(host(a2), a.astype(np.float64)) and np.array_equal(host(b2), b.astype(np.float64))
+    c = si.normal(50, 4, a.shape, bf16=True)
+    s = dev(a)
+    glue.add_inplace(s, dev(c))
+    ref = a.astype(np.float64) + c.astype(np.float64)
+    assert np.max(np.abs(host(s) - ref)) <= 2 ** -8 * np.max(np.abs(ref))
+
+
+@pytest.mark.parametrize("vol", [8, 24])
+def test_dice_loss_and_gradient(glue, vol):
+    N = 2
+    logits = si.normal(50, 5, (N, vol, vol, vol, 3), std=2.0, bf16=True)
+    labels = si.ellipsoid_labels(50, 6, N, vol)
+    loss_ref, grad_ref = ou.dice_loss(logits.astype(np.float64), labels)
+    lg, lb = dev(logits), torch.from_numpy(labels).cuda()
+    ws = glue.dice_workspace()
+    sums = torch.empty(9, dtype=torch.float32, device="cuda")
+    loss = torch.empty(1, dtype=torch.float32, device="cuda")
+    glue.dice_loss(lg, lb, ws, sums, loss)
+    assert abs(float(loss.item()) - loss_ref) <= 1e-5
+    loss2 = torch.empty(1, dtype=torch.float32, device="cuda")
+    glue.dice_loss(lg, lb, ws, sums, loss2)
+    assert loss2.item() == loss.item()            # fixed reduction order
+    d = torch.empty_like(lg)
+    glue.dice_grad(lg, lb, sums, d)
+    err = np.max(np.abs(host(d) - grad_ref)) / np.max(np.abs(grad_ref))
+    assert err <= 1e-2, err
+
+
+def test_sgd_update(glue):
+    rng = np.random.default_rng(7)
+    w = rng.standard_normal(1000).astype(np.float32)
+    dw = rng.standard_normal(1000).astype(np.float32)
+    w32, d32 = torch.from_numpy(w).cuda(), torch.from_numpy(dw).cuda()
+    w16 = torch.empty(1000, dtype=torch.bfloat16, device="cuda")
+    glue.sgd_update(w32, d32, w16, 0.125)
+    ref = w - np.float32(0.125) * dw
+    assert np.allclose(w32.cpu().numpy(), ref, rtol=1e-6, atol=1e-7)
+    assert np.array_equal(w16.float().cpu().numpy(), si.bf16_round(w32.cpu().numpy()))
