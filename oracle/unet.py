@@ -20,6 +20,23 @@ SLOPE = 0.01
 DICE_EPS = 1e-5
 
 
+def exact(a):
+    return a
+
+
+def bf16(a):
+    """Values rounded to the nearest bfloat16 (ties to even), returned as float64.
+    Passed as `q` to forward/backward it puts the step's storage roundings where
+    the bf16 pipeline has them (every activation and activation gradient that
+    is written to memory), so that the sign decisions of the LeakyReLU are
+    taken on the same numbers on both sides of a comparison; the sums inside a
+    convolution, the loss and the weight gradients stay in float64."""
+    f = np.ascontiguousarray(a, dtype=np.float64).astype(np.float32)
+    u = f.view(np.uint32)
+    r = (u + (np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1)))) & np.uint32(0xFFFF0000)
+    return r.view(np.float32).astype(np.float64)
+
+
 def _lrelu(z):
     return np.where(z > 0, z, SLOPE * z)
 
@@ -28,10 +45,11 @@ def _lrelu_grad(z, da):
     return np.where(z > 0, da, SLOPE * da)
 
 
-def forward(x, weights, channels):
+def forward(x, weights, channels, q=exact):
     """x [N, V, V, V, Cin] float64; weights in the order of
-    synth_inputs.unet_weight_shapes.  Returns (logits, saved) where saved holds
-    what the backward pass needs."""
+    synth_inputs.unet_weight_shapes; q: rounding applied to every tensor the
+    step stores (exact = none).  Returns (logits, saved) where saved holds what
+    the backward pass needs."""
     L = len(channels)
     N, V = x.shape[0], x.shape[1]
     it = iter(weights)
@@ -41,8 +59,8 @@ def forward(x, weights, channels):
     def conv(a, w, vol, s):
         cout, cin = w.shape[0], w.shape[4]
         g = oc.shape(N, vol, vol, vol, cin, cout, 3, s, 1)
-        z = oc.fwd(g, a, w)
-        return _lrelu(z), (g, a, w, z)
+        z = q(oc.fwd(g, a, w))
+        return q(_lrelu(z)), (g, a, w, z)
 
     for l in range(L):
         a, r1 = conv(a, next(it), vol, 1 if l == 0 else 2)
@@ -56,7 +74,7 @@ def forward(x, weights, channels):
         w_up = next(it)
         vol *= 2
         g = oc.shape(N, vol, vol, vol, channels[l], channels[l + 1], 2, 2, 0)
-        u = oc.dgrad(g, a, w_up)            # transposed convolution = data gradient of the k2/s2 convolution
+        u = q(oc.dgrad(g, a, w_up))         # transposed convolution = data gradient of the k2/s2 convolution
         rup = (g, a, w_up)
         a = np.concatenate([u, saved["skip"][l]], axis=-1)
         a, r1 = conv(a, next(it), vol, 1)
@@ -64,7 +82,7 @@ def forward(x, weights, channels):
         saved["dec"][l] = (rup, r1, r2)
     w_head = next(it)
     g = oc.shape(N, vol, vol, vol, channels[0], w_head.shape[0], 1, 1, 0)
-    logits = oc.fwd(g, a, w_head)
+    logits = q(oc.fwd(g, a, w_head))
     saved["head"] = (g, a, w_head)
     return logits, saved
 
@@ -85,21 +103,26 @@ def dice_loss(logits, labels):
     return loss, dp * p * (1.0 - p)
 
 
-def backward(saved, dlogits, channels):
+def backward(saved, dlogits, channels, q=exact, trace=None):
     """Weight gradients in the order of the weights (the gradient with respect
-    to the network input is not formed)."""
+    to the network input is not formed).  q as in forward."""
     L = len(channels)
     dw = {}
 
     def conv_bwd(rec, da, name, need_dx=True):
         g, a, w, z = rec
-        dz = _lrelu_grad(z, da)
+        dz = q(_lrelu_grad(z, da))
+        if trace is not None:
+            trace[name + ".dz"] = dz
         dw[name] = oc.wgrad(g, a, dz)
-        return oc.dgrad(g, dz, w) if need_dx else None
+        return q(oc.dgrad(g, dz, w)) if need_dx else None
 
     g, a, w = saved["head"]
+    dlogits = q(dlogits)
+    if trace is not None:
+        trace["dlogits"] = dlogits
     dw["head"] = oc.wgrad(g, a, dlogits)
-    da = oc.dgrad(g, dlogits, w)
+    da = q(oc.dgrad(g, dlogits, w))
     dskip = {}
     for l in range(0, L - 1):
         rup, r1, r2 = saved["dec"][l]
@@ -109,10 +132,10 @@ def backward(saved, dlogits, channels):
         d_up, dskip[l] = da[..., :c], da[..., c:]
         g, a_small, w_up = rup
         dw[f"dec{l}.up"] = oc.wgrad(g, d_up, a_small)   # roles: x := gradient of the upsampled map, dy := the small input
-        da = oc.fwd(g, d_up, w_up)
+        da = q(oc.fwd(g, d_up, w_up))
     for l in range(L - 1, -1, -1):
         if l < L - 1:
-            da = da + dskip[l]
+            da = q(da + dskip[l])
         r1, r2 = saved["enc"][l]
         da = conv_bwd(r2, da, f"enc{l}.conv2")
         da = conv_bwd(r1, da, f"enc{l}.conv1", need_dx=l > 0)
@@ -123,10 +146,10 @@ def backward(saved, dlogits, channels):
     return [dw[k] for k in order]
 
 
-def train_step(x, labels, weights, channels, lr):
+def train_step(x, labels, weights, channels, lr, q=exact):
     """One SGD step: (loss, weight gradients, updated weights)."""
     w64 = [np.asarray(w, dtype=np.float64) for w in weights]
-    logits, saved = forward(x, w64, channels)
+    logits, saved = forward(x, w64, channels, q)
     loss, dlogits = dice_loss(logits, labels)
-    grads = backward(saved, dlogits, channels)
+    grads = backward(saved, dlogits, channels, q)
     return loss, grads, [w - lr * g for w, g in zip(w64, grads)]

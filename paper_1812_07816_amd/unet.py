@@ -1,0 +1,337 @@
+"""One training step of the 3D U-Net with data swapping (host-side orchestration).
+
+Every arithmetic step is a call into libmi3d.so: the convolutions
+(conv3d_fwd / dgrad / wgrad; the 2x2x2 stride-2 transposed convolution is the
+data gradient of a 2x2x2 / stride-2 convolution with roles swapped), LeakyReLU,
+channel concatenation, sigmoid + soft Dice, SGD.  Saved feature maps (the
+inputs of the convolutions, Section 3.1 of the paper) live in the swap engine's
+arena and are moved to pinned host memory and back according to its plan.
+
+Network: L encoder levels of two 3x3x3 convolutions (the first of each level
+but the top with stride 2), decoder levels of up-sampling, concatenation
+[upsampled, skip] and two 3x3x3 convolutions, a 1x1x1 head; LeakyReLU after
+every 3x3x3 convolution; no bias, no normalisation.
+
+Op timeline for the planner: forward ops in program order, then one backward
+op per forward op in reverse order (backward op of forward op f is
+n_fwd + (n_fwd - 1 - f)).
+"""
+import torch
+
+from . import conv3d as mc
+from . import glue
+from . import swap as sw
+
+SLOPE = 0.01
+
+
+def _numel(shape):
+    n = 1
+    for v in shape:
+        n *= v
+    return n
+
+
+class _Saved:
+    """A tensor produced in the forward pass and needed again in the backward pass."""
+
+    def __init__(self, sid, shape, produce, tag):
+        self.id, self.shape, self.bytes = sid, tuple(shape), _numel(shape) * 2
+        self.produce, self.last_fwd, self.tag = produce, produce, tag
+        self.bwd_ops = []          # backward ops that read it
+        self.ptr, self.view = None, None
+
+
+class UNetStep:
+    def __init__(self, N, vol, channels, weights, x, labels, lr=1e-2, in_ch=4, classes=3, swap=True,
+                 budget_bytes=None, lookahead=2, policy=sw.POLICY_BUDGET, n_tensors=-1, exclude_tags=0):
+        """weights: list of float32 CPU tensors/arrays (bf16-exact start values) in the order enc convs,
+        (dec up, conv1, conv2) from the deepest decoder level up, head; x: bf16 CUDA [N,vol,vol,vol,in_ch];
+        labels: uint8 CUDA [N,vol,vol,vol,classes]."""
+        self.N, self.vol, self.ch, self.L = N, vol, list(channels), len(channels)
+        self.lr, self.classes, self.swap_on = lr, classes, swap
+        self.x_in, self.labels = x, labels
+        L, ch = self.L, self.ch
+        # ---- parameters: flat fp32 master / gradient buffers and a flat bf16 working copy, 64-element aligned views
+        offs, total = [], 0
+        for w in weights:
+            offs.append(total)
+            total += (_numel(w.shape) + 63) // 64 * 64
+        self.w32 = torch.zeros(total, dtype=torch.float32, device="cuda")
+        self.dw32 = torch.zeros(total, dtype=torch.float32, device="cuda")
+        self.w16 = torch.zeros(total, dtype=torch.bfloat16, device="cuda")
+        self.w, self.dw, self.wm = [], [], []
+        for w, o in zip(weights, offs):
+            n = _numel(w.shape)
+            wt = torch.as_tensor(w, dtype=torch.float32).reshape(-1).cuda()
+            self.w32[o:o + n].copy_(wt)
+            self.w16[o:o + n].copy_(wt.to(torch.bfloat16))
+            self.w.append(self.w16[o:o + n].view(tuple(w.shape)))
+            self.dw.append(self.dw32[o:o + n].view(tuple(w.shape)))
+            self.wm.append(self.w32[o:o + n].view(tuple(w.shape)))
+        # ---- forward program
+        self.ops, self.saved = [], []
+        self.flops = 0.0
+
+        def new_saved(shape, tag):
+            s = _Saved(len(self.saved), shape, len(self.ops), tag)
+            self.saved.append(s)
+            return s
+
+        def conv_op(name, src, vol_in, cin, cout, s, widx, tag, first=False):
+            d = mc.make_desc(N, vol_in, vol_in, vol_in, cin, cout, 3, s, 1, torch.bfloat16)
+            vo = vol_in // s
+            out = new_saved((N, vo, vo, vo, cout), tag)
+            src.last_fwd = len(self.ops)
+            self.ops.append(dict(kind="conv", name=name, desc=d, src=src, out=out, w=widx, first=first))
+            fl = 2.0 * N * vo ** 3 * 27 * cin * cout
+            self.flops += fl * (2 if first else 3)
+            return out, vo
+
+        xs = _Saved(0, (N, vol, vol, vol, in_ch), 0, sw.TAG_INPUT)
+        self.saved.append(xs)
+        self.ops.append(dict(kind="input", name="input", out=xs))
+        a, v, wi = xs, vol, 0
+        skips = []
+        for l in range(L):
+            a, v = conv_op(f"enc{l}.conv1", a, v, in_ch if l == 0 else ch[l - 1], ch[l], 1 if l == 0 else 2, wi, sw.TAG_ENCODER, first=(l == 0)); wi += 1
+            a, v = conv_op(f"enc{l}.conv2", a, v, ch[l], ch[l], 1, wi, sw.TAG_ENCODER); wi += 1
+            if l < L - 1:
+                skips.append(a)
+        for l in range(L - 2, -1, -1):
+            v *= 2
+            d = mc.make_desc(N, v, v, v, ch[l], ch[l + 1], 2, 2, 0, torch.bfloat16)  # the convolution whose dgrad is the up-sampling
+            a.last_fwd = len(self.ops)
+            self.ops.append(dict(kind="up", name=f"dec{l}.up", desc=d, src=a, w=wi, shape=(N, v, v, v, ch[l]))); wi += 1
+            self.flops += 3 * 2.0 * N * (v // 2) ** 3 * 8 * ch[l] * ch[l + 1]
+            cat = new_saved((N, v, v, v, 2 * ch[l]), sw.TAG_DECODER)
+            skips[l].last_fwd = len(self.ops)
+            self.ops.append(dict(kind="cat", name=f"dec{l}.cat", skip=skips[l], out=cat, c=ch[l]))
+            a, _ = conv_op(f"dec{l}.conv1", cat, v, 2 * ch[l], ch[l], 1, wi, sw.TAG_DECODER); wi += 1
+            a, _ = conv_op(f"dec{l}.conv2", a, v, ch[l], ch[l], 1, wi, sw.TAG_DECODER); wi += 1
+        d = mc.make_desc(N, v, v, v, ch[0], classes, 1, 1, 0, torch.bfloat16)
+        logits = new_saved((N, v, v, v, classes), sw.TAG_HEAD)
+        a.last_fwd = len(self.ops)
+        self.ops.append(dict(kind="head", name="head", desc=d, src=a, out=logits, w=wi))
+        self.flops += 3 * 2.0 * N * v ** 3 * ch[0] * classes
+        logits.last_fwd = len(self.ops)
+        self.ops.append(dict(kind="loss", name="loss", src=logits))
+        self.n_fwd = len(self.ops)
+        self.n_ops = 2 * self.n_fwd
+        # backward readers: conv f reads its input (weight gradient) and its output (LeakyReLU derivative); up and head
+        # read their input (weight gradient); the loss reads the logits
+        for f, op in enumerate(self.ops):
+            b = self.bwd_op(f)
+            if op["kind"] == "conv":
+                op["src"].bwd_ops.append(b)
+                op["out"].bwd_ops.append(b)
+            elif op["kind"] in ("up", "head"):
+                op["src"].bwd_ops.append(b)
+            elif op["kind"] == "loss":
+                op["src"].bwd_ops.append(b)
+        # ---- workspaces and small buffers
+        ws_bytes = 256
+        for op in self.ops:
+            if "desc" in op:
+                ws_bytes = max(ws_bytes, max(mc.workspace_bytes(op["desc"], p) for p in range(3)) + 256)
+        self.ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+        self.dice_ws = glue.dice_workspace(classes)
+        self.sums = torch.zeros(3 * classes, dtype=torch.float32, device="cuda")
+        self.loss = torch.zeros(1, dtype=torch.float32, device="cuda")
+        # ---- swap engine
+        self.engine = None
+        if swap:
+            budget = (1 << 62) if budget_bytes is None else int(budget_bytes)
+            sizes = [s.bytes for s in self.saved]
+            pool = sum((b + 4095) // 4096 * 4096 for b in sizes) + 4096
+            arena_bytes = sum((b + 255) // 256 * 256 for b in sizes) + 4096
+            self.arena = torch.empty(arena_bytes, dtype=torch.uint8, device="cuda")
+            self.engine = e = sw.SwapEngine(budget_bytes=budget, host_pool_bytes=pool, arena=self.arena, lookahead=lookahead,
+                                            policy=policy, n_tensors=n_tensors, exclude_tags=exclude_tags)
+            e.set_timeline(self.n_fwd, self.n_ops)
+            for s in self.saved:
+                e.register(s.id, s.bytes, s.produce, s.last_fwd, min(s.bwd_ops), max(s.bwd_ops), s.tag)
+            for op in range(self.n_ops):
+                e.set_transient(op, self._transient(op))
+            self.plan_status = e.plan(allow_over_budget=True)
+            self.planned = [e.is_planned(s.id) for s in self.saved]
+            self.prefetch = [e.prefetch_op(s.id) for s in self.saved]
+        else:
+            self.planned = [False] * len(self.saved)
+            self.prefetch = [-1] * len(self.saved)
+            self.plan_status = 0
+
+    def bwd_op(self, f):
+        return self.n_fwd + (self.n_fwd - 1 - f)
+
+    def _transient(self, op):
+        """Device bytes an op holds besides saved tensors: parameters, workspace, labels, and the gradient tensors
+        alive during it (the gradient pair of the layer, plus the skip gradients waiting for the encoder)."""
+        fixed = self.w32.numel() * 10 + self.ws.numel() + self.labels.numel()
+        if op < self.n_fwd:
+            o = self.ops[op]
+            return fixed + (_numel(o["shape"]) * 2 if o["kind"] == "up" else 0)
+        f = self.n_fwd - 1 - (op - self.n_fwd)
+        o = self.ops[f]
+        live = 0
+        if "out" in o:
+            live += o["out"].bytes
+        if "src" in o:
+            live += o["src"].bytes
+        # skip gradients produced by decoder levels already walked back and not yet consumed by the encoder
+        for g, oo in enumerate(self.ops):
+            if oo["kind"] == "cat" and g >= f:
+                enc_reader = min(oo["skip"].bwd_ops)   # conv1 of the next encoder level reads the skip tensor
+                if enc_reader >= op:
+                    live += oo["skip"].bytes
+        return fixed + live
+
+    # ---- storage of saved tensors
+    def _view(self, ptr, shape):
+        off = ptr - self.arena.data_ptr()
+        return self.arena[off:off + _numel(shape) * 2].view(torch.bfloat16).view(shape)
+
+    def _produce(self, s):
+        if self.engine is None:
+            s.view = torch.empty(s.shape, dtype=torch.bfloat16, device="cuda")
+        else:
+            s.ptr = self.engine.alloc(s.bytes)
+            s.view = self._view(s.ptr, s.shape)
+        return s.view
+
+    def _after_fwd_op(self, f):
+        """Swap-outs of tensors produced by op f, releases of tensors whose last forward reader was op f."""
+        if self.engine is None:
+            return
+        for s in self.saved:
+            if not self.planned[s.id]:
+                continue
+            if s.produce == f:
+                self.engine.swap_out(s.id, s.ptr)
+            if s.last_fwd == f:
+                self.engine.release(s.id)
+                s.ptr, s.view = None, None
+
+    def _before_bwd_op(self, op):
+        if self.engine is None:
+            return
+        for s in self.saved:
+            if self.planned[s.id] and self.prefetch[s.id] == op:
+                s.ptr = self.engine.alloc(s.bytes)
+                self.engine.swap_in(s.id, s.ptr)
+                s.view = self._view(s.ptr, s.shape)
+
+    def _need(self, s):
+        if self.engine is not None and self.planned[s.id] and not getattr(s, "_waited", False):
+            self.engine.wait_in(s.id)
+            s._waited = True
+        return s.view
+
+    def _after_bwd_op(self, op):
+        for s in self.saved:
+            if max(s.bwd_ops) == op:
+                if self.engine is not None:
+                    if self.planned[s.id]:
+                        self.engine.done(s.id)
+                    self.engine.free(s.ptr)
+                s.ptr, s.view, s._waited = None, None, False
+
+    # ---- the step
+    def run(self, update=True, trace=None):
+        """trace: optional dict that receives copies of intermediate tensors (tests)."""
+        e = self.engine
+        if e is not None:
+            e.reset_step()
+        bf = torch.bfloat16
+        # forward
+        for f, op in enumerate(self.ops):
+            k = op["kind"]
+            if k == "input":
+                self._produce(op["out"]).copy_(self.x_in)
+                if trace is not None:
+                    trace["input.a"] = op["out"].view.clone()
+            elif k == "conv":
+                out = self._produce(op["out"])
+                mc.conv3d_fwd(op["desc"], op["src"].view, self.w[op["w"]], out, self.ws)
+                glue.leaky_relu_fwd(out, SLOPE)
+                if trace is not None:
+                    trace[op["name"] + ".a"] = out.clone()
+            elif k == "up":
+                op["u"] = torch.empty(op["shape"], dtype=bf, device="cuda")
+                mc.conv3d_dgrad(op["desc"], op["src"].view, self.w[op["w"]], op["u"], self.ws)
+                if trace is not None:
+                    trace[op["name"] + ".a"] = op["u"].clone()
+            elif k == "cat":
+                up = self.ops[f - 1]
+                glue.concat_channels(up["u"], op["skip"].view, self._produce(op["out"]))
+                up["u"] = None
+                if trace is not None:
+                    trace[op["name"] + ".a"] = op["out"].view.clone()
+            elif k == "head":
+                mc.conv3d_fwd(op["desc"], op["src"].view, self.w[op["w"]], self._produce(op["out"]), self.ws)
+                if trace is not None:
+                    trace["head.a"] = op["out"].view.clone()
+            elif k == "loss":
+                glue.dice_loss(op["src"].view, self.labels, self.dice_ws, self.sums, self.loss)
+            self._after_fwd_op(f)
+        # backward
+        da = None              # gradient with respect to the output of the op being walked back
+        dskip = {}
+        for f in range(self.n_fwd - 1, -1, -1):
+            op, b = self.ops[f], self.bwd_op(f)
+            self._before_bwd_op(b)
+            k = op["kind"]
+            if trace is not None and da is not None:
+                trace[op["name"] + ".dout"] = da.clone()
+            if k == "loss":
+                lg = self._need(op["src"])
+                da = torch.empty(op["src"].shape, dtype=bf, device="cuda")
+                glue.dice_grad(lg, self.labels, self.sums, da)
+            elif k == "head":
+                a = self._need(op["src"])
+                mc.conv3d_wgrad(op["desc"], a, da, self.dw[op["w"]], self.ws)
+                nxt = torch.empty(op["src"].shape, dtype=bf, device="cuda")
+                mc.conv3d_dgrad(op["desc"], da, self.w[op["w"]], nxt, self.ws)
+                da = nxt
+            elif k == "conv":
+                glue.leaky_relu_bwd(da, self._need(op["out"]), SLOPE)
+                if trace is not None:
+                    trace[op["name"] + ".dz"] = da.clone()
+                mc.conv3d_wgrad(op["desc"], self._need(op["src"]), da, self.dw[op["w"]], self.ws)
+                if op["first"]:
+                    da = None      # the network input needs no gradient
+                else:
+                    nxt = torch.empty(op["src"].shape, dtype=bf, device="cuda")
+                    mc.conv3d_dgrad(op["desc"], da, self.w[op["w"]], nxt, self.ws)
+                    da = nxt
+                    if op["src"].id in dskip:          # the input is also a skip connection: add its second gradient
+                        if trace is not None:
+                            trace[op["name"] + ".dgrad"] = da.clone()
+                        glue.add_inplace(da, dskip.pop(op["src"].id))
+            elif k == "cat":
+                c = op["c"]
+                shp = op["out"].shape[:-1]
+                d_up = torch.empty(shp + (c,), dtype=bf, device="cuda")
+                d_sk = torch.empty(shp + (c,), dtype=bf, device="cuda")
+                glue.split_channels(da, d_up, d_sk)
+                dskip[op["skip"].id] = d_sk
+                da = d_up
+                if trace is not None:
+                    trace[op["name"] + ".dskip"] = d_sk.clone()
+            elif k == "up":
+                a = self._need(op["src"])
+                # roles: x := gradient of the up-sampled map, dy := the small input
+                mc.conv3d_wgrad(op["desc"], da, a, self.dw[op["w"]], self.ws)
+                nxt = torch.empty(op["src"].shape, dtype=bf, device="cuda")
+                mc.conv3d_fwd(op["desc"], da, self.w[op["w"]], nxt, self.ws)
+                da = nxt
+            if trace is not None and da is not None:
+                trace[op["name"] + ".din"] = da.clone()
+            self._after_bwd_op(b)
+        if update:
+            glue.sgd_update(self.w32, self.dw32, self.w16, self.lr)
+
+    def close(self):
+        if self.engine is not None:
+            self.engine.close()
+            self.engine = None

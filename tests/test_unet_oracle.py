@@ -84,3 +84,25 @@ def test_label_generator_shape_and_determinism():
     b = si.ellipsoid_labels(5, 7, 2, 16)
     assert a.dtype == np.uint8 and a.shape == (2, 16, 16, 16, 3)
     assert np.array_equal(a, b) and set(np.unique(a)) <= {0, 1} and a.any()
+
+
+def test_bf16_rounding_helper():
+    # ties to even on the 16th mantissa bit; exact values unchanged; matches the shared input rounding
+    a = np.array([1.0, 1.00390625, 1.01171875, -3.0e-5, 123456.789, 0.0])
+    r = ou.bf16(a)
+    assert r[0] == 1.0 and r[1] == 1.0 and r[2] == 1.015625          # 1 + 2^-8 ties down, 1 + 3 * 2^-8 ties up
+    assert np.array_equal(r.astype(np.float32), si.bf16_round(a.astype(np.float32)))
+    assert np.all(np.abs(r - a) <= np.abs(a) * 2.0 ** -8)
+
+
+def test_rounded_step_stays_close_to_exact_step():
+    channels = [4, 8]
+    rng = np.random.default_rng(5)
+    ws = [si.bf16_round((rng.standard_normal(shp) * 0.3).astype(np.float32)) for _, shp in si.unet_weight_shapes(channels, in_ch=2)]
+    x = si.bf16_round(rng.standard_normal((1, 8, 8, 8, 2)).astype(np.float32))
+    t = (rng.random((1, 8, 8, 8, 3)) < 0.4).astype(np.uint8)
+    l0, g0, _ = ou.train_step(x, t, ws, channels, 0.0)
+    l1, g1, _ = ou.train_step(x, t, ws, channels, 0.0, q=ou.bf16)
+    assert abs(l0 - l1) < 1e-2 * abs(l0)
+    for a, b in zip(g0, g1):
+        assert np.sum(a * b) / np.sqrt(np.sum(a * a) * np.sum(b * b)) > 0.98
