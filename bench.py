@@ -108,6 +108,62 @@ def unet_layer_table(N):
     return {"layers": rows, "total_ms": tot_ms, "total_tflops": tot_flop / tot_ms / 1e9}
 
 
+def unet_train_step(steps=3, warmup=1):
+    """Full training step of the 5-level U-Net at 192^3, N = 2 (forward, soft Dice, backward, SGD; every step through
+    the C ABI) with the swap engine: unswapped, at the 16 GiB budget, and at tighter budgets that force swapping."""
+    import numpy as np
+    import torch
+    import synth_inputs as si
+    from paper_1812_07816_amd import unet
+
+    N, vol, ch = 2, 192, [32, 64, 128, 256, 320]
+    x = si.normal(5, 0, (N, vol, vol, vol, 4), bf16=True)
+    labels = torch.from_numpy(si.ellipsoid_labels(5, 1, N, vol)).cuda()
+    ws = si.unet_weights(5, ch)
+    xd = torch.from_numpy(si.bf16_bits(x).view(np.int16)).cuda().view(torch.bfloat16).reshape(x.shape)
+
+    def timed(step):
+        for _ in range(warmup):
+            step.run()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            step.run()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / steps
+
+    plain = unet.UNetStep(N, vol, ch, ws, xd, labels, swap=False)
+    plain.run(update=False)          # gradients at the start weights: reference bits for the swapped runs
+    torch.cuda.synchronize()
+    ref = plain.dw32.clone()
+    ms0 = timed(plain)
+    flops = plain.flops
+    out = {"workload": "5-level 3D U-Net at 192^3, N=2, bf16: forward, sigmoid + soft Dice, backward, SGD; 23 convolution layers",
+           "ms_per_step_no_swap": ms0, "conv_tflops_no_swap": flops / ms0 / 1e9, "conv_flop_per_step": flops,
+           "loss": float(plain.loss.item()), "budgets": []}
+    del plain
+    torch.cuda.empty_cache()
+    for gib, la in ((16, 2), (8, 16), (7, 12)):
+        st = unet.UNetStep(N, vol, ch, ws, xd, labels, swap=True, budget_bytes=int(gib * 2 ** 30), lookahead=la)
+        st.run(update=False)
+        torch.cuda.synchronize()
+        same = bool(torch.equal(st.dw32, ref))
+        ms = timed(st)
+        s = st.engine.stats()
+        exposed = max(0.0, ms - ms0)
+        out["budgets"].append({"budget_gib": gib, "lookahead": la, "plan_feasible": st.plan_status == 0, "ms_per_step": ms,
+                               "n_swapped": s["n_planned"], "bytes_out": s["bytes_out"], "bit_identical_to_unswapped": same,
+                               "transfer_ms": s["busy_ms"], "exposed_ms": exposed,
+                               "hidden_frac": (1.0 - exposed / s["busy_ms"]) if s["busy_ms"] > 0 else None,
+                               "planned_peak_bytes": s["planned_peak_bytes"], "unswapped_peak_bytes": s["unswapped_peak_bytes"],
+                               "d2h_gbs": s["bytes_out"] / s["copy_ms_out"] / 1e6 if s["copy_ms_out"] else None,
+                               "h2d_gbs": s["bytes_in"] / s["copy_ms_in"] / 1e6 if s["copy_ms_in"] else None})
+        st.close()
+        del st
+        torch.cuda.empty_cache()
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -121,6 +177,7 @@ def main():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="first run three 256 MiB device-to-device copies: dispatches of known size against which "
                          "rocprofv3's FETCH_SIZE / WRITE_SIZE readings are scaled")
+    ap.add_argument("--no-unet-step", action="store_true", help="skip the full N=2 U-Net training step (adds ~40 s)")
     ap.add_argument("--unet-layers", action="store_true",
                     help="also time fwd/dgrad/wgrad of every Conv3D layer of the 5-level U-Net at 192^3 (adds ~20 s)")
     args = ap.parse_args()
@@ -286,6 +343,9 @@ def main():
         "kernels": [{k: (round(v, 4) if isinstance(v, float) else v) for k, v in r.items() if k not in ("flop", "bytes")} for r in per],
         "roofline": roof,
     }
+    if not args.no_unet_step:
+        torch.cuda.empty_cache()
+        out["unet_step"] = unet_train_step()
     if args.unet_layers:
         out["unet_layers"] = unet_layer_table(N)
     if not args.no_cpu_baseline:
