@@ -215,6 +215,15 @@ int mi3d_swap_register(mi3d_swap_engine *e, int id, size_t bytes, int produce_op
                        int bwd_first_use_op, int bwd_last_use_op, unsigned tags);
 /* Device bytes op `op` holds besides saved tensors (gradients, workspaces, weights). */
 int mi3d_swap_set_transient(mi3d_swap_engine *e, int op, size_t bytes);
+
+/* Optional: measured duration of every op of the timeline (ms, n values) and
+ * the host-link rate (GB/s).  With them mi3d_swap_plan schedules the swap-ins
+ * by time instead of by op count: the copies share one stream, so they are
+ * laid out back to back, latest use first, each ending before its tensor's
+ * first backward use (duration = bytes / rate + 15 % + 50 us) and issued at
+ * the latest op that starts early enough; `lookahead` stays the minimum
+ * distance in ops.  n = 0 returns to the op-count rule.  Invalidates the plan. */
+int mi3d_swap_set_op_times(mi3d_swap_engine *e, const float *ms, int n, float link_gbs);
 /* Host-only: chooses the swap set.  MI3D_ERR_OVER_BUDGET if even the chosen
  * policy's full set leaves the modelled peak above budget_bytes (the plan is
  * still filled in, so callers may inspect it), MI3D_ERR_HOST_POOL if the set

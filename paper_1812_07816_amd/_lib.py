@@ -57,6 +57,7 @@ SIGNATURES = {
     "mi3d_swap_destroy": (_i, [_vp]),
     "mi3d_swap_set_timeline": (_i, [_vp, _i, _i]),
     "mi3d_swap_register": (_i, [_vp, _i, _sz, _i, _i, _i, _i, _u]),
+    "mi3d_swap_set_op_times": (_i, [_vp, ctypes.POINTER(ctypes.c_float), _i, ctypes.c_float]),
     "mi3d_swap_set_transient": (_i, [_vp, _i, _sz]),
     "mi3d_swap_plan": (_i, [_vp]),
     "mi3d_swap_is_planned": (_i, [_vp, _i]),

@@ -29,10 +29,18 @@ struct Tensor {
     Copy out, in;
 };
 
+// An event a freed block waits for.  copy: recorded on one of the engine's copy streams (behind a swap-out that
+// still reads the block); such a wait can take a whole transfer, a wait on a compute-stream event is free for
+// the next kernel of that stream.
+struct Pending {
+    std::shared_ptr<void> ev;
+    bool copy;
+};
+
 struct ArenaBlock {
     size_t off, size;
     bool free;
-    std::vector<std::shared_ptr<void>> pending;  // events that must fire before reuse
+    std::vector<Pending> pending;  // events that must fire before reuse
 };
 
 }  // namespace
@@ -41,6 +49,8 @@ struct mi3d_swap_engine {
     mi3d_swap_config cfg;
     std::map<int, Tensor> tensors;
     std::vector<size_t> transient;
+    std::vector<float> op_ms;   // measured op durations (optional): swap-ins are then scheduled by time
+    float link_gbs = 0.f;
     int n_fwd_ops = 0, n_ops = 0;
     bool have_plan = false;
     PlanResult plan_res;
@@ -102,10 +112,18 @@ bool in_arena(const mi3d_swap_engine* e, const void* p) {
     return b && (const char*)p >= b && (const char*)p < b + e->cfg.arena_bytes;
 }
 
+bool waits_for_copy(const ArenaBlock& b) {
+    for (const Pending& p : b.pending)
+        if (p.copy) return true;
+    return false;
+}
+
+// Merges neighbouring free blocks.  A block that still waits for a copy is kept apart, so that an allocation
+// from its neighbour does not inherit that wait; it is merged once the copy's event has fired (see alloc).
 void coalesce(mi3d_swap_engine* e) {
     std::vector<ArenaBlock>& bl = e->blocks;
     for (size_t i = 0; i + 1 < bl.size();) {
-        if (bl[i].free && bl[i + 1].free) {
+        if (bl[i].free && bl[i + 1].free && !waits_for_copy(bl[i]) && !waits_for_copy(bl[i + 1])) {
             bl[i].size += bl[i + 1].size;
             for (auto& ev : bl[i + 1].pending) bl[i].pending.push_back(ev);
             bl.erase(bl.begin() + i + 1);
@@ -115,7 +133,7 @@ void coalesce(mi3d_swap_engine* e) {
     }
 }
 
-int arena_free(mi3d_swap_engine* e, const void* ptr, std::vector<std::shared_ptr<void>> pending) {
+int arena_free(mi3d_swap_engine* e, const void* ptr, std::vector<Pending> pending) {
     size_t off = (const char*)ptr - (const char*)e->cfg.dev_arena;
     for (ArenaBlock& b : e->blocks) {
         if (b.off == off && !b.free) {
@@ -236,6 +254,16 @@ int mi3d_swap_set_transient(mi3d_swap_engine* e, int op, size_t bytes) {
     return MI3D_OK;
 }
 
+int mi3d_swap_set_op_times(mi3d_swap_engine* e, const float* ms, int n, float link_gbs) {
+    if (!e || n < 0 || (n > 0 && (!ms || !(link_gbs > 0.f)))) return MI3D_ERR_INVALID_ARG;
+    for (int i = 0; i < n; ++i)
+        if (!(ms[i] >= 0.f)) return MI3D_ERR_INVALID_ARG;
+    e->op_ms.assign(ms, ms + n);
+    e->link_gbs = link_gbs;
+    e->have_plan = false;
+    return MI3D_OK;
+}
+
 int mi3d_swap_plan(mi3d_swap_engine* e) {
     if (!e) return MI3D_ERR_INVALID_ARG;
     std::vector<PlanTensor> ts;
@@ -244,6 +272,8 @@ int mi3d_swap_plan(mi3d_swap_engine* e) {
     p.budget_bytes = e->cfg.budget_bytes;
     p.host_pool_bytes = e->cfg.host_pool_bytes;
     p.lookahead = e->cfg.lookahead;
+    p.op_ms = &e->op_ms;
+    p.link_gbs = e->link_gbs;
     p.policy = e->cfg.policy;
     p.n_tensors = e->cfg.n_tensors;
     p.exclude_tags = e->cfg.exclude_tags;
@@ -288,16 +318,20 @@ int mi3d_swap_alloc(mi3d_swap_engine* e, size_t bytes, void* stream, void** dev_
     for (ArenaBlock& b : e->blocks) {
         if (!b.free) continue;
         auto& pv = b.pending;
-        pv.erase(std::remove_if(pv.begin(), pv.end(), [](const std::shared_ptr<void>& ev) { return hipEventQuery((hipEvent_t)ev.get()) == hipSuccess; }), pv.end());
+        pv.erase(std::remove_if(pv.begin(), pv.end(), [](const Pending& p) { return hipEventQuery((hipEvent_t)p.ev.get()) == hipSuccess; }), pv.end());
     }
+    coalesce(e);
+    // first fit among blocks that do not wait for a copy (the host runs ahead of the device, so most freed
+    // blocks still carry an unfired compute-stream event: that wait costs nothing); a block behind a swap-out
+    // in flight is the last resort, since the allocating stream would stall for the rest of that transfer
     int pick = -1;
     for (int pass = 0; pass < 2 && pick < 0; ++pass)
         for (int i = 0; i < (int)e->blocks.size(); ++i) {
             const ArenaBlock& b = e->blocks[i];
-            if (b.free && b.size >= need && (pass == 1 || b.pending.empty())) { pick = i; break; }
+            if (b.free && b.size >= need && (pass == 1 || !waits_for_copy(b))) { pick = i; break; }
         }
     if (pick < 0) return MI3D_ERR_OVER_BUDGET;
-    for (auto& ev : e->blocks[pick].pending) HIP_TRY(hipStreamWaitEvent((hipStream_t)stream, (hipEvent_t)ev.get(), 0));
+    for (auto& p : e->blocks[pick].pending) HIP_TRY(hipStreamWaitEvent((hipStream_t)stream, (hipEvent_t)p.ev.get(), 0));
     ArenaBlock& b = e->blocks[pick];
     if (b.size > need) {
         ArenaBlock rest{b.off + need, b.size - need, true, b.pending};
@@ -319,7 +353,7 @@ int mi3d_swap_free(mi3d_swap_engine* e, void* dev_ptr, void* stream) {
     std::shared_ptr<void> ev;
     int st = record_shared(e, (hipStream_t)stream, &ev);
     if (st) return st;
-    return arena_free(e, dev_ptr, {ev});
+    return arena_free(e, dev_ptr, {Pending{ev, false}});
 }
 
 int mi3d_swap_out(mi3d_swap_engine* e, int id, const void* dev_src, void* producer_stream) {
@@ -353,7 +387,7 @@ int mi3d_swap_release(mi3d_swap_engine* e, int id, void* last_consumer_stream) {
         int st = record_shared(e, (hipStream_t)last_consumer_stream, &consumer);
         if (st) return st;
         if ((st = record_shared(e, e->s_out, &copy))) return st;  // s_out is in order: fires after this tensor's copy
-        if ((st = arena_free(e, t->dev_src, {consumer, copy}))) return st;
+        if ((st = arena_free(e, t->dev_src, {Pending{consumer, false}, Pending{copy, true}}))) return st;
     } else {
         HIP_TRY(hipStreamWaitEvent((hipStream_t)last_consumer_stream, t->out.done, 0));
     }

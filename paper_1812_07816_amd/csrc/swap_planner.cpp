@@ -30,24 +30,61 @@ static uint64_t peak(const std::vector<PlanTensor>& ts, const std::vector<size_t
     return best;
 }
 
+// Prefetch op by op count: `lookahead` ops before the first backward use, but never before the backward pass
+// starts or the forward use ends.
+static int prefetch_by_ops(const PlanTensor& t, const PlanParams& p) {
+    int pf = t.bwd_first_use_op - p.lookahead;
+    pf = std::max(pf, p.n_fwd_ops);
+    pf = std::max(pf, t.last_fwd_use_op + 1);
+    return std::min(pf, t.bwd_first_use_op);
+}
+
+// Prefetch ops by time for the planned tensors: the swap-ins share one copy stream, so they are laid out back
+// to back, latest use first: a copy must end by the start of its tensor's first backward use and by the start
+// of the copy scheduled after it; its duration is bytes / link rate plus 15 % and 50 us; it is issued at the
+// latest op that starts no later than that.  Never later than the op-count rule.
+static void prefetch_by_time(std::vector<PlanTensor>& ts, const PlanParams& p, int n_ops) {
+    const std::vector<float>& ms = *p.op_ms;
+    std::vector<double> start(n_ops + 1, 0.0);
+    for (int op = 0; op < n_ops; ++op) start[op + 1] = start[op] + (op < (int)ms.size() ? (double)ms[op] : 0.0);
+    std::vector<int> order;
+    for (int i = 0; i < (int)ts.size(); ++i)
+        if (ts[i].planned) order.push_back(i);
+    std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return ts[a].bwd_first_use_op > ts[b].bwd_first_use_op; });
+    double next_start = 1e300;
+    for (int i : order) {
+        PlanTensor& t = ts[i];
+        const double dur = (double)t.bytes / ((double)p.link_gbs * 1e6) * 1.15 + 0.05;
+        const double finish = std::min(start[std::min(t.bwd_first_use_op, n_ops)], next_start);
+        const double begin = finish - dur;
+        next_start = begin;
+        int pf = prefetch_by_ops(t, p);
+        while (pf > 0 && start[pf] > begin) --pf;
+        pf = std::max(pf, p.n_fwd_ops);
+        pf = std::max(pf, t.last_fwd_use_op + 1);
+        t.prefetch_op = std::min(pf, t.bwd_first_use_op);
+    }
+}
+
 int plan_swaps(std::vector<PlanTensor>& ts, const std::vector<size_t>& transient, const PlanParams& p, PlanResult* res) {
     int n_ops = p.n_ops;
     for (const PlanTensor& t : ts) n_ops = std::max(n_ops, t.bwd_last_use_op + 1);
     if (p.n_fwd_ops < 0 || p.n_fwd_ops > n_ops || p.lookahead < 0) return MI3D_ERR_INVALID_ARG;
+    const bool timed = p.op_ms && !p.op_ms->empty() && p.link_gbs > 0.f;
     for (PlanTensor& t : ts) {
         if (t.produce_op > t.last_fwd_use_op || t.last_fwd_use_op >= t.bwd_first_use_op ||
             t.bwd_first_use_op > t.bwd_last_use_op || t.produce_op < 0)
             return MI3D_ERR_INVALID_ARG;
         t.planned = false;
-        // `lb`: issue the swap-in `lookahead` ops before the first backward use,
-        // but never before the backward pass starts or the forward use ends.
-        int pf = t.bwd_first_use_op - p.lookahead;
-        pf = std::max(pf, p.n_fwd_ops);
-        pf = std::max(pf, t.last_fwd_use_op + 1);
-        pf = std::min(pf, t.bwd_first_use_op);
-        t.prefetch_op = pf;
+        t.prefetch_op = prefetch_by_ops(t, p);
         t.host_offset = 0;
     }
+    // the residency model with the current choice; with op times the chosen tensors come back earlier
+    auto reschedule = [&]() {
+        if (!timed) return;
+        for (PlanTensor& t : ts) t.prefetch_op = prefetch_by_ops(t, p);
+        prefetch_by_time(ts, p, n_ops);
+    };
     res->unswapped_peak = peak(ts, transient, n_ops, true, nullptr);
 
     auto eligible = [&](const PlanTensor& t) {
@@ -63,9 +100,11 @@ int plan_swaps(std::vector<PlanTensor>& ts, const std::vector<size_t>& transient
 
     if (p.policy == MI3D_SWAP_ALL) {
         for (int i : order) ts[i].planned = true;
+        reschedule();
     } else if (p.policy == MI3D_SWAP_FIRST_N) {
         int n = p.n_tensors < 0 ? (int)order.size() : std::min<int>(p.n_tensors, (int)order.size());
         for (int k = 0; k < n; ++k) ts[order[k]].planned = true;
+        reschedule();
     } else if (p.policy == MI3D_SWAP_BUDGET) {
         std::vector<int> chosen;
         for (;;) {
@@ -97,6 +136,25 @@ int plan_swaps(std::vector<PlanTensor>& ts, const std::vector<size_t>& transient
         }
     } else {
         return MI3D_ERR_INVALID_ARG;
+    }
+
+    // The swap set is chosen with the op-count rule (least residency, least traffic); only then are its swap-ins
+    // moved earlier by time.  The budget comes before the hiding: where that lifts the model over the budget,
+    // the tensors that are resident early at the peak are moved later again (at most back to the op-count rule).
+    if (timed && p.policy == MI3D_SWAP_BUDGET) {
+        reschedule();
+        for (int guard = 0; guard < 4 * n_ops * (int)ts.size() + 16; ++guard) {
+            int at = 0;
+            if (peak(ts, transient, n_ops, false, &at) <= p.budget_bytes) break;
+            int pick = -1;
+            for (int i : order) {
+                const PlanTensor& t = ts[i];
+                if (!t.planned || at < t.prefetch_op || at >= prefetch_by_ops(t, p)) continue;
+                if (pick < 0 || t.bwd_first_use_op > ts[pick].bwd_first_use_op) pick = i;   // needed last: least urgent
+            }
+            if (pick < 0) break;
+            ts[pick].prefetch_op = std::min(at + 1, prefetch_by_ops(ts[pick], p));
+        }
     }
 
     size_t off = 0;

@@ -27,6 +27,10 @@ struct PlanParams {
     int n_tensors = -1;
     unsigned exclude_tags = 0, include_tags = 0;
     int n_fwd_ops = 0, n_ops = 0;
+    // optional measured op durations (ms, one per op) and host-link rate: with them the swap-ins are scheduled by
+    // time (see plan_swaps), with `lookahead` as the minimum distance in ops
+    const std::vector<float>* op_ms = nullptr;
+    float link_gbs = 0.f;
 };
 
 struct PlanResult {

@@ -47,6 +47,10 @@ class SwapEngine:
         check(lib().mi3d_swap_register(self._h, id, bytes, produce_op, last_fwd_use_op, bwd_first_use_op,
                                        bwd_last_use_op, tags), "swap_register")
 
+    def set_op_times(self, ms, link_gbs):
+        arr = (ctypes.c_float * len(ms))(*[float(v) for v in ms])
+        check(lib().mi3d_swap_set_op_times(self._h, arr, len(ms), float(link_gbs)), "swap_set_op_times")
+
     def set_transient(self, op, bytes):
         check(lib().mi3d_swap_set_transient(self._h, op, bytes), "swap_set_transient")
 

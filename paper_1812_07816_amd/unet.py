@@ -237,9 +237,18 @@ class UNetStep:
                 s.ptr, s.view, s._waited = None, None, False
 
     # ---- the step
-    def run(self, update=True, trace=None):
-        """trace: optional dict that receives copies of intermediate tensors (tests)."""
+    def run(self, update=True, trace=None, timeline=None):
+        """trace: optional dict that receives copies of intermediate tensors (tests).  timeline: optional list that
+        receives (op name, "fwd" | "bwd", event recorded on the compute stream after the op) for a per-op time line."""
         e = self.engine
+
+        def mark(name, phase):
+            if timeline is not None:
+                ev = torch.cuda.Event(enable_timing=True)
+                ev.record()
+                timeline.append((name, phase, ev))
+
+        mark("start", "fwd")
         if e is not None:
             e.reset_step()
         bf = torch.bfloat16
@@ -274,6 +283,7 @@ class UNetStep:
             elif k == "loss":
                 glue.dice_loss(op["src"].view, self.labels, self.dice_ws, self.sums, self.loss)
             self._after_fwd_op(f)
+            mark(op["name"], "fwd")
         # backward
         da = None              # gradient with respect to the output of the op being walked back
         dskip = {}
@@ -328,8 +338,28 @@ class UNetStep:
             if trace is not None and da is not None:
                 trace[op["name"] + ".din"] = da.clone()
             self._after_bwd_op(b)
+            mark(op["name"], "bwd")
         if update:
             glue.sgd_update(self.w32, self.dw32, self.w16, self.lr)
+
+    def calibrate(self, link_gbs=55.0):
+        """Runs one step with per-op events, hands the measured op durations and the host-link rate to the
+        planner and plans again: the swap-ins are then scheduled by time instead of by op count."""
+        if self.engine is None:
+            return
+        self.run(update=False)
+        tl = []
+        self.run(update=False, timeline=tl)
+        torch.cuda.synchronize()
+        t = [tl[0][2].elapsed_time(ev) for _, _, ev in tl]
+        ms = [max(t[i + 1] - t[i], 0.0) for i in range(len(t) - 1)]     # forward ops, then backward ops in timeline order
+        assert len(ms) == self.n_ops
+        e = self.engine
+        e.set_op_times(ms, link_gbs)
+        self.plan_status = e.plan(allow_over_budget=True)
+        self.planned = [e.is_planned(s.id) for s in self.saved]
+        self.prefetch = [e.prefetch_op(s.id) for s in self.saved]
+        self.op_ms = ms
 
     def close(self):
         if self.engine is not None:

@@ -192,3 +192,57 @@ def test_host_pool_capacity_is_checked_at_plan_time():
     e = make(ts, n_fwd, n_ops, budget_bytes=1 << 40, policy=sw.POLICY_ALL)
     e.plan()
     assert e.stats()["n_planned"] == 4
+
+
+def test_prefetch_by_time_lays_copies_out_back_to_back():
+    # chain of 6 layers, every op 1 ms; link 1 GB/s -> a tensor of b bytes takes b / 1e6 * 1.15 + 0.05 ms
+    sizes = [3_000_000, 2_000_000, 1_000_000, 500_000, 100_000, 50_000]
+    n_fwd, n_ops, ts = chain(6, sizes)
+    e = make(ts, n_fwd, n_ops, budget_bytes=1 << 40, policy=sw.POLICY_ALL, lookahead=1)
+    e.plan()
+    by_ops = [e.prefetch_op(i) for i in range(6)]
+    e.set_op_times([1.0] * n_ops, 1.0)
+    e.plan()
+    pf = [e.prefetch_op(i) for i in range(6)]
+    dur = [b / 1e6 * 1.15 + 0.05 for b in sizes]
+    use = [n_ops - 1 - i for i in range(6)]          # first backward use; with 1 ms ops the start time equals the op index
+    # latest use first: tensor 0 (used last) must end by its use; the copy before it must end when that one starts
+    end = float("inf")
+    for i in range(6):
+        finish = min(use[i], end)
+        begin = finish - dur[i]
+        lower = max(n_fwd, ts[i][3] + 1)
+        assert pf[i] <= by_ops[i]
+        assert pf[i] <= max(begin, lower) + 1e-9, (i, pf[i], begin)          # issued early enough ...
+        assert pf[i] == lower or pf[i] + 1 > begin - 1e-9, (i, pf[i], begin)   # ... and at the latest such op
+        end = begin
+    # back to the op-count rule
+    e.set_op_times([], 0.0)
+    e.plan()
+    assert [e.prefetch_op(i) for i in range(6)] == by_ops
+    e.close()
+
+
+def test_op_times_count_in_the_budget_model():
+    # earlier swap-ins keep tensors resident longer; the budget has priority over the hiding
+    sizes = [4000, 3000, 2000, 1000, 500, 250]
+    n_fwd, n_ops, ts = chain(6, sizes)
+    total = sum(sizes)
+    for frac, expect_earlier in ((0.7, False), (0.9, True)):
+        budget = int(total * frac)
+        e = make(ts, n_fwd, n_ops, budget_bytes=budget, lookahead=1)
+        e.plan()
+        by_ops = {i: e.prefetch_op(i) for i in range(6) if e.is_planned(i)}
+        e.set_op_times([1.0] * n_ops, 4e-3)              # 4 MB/s: a 4000-byte tensor takes 1.2 ms, more than one op
+        assert e.plan(allow_over_budget=True) == 0
+        planned = {i for i in range(6) if e.is_planned(i)}
+        prefetch = {i: e.prefetch_op(i) for i in planned}
+        assert planned and all(prefetch[i] <= by_ops.get(i, 10 ** 9) for i in planned)
+        assert any(prefetch[i] < by_ops.get(i, 10 ** 9) for i in planned) == expect_earlier
+        for op in range(n_ops):
+            assert brute_bytes(ts, planned, prefetch, op) == e.planned_bytes_at(op) <= budget
+        e.close()
+    e = make(ts, n_fwd, n_ops, budget_bytes=total, lookahead=1)
+    with pytest.raises(Mi3dError):
+        e.set_op_times([1.0, -1.0], 1.0)
+    e.close()
