@@ -45,7 +45,7 @@ static bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
 
 enum Kernel {
     K_DIRECT = 0, K_SP, K_WGRAD_MFMA, K_S2_FWD, K_WGRAD_S2, K_DGRAD_S2, K_C4_FWD, K_C4_DGRAD, K_C4_WGRAD, K_POINTWISE,
-    K_EMBED_C, K_EMBED_S, K_EMBED_K2
+    K_EMBED_C, K_EMBED_S, K_EMBED_K2, K_K2
 };
 
 static Kernel choose(const Geom& g, int pass) {
@@ -58,6 +58,7 @@ static Kernel choose(const Geom& g, int pass) {
     if (pass == MI3D_PASS_FWD && c4_fwd_supported(g)) return K_C4_FWD;
     if (pass == MI3D_PASS_DGRAD && c4_dgrad_supported(g)) return K_C4_DGRAD;
     if (pass == MI3D_PASS_WGRAD && c4_wgrad_supported(g)) return K_C4_WGRAD;
+    if (k2_supported(g, pass)) return K_K2;
     if (embed_c_supported(g, pass)) return K_EMBED_C;
     if (embed_s_supported(g, pass)) return K_EMBED_S;
     if (embed_k2_supported(g, pass)) return K_EMBED_K2;
@@ -79,6 +80,7 @@ static const char* kernel_name(Kernel k) {
         case K_EMBED_C: return "mfma_via_channel_padding";
         case K_EMBED_S: return "mfma_via_unit_stride";
         case K_EMBED_K2: return "mfma_via_k3s2_embedding";
+        case K_K2: return "mfma_k2s2_panel_gemm";
         default: return "none";
     }
 }
@@ -98,6 +100,7 @@ static size_t kernel_workspace(Kernel k, const Geom& g, int pass) {
         case K_EMBED_C: return embed_c_workspace_bytes(g, pass);
         case K_EMBED_S: return embed_s_workspace_bytes(g, pass);
         case K_EMBED_K2: return embed_k2_workspace_bytes(g, pass);
+        case K_K2: return k2_workspace_bytes(g, pass);
     }
     return 0;
 }
@@ -121,6 +124,7 @@ static int run_kernel(Kernel k, const Geom& g, int pass, const void* a, const vo
         case K_EMBED_C: return embed_c_conv(g, pass, a, b, out, ws, ws_bytes, s);
         case K_EMBED_S: return embed_s_conv(g, pass, a, b, out, ws, ws_bytes, s);
         case K_EMBED_K2: return embed_k2_conv(g, pass, a, b, out, ws, ws_bytes, s);
+        case K_K2: return k2_conv(g, pass, a, b, out, ws, ws_bytes, s);
     }
     return MI3D_ERR_UNSUPPORTED;
 }

@@ -79,6 +79,9 @@ int wgrad_s2(const Geom& g, const void* x, const void* dy, float* dw, void* ws, 
 
 
 // first-layer kernels (4 input channels)
+bool k2_supported(const Geom& g, int pass);
+size_t k2_workspace_bytes(const Geom& g, int pass);
+int k2_conv(const Geom& g, int pass, const void* a, const void* w, void* out, void* ws, size_t ws_bytes, hipStream_t s);
 bool c4_fwd_supported(const Geom& g);
 size_t c4_fwd_workspace_bytes(const Geom& g);
 int c4_fwd(const Geom& g, const void* x, const void* w, void* y, void* ws, size_t ws_bytes, hipStream_t s);

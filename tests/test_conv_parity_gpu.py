@@ -68,6 +68,9 @@ MID = [
     (1, 4, 16, 33, 4, 32, 3, 1, 2),
     (1, 6, 10, 40, 32, 3, 1, 1, 0),
     (1, 8, 8, 16, 32, 64, 2, 2, 0),
+    (2, 6, 10, 14, 64, 128, 2, 2, 0),
+    (1, 4, 6, 6, 256, 320, 2, 2, 0),
+    (1, 4, 4, 8, 32, 96, 2, 2, 0),
 ]
 
 
