@@ -1,5 +1,4 @@
-// Forward pass of the 3x3x3 / stride 2 downsampling convolution with 32 input
-// channels on bf16 MFMA (v_mfma_f32_32x32x16_bf16), fp32 accumulation: the
+// Forward pass of the 3x3x3 / stride 2 downsampling convolution on bf16 MFMA (v_mfma_f32_32x32x16_bf16), fp32 accumulation: the
 // layer that leaves a U-Net level (feature maps of Section 3.1).
 //
 // The layer moves 64 bytes of input per 27/8 taps, so it is bound by memory
@@ -11,6 +10,10 @@
 // 2), odd ones feed one (kd 1); two output planes are in flight in registers.
 // The staged plane patch (9 x 65 voxels) is split by column parity in LDS, so
 // that the 32 voxels of a fragment (input columns 2 j + kw) are contiguous.
+// A kernel instance contracts 32 input channels.  With more input channels the
+// 32-channel chunks are separate work units that write fp32 partial outputs, and
+// a second kernel adds the chunks in index order and rounds to bf16 (the deep,
+// small layers of the encoder: their outputs are a few MB).
 #include "mi3d_internal.h"
 
 namespace mi3d {
@@ -28,11 +31,12 @@ constexpr int WB_BYTES = 27 * 2 * 1024;           // packed weights of one 32-wi
 
 struct S2Params {
     const uint16_t* x;
-    const uint16_t* wpack;  // [cout block][kw][kd][kh][k16][lane][8]
+    const uint16_t* wpack;  // [cout block][cin chunk][kw][kd][kh][k16][lane][8]
     uint16_t* y;
+    float* part;            // [cin chunk][voxel][Cout] fp32 partial outputs (more than one chunk)
     uint16_t* dump;         // 2 KB that masked store lanes write to instead of y
-    int N, D, H, W, Cout, Do, Ho, Wo, pD, pH, pW;
-    int HT, WT, CT;         // tiles per plane, cout tiles
+    int N, D, H, W, Cin, Cout, Do, Ho, Wo, pD, pH, pW;
+    int HT, WT, CT, NCH;    // tiles per plane, cout tiles, cin chunks
     long long units;
     int nwg;
 };
@@ -117,13 +121,23 @@ __device__ __forceinline__ void store_rows(const f32x16 (&a)[RH], uint16_t* p, l
     }
 }
 
+// fp32 partial rows: accumulator register i of lane (voxel n, half h) is channel 8 (i / 4) + 4 h + i % 4
+__device__ __forceinline__ void store_rows_f32(const f32x16 (&a)[RH], float* p, long long row_pitch, bool col_ok, int rows_ok, float* dump) {
+#pragma unroll
+    for (int r = 0; r < RH; ++r) {
+        float* q = (col_ok && r < rows_ok) ? p + r * row_pitch : dump;
+#pragma unroll
+        for (int g4 = 0; g4 < 4; ++g4) *(float4*)(q + 8 * g4) = float4{a[r][4 * g4], a[r][4 * g4 + 1], a[r][4 * g4 + 2], a[r][4 * g4 + 3]};
+    }
+}
+
 // CB = 2 (Cout % 64 == 0): a tile is 4 output rows x 2 cout blocks; waves 0,1 serve block 0 and waves
 // 2,3 block 1, two rows each; the staged patch has 9 rows.  CB = 1: 8 output rows x 1 cout block, one
 // wave per row pair, 17 staged rows.  The layer is bound by HBM reads and one workgroup per CU holds
 // only one plane patch in LDS, so the global loads run two planes ahead of the MFMAs through two
 // register sets (plane tq + 2 is requested during step tq and written to LDS at the end of step
 // tq + 1): with one plane of lookahead the load latency (about 2 us under load) was exposed in every step.
-template <int CB>
+template <int CB, bool PART>
 __global__ void __launch_bounds__(256, 1) s2_fwd_kernel(S2Params P) {
     extern __shared__ __attribute__((aligned(16))) char lds[];
     constexpr int TROWS = CB == 2 ? TH : 2 * TH;      // output rows per workgroup
@@ -162,15 +176,19 @@ __global__ void __launch_bounds__(256, 1) s2_fwd_kernel(S2Params P) {
         u0 += od_end - od_start;
         const int wt = (int)(column % P.WT); column /= P.WT;
         const int ht = (int)(column % P.HT); column /= P.HT;
+        const int chunk = PART ? (int)(column % P.NCH) : 0;
+        if (PART) column /= P.NCH;
         const int ct = (int)(column % P.CT);
         const int n = (int)(column / P.CT);
         const int h0 = ht * TROWS, w0 = wt * TW;
 
         __syncthreads();   // previous segment's readers are done with the weights and the stage
-        if (ct != cur_ct) {
-            const uint4* src = (const uint4*)(P.wpack + (long long)ct * CB * (WB_BYTES / 2));
-            for (int i = t; i < CB * WB_BYTES / 16; i += 256) ((uint4*)w_lds)[i] = src[i];
-            cur_ct = ct;
+        if (ct * P.NCH + chunk != cur_ct) {
+            for (int b = 0; b < CB; ++b) {   // the CB cout blocks of the tile, this cin chunk
+                const uint4* src = (const uint4*)(P.wpack + ((long long)(ct * CB + b) * P.NCH + chunk) * (WB_BYTES / 2));
+                for (int i = t; i < WB_BYTES / 16; i += 256) ((uint4*)(w_lds + b * WB_BYTES))[i] = src[i];
+            }
+            cur_ct = ct * P.NCH + chunk;
         }
         // load plan: piece q = channels 8c..8c+7 of voxel q / 4 (row-major PR x 65)
         int goff[NLOAD];
@@ -182,12 +200,14 @@ __global__ void __launch_bounds__(256, 1) s2_fwd_kernel(S2Params P) {
             const int row = (v * 1009) >> 16, col = v - row * PC;
             const int gh = 2 * h0 - P.pH + row, gw = 2 * w0 - P.pW + col;
             const bool ok = q < NPIECE && gh >= 0 && gh < P.H && gw >= 0 && gw < P.W;
-            goff[i] = ok ? (gh * P.W + gw) * 32 + c * 8 : 0;
+            goff[i] = ok ? (gh * P.W + gw) * P.Cin + chunk * 32 + c * 8 : 0;
             valid |= (ok ? 1u : 0u) << i;
         }
-        const long long plane_elems = (long long)P.H * P.W * 32;
+        const long long plane_elems = (long long)P.H * P.W * P.Cin;
         const uint16_t* xn = P.x + (long long)n * P.D * plane_elems;
-        uint16_t* yn = P.y + (long long)n * P.Do * P.Ho * P.Wo * P.Cout;
+        const long long out_n = (long long)n * P.Do * P.Ho * P.Wo * P.Cout;
+        uint16_t* yn = P.y + out_n;
+        float* pn = PART ? P.part + (long long)chunk * P.N * P.Do * P.Ho * P.Wo * P.Cout + out_n : nullptr;
         const int nP = od_end - od_start;
         const int nT = 2 * nP + 1;     // staged planes tq = 0 .. 2 nP, input plane ip = 2 od_start - pD + tq
         const int ip0 = 2 * od_start - P.pD;
@@ -250,8 +270,10 @@ __global__ void __launch_bounds__(256, 1) s2_fwd_kernel(S2Params P) {
             });                                                                                  \
             if (EVEN) {                                                                          \
                 const int od_ = od_start + (tq >> 1) - 1;                                        \
-                store_rows(acc[1 - (SET)], yn + ((long long)od_ * P.Ho + oh0) * row_pitch + (long long)ow * P.Cout + co0, \
-                           row_pitch, tq >= 2 && ow < P.Wo, P.Ho - oh0, P.dump + lane * 16);     \
+                const long long off_ = ((long long)od_ * P.Ho + oh0) * row_pitch + (long long)ow * P.Cout;  \
+                if (PART) store_rows_f32(acc[1 - (SET)], pn + off_ + (ct * CB + cb) * 32 + 4 * (lane >> 5), row_pitch, \
+                                         tq >= 2 && ow < P.Wo, P.Ho - oh0, (float*)P.dump + lane * 32); \
+                else store_rows(acc[1 - (SET)], yn + off_ + co0, row_pitch, tq >= 2 && ow < P.Wo, P.Ho - oh0, P.dump + lane * 16); \
             }                                                                                    \
             __syncthreads();                                                                     \
             write_plane(1 - rs_);                                                                \
@@ -271,9 +293,9 @@ __global__ void __launch_bounds__(256, 1) s2_fwd_kernel(S2Params P) {
     }
 }
 
-// [Cout][3][3][3][32] -> [cout block][kw][kd][kh][k16][lane][8] MFMA A fragments
-__global__ void __launch_bounds__(256) s2_pack_weights_kernel(const uint16_t* __restrict__ w, uint16_t* __restrict__ wpack, int Cout) {
-    long long total = 27ll * 32 * Cout;
+// [Cout][3][3][3][Cin] -> [cout block][cin chunk][kw][kd][kh][k16][lane][8] MFMA A fragments
+__global__ void __launch_bounds__(256) s2_pack_weights_kernel(const uint16_t* __restrict__ w, uint16_t* __restrict__ wpack, int Cin, int Cout) {
+    long long total = 27ll * Cin * Cout;
     long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
     if (idx >= total) return;
     int j = (int)(idx & 7);
@@ -283,40 +305,71 @@ __global__ void __launch_bounds__(256) s2_pack_weights_kernel(const uint16_t* __
     int kh = (int)(r % 3); r /= 3;
     int kd = (int)(r % 3); r /= 3;
     int kw = (int)(r % 3); r /= 3;
-    int blk = (int)r;
+    int nch = Cin / 32;
+    int chunk = (int)(r % nch);
+    int blk = (int)(r / nch);
     int co = blk * 32 + (lane & 31);
-    int ci = kk * 16 + 8 * (lane >> 5) + j;
-    wpack[idx] = w[((((long long)co * 3 + kd) * 3 + kh) * 3 + kw) * 32 + ci];
+    int ci = chunk * 32 + kk * 16 + 8 * (lane >> 5) + j;
+    wpack[idx] = w[((((long long)co * 3 + kd) * 3 + kh) * 3 + kw) * Cin + ci];
+}
+
+// y = bf16(sum over chunks of part[chunk]), chunks added in index order; 8 outputs per thread
+__global__ void __launch_bounds__(256) s2_sum_chunks_kernel(const float* __restrict__ part, uint16_t* __restrict__ y, long long n8, long long n, int nch) {
+    for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < n8; i += (long long)gridDim.x * 256) {
+        float a[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) a[j] = 0.f;
+        for (int c = 0; c < nch; ++c) {
+            const float4 lo = *(const float4*)(part + c * n + 8 * i), hi = *(const float4*)(part + c * n + 8 * i + 4);
+            a[0] += lo.x; a[1] += lo.y; a[2] += lo.z; a[3] += lo.w; a[4] += hi.x; a[5] += hi.y; a[6] += hi.z; a[7] += hi.w;
+        }
+        uint32_t o[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            f32x2 v = {a[2 * j], a[2 * j + 1]};
+            o[j] = __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+        }
+        *(uint4*)(y + 8 * i) = uint4{o[0], o[1], o[2], o[3]};
+    }
 }
 
 }  // namespace
+
+static size_t s2_part_offset(const Geom& g) { return (((size_t)g.w_elems() * 2 + 255) & ~(size_t)255) + 8192; }
 
 bool s2_fwd_supported(const Geom& g) {
     if (g.dtype != MI3D_BF16 || g.kD != 3 || g.kH != 3 || g.kW != 3) return false;
     if (g.sD != 2 || g.sH != 2 || g.sW != 2) return false;
     if (g.pD > 1 || g.pH > 1 || g.pW > 1) return false;
-    return g.Cin == 32 && g.Cout % 32 == 0;
+    return g.Cin % 32 == 0 && g.Cout % 32 == 0;
 }
 
-size_t s2_fwd_workspace_bytes(const Geom& g) { return s2_fwd_supported(g) ? (((size_t)g.w_elems() * 2 + 255) & ~(size_t)255) + 2048 : 0; }
+size_t s2_fwd_workspace_bytes(const Geom& g) {
+    if (!s2_fwd_supported(g)) return 0;
+    size_t b = s2_part_offset(g);   // packed weights + store dump area
+    if (g.Cin > 32) b += (size_t)(g.Cin / 32) * g.out_voxels() * g.Cout * sizeof(float);
+    return b;
+}
 
 int s2_fwd(const Geom& g, const void* x, const void* w, void* y, void* ws, size_t ws_bytes, hipStream_t s) {
     if (ws_bytes < s2_fwd_workspace_bytes(g)) return MI3D_ERR_WORKSPACE;
     long long total = g.w_elems();
-    s2_pack_weights_kernel<<<(unsigned)((total + 255) / 256), 256, 0, s>>>((const uint16_t*)w, (uint16_t*)ws, g.Cout);
+    s2_pack_weights_kernel<<<(unsigned)((total + 255) / 256), 256, 0, s>>>((const uint16_t*)w, (uint16_t*)ws, g.Cin, g.Cout);
     int st = check_launch();
     if (st) return st;
     S2Params P;
     P.x = (const uint16_t*)x; P.wpack = (const uint16_t*)ws; P.y = (uint16_t*)y;
     P.dump = (uint16_t*)((char*)ws + (((size_t)g.w_elems() * 2 + 255) & ~(size_t)255));
-    P.N = g.N; P.D = g.D; P.H = g.H; P.W = g.W; P.Cout = g.Cout;
+    P.part = (float*)((char*)ws + s2_part_offset(g));
+    P.N = g.N; P.D = g.D; P.H = g.H; P.W = g.W; P.Cin = g.Cin; P.Cout = g.Cout;
     P.Do = g.Do; P.Ho = g.Ho; P.Wo = g.Wo; P.pD = g.pD; P.pH = g.pH; P.pW = g.pW;
     const int CB = (g.Cout % 64 == 0) ? 2 : 1;
     P.CT = g.Cout / (32 * CB);
+    P.NCH = g.Cin / 32;
     const int th = CB == 2 ? TH : 2 * TH;
     P.HT = (g.Ho + th - 1) / th;
     P.WT = (g.Wo + TW - 1) / TW;
-    P.units = (long long)g.N * P.CT * P.HT * P.WT * g.Do;
+    P.units = (long long)g.N * P.CT * P.NCH * P.HT * P.WT * g.Do;
     int dev = 0, cus = 256;
     if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
     long long nwg = cus < P.units ? cus : P.units;
@@ -324,13 +377,24 @@ int s2_fwd(const Geom& g, const void* x, const void* w, void* y, void* ws, size_
     const size_t lds2 = 2 * WB_BYTES + 4 * (2 * TH + 1) * PITCH * 16, lds1 = WB_BYTES + 4 * (4 * TH + 1) * PITCH * 16;
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void*)s2_fwd_kernel<2>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds2);
-        if (e == hipSuccess) e = hipFuncSetAttribute((const void*)s2_fwd_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds1);
+        hipError_t e = hipFuncSetAttribute((const void*)s2_fwd_kernel<2, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds2);
+        if (e == hipSuccess) e = hipFuncSetAttribute((const void*)s2_fwd_kernel<1, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds1);
+        if (e == hipSuccess) e = hipFuncSetAttribute((const void*)s2_fwd_kernel<2, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds2);
+        if (e == hipSuccess) e = hipFuncSetAttribute((const void*)s2_fwd_kernel<1, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds1);
         if (e != hipSuccess) { note_hip_error(e); return MI3D_ERR_HIP; }
         attr_set = true;
     }
-    if (CB == 2) s2_fwd_kernel<2><<<(unsigned)nwg, 256, lds2, s>>>(P);
-    else s2_fwd_kernel<1><<<(unsigned)nwg, 256, lds1, s>>>(P);
+    const bool part = P.NCH > 1;
+    if (CB == 2 && !part) s2_fwd_kernel<2, false><<<(unsigned)nwg, 256, lds2, s>>>(P);
+    else if (CB == 2) s2_fwd_kernel<2, true><<<(unsigned)nwg, 256, lds2, s>>>(P);
+    else if (!part) s2_fwd_kernel<1, false><<<(unsigned)nwg, 256, lds1, s>>>(P);
+    else s2_fwd_kernel<1, true><<<(unsigned)nwg, 256, lds1, s>>>(P);
+    st = check_launch();
+    if (st || !part) return st;
+    const long long n = (long long)g.out_voxels() * g.Cout;   // Cout % 32 == 0: a multiple of 8
+    long long blocks = (n / 8 + 255) / 256;
+    if (blocks > 8192) blocks = 8192;
+    s2_sum_chunks_kernel<<<(unsigned)blocks, 256, 0, s>>>(P.part, (uint16_t*)y, n / 8, n, P.NCH);
     return check_launch();
 }
 
