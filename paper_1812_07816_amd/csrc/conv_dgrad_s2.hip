@@ -34,9 +34,10 @@ struct Dg2Params {
     const uint16_t* dy;
     const uint16_t* wpack;  // [cin tile][kd][kh][kw][k16][lane][8]
     uint16_t* dx;
-    uint16_t* dump;         // 2 KB that masked store lanes write to instead of dx
+    uint16_t* dump;         // 8 KB that masked store lanes write to instead of dx
+    float* part;            // [cout chunk][voxel][Cin] fp32 partial gradients (Cout > 64)
     int N, D, H, W, Cin, Cout, Do, Ho, Wo, p;
-    int QD, HT, WT, CiT;
+    int QD, HT, WT, CiT, NCO;   // ..., cin tiles, cout chunks (of 64 when Cout > 64)
     long long units;
     int nwg;
 };
@@ -104,7 +105,9 @@ __device__ __forceinline__ void pack_block(const f32x16& a, uint4 (&c)[2]) {
 // KK = Cout / 16 k16 steps.  Every MFMA needs its own 1 KB weight fragment from LDS (a tap is used once
 // per wave and step), so the kernel runs at the LDS rate: the fragment reads are issued two groups of
 // three MFMAs ahead of their use from a ring of three register groups.
-template <int P, int KK>
+// PART: Cout > 64 is contracted in chunks of 64 that are separate work units writing fp32 partial gradients; a second
+// kernel adds the chunks in index order and rounds to bf16.
+template <int P, int KK, bool PART>
 __global__ void __launch_bounds__(256, 1) dgrad_s2_kernel(Dg2Params G) {
     extern __shared__ __attribute__((aligned(16))) char lds[];
     constexpr int SLABS = 2 * KK;
@@ -131,15 +134,17 @@ __global__ void __launch_bounds__(256, 1) dgrad_s2_kernel(Dg2Params G) {
         u0 += q_end - q_start;
         const int wt = (int)(column % G.WT); column /= G.WT;
         const int ht = (int)(column % G.HT); column /= G.HT;
+        const int chunk = PART ? (int)(column % G.NCO) : 0;
+        if (PART) column /= G.NCO;
         const int cit = (int)(column % G.CiT);
         const int n = (int)(column / G.CiT);
         const int rq0 = ht * RP, cq0 = wt * CP;   // first row pair / column pair
 
         __syncthreads();  // previous segment's readers are done
-        if (cit != cur_cit) {
-            const uint4* src = (const uint4*)(G.wpack + (long long)cit * (W_BYTES / 2));
+        if (cit * G.NCO + chunk != cur_cit) {
+            const uint4* src = (const uint4*)(G.wpack + ((long long)cit * G.NCO + chunk) * (W_BYTES / 2));
             for (int i = t; i < W_BYTES / 16; i += 256) ((uint4*)w_lds)[i] = src[i];
-            cur_cit = cit;
+            cur_cit = cit * G.NCO + chunk;
         }
         // load plan: piece q = (voxel v = q / SLABS, slab c = q % SLABS), voxel row-major over 5 x 33
         int goff[NL], loff[NL];
@@ -151,13 +156,14 @@ __global__ void __launch_bounds__(256, 1) dgrad_s2_kernel(Dg2Params G) {
             const int row = v / PC, col = v - row * PC;
             const int gh = rq0 + G.p - 1 + row, gw = cq0 + G.p - 1 + col;
             const bool ok = q < NPIECE && gh >= 0 && gh < G.Ho && gw >= 0 && gw < G.Wo;
-            goff[i] = ok ? (gh * G.Wo + gw) * G.Cout + c * 8 : 0;
+            goff[i] = ok ? (gh * G.Wo + gw) * G.Cout + chunk * (16 * KK) + c * 8 : 0;
             loff[i] = (c * SLABV + row * PITCH + col) * 16;
             valid |= (ok ? 1u : 0u) << i;
         }
         const long long dy_plane = (long long)G.Ho * G.Wo * G.Cout;
         const uint16_t* dyn = G.dy + (long long)n * G.Do * dy_plane;
         uint16_t* dxn = G.dx + (long long)n * G.D * G.H * G.W * G.Cin;
+        float* pn = PART ? G.part + ((long long)chunk * G.N + n) * G.D * G.H * G.W * G.Cin : nullptr;
 
         uint4 pre[NL];
         unsigned pre_mask = 0;
@@ -242,6 +248,20 @@ __global__ void __launch_bounds__(256, 1) dgrad_s2_kernel(Dg2Params G) {
 #pragma unroll
                 for (int ch = 0; ch < 2; ++ch) {
                     const int ih_ = 2 * rq + (ch == 0 ? G.p : 1 - G.p);
+                    if (PART) {
+                        // fp32 partials: register i of lane (n, h) is cin 8 (i / 4) + 4 h + i % 4; class cw sits in column
+                        // 2 cq + (cw == 0 ? p : 1 - p)
+#pragma unroll
+                        for (int cw = 0; cw < 2; ++cw) {
+                            const int iw_ = 2 * cq + (cw == 0 ? P : 1 - P);
+                            float* ptr = pn + (((long long)id_ * G.H + ih_) * G.W + iw_) * G.Cin + cit * 32 + 4 * (lane >> 5);
+                            float* qf = (id_ < G.D && ih_ < G.H && iw_ < G.W) ? ptr : (float*)G.dump + lane * 32;
+                            const f32x16& a = acc[cd][ch][cw];
+#pragma unroll
+                            for (int g4 = 0; g4 < 4; ++g4) *(float4*)(qf + 8 * g4) = float4{a[4 * g4], a[4 * g4 + 1], a[4 * g4 + 2], a[4 * g4 + 3]};
+                        }
+                        continue;
+                    }
                     uint4 be[2], bo[2];
                     pack_block(acc[cd][ch][0], be);   // class E columns: 2 cq + p
                     pack_block(acc[cd][ch][1], bo);   // class O columns: 2 cq + 1 - p
@@ -272,69 +292,92 @@ __global__ void __launch_bounds__(256, 1) dgrad_s2_kernel(Dg2Params G) {
     }
 }
 
-// [Cout][3][3][3][Cin] -> [cin tile][tap][k16][lane][8]: lane (ci = l % 32, half h) holds couts 16 kk + 8 h + j
-__global__ void __launch_bounds__(256) dgrad_s2_pack_kernel(const uint16_t* __restrict__ w, uint16_t* __restrict__ wpack, int Cin, int Cout) {
+// [Cout][3][3][3][Cin] -> [cin tile][cout chunk][tap][k16][lane][8]: lane (ci = l % 32, half h) holds couts
+// chunk * 16 KK + 16 kk + 8 h + j; KK k16-steps per chunk
+__global__ void __launch_bounds__(256) dgrad_s2_pack_kernel(const uint16_t* __restrict__ w, uint16_t* __restrict__ wpack, int Cin, int Cout, int KK) {
     const long long total = 27ll * Cin * Cout;
     const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
     if (idx >= total) return;
     const int j = (int)(idx & 7);
     long long r = idx >> 3;
     const int lane = (int)(r & 63); r >>= 6;
-    const int KK = Cout / 16;
     const int kk = (int)(r % KK); r /= KK;
-    const int tap = (int)(r % 27);
-    const int cit = (int)(r / 27);
+    const int tap = (int)(r % 27); r /= 27;
+    const int nco = Cout / (16 * KK);
+    const int chunk = (int)(r % nco);
+    const int cit = (int)(r / nco);
     const int ci = cit * 32 + (lane & 31);
-    const int co = kk * 16 + 8 * (lane >> 5) + j;
+    const int co = chunk * 16 * KK + kk * 16 + 8 * (lane >> 5) + j;
     wpack[idx] = w[((long long)co * 27 + tap) * Cin + ci];
 }
 
 }  // namespace
 
+static size_t dg2_part_offset(const Geom& g) { return (((size_t)g.w_elems() * 2 + 255) & ~(size_t)255) + 8192; }
+
 bool dgrad_s2_supported(const Geom& g) {
     if (g.dtype != MI3D_BF16 || g.kD != 3 || g.kH != 3 || g.kW != 3) return false;
     if (g.sD != 2 || g.sH != 2 || g.sW != 2) return false;
     if (g.pD != g.pH || g.pD != g.pW || g.pD > 1) return false;
-    return g.Cin % 32 == 0 && (g.Cout == 32 || g.Cout == 64);
+    return g.Cin % 32 == 0 && (g.Cout == 32 || g.Cout % 64 == 0);
 }
 
-size_t dgrad_s2_workspace_bytes(const Geom& g) { return dgrad_s2_supported(g) ? (((size_t)g.w_elems() * 2 + 255) & ~(size_t)255) + 2048 : 0; }
+size_t dgrad_s2_workspace_bytes(const Geom& g) {
+    if (!dgrad_s2_supported(g)) return 0;
+    size_t b = dg2_part_offset(g);   // packed weights + store dump area
+    if (g.Cout > 64) b += (size_t)(g.Cout / 64) * g.in_voxels() * g.Cin * sizeof(float);
+    return b;
+}
 
 int dgrad_s2(const Geom& g, const void* dy, const void* w, void* dx, void* ws, size_t ws_bytes, hipStream_t s) {
     if (ws_bytes < dgrad_s2_workspace_bytes(g)) return MI3D_ERR_WORKSPACE;
     const long long total = g.w_elems();
-    dgrad_s2_pack_kernel<<<(unsigned)((total + 255) / 256), 256, 0, s>>>((const uint16_t*)w, (uint16_t*)ws, g.Cin, g.Cout);
+    const int KK = g.Cout == 32 ? 2 : 4;
+    dgrad_s2_pack_kernel<<<(unsigned)((total + 255) / 256), 256, 0, s>>>((const uint16_t*)w, (uint16_t*)ws, g.Cin, g.Cout, KK);
     int st = check_launch();
     if (st) return st;
     Dg2Params G;
     G.dy = (const uint16_t*)dy; G.wpack = (const uint16_t*)ws; G.dx = (uint16_t*)dx;
     G.dump = (uint16_t*)((char*)ws + (((size_t)g.w_elems() * 2 + 255) & ~(size_t)255));
+    G.part = (float*)((char*)ws + dg2_part_offset(g));
     G.N = g.N; G.D = g.D; G.H = g.H; G.W = g.W; G.Cin = g.Cin; G.Cout = g.Cout;
     G.Do = g.Do; G.Ho = g.Ho; G.Wo = g.Wo; G.p = g.pD;
     G.QD = (g.D + 1) / 2;
     G.HT = ((g.H + 1) / 2 + RP - 1) / RP;
     G.WT = ((g.W + 1) / 2 + CP - 1) / CP;
     G.CiT = g.Cin / 32;
-    G.units = (long long)g.N * G.CiT * G.HT * G.WT * G.QD;
+    G.NCO = g.Cout / (16 * KK);
+    G.units = (long long)g.N * G.CiT * G.NCO * G.HT * G.WT * G.QD;
     int dev = 0, cus = 256;
     if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
     const long long nwg = cus < G.units ? cus : G.units;
     G.nwg = (int)nwg;
-    const size_t lds = (size_t)27 * (g.Cout / 16) * 1024 + 2 * (size_t)(g.Cout / 8) * SLABV * 16;
+    const size_t lds = (size_t)27 * KK * 1024 + 2 * (size_t)(2 * KK) * SLABV * 16;
     static bool attr_set = false;
     if (!attr_set) {
         const int max_lds = 27 * 4 * 1024 + 2 * 8 * SLABV * 16;
-        hipError_t e = hipFuncSetAttribute((const void*)dgrad_s2_kernel<0, 2>, hipFuncAttributeMaxDynamicSharedMemorySize, max_lds);
-        if (e == hipSuccess) e = hipFuncSetAttribute((const void*)dgrad_s2_kernel<1, 2>, hipFuncAttributeMaxDynamicSharedMemorySize, max_lds);
-        if (e == hipSuccess) e = hipFuncSetAttribute((const void*)dgrad_s2_kernel<0, 4>, hipFuncAttributeMaxDynamicSharedMemorySize, max_lds);
-        if (e == hipSuccess) e = hipFuncSetAttribute((const void*)dgrad_s2_kernel<1, 4>, hipFuncAttributeMaxDynamicSharedMemorySize, max_lds);
-        if (e != hipSuccess) { note_hip_error(e); return MI3D_ERR_HIP; }
+        const void* fns[6] = {(const void*)dgrad_s2_kernel<0, 2, false>, (const void*)dgrad_s2_kernel<1, 2, false>,
+                              (const void*)dgrad_s2_kernel<0, 4, false>, (const void*)dgrad_s2_kernel<1, 4, false>,
+                              (const void*)dgrad_s2_kernel<0, 4, true>, (const void*)dgrad_s2_kernel<1, 4, true>};
+        for (const void* f : fns) {
+            hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, max_lds);
+            if (e != hipSuccess) { note_hip_error(e); return MI3D_ERR_HIP; }
+        }
         attr_set = true;
     }
-    if (g.pD == 0 && g.Cout == 32) dgrad_s2_kernel<0, 2><<<(unsigned)nwg, 256, lds, s>>>(G);
-    else if (g.pD == 0) dgrad_s2_kernel<0, 4><<<(unsigned)nwg, 256, lds, s>>>(G);
-    else if (g.Cout == 32) dgrad_s2_kernel<1, 2><<<(unsigned)nwg, 256, lds, s>>>(G);
-    else dgrad_s2_kernel<1, 4><<<(unsigned)nwg, 256, lds, s>>>(G);
+    const bool part = G.NCO > 1;
+    if (part && g.pD == 0) dgrad_s2_kernel<0, 4, true><<<(unsigned)nwg, 256, lds, s>>>(G);
+    else if (part) dgrad_s2_kernel<1, 4, true><<<(unsigned)nwg, 256, lds, s>>>(G);
+    else if (g.pD == 0 && KK == 2) dgrad_s2_kernel<0, 2, false><<<(unsigned)nwg, 256, lds, s>>>(G);
+    else if (g.pD == 0) dgrad_s2_kernel<0, 4, false><<<(unsigned)nwg, 256, lds, s>>>(G);
+    else if (KK == 2) dgrad_s2_kernel<1, 2, false><<<(unsigned)nwg, 256, lds, s>>>(G);
+    else dgrad_s2_kernel<1, 4, false><<<(unsigned)nwg, 256, lds, s>>>(G);
+    st = check_launch();
+    if (st || !part) return st;
+    const long long n = (long long)g.in_voxels() * g.Cin;
+    long long blocks = (n / 8 + 255) / 256;
+    if (blocks > 8192) blocks = 8192;
+    sum_chunks_bf16_kernel<<<(unsigned)blocks, 256, 0, s>>>(G.part, (uint16_t*)dx, n / 8, n, G.NCO);
     return check_launch();
 }
 

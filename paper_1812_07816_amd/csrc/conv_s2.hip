@@ -313,8 +313,12 @@ __global__ void __launch_bounds__(256) s2_pack_weights_kernel(const uint16_t* __
     wpack[idx] = w[((((long long)co * 3 + kd) * 3 + kh) * 3 + kw) * Cin + ci];
 }
 
+}  // namespace
+
 // y = bf16(sum over chunks of part[chunk]), chunks added in index order; 8 outputs per thread
-__global__ void __launch_bounds__(256) s2_sum_chunks_kernel(const float* __restrict__ part, uint16_t* __restrict__ y, long long n8, long long n, int nch) {
+__global__ void __launch_bounds__(256) sum_chunks_bf16_kernel(const float* __restrict__ part, uint16_t* __restrict__ y, long long n8, long long n, int nch) {
+    typedef __attribute__((__vector_size__(2 * sizeof(float)))) float f32x2_;
+    typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2_;
     for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < n8; i += (long long)gridDim.x * 256) {
         float a[8];
 #pragma unroll
@@ -326,14 +330,12 @@ __global__ void __launch_bounds__(256) s2_sum_chunks_kernel(const float* __restr
         uint32_t o[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            f32x2 v = {a[2 * j], a[2 * j + 1]};
-            o[j] = __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+            f32x2_ v = {a[2 * j], a[2 * j + 1]};
+            o[j] = __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_));
         }
         *(uint4*)(y + 8 * i) = uint4{o[0], o[1], o[2], o[3]};
     }
 }
-
-}  // namespace
 
 static size_t s2_part_offset(const Geom& g) { return (((size_t)g.w_elems() * 2 + 255) & ~(size_t)255) + 8192; }
 
@@ -394,7 +396,7 @@ int s2_fwd(const Geom& g, const void* x, const void* w, void* y, void* ws, size_
     const long long n = (long long)g.out_voxels() * g.Cout;   // Cout % 32 == 0: a multiple of 8
     long long blocks = (n / 8 + 255) / 256;
     if (blocks > 8192) blocks = 8192;
-    s2_sum_chunks_kernel<<<(unsigned)blocks, 256, 0, s>>>(P.part, (uint16_t*)y, n / 8, n, P.NCH);
+    sum_chunks_bf16_kernel<<<(unsigned)blocks, 256, 0, s>>>(P.part, (uint16_t*)y, n / 8, n, P.NCH);
     return check_launch();
 }
 

@@ -42,6 +42,8 @@ int direct_fwd(const Geom& g, const void* x, const void* w, void* y, hipStream_t
 int direct_dgrad(const Geom& g, const void* dy, const void* w, void* dx, hipStream_t s);
 int direct_wgrad(const Geom& g, const void* x, const void* dy, float* dw, void* ws, size_t ws_bytes, hipStream_t s);
 // out[i] = sum_p part[p*n + i] in a fixed order (bit-reproducible); launch with (n + 15) / 16 blocks of 256
+// y[i] = bf16(sum_c part[c * n + i]), chunks added in index order; n8 = n / 8 outputs of 8
+__global__ void sum_chunks_bf16_kernel(const float* __restrict__ part, uint16_t* __restrict__ y, long long n8, long long n, int nch);
 __global__ void reduce_partials_kernel(const float* __restrict__ part, float* __restrict__ out, long long n, int parts);
 
 
