@@ -99,6 +99,25 @@ int mi3d_conv3d_dgrad(const mi3d_conv_desc *desc, const void *dy, const void *w,
 int mi3d_conv3d_wgrad(const mi3d_conv_desc *desc, const void *x, const void *dy, float *dw,
                       void *ws, size_t ws_bytes, void *stream);
 
+/* Convolution followed by the network's LeakyReLU (Section 4.1) in one call:
+ * y = lrelu(conv(x, w)), lrelu(v) = v > 0 ? v : slope * v, applied to the fp32
+ * accumulator before the single rounding to bf16.  bf16 only, 0 <= slope < 1
+ * (else MI3D_ERR_INVALID_ARG).  The MFMA forward kernels apply it in their
+ * epilogue; other geometries run the convolution and one elementwise pass.
+ * Same workspace as mi3d_conv3d_fwd. */
+int mi3d_conv3d_fwd_lrelu(const mi3d_conv_desc *desc, const void *x, const void *w, void *y, float slope,
+                          void *ws, size_t ws_bytes, void *stream);
+
+/* Data gradient through a convolution AND through the LeakyReLU that produced
+ * its input: dz_in = dgrad(dy, w) * (a_in > 0 ? 1 : slope), where a_in (device,
+ * bf16, shape of x) is the activated input of the layer, whose sign is that of
+ * the pre-activation.  Kernels that sum fp32 partial gradients apply the factor
+ * before the single rounding to bf16; other geometries run mi3d_conv3d_dgrad
+ * and mi3d_leaky_relu_bwd (two roundings).  bf16 only, 0 <= slope < 1.  dz_in
+ * must not alias a_in.  Same workspace as mi3d_conv3d_dgrad. */
+int mi3d_conv3d_dgrad_lrelu(const mi3d_conv_desc *desc, const void *dy, const void *w, const void *a_in, float slope,
+                            void *dx, void *ws, size_t ws_bytes, void *stream);
+
 /* Kernel family used for a pass: 0 = automatic choice, 1 = force the plain
  * one-thread-per-output kernels (slow; for debugging and cross-checks).
  * Process-wide; returns the previous value. */

@@ -51,6 +51,8 @@ SIGNATURES = {
     "mi3d_conv3d_fwd": (_i, [_pd, _vp, _vp, _vp, _vp, _sz, _vp]),
     "mi3d_conv3d_dgrad": (_i, [_pd, _vp, _vp, _vp, _vp, _sz, _vp]),
     "mi3d_conv3d_wgrad": (_i, [_pd, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "mi3d_conv3d_fwd_lrelu": (_i, [_pd, _vp, _vp, _vp, ctypes.c_float, _vp, _sz, _vp]),
+    "mi3d_conv3d_dgrad_lrelu": (_i, [_pd, _vp, _vp, _vp, ctypes.c_float, _vp, _vp, _sz, _vp]),
     "mi3d_conv3d_set_kernel_family": (_i, [_i]),
     "mi3d_conv3d_kernel_name": (_i, [_pd, _i, ctypes.c_char_p, _sz]),
     "mi3d_swap_create": (_i, [ctypes.POINTER(SwapConfig), ctypes.POINTER(_vp)]),

@@ -96,6 +96,33 @@ def conv3d_dgrad(desc, dy, w, dx=None, ws=None):
     return dx
 
 
+def conv3d_fwd_lrelu(desc, x, w, slope, y=None, ws=None):
+    """y = LeakyReLU(conv(x, w)) in one call."""
+    xs, wsh, ys = _shapes(desc)
+    dt = _tdtype(desc)
+    _chk(x, xs, dt, "x"); _chk(w, wsh, dt, "w")
+    if y is None:
+        y = torch.empty(ys, dtype=dt, device=x.device)
+    _chk(y, ys, dt, "y")
+    ws, p, n = _ws(desc, PASS_FWD, ws)
+    check(lib().mi3d_conv3d_fwd_lrelu(ctypes.byref(desc), x.data_ptr(), w.data_ptr(), y.data_ptr(), float(slope), p, n, _stream()), "conv3d_fwd_lrelu")
+    return y
+
+
+def conv3d_dgrad_lrelu(desc, dy, w, a_in, slope, dx=None, ws=None):
+    """dx = dgrad(dy, w) * (a_in > 0 ? 1 : slope): the gradient with respect to the pre-activation of the layer below."""
+    xs, wsh, ys = _shapes(desc)
+    dt = _tdtype(desc)
+    _chk(dy, ys, dt, "dy"); _chk(w, wsh, dt, "w"); _chk(a_in, xs, dt, "a_in")
+    if dx is None:
+        dx = torch.empty(xs, dtype=dt, device=dy.device)
+    _chk(dx, xs, dt, "dx")
+    ws, p, n = _ws(desc, PASS_DGRAD, ws)
+    check(lib().mi3d_conv3d_dgrad_lrelu(ctypes.byref(desc), dy.data_ptr(), w.data_ptr(), a_in.data_ptr(), float(slope), dx.data_ptr(), p, n, _stream()),
+          "conv3d_dgrad_lrelu")
+    return dx
+
+
 def conv3d_wgrad(desc, x, dy, dw=None, ws=None):
     xs, wsh, ys = _shapes(desc)
     dt = _tdtype(desc)

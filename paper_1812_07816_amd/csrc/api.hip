@@ -129,6 +129,13 @@ static int run_kernel(Kernel k, const Geom& g, int pass, const void* a, const vo
     return MI3D_ERR_UNSUPPORTED;
 }
 
+// Kernels that apply the optional epilogue of the geometry themselves (the others are followed by one elementwise pass)
+static bool fuses_epilogue(Kernel k, const Geom& g, int pass) {
+    if (pass == MI3D_PASS_FWD) return k == K_SP || k == K_S2_FWD || k == K_C4_FWD;
+    if (pass == MI3D_PASS_DGRAD) return (k == K_SP && sp_fuses_dgrad_factor(g)) || (k == K_DGRAD_S2 && dgrad_s2_fuses_factor(g));
+    return false;
+}
+
 // automatic choice for a geometry, used by the entry points and by fallbacks that re-enter with a derived geometry
 size_t auto_workspace_bytes(const Geom& g, int pass) { return kernel_workspace(choose(g, pass), g, pass); }
 int auto_conv(const Geom& g, int pass, const void* a, const void* b, void* out, void* ws, size_t ws_bytes, hipStream_t s) {
@@ -189,7 +196,9 @@ size_t mi3d_conv3d_workspace_bytes(const mi3d_conv_desc* desc, int pass) {
     return plain > chosen ? plain : chosen;
 }
 
-static int conv_entry(const mi3d_conv_desc* desc, int pass, const void* a, const void* b, void* out, void* ws, size_t ws_bytes, void* stream) {
+// slope / ref: optional LeakyReLU epilogue (forward: on y; data gradient: derivative factor from ref), 1 / null = none
+static int conv_entry(const mi3d_conv_desc* desc, int pass, const void* a, const void* b, void* out, void* ws, size_t ws_bytes, void* stream,
+                      float slope = 1.f, const void* ref = nullptr) {
     Geom g;
     int st = make_geom(desc, &g);
     if (st) return st;
@@ -197,7 +206,20 @@ static int conv_entry(const mi3d_conv_desc* desc, int pass, const void* a, const
     if (ws_bytes && !ws) return MI3D_ERR_INVALID_ARG;
     if (ws_bytes < mi3d_conv3d_workspace_bytes(desc, pass)) return MI3D_ERR_WORKSPACE;
     Kernel k = g_family.load() == 1 ? K_DIRECT : choose(g, pass);
-    return run_kernel(k, g, pass, a, b, out, ws, ws_bytes, (hipStream_t)stream);
+    const bool epilogue = slope != 1.f;
+    if (!epilogue) return run_kernel(k, g, pass, a, b, out, ws, ws_bytes, (hipStream_t)stream);
+    if (!(slope >= 0.f && slope < 1.f) || g.dtype != MI3D_BF16 || pass == MI3D_PASS_WGRAD) return MI3D_ERR_INVALID_ARG;
+    if (pass == MI3D_PASS_DGRAD && (!ref || !aligned16(ref))) return MI3D_ERR_INVALID_ARG;
+    Geom ge = g;
+    ge.slope = slope;
+    ge.ref = ref;
+    if (fuses_epilogue(k, ge, pass)) return run_kernel(k, ge, pass, a, b, out, ws, ws_bytes, (hipStream_t)stream);
+    st = run_kernel(k, g, pass, a, b, out, ws, ws_bytes, (hipStream_t)stream);
+    if (st) return st;
+    const long long n = pass == MI3D_PASS_FWD ? g.out_voxels() * g.Cout : g.in_voxels() * g.Cin;
+    if (n % 8) return MI3D_ERR_UNSUPPORTED;
+    if (pass == MI3D_PASS_FWD) return mi3d_leaky_relu_fwd(out, n, slope, stream);
+    return mi3d_leaky_relu_bwd(out, ref, n, slope, stream);
 }
 
 int mi3d_conv3d_fwd(const mi3d_conv_desc* desc, const void* x, const void* w, void* y, void* ws, size_t ws_bytes, void* stream) {
@@ -210,6 +232,17 @@ int mi3d_conv3d_dgrad(const mi3d_conv_desc* desc, const void* dy, const void* w,
 
 int mi3d_conv3d_wgrad(const mi3d_conv_desc* desc, const void* x, const void* dy, float* dw, void* ws, size_t ws_bytes, void* stream) {
     return conv_entry(desc, MI3D_PASS_WGRAD, x, dy, dw, ws, ws_bytes, stream);
+}
+
+int mi3d_conv3d_fwd_lrelu(const mi3d_conv_desc* desc, const void* x, const void* w, void* y, float slope, void* ws, size_t ws_bytes, void* stream) {
+    if (slope == 1.f) return MI3D_ERR_INVALID_ARG;
+    return conv_entry(desc, MI3D_PASS_FWD, x, w, y, ws, ws_bytes, stream, slope, nullptr);
+}
+
+int mi3d_conv3d_dgrad_lrelu(const mi3d_conv_desc* desc, const void* dy, const void* w, const void* a_in, float slope, void* dx,
+                            void* ws, size_t ws_bytes, void* stream) {
+    if (slope == 1.f) return MI3D_ERR_INVALID_ARG;
+    return conv_entry(desc, MI3D_PASS_DGRAD, dy, w, dx, ws, ws_bytes, stream, slope, a_in);
 }
 
 }  // extern "C"

@@ -33,6 +33,7 @@ struct C4Params {
     int N, D, H, W, Cout, Do, Ho, Wo, pD, pH, pW, HT, WT;
     long long tiles;        // N*Do*HT*WT
     int nwg;
+    float slope;            // LeakyReLU slope applied to the output (1 = none)
 };
 
 // Persistent workgroups walk a contiguous range of (n, od, 16-row, 32-col) tiles; the input patch of
@@ -138,7 +139,7 @@ __global__ void __launch_bounds__(256, 2) c4_fwd_kernel(C4Params P) {
                 uint32_t o[8];
 #pragma unroll
                 for (int i = 0; i < 8; ++i) {
-                    f32x2 v = {acc[r][2 * i], acc[r][2 * i + 1]};
+                    f32x2 v = {fmaxf(acc[r][2 * i], P.slope * acc[r][2 * i]), fmaxf(acc[r][2 * i + 1], P.slope * acc[r][2 * i + 1])};  // LeakyReLU, 0 <= slope <= 1
                     bf16x2 bb = __builtin_convertvector(v, bf16x2);
                     o[i] = __builtin_bit_cast(uint32_t, bb);
                 }
@@ -211,6 +212,7 @@ int c4_fwd(const Geom& g, const void* x, const void* w, void* y, void* ws, size_
     P.WT = (g.Wo + TW - 1) / TW;
     P.tiles = (long long)g.N * g.Do * P.HT * P.WT;
     P.nwg = (int)(P.tiles < 512 ? P.tiles : 512);
+    P.slope = g.slope;
     if (g.Cout == 32) c4_fwd_kernel<true><<<(unsigned)P.nwg, 256, 0, s>>>(P);
     else c4_fwd_kernel<false><<<(unsigned)P.nwg, 256, 0, s>>>(P);
     return check_launch();

@@ -322,6 +322,9 @@ bool dgrad_s2_supported(const Geom& g) {
     return g.Cin % 32 == 0 && (g.Cout == 32 || g.Cout % 64 == 0);
 }
 
+// the chunked variant applies the optional derivative factor of the geometry while it sums the chunks
+bool dgrad_s2_fuses_factor(const Geom& g) { return dgrad_s2_supported(g) && g.Cout > 64; }
+
 size_t dgrad_s2_workspace_bytes(const Geom& g) {
     if (!dgrad_s2_supported(g)) return 0;
     size_t b = dg2_part_offset(g);   // packed weights + store dump area
@@ -377,7 +380,7 @@ int dgrad_s2(const Geom& g, const void* dy, const void* w, void* dx, void* ws, s
     const long long n = (long long)g.in_voxels() * g.Cin;
     long long blocks = (n / 8 + 255) / 256;
     if (blocks > 8192) blocks = 8192;
-    sum_chunks_bf16_kernel<<<(unsigned)blocks, 256, 0, s>>>(G.part, (uint16_t*)dx, n / 8, n, G.NCO);
+    sum_chunks_bf16_kernel<<<(unsigned)blocks, 256, 0, s>>>(G.part, (uint16_t*)dx, n / 8, n, G.NCO, g.slope, (const uint16_t*)g.ref);
     return check_launch();
 }
 

@@ -39,6 +39,7 @@ struct S2Params {
     int HT, WT, CT, NCH;    // tiles per plane, cout tiles, cin chunks
     long long units;
     int nwg;
+    float slope;            // LeakyReLU slope applied to the output (1 = none)
 };
 
 __device__ __forceinline__ f32x16 mfma(bf16x8 a, bf16x8 b, f32x16 c) {
@@ -97,14 +98,14 @@ __device__ __forceinline__ void plane_compute(f32x16 (&acc)[2][RH], const char* 
 
 // Stores are unconditional (masked lanes write to the dump area): behind a branch the compiler cannot count
 // them and makes the LDS write that follows wait for vmcnt(0), i.e. for the stores themselves.
-__device__ __forceinline__ void store_rows(const f32x16 (&a)[RH], uint16_t* p, long long row_pitch, bool col_ok, int rows_ok, uint16_t* dump) {
+__device__ __forceinline__ void store_rows(const f32x16 (&a)[RH], uint16_t* p, long long row_pitch, bool col_ok, int rows_ok, uint16_t* dump, float slope) {
     typedef __attribute__((ext_vector_type(2))) unsigned u32x2;
 #pragma unroll
     for (int r = 0; r < RH; ++r) {
         uint32_t o[8];
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-            f32x2 v = {a[r][2 * i], a[r][2 * i + 1]};
+            f32x2 v = {fmaxf(a[r][2 * i], slope * a[r][2 * i]), fmaxf(a[r][2 * i + 1], slope * a[r][2 * i + 1])};  // LeakyReLU, 0 <= slope <= 1
             bf16x2 b = __builtin_convertvector(v, bf16x2);
             o[i] = __builtin_bit_cast(uint32_t, b);
         }
@@ -273,7 +274,7 @@ __global__ void __launch_bounds__(256, 1) s2_fwd_kernel(S2Params P) {
                 const long long off_ = ((long long)od_ * P.Ho + oh0) * row_pitch + (long long)ow * P.Cout;  \
                 if (PART) store_rows_f32(acc[1 - (SET)], pn + off_ + (ct * CB + cb) * 32 + 4 * (lane >> 5), row_pitch, \
                                          tq >= 2 && ow < P.Wo, P.Ho - oh0, (float*)P.dump + lane * 32); \
-                else store_rows(acc[1 - (SET)], yn + off_ + co0, row_pitch, tq >= 2 && ow < P.Wo, P.Ho - oh0, P.dump + lane * 16); \
+                else store_rows(acc[1 - (SET)], yn + off_ + co0, row_pitch, tq >= 2 && ow < P.Wo, P.Ho - oh0, P.dump + lane * 16, P.slope); \
             }                                                                                    \
             __syncthreads();                                                                     \
             write_plane(1 - rs_);                                                                \
@@ -315,8 +316,11 @@ __global__ void __launch_bounds__(256) s2_pack_weights_kernel(const uint16_t* __
 
 }  // namespace
 
-// y = bf16(sum over chunks of part[chunk]), chunks added in index order; 8 outputs per thread
-__global__ void __launch_bounds__(256) sum_chunks_bf16_kernel(const float* __restrict__ part, uint16_t* __restrict__ y, long long n8, long long n, int nch) {
+// y = bf16(act(sum over chunks of part[chunk])), chunks added in index order; 8 outputs per thread.
+// act: LeakyReLU with `slope` (1 = none) if ref is null; otherwise the factor of element i is 1 where
+// ref[i] > 0 and `slope` elsewhere (LeakyReLU derivative taken from the activated tensor ref).
+__global__ void __launch_bounds__(256) sum_chunks_bf16_kernel(const float* __restrict__ part, uint16_t* __restrict__ y, long long n8, long long n, int nch,
+                                                              float slope, const uint16_t* __restrict__ ref) {
     typedef __attribute__((__vector_size__(2 * sizeof(float)))) float f32x2_;
     typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2_;
     for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < n8; i += (long long)gridDim.x * 256) {
@@ -326,6 +330,18 @@ __global__ void __launch_bounds__(256) sum_chunks_bf16_kernel(const float* __res
         for (int c = 0; c < nch; ++c) {
             const float4 lo = *(const float4*)(part + c * n + 8 * i), hi = *(const float4*)(part + c * n + 8 * i + 4);
             a[0] += lo.x; a[1] += lo.y; a[2] += lo.z; a[3] += lo.w; a[4] += hi.x; a[5] += hi.y; a[6] += hi.z; a[7] += hi.w;
+        }
+        if (ref) {
+            const uint4 m4 = *(const uint4*)(ref + 8 * i);
+            const uint32_t m[4] = {m4.x, m4.y, m4.z, m4.w};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                if (!((int)(m[j] << 16) > 0)) a[2 * j] *= slope;
+                if (!((int)(m[j] & 0xFFFF0000u) > 0)) a[2 * j + 1] *= slope;
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) a[j] = fmaxf(a[j], slope * a[j]);
         }
         uint32_t o[4];
 #pragma unroll
@@ -376,6 +392,7 @@ int s2_fwd(const Geom& g, const void* x, const void* w, void* y, void* ws, size_
     if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
     long long nwg = cus < P.units ? cus : P.units;
     P.nwg = (int)nwg;
+    P.slope = g.slope;
     const size_t lds2 = 2 * WB_BYTES + 4 * (2 * TH + 1) * PITCH * 16, lds1 = WB_BYTES + 4 * (4 * TH + 1) * PITCH * 16;
     static bool attr_set = false;
     if (!attr_set) {
@@ -396,7 +413,7 @@ int s2_fwd(const Geom& g, const void* x, const void* w, void* y, void* ws, size_
     const long long n = (long long)g.out_voxels() * g.Cout;   // Cout % 32 == 0: a multiple of 8
     long long blocks = (n / 8 + 255) / 256;
     if (blocks > 8192) blocks = 8192;
-    sum_chunks_bf16_kernel<<<(unsigned)blocks, 256, 0, s>>>(P.part, (uint16_t*)y, n / 8, n, P.NCH);
+    sum_chunks_bf16_kernel<<<(unsigned)blocks, 256, 0, s>>>(P.part, (uint16_t*)y, n / 8, n, P.NCH, g.slope, nullptr);
     return check_launch();
 }
 

@@ -41,6 +41,7 @@ struct SpParams {
     uint16_t* dump;         // 8 KB that masked store lanes write to instead of y
     float* part;            // [cin chunk][voxel][Cout] fp32 partial outputs (chunked variant)
     int NCH;                // cin chunks of the chunked variant
+    float slope;            // LeakyReLU slope applied to the output (1 = none)
     int N, D, H, W, Cin, Cout, Do, Ho, Wo, pD, pH, pW;
     int HT, WT, CT;         // tiles per plane, cout tiles
     long long units;        // N*CT*HT*WT*Do
@@ -92,8 +93,8 @@ __device__ __forceinline__ void group_mfma(f32x16 (&acc)[3][RH], const XFrag& x,
     }
 }
 
-__device__ __forceinline__ void convert_rows(const f32x16 (&a)[RH], uint32_t (&o)[RH][8]);
-__device__ __forceinline__ void convert_rows(const f32x16 (&a)[RH], float (&o)[RH][16]);
+__device__ __forceinline__ void convert_rows(const f32x16 (&a)[RH], uint32_t (&o)[RH][8], float slope);
+__device__ __forceinline__ void convert_rows(const f32x16 (&a)[RH], float (&o)[RH][16], float slope);
 
 #define SP_FENCE() __builtin_amdgcn_sched_barrier(0)
 
@@ -102,14 +103,14 @@ __device__ __forceinline__ void convert_rows(const f32x16 (&a)[RH], float (&o)[R
 // are in flight for at least one group of MFMAs.
 template <int PH, int SUB, bool ZERO, bool LAST, class Out, class Hook>
 __device__ __forceinline__ void sub_step(f32x16 (&acc)[3][RH], XFrag& xc, XFrag& xn, WFrag& w2, WFrag& w1, WFrag& w0,
-                                         const char* in_lane, const char* w_lane, Out& outp, int kdmask, Hook&& hook) {
+                                         const char* in_lane, const char* w_lane, Out& outp, float slope, int kdmask, Hook&& hook) {
     constexpr bool last = SUB == 5;
     load_w<SUB, 0>(w0, w_lane);
     if (kdmask & 4) group_mfma<PH, SUB, 2, ZERO>(acc, xc, w2);
     hook(3 * SUB + 0);
     SP_FENCE();
     if (!last) load_x<last ? 0 : SUB + 1>(xn, in_lane);
-    if (last && LAST) convert_rows(acc[(PH + 1) % 3], outp);
+    if (last && LAST) convert_rows(acc[(PH + 1) % 3], outp, slope);
     if (kdmask & 2) group_mfma<PH, SUB, 1, ZERO>(acc, xc, w1);
     hook(3 * SUB + 1);
     SP_FENCE();
@@ -133,36 +134,36 @@ __device__ __forceinline__ void sub_step(f32x16 (&acc)[3][RH], XFrag& xc, XFrag&
 // a weight slot and synchronises there).
 template <int PH, bool ZERO, bool LAST, class Out, class Hook, class PhaseEnd>
 __device__ __forceinline__ void plane_compute(f32x16 (&acc)[3][RH], const char* in_lane, const char* w_lane,
-                                              Out& outp, int kdmask, Hook&& hook, PhaseEnd&& phase_end) {
+                                              Out& outp, float slope, int kdmask, Hook&& hook, PhaseEnd&& phase_end) {
     XFrag xa, xb;
     WFrag w2, w1, w0;
     load_x<0>(xa, in_lane);
     load_w<0, 2>(w2, w_lane);
     load_w<0, 1>(w1, w_lane);
-    sub_step<PH, 0, ZERO, LAST>(acc, xa, xb, w2, w1, w0, in_lane, w_lane, outp, kdmask, hook);
-    sub_step<PH, 1, ZERO, LAST>(acc, xb, xa, w2, w1, w0, in_lane, w_lane, outp, kdmask, hook);
+    sub_step<PH, 0, ZERO, LAST>(acc, xa, xb, w2, w1, w0, in_lane, w_lane, outp, slope, kdmask, hook);
+    sub_step<PH, 1, ZERO, LAST>(acc, xb, xa, w2, w1, w0, in_lane, w_lane, outp, slope, kdmask, hook);
     phase_end(0);
-    sub_step<PH, 2, ZERO, LAST>(acc, xa, xb, w2, w1, w0, in_lane, w_lane, outp, kdmask, hook);
-    sub_step<PH, 3, ZERO, LAST>(acc, xb, xa, w2, w1, w0, in_lane, w_lane, outp, kdmask, hook);
+    sub_step<PH, 2, ZERO, LAST>(acc, xa, xb, w2, w1, w0, in_lane, w_lane, outp, slope, kdmask, hook);
+    sub_step<PH, 3, ZERO, LAST>(acc, xb, xa, w2, w1, w0, in_lane, w_lane, outp, slope, kdmask, hook);
     phase_end(1);
-    sub_step<PH, 4, ZERO, LAST>(acc, xa, xb, w2, w1, w0, in_lane, w_lane, outp, kdmask, hook);
-    sub_step<PH, 5, ZERO, LAST>(acc, xb, xa, w2, w1, w0, in_lane, w_lane, outp, kdmask, hook);
+    sub_step<PH, 4, ZERO, LAST>(acc, xa, xb, w2, w1, w0, in_lane, w_lane, outp, slope, kdmask, hook);
+    sub_step<PH, 5, ZERO, LAST>(acc, xb, xa, w2, w1, w0, in_lane, w_lane, outp, slope, kdmask, hook);
 }
 
-// fp32 accumulators of one finished output plane -> packed bf16 (RNE)
-__device__ __forceinline__ void convert_rows(const f32x16 (&a)[RH], uint32_t (&o)[RH][8]) {
+// fp32 accumulators of one finished output plane -> LeakyReLU (max(v, slope v), 0 <= slope <= 1) -> packed bf16 (RNE)
+__device__ __forceinline__ void convert_rows(const f32x16 (&a)[RH], uint32_t (&o)[RH][8], float slope) {
 #pragma unroll
     for (int r = 0; r < RH; ++r)
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-            f32x2 v = {a[r][2 * i], a[r][2 * i + 1]};
+            f32x2 v = {fmaxf(a[r][2 * i], slope * a[r][2 * i]), fmaxf(a[r][2 * i + 1], slope * a[r][2 * i + 1])};
             bf16x2 b = __builtin_convertvector(v, bf16x2);
             o[r][i] = __builtin_bit_cast(uint32_t, b);
         }
 }
 
-// chunked variant: the fp32 accumulators are kept as they are
-__device__ __forceinline__ void convert_rows(const f32x16 (&a)[RH], float (&o)[RH][16]) {
+// chunked variant: the fp32 accumulators are kept as they are (the activation follows the sum of the chunks)
+__device__ __forceinline__ void convert_rows(const f32x16 (&a)[RH], float (&o)[RH][16], float) {
 #pragma unroll
     for (int r = 0; r < RH; ++r)
 #pragma unroll
@@ -391,7 +392,7 @@ __global__ void __launch_bounds__(256, 1) sp_conv_kernel(SpParams P) {
             for (int kd_ = 0; kd_ < 3; ++kd_)                                                   \
                 if (jj - kd_ >= 0 && jj - kd_ < nJ - 2) kdmask_ |= 1 << kd_;                    \
             plane_compute<PHASE, ZERO, LAST>(acc, in_lds + buf_ * STAGE_BYTES + lane_in_off,    \
-                                             w_lane + (STREAM ? 0 : (CHUNK) * W_BYTES), outp, kdmask_, [&](int k) { \
+                                             w_lane + (STREAM ? 0 : (CHUNK) * W_BYTES), outp, P.slope, kdmask_, [&](int k) { \
                 if (STREAM && k % 6 == 0) { /* all pieces of the slot at the start of its phase: a full phase of cover */ \
                     _Pragma("unroll") for (int i_ = 0; i_ < NWL; ++i_) wreg[i_] = *(const uint4*)(wsrc_[k / 6] + wpiece[i_] * 16); \
                 }                                                                               \
@@ -491,6 +492,9 @@ static bool sp_use_chunks(const Geom& g, int pass) {
     return cin >= 96 && vox <= 64ll * 64 * 64;
 }
 
+// the chunked variant applies the optional derivative factor of the geometry while it sums the chunks
+bool sp_fuses_dgrad_factor(const Geom& g) { return sp_supported(g, MI3D_PASS_DGRAD) && sp_use_chunks(g, MI3D_PASS_DGRAD); }
+
 static size_t sp_part_offset(const Geom& g) { return (((size_t)g.w_elems() * 2 + 255) & ~(size_t)255) + 8192; }
 
 size_t sp_workspace_bytes(const Geom& g, int pass) {
@@ -531,6 +535,7 @@ int sp_conv(const Geom& g, int pass, const void* in, const void* w, void* out, v
     P.CT = P.Cout / 32;
     const bool chunks = sp_use_chunks(g, pass);
     P.NCH = chunks ? P.Cin / 32 : 1;
+    P.slope = pass == MI3D_PASS_FWD ? g.slope : 1.f;
     P.units = (long long)P.N * P.CT * P.NCH * P.HT * P.WT * P.Do;
     int dev = 0, cus = 256;
     if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
@@ -555,7 +560,7 @@ int sp_conv(const Geom& g, int pass, const void* in, const void* w, void* out, v
         const long long n = (long long)P.N * P.Do * P.Ho * P.Wo * P.Cout;   // a multiple of 32
         long long blocks = (n / 8 + 255) / 256;
         if (blocks > 8192) blocks = 8192;
-        sum_chunks_bf16_kernel<<<(unsigned)blocks, 256, 0, s>>>(P.part, (uint16_t*)out, n / 8, n, P.NCH);
+        sum_chunks_bf16_kernel<<<(unsigned)blocks, 256, 0, s>>>(P.part, (uint16_t*)out, n / 8, n, P.NCH, g.slope, pass == MI3D_PASS_DGRAD ? (const uint16_t*)g.ref : nullptr);
         return check_launch();
     }
     if (nc == 1) sp_conv_kernel<1><<<(unsigned)nwg, 256, lds1, s>>>(P);

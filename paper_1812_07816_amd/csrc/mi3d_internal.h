@@ -15,6 +15,11 @@ struct Geom {
     int sD, sH, sW, pD, pH, pW;
     int Do, Ho, Wo;
     int dtype;
+    // Optional fused epilogue, set by the dispatcher only for kernels that implement it.  Forward: LeakyReLU with
+    // `slope` on the output.  Data gradient: dx is multiplied by (ref > 0 ? 1 : slope), the LeakyReLU derivative of
+    // the layer below, whose activated output `ref` has the shape of dx.
+    float slope = 1.f;
+    const void* ref = nullptr;
     __host__ __device__ long long in_voxels() const { return (long long)N * D * H * W; }
     __host__ __device__ long long out_voxels() const { return (long long)N * Do * Ho * Wo; }
     __host__ __device__ long long taps() const { return (long long)kD * kH * kW; }
@@ -42,8 +47,10 @@ int direct_fwd(const Geom& g, const void* x, const void* w, void* y, hipStream_t
 int direct_dgrad(const Geom& g, const void* dy, const void* w, void* dx, hipStream_t s);
 int direct_wgrad(const Geom& g, const void* x, const void* dy, float* dw, void* ws, size_t ws_bytes, hipStream_t s);
 // out[i] = sum_p part[p*n + i] in a fixed order (bit-reproducible); launch with (n + 15) / 16 blocks of 256
-// y[i] = bf16(sum_c part[c * n + i]), chunks added in index order; n8 = n / 8 outputs of 8
-__global__ void sum_chunks_bf16_kernel(const float* __restrict__ part, uint16_t* __restrict__ y, long long n8, long long n, int nch);
+// y[i] = bf16(act(sum_c part[c * n + i])), chunks added in index order; n8 = n / 8 outputs of 8; act = LeakyReLU with
+// `slope` (ref null) or the factor (ref[i] > 0 ? 1 : slope)
+__global__ void sum_chunks_bf16_kernel(const float* __restrict__ part, uint16_t* __restrict__ y, long long n8, long long n, int nch,
+                                       float slope, const uint16_t* __restrict__ ref);
 __global__ void reduce_partials_kernel(const float* __restrict__ part, float* __restrict__ out, long long n, int parts);
 
 
@@ -51,6 +58,7 @@ __global__ void reduce_partials_kernel(const float* __restrict__ part, float* __
 bool sp_supported(const Geom& g, int pass);
 size_t sp_workspace_bytes(const Geom& g, int pass);
 int sp_conv(const Geom& g, int pass, const void* in, const void* w, void* out, void* ws, size_t ws_bytes, hipStream_t s);
+bool sp_fuses_dgrad_factor(const Geom& g);  // the forward LeakyReLU is always fused
 
 
 // MFMA weight gradient: bf16, 3x3x3, stride 1, channels in multiples of 32
@@ -80,10 +88,11 @@ size_t wgrad_s2_workspace_bytes(const Geom& g);
 int wgrad_s2(const Geom& g, const void* x, const void* dy, float* dw, void* ws, size_t ws_bytes, hipStream_t s);
 
 
-// first-layer kernels (4 input channels)
+// 2x2x2 stride-2 pad-0 layers (decoder up-sampling): forward (gather) and data gradient (scatter) as panel GEMMs
 bool k2_supported(const Geom& g, int pass);
 size_t k2_workspace_bytes(const Geom& g, int pass);
 int k2_conv(const Geom& g, int pass, const void* a, const void* w, void* out, void* ws, size_t ws_bytes, hipStream_t s);
+// first-layer kernels (4 input channels)
 bool c4_fwd_supported(const Geom& g);
 size_t c4_fwd_workspace_bytes(const Geom& g);
 int c4_fwd(const Geom& g, const void* x, const void* w, void* y, void* ws, size_t ws_bytes, hipStream_t s);
@@ -99,6 +108,7 @@ int c4_wgrad(const Geom& g, const void* x, const void* dy, float* dw, void* ws, 
 bool dgrad_s2_supported(const Geom& g);
 size_t dgrad_s2_workspace_bytes(const Geom& g);
 int dgrad_s2(const Geom& g, const void* dy, const void* w, void* dx, void* ws, size_t ws_bytes, hipStream_t s);
+bool dgrad_s2_fuses_factor(const Geom& g);
 
 
 // 1x1x1 convolution to <= 4 output channels (segmentation head), all passes

@@ -2,8 +2,8 @@
 
 Every arithmetic step is a call into libmi3d.so: the convolutions
 (conv3d_fwd / dgrad / wgrad; the 2x2x2 stride-2 transposed convolution is the
-data gradient of a 2x2x2 / stride-2 convolution with roles swapped), LeakyReLU,
-channel concatenation, sigmoid + soft Dice, SGD.  Saved feature maps (the
+data gradient of a 2x2x2 / stride-2 convolution with roles swapped; LeakyReLU
+rides in the convolution calls where it can), channel concatenation, sigmoid + soft Dice, SGD.  Saved feature maps (the
 inputs of the convolutions, Section 3.1 of the paper) live in the swap engine's
 arena and are moved to pinned host memory and back according to its plan.
 
@@ -118,6 +118,12 @@ class UNetStep:
         self.ops.append(dict(kind="loss", name="loss", src=logits))
         self.n_fwd = len(self.ops)
         self.n_ops = 2 * self.n_fwd
+        # a convolution whose input is the activation of the convolution right before it, read by nobody else
+        skip_ids = {s.id for s in skips}
+        for f, op in enumerate(self.ops):
+            if op["kind"] == "conv":
+                prev = self.ops[f - 1]
+                op["through_act"] = prev["kind"] == "conv" and prev["out"] is op["src"] and op["src"].id not in skip_ids
         # backward readers: conv f reads its input (weight gradient) and its output (LeakyReLU derivative); up and head
         # read their input (weight gradient); the loss reads the logits
         for f, op in enumerate(self.ops):
@@ -261,8 +267,7 @@ class UNetStep:
                     trace["input.a"] = op["out"].view.clone()
             elif k == "conv":
                 out = self._produce(op["out"])
-                mc.conv3d_fwd(op["desc"], op["src"].view, self.w[op["w"]], out, self.ws)
-                glue.leaky_relu_fwd(out, SLOPE)
+                mc.conv3d_fwd_lrelu(op["desc"], op["src"].view, self.w[op["w"]], SLOPE, out, self.ws)
                 if trace is not None:
                     trace[op["name"] + ".a"] = out.clone()
             elif k == "up":
@@ -286,6 +291,7 @@ class UNetStep:
             mark(op["name"], "fwd")
         # backward
         da = None              # gradient with respect to the output of the op being walked back
+        premasked = False      # da already carries the LeakyReLU derivative of the op being walked back
         dskip = {}
         for f in range(self.n_fwd - 1, -1, -1):
             op, b = self.ops[f], self.bwd_op(f)
@@ -304,7 +310,9 @@ class UNetStep:
                 mc.conv3d_dgrad(op["desc"], da, self.w[op["w"]], nxt, self.ws)
                 da = nxt
             elif k == "conv":
-                glue.leaky_relu_bwd(da, self._need(op["out"]), SLOPE)
+                if not premasked:
+                    glue.leaky_relu_bwd(da, self._need(op["out"]), SLOPE)
+                premasked = False
                 if trace is not None:
                     trace[op["name"] + ".dz"] = da.clone()
                 mc.conv3d_wgrad(op["desc"], self._need(op["src"]), da, self.dw[op["w"]], self.ws)
@@ -312,7 +320,13 @@ class UNetStep:
                     da = None      # the network input needs no gradient
                 else:
                     nxt = torch.empty(op["src"].shape, dtype=bf, device="cuda")
-                    mc.conv3d_dgrad(op["desc"], da, self.w[op["w"]], nxt, self.ws)
+                    if op["through_act"]:
+                        # the input is the previous convolution's activation and nothing else feeds its gradient:
+                        # the data gradient applies that LeakyReLU's derivative as well
+                        mc.conv3d_dgrad_lrelu(op["desc"], da, self.w[op["w"]], self._need(op["src"]), SLOPE, nxt, self.ws)
+                        premasked = True
+                    else:
+                        mc.conv3d_dgrad(op["desc"], da, self.w[op["w"]], nxt, self.ws)
                     da = nxt
                     if op["src"].id in dskip:          # the input is also a skip connection: add its second gradient
                         if trace is not None:

@@ -1,0 +1,81 @@
+"""GPU-vs-oracle parity of the convolution entry points with the LeakyReLU epilogue:
+conv3d_fwd_lrelu (y = lrelu(conv(x, w))) and conv3d_dgrad_lrelu (dx = dgrad(dy, w) * lrelu'(a_in)).
+The oracle side is the fp64 convolution followed by the network's LeakyReLU (Section 4.1) written out with
+numpy; tolerance as for the plain bf16 passes.  The geometries cover every kernel that applies the epilogue
+itself (stride-1 plane streaming with 1, 2 and more input-channel chunks, the chunked variants, the stride-2
+forward kernels, the 4-channel first layer) and ones that fall back to a separate elementwise pass."""
+import numpy as np
+import pytest
+import torch
+
+import synth_inputs as si
+from oracle import conv3d as oc
+from oracle import unet as ou
+from paper_1812_07816_amd import conv3d as mc
+from tests import parity
+
+pytestmark = pytest.mark.gpu
+
+CASES = [
+    # N, D, H, W, Cin, Cout, k, s, p
+    (1, 10, 20, 40, 32, 32, 3, 1, 1),     # plane streaming, one chunk
+    (1, 8, 16, 32, 64, 32, 3, 1, 1),      # two chunks (forward) / one chunk, two cout tiles (data gradient)
+    (1, 65, 65, 66, 128, 32, 3, 1, 1),    # streamed weights (volume above the chunked variant's limit); sampled
+    (1, 6, 6, 12, 128, 64, 3, 1, 1),      # chunked variant, forward
+    (1, 4, 6, 12, 64, 128, 3, 1, 1),      # chunked variant, data gradient
+    (1, 4, 4, 6, 320, 320, 3, 1, 1),
+    (2, 12, 20, 36, 4, 32, 3, 1, 1),      # first layer
+    (1, 12, 14, 34, 32, 64, 3, 2, 1),     # stride 2, one chunk
+    (1, 12, 12, 12, 64, 128, 3, 2, 1),    # stride 2, chunked forward and chunked data gradient
+    (1, 9, 21, 37, 32, 32, 3, 2, 1),
+    (1, 8, 8, 16, 32, 64, 2, 2, 0),       # up-sampling geometry: separate elementwise pass
+    (2, 9, 10, 37, 8, 8, 3, 1, 1),        # operand embedding: separate elementwise pass
+]
+
+
+@pytest.mark.parametrize("case", CASES)
+def test_fwd_lrelu_and_dgrad_lrelu(device, case):
+    N, D, H, W, Cin, Cout, k, s, p = case
+    x, w, dy = si.conv_case(92, 10 * CASES.index(case), N, D, H, W, Cin, Cout, k, s, p, True)
+    g = oc.shape(N, D, H, W, Cin, Cout, k, s, p)
+    desc = mc.make_desc(N, D, H, W, Cin, Cout, k, s, p, torch.bfloat16)
+    xd, wd, dyd = parity.to_device(x, True), parity.to_device(w, True), parity.to_device(dy, True)
+    tol = parity.TOL["bf16"]
+
+    full = N * D * H * W * Cin * Cout * 27 < 4e9
+    y = parity.to_host(mc.conv3d_fwd_lrelu(desc, xd, wd, ou.SLOPE))
+    if full:
+        ref = ou._lrelu(oc.fwd(g, x, w))
+    else:
+        idx = parity.structured_and_random(y.shape, 20000, 1)
+        y, ref = y.ravel()[idx], ou._lrelu(oc.fwd_at(g, x, w, idx))
+    e_f = oc.rel_err(y, ref)
+    # the activation must have been applied: negative outputs are scaled, not clipped and not left alone
+    neg = ref < 0
+    assert neg.any() and (~neg).any()
+    e_neg = oc.rel_err(y[neg], ref[neg])
+
+    # x doubles as the activated input of the layer (mixed signs)
+    dxd = mc.conv3d_dgrad_lrelu(desc, dyd, wd, xd, ou.SLOPE)
+    dx = parity.to_host(dxd)
+    if full:
+        ref_d = ou._lrelu_grad(x.astype(np.float64), oc.dgrad(g, dy, w))
+        e_d = oc.rel_err(dx, ref_d)
+    else:
+        idx = parity.structured_and_random(dx.shape, 20000, 2)
+        ref_d = ou._lrelu_grad(x.astype(np.float64).ravel()[idx], oc.dgrad_at(g, dy, w, idx))
+        e_d = oc.rel_err(dx.ravel()[idx], ref_d)
+    print(case, f"fwd {e_f:.2e} (negative part {e_neg:.2e}) dgrad {e_d:.2e}", flush=True)
+    assert e_f <= tol and e_neg <= tol and e_d <= tol
+
+
+def test_epilogue_argument_checks(device):
+    desc = mc.make_desc(1, 4, 4, 4, 32, 32, 3, 1, 1, torch.bfloat16)
+    x = torch.zeros((1, 4, 4, 4, 32), dtype=torch.bfloat16, device="cuda")
+    w = torch.zeros((32, 3, 3, 3, 32), dtype=torch.bfloat16, device="cuda")
+    for bad in (1.0, 1.5, -0.1):
+        with pytest.raises(RuntimeError):
+            mc.conv3d_fwd_lrelu(desc, x, w, bad)
+    d32 = mc.make_desc(1, 4, 4, 4, 4, 4, 3, 1, 1, torch.float32)
+    with pytest.raises(RuntimeError):
+        mc.conv3d_fwd_lrelu(d32, torch.zeros((1, 4, 4, 4, 4), device="cuda"), torch.zeros((4, 3, 3, 3, 4), device="cuda"), 0.01)
