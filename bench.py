@@ -170,10 +170,33 @@ def unet_train_step(steps=3, warmup=1):
         st.close()
         del st
         torch.cuda.empty_cache()
+    # Swapping against re-computation and their mix (Section 5) at the same tight budgets: a dropped tensor is
+    # produced again by its convolution at its first backward use; the mix re-computes where that costs less
+    # compute time than the swap-in would take on the link
+    from paper_1812_07816_amd import swap as sw
+    comp = []
+    for budget in (peak - (5 << 28), peak - (9 << 28), peak - (13 << 28)):
+        for name, ev in (("swap", sw.EVICT_SWAP), ("recompute", sw.EVICT_RECOMPUTE), ("hybrid", sw.EVICT_HYBRID)):
+            st = unet.UNetStep(N, vol, ch, ws, xd, labels, swap=True, budget_bytes=int(budget), lookahead=1, eviction=ev)
+            st.calibrate(link_gbs=55.0)
+            row = {"budget_gib": budget / 2 ** 30, "eviction": name, "plan_feasible": st.plan_status == 0}
+            if st.plan_status == 0 or name == "swap":
+                st.run(update=False)
+                torch.cuda.synchronize()
+                same = bool(torch.equal(st.dw32, ref))
+                ms = timed(st)
+                s = st.engine.stats()
+                row.update({"ms_per_step": ms, "slowdown_vs_unswapped": ms / ms0, "n_swapped": s["n_planned"], "n_recomputed": s["n_recompute"],
+                            "recompute_ms_planned": s["recompute_ms"], "bytes_out": s["bytes_out"],
+                            "planned_peak_bytes": s["planned_peak_bytes"], "bit_identical_to_unswapped": same})
+            comp.append(row)
+            st.close()
+            del st
+            torch.cuda.empty_cache()
+    out["swap_vs_recompute"] = comp
     # The paper's four tuning configurations (Section 3.3, Table 1) on this step: 1 swap every saved tensor, swap-in one
     # op ahead; 2 only the first 60 % of the tensors in production order (n_tensors 500 of 843 in the paper); 3 every
     # tensor outside the decoder and head (excl_scopes = synthesis path); 4 as 3 with swap-ins 20 ops ahead.
-    from paper_1812_07816_amd import swap as sw
     n_saved = None
     table = []
     for name, kw in (("1 all, lb 1", dict(policy=sw.POLICY_ALL, lookahead=1)),

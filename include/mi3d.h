@@ -193,6 +193,16 @@ int mi3d_sgd_update(float *w, const float *dw, void *w_bf16, size_t n, float lr,
  *                             (the `lb` knob: larger = earlier)
  */
 enum { MI3D_SWAP_BUDGET = 0, MI3D_SWAP_ALL = 1, MI3D_SWAP_FIRST_N = 2 };
+/* What happens to a tensor the policy removes from the device between its
+ * last forward and first backward use (Section 5 compares the two and proposes
+ * their mix for slow host links):
+ *   MI3D_EVICT_SWAP       copied to the pinned pool and back (the paper's method; default)
+ *   MI3D_EVICT_RECOMPUTE  dropped and produced again by the caller at its first backward
+ *                         use, from the tensors named in mi3d_swap_set_recompute;
+ *                         tensors without that option stay on the device
+ *   MI3D_EVICT_HYBRID     re-computed where the stated cost is below the time the
+ *                         swap-in alone would take on the link, swapped otherwise */
+enum { MI3D_EVICT_SWAP = 0, MI3D_EVICT_RECOMPUTE = 1, MI3D_EVICT_HYBRID = 2 };
 enum { MI3D_TAG_ENCODER = 1u, MI3D_TAG_DECODER = 2u, MI3D_TAG_INPUT = 4u, MI3D_TAG_HEAD = 8u };
 
 typedef struct {
@@ -216,6 +226,8 @@ typedef struct {
     uint64_t unswapped_peak_bytes;       /* same model with nothing swapped */
     int      n_registered, n_planned;    /* tensors known / chosen for swapping */
     int      n_swapped_out, n_swapped_in;/* copies actually issued */
+    int      n_recompute;                /* tensors the plan re-computes */
+    double   recompute_ms;               /* sum of their stated costs */
 } mi3d_swap_stats_t;
 
 typedef struct mi3d_swap_engine mi3d_swap_engine;
@@ -243,6 +255,24 @@ int mi3d_swap_set_transient(mi3d_swap_engine *e, int op, size_t bytes);
  * the latest op that starts early enough; `lookahead` stays the minimum
  * distance in ops.  n = 0 returns to the op-count rule.  Invalidates the plan. */
 int mi3d_swap_set_op_times(mi3d_swap_engine *e, const float *ms, int n, float link_gbs);
+/* Optional: how evicted tensors are handled (MI3D_EVICT_*; default swap) and,
+ * per tensor, that the caller can produce it again: cost_ms is the compute
+ * time of doing so, dep0 / dep1 the ids of registered tensors that must be on
+ * the device for it (-1 = none).  The plan then treats a re-computed tensor as
+ * absent between its last forward use and its first backward use, where the
+ * caller re-runs the producer, and makes its dependencies present at that op
+ * (their swap-ins are scheduled for it; a dependency that is re-computed itself
+ * comes first).  The engine issues no work for such tensors: the caller frees
+ * the block after the last forward use and allocates a new one before it
+ * re-runs the producer.  Both calls invalidate the plan. */
+int mi3d_swap_set_eviction(mi3d_swap_engine *e, int eviction);
+int mi3d_swap_set_recompute(mi3d_swap_engine *e, int id, float cost_ms, int dep0, int dep1);
+/* 1 if the plan re-computes the tensor, 0 if not, <0 on error. */
+int mi3d_swap_is_recomputed(mi3d_swap_engine *e, int id);
+/* First backward op at which the tensor must be on the device under the
+ * current plan: the registered one, or earlier if a re-computation reads it. */
+int mi3d_swap_first_use_op(mi3d_swap_engine *e, int id);
+
 /* Host-only: chooses the swap set.  MI3D_ERR_OVER_BUDGET if even the chosen
  * policy's full set leaves the modelled peak above budget_bytes (the plan is
  * still filled in, so callers may inspect it), MI3D_ERR_HOST_POOL if the set

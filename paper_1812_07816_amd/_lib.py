@@ -26,7 +26,8 @@ class SwapStats(ctypes.Structure):
                 ("peak_arena_bytes", ctypes.c_uint64), ("planned_peak_bytes", ctypes.c_uint64),
                 ("unswapped_peak_bytes", ctypes.c_uint64),
                 ("n_registered", ctypes.c_int), ("n_planned", ctypes.c_int),
-                ("n_swapped_out", ctypes.c_int), ("n_swapped_in", ctypes.c_int)]
+                ("n_swapped_out", ctypes.c_int), ("n_swapped_in", ctypes.c_int),
+                ("n_recompute", ctypes.c_int), ("recompute_ms", ctypes.c_double)]
 
 
 _vp, _sz, _i, _u = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int, ctypes.c_uint
@@ -59,6 +60,10 @@ SIGNATURES = {
     "mi3d_swap_destroy": (_i, [_vp]),
     "mi3d_swap_set_timeline": (_i, [_vp, _i, _i]),
     "mi3d_swap_register": (_i, [_vp, _i, _sz, _i, _i, _i, _i, _u]),
+    "mi3d_swap_set_eviction": (_i, [_vp, _i]),
+    "mi3d_swap_set_recompute": (_i, [_vp, _i, ctypes.c_float, _i, _i]),
+    "mi3d_swap_is_recomputed": (_i, [_vp, _i]),
+    "mi3d_swap_first_use_op": (_i, [_vp, _i]),
     "mi3d_swap_set_op_times": (_i, [_vp, ctypes.POINTER(ctypes.c_float), _i, ctypes.c_float]),
     "mi3d_swap_set_transient": (_i, [_vp, _i, _sz]),
     "mi3d_swap_plan": (_i, [_vp]),

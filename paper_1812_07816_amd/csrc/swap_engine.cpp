@@ -51,6 +51,7 @@ struct mi3d_swap_engine {
     std::vector<size_t> transient;
     std::vector<float> op_ms;   // measured op durations (optional): swap-ins are then scheduled by time
     float link_gbs = 0.f;
+    int eviction = MI3D_EVICT_SWAP;
     int n_fwd_ops = 0, n_ops = 0;
     bool have_plan = false;
     PlanResult plan_res;
@@ -278,6 +279,7 @@ int mi3d_swap_plan(mi3d_swap_engine* e) {
     p.n_tensors = e->cfg.n_tensors;
     p.exclude_tags = e->cfg.exclude_tags;
     p.include_tags = e->cfg.include_tags;
+    p.eviction = e->eviction;
     p.n_fwd_ops = e->n_fwd_ops;
     p.n_ops = std::max<int>(e->n_ops, (int)e->transient.size());
     int st = plan_swaps(ts, e->transient, p, &e->plan_res);
@@ -285,6 +287,40 @@ int mi3d_swap_plan(mi3d_swap_engine* e) {
     for (const PlanTensor& t : ts) e->tensors[t.id].plan = t;
     e->have_plan = true;
     return st;
+}
+
+int mi3d_swap_set_eviction(mi3d_swap_engine* e, int eviction) {
+    if (!e || (eviction != MI3D_EVICT_SWAP && eviction != MI3D_EVICT_RECOMPUTE && eviction != MI3D_EVICT_HYBRID)) return MI3D_ERR_INVALID_ARG;
+    e->eviction = eviction;
+    e->have_plan = false;
+    return MI3D_OK;
+}
+
+int mi3d_swap_set_recompute(mi3d_swap_engine* e, int id, float cost_ms, int dep0, int dep1) {
+    if (!e || !(cost_ms >= 0.f) || dep0 == id || dep1 == id) return MI3D_ERR_INVALID_ARG;
+    Tensor* t = find(e, id);
+    if (!t) return MI3D_ERR_BAD_STATE;
+    for (int d : {dep0, dep1})
+        if (d >= 0 && !find(e, d)) return MI3D_ERR_BAD_STATE;
+    t->plan.recompute_ms = cost_ms;
+    t->plan.dep[0] = dep0 >= 0 ? dep0 : -1;
+    t->plan.dep[1] = dep1 >= 0 ? dep1 : -1;
+    e->have_plan = false;
+    return MI3D_OK;
+}
+
+int mi3d_swap_is_recomputed(mi3d_swap_engine* e, int id) {
+    if (!e) return MI3D_ERR_INVALID_ARG;
+    Tensor* t = find(e, id);
+    if (!t || !e->have_plan) return MI3D_ERR_BAD_STATE;
+    return t->plan.recompute ? 1 : 0;
+}
+
+int mi3d_swap_first_use_op(mi3d_swap_engine* e, int id) {
+    if (!e) return MI3D_ERR_INVALID_ARG;
+    Tensor* t = find(e, id);
+    if (!t || !e->have_plan) return MI3D_ERR_BAD_STATE;
+    return t->plan.bwd_first_use_op;
 }
 
 int mi3d_swap_is_planned(mi3d_swap_engine* e, int id) {
@@ -464,6 +500,8 @@ int mi3d_swap_stats(mi3d_swap_engine* e, mi3d_swap_stats_t* out) {
     out->n_planned = e->have_plan ? e->plan_res.n_planned : 0;
     out->n_swapped_out = e->n_out;
     out->n_swapped_in = e->n_in;
+    out->n_recompute = e->have_plan ? e->plan_res.n_recompute : 0;
+    out->recompute_ms = e->have_plan ? e->plan_res.recompute_ms : 0.0;
     if (!e->live) return MI3D_OK;
     int st = mi3d_swap_sync(e);
     if (st) return st;

@@ -8,7 +8,9 @@ namespace mi3d {
 
 static bool resident(const PlanTensor& t, int op, bool ignore_plan) {
     if (op < t.produce_op || op > t.bwd_last_use_op) return false;
-    if (ignore_plan || !t.planned) return true;
+    if (ignore_plan) return true;
+    if (t.recompute) return op <= t.last_fwd_use_op || op >= t.bwd_first_use_op;
+    if (!t.planned) return true;
     return op <= t.last_fwd_use_op || op >= t.prefetch_op;
 }
 
@@ -45,8 +47,11 @@ static int prefetch_by_ops(const PlanTensor& t, const PlanParams& p) {
 // latest op that starts no later than that.  Never later than the op-count rule.
 static void prefetch_by_time(std::vector<PlanTensor>& ts, const PlanParams& p, int n_ops) {
     const std::vector<float>& ms = *p.op_ms;
+    std::vector<double> extra(n_ops + 1, 0.0);   // re-computations run at the first backward use of their tensor
+    for (const PlanTensor& t : ts)
+        if (t.recompute && t.bwd_first_use_op >= 0 && t.bwd_first_use_op < n_ops) extra[t.bwd_first_use_op] += t.recompute_ms;
     std::vector<double> start(n_ops + 1, 0.0);
-    for (int op = 0; op < n_ops; ++op) start[op + 1] = start[op] + (op < (int)ms.size() ? (double)ms[op] : 0.0);
+    for (int op = 0; op < n_ops; ++op) start[op + 1] = start[op] + (op < (int)ms.size() ? (double)ms[op] : 0.0) + extra[op];
     std::vector<int> order;
     for (int i = 0; i < (int)ts.size(); ++i)
         if (ts[i].planned) order.push_back(i);
@@ -66,24 +71,78 @@ static void prefetch_by_time(std::vector<PlanTensor>& ts, const PlanParams& p, i
     }
 }
 
+// A re-computation reads its dependencies at its tensor's first backward use: they must be on the device by
+// then, so their own first backward use is lowered to that op (transitively: a dependency that is re-computed
+// itself is produced first, from its own dependencies).  Resets the prefetch ops to the op-count rule.
+static void apply_deps(std::vector<PlanTensor>& ts, const PlanParams& p) {
+    for (PlanTensor& t : ts) t.bwd_first_use_op = t.bwd_first_use_reg;
+    bool changed = true;
+    for (size_t guard = 0; changed && guard < ts.size() + 2; ++guard) {
+        changed = false;
+        for (const PlanTensor& t : ts) {
+            if (!t.recompute) continue;
+            for (int d : t.dep) {
+                if (d < 0) continue;
+                for (PlanTensor& u : ts)
+                    if (u.id == d && u.bwd_first_use_op > t.bwd_first_use_op) {
+                        u.bwd_first_use_op = t.bwd_first_use_op;
+                        changed = true;
+                    }
+            }
+        }
+    }
+    for (PlanTensor& t : ts) t.prefetch_op = prefetch_by_ops(t, p);
+}
+
 int plan_swaps(std::vector<PlanTensor>& ts, const std::vector<size_t>& transient, const PlanParams& p, PlanResult* res) {
     int n_ops = p.n_ops;
     for (const PlanTensor& t : ts) n_ops = std::max(n_ops, t.bwd_last_use_op + 1);
     if (p.n_fwd_ops < 0 || p.n_fwd_ops > n_ops || p.lookahead < 0) return MI3D_ERR_INVALID_ARG;
+    if (p.eviction != MI3D_EVICT_SWAP && p.eviction != MI3D_EVICT_RECOMPUTE && p.eviction != MI3D_EVICT_HYBRID) return MI3D_ERR_INVALID_ARG;
     const bool timed = p.op_ms && !p.op_ms->empty() && p.link_gbs > 0.f;
     for (PlanTensor& t : ts) {
+        if (t.bwd_first_use_reg < 0) t.bwd_first_use_reg = t.bwd_first_use_op;
+        t.bwd_first_use_op = t.bwd_first_use_reg;
         if (t.produce_op > t.last_fwd_use_op || t.last_fwd_use_op >= t.bwd_first_use_op ||
             t.bwd_first_use_op > t.bwd_last_use_op || t.produce_op < 0)
             return MI3D_ERR_INVALID_ARG;
         t.planned = false;
+        t.recompute = false;
         t.prefetch_op = prefetch_by_ops(t, p);
         t.host_offset = 0;
     }
+    // a re-computation is possible if every dependency is a known tensor that is still alive at that op
+    std::vector<char> recomputable(ts.size(), 0);
+    for (size_t i = 0; i < ts.size(); ++i) {
+        const PlanTensor& t = ts[i];
+        bool ok = t.recompute_ms >= 0.f;
+        for (int d : t.dep) {
+            if (d < 0 || !ok) continue;
+            bool found = false;
+            for (const PlanTensor& u : ts)
+                if (u.id == d && u.id != t.id && u.produce_op < t.produce_op + 1 && u.bwd_last_use_op >= t.bwd_first_use_op) found = true;
+            ok = found;
+        }
+        recomputable[i] = ok;
+    }
+    const bool can_swap = p.eviction != MI3D_EVICT_RECOMPUTE;
+    // hybrid: re-compute where that costs less compute time than the swap-in alone would take on the link
+    auto wants_recompute = [&](int i) {
+        if (p.eviction == MI3D_EVICT_SWAP || !recomputable[i]) return false;
+        if (!can_swap) return true;
+        const double link = p.link_gbs > 0.f ? (double)p.link_gbs : 50.0;
+        return (double)ts[i].recompute_ms < (double)ts[i].bytes / (link * 1e6);
+    };
+    auto dep_recomputed = [&](int i) {
+        for (int d : ts[i].dep)
+            for (const PlanTensor& u : ts)
+                if (d >= 0 && u.id == d && u.recompute) return true;
+        return false;
+    };
     // the residency model with the current choice; with op times the chosen tensors come back earlier
     auto reschedule = [&]() {
-        if (!timed) return;
-        for (PlanTensor& t : ts) t.prefetch_op = prefetch_by_ops(t, p);
-        prefetch_by_time(ts, p, n_ops);
+        apply_deps(ts, p);
+        if (timed) prefetch_by_time(ts, p, n_ops);
     };
     res->unswapped_peak = peak(ts, transient, n_ops, true, nullptr);
 
@@ -98,12 +157,16 @@ int plan_swaps(std::vector<PlanTensor>& ts, const std::vector<size_t>& transient
         if (eligible(ts[i])) order.push_back(i);
     std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return ts[a].produce_op < ts[b].produce_op; });
 
-    if (p.policy == MI3D_SWAP_ALL) {
-        for (int i : order) ts[i].planned = true;
-        reschedule();
-    } else if (p.policy == MI3D_SWAP_FIRST_N) {
-        int n = p.n_tensors < 0 ? (int)order.size() : std::min<int>(p.n_tensors, (int)order.size());
-        for (int k = 0; k < n; ++k) ts[order[k]].planned = true;
+    if (p.policy == MI3D_SWAP_ALL || p.policy == MI3D_SWAP_FIRST_N) {
+        int n = (int)order.size();
+        if (p.policy == MI3D_SWAP_FIRST_N && p.n_tensors >= 0) n = std::min<int>(p.n_tensors, n);
+        for (int k = 0; k < n; ++k) {
+            const int i = order[k];
+            // re-computing a tensor from one that is re-computed itself would bring the whole chain back at
+            // once: such a tensor is swapped instead (or kept, where swapping is not allowed)
+            if (wants_recompute(i) && !dep_recomputed(i)) ts[i].recompute = true;
+            else if (can_swap) ts[i].planned = true;
+        }
         reschedule();
     } else if (p.policy == MI3D_SWAP_BUDGET) {
         std::vector<int> chosen;
@@ -114,24 +177,40 @@ int plan_swaps(std::vector<PlanTensor>& ts, const std::vector<size_t>& transient
             // candidates: tensors idle at the peak op.  Prefer the longest idle
             // interval (early feature maps live longest), then the earlier
             // producer, then the larger tensor.
-            int best = -1;
+            int best = -1, best_gap = 0;
             for (int i : order) {
                 const PlanTensor& t = ts[i];
-                if (t.planned || at <= t.last_fwd_use_op || at >= t.prefetch_op) continue;
-                if (best < 0) { best = i; continue; }
-                const PlanTensor& b = ts[best];
-                int gt = t.prefetch_op - t.last_fwd_use_op, gb = b.prefetch_op - b.last_fwd_use_op;
-                if (gt != gb ? gt > gb : (t.produce_op != b.produce_op ? t.produce_op < b.produce_op : t.bytes > b.bytes)) best = i;
+                if (t.planned || t.recompute) continue;
+                const bool rc = wants_recompute(i);
+                if (!rc && !can_swap) continue;
+                const int back = rc ? t.bwd_first_use_op : t.prefetch_op;
+                if (at <= t.last_fwd_use_op || at >= back) continue;
+                const int gap = back - t.last_fwd_use_op;
+                if (best >= 0) {
+                    const PlanTensor& b = ts[best];
+                    if (!(gap != best_gap ? gap > best_gap : (t.produce_op != b.produce_op ? t.produce_op < b.produce_op : t.bytes > b.bytes))) continue;
+                }
+                best = i;
+                best_gap = gap;
             }
             if (best < 0) break;  // nothing more can lower this peak
-            ts[best].planned = true;
+            if (wants_recompute(best)) ts[best].recompute = true;
+            else ts[best].planned = true;
+            apply_deps(ts, p);
             chosen.push_back(best);
         }
-        // drop tensors that later choices made unnecessary (less traffic)
+        // drop tensors that later choices made unnecessary (less traffic, less re-computation)
         if (peak(ts, transient, n_ops, false, nullptr) <= p.budget_bytes) {
             for (int k = (int)chosen.size() - 1; k >= 0; --k) {
-                ts[chosen[k]].planned = false;
-                if (peak(ts, transient, n_ops, false, nullptr) > p.budget_bytes) ts[chosen[k]].planned = true;
+                PlanTensor& t = ts[chosen[k]];
+                const bool was_planned = t.planned, was_recompute = t.recompute;
+                t.planned = t.recompute = false;
+                apply_deps(ts, p);
+                if (peak(ts, transient, n_ops, false, nullptr) > p.budget_bytes) {
+                    t.planned = was_planned;
+                    t.recompute = was_recompute;
+                    apply_deps(ts, p);
+                }
             }
         }
     } else {
@@ -167,6 +246,13 @@ int plan_swaps(std::vector<PlanTensor>& ts, const std::vector<size_t>& transient
     }
     res->n_planned = n;
     res->host_bytes = off;
+    res->n_recompute = 0;
+    res->recompute_ms = 0.0;
+    for (const PlanTensor& t : ts)
+        if (t.recompute) {
+            ++res->n_recompute;
+            res->recompute_ms += t.recompute_ms;
+        }
     res->planned_peak = peak(ts, transient, n_ops, false, nullptr);
     if (p.host_pool_bytes && off > p.host_pool_bytes) return MI3D_ERR_HOST_POOL;
     if (res->planned_peak > p.budget_bytes) return MI3D_ERR_OVER_BUDGET;

@@ -6,6 +6,7 @@ import torch
 from ._lib import SwapConfig, SwapStats, check, lib
 
 POLICY_BUDGET, POLICY_ALL, POLICY_FIRST_N = 0, 1, 2
+EVICT_SWAP, EVICT_RECOMPUTE, EVICT_HYBRID = 0, 1, 2
 TAG_ENCODER, TAG_DECODER, TAG_INPUT, TAG_HEAD = 1, 2, 4, 8
 
 
@@ -50,6 +51,24 @@ class SwapEngine:
     def set_op_times(self, ms, link_gbs):
         arr = (ctypes.c_float * len(ms))(*[float(v) for v in ms])
         check(lib().mi3d_swap_set_op_times(self._h, arr, len(ms), float(link_gbs)), "swap_set_op_times")
+
+    def set_eviction(self, eviction):
+        check(lib().mi3d_swap_set_eviction(self._h, int(eviction)), "swap_set_eviction")
+
+    def set_recompute(self, id, cost_ms, dep0=-1, dep1=-1):
+        check(lib().mi3d_swap_set_recompute(self._h, id, float(cost_ms), dep0, dep1), "swap_set_recompute")
+
+    def is_recomputed(self, id):
+        r = lib().mi3d_swap_is_recomputed(self._h, id)
+        if r < 0:
+            check(r, "swap_is_recomputed")
+        return bool(r)
+
+    def first_use_op(self, id):
+        r = lib().mi3d_swap_first_use_op(self._h, id)
+        if r < 0:
+            check(r, "swap_first_use_op")
+        return r
 
     def set_transient(self, op, bytes):
         check(lib().mi3d_swap_set_transient(self._h, op, bytes), "swap_set_transient")

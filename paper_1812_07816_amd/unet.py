@@ -44,7 +44,8 @@ class _Saved:
 
 class UNetStep:
     def __init__(self, N, vol, channels, weights, x, labels, lr=1e-2, in_ch=4, classes=3, swap=True,
-                 budget_bytes=None, lookahead=2, policy=sw.POLICY_BUDGET, n_tensors=-1, exclude_tags=0):
+                 budget_bytes=None, lookahead=2, policy=sw.POLICY_BUDGET, n_tensors=-1, exclude_tags=0,
+                 eviction=sw.EVICT_SWAP):
         """weights: list of float32 CPU tensors/arrays (bf16-exact start values) in the order enc convs,
         (dec up, conv1, conv2) from the deepest decoder level up, head; x: bf16 CUDA [N,vol,vol,vol,in_ch];
         labels: uint8 CUDA [N,vol,vol,vol,classes]."""
@@ -124,13 +125,16 @@ class UNetStep:
             if op["kind"] == "conv":
                 prev = self.ops[f - 1]
                 op["through_act"] = prev["kind"] == "conv" and prev["out"] is op["src"] and op["src"].id not in skip_ids
-        # backward readers: conv f reads its input (weight gradient) and its output (LeakyReLU derivative); up and head
-        # read their input (weight gradient); the loss reads the logits
+        # backward readers: conv f reads its input (weight gradient; LeakyReLU derivative of the layer below where the
+        # data gradient applies it) and, unless the layer above has applied it already, its output (LeakyReLU
+        # derivative); up and head read their input (weight gradient); the loss reads the logits
         for f, op in enumerate(self.ops):
             b = self.bwd_op(f)
             if op["kind"] == "conv":
                 op["src"].bwd_ops.append(b)
-                op["out"].bwd_ops.append(b)
+                nxt = self.ops[f + 1]
+                if not (nxt["kind"] == "conv" and nxt["through_act"]):
+                    op["out"].bwd_ops.append(b)
             elif op["kind"] in ("up", "head"):
                 op["src"].bwd_ops.append(b)
             elif op["kind"] == "loss":
@@ -155,17 +159,33 @@ class UNetStep:
             self.engine = e = sw.SwapEngine(budget_bytes=budget, host_pool_bytes=pool, arena=self.arena, lookahead=lookahead,
                                             policy=policy, n_tensors=n_tensors, exclude_tags=exclude_tags)
             e.set_timeline(self.n_fwd, self.n_ops)
+            e.set_eviction(eviction)
             for s in self.saved:
                 e.register(s.id, s.bytes, s.produce, s.last_fwd, min(s.bwd_ops), max(s.bwd_ops), s.tag)
+            # outputs of convolutions can be produced again from their input; cost until measured: the forward
+            # pass at 800 TFLOP/s or 4 TB/s, whichever is slower
+            for op in self.ops:
+                if op["kind"] in ("conv", "head"):
+                    d = op["desc"]
+                    fl = 2.0 * _numel(op["out"].shape) * d.kD * d.kH * d.kW * d.Cin
+                    ms = max(fl / 8e14, (op["src"].bytes + op["out"].bytes) / 4e12) * 1e3
+                    e.set_recompute(op["out"].id, ms, op["src"].id)
             for op in range(self.n_ops):
                 e.set_transient(op, self._transient(op))
-            self.plan_status = e.plan(allow_over_budget=True)
-            self.planned = [e.is_planned(s.id) for s in self.saved]
-            self.prefetch = [e.prefetch_op(s.id) for s in self.saved]
+            self._read_plan(e.plan(allow_over_budget=True))
         else:
             self.planned = [False] * len(self.saved)
+            self.recomputed = [False] * len(self.saved)
             self.prefetch = [-1] * len(self.saved)
             self.plan_status = 0
+        self.producer = {op["out"].id: op for op in self.ops if op["kind"] in ("conv", "head")}
+
+    def _read_plan(self, status):
+        e = self.engine
+        self.plan_status = status
+        self.planned = [e.is_planned(s.id) for s in self.saved]
+        self.recomputed = [e.is_recomputed(s.id) for s in self.saved]
+        self.prefetch = [e.prefetch_op(s.id) for s in self.saved]
 
     def bwd_op(self, f):
         return self.n_fwd + (self.n_fwd - 1 - f)
@@ -210,6 +230,9 @@ class UNetStep:
         if self.engine is None:
             return
         for s in self.saved:
+            if self.recomputed[s.id] and s.last_fwd == f:      # dropped; produced again at its first backward use
+                self.engine.free(s.ptr)
+                s.ptr, s.view = None, None
             if not self.planned[s.id]:
                 continue
             if s.produce == f:
@@ -231,7 +254,20 @@ class UNetStep:
         if self.engine is not None and self.planned[s.id] and not getattr(s, "_waited", False):
             self.engine.wait_in(s.id)
             s._waited = True
+        if s.view is None and self.recomputed[s.id]:
+            op = self.producer[s.id]
+            self._need(op["src"])
+            self._forward_conv(op)
+            self.n_recomputed += 1
         return s.view
+
+    def _forward_conv(self, op):
+        out = self._produce(op["out"])
+        if op["kind"] == "conv":
+            mc.conv3d_fwd_lrelu(op["desc"], op["src"].view, self.w[op["w"]], SLOPE, out, self.ws)
+        else:
+            mc.conv3d_fwd(op["desc"], op["src"].view, self.w[op["w"]], out, self.ws)
+        return out
 
     def _after_bwd_op(self, op):
         for s in self.saved:
@@ -255,6 +291,7 @@ class UNetStep:
                 timeline.append((name, phase, ev))
 
         mark("start", "fwd")
+        self.n_recomputed = 0
         if e is not None:
             e.reset_step()
         bf = torch.bfloat16
@@ -266,8 +303,7 @@ class UNetStep:
                 if trace is not None:
                     trace["input.a"] = op["out"].view.clone()
             elif k == "conv":
-                out = self._produce(op["out"])
-                mc.conv3d_fwd_lrelu(op["desc"], op["src"].view, self.w[op["w"]], SLOPE, out, self.ws)
+                out = self._forward_conv(op)
                 if trace is not None:
                     trace[op["name"] + ".a"] = out.clone()
             elif k == "up":
@@ -282,7 +318,7 @@ class UNetStep:
                 if trace is not None:
                     trace[op["name"] + ".a"] = op["out"].view.clone()
             elif k == "head":
-                mc.conv3d_fwd(op["desc"], op["src"].view, self.w[op["w"]], self._produce(op["out"]), self.ws)
+                self._forward_conv(op)
                 if trace is not None:
                     trace["head.a"] = op["out"].view.clone()
             elif k == "loss":
@@ -369,10 +405,17 @@ class UNetStep:
         ms = [max(t[i + 1] - t[i], 0.0) for i in range(len(t) - 1)]     # forward ops, then backward ops in timeline order
         assert len(ms) == self.n_ops
         e = self.engine
+        # a re-computation costs what the forward op took; the backward ops that ran one under the current plan are
+        # charged without it (the planner adds the cost of the re-computations it chooses itself)
+        for s in self.saved:
+            if self.recomputed[s.id]:
+                b = e.first_use_op(s.id)
+                ms[b] = max(ms[b] - ms[s.produce], 0.0)
         e.set_op_times(ms, link_gbs)
-        self.plan_status = e.plan(allow_over_budget=True)
-        self.planned = [e.is_planned(s.id) for s in self.saved]
-        self.prefetch = [e.prefetch_op(s.id) for s in self.saved]
+        for f, op in enumerate(self.ops):
+            if op["kind"] in ("conv", "head"):
+                e.set_recompute(op["out"].id, ms[f], op["src"].id)
+        self._read_plan(e.plan(allow_over_budget=True))
         self.op_ms = ms
 
     def close(self):

@@ -246,3 +246,162 @@ def test_op_times_count_in_the_budget_model():
     with pytest.raises(Mi3dError):
         e.set_op_times([1.0, -1.0], 1.0)
     e.close()
+
+
+# ---- re-computation and the hybrid (Section 5) ------------------------------------------------------------------
+def real_chain(sizes):
+    """Chain of layers: op i produces tensor i from tensor i-1; backward op of layer i (n_ops-1-i) reads tensor i and
+    tensor i-1, so tensor i is first needed again at the backward op of layer i+1."""
+    n = len(sizes)
+    n_ops = 2 * n
+    ts = []
+    for i in range(n):
+        bwd_own, bwd_next = n_ops - 1 - i, n_ops - 1 - (i + 1)
+        first = bwd_next if i + 1 < n else bwd_own
+        ts.append((i, sizes[i], i, min(i + 1, n - 1), first, bwd_own, sw.TAG_ENCODER))
+    return n, n_ops, ts
+
+
+def closure_first_use(ts, recomputed, deps):
+    first = {t[0]: t[4] for t in ts}
+    for _ in range(len(ts) + 2):
+        for i in recomputed:
+            for d in deps.get(i, ()):
+                first[d] = min(first[d], first[i])
+    return first
+
+
+def brute_bytes_hybrid(ts, planned, recomputed, prefetch, first, op):
+    b = 0
+    for (i, size, prod, lf, _bf, bl, _tag) in ts:
+        if op < prod or op > bl:
+            continue
+        if i in recomputed and lf < op < first[i]:
+            continue
+        if i in planned and lf < op < prefetch[i]:
+            continue
+        b += size
+    return b
+
+
+def plan_state(e, ts):
+    ids = [t[0] for t in ts]
+    return ({i for i in ids if e.is_planned(i)}, {i for i in ids if e.is_recomputed(i)},
+            {i: e.prefetch_op(i) for i in ids}, {i: e.first_use_op(i) for i in ids})
+
+
+@pytest.mark.parametrize("eviction", [sw.EVICT_RECOMPUTE, sw.EVICT_HYBRID])
+def test_recompute_accounting_matches_brute_force_on_random_chains(eviction):
+    rng = np.random.default_rng(7)
+    seen_recompute = seen_swap = 0
+    for trial in range(60):
+        n = int(rng.integers(3, 9))
+        sizes = [int(v) for v in rng.integers(50, 900, size=n)]
+        n_fwd, n_ops, ts = real_chain(sizes)
+        total = sum(sizes)
+        budget = int(total * rng.uniform(0.45, 0.95))
+        e = make(ts, n_fwd, n_ops, budget_bytes=budget, lookahead=int(rng.integers(1, 3)))
+        e.set_eviction(eviction)
+        deps = {}
+        for i in range(1, n):
+            if rng.uniform() < 0.8:
+                # cost 0 ms is cheaper than any copy, 1e3 ms dearer than any: the hybrid re-computes the former only
+                e.set_recompute(i, 0.0 if rng.uniform() < 0.6 else 1e3, i - 1)
+                deps[i] = (i - 1,)
+        st = e.plan(allow_over_budget=True)
+        planned, recomputed, prefetch, first = plan_state(e, ts)
+        assert first == closure_first_use(ts, recomputed, deps)
+        assert not (planned & recomputed)
+        if eviction == sw.EVICT_RECOMPUTE:
+            assert not planned and recomputed <= set(deps)
+        sweep = [brute_bytes_hybrid(ts, planned, recomputed, prefetch, first, op) for op in range(n_ops)]
+        assert sweep == [e.planned_bytes_at(op) for op in range(n_ops)]
+        s = e.stats()
+        assert s["planned_peak_bytes"] == max(sweep) and s["n_recompute"] == len(recomputed) and s["n_planned"] == len(planned)
+        assert (st == 0) == (max(sweep) <= budget)
+        for i in planned:
+            assert first[i] - 2 <= prefetch[i] <= first[i]
+        seen_recompute += len(recomputed)
+        seen_swap += len(planned)
+        e.close()
+    assert seen_recompute > 10 and (eviction == sw.EVICT_RECOMPUTE or seen_swap > 5)
+
+
+def test_hybrid_recomputes_cheap_tensors_and_swaps_dear_ones():
+    n_fwd, n_ops, ts = real_chain([100, 600, 500, 400, 300, 200])
+    for cost, expect_recompute in ((0.0, True), (1e3, False)):
+        e = make(ts, n_fwd, n_ops, budget_bytes=1600, lookahead=1)
+        e.set_eviction(sw.EVICT_HYBRID)
+        for i in range(1, 6):
+            e.set_recompute(i, cost, i - 1)
+        e.plan()
+        planned, recomputed, _, _ = plan_state(e, ts)
+        assert (recomputed, planned) == (({1}, set()) if expect_recompute else (set(), {1}))
+        assert e.stats()["planned_peak_bytes"] <= 1600
+        e.close()
+    # with a measured link rate the comparison is cost against bytes / rate: 600 bytes at 1e-3 GB/s take 0.6 ms
+    for cost, expect in ((0.5, True), (0.7, False)):
+        e = make(ts, n_fwd, n_ops, budget_bytes=1600, lookahead=1)
+        e.set_eviction(sw.EVICT_HYBRID)
+        e.set_op_times([1.0] * n_ops, 1e-3)
+        e.set_recompute(1, cost, 0)
+        e.plan()
+        assert e.is_recomputed(1) == expect and e.is_planned(1) == (not expect)
+        e.close()
+
+
+def test_recompute_only_never_evicts_tensors_without_the_option():
+    n_fwd, n_ops, ts = real_chain([600, 500, 400, 300, 200, 100])
+    e = make(ts, n_fwd, n_ops, budget_bytes=100, lookahead=1, policy=sw.POLICY_ALL)
+    e.set_eviction(sw.EVICT_RECOMPUTE)
+    e.set_recompute(2, 0.1, 1)
+    e.set_recompute(4, 0.1, 3)
+    assert e.plan(allow_over_budget=True) != 0        # cannot be met
+    planned, recomputed, _, first = plan_state(e, ts)
+    assert not planned and recomputed == {2, 4}
+    s = e.stats()
+    assert s["n_recompute"] == 2 and abs(s["recompute_ms"] - 0.2) < 1e-6
+    # the inputs of the re-computations are needed one op earlier than their own backward use
+    assert first[1] == first[2] and first[3] == first[4]
+    e.close()
+
+
+def test_policy_all_with_recomputation_keeps_every_other_tensor_of_a_chain():
+    n_fwd, n_ops, ts = real_chain([100] * 7)
+    e = make(ts, n_fwd, n_ops, budget_bytes=10 ** 9, lookahead=1, policy=sw.POLICY_ALL)
+    e.set_eviction(sw.EVICT_RECOMPUTE)
+    for i in range(1, 7):
+        e.set_recompute(i, 0.1, i - 1)
+    e.plan()
+    _, recomputed, _, _ = plan_state(e, ts)
+    # no tensor is re-computed from a re-computed one (that would bring the whole chain back at once)
+    assert recomputed and all(i - 1 not in recomputed for i in recomputed)
+    assert len(recomputed) == 3
+    e.close()
+    # the hybrid swaps the ones in between
+    e = make(ts, n_fwd, n_ops, budget_bytes=10 ** 9, lookahead=1, policy=sw.POLICY_ALL)
+    e.set_eviction(sw.EVICT_HYBRID)
+    for i in range(1, 7):
+        e.set_recompute(i, 0.0, i - 1)
+    e.plan()
+    planned, recomputed, _, _ = plan_state(e, ts)
+    assert len(recomputed) == 3 and planned | recomputed == set(range(7))
+    e.close()
+
+
+def test_recompute_argument_checks():
+    n_fwd, n_ops, ts = real_chain([100, 100, 100])
+    e = make(ts, n_fwd, n_ops, budget_bytes=1000)
+    with pytest.raises(Mi3dError):
+        e.set_eviction(7)
+    with pytest.raises(Mi3dError):
+        e.set_recompute(1, -1.0, 0)
+    with pytest.raises(Mi3dError):
+        e.set_recompute(1, 0.1, 1)          # depends on itself
+    with pytest.raises(Mi3dError):
+        e.set_recompute(1, 0.1, 42)         # unknown dependency
+    with pytest.raises(Mi3dError):
+        e.set_recompute(42, 0.1, 0)         # unknown tensor
+    with pytest.raises(Mi3dError):
+        e.is_recomputed(1)                  # no plan yet
+    e.close()

@@ -182,3 +182,51 @@ def test_swapped_step_is_bit_identical(unet):
         torch.cuda.synchronize()
         assert torch.equal(st.dw32, ref)
         st.close()
+
+
+def test_recomputed_and_hybrid_steps_are_bit_identical(unet):
+    """Section 5: dropped tensors are produced again by their convolution at their first backward use; the kernels
+    are deterministic, so the gradients are those of the plain step bit for bit."""
+    from paper_1812_07816_amd import swap as sw
+    N, vol = 2, 32
+    _, _, ws, xd, ld = _inputs(N, vol, CH, 5)
+    plain = unet.UNetStep(N, vol, CH, ws, xd, ld, swap=False)
+    plain.run(update=False)
+    torch.cuda.synchronize()
+    ref, ref_loss = plain.dw32.clone(), plain.loss.clone()
+    probe = unet.UNetStep(N, vol, CH, ws, xd, ld, swap=True)
+    peak = probe.engine.stats()["unswapped_peak_bytes"]
+    fixed = probe._transient(0)           # weights, workspace, labels: nothing the plan can move
+    probe.close()
+
+    def check(st, budget):
+        for calibrated in (False, True):
+            if calibrated:
+                st.calibrate()
+            st.run(update=False)
+            torch.cuda.synchronize()
+            s = st.engine.stats()
+            assert s["n_recompute"] > 0 and st.n_recomputed == s["n_recompute"], (s, st.n_recomputed)
+            if budget is not None and st.plan_status == 0:
+                assert s["planned_peak_bytes"] <= budget and s["peak_arena_bytes"] <= s["planned_peak_bytes"] - fixed
+            assert torch.equal(st.dw32, ref) and torch.equal(st.loss, ref_loss)
+        return s
+
+    for eviction in (sw.EVICT_RECOMPUTE, sw.EVICT_HYBRID):
+        # a budget that takes a part of the movable bytes away; the largest cut this eviction mode can meet
+        for cut in (0.5, 0.35, 0.2, 0.1):
+            budget = int(peak - cut * (peak - fixed))
+            st = unet.UNetStep(N, vol, CH, ws, xd, ld, swap=True, budget_bytes=budget, lookahead=2, eviction=eviction)
+            if st.plan_status == 0:
+                break
+            st.close()
+        assert st.plan_status == 0, "no cut of the movable bytes is feasible"
+        s = check(st, budget)
+        print("eviction", eviction, "cut", cut, "recomputed", s["n_recompute"], "swapped", s["n_planned"])
+        if eviction == sw.EVICT_RECOMPUTE:
+            assert s["n_swapped_out"] == 0
+        st.close()
+        st = unet.UNetStep(N, vol, CH, ws, xd, ld, swap=True, budget_bytes=None, lookahead=2, policy=sw.POLICY_ALL, eviction=eviction)
+        s = check(st, None)
+        assert (s["n_swapped_out"] == 0) if eviction == sw.EVICT_RECOMPUTE else (s["n_swapped_out"] > 0 and s["n_swapped_out"] == s["n_swapped_in"])
+        st.close()
