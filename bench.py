@@ -220,6 +220,18 @@ def unet_train_step(steps=3, warmup=1):
         del st
         torch.cuda.empty_cache()
     out["paper_tuning_configurations"] = table
+    # the larger volume of Section 5 (208^3), same network and batch
+    v2 = 208
+    x2 = si.normal(6, 0, (N, v2, v2, v2, 4), bf16=True)
+    l2 = torch.from_numpy(si.ellipsoid_labels(6, 1, N, v2)).cuda()
+    x2d = torch.from_numpy(si.bf16_bits(x2).view(np.int16)).cuda().view(torch.bfloat16).reshape(x2.shape)
+    big = unet.UNetStep(N, v2, ch, ws, x2d, l2, swap=True, budget_bytes=16 << 30, lookahead=1)
+    ms2 = timed(big)
+    s = big.engine.stats()
+    out["volume_208"] = {"workload": "same U-Net at 208^3, N=2", "ms_per_step": ms2, "conv_tflops": big.flops / ms2 / 1e9,
+                         "unswapped_peak_bytes": s["unswapped_peak_bytes"], "planned_peak_bytes": s["planned_peak_bytes"],
+                         "budget_gib": 16.0, "n_swapped": s["n_planned"], "loss": float(big.loss.item())}
+    big.close()
     return out
 
 

@@ -93,6 +93,15 @@ def test_config3_192cube(device, layer):
                            bf16=True, full=False), True, f"cfg3 {cin}->{cout} s{s}")
 
 
+# ---- the second workload shape: a 208^3 volume (Section 5), whose extents are no multiple of the 32-column patches
+@pytest.mark.parametrize("layer", [(208, 4, 32, 3, 1, 1), (208, 32, 32, 3, 1, 1), (208, 32, 64, 3, 2, 1), (104, 64, 64, 3, 1, 1),
+                                   (26, 256, 320, 3, 2, 1), (13, 320, 320, 3, 1, 1), (26, 256, 320, 2, 2, 0), (208, 32, 64, 2, 2, 0)])
+def test_208cube_layers(device, layer):
+    vol, cin, cout, k, s, p = layer
+    _check(parity.run_case(6, 10 * (cin % 7) + vol % 5, 1, vol, vol, vol, cin, cout, k, s, p, bf16=True, full=False,
+                           n_samples=40000, n_wgrad_samples=48), True, f"208 {layer}")
+
+
 # ---- config 4: every layer shape of the 5-level U-Net at 192^3 -------------
 CH = [32, 64, 128, 256, 320]
 VOL = [192, 96, 48, 24, 12]

@@ -52,7 +52,8 @@ def _h(t):
     return t.detach().float().cpu().numpy().astype(np.float64)
 
 
-@pytest.mark.parametrize("N,vol,channels", [(2, 32, CH), (1, 16, CH[:4])])
+# 48 = 16 x 3: odd extents at the two deepest levels, as in the 208^3 volume (16 x 13)
+@pytest.mark.parametrize("N,vol,channels", [(2, 32, CH), (1, 16, CH[:4]), (1, 48, CH)])
 def test_every_op_matches_oracle_on_the_steps_own_tensors(unet, N, vol, channels):
     x, labels, ws, xd, ld = _inputs(N, vol, channels, 5)
     L = len(channels)
