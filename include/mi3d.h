@@ -146,6 +146,16 @@ int mi3d_concat_channels(const void *a, int Ca, const void *b, int Cb, void *out
 int mi3d_split_channels(const void *in, int Ca, int Cb, void *a, void *b, size_t voxels, void *stream);
 /* a[i] <- a[i] + b[i]  (bf16 operands, fp32 add, one rounding). */
 int mi3d_add_inplace(void *a, const void *b, size_t n, void *stream);
+/* out[v][0:C] = in[v][c_off : c_off + C] for a tensor of C_total channels per voxel (bf16; channel counts and the
+ * offset in multiples of 8): one half of a concatenated tensor's gradient without writing the other. */
+int mi3d_slice_channels(const void *in, int C_total, int c_off, int C, void *out, size_t voxels, void *stream);
+/* Gradient that reaches a skip connection's source layer, in one pass:
+ * da[v][c] <- (da[v][c] + dcat[v][c_off + c]) * (a[v][c] > 0 ? 1 : slope).  da (C channels, in place) is the
+ * gradient from the encoder path, dcat (C_total channels) the gradient of the concatenated decoder input whose
+ * channels c_off.. belong to the skip tensor, a the skip tensor itself (LeakyReLU output).  fp32 arithmetic, one
+ * rounding to bf16. */
+int mi3d_skip_grad(void *da, const void *dcat, int C_total, int c_off, const void *a, int C, size_t voxels, float slope,
+                   void *stream);
 
 /* Sigmoid + soft Dice over `voxels` voxels (all samples) of `classes` = 3
  * channels: p = sigmoid(logit), per class I = sum p t, P = sum p, T = sum t,

@@ -44,6 +44,8 @@ SIGNATURES = {
     "mi3d_concat_channels": (_i, [_vp, _i, _vp, _i, _vp, _sz, _vp]),
     "mi3d_split_channels": (_i, [_vp, _i, _i, _vp, _vp, _sz, _vp]),
     "mi3d_add_inplace": (_i, [_vp, _vp, _sz, _vp]),
+    "mi3d_slice_channels": (_i, [_vp, _i, _i, _i, _vp, _sz, _vp]),
+    "mi3d_skip_grad": (_i, [_vp, _vp, _i, _i, _vp, _i, _sz, ctypes.c_float, _vp]),
     "mi3d_dice_workspace_bytes": (_sz, [_i]),
     "mi3d_dice_loss": (_i, [_vp, _vp, _sz, _i, ctypes.c_float, _vp, _sz, _vp, _vp, _vp]),
     "mi3d_dice_grad": (_i, [_vp, _vp, _sz, _i, ctypes.c_float, _vp, _vp, _vp]),

@@ -132,7 +132,7 @@ static int run_kernel(Kernel k, const Geom& g, int pass, const void* a, const vo
 // Kernels that apply the optional epilogue of the geometry themselves (the others are followed by one elementwise pass)
 static bool fuses_epilogue(Kernel k, const Geom& g, int pass) {
     if (pass == MI3D_PASS_FWD) return k == K_SP || k == K_S2_FWD || k == K_C4_FWD;
-    if (pass == MI3D_PASS_DGRAD) return (k == K_SP && sp_fuses_dgrad_factor(g)) || (k == K_DGRAD_S2 && dgrad_s2_fuses_factor(g));
+    if (pass == MI3D_PASS_DGRAD) return (k == K_SP && sp_fuses_dgrad_factor(g)) || (k == K_DGRAD_S2 && dgrad_s2_fuses_factor(g)) || k == K_POINTWISE;
     return false;
 }
 

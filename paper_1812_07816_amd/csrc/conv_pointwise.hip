@@ -48,7 +48,8 @@ __global__ void __launch_bounds__(256) pw_fwd_kernel(const uint16_t* __restrict_
 
 template <int CO>
 __global__ void __launch_bounds__(256) pw_dgrad_kernel(const uint16_t* __restrict__ dy, const uint16_t* __restrict__ w,
-                                                       uint16_t* __restrict__ dx, long long voxels, int Cin) {
+                                                       uint16_t* __restrict__ dx, long long voxels, int Cin,
+                                                       const uint16_t* __restrict__ ref, float slope) {
     __shared__ float ws[MAXCO * MAXCI];
     for (int i = threadIdx.x; i < CO * Cin; i += 256) ws[i] = bf16_to_f32(w[i]);
     __syncthreads();
@@ -60,6 +61,10 @@ __global__ void __launch_bounds__(256) pw_dgrad_kernel(const uint16_t* __restric
     float g[CO];
 #pragma unroll
     for (int co = 0; co < CO; ++co) g[co] = bf16_to_f32(dy[v * CO + co]);
+    // optional LeakyReLU derivative of the layer below: factor 1 where its activated output ref is > 0, slope elsewhere
+    uint4 m4 = uint4{0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};
+    if (ref) m4 = *(const uint4*)(ref + v * Cin + c0);
+    const uint32_t m[4] = {m4.x, m4.y, m4.z, m4.w};
     uint32_t o[4];
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
@@ -69,6 +74,8 @@ __global__ void __launch_bounds__(256) pw_dgrad_kernel(const uint16_t* __restric
             a = fmaf(g[co], ws[co * Cin + c0 + 2 * j], a);
             b = fmaf(g[co], ws[co * Cin + c0 + 2 * j + 1], b);
         }
+        if (!((int)(m[j] << 16) > 0)) a *= slope;
+        if (!((int)(m[j] & 0xffff0000u) > 0)) b *= slope;
         o[j] = (uint32_t)f32_to_bf16_rne(a) | ((uint32_t)f32_to_bf16_rne(b) << 16);
     }
     *(uint4*)(dx + v * Cin + c0) = uint4{o[0], o[1], o[2], o[3]};
@@ -140,7 +147,8 @@ static int pw_run(const Geom& g, int pass, const void* a, const void* b, void* o
     }
     if (pass == MI3D_PASS_DGRAD) {
         const long long n = vox * (g.Cin / 8);
-        pw_dgrad_kernel<CO><<<(unsigned)((n + 255) / 256), 256, 0, s>>>((const uint16_t*)a, (const uint16_t*)b, (uint16_t*)out, vox, g.Cin);
+        pw_dgrad_kernel<CO><<<(unsigned)((n + 255) / 256), 256, 0, s>>>((const uint16_t*)a, (const uint16_t*)b, (uint16_t*)out, vox, g.Cin,
+                                                                             (const uint16_t*)g.ref, g.slope);
         return check_launch();
     }
     const int blocks = pw_wgrad_blocks(g);

@@ -41,7 +41,8 @@ struct SpParams {
     uint16_t* dump;         // 8 KB that masked store lanes write to instead of y
     float* part;            // [cin chunk][voxel][Cout] fp32 partial outputs (chunked variant)
     int NCH;                // cin chunks of the chunked variant
-    float slope;            // LeakyReLU slope applied to the output (1 = none)
+    float slope;            // LeakyReLU slope applied to the output (1 = none); with ref: the factor where ref <= 0
+    const uint16_t* ref;    // MASK variant: tensor of the output's shape whose sign selects the factor 1 or slope
     int N, D, H, W, Cin, Cout, Do, Ho, Wo, pD, pH, pW;
     int HT, WT, CT;         // tiles per plane, cout tiles
     long long units;        // N*CT*HT*WT*Do
@@ -180,7 +181,18 @@ __device__ __forceinline__ void store_row(const float (&o)[16], float* p, bool o
 // Lanes l and l+32 hold the two interleaved halves of a voxel's 32 couts
 // (4 couts of every group of 8).  Swapping between the lane halves gives each
 // lane 16 consecutive couts, stored as two 16-byte pieces.
-__device__ __forceinline__ void store_row(const uint32_t (&o)[8], uint16_t* p, bool ok, uint16_t* dump) {
+// Two packed bf16 values times the factor chosen by the sign of the two bf16 values of m (> 0: 1, else slope);
+// fp32 product, rounded to nearest even.  A factor of 1 returns the input bits.
+__device__ __forceinline__ uint32_t scale_pair(uint32_t v, uint32_t m, float slope) {
+    float lo = __builtin_bit_cast(float, v << 16), hi = __builtin_bit_cast(float, v & 0xffff0000u);
+    lo = (int)(m << 16) > 0 ? lo : lo * slope;
+    hi = (int)(m & 0xffff0000u) > 0 ? hi : hi * slope;
+    f32x2 f = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2));
+}
+
+template <bool MASK>
+__device__ __forceinline__ void store_row(const uint32_t (&o)[8], uint16_t* p, bool ok, uint16_t* dump, const uint4 (&m)[2], float slope) {
     typedef __attribute__((ext_vector_type(2))) unsigned u32x2;
     uint4 c[2];
 #pragma unroll
@@ -188,6 +200,10 @@ __device__ __forceinline__ void store_row(const uint32_t (&o)[8], uint16_t* p, b
         u32x2 s0 = __builtin_amdgcn_permlane32_swap(o[2 * k], o[2 * k + 4], false, false);
         u32x2 s1 = __builtin_amdgcn_permlane32_swap(o[2 * k + 1], o[2 * k + 5], false, false);
         c[k].x = s0[0]; c[k].y = s1[0]; c[k].z = s0[1]; c[k].w = s1[1];
+        if (MASK) {
+            c[k].x = scale_pair(c[k].x, m[k].x, slope); c[k].y = scale_pair(c[k].y, m[k].y, slope);
+            c[k].z = scale_pair(c[k].z, m[k].z, slope); c[k].w = scale_pair(c[k].w, m[k].w, slope);
+        }
     }
     // Unconditional stores: lanes outside the tensor (or with nothing pending) write to the dump area.
     // Behind a branch the compiler cannot count the stores in its vmcnt bookkeeping and makes the next
@@ -208,7 +224,10 @@ __device__ __forceinline__ void store_row(const uint32_t (&o)[8], uint16_t* p, b
 // PART (with NC = 1): the 32-channel chunks of Cin are separate work units whose weights (54 KB) stay resident; each
 // writes fp32 partial outputs and a second kernel adds the chunks in index order.  For the deep, small layers this is
 // two to three times faster than streaming the weights of all chunks through LDS for every staged plane.
-template <int NC, bool PART = false>
+// MASK (with NC = 1, data gradient): every output element is multiplied by 1 where P.ref is > 0 and by P.slope
+// elsewhere (LeakyReLU derivative of the layer below) after its rounding to bf16 and rounded again: the bits of the
+// plain kernel followed by an elementwise pass, without that pass's read and write of the gradient.
+template <int NC, bool PART = false, bool MASK = false>
 __global__ void __launch_bounds__(256, 1) sp_conv_kernel(SpParams P) {
     extern __shared__ __attribute__((aligned(16))) char lds[];
     constexpr bool STREAM = NC == 0;
@@ -353,10 +372,20 @@ __global__ void __launch_bounds__(256, 1) sp_conv_kernel(SpParams P) {
         bool st_pending = false;
         const int ow_ = w0 + (lane & 31);
         const long long row_pitch = (long long)P.Wo * P.Cout;
+        uint4 mk[MASK ? RH : 1][2];   // MASK: the pieces of ref at the addresses of the pending stores
+        const uint16_t* refn = MASK ? P.ref + (long long)n * P.Do * P.Ho * P.Wo * P.Cout : nullptr;
+        auto load_mask = [&](int r) {     // unconditional, like the stores: masked lanes read the dump area
+            if constexpr (MASK) {
+                const bool ok = st_pending && ow_ < P.Wo && h0 + wave * RH + r < P.Ho;
+                const uint16_t* q = ok ? refn + st_off + r * row_pitch + 16 * (lane >> 5) : P.dump + lane * 16;
+                mk[r][0] = *(const uint4*)q;
+                mk[r][1] = *(const uint4*)(q + 8);
+            }
+        };
         auto store_piece = [&](int r) {
             const bool ok = st_pending && ow_ < P.Wo && h0 + wave * RH + r < P.Ho;
             if constexpr (PART) store_row(outp[r], partn + st_off + r * row_pitch + 4 * (lane >> 5), ok, (float*)P.dump + lane * 32);
-            else store_row(outp[r], yn + st_off + r * row_pitch + 16 * (lane >> 5), ok, P.dump + lane * 16);
+            else store_row<MASK>(outp[r], yn + st_off + r * row_pitch + 16 * (lane >> 5), ok, P.dump + lane * 16, mk[MASK ? r : 0], P.slope);
         };
 
         // every segment starts from cleared accumulators (keeps them dead across segments)
@@ -392,11 +421,13 @@ __global__ void __launch_bounds__(256, 1) sp_conv_kernel(SpParams P) {
             for (int kd_ = 0; kd_ < 3; ++kd_)                                                   \
                 if (jj - kd_ >= 0 && jj - kd_ < nJ - 2) kdmask_ |= 1 << kd_;                    \
             plane_compute<PHASE, ZERO, LAST>(acc, in_lds + buf_ * STAGE_BYTES + lane_in_off,    \
-                                             w_lane + (STREAM ? 0 : (CHUNK) * W_BYTES), outp, P.slope, kdmask_, [&](int k) { \
+                                             w_lane + (STREAM ? 0 : (CHUNK) * W_BYTES), outp, MASK ? 1.f : P.slope, kdmask_, [&](int k) { \
                 if (STREAM && k % 6 == 0) { /* all pieces of the slot at the start of its phase: a full phase of cover */ \
                     _Pragma("unroll") for (int i_ = 0; i_ < NWL; ++i_) wreg[i_] = *(const uint4*)(wsrc_[k / 6] + wpiece[i_] * 16); \
                 }                                                                               \
                 if (k < NLOAD) load_piece(k, NBUF == 2 ? ((sq + 1) & 1) : 0);                   \
+                if (MASK && k >= NLOAD - RH && k < NLOAD) load_mask(k - (NLOAD - RH));          \
+                if (k < NLOAD) {}                                                               \
                 else if (k < NLOAD + RH) {                                                      \
                     store_piece(k - NLOAD);                                                     \
                     if (k == NLOAD + RH - 1) st_pending = false;                                \
@@ -435,6 +466,8 @@ __global__ void __launch_bounds__(256, 1) sp_conv_kernel(SpParams P) {
         }
 #undef SP_STEP
 #undef SP_STAGE
+#pragma unroll
+        for (int r = 0; r < RH; ++r) load_mask(r);
 #pragma unroll
         for (int r = 0; r < RH; ++r) store_piece(r);  // the last plane of the segment
     }
@@ -493,7 +526,10 @@ static bool sp_use_chunks(const Geom& g, int pass) {
 }
 
 // the chunked variant applies the optional derivative factor of the geometry while it sums the chunks
-bool sp_fuses_dgrad_factor(const Geom& g) { return sp_supported(g, MI3D_PASS_DGRAD) && sp_use_chunks(g, MI3D_PASS_DGRAD); }
+// ... and so does the one-chunk kernel (contraction over 32 channels), in its store path
+bool sp_fuses_dgrad_factor(const Geom& g) {
+    return sp_supported(g, MI3D_PASS_DGRAD) && (sp_use_chunks(g, MI3D_PASS_DGRAD) || g.Cout == 32);
+}
 
 static size_t sp_part_offset(const Geom& g) { return (((size_t)g.w_elems() * 2 + 255) & ~(size_t)255) + 8192; }
 
@@ -535,7 +571,9 @@ int sp_conv(const Geom& g, int pass, const void* in, const void* w, void* out, v
     P.CT = P.Cout / 32;
     const bool chunks = sp_use_chunks(g, pass);
     P.NCH = chunks ? P.Cin / 32 : 1;
-    P.slope = pass == MI3D_PASS_FWD ? g.slope : 1.f;
+    const bool mask = pass == MI3D_PASS_DGRAD && g.ref && g.slope != 1.f && !chunks && P.Cin == 32;
+    P.slope = (pass == MI3D_PASS_FWD || mask) ? g.slope : 1.f;
+    P.ref = mask ? (const uint16_t*)g.ref : nullptr;
     P.units = (long long)P.N * P.CT * P.NCH * P.HT * P.WT * P.Do;
     int dev = 0, cus = 256;
     if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
@@ -550,6 +588,7 @@ int sp_conv(const Geom& g, int pass, const void* in, const void* w, void* out, v
         if (e == hipSuccess) e = hipFuncSetAttribute((const void*)sp_conv_kernel<2>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds2);
         if (e == hipSuccess) e = hipFuncSetAttribute((const void*)sp_conv_kernel<0>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds1);
         if (e == hipSuccess) e = hipFuncSetAttribute((const void*)sp_conv_kernel<1, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds1);
+        if (e == hipSuccess) e = hipFuncSetAttribute((const void*)sp_conv_kernel<1, false, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds1);
         if (e != hipSuccess) { note_hip_error(e); return MI3D_ERR_HIP; }
         attr_set = true;
     }
@@ -563,7 +602,8 @@ int sp_conv(const Geom& g, int pass, const void* in, const void* w, void* out, v
         sum_chunks_bf16_kernel<<<(unsigned)blocks, 256, 0, s>>>(P.part, (uint16_t*)out, n / 8, n, P.NCH, g.slope, pass == MI3D_PASS_DGRAD ? (const uint16_t*)g.ref : nullptr);
         return check_launch();
     }
-    if (nc == 1) sp_conv_kernel<1><<<(unsigned)nwg, 256, lds1, s>>>(P);
+    if (mask) sp_conv_kernel<1, false, true><<<(unsigned)nwg, 256, lds1, s>>>(P);
+    else if (nc == 1) sp_conv_kernel<1><<<(unsigned)nwg, 256, lds1, s>>>(P);
     else if (nc == 2) sp_conv_kernel<2><<<(unsigned)nwg, 256, lds2, s>>>(P);
     else sp_conv_kernel<0><<<(unsigned)nwg, 256, lds1, s>>>(P);
     return check_launch();

@@ -78,6 +78,36 @@ __global__ void __launch_bounds__(256) split_kernel(const uint4* __restrict__ in
     }
 }
 
+// out[v] = in[v][off : off + C]; channel counts in 16-byte pieces
+__global__ void __launch_bounds__(256) slice_kernel(const uint4* __restrict__ in, int pt, int poff, int pc, uint4* __restrict__ out, long long total) {
+    for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < total; i += (long long)gridDim.x * 256) {
+        const long long v = i / pc;
+        const int c = (int)(i - v * pc);
+        out[i] = in[v * pt + poff + c];
+    }
+}
+
+// da[v][c] <- (da[v][c] + dcat[v][off + c]) * (a[v][c] > 0 ? 1 : slope): the second gradient of a skip tensor is taken
+// from its half of the concatenated tensor's gradient, and the LeakyReLU derivative of the layer that produced
+// the skip tensor is applied, in one pass (fp32, one rounding)
+__global__ void __launch_bounds__(256) skip_grad_kernel(uint4* __restrict__ da, const uint4* __restrict__ dcat, int pt, int poff, int pc,
+                                                        const uint4* __restrict__ a, long long total, float slope) {
+    for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < total; i += (long long)gridDim.x * 256) {
+        const long long v = i / pc;
+        const int c = (int)(i - v * pc);
+        float g[8], h[8], f[8];
+        unpack8(da[i], g);
+        unpack8(dcat[v * pt + poff + c], h);
+        unpack8(a[i], f);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const float sum = g[j] + h[j];
+            g[j] = f[j] > 0.f ? sum : slope * sum;
+        }
+        da[i] = pack8(g);
+    }
+}
+
 // a <- a + b (fp32 add, one rounding)
 __global__ void __launch_bounds__(256) add_kernel(uint4* __restrict__ a, const uint4* __restrict__ b, long long n8) {
     for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < n8; i += (long long)gridDim.x * 256) {
@@ -230,6 +260,23 @@ int mi3d_split_channels(const void* in, int Ca, int Cb, void* a, void* b, size_t
     if (voxels == 0) return MI3D_OK;
     const long long total = (long long)voxels * ((Ca + Cb) / 8);
     split_kernel<<<grid_for(total), 256, 0, (hipStream_t)stream>>>((const uint4*)in, Ca / 8, Cb / 8, (uint4*)a, (uint4*)b, total);
+    return check_launch();
+}
+
+int mi3d_slice_channels(const void* in, int C_total, int c_off, int C, void* out, size_t voxels, void* stream) {
+    if (!in || !out || !al16(in) || !al16(out) || C <= 0 || c_off < 0 || c_off + C > C_total || C % 8 || c_off % 8 || C_total % 8) return MI3D_ERR_INVALID_ARG;
+    if (voxels == 0) return MI3D_OK;
+    const long long total = (long long)voxels * (C / 8);
+    slice_kernel<<<grid_for(total), 256, 0, (hipStream_t)stream>>>((const uint4*)in, C_total / 8, c_off / 8, C / 8, (uint4*)out, total);
+    return check_launch();
+}
+
+int mi3d_skip_grad(void* da, const void* dcat, int C_total, int c_off, const void* a, int C, size_t voxels, float slope, void* stream) {
+    if (!da || !dcat || !a || !al16(da) || !al16(dcat) || !al16(a)) return MI3D_ERR_INVALID_ARG;
+    if (C <= 0 || c_off < 0 || c_off + C > C_total || C % 8 || c_off % 8 || C_total % 8) return MI3D_ERR_INVALID_ARG;
+    if (voxels == 0) return MI3D_OK;
+    const long long total = (long long)voxels * (C / 8);
+    skip_grad_kernel<<<grid_for(total), 256, 0, (hipStream_t)stream>>>((uint4*)da, (const uint4*)dcat, C_total / 8, c_off / 8, C / 8, (const uint4*)a, total, slope);
     return check_launch();
 }
 

@@ -34,6 +34,21 @@ def split_channels(x, a, b):
     check(lib().mi3d_split_channels(_p(x), Ca, Cb, _p(a), _p(b), vox, _stream()), "split_channels")
 
 
+def slice_channels(x, c_off, out):
+    Ct, C = x.shape[-1], out.shape[-1]
+    vox = out.numel() // C
+    assert x.numel() == vox * Ct
+    check(lib().mi3d_slice_channels(_p(x), Ct, c_off, C, _p(out), vox, _stream()), "slice_channels")
+
+
+def skip_grad(da, dcat, c_off, a, slope=0.01):
+    """da <- (da + dcat[..., c_off : c_off + C]) * (a > 0 ? 1 : slope), in place on da."""
+    Ct, C = dcat.shape[-1], da.shape[-1]
+    vox = da.numel() // C
+    assert dcat.numel() == vox * Ct and a.numel() == da.numel()
+    check(lib().mi3d_skip_grad(_p(da), _p(dcat), Ct, c_off, _p(a), C, vox, slope, _stream()), "skip_grad")
+
+
 def add_inplace(a, b):
     assert a.numel() == b.numel()
     check(lib().mi3d_add_inplace(_p(a), _p(b), a.numel(), _stream()), "add_inplace")

@@ -204,12 +204,13 @@ class UNetStep:
             live += o["out"].bytes
         if "src" in o:
             live += o["src"].bytes
-        # skip gradients produced by decoder levels already walked back and not yet consumed by the encoder
+        # gradients of concatenated tensors (their skip halves) of decoder levels already walked back and not yet
+        # consumed by the encoder
         for g, oo in enumerate(self.ops):
             if oo["kind"] == "cat" and g >= f:
                 enc_reader = min(oo["skip"].bwd_ops)   # conv1 of the next encoder level reads the skip tensor
                 if enc_reader >= op:
-                    live += oo["skip"].bytes
+                    live += oo["out"].bytes
         return fixed + live
 
     # ---- storage of saved tensors
@@ -343,7 +344,9 @@ class UNetStep:
                 a = self._need(op["src"])
                 mc.conv3d_wgrad(op["desc"], a, da, self.dw[op["w"]], self.ws)
                 nxt = torch.empty(op["src"].shape, dtype=bf, device="cuda")
-                mc.conv3d_dgrad(op["desc"], da, self.w[op["w"]], nxt, self.ws)
+                # its input is the last convolution's activation: the data gradient applies that derivative as well
+                mc.conv3d_dgrad_lrelu(op["desc"], da, self.w[op["w"]], a, SLOPE, nxt, self.ws)
+                premasked = True
                 da = nxt
             elif k == "conv":
                 if not premasked:
@@ -364,20 +367,22 @@ class UNetStep:
                     else:
                         mc.conv3d_dgrad(op["desc"], da, self.w[op["w"]], nxt, self.ws)
                     da = nxt
-                    if op["src"].id in dskip:          # the input is also a skip connection: add its second gradient
+                    if op["src"].id in dskip:
+                        # the input is also a skip connection: its second gradient is the skip half of the gradient of
+                        # the concatenated tensor; one pass adds it and applies the derivative of the producing layer
                         if trace is not None:
                             trace[op["name"] + ".dgrad"] = da.clone()
-                        glue.add_inplace(da, dskip.pop(op["src"].id))
+                        dcat, c_off = dskip.pop(op["src"].id)
+                        glue.skip_grad(da, dcat, c_off, self._need(op["src"]), SLOPE)
+                        premasked = True
             elif k == "cat":
                 c = op["c"]
-                shp = op["out"].shape[:-1]
-                d_up = torch.empty(shp + (c,), dtype=bf, device="cuda")
-                d_sk = torch.empty(shp + (c,), dtype=bf, device="cuda")
-                glue.split_channels(da, d_up, d_sk)
-                dskip[op["skip"].id] = d_sk
-                da = d_up
+                d_up = torch.empty(op["out"].shape[:-1] + (c,), dtype=bf, device="cuda")
+                glue.slice_channels(da, 0, d_up)
+                dskip[op["skip"].id] = (da, c)      # the skip half stays where it is until the encoder reads it
                 if trace is not None:
-                    trace[op["name"] + ".dskip"] = d_sk.clone()
+                    trace[op["name"] + ".dskip"] = da[..., c:].clone()
+                da = d_up
             elif k == "up":
                 a = self._need(op["src"])
                 # roles: x := gradient of the up-sampled map, dy := the small input

@@ -55,6 +55,25 @@ def test_concat_split_add(glue):
     assert np.max(np.abs(host(s) - ref)) <= 2 ** -8 * np.max(np.abs(ref))
 
 
+def test_slice_and_skip_gradient(glue):
+    shape = (2, 3, 5, 7)
+    dcat = si.normal(50, 5, shape + (96,), bf16=True)
+    for off, C in ((0, 32), (32, 64), (64, 32)):
+        out = torch.empty(shape + (C,), dtype=torch.bfloat16, device="cuda")
+        glue.slice_channels(dev(dcat), off, out)
+        assert np.array_equal(host(out), dcat[..., off:off + C].astype(np.float64))
+    # gradient of a skip tensor: (encoder-path gradient + its half of the concatenated gradient) * LeakyReLU'(a)
+    da = si.normal(50, 6, shape + (64,), bf16=True)
+    a = si.normal(50, 7, shape + (64,), bf16=True)
+    a[0, 0, 0, 0, :4] = 0.0                       # zero counts as the negative branch
+    g = dev(da)
+    glue.skip_grad(g, dev(dcat), 32, dev(a))
+    ref = ou._lrelu_grad(a.astype(np.float64), da.astype(np.float64) + dcat[..., 32:].astype(np.float64))
+    assert np.max(np.abs(host(g) - ref)) <= 2 ** -8 * np.max(np.abs(ref))
+    neg = a <= 0
+    assert neg.any() and np.max(np.abs(host(g)[neg] - ref[neg])) <= 2 ** -8 * np.max(np.abs(ref[neg]))
+
+
 @pytest.mark.parametrize("vol", [8, 24])
 def test_dice_loss_and_gradient(glue, vol):
     N = 2

@@ -103,13 +103,17 @@ def test_every_op_matches_oracle_on_the_steps_own_tensors(unet, N, vol, channels
     close("loss grad", t["loss.din"], dl_ref)
     # ---- backward ops
     close("head wgrad", dw["head"], oc.wgrad(gh, t["dec0.conv2.a"], t["head.dout"]))
-    close("head dgrad", t["head.din"], oc.dgrad(gh, t["head.dout"], w["head"]))
-    # the second convolution of a level hands down the gradient with the first one's LeakyReLU derivative applied
-    # (one call); everywhere else the derivative is a step of its own
+    close("head dgrad", t["head.din"], ou._lrelu_grad(t["dec0.conv2.a"], oc.dgrad(gh, t["head.dout"], w["head"])))
+    # The LeakyReLU derivative of a layer is applied by whoever hands the gradient down to it where that is one
+    # call: the second convolution of a level (to the first), the head (to the last convolution) and the pass that
+    # adds the skip half of a concatenated gradient (to the skip tensor's producer).  Elsewhere (below an
+    # up-sampling layer) it is a step of its own.
     through = {name: src for name, src, *_ in convs if name.endswith("conv2")}
+    skip_src = {f"enc{l}.conv2" for l in range(L - 1)}
+    handed_down = set(through.values()) | skip_src | {"dec0.conv2"}
     for name, src, vin, ci, co, s in convs:
         g = oc.shape(N, vin, vin, vin, ci, co, 3, s, 1)
-        if name in through.values():
+        if name in handed_down:
             assert np.array_equal(t[name + ".dz"], t[name + ".dout"])
         else:
             dz_ref = ou._lrelu_grad(t[name + ".a"], t[name + ".dout"])     # the output has the sign of the pre-activation
@@ -124,7 +128,7 @@ def test_every_op_matches_oracle_on_the_steps_own_tensors(unet, N, vol, channels
         if name.startswith("enc") and name.endswith("conv1"):          # its input is a skip tensor: second gradient
             l = int(name[3]) - 1
             close(name + " dgrad", t[name + ".dgrad"], din_ref)
-            close(name + " skip add", t[name + ".din"], t[name + ".dgrad"] + t[f"dec{l}.cat.dskip"])
+            close(name + " skip add", t[name + ".din"], ou._lrelu_grad(t[src + ".a"], t[name + ".dgrad"] + t[f"dec{l}.cat.dskip"]))
         else:
             close(name + " dgrad", t[name + ".din"], din_ref)
     for dn, src, vbig, c, deep in ups:
