@@ -8,8 +8,8 @@
 // per (kd, kh) covers 32 voxels x 32 couts.  In NDHWC with 4 channels the 8
 // k-values of a lane half are two neighbouring voxels, i.e. 16 contiguous
 // bytes of the staged row: fragments need no im2col.  A workgroup computes a
-// 16 x 32 patch of one output plane from a 3-plane input patch (15 KB of LDS);
-// two persistent workgroups per CU walk the patches.
+// 16 x 32 patch of one output plane from three input plane patches in LDS;
+// two persistent workgroups per CU walk patch columns along D.
 #include "mi3d_internal.h"
 
 namespace mi3d {
@@ -23,150 +23,216 @@ typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
 constexpr int TH = 16, TW = 32, RH = 4;
 constexpr int PR = TH + 2, PCOLS = TW + 3, PITCH = 36;  // patch rows, columns read, row pitch (voxels of 8 bytes)
 constexpr int PLANE = PR * PITCH;                        // voxels per staged plane
-constexpr int NVOX = 3 * PR * PCOLS;                     // voxels to load (1890)
-constexpr int NLOAD = (NVOX + 255) / 256;                // 8
+constexpr int NVOX = PR * PCOLS;                         // voxels to load per plane (630)
+constexpr int NLOAD = (NVOX + 255) / 256;                // 3
+constexpr int SLOTS = 4;                                 // ring of staged planes: three being read, one being filled
 
 struct C4Params {
     const uint16_t* x;
     const uint16_t* wpack;  // [cout block][kd][kh][lane][8]
     uint16_t* y;
+    uint16_t* dump;         // 4 KB that masked store lanes write to instead of y
     int N, D, H, W, Cout, Do, Ho, Wo, pD, pH, pW, HT, WT;
-    long long tiles;        // N*Do*HT*WT
+    long long tiles;        // N*HT*WT*Do, output plane fastest
     int nwg;
     float slope;            // LeakyReLU slope applied to the output (1 = none)
 };
 
-// Persistent workgroups walk a contiguous range of (n, od, 16-row, 32-col) tiles; the input patch of
-// the next tile is fetched into registers while the current one is computed and stored.
+// Persistent workgroups walk a contiguous range of (n, 16-row, 32-col, od) tiles, output plane fastest: a
+// workgroup moves along D through one patch column and keeps the input planes in a ring of four LDS slots, so
+// that every input plane of a segment is fetched once (three planes at the start of a segment, then one per
+// tile, loaded into registers while the current tile is computed and stored).
 // ONE: Cout == 32, the 9 weight fragments stay in registers for the whole kernel (otherwise they are
 // re-read from L2 for every cout block of every tile, a load latency per tile that nothing hides)
 template <bool ONE>
 __global__ void __launch_bounds__(256, 2) c4_fwd_kernel(C4Params P) {
-    __shared__ __attribute__((aligned(16))) char lds[3 * PLANE * 8 + 4 * RH * 2048];
+    // ring of planes, 1 KB that threads without a voxel of the plane write to, store staging
+    __shared__ __attribute__((aligned(16))) char lds[SLOTS * PLANE * 8 + 1024 + 4 * RH * 2048];
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     bf16x8 wf[9];
     if (ONE) {
 #pragma unroll
         for (int q = 0; q < 9; ++q) wf[q] = ((const bf16x8*)P.wpack)[q * 64 + lane];
     }
-    char* stg = lds + 3 * PLANE * 8 + wave * RH * 2048;  // this wave's store staging: RH rows x 32 voxels x 64 B
-    const long long t0 = P.tiles * blockIdx.x / P.nwg, t1 = P.tiles * (blockIdx.x + 1) / P.nwg;
+    char* stg = lds + SLOTS * PLANE * 8 + 1024 + wave * RH * 2048;  // this wave's store staging: RH rows x 32 voxels x 64 B
+    // Work split.  With at least as many workgroups as patch columns, workgroup g takes column g % columns and
+    // the g / columns-th of S equal D segments: workgroups that run side by side then write neighbouring patches of
+    // the same few planes (one workgroup per contiguous range of tiles, each in a plane of its own, measured 25 %
+    // slower: the stores of the whole chip were spread over 500 distant 2 KB rows).  Otherwise contiguous ranges.
+    long long u, u1;
+    const long long columns = P.tiles / P.Do;
+    if (P.nwg >= columns) {
+        const int S = (int)(P.nwg / columns);
+        const int seg = (int)(blockIdx.x / columns);
+        const long long col = blockIdx.x % columns;
+        if (seg >= S) return;
+        u = col * P.Do + (long long)P.Do * seg / S;
+        u1 = col * P.Do + (long long)P.Do * (seg + 1) / S;
+    } else {
+        u = P.tiles * blockIdx.x / P.nwg;
+        u1 = P.tiles * (blockIdx.x + 1) / P.nwg;
+    }
 
-    uint2 px[NLOAD];
-    auto load_tile = [&](long long tile) {  // 3 x 18 x 35 voxels (8 bytes each), zero outside the volume
-        long long b = tile;
-        const int wt = (int)(b % P.WT); b /= P.WT;
-        const int ht = (int)(b % P.HT); b /= P.HT;
-        const int od = (int)(b % P.Do);
-        const int n = (int)(b / P.Do);
+    // this thread's voxels of a staged plane: row, column and LDS offset are the same for every plane
+    int prow[NLOAD], pcol[NLOAD], lds_off[NLOAD];
 #pragma unroll
-        for (int i = 0; i < NLOAD; ++i) {
-            const int q = t + 256 * i;
-            const int pl = q / (PR * PCOLS), rem = q - pl * (PR * PCOLS);
-            const int row = rem / PCOLS, col = rem - row * PCOLS;
-            const int gd = od - P.pD + pl, gh = ht * TH - P.pH + row, gw = wt * TW - P.pW + col;
-            px[i] = uint2{0u, 0u};
-            if (q < NVOX && gd >= 0 && gd < P.D && gh >= 0 && gh < P.H && gw >= 0 && gw < P.W)
-                px[i] = *(const uint2*)(P.x + ((((long long)n * P.D + gd) * P.H + gh) * P.W + gw) * 4);
-        }
-    };
-    auto write_tile = [&]() {
-#pragma unroll
-        for (int i = 0; i < NLOAD; ++i) {
-            const int q = t + 256 * i;
-            const int pl = q / (PR * PCOLS), rem = q - pl * (PR * PCOLS);
-            const int row = rem / PCOLS, col = rem - row * PCOLS;
-            if (q < NVOX) *(uint2*)(lds + (pl * PLANE + row * PITCH + col) * 8) = px[i];
-        }
-    };
+    for (int i = 0; i < NLOAD; ++i) {
+        const int q = t + 256 * i;
+        prow[i] = q / PCOLS;
+        pcol[i] = q - prow[i] * PCOLS;
+        lds_off[i] = q < NVOX ? (prow[i] * PITCH + pcol[i]) * 8 : -1;
+    }
 
-    if (t0 < t1) load_tile(t0);
-    for (long long tile = t0; tile < t1; ++tile) {
-        long long b = tile;
+    while (u < u1) {
+        long long b = u / P.Do;
+        const int od0 = (int)(u - b * P.Do);
+        const long long left = u1 - u;
+        const int od1 = left < (long long)(P.Do - od0) ? od0 + (int)left : P.Do;
+        u += od1 - od0;
         const int wt = (int)(b % P.WT); b /= P.WT;
-        const int ht = (int)(b % P.HT); b /= P.HT;
-        const int od = (int)(b % P.Do);
-        const int n = (int)(b / P.Do);
+        const int ht = (int)(b % P.HT);
+        const int n = (int)(b / P.HT);
         const int h0 = ht * TH, w0 = wt * TW;
-        __syncthreads();  // readers of the previous tile are done
-        write_tile();
+
+        // plane q of the ring is input plane gd = q - pD (zero outside the volume), kept in slot q % 4
+        long long voff[NLOAD];
+        bool vok[NLOAD];
+#pragma unroll
+        for (int i = 0; i < NLOAD; ++i) {
+            const int gh = h0 - P.pH + prow[i], gw = w0 - P.pW + pcol[i];
+            vok[i] = t + 256 * i < NVOX && gh >= 0 && gh < P.H && gw >= 0 && gw < P.W;
+            voff[i] = vok[i] ? ((long long)gh * P.W + gw) * 4 : 0;
+        }
+        const uint16_t* xn = P.x + (long long)n * P.D * P.H * P.W * 4;
+        const long long plane_elems = (long long)P.H * P.W * 4;
+        // Loads and LDS writes are unconditional: voxels outside the volume read a valid address and are zeroed when
+        // they are written, threads without a voxel write to the spare KB.  Behind a branch the compiler cannot pair
+        // a load with its use and waits for vmcnt(0), i.e. for the stores of the tile as well.
+        uint2 px[NLOAD];
+        bool pin = false;
+        auto load_plane = [&](int q) {
+            const int gd = q - P.pD;
+            pin = gd >= 0 && gd < P.D;
+            const uint16_t* base = xn + (pin ? gd : 0) * plane_elems;
+#pragma unroll
+            for (int i = 0; i < NLOAD; ++i) px[i] = *(const uint2*)(base + voff[i]);
+        };
+        auto write_plane = [&](int q) {
+            char* dst = lds + (q & (SLOTS - 1)) * PLANE * 8;
+#pragma unroll
+            for (int i = 0; i < NLOAD; ++i) {
+                const bool keep = pin && vok[i];
+                const uint2 v = {keep ? px[i].x : 0u, keep ? px[i].y : 0u};
+                char* w = lds_off[i] >= 0 ? dst + lds_off[i] : lds + SLOTS * PLANE * 8 + (t & 127) * 8;
+                *(uint2*)w = v;
+            }
+        };
+
+        __syncthreads();  // readers of the previous segment are done
+        for (int kd = 0; kd < 3; ++kd) {
+            load_plane(od0 + kd);
+            write_plane(od0 + kd);
+        }
         __syncthreads();
-        if (tile + 1 < t1) load_tile(tile + 1);
 
-        // input fragments: lane (voxel n, half h) holds voxels n + 2h and n + 2h + 1 of the row = taps kw 2h, 2h + 1
-        bf16x8 xf[3][RH + 2];
-        const char* xl = lds + (wave * RH * PITCH + (lane & 31) + 2 * (lane >> 5)) * 8;
+        // Registers that hold the data of the tile's global stores.  The compiler makes whoever writes a register
+        // next wait until the store that read it has completed; left to the allocator these registers are reused
+        // right at the top of the next tile, which then waits a full store latency.  The empty asm below keeps them
+        // allocated until the next tile's own data replaces them, when those stores are long done.
+        typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
+        u32x4 ov[2 * RH];
 #pragma unroll
-        for (int kd = 0; kd < 3; ++kd)
+        for (int i = 0; i < 2 * RH; ++i) ov[i] = u32x4{0u, 0u, 0u, 0u};
+        for (int od = od0; od < od1; ++od) {
+            load_plane(od + 3);  // the plane the next tile adds (after the last tile: fetched, never read)
+            __builtin_amdgcn_sched_barrier(0);  // keeps the loads here, a whole tile ahead of the LDS write that uses them
+
+            // input fragments: lane (voxel n, half h) holds voxels n + 2h and n + 2h + 1 of the row = taps kw 2h, 2h + 1
+            bf16x8 xf[3][RH + 2];
+            const char* xl = lds + (wave * RH * PITCH + (lane & 31) + 2 * (lane >> 5)) * 8;
 #pragma unroll
-            for (int r = 0; r < RH + 2; ++r) {
-                const uint2 lo = *(const uint2*)(xl + (kd * PLANE + r * PITCH) * 8);
-                const uint2 hi = *(const uint2*)(xl + (kd * PLANE + r * PITCH + 1) * 8);
-                const uint4 v = {lo.x, lo.y, hi.x, hi.y};
-                xf[kd][r] = __builtin_bit_cast(bf16x8, v);
+            for (int kd = 0; kd < 3; ++kd) {
+                const char* xs = xl + ((od + kd) & (SLOTS - 1)) * PLANE * 8;
+#pragma unroll
+                for (int r = 0; r < RH + 2; ++r) {
+                    const uint2 lo = *(const uint2*)(xs + (r * PITCH) * 8);
+                    const uint2 hi = *(const uint2*)(xs + (r * PITCH + 1) * 8);
+                    const uint4 v = {lo.x, lo.y, hi.x, hi.y};
+                    xf[kd][r] = __builtin_bit_cast(bf16x8, v);
+                }
             }
 
-        const int oh0 = h0 + wave * RH;
-        const long long row_pitch = (long long)P.Wo * P.Cout;
-        uint16_t* ybase = P.y + ((((long long)n * P.Do + od) * P.Ho + oh0) * P.Wo + w0) * P.Cout;
+            const int oh0 = h0 + wave * RH;
+            const long long row_pitch = (long long)P.Wo * P.Cout;
+            uint16_t* ybase = P.y + ((((long long)n * P.Do + od) * P.Ho + oh0) * P.Wo + w0) * P.Cout;
 
-        for (int cb = 0; cb < (ONE ? 1 : P.Cout / 32); ++cb) {
-            if (!ONE) {
-                const bf16x8* wp = (const bf16x8*)(P.wpack + (long long)cb * 9 * 512) + lane;
+            for (int cb = 0; cb < (ONE ? 1 : P.Cout / 32); ++cb) {
+                if (!ONE) {
+                    const bf16x8* wp = (const bf16x8*)(P.wpack + (long long)cb * 9 * 512) + lane;
 #pragma unroll
-                for (int q = 0; q < 9; ++q) wf[q] = wp[q * 64];
-            }
-            f32x16 acc[RH];
+                    for (int q = 0; q < 9; ++q) wf[q] = wp[q * 64];
+                }
+                f32x16 acc[RH];
 #pragma unroll
-            for (int kd = 0; kd < 3; ++kd)
+                for (int kd = 0; kd < 3; ++kd)
 #pragma unroll
-                for (int kh = 0; kh < 3; ++kh)
+                    for (int kh = 0; kh < 3; ++kh)
 #pragma unroll
-                    for (int r = 0; r < RH; ++r) {
-                        if (kd == 0 && kh == 0) {
-                            f32x16 z = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-                            acc[r] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[0], xf[0][r], z, 0, 0, 0);
-                        } else {
-                            acc[r] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[kd * 3 + kh], xf[kd][r + kh], acc[r], 0, 0, 0);
+                        for (int r = 0; r < RH; ++r) {
+                            if (kd == 0 && kh == 0) {
+                                f32x16 z = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+                                acc[r] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[0], xf[0][r], z, 0, 0, 0);
+                            } else {
+                                acc[r] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[kd * 3 + kh], xf[kd][r + kh], acc[r], 0, 0, 0);
+                            }
                         }
+                typedef __attribute__((ext_vector_type(2))) unsigned u32x2;
+                // lane (n, h) ends with couts 16h .. 16h+15 of voxel n; the rows pass through LDS so that
+                // each store instruction writes whole 64-byte voxels of 16 neighbouring voxels
+                __builtin_amdgcn_wave_barrier();
+#pragma unroll
+                for (int r = 0; r < RH; ++r) {
+                    uint32_t o[8];
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) {
+                        f32x2 v = {fmaxf(acc[r][2 * i], P.slope * acc[r][2 * i]), fmaxf(acc[r][2 * i + 1], P.slope * acc[r][2 * i + 1])};  // LeakyReLU, 0 <= slope <= 1
+                        bf16x2 bb = __builtin_convertvector(v, bf16x2);
+                        o[i] = __builtin_bit_cast(uint32_t, bb);
                     }
-            typedef __attribute__((ext_vector_type(2))) unsigned u32x2;
-            // lane (n, h) ends with couts 16h .. 16h+15 of voxel n; the rows pass through LDS so that
-            // each store instruction writes whole 64-byte voxels of 16 neighbouring voxels
-            __builtin_amdgcn_wave_barrier();
+                    uint4 c[2];
 #pragma unroll
-            for (int r = 0; r < RH; ++r) {
-                uint32_t o[8];
-#pragma unroll
-                for (int i = 0; i < 8; ++i) {
-                    f32x2 v = {fmaxf(acc[r][2 * i], P.slope * acc[r][2 * i]), fmaxf(acc[r][2 * i + 1], P.slope * acc[r][2 * i + 1])};  // LeakyReLU, 0 <= slope <= 1
-                    bf16x2 bb = __builtin_convertvector(v, bf16x2);
-                    o[i] = __builtin_bit_cast(uint32_t, bb);
+                    for (int k = 0; k < 2; ++k) {
+                        u32x2 s0 = __builtin_amdgcn_permlane32_swap(o[2 * k], o[2 * k + 4], false, false);
+                        u32x2 s1 = __builtin_amdgcn_permlane32_swap(o[2 * k + 1], o[2 * k + 5], false, false);
+                        c[k].x = s0[0]; c[k].y = s1[0]; c[k].z = s0[1]; c[k].w = s1[1];
+                    }
+                    char* q = stg + r * 2048 + (lane & 31) * 64 + (lane >> 5) * 32;
+                    *(uint4*)q = c[0];
+                    *(uint4*)(q + 16) = c[1];
                 }
-                uint4 c[2];
+                // same wave, LDS executes in order: only the compiler must not move the reads above the writes
+                asm volatile("" ::: "memory");
+                __builtin_amdgcn_wave_barrier();
+                asm volatile("" ::: "memory");
 #pragma unroll
-                for (int k = 0; k < 2; ++k) {
-                    u32x2 s0 = __builtin_amdgcn_permlane32_swap(o[2 * k], o[2 * k + 4], false, false);
-                    u32x2 s1 = __builtin_amdgcn_permlane32_swap(o[2 * k + 1], o[2 * k + 5], false, false);
-                    c[k].x = s0[0]; c[k].y = s1[0]; c[k].z = s0[1]; c[k].w = s1[1];
-                }
-                char* q = stg + r * 2048 + (lane & 31) * 64 + (lane >> 5) * 32;
-                *(uint4*)q = c[0];
-                *(uint4*)(q + 16) = c[1];
+                for (int i = 0; i < 2 * RH; ++i) asm volatile("" ::"v"(ov[i]));
+#pragma unroll
+                for (int r = 0; r < RH; ++r)
+#pragma unroll
+                    for (int i = 0; i < 2; ++i) {
+                        const u32x4 v = ov[2 * r + i] = *(const u32x4*)(stg + r * 2048 + i * 1024 + lane * 16);
+                        const int vox = i * 16 + (lane >> 2);
+                        // unconditional (masked lanes write to the dump area): the compiler can then count the stores and
+                        // lets them fly while the next plane goes to LDS, instead of waiting for vmcnt(0) every tile
+                        uint16_t* dst = (w0 + vox < P.Wo && oh0 + r < P.Ho) ? ybase + r * row_pitch + (long long)vox * P.Cout + cb * 32 + (lane & 3) * 8
+                                                                            : P.dump + t * 8;
+                        *(u32x4*)dst = v;
+                    }
             }
-            // same wave, LDS executes in order: only the compiler must not move the reads above the writes
-            asm volatile("" ::: "memory");
-            __builtin_amdgcn_wave_barrier();
-            asm volatile("" ::: "memory");
-#pragma unroll
-            for (int r = 0; r < RH; ++r)
-#pragma unroll
-                for (int i = 0; i < 2; ++i) {
-                    const uint4 v = *(const uint4*)(stg + r * 2048 + i * 1024 + lane * 16);
-                    const int vox = i * 16 + (lane >> 2);
-                    if (w0 + vox < P.Wo && oh0 + r < P.Ho)
-                        *(uint4*)(ybase + r * row_pitch + (long long)vox * P.Cout + cb * 32 + (lane & 3) * 8) = v;
-                }
+            // the slot of plane od + 3 held plane od - 1, whose readers passed the barrier of the previous tile
+            __builtin_amdgcn_sched_barrier(0);  // the use of the loaded plane stays down here, behind the tile's work
+            write_plane(od + 3);
+            __syncthreads();
         }
     }
 }
@@ -196,7 +262,7 @@ bool c4_fwd_supported(const Geom& g) {
     return g.Cin == 4 && g.Cout % 32 == 0;
 }
 
-size_t c4_fwd_workspace_bytes(const Geom& g) { return c4_fwd_supported(g) ? (size_t)(g.Cout / 32) * 9 * 1024 : 0; }
+size_t c4_fwd_workspace_bytes(const Geom& g) { return c4_fwd_supported(g) ? (size_t)(g.Cout / 32) * 9 * 1024 + 4096 : 0; }
 
 int c4_fwd(const Geom& g, const void* x, const void* w, void* y, void* ws, size_t ws_bytes, hipStream_t s) {
     if (ws_bytes < c4_fwd_workspace_bytes(g)) return MI3D_ERR_WORKSPACE;
@@ -206,11 +272,12 @@ int c4_fwd(const Geom& g, const void* x, const void* w, void* y, void* ws, size_
     if (st) return st;
     C4Params P;
     P.x = (const uint16_t*)x; P.wpack = (const uint16_t*)ws; P.y = (uint16_t*)y;
+    P.dump = (uint16_t*)((char*)ws + (size_t)(g.Cout / 32) * 9 * 1024);
     P.N = g.N; P.D = g.D; P.H = g.H; P.W = g.W; P.Cout = g.Cout;
     P.Do = g.Do; P.Ho = g.Ho; P.Wo = g.Wo; P.pD = g.pD; P.pH = g.pH; P.pW = g.pW;
     P.HT = (g.Ho + TH - 1) / TH;
     P.WT = (g.Wo + TW - 1) / TW;
-    P.tiles = (long long)g.N * g.Do * P.HT * P.WT;
+    P.tiles = (long long)g.N * P.HT * P.WT * g.Do;
     P.nwg = (int)(P.tiles < 512 ? P.tiles : 512);
     P.slope = g.slope;
     if (g.Cout == 32) c4_fwd_kernel<true><<<(unsigned)P.nwg, 256, 0, s>>>(P);
@@ -239,6 +306,8 @@ typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
 
 constexpr int WDY_SLAB = TH * TW * 32;          // one 16-cout slab of the dy patch
 constexpr int WDY_BYTES = 2 * WDY_SLAB;         // 32 KB
+constexpr int NVOX3 = 3 * PR * PCOLS;           // voxels of a three-plane x patch (1890)
+constexpr int NLOAD3 = (NVOX3 + 255) / 256;      // 8
 constexpr int WX_BYTES = 3 * PLANE * 8;         // 15.2 KB
 constexpr int WNDY = TH * TW * 4 / 256;         // 8 16-byte pieces per thread
 
@@ -281,7 +350,7 @@ __global__ void __launch_bounds__(256, 2) c4_wgrad_kernel(C4WgParams P) {
         for (int b = 0; b < 3; ++b) acc[a][b] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     // patch loads of one tile into registers (zero outside the volume)
-    uint2 px[NLOAD];
+    uint2 px[NLOAD3];
     uint4 pdy[WNDY];
     auto load_tile = [&](long long tile) {
         long long b = tile;
@@ -291,13 +360,13 @@ __global__ void __launch_bounds__(256, 2) c4_wgrad_kernel(C4WgParams P) {
         const int n = (int)(b / P.Do);
         const int h0 = ht * TH, w0 = wt * TW;
 #pragma unroll
-        for (int i = 0; i < NLOAD; ++i) {
+        for (int i = 0; i < NLOAD3; ++i) {
             const int q = t + 256 * i;
             const int pl = q / (PR * PCOLS), rem = q - pl * (PR * PCOLS);
             const int row = rem / PCOLS, col = rem - row * PCOLS;
             const int gd = od - P.pD + pl, gh = h0 - P.pH + row, gw = w0 - P.pW + col;
             px[i] = uint2{0u, 0u};
-            if (q < NVOX && gd >= 0 && gd < P.D && gh >= 0 && gh < P.H && gw >= 0 && gw < P.W)
+            if (q < NVOX3 && gd >= 0 && gd < P.D && gh >= 0 && gh < P.H && gw >= 0 && gw < P.W)
                 px[i] = *(const uint2*)(P.x + ((((long long)n * P.D + gd) * P.H + gh) * P.W + gw) * 4);
         }
 #pragma unroll
@@ -311,11 +380,11 @@ __global__ void __launch_bounds__(256, 2) c4_wgrad_kernel(C4WgParams P) {
     };
     auto write_tile = [&]() {
 #pragma unroll
-        for (int i = 0; i < NLOAD; ++i) {
+        for (int i = 0; i < NLOAD3; ++i) {
             const int q = t + 256 * i;
             const int pl = q / (PR * PCOLS), rem = q - pl * (PR * PCOLS);
             const int row = rem / PCOLS, col = rem - row * PCOLS;
-            if (q < NVOX) *(uint2*)(x_lds + (pl * PLANE + row * PITCH + col) * 8) = px[i];
+            if (q < NVOX3) *(uint2*)(x_lds + (pl * PLANE + row * PITCH + col) * 8) = px[i];
         }
 #pragma unroll
         for (int i = 0; i < WNDY; ++i) {
@@ -422,7 +491,7 @@ int c4_wgrad(const Geom& g, const void* x, const void* dy, float* dw, void* ws, 
     P.Do = g.Do; P.Ho = g.Ho; P.Wo = g.Wo; P.pD = g.pD; P.pH = g.pH; P.pW = g.pW;
     P.HT = (g.Ho + TH - 1) / TH;
     P.WT = (g.Wo + TW - 1) / TW;
-    P.tiles = (long long)g.N * g.Do * P.HT * P.WT;
+    P.tiles = (long long)g.N * P.HT * P.WT * g.Do;
     P.nwg = c4_wgrad_nwg(g);
     c4_wgrad_kernel<<<dim3((unsigned)P.nwg, (unsigned)(g.Cout / 32)), 256, 0, s>>>(P);
     int st = check_launch();
