@@ -99,6 +99,25 @@ int mi3d_conv3d_dgrad(const mi3d_conv_desc *desc, const void *dy, const void *w,
 int mi3d_conv3d_wgrad(const mi3d_conv_desc *desc, const void *x, const void *dy, float *dw,
                       void *ws, size_t ws_bytes, void *stream);
 
+/* Channel-range operands for the decoder's 2x2x2 stride-2 up-sampling layers (Section 4.1: up-sampling,
+ * then concatenation with the skip connection).  The tensor of x's shape (x of the forward pass and of the weight
+ * gradient, dx of the data gradient) may be `Cin` channels starting at channel `offset` of a tensor that holds
+ * `pitch` channels per voxel (both multiples of 8; pitch 0 or a null view = dense).  With it the transposed
+ * convolution (run as mi3d_conv3d_dgrad with roles swapped) writes straight into its half of the concatenated
+ * tensor, leaving the other channels untouched, and its backward passes read their half of that tensor's
+ * gradient in place.  Only the k = 2, s = 2, p = 0 MFMA kernels take views (even extents, Cin % 32 == 0,
+ * Cout % 64 == 0); any other geometry returns MI3D_ERR_UNSUPPORTED.  The pointer is that of the wide tensor. */
+typedef struct {
+    int pitch;   /* channels per voxel of the tensor in memory */
+    int offset;  /* first channel of the operand */
+} mi3d_view;
+int mi3d_conv3d_fwd_view(const mi3d_conv_desc *desc, const void *x, const mi3d_view *xv, const void *w, void *y,
+                         void *ws, size_t ws_bytes, void *stream);
+int mi3d_conv3d_dgrad_view(const mi3d_conv_desc *desc, const void *dy, const void *w, void *dx, const mi3d_view *dxv,
+                           void *ws, size_t ws_bytes, void *stream);
+int mi3d_conv3d_wgrad_view(const mi3d_conv_desc *desc, const void *x, const mi3d_view *xv, const void *dy, float *dw,
+                           void *ws, size_t ws_bytes, void *stream);
+
 /* Convolution followed by the network's LeakyReLU (Section 4.1) in one call:
  * y = lrelu(conv(x, w)), lrelu(v) = v > 0 ? v : slope * v, applied to the fp32
  * accumulator before the single rounding to bf16.  bf16 only, 0 <= slope < 1
@@ -149,6 +168,9 @@ int mi3d_add_inplace(void *a, const void *b, size_t n, void *stream);
 /* out[v][0:C] = in[v][c_off : c_off + C] for a tensor of C_total channels per voxel (bf16; channel counts and the
  * offset in multiples of 8): one half of a concatenated tensor's gradient without writing the other. */
 int mi3d_slice_channels(const void *in, int C_total, int c_off, int C, void *out, size_t voxels, void *stream);
+/* out[v][c_off : c_off + C] = in[v][0:C] for a tensor `out` of C_total channels per voxel; the other channels
+ * of out are left as they are (the skip connection's half of a concatenated tensor). */
+int mi3d_place_channels(const void *in, int C, void *out, int C_total, int c_off, size_t voxels, void *stream);
 /* Gradient that reaches a skip connection's source layer, in one pass:
  * da[v][c] <- (da[v][c] + dcat[v][c_off + c]) * (a[v][c] > 0 ? 1 : slope).  da (C channels, in place) is the
  * gradient from the encoder path, dcat (C_total channels) the gradient of the concatenated decoder input whose

@@ -12,6 +12,10 @@ class ConvDesc(ctypes.Structure):
                  "sD", "sH", "sW", "pD", "pH", "pW", "dtype")]
 
 
+class View(ctypes.Structure):
+    _fields_ = [("pitch", ctypes.c_int), ("offset", ctypes.c_int)]
+
+
 class SwapConfig(ctypes.Structure):
     _fields_ = [("budget_bytes", ctypes.c_size_t), ("dev_arena", ctypes.c_void_p),
                 ("arena_bytes", ctypes.c_size_t), ("host_pool_bytes", ctypes.c_size_t),
@@ -45,6 +49,7 @@ SIGNATURES = {
     "mi3d_split_channels": (_i, [_vp, _i, _i, _vp, _vp, _sz, _vp]),
     "mi3d_add_inplace": (_i, [_vp, _vp, _sz, _vp]),
     "mi3d_slice_channels": (_i, [_vp, _i, _i, _i, _vp, _sz, _vp]),
+    "mi3d_place_channels": (_i, [_vp, _i, _vp, _i, _i, _sz, _vp]),
     "mi3d_skip_grad": (_i, [_vp, _vp, _i, _i, _vp, _i, _sz, ctypes.c_float, _vp]),
     "mi3d_dice_workspace_bytes": (_sz, [_i]),
     "mi3d_dice_loss": (_i, [_vp, _vp, _sz, _i, ctypes.c_float, _vp, _sz, _vp, _vp, _vp]),
@@ -54,6 +59,9 @@ SIGNATURES = {
     "mi3d_conv3d_fwd": (_i, [_pd, _vp, _vp, _vp, _vp, _sz, _vp]),
     "mi3d_conv3d_dgrad": (_i, [_pd, _vp, _vp, _vp, _vp, _sz, _vp]),
     "mi3d_conv3d_wgrad": (_i, [_pd, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "mi3d_conv3d_fwd_view": (_i, [_pd, _vp, ctypes.POINTER(View), _vp, _vp, _vp, _sz, _vp]),
+    "mi3d_conv3d_dgrad_view": (_i, [_pd, _vp, _vp, _vp, ctypes.POINTER(View), _vp, _sz, _vp]),
+    "mi3d_conv3d_wgrad_view": (_i, [_pd, _vp, ctypes.POINTER(View), _vp, _vp, _vp, _sz, _vp]),
     "mi3d_conv3d_fwd_lrelu": (_i, [_pd, _vp, _vp, _vp, ctypes.c_float, _vp, _sz, _vp]),
     "mi3d_conv3d_dgrad_lrelu": (_i, [_pd, _vp, _vp, _vp, ctypes.c_float, _vp, _vp, _sz, _vp]),
     "mi3d_conv3d_set_kernel_family": (_i, [_i]),

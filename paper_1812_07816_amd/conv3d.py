@@ -96,6 +96,53 @@ def conv3d_dgrad(desc, dy, w, dx=None, ws=None):
     return dx
 
 
+def _view(t, C, offset):
+    """(View, shape check) for the `C` channels starting at `offset` of the channel-last tensor t."""
+    from ._lib import View
+    pitch = t.shape[-1]
+    assert 0 <= offset and offset + C <= pitch
+    return View(int(pitch), int(offset))
+
+
+def conv3d_fwd_view(desc, x_wide, offset, w, y=None, ws=None):
+    """conv3d_fwd whose x is channels [offset, offset + Cin) of x_wide (k2/s2 layers only)."""
+    xs, wsh, ys = _shapes(desc)
+    dt = _tdtype(desc)
+    _chk(x_wide, xs[:-1] + (x_wide.shape[-1],), dt, "x"); _chk(w, wsh, dt, "w")
+    if y is None:
+        y = torch.empty(ys, dtype=dt, device=x_wide.device)
+    _chk(y, ys, dt, "y")
+    v = _view(x_wide, desc.Cin, offset)
+    ws, p, n = _ws(desc, PASS_FWD, ws)
+    check(lib().mi3d_conv3d_fwd_view(ctypes.byref(desc), x_wide.data_ptr(), ctypes.byref(v), w.data_ptr(), y.data_ptr(), p, n, _stream()), "conv3d_fwd_view")
+    return y
+
+
+def conv3d_dgrad_view(desc, dy, w, dx_wide, offset, ws=None):
+    """conv3d_dgrad that writes dx into channels [offset, offset + Cin) of dx_wide (k2/s2 layers only)."""
+    xs, wsh, ys = _shapes(desc)
+    dt = _tdtype(desc)
+    _chk(dy, ys, dt, "dy"); _chk(w, wsh, dt, "w"); _chk(dx_wide, xs[:-1] + (dx_wide.shape[-1],), dt, "dx")
+    v = _view(dx_wide, desc.Cin, offset)
+    ws, p, n = _ws(desc, PASS_DGRAD, ws)
+    check(lib().mi3d_conv3d_dgrad_view(ctypes.byref(desc), dy.data_ptr(), w.data_ptr(), dx_wide.data_ptr(), ctypes.byref(v), p, n, _stream()), "conv3d_dgrad_view")
+    return dx_wide
+
+
+def conv3d_wgrad_view(desc, x_wide, offset, dy, dw=None, ws=None):
+    """conv3d_wgrad whose x is channels [offset, offset + Cin) of x_wide (k2/s2 layers only)."""
+    xs, wsh, ys = _shapes(desc)
+    dt = _tdtype(desc)
+    _chk(x_wide, xs[:-1] + (x_wide.shape[-1],), dt, "x"); _chk(dy, ys, dt, "dy")
+    if dw is None:
+        dw = torch.empty(wsh, dtype=torch.float32, device=dy.device)
+    _chk(dw, wsh, torch.float32, "dw")
+    v = _view(x_wide, desc.Cin, offset)
+    ws, p, n = _ws(desc, PASS_WGRAD, ws)
+    check(lib().mi3d_conv3d_wgrad_view(ctypes.byref(desc), x_wide.data_ptr(), ctypes.byref(v), dy.data_ptr(), dw.data_ptr(), p, n, _stream()), "conv3d_wgrad_view")
+    return dw
+
+
 def conv3d_fwd_lrelu(desc, x, w, slope, y=None, ws=None):
     """y = LeakyReLU(conv(x, w)) in one call."""
     xs, wsh, ys = _shapes(desc)

@@ -198,10 +198,16 @@ size_t mi3d_conv3d_workspace_bytes(const mi3d_conv_desc* desc, int pass) {
 
 // slope / ref: optional LeakyReLU epilogue (forward: on y; data gradient: derivative factor from ref), 1 / null = none
 static int conv_entry(const mi3d_conv_desc* desc, int pass, const void* a, const void* b, void* out, void* ws, size_t ws_bytes, void* stream,
-                      float slope = 1.f, const void* ref = nullptr) {
+                      float slope = 1.f, const void* ref = nullptr, const mi3d_view* xv = nullptr) {
     Geom g;
     int st = make_geom(desc, &g);
     if (st) return st;
+    if (xv && xv->pitch) {   // the tensor of x's shape is a channel range of a wider tensor
+        if (xv->pitch < 0 || xv->offset < 0 || xv->offset + g.Cin > xv->pitch || xv->pitch % 8 || xv->offset % 8) return MI3D_ERR_INVALID_ARG;
+        if (g_family.load() == 1 || choose(g, pass) != K_K2) return MI3D_ERR_UNSUPPORTED;
+        g.x_pitch = xv->pitch;
+        g.x_off = xv->offset;
+    }
     if (!a || !b || !out || !aligned16(a) || !aligned16(b) || !aligned16(out) || !aligned16(ws)) return MI3D_ERR_INVALID_ARG;
     if (ws_bytes && !ws) return MI3D_ERR_INVALID_ARG;
     if (ws_bytes < mi3d_conv3d_workspace_bytes(desc, pass)) return MI3D_ERR_WORKSPACE;
@@ -232,6 +238,18 @@ int mi3d_conv3d_dgrad(const mi3d_conv_desc* desc, const void* dy, const void* w,
 
 int mi3d_conv3d_wgrad(const mi3d_conv_desc* desc, const void* x, const void* dy, float* dw, void* ws, size_t ws_bytes, void* stream) {
     return conv_entry(desc, MI3D_PASS_WGRAD, x, dy, dw, ws, ws_bytes, stream);
+}
+
+int mi3d_conv3d_fwd_view(const mi3d_conv_desc* desc, const void* x, const mi3d_view* xv, const void* w, void* y, void* ws, size_t ws_bytes, void* stream) {
+    return conv_entry(desc, MI3D_PASS_FWD, x, w, y, ws, ws_bytes, stream, 1.f, nullptr, xv);
+}
+
+int mi3d_conv3d_dgrad_view(const mi3d_conv_desc* desc, const void* dy, const void* w, void* dx, const mi3d_view* dxv, void* ws, size_t ws_bytes, void* stream) {
+    return conv_entry(desc, MI3D_PASS_DGRAD, dy, w, dx, ws, ws_bytes, stream, 1.f, nullptr, dxv);
+}
+
+int mi3d_conv3d_wgrad_view(const mi3d_conv_desc* desc, const void* x, const mi3d_view* xv, const void* dy, float* dw, void* ws, size_t ws_bytes, void* stream) {
+    return conv_entry(desc, MI3D_PASS_WGRAD, x, dy, dw, ws, ws_bytes, stream, 1.f, nullptr, xv);
 }
 
 int mi3d_conv3d_fwd_lrelu(const mi3d_conv_desc* desc, const void* x, const void* w, void* y, float slope, void* ws, size_t ws_bytes, void* stream) {

@@ -15,6 +15,16 @@
 // v_permlane32_swap), at the voxel's own address (forward) or at the address of
 // voxel 2 o + t (data gradient).  Workgroups are persistent: workgroup g owns
 // the panel g % NG and walks tiles of 128 small-volume voxels.
+//
+// The big-volume tensor (x of the forward pass and of the weight gradient, dx of the data gradient) may be a
+// channel range of a wider tensor: `pitch` channels per voxel, the operand starting at channel `offset`.  The
+// decoder uses that to up-sample straight into the concatenated tensor and to read the up-sampled half of its
+// gradient in place.
+//
+// Weight gradient: dw[co][t][ci] = sum_o dy[o][co] x[2 o + t][ci], a contraction over the small-volume voxels with
+// both operands transposed on the way (ds_read_b64_tr_b16 from [16-channel slab][voxel] tiles in LDS, as in the
+// 3x3x3 weight-gradient kernels).  A workgroup owns 64 couts x 32 cins x 8 taps (wave w: taps 2w, 2w + 1) and a
+// range of voxels, staged 64 at a time (double buffered); partial sums per workgroup, added in a fixed order.
 #include "mi3d_internal.h"
 
 namespace mi3d {
@@ -33,6 +43,7 @@ struct K2Params {
     uint16_t* dump;         // 2 KB that masked store lanes write to
     int N, Ds, Hs, Ws;      // small volume
     int Cs, Cb;             // channels of the small-volume / big-volume tensor (Cout / Cin of the convolution)
+    int pb, ob;             // big-volume tensor: channels per voxel in memory, first channel of the operand
     int K16;                // k-steps of 16
     int NG;                 // panels (groups of G blocks)
     long long vox;          // N * Ds * Hs * Ws
@@ -65,8 +76,8 @@ __global__ void __launch_bounds__(256, MODE == 1 ? 2 : 1) k2_kernel(K2Params P) 
         const int n = (int)(r / P.Ds);
         // element offset of big-volume voxel 2 o (tap 0); tap (td, th, tw) adds ((td * Hb + th) * Wb + tw) * Cb
         const long long Hb = 2ll * P.Hs, Wb = 2ll * P.Ws;
-        const long long big0 = ((((long long)n * 2 * P.Ds + 2 * od) * Hb + 2 * oh) * Wb + 2 * ow) * P.Cb;
-        auto tap_off = [&](int tap) { return (((long long)(tap >> 2) * Hb + ((tap >> 1) & 1)) * Wb + (tap & 1)) * P.Cb; };
+        const long long big0 = ((((long long)n * 2 * P.Ds + 2 * od) * Hb + 2 * oh) * Wb + 2 * ow) * P.pb + P.ob;
+        auto tap_off = [&](int tap) { return (((long long)(tap >> 2) * Hb + ((tap >> 1) & 1)) * Wb + (tap & 1)) * P.pb; };
         const uint16_t* src = MODE == 0 ? P.in + big0 + 8 * h : P.in + (ok ? v : 0) * P.Cs + 8 * h;
         auto load_b = [&](int kk) -> uint4 {
             if (MODE == 0) {
@@ -150,6 +161,155 @@ __global__ void __launch_bounds__(256) k2_pack_kernel(const uint16_t* __restrict
     wpack[idx] = w[((long long)co * 8 + tap) * Cin + ci];
 }
 
+
+// ---- weight gradient --------------------------------------------------------------------------------------
+typedef __attribute__((__vector_size__(4 * sizeof(short)))) short s16x4;
+typedef __attribute__((__vector_size__(8 * sizeof(short)))) short s16x8;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
+
+constexpr int WV = 64;                              // small-volume voxels per stage
+constexpr int WCO = 64, WCI = 32;                   // channel block of a workgroup
+constexpr int DY_STAGE = (WCO / 16) * WV * 32;      // 4 slabs x 64 voxels x 32 bytes
+constexpr int X_STAGE = 8 * (WCI / 16) * WV * 32;   // 8 taps x 2 slabs x 64 voxels x 32 bytes
+constexpr int W_STAGE = DY_STAGE + X_STAGE;         // 40 KB
+
+struct K2WgParams {
+    const uint16_t* x;      // big volume (a channel range of a tensor with xpitch channels per voxel)
+    const uint16_t* dy;     // small volume, Cs channels
+    float* part;            // [slot][Cs][8][Cb]
+    int Ds, Hs, Ws, Cs, Cb, xpitch, xoff;
+    int vox;                // N * Ds * Hs * Ws
+    int CiT;                // cin blocks
+    int slots;              // workgroups per (cout block, cin block) pair
+};
+
+// 16 channels x 32 voxels from a [voxel][16 channels] slab: lane group g = lane / 16 gets voxels 4g .. 4g + 3 and
+// 16 + 4g .. 16 + 4g + 3 of channel lane % 16 (the same permutation of the contraction index for both operands)
+__device__ __forceinline__ bf16x8 tr_frag(const char* p) {
+    typedef __attribute__((address_space(3))) s16x4* lptr;
+    s16x4 a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lptr)(p));
+    s16x4 b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lptr)(p + 16 * 32));
+    s16x8 c = __builtin_shufflevector(a, b, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8, c);
+}
+
+__global__ void __launch_bounds__(256, 2) k2_wgrad_kernel(K2WgParams P) {
+    extern __shared__ __attribute__((aligned(16))) char lds[];   // two stages
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const int pair = blockIdx.y, slot = blockIdx.x;
+    const int cot = pair / P.CiT, cit = pair % P.CiT;
+    const int stages = (P.vox + WV - 1) / WV;
+    const int s0 = (int)((long long)stages * slot / P.slots), s1 = (int)((long long)stages * (slot + 1) / P.slots);
+
+    // staging plan.  x: piece c = t % 4 (8 channels) of voxel j = t / 4, once per tap; dy: piece c8 = t % 8 of voxels
+    // t / 8 and t / 8 + 32.  Loads are unconditional (voxels past the end read voxel 0 and are zeroed on the way to LDS).
+    const int c = t & 3, j = t >> 2, c8 = t & 7, j2 = t >> 3;
+    const long long Hb = 2ll * P.Hs, Wb = 2ll * P.Ws;
+    typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
+    u32x4 px[8], pdy[2];
+    unsigned okbits = 0;
+    auto load_stage = [&](int s) {
+        const int v = s * WV + j;
+        const bool ok = v < P.vox;
+        int r = ok ? v : 0;
+        const int ow = r % P.Ws; r /= P.Ws;
+        const int oh = r % P.Hs; r /= P.Hs;
+        const int od = r % P.Ds;
+        const int n = r / P.Ds;
+        const uint16_t* src = P.x + ((((long long)n * 2 * P.Ds + 2 * od) * Hb + 2 * oh) * Wb + 2 * ow) * P.xpitch + P.xoff + cit * WCI + c * 8;
+#pragma unroll
+        for (int tap = 0; tap < 8; ++tap)
+            px[tap] = *(const u32x4*)(src + (((long long)(tap >> 2) * Hb + ((tap >> 1) & 1)) * Wb + (tap & 1)) * P.xpitch);
+        okbits = ok ? 1u : 0u;
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int v2 = s * WV + j2 + 32 * i;
+            const bool ok2 = v2 < P.vox;
+            pdy[i] = *(const u32x4*)(P.dy + (long long)(ok2 ? v2 : 0) * P.Cs + cot * WCO + c8 * 8);
+            okbits |= (ok2 ? 2u : 0u) << i;
+        }
+    };
+    auto write_stage = [&](int buf) {
+        char* dyb = lds + buf * W_STAGE;
+        char* xb = dyb + DY_STAGE;
+        const unsigned mx = (okbits & 1u) ? ~0u : 0u;
+#pragma unroll
+        for (int tap = 0; tap < 8; ++tap)
+            *(u32x4*)(xb + ((tap * 2 + (c >> 1)) * WV + j) * 32 + (c & 1) * 16) = px[tap] & mx;
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const unsigned md = ((okbits >> (1 + i)) & 1u) ? ~0u : 0u;
+            *(u32x4*)(dyb + ((c8 >> 1) * WV + j2 + 32 * i) * 32 + (c8 & 1) * 16) = pdy[i] & md;
+        }
+    };
+
+    f32x4 acc[2][4][2];   // [tap of the wave][cout slab][cin slab]
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 4; ++b)
+#pragma unroll
+            for (int d = 0; d < 2; ++d) acc[a][b][d] = f32x4{0.f, 0.f, 0.f, 0.f};
+    const int g = lane >> 4, sl = lane & 15;
+    const int lane_off = (4 * g + (sl >> 2)) * 32 + (sl & 3) * 8;
+
+    if (s0 < s1) {
+        load_stage(s0);
+        write_stage(0);
+    }
+    __syncthreads();
+    for (int s = s0; s < s1; ++s) {
+        const int buf = (s - s0) & 1;
+        load_stage(s + 1 < s1 ? s + 1 : s);   // unconditional; after the last stage: fetched, never used
+        __builtin_amdgcn_sched_barrier(0);
+        const char* dyb = lds + buf * W_STAGE + lane_off;
+        const char* xb = dyb + DY_STAGE;
+#pragma unroll
+        for (int kc = 0; kc < WV / 32; ++kc) {
+            bf16x8 a[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) a[q] = tr_frag(dyb + (q * WV + kc * 32) * 32);
+#pragma unroll
+            for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+                for (int cs = 0; cs < 2; ++cs) {
+                    const bf16x8 b = tr_frag(xb + (((2 * wave + tt) * 2 + cs) * WV + kc * 32) * 32);
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) acc[tt][q][cs] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[q], b, acc[tt][q][cs], 0, 0, 0);
+                }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        write_stage(buf ^ 1);   // its readers passed the barrier of the previous stage
+        __syncthreads();
+    }
+    // C layout of the 16x16 tile: column lane % 16 = cin, row 4 (lane / 16) + v = cout
+    float* out = P.part + (long long)slot * P.Cs * 8 * P.Cb;
+#pragma unroll
+    for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+#pragma unroll
+            for (int cs = 0; cs < 2; ++cs)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int co = cot * WCO + q * 16 + 4 * (lane >> 4) + v;
+                    const int ci = cit * WCI + cs * 16 + (lane & 15);
+                    out[((long long)co * 8 + 2 * wave + tt) * P.Cb + ci] = acc[tt][q][cs][v];
+                }
+}
+
+static int k2_wgrad_slots(const Geom& g) {
+    const int pairs = (g.Cout / WCO) * (g.Cin / WCI);
+    const long long vox = (long long)g.N * g.Do * g.Ho * g.Wo;
+    const long long stages = (vox + WV - 1) / WV;
+    int dev = 0, cus = 256;
+    if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+    long long slots = 2ll * cus / pairs;          // two workgroups per CU
+    if (slots < 1) slots = 1;
+    if (slots > stages) slots = stages;
+    return (int)slots;
+}
+
 int pick_g(int blocks, int K16, int max_kb) {   // largest G in {4, 2, 1} that divides the block count and fits the panel
     for (int g = 4; g >= 1; g >>= 1)
         if (blocks % g == 0 && g * K16 <= max_kb) return g;
@@ -159,22 +319,47 @@ int pick_g(int blocks, int K16, int max_kb) {   // largest G in {4, 2, 1} that d
 }  // namespace
 
 bool k2_supported(const Geom& g, int pass) {
-    if (pass == MI3D_PASS_WGRAD) return false;
     if (g.dtype != MI3D_BF16 || g.kD != 2 || g.kH != 2 || g.kW != 2) return false;
     if (g.sD != 2 || g.sH != 2 || g.sW != 2 || g.pD || g.pH || g.pW) return false;
     if ((g.D | g.H | g.W) & 1) return false;
-    if (g.Cin % 32 || g.Cout % 64) return false;   // k-steps come in fours (the register ring)
+    if (g.Cin % 32 || g.Cout % 64) return false;   // k-steps come in fours (the register ring); 64-cout blocks (weight gradient)
+    if (pass == MI3D_PASS_WGRAD) return (long long)g.N * g.Do * g.Ho * g.Wo < (1ll << 31);
     if (pass == MI3D_PASS_FWD) return pick_g(g.Cout / 32, g.Cin / 2, 128) > 0;
     return pick_g(g.Cin / 4, g.Cout / 16, 64) > 0;
 }
 
 size_t k2_workspace_bytes(const Geom& g, int pass) {
-    return k2_supported(g, pass) ? (((size_t)g.w_elems() * 2 + 255) & ~(size_t)255) + 2048 : 0;
+    if (!k2_supported(g, pass)) return 0;
+    if (pass == MI3D_PASS_WGRAD) return (size_t)k2_wgrad_slots(g) * g.w_elems() * sizeof(float);
+    return (((size_t)g.w_elems() * 2 + 255) & ~(size_t)255) + 2048;
+}
+
+static int k2_wgrad(const Geom& g, const void* x, const void* dy, float* dw, void* ws, hipStream_t s) {
+    K2WgParams P;
+    P.x = (const uint16_t*)x; P.dy = (const uint16_t*)dy; P.part = (float*)ws;
+    P.Ds = g.Do; P.Hs = g.Ho; P.Ws = g.Wo; P.Cs = g.Cout; P.Cb = g.Cin;
+    P.xpitch = g.x_pitch ? g.x_pitch : g.Cin; P.xoff = g.x_off;
+    P.vox = (int)((long long)g.N * g.Do * g.Ho * g.Wo);
+    P.CiT = g.Cin / WCI;
+    P.slots = k2_wgrad_slots(g);
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void*)k2_wgrad_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 2 * W_STAGE);
+        if (e != hipSuccess) { note_hip_error(e); return MI3D_ERR_HIP; }
+        attr_set = true;
+    }
+    k2_wgrad_kernel<<<dim3((unsigned)P.slots, (unsigned)((g.Cout / WCO) * P.CiT)), 256, 2 * W_STAGE, s>>>(P);
+    int st = check_launch();
+    if (st) return st;
+    const long long n = g.w_elems();
+    reduce_partials_kernel<<<(unsigned)((n + 15) / 16), 256, 0, s>>>((const float*)ws, dw, n, P.slots);
+    return check_launch();
 }
 
 int k2_conv(const Geom& g, int pass, const void* a, const void* w, void* out, void* ws, size_t ws_bytes, hipStream_t s) {
     if (!k2_supported(g, pass)) return MI3D_ERR_UNSUPPORTED;
     if (ws_bytes < k2_workspace_bytes(g, pass)) return MI3D_ERR_WORKSPACE;
+    if (pass == MI3D_PASS_WGRAD) return k2_wgrad(g, a, w, (float*)out, ws, s);   // (x, dy, dw)
     const int mode = pass == MI3D_PASS_FWD ? 0 : 1;
     const long long total = g.w_elems();
     k2_pack_kernel<<<(unsigned)((total + 255) / 256), 256, 0, s>>>((const uint16_t*)w, (uint16_t*)ws, g.Cin, g.Cout, mode);
@@ -184,6 +369,7 @@ int k2_conv(const Geom& g, int pass, const void* a, const void* w, void* out, vo
     P.in = (const uint16_t*)a; P.wpack = (const uint16_t*)ws; P.out = (uint16_t*)out;
     P.dump = (uint16_t*)((char*)ws + (((size_t)g.w_elems() * 2 + 255) & ~(size_t)255));
     P.N = g.N; P.Ds = g.Do; P.Hs = g.Ho; P.Ws = g.Wo; P.Cs = g.Cout; P.Cb = g.Cin;
+    P.pb = g.x_pitch ? g.x_pitch : g.Cin; P.ob = g.x_off;
     P.vox = (long long)g.N * g.Do * g.Ho * g.Wo;
     int blocks, G;
     if (mode == 0) { P.K16 = g.Cin / 2; blocks = g.Cout / 32; G = pick_g(blocks, P.K16, 128); }

@@ -87,6 +87,15 @@ __global__ void __launch_bounds__(256) slice_kernel(const uint4* __restrict__ in
     }
 }
 
+// out[v][off : off + C] = in[v]
+__global__ void __launch_bounds__(256) place_kernel(const uint4* __restrict__ in, int pc, uint4* __restrict__ out, int pt, int poff, long long total) {
+    for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < total; i += (long long)gridDim.x * 256) {
+        const long long v = i / pc;
+        const int c = (int)(i - v * pc);
+        out[v * pt + poff + c] = in[i];
+    }
+}
+
 // da[v][c] <- (da[v][c] + dcat[v][off + c]) * (a[v][c] > 0 ? 1 : slope): the second gradient of a skip tensor is taken
 // from its half of the concatenated tensor's gradient, and the LeakyReLU derivative of the layer that produced
 // the skip tensor is applied, in one pass (fp32, one rounding)
@@ -268,6 +277,14 @@ int mi3d_slice_channels(const void* in, int C_total, int c_off, int C, void* out
     if (voxels == 0) return MI3D_OK;
     const long long total = (long long)voxels * (C / 8);
     slice_kernel<<<grid_for(total), 256, 0, (hipStream_t)stream>>>((const uint4*)in, C_total / 8, c_off / 8, C / 8, (uint4*)out, total);
+    return check_launch();
+}
+
+int mi3d_place_channels(const void* in, int C, void* out, int C_total, int c_off, size_t voxels, void* stream) {
+    if (!in || !out || !al16(in) || !al16(out) || C <= 0 || c_off < 0 || c_off + C > C_total || C % 8 || c_off % 8 || C_total % 8) return MI3D_ERR_INVALID_ARG;
+    if (voxels == 0) return MI3D_OK;
+    const long long total = (long long)voxels * (C / 8);
+    place_kernel<<<grid_for(total), 256, 0, (hipStream_t)stream>>>((const uint4*)in, C / 8, (uint4*)out, C_total / 8, c_off / 8, total);
     return check_launch();
 }
 

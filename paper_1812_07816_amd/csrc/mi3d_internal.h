@@ -20,6 +20,10 @@ struct Geom {
     // the layer below, whose activated output `ref` has the shape of dx.
     float slope = 1.f;
     const void* ref = nullptr;
+    // Optional channel-range view of the tensor of x's shape (x of the forward pass and the weight gradient, dx of
+    // the data gradient): it lives in a tensor with x_pitch channels per voxel, starting at channel x_off
+    // (x_pitch = 0: dense).  Set by the dispatcher only for kernels that implement it.
+    int x_pitch = 0, x_off = 0;
     __host__ __device__ long long in_voxels() const { return (long long)N * D * H * W; }
     __host__ __device__ long long out_voxels() const { return (long long)N * Do * Ho * Wo; }
     __host__ __device__ long long taps() const { return (long long)kD * kH * kW; }

@@ -41,6 +41,14 @@ def slice_channels(x, c_off, out):
     check(lib().mi3d_slice_channels(_p(x), Ct, c_off, C, _p(out), vox, _stream()), "slice_channels")
 
 
+def place_channels(x, out, c_off):
+    """out[..., c_off : c_off + C] = x; the other channels of out stay as they are."""
+    C, Ct = x.shape[-1], out.shape[-1]
+    vox = x.numel() // C
+    assert out.numel() == vox * Ct
+    check(lib().mi3d_place_channels(_p(x), C, _p(out), Ct, c_off, vox, _stream()), "place_channels")
+
+
 def skip_grad(da, dcat, c_off, a, slope=0.01):
     """da <- (da + dcat[..., c_off : c_off + C]) * (a > 0 ? 1 : slope), in place on da."""
     Ct, C = dcat.shape[-1], da.shape[-1]

@@ -38,6 +38,7 @@ class _Saved:
     def __init__(self, sid, shape, produce, tag):
         self.id, self.shape, self.bytes = sid, tuple(shape), _numel(shape) * 2
         self.produce, self.last_fwd, self.tag = produce, produce, tag
+        self.complete = produce    # forward op after which the contents are final (a swap-out may start)
         self.bwd_ops = []          # backward ops that read it
         self.ptr, self.view = None, None
 
@@ -103,9 +104,14 @@ class UNetStep:
             v *= 2
             d = mc.make_desc(N, v, v, v, ch[l], ch[l + 1], 2, 2, 0, torch.bfloat16)  # the convolution whose dgrad is the up-sampling
             a.last_fwd = len(self.ops)
-            self.ops.append(dict(kind="up", name=f"dec{l}.up", desc=d, src=a, w=wi, shape=(N, v, v, v, ch[l]))); wi += 1
+            # the up-sampling writes straight into its half of the concatenated tensor, and its backward passes read
+            # their half of that tensor's gradient in place, where the library has the kernels for it
+            in_place = all(mc.kernel_name(d, p) == "mfma_k2s2_panel_gemm" for p in range(3))
+            self.ops.append(dict(kind="up", name=f"dec{l}.up", desc=d, src=a, w=wi, shape=(N, v, v, v, ch[l]), in_place=in_place)); wi += 1
             self.flops += 3 * 2.0 * N * (v // 2) ** 3 * 8 * ch[l] * ch[l + 1]
             cat = new_saved((N, v, v, v, 2 * ch[l]), sw.TAG_DECODER)
+            if in_place:
+                cat.produce = len(self.ops) - 1      # allocated and half filled by the up-sampling, completed by the next op
             skips[l].last_fwd = len(self.ops)
             self.ops.append(dict(kind="cat", name=f"dec{l}.cat", skip=skips[l], out=cat, c=ch[l]))
             a, _ = conv_op(f"dec{l}.conv1", cat, v, 2 * ch[l], ch[l], 1, wi, sw.TAG_DECODER); wi += 1
@@ -196,7 +202,7 @@ class UNetStep:
         fixed = self.w32.numel() * 10 + self.ws.numel() + self.labels.numel()
         if op < self.n_fwd:
             o = self.ops[op]
-            return fixed + (_numel(o["shape"]) * 2 if o["kind"] == "up" else 0)
+            return fixed + (_numel(o["shape"]) * 2 if o["kind"] == "up" and not o["in_place"] else 0)
         f = self.n_fwd - 1 - (op - self.n_fwd)
         o = self.ops[f]
         live = 0
@@ -236,7 +242,7 @@ class UNetStep:
                 s.ptr, s.view = None, None
             if not self.planned[s.id]:
                 continue
-            if s.produce == f:
+            if s.complete == f:
                 self.engine.swap_out(s.id, s.ptr)
             if s.last_fwd == f:
                 self.engine.release(s.id)
@@ -308,14 +314,23 @@ class UNetStep:
                 if trace is not None:
                     trace[op["name"] + ".a"] = out.clone()
             elif k == "up":
-                op["u"] = torch.empty(op["shape"], dtype=bf, device="cuda")
-                mc.conv3d_dgrad(op["desc"], op["src"].view, self.w[op["w"]], op["u"], self.ws)
-                if trace is not None:
-                    trace[op["name"] + ".a"] = op["u"].clone()
+                if op["in_place"]:
+                    cat = self._produce(self.ops[f + 1]["out"])
+                    mc.conv3d_dgrad_view(op["desc"], op["src"].view, self.w[op["w"]], cat, 0, self.ws)
+                    if trace is not None:
+                        trace[op["name"] + ".a"] = cat[..., :op["shape"][-1]].clone()
+                else:
+                    op["u"] = torch.empty(op["shape"], dtype=bf, device="cuda")
+                    mc.conv3d_dgrad(op["desc"], op["src"].view, self.w[op["w"]], op["u"], self.ws)
+                    if trace is not None:
+                        trace[op["name"] + ".a"] = op["u"].clone()
             elif k == "cat":
                 up = self.ops[f - 1]
-                glue.concat_channels(up["u"], op["skip"].view, self._produce(op["out"]))
-                up["u"] = None
+                if up["in_place"]:
+                    glue.place_channels(op["skip"].view, op["out"].view, op["c"])
+                else:
+                    glue.concat_channels(up["u"], op["skip"].view, self._produce(op["out"]))
+                    up["u"] = None
                 if trace is not None:
                     trace[op["name"] + ".a"] = op["out"].view.clone()
             elif k == "head":
@@ -335,7 +350,7 @@ class UNetStep:
             self._before_bwd_op(b)
             k = op["kind"]
             if trace is not None and da is not None:
-                trace[op["name"] + ".dout"] = da.clone()
+                trace[op["name"] + ".dout"] = da[..., :op["shape"][-1]].clone() if k == "up" else da.clone()
             if k == "loss":
                 lg = self._need(op["src"])
                 da = torch.empty(op["src"].shape, dtype=bf, device="cuda")
@@ -377,21 +392,26 @@ class UNetStep:
                         premasked = True
             elif k == "cat":
                 c = op["c"]
-                d_up = torch.empty(op["out"].shape[:-1] + (c,), dtype=bf, device="cuda")
-                glue.slice_channels(da, 0, d_up)
                 dskip[op["skip"].id] = (da, c)      # the skip half stays where it is until the encoder reads it
                 if trace is not None:
                     trace[op["name"] + ".dskip"] = da[..., c:].clone()
-                da = d_up
+                if not self.ops[f - 1]["in_place"]:  # otherwise the up-sampling layer reads its half in place
+                    d_up = torch.empty(op["out"].shape[:-1] + (c,), dtype=bf, device="cuda")
+                    glue.slice_channels(da, 0, d_up)
+                    da = d_up
             elif k == "up":
                 a = self._need(op["src"])
                 # roles: x := gradient of the up-sampled map, dy := the small input
-                mc.conv3d_wgrad(op["desc"], da, a, self.dw[op["w"]], self.ws)
                 nxt = torch.empty(op["src"].shape, dtype=bf, device="cuda")
-                mc.conv3d_fwd(op["desc"], da, self.w[op["w"]], nxt, self.ws)
+                if op["in_place"]:   # da is the gradient of the concatenated tensor; the first half is this layer's
+                    mc.conv3d_wgrad_view(op["desc"], da, 0, a, self.dw[op["w"]], self.ws)
+                    mc.conv3d_fwd_view(op["desc"], da, 0, self.w[op["w"]], nxt, self.ws)
+                else:
+                    mc.conv3d_wgrad(op["desc"], da, a, self.dw[op["w"]], self.ws)
+                    mc.conv3d_fwd(op["desc"], da, self.w[op["w"]], nxt, self.ws)
                 da = nxt
             if trace is not None and da is not None:
-                trace[op["name"] + ".din"] = da.clone()
+                trace[op["name"] + ".din"] = da[..., :op["c"]].clone() if k == "cat" else da.clone()
             self._after_bwd_op(b)
             mark(op["name"], "bwd")
         if update:
