@@ -290,12 +290,15 @@ __global__ void __launch_bounds__(256, 1) sp_conv_kernel(SpParams P) {
             for (int i = t; i < NC * W_BYTES / 16; i += 256) ((uint4*)w_lds)[i] = ((const uint4*)wct)[i];
             cur_ct = ct * (PART ? P.NCH : 1) + chunk0;
         }
-        uint4 wreg[NWL];
-        const int wpiece[NWL] = {t, t + 256, t + 512, t + 768, t + 1024 < WPIECES ? t + 1024 : WPIECES - 1};
+        // (vector type and no pointer table: with a struct type or an indexed table of sources the pieces were kept
+        // in scratch memory, whose loads and stores share the counter of the global loads)
+        typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
+        u32x4 wreg[NWL];
+        const int wlast = t + 1024 < WPIECES ? t + 1024 : WPIECES - 1;
         auto write_wslot = [&](int slot) {
 #pragma unroll
             for (int i = 0; i < NWL; ++i)
-                if (t + 256 * i < WPIECES) *(uint4*)(w_lds + slot * WSLOT + (t + 256 * i) * 16) = wreg[i];
+                if (t + 256 * i < WPIECES) *(u32x4*)(w_lds + slot * WSLOT + (t + 256 * i) * 16) = wreg[i];
         };
         // offsets of this thread's pieces relative to the plane base: bytes (DMA) or elements (register path)
         int goff[NLOAD];
@@ -416,14 +419,17 @@ __global__ void __launch_bounds__(256, 1) sp_conv_kernel(SpParams P) {
             else begin_stage(j_ + 1 - P.pD, 0);                                                 \
             const int buf_ = NBUF == 2 ? (sq & 1) : 0;                                          \
             /* streamed weights: block refilled during phase k = the next user of slot (k + 2) % 3 */ \
-            const char* wsrc_[3] = {wct + ((CHUNK) * 3 + 2) * WSLOT, wct + (cnext_ * 3 + 0) * WSLOT, wct + (cnext_ * 3 + 1) * WSLOT}; \
+            const char* wsrc0_ = wct + ((CHUNK) * 3 + 2) * WSLOT;                               \
+            const char* wsrc1_ = wct + (cnext_ * 3 + 0) * WSLOT;                                \
+            const char* wsrc2_ = wct + (cnext_ * 3 + 1) * WSLOT;                                \
             int kdmask_ = 0;                                                                    \
             for (int kd_ = 0; kd_ < 3; ++kd_)                                                   \
                 if (jj - kd_ >= 0 && jj - kd_ < nJ - 2) kdmask_ |= 1 << kd_;                    \
             plane_compute<PHASE, ZERO, LAST>(acc, in_lds + buf_ * STAGE_BYTES + lane_in_off,    \
                                              w_lane + (STREAM ? 0 : (CHUNK) * W_BYTES), outp, MASK ? 1.f : P.slope, kdmask_, [&](int k) { \
                 if (STREAM && k % 6 == 0) { /* all pieces of the slot at the start of its phase: a full phase of cover */ \
-                    _Pragma("unroll") for (int i_ = 0; i_ < NWL; ++i_) wreg[i_] = *(const uint4*)(wsrc_[k / 6] + wpiece[i_] * 16); \
+                    const char* ws_ = k / 6 == 0 ? wsrc0_ : k / 6 == 1 ? wsrc1_ : wsrc2_;       \
+                    _Pragma("unroll") for (int i_ = 0; i_ < NWL; ++i_) wreg[i_] = *(const u32x4*)(ws_ + (i_ < NWL - 1 ? t + 256 * i_ : wlast) * 16); \
                 }                                                                               \
                 if (k < NLOAD) load_piece(k, NBUF == 2 ? ((sq + 1) & 1) : 0);                   \
                 if (MASK && k >= NLOAD - RH && k < NLOAD) load_mask(k - (NLOAD - RH));          \
