@@ -520,15 +520,23 @@ bool sp_supported(const Geom& g, int pass) {
     return false;
 }
 
+static int sp_cu_count() {
+    int dev = 0, cus = 256;
+    if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+    return cus;
+}
+
 // Chunked variant (32-channel chunks of the contracted channels as work units, resident weights, fp32 partial
-// outputs): used when the convolution contracts at least 96 channels on a volume of at most 64^3 voxels per sample.
-// Measured at N = 1: 128->128 at 48^3 0.31 -> 0.18 ms, 256->256 at 24^3 0.28 -> 0.12 ms, 512->256 at 24^3
-// 0.55 -> 0.21 ms, 320->320 at 12^3 0.21 -> 0.08 ms; at 96^3 (128->64) the two variants tie and the partial
-// outputs would take 0.9 GB, so larger volumes keep the streamed weights.
+// outputs): used when the convolution contracts at least 96 channels and has fewer (cout tile, patch, plane) units
+// than two per CU, i.e. on the smallest volumes, where whole-Cin units leave most of the chip idle.  Measured at
+// N = 1 (chunked / streamed weights): 320->320 at 12^3 0.082 / 0.091 ms, 256->256 at 24^3 0.120 / 0.116,
+// 512->256 at 24^3 0.207 / 0.219; with more units the streamed weights win (256->128 at 48^3 0.38 / 0.28).
 static bool sp_use_chunks(const Geom& g, int pass) {
-    const int cin = pass == MI3D_PASS_DGRAD ? g.Cout : g.Cin;
-    const long long vox = pass == MI3D_PASS_DGRAD ? (long long)g.D * g.H * g.W : (long long)g.Do * g.Ho * g.Wo;
-    return cin >= 96 && vox <= 64ll * 64 * 64;
+    const bool flip = pass == MI3D_PASS_DGRAD;
+    const int cin = flip ? g.Cout : g.Cin, cout = flip ? g.Cin : g.Cout;
+    const int Do = flip ? g.D : g.Do, Ho = flip ? g.H : g.Ho, Wo = flip ? g.W : g.Wo;
+    const long long units = (long long)g.N * (cout / 32) * ((Ho + TH - 1) / TH) * ((Wo + TW - 1) / TW) * Do;
+    return cin >= 96 && units < 2ll * sp_cu_count();
 }
 
 // the chunked variant applies the optional derivative factor of the geometry while it sums the chunks
@@ -581,9 +589,7 @@ int sp_conv(const Geom& g, int pass, const void* in, const void* w, void* out, v
     P.slope = (pass == MI3D_PASS_FWD || mask) ? g.slope : 1.f;
     P.ref = mask ? (const uint16_t*)g.ref : nullptr;
     P.units = (long long)P.N * P.CT * P.NCH * P.HT * P.WT * P.Do;
-    int dev = 0, cus = 256;
-    if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
-    long long nwg = cus;
+    long long nwg = sp_cu_count();
     if (nwg > P.units) nwg = P.units;
     P.nwg = (int)nwg;
     const int nc = P.Cin / 32;

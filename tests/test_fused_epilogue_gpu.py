@@ -20,7 +20,7 @@ CASES = [
     # N, D, H, W, Cin, Cout, k, s, p
     (1, 10, 20, 40, 32, 32, 3, 1, 1),     # plane streaming, one chunk
     (1, 8, 16, 32, 64, 32, 3, 1, 1),      # two chunks (forward) / one chunk, two cout tiles (data gradient)
-    (1, 65, 65, 66, 128, 32, 3, 1, 1),    # streamed weights (volume above the chunked variant's limit); sampled
+    (1, 65, 65, 66, 128, 32, 3, 1, 1),    # streamed weights (enough units to fill the chip without chunking); sampled
     (1, 6, 6, 12, 128, 64, 3, 1, 1),      # chunked variant, forward
     (1, 4, 6, 12, 64, 128, 3, 1, 1),      # chunked variant, data gradient
     (1, 4, 4, 6, 320, 320, 3, 1, 1),
