@@ -66,40 +66,53 @@ __global__ void __launch_bounds__(256, MODE == 1 ? 2 : 1) k2_kernel(K2Params P) 
     const int h = lane >> 5;
     const int cb16 = P.Cb / 16;   // k-steps per tap (forward)
 
+    // Per-tile addressing of this lane's voxel: v (small volume), element offset of big-volume voxel 2 o (tap 0).
+    const long long Hb = 2ll * P.Hs, Wb = 2ll * P.Ws;
+    auto tap_off = [&](int tap) { return (((long long)(tap >> 2) * Hb + ((tap >> 1) & 1)) * Wb + (tap & 1)) * P.pb; };
+    struct Where { long long v, big0; bool ok; };
+    auto locate = [&](long long tile) {
+        Where w;
+        w.v = tile * 128 + wave * 32 + (lane & 31);
+        w.ok = tile < tiles && w.v < P.vox;
+        int r = w.ok ? (int)w.v : 0;             // the small volume has fewer than 2^31 voxels
+        const int ow = r % P.Ws; r /= P.Ws;
+        const int oh = r % P.Hs; r /= P.Hs;
+        const int od = r % P.Ds;
+        const int n = r / P.Ds;
+        w.big0 = ((((long long)n * 2 * P.Ds + 2 * od) * Hb + 2 * oh) * Wb + 2 * ow) * P.pb + P.ob;
+        return w;
+    };
+    auto source = [&](const Where& w) { return MODE == 0 ? P.in + w.big0 + 8 * h : P.in + (w.ok ? w.v : 0) * P.Cs + 8 * h; };
+    auto load_b = [&](const uint16_t* src, int kk) -> uint4 {
+        if (MODE == 0) {
+            const int tap = kk / cb16, c = (kk - tap * cb16) * 16;
+            return *(const uint4*)(src + tap_off(tap) + c);
+        }
+        return *(const uint4*)(src + kk * 16);
+    };
+
+    // The B fragments run through a ring four k-steps deep that does not stop at tile ends: the last four steps of a
+    // tile fetch the first four of the workgroup's next tile, so a tile starts with its operands in registers
+    // (without this every tile began with an exposed load latency).
+    Where cur = locate(first_tile);
+    const uint16_t* src = source(cur);
+    uint4 ring[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) ring[i] = load_b(src, i);
     for (long long tile = first_tile; tile < tiles; tile += tile_step) {
-        const long long v = tile * 128 + wave * 32 + (lane & 31);
-        const bool ok = v < P.vox;
-        long long r = ok ? v : 0;
-        const int ow = (int)(r % P.Ws); r /= P.Ws;
-        const int oh = (int)(r % P.Hs); r /= P.Hs;
-        const int od = (int)(r % P.Ds);
-        const int n = (int)(r / P.Ds);
-        // element offset of big-volume voxel 2 o (tap 0); tap (td, th, tw) adds ((td * Hb + th) * Wb + tw) * Cb
-        const long long Hb = 2ll * P.Hs, Wb = 2ll * P.Ws;
-        const long long big0 = ((((long long)n * 2 * P.Ds + 2 * od) * Hb + 2 * oh) * Wb + 2 * ow) * P.pb + P.ob;
-        auto tap_off = [&](int tap) { return (((long long)(tap >> 2) * Hb + ((tap >> 1) & 1)) * Wb + (tap & 1)) * P.pb; };
-        const uint16_t* src = MODE == 0 ? P.in + big0 + 8 * h : P.in + (ok ? v : 0) * P.Cs + 8 * h;
-        auto load_b = [&](int kk) -> uint4 {
-            if (MODE == 0) {
-                const int tap = kk / cb16, c = (kk - tap * cb16) * 16;
-                return *(const uint4*)(src + tap_off(tap) + c);
-            }
-            return *(const uint4*)(src + kk * 16);
-        };
+        const Where nxt_w = locate(tile + tile_step);      // past the end: voxel 0, loaded and never used
+        const uint16_t* src_next = source(nxt_w);
         f32x16 acc[G];
 #pragma unroll
         for (int g = 0; g < G; ++g)
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[g][i] = 0.f;
-        uint4 ring[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) ring[i] = load_b(i);
         for (int kk0 = 0; kk0 < P.K16; kk0 += 4) {
+            const bool last = kk0 + 4 >= P.K16;
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const bf16x8 b = __builtin_bit_cast(bf16x8, ring[i]);
-                const int nxt = kk0 + 4 + i;
-                ring[i] = load_b(nxt < P.K16 ? nxt : P.K16 - 1);   // unconditional (the last ones are re-reads nobody uses)
+                ring[i] = load_b(last ? src_next : src, last ? i : kk0 + 4 + i);   // unconditional
 #pragma unroll
                 for (int g = 0; g < G; ++g) {
                     const bf16x8 a = *(const bf16x8*)(a_lane + ((long long)(g * P.K16 + kk0 + i)) * 1024);
@@ -126,16 +139,18 @@ __global__ void __launch_bounds__(256, MODE == 1 ? 2 : 1) k2_kernel(K2Params P) 
             const int nb = group * G + g;     // block of 32 output channels
             uint16_t* dst;
             if (MODE == 0) {
-                dst = P.out + v * P.Cs + nb * 32 + 16 * h;
+                dst = P.out + cur.v * P.Cs + nb * 32 + 16 * h;
             } else {
                 const int per_tap = P.Cb / 32;
                 const int tap = nb / per_tap, c0 = (nb - tap * per_tap) * 32;
-                dst = P.out + big0 + tap_off(tap) + c0 + 16 * h;
+                dst = P.out + cur.big0 + tap_off(tap) + c0 + 16 * h;
             }
-            uint16_t* q = ok ? dst : P.dump + lane * 16;
+            uint16_t* q = cur.ok ? dst : P.dump + lane * 16;
             *(uint4*)q = c[0];
             *(uint4*)(q + 8) = c[1];
         }
+        cur = nxt_w;
+        src = src_next;
     }
 }
 
@@ -323,7 +338,8 @@ bool k2_supported(const Geom& g, int pass) {
     if (g.sD != 2 || g.sH != 2 || g.sW != 2 || g.pD || g.pH || g.pW) return false;
     if ((g.D | g.H | g.W) & 1) return false;
     if (g.Cin % 32 || g.Cout % 64) return false;   // k-steps come in fours (the register ring); 64-cout blocks (weight gradient)
-    if (pass == MI3D_PASS_WGRAD) return (long long)g.N * g.Do * g.Ho * g.Wo < (1ll << 31);
+    if ((long long)g.N * g.Do * g.Ho * g.Wo >= (1ll << 31)) return false;   // 32-bit voxel arithmetic
+    if (pass == MI3D_PASS_WGRAD) return true;
     if (pass == MI3D_PASS_FWD) return pick_g(g.Cout / 32, g.Cin / 2, 128) > 0;
     return pick_g(g.Cin / 4, g.Cout / 16, 64) > 0;
 }
