@@ -55,22 +55,24 @@ __global__ void __launch_bounds__(256) lrelu_bwd_kernel(uint4* __restrict__ da, 
 }
 
 // out[v][0:Ca] = a[v], out[v][Ca:Ca+Cb] = b[v]; channel counts in 16-byte pieces
+template <typename I>
 __global__ void __launch_bounds__(256) concat_kernel(const uint4* __restrict__ a, int pa, const uint4* __restrict__ b, int pb,
-                                                     uint4* __restrict__ out, long long total) {
+                                                     uint4* __restrict__ out, I total) {
     const int pc = pa + pb;
-    for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < total; i += (long long)gridDim.x * 256) {
-        const long long v = i / pc;
+    for (I i = (I)blockIdx.x * 256 + threadIdx.x; i < total; i += (I)gridDim.x * 256) {
+        const I v = i / pc;
         const int c = (int)(i - v * pc);
         out[i] = c < pa ? a[v * pa + c] : b[v * pb + (c - pa)];
     }
 }
 
 // a[v] = in[v][0:Ca], b[v] = in[v][Ca:Ca+Cb]
+template <typename I>
 __global__ void __launch_bounds__(256) split_kernel(const uint4* __restrict__ in, int pa, int pb, uint4* __restrict__ a,
-                                                    uint4* __restrict__ b, long long total) {
+                                                    uint4* __restrict__ b, I total) {
     const int pc = pa + pb;
-    for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < total; i += (long long)gridDim.x * 256) {
-        const long long v = i / pc;
+    for (I i = (I)blockIdx.x * 256 + threadIdx.x; i < total; i += (I)gridDim.x * 256) {
+        const I v = i / pc;
         const int c = (int)(i - v * pc);
         const uint4 x = in[i];
         if (c < pa) a[v * pa + c] = x;
@@ -79,18 +81,20 @@ __global__ void __launch_bounds__(256) split_kernel(const uint4* __restrict__ in
 }
 
 // out[v] = in[v][off : off + C]; channel counts in 16-byte pieces
-__global__ void __launch_bounds__(256) slice_kernel(const uint4* __restrict__ in, int pt, int poff, int pc, uint4* __restrict__ out, long long total) {
-    for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < total; i += (long long)gridDim.x * 256) {
-        const long long v = i / pc;
+template <typename I>
+__global__ void __launch_bounds__(256) slice_kernel(const uint4* __restrict__ in, int pt, int poff, int pc, uint4* __restrict__ out, I total) {
+    for (I i = (I)blockIdx.x * 256 + threadIdx.x; i < total; i += (I)gridDim.x * 256) {
+        const I v = i / pc;
         const int c = (int)(i - v * pc);
         out[i] = in[v * pt + poff + c];
     }
 }
 
 // out[v][off : off + C] = in[v]
-__global__ void __launch_bounds__(256) place_kernel(const uint4* __restrict__ in, int pc, uint4* __restrict__ out, int pt, int poff, long long total) {
-    for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < total; i += (long long)gridDim.x * 256) {
-        const long long v = i / pc;
+template <typename I>
+__global__ void __launch_bounds__(256) place_kernel(const uint4* __restrict__ in, int pc, uint4* __restrict__ out, int pt, int poff, I total) {
+    for (I i = (I)blockIdx.x * 256 + threadIdx.x; i < total; i += (I)gridDim.x * 256) {
+        const I v = i / pc;
         const int c = (int)(i - v * pc);
         out[v * pt + poff + c] = in[i];
     }
@@ -99,10 +103,11 @@ __global__ void __launch_bounds__(256) place_kernel(const uint4* __restrict__ in
 // da[v][c] <- (da[v][c] + dcat[v][off + c]) * (a[v][c] > 0 ? 1 : slope): the second gradient of a skip tensor is taken
 // from its half of the concatenated tensor's gradient, and the LeakyReLU derivative of the layer that produced
 // the skip tensor is applied, in one pass (fp32, one rounding)
+template <typename I>
 __global__ void __launch_bounds__(256) skip_grad_kernel(uint4* __restrict__ da, const uint4* __restrict__ dcat, int pt, int poff, int pc,
-                                                        const uint4* __restrict__ a, long long total, float slope) {
-    for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < total; i += (long long)gridDim.x * 256) {
-        const long long v = i / pc;
+                                                        const uint4* __restrict__ a, I total, float slope) {
+    for (I i = (I)blockIdx.x * 256 + threadIdx.x; i < total; i += (I)gridDim.x * 256) {
+        const I v = i / pc;
         const int c = (int)(i - v * pc);
         float g[8], h[8], f[8];
         unpack8(da[i], g);
@@ -260,7 +265,8 @@ int mi3d_concat_channels(const void* a, int Ca, const void* b, int Cb, void* out
     if (!a || !b || !out || !al16(a) || !al16(b) || !al16(out) || Ca <= 0 || Cb <= 0 || Ca % 8 || Cb % 8) return MI3D_ERR_INVALID_ARG;
     if (voxels == 0) return MI3D_OK;
     const long long total = (long long)voxels * ((Ca + Cb) / 8);
-    concat_kernel<<<grid_for(total), 256, 0, (hipStream_t)stream>>>((const uint4*)a, Ca / 8, (const uint4*)b, Cb / 8, (uint4*)out, total);
+    if (total < (1ll << 31)) concat_kernel<unsigned><<<grid_for(total), 256, 0, (hipStream_t)stream>>>((const uint4*)a, Ca / 8, (const uint4*)b, Cb / 8, (uint4*)out, (unsigned)total);
+    else concat_kernel<long long><<<grid_for(total), 256, 0, (hipStream_t)stream>>>((const uint4*)a, Ca / 8, (const uint4*)b, Cb / 8, (uint4*)out, total);
     return check_launch();
 }
 
@@ -268,7 +274,8 @@ int mi3d_split_channels(const void* in, int Ca, int Cb, void* a, void* b, size_t
     if (!a || !b || !in || !al16(a) || !al16(b) || !al16(in) || Ca <= 0 || Cb <= 0 || Ca % 8 || Cb % 8) return MI3D_ERR_INVALID_ARG;
     if (voxels == 0) return MI3D_OK;
     const long long total = (long long)voxels * ((Ca + Cb) / 8);
-    split_kernel<<<grid_for(total), 256, 0, (hipStream_t)stream>>>((const uint4*)in, Ca / 8, Cb / 8, (uint4*)a, (uint4*)b, total);
+    if (total < (1ll << 31)) split_kernel<unsigned><<<grid_for(total), 256, 0, (hipStream_t)stream>>>((const uint4*)in, Ca / 8, Cb / 8, (uint4*)a, (uint4*)b, (unsigned)total);
+    else split_kernel<long long><<<grid_for(total), 256, 0, (hipStream_t)stream>>>((const uint4*)in, Ca / 8, Cb / 8, (uint4*)a, (uint4*)b, total);
     return check_launch();
 }
 
@@ -276,7 +283,8 @@ int mi3d_slice_channels(const void* in, int C_total, int c_off, int C, void* out
     if (!in || !out || !al16(in) || !al16(out) || C <= 0 || c_off < 0 || c_off + C > C_total || C % 8 || c_off % 8 || C_total % 8) return MI3D_ERR_INVALID_ARG;
     if (voxels == 0) return MI3D_OK;
     const long long total = (long long)voxels * (C / 8);
-    slice_kernel<<<grid_for(total), 256, 0, (hipStream_t)stream>>>((const uint4*)in, C_total / 8, c_off / 8, C / 8, (uint4*)out, total);
+    if ((long long)voxels * (C_total / 8) < (1ll << 31)) slice_kernel<unsigned><<<grid_for(total), 256, 0, (hipStream_t)stream>>>((const uint4*)in, C_total / 8, c_off / 8, C / 8, (uint4*)out, (unsigned)total);
+    else slice_kernel<long long><<<grid_for(total), 256, 0, (hipStream_t)stream>>>((const uint4*)in, C_total / 8, c_off / 8, C / 8, (uint4*)out, total);
     return check_launch();
 }
 
@@ -284,7 +292,8 @@ int mi3d_place_channels(const void* in, int C, void* out, int C_total, int c_off
     if (!in || !out || !al16(in) || !al16(out) || C <= 0 || c_off < 0 || c_off + C > C_total || C % 8 || c_off % 8 || C_total % 8) return MI3D_ERR_INVALID_ARG;
     if (voxels == 0) return MI3D_OK;
     const long long total = (long long)voxels * (C / 8);
-    place_kernel<<<grid_for(total), 256, 0, (hipStream_t)stream>>>((const uint4*)in, C / 8, (uint4*)out, C_total / 8, c_off / 8, total);
+    if ((long long)voxels * (C_total / 8) < (1ll << 31)) place_kernel<unsigned><<<grid_for(total), 256, 0, (hipStream_t)stream>>>((const uint4*)in, C / 8, (uint4*)out, C_total / 8, c_off / 8, (unsigned)total);
+    else place_kernel<long long><<<grid_for(total), 256, 0, (hipStream_t)stream>>>((const uint4*)in, C / 8, (uint4*)out, C_total / 8, c_off / 8, total);
     return check_launch();
 }
 
@@ -293,7 +302,8 @@ int mi3d_skip_grad(void* da, const void* dcat, int C_total, int c_off, const voi
     if (C <= 0 || c_off < 0 || c_off + C > C_total || C % 8 || c_off % 8 || C_total % 8) return MI3D_ERR_INVALID_ARG;
     if (voxels == 0) return MI3D_OK;
     const long long total = (long long)voxels * (C / 8);
-    skip_grad_kernel<<<grid_for(total), 256, 0, (hipStream_t)stream>>>((uint4*)da, (const uint4*)dcat, C_total / 8, c_off / 8, C / 8, (const uint4*)a, total, slope);
+    if ((long long)voxels * (C_total / 8) < (1ll << 31)) skip_grad_kernel<unsigned><<<grid_for(total), 256, 0, (hipStream_t)stream>>>((uint4*)da, (const uint4*)dcat, C_total / 8, c_off / 8, C / 8, (const uint4*)a, (unsigned)total, slope);
+    else skip_grad_kernel<long long><<<grid_for(total), 256, 0, (hipStream_t)stream>>>((uint4*)da, (const uint4*)dcat, C_total / 8, c_off / 8, C / 8, (const uint4*)a, total, slope);
     return check_launch();
 }
 
