@@ -143,6 +143,10 @@ def unet_train_step(steps=3, warmup=1):
            "loss": float(plain.loss.item()), "budgets": []}
     del plain
     torch.cuda.empty_cache()
+    adam = unet.UNetStep(N, vol, ch, ws, xd, labels, lr=5e-4, swap=False, optimizer="adam")   # the paper's optimiser and rate
+    out["ms_per_step_no_swap_adam"] = timed(adam)
+    del adam
+    torch.cuda.empty_cache()
     probe = unet.UNetStep(N, vol, ch, ws, xd, labels, swap=True)
     peak = probe.engine.stats()["unswapped_peak_bytes"]
     probe.close()

@@ -195,6 +195,12 @@ int mi3d_dice_grad(const void *logits, const uint8_t *labels, size_t voxels, int
 /* w[i] <- w[i] - lr * dw[i] on the fp32 master weights; w_bf16[i] <- the
  * updated value rounded to bf16 (the copy the convolutions read). */
 int mi3d_sgd_update(float *w, const float *dw, void *w_bf16, size_t n, float lr, void *stream);
+/* Adam, the optimiser the paper trains with (Section 4.1), on fp32 state (m, v: first and second moment, n values each,
+ * zero before step 1): m <- beta1 m + (1 - beta1) dw, v <- beta2 v + (1 - beta2) dw^2,
+ * w <- w - lr (m / (1 - beta1^step)) / (sqrt(v / (1 - beta2^step)) + eps); w_bf16 as in mi3d_sgd_update.
+ * step counts from 1.  MI3D_ERR_INVALID_ARG for step < 1, a beta outside [0, 1) or eps <= 0. */
+int mi3d_adam_update(float *w, const float *dw, float *m, float *v, void *w_bf16, size_t n, float lr, float beta1,
+                     float beta2, float eps, int step, void *stream);
 
 /* ------------------------------------------------------------------------ */
 /* Data-swapping engine                                                     */

@@ -153,3 +153,12 @@ def train_step(x, labels, weights, channels, lr, q=exact):
     loss, dlogits = dice_loss(logits, labels)
     grads = backward(saved, dlogits, channels, q)
     return loss, grads, [w - lr * g for w, g in zip(w64, grads)]
+
+
+def adam_step(w, g, m, v, lr, step, beta1=0.9, beta2=0.999, eps=1e-8):
+    """One Adam update (the optimiser of Section 4.1) in fp64: returns (w, m, v) after step `step` (counted from 1)."""
+    m = beta1 * m + (1.0 - beta1) * g
+    v = beta2 * v + (1.0 - beta2) * g * g
+    mhat = m / (1.0 - beta1 ** step)
+    vhat = v / (1.0 - beta2 ** step)
+    return w - lr * mhat / (np.sqrt(vhat) + eps), m, v

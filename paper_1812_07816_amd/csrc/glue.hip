@@ -4,6 +4,8 @@
 // coefficient of Section 4.3) and the SGD update.  All of them move a few
 // bytes per flop, so each is one pass over its tensors with 16-byte accesses;
 // reductions use a fixed partition and a fixed order (bit-reproducible).
+#include <cmath>
+
 #include "mi3d_internal.h"
 
 
@@ -233,6 +235,22 @@ __global__ void __launch_bounds__(256) sgd_kernel(float* __restrict__ w, const f
     }
 }
 
+// Adam (the optimiser of Section 4.1) on fp32 state: m <- b1 m + (1 - b1) g, v <- b2 v + (1 - b2) g^2,
+// w <- w - lr (m / c1) / (sqrt(v / c2) + eps) with the bias corrections c1 = 1 - b1^t, c2 = 1 - b2^t; wb <- bf16(w)
+__global__ void __launch_bounds__(256) adam_kernel(float* __restrict__ w, const float* __restrict__ dw, float* __restrict__ m, float* __restrict__ v,
+                                                   uint16_t* __restrict__ wb, long long n, float lr, float b1, float b2, float eps, float c1, float c2) {
+    for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < n; i += (long long)gridDim.x * 256) {
+        const float g = dw[i];
+        const float mi = b1 * m[i] + (1.f - b1) * g;
+        const float vi = b2 * v[i] + (1.f - b2) * g * g;
+        m[i] = mi;
+        v[i] = vi;
+        const float x = w[i] - lr * (mi / c1) / (sqrtf(vi / c2) + eps);
+        w[i] = x;
+        wb[i] = f32_to_bf16(x);
+    }
+}
+
 unsigned grid_for(long long items) {
     long long b = (items + 255) / 256;
     return (unsigned)(b < 1 ? 1 : (b > 8192 ? 8192 : b));
@@ -344,6 +362,16 @@ int mi3d_sgd_update(float* w, const float* dw, void* w_bf16, size_t n, float lr,
     if (!w || !dw || !w_bf16) return MI3D_ERR_INVALID_ARG;
     if (n == 0) return MI3D_OK;
     sgd_kernel<<<grid_for((long long)n), 256, 0, (hipStream_t)stream>>>(w, dw, (uint16_t*)w_bf16, (long long)n, lr);
+    return check_launch();
+}
+
+int mi3d_adam_update(float* w, const float* dw, float* m, float* v, void* w_bf16, size_t n, float lr, float beta1, float beta2, float eps,
+                     int step, void* stream) {
+    if (!w || !dw || !m || !v || !w_bf16 || step < 1) return MI3D_ERR_INVALID_ARG;
+    if (!(beta1 >= 0.f && beta1 < 1.f && beta2 >= 0.f && beta2 < 1.f && eps > 0.f)) return MI3D_ERR_INVALID_ARG;
+    if (n == 0) return MI3D_OK;
+    const float c1 = (float)(1.0 - pow((double)beta1, (double)step)), c2 = (float)(1.0 - pow((double)beta2, (double)step));
+    adam_kernel<<<grid_for((long long)n), 256, 0, (hipStream_t)stream>>>(w, dw, m, v, (uint16_t*)w_bf16, (long long)n, lr, beta1, beta2, eps, c1, c2);
     return check_launch();
 }
 

@@ -81,3 +81,8 @@ def dice_grad(logits, labels, sums, dlogits, eps=1e-5):
 def sgd_update(w32, dw32, w16, lr):
     assert w32.numel() == dw32.numel() == w16.numel()
     check(lib().mi3d_sgd_update(_p(w32), _p(dw32), _p(w16), w32.numel(), lr, _stream()), "sgd_update")
+
+
+def adam_update(w32, dw32, m32, v32, w16, lr, step, beta1=0.9, beta2=0.999, eps=1e-8):
+    assert w32.numel() == dw32.numel() == m32.numel() == v32.numel() == w16.numel()
+    check(lib().mi3d_adam_update(_p(w32), _p(dw32), _p(m32), _p(v32), _p(w16), w32.numel(), lr, beta1, beta2, eps, int(step), _stream()), "adam_update")

@@ -3,7 +3,7 @@
 Every arithmetic step is a call into libmi3d.so: the convolutions
 (conv3d_fwd / dgrad / wgrad; the 2x2x2 stride-2 transposed convolution is the
 data gradient of a 2x2x2 / stride-2 convolution with roles swapped; LeakyReLU
-rides in the convolution calls where it can), channel concatenation, sigmoid + soft Dice, SGD.  Saved feature maps (the
+rides in the convolution calls where it can), channel concatenation, sigmoid + soft Dice, SGD or Adam.  Saved feature maps (the
 inputs of the convolutions, Section 3.1 of the paper) live in the swap engine's
 arena and are moved to pinned host memory and back according to its plan.
 
@@ -46,7 +46,7 @@ class _Saved:
 class UNetStep:
     def __init__(self, N, vol, channels, weights, x, labels, lr=1e-2, in_ch=4, classes=3, swap=True,
                  budget_bytes=None, lookahead=2, policy=sw.POLICY_BUDGET, n_tensors=-1, exclude_tags=0,
-                 eviction=sw.EVICT_SWAP):
+                 eviction=sw.EVICT_SWAP, optimizer="sgd"):
         """weights: list of float32 CPU tensors/arrays (bf16-exact start values) in the order enc convs,
         (dec up, conv1, conv2) from the deepest decoder level up, head; x: bf16 CUDA [N,vol,vol,vol,in_ch];
         labels: uint8 CUDA [N,vol,vol,vol,classes]."""
@@ -59,8 +59,13 @@ class UNetStep:
         for w in weights:
             offs.append(total)
             total += (_numel(w.shape) + 63) // 64 * 64
+        assert optimizer in ("sgd", "adam")
+        self.optimizer, self.opt_step = optimizer, 0
         self.w32 = torch.zeros(total, dtype=torch.float32, device="cuda")
         self.dw32 = torch.zeros(total, dtype=torch.float32, device="cuda")
+        if optimizer == "adam":    # first and second moments (Section 4.1 trains with Adam)
+            self.m32 = torch.zeros(total, dtype=torch.float32, device="cuda")
+            self.v32 = torch.zeros(total, dtype=torch.float32, device="cuda")
         self.w16 = torch.zeros(total, dtype=torch.bfloat16, device="cuda")
         self.w, self.dw, self.wm = [], [], []
         for w, o in zip(weights, offs):
@@ -199,7 +204,7 @@ class UNetStep:
     def _transient(self, op):
         """Device bytes an op holds besides saved tensors: parameters, workspace, labels, and the gradient tensors
         alive during it (the gradient pair of the layer, plus the skip gradients waiting for the encoder)."""
-        fixed = self.w32.numel() * 10 + self.ws.numel() + self.labels.numel()
+        fixed = self.w32.numel() * (18 if self.optimizer == "adam" else 10) + self.ws.numel() + self.labels.numel()
         if op < self.n_fwd:
             o = self.ops[op]
             return fixed + (_numel(o["shape"]) * 2 if o["kind"] == "up" and not o["in_place"] else 0)
@@ -415,7 +420,11 @@ class UNetStep:
             self._after_bwd_op(b)
             mark(op["name"], "bwd")
         if update:
-            glue.sgd_update(self.w32, self.dw32, self.w16, self.lr)
+            self.opt_step += 1
+            if self.optimizer == "adam":
+                glue.adam_update(self.w32, self.dw32, self.m32, self.v32, self.w16, self.lr, self.opt_step)
+            else:
+                glue.sgd_update(self.w32, self.dw32, self.w16, self.lr)
 
     def calibrate(self, link_gbs=55.0):
         """Runs one step with per-op events, hands the measured op durations and the host-link rate to the

@@ -105,3 +105,29 @@ def test_sgd_update(glue):
     ref = w - np.float32(0.125) * dw
     assert np.allclose(w32.cpu().numpy(), ref, rtol=1e-6, atol=1e-7)
     assert np.array_equal(w16.float().cpu().numpy(), si.bf16_round(w32.cpu().numpy()))
+
+
+def test_adam_update_over_several_steps(glue):
+    rng = np.random.default_rng(11)
+    n = 4099
+    w = rng.standard_normal(n).astype(np.float32)
+    w32 = torch.from_numpy(w).cuda()
+    m32, v32 = torch.zeros(n, device="cuda"), torch.zeros(n, device="cuda")
+    w16 = torch.empty(n, dtype=torch.bfloat16, device="cuda")
+    rw, rm, rv = w.astype(np.float64), np.zeros(n), np.zeros(n)
+    # the C ABI takes the coefficients as floats: the oracle gets the same (float32-rounded) values
+    b1, b2, eps, lr = (float(np.float32(c)) for c in (0.9, 0.999, 1e-8, 5e-4))
+    mag = np.zeros(n)     # the first moment is a sum of signed terms: its fp32 error is relative to the terms' magnitudes
+    for step in range(1, 6):
+        g = (rng.standard_normal(n) * 10.0 ** rng.integers(-4, 2, size=n)).astype(np.float32)    # gradients over six decades
+        mag = b1 * mag + (1.0 - b1) * np.abs(g)
+        glue.adam_update(w32, torch.from_numpy(g).cuda(), m32, v32, w16, 5e-4, step)
+        rw, rm, rv = ou.adam_step(rw, g.astype(np.float64), rm, rv, lr, step, b1, b2, eps)
+        assert np.allclose(w32.cpu().numpy(), rw, rtol=2e-6, atol=1e-7), step
+        assert np.all(np.abs(m32.cpu().numpy() - rm) <= 1e-6 * mag) and np.allclose(v32.cpu().numpy(), rv, rtol=1e-5, atol=1e-20)
+    assert np.array_equal(w16.float().cpu().numpy(), si.bf16_round(w32.cpu().numpy()))
+    # the first step moves every weight by lr in the direction of its gradient's sign, whatever the gradient's size
+    w1 = torch.from_numpy(w).cuda()
+    g1 = torch.from_numpy(np.where(np.arange(n) % 2 == 0, 3e-3, -7.0).astype(np.float32)).cuda()
+    glue.adam_update(w1, g1, torch.zeros(n, device="cuda"), torch.zeros(n, device="cuda"), w16, 0.25, 1)
+    assert np.allclose(w1.cpu().numpy() - w, np.where(np.arange(n) % 2 == 0, -0.25, 0.25), rtol=1e-4)

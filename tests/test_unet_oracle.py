@@ -106,3 +106,23 @@ def test_rounded_step_stays_close_to_exact_step():
     assert abs(l0 - l1) < 1e-2 * abs(l0)
     for a, b in zip(g0, g1):
         assert np.sum(a * b) / np.sqrt(np.sum(a * a) * np.sum(b * b)) > 0.98
+
+
+def test_adam_step_against_closed_forms():
+    """Pins of the Adam oracle (Section 4.1): the first step is -lr * sign(g) up to eps; with a constant gradient the
+    bias-corrected moments equal g and g^2 at every step, so every step moves by lr * g / (|g| + eps)."""
+    g = np.array([3e-3, -7.0, 0.5, -1e-6])
+    w, m, v = np.zeros(4), np.zeros(4), np.zeros(4)
+    w1, m1, v1 = ou.adam_step(w, g, m, v, 0.1, 1)
+    assert np.allclose(w1, -0.1 * np.sign(g), rtol=1e-2) and np.allclose(m1, 0.1 * g) and np.allclose(v1, 1e-3 * g * g)
+    for step in range(1, 8):
+        w_new, m, v = ou.adam_step(w, g, m, v, 0.1, step)
+        assert np.allclose(w_new - w, -0.1 * g / (np.abs(g) + 1e-8), rtol=1e-9)
+        assert np.allclose(m / (1 - 0.9 ** step), g) and np.allclose(v / (1 - 0.999 ** step), g * g)
+        w = w_new
+    # hand-worked second step with a changing gradient: g1 = 1, g2 = -1, lr = 1, eps -> 0
+    w, m, v = ou.adam_step(0.0, 1.0, 0.0, 0.0, 1.0, 1, eps=1e-12)
+    w, m, v = ou.adam_step(w, -1.0, m, v, 1.0, 2, eps=1e-12)
+    mhat = (0.9 * 0.1 - 0.1) / (1 - 0.81)
+    vhat = (0.999 * 0.001 + 0.001) / (1 - 0.999 ** 2)
+    assert abs(w - (-1.0 - mhat / np.sqrt(vhat))) < 1e-9

@@ -235,3 +235,22 @@ def test_recomputed_and_hybrid_steps_are_bit_identical(unet):
         s = check(st, None)
         assert (s["n_swapped_out"] == 0) if eviction == sw.EVICT_RECOMPUTE else (s["n_swapped_out"] > 0 and s["n_swapped_out"] == s["n_swapped_in"])
         st.close()
+
+
+def test_adam_steps_follow_the_oracle_update_on_the_steps_own_gradients(unet):
+    N, vol = 1, 16
+    ch = CH[:4]
+    _, _, ws, xd, ld = _inputs(N, vol, ch, 5)
+    lr = 5e-4
+    step = unet.UNetStep(N, vol, ch, ws, xd, ld, lr=lr, swap=False, optimizer="adam")
+    w = step.w32.cpu().numpy().astype(np.float64)
+    m, v = np.zeros_like(w), np.zeros_like(w)
+    for k in range(1, 4):
+        step.run(update=True)
+        torch.cuda.synchronize()
+        g = step.dw32.cpu().numpy().astype(np.float64)
+        # the C ABI takes the coefficients as floats: the oracle gets the same (float32-rounded) values
+        w, m, v = ou.adam_step(w, g, m, v, float(np.float32(lr)), k, float(np.float32(0.9)), float(np.float32(0.999)), float(np.float32(1e-8)))
+        assert np.allclose(step.w32.cpu().numpy(), w, rtol=1e-5, atol=1e-7), k
+        assert torch.equal(step.w16, step.w32.to(torch.bfloat16))
+    assert float(np.max(np.abs(w - step.w32.cpu().numpy()))) < 1e-6
