@@ -147,6 +147,13 @@ def unet_train_step(steps=3, warmup=1):
     out["ms_per_step_no_swap_adam"] = timed(adam)
     del adam
     torch.cuda.empty_cache()
+    # the block of Section 4.1 proper: convolution -> instance normalisation -> LeakyReLU, trained with Adam
+    normed = unet.UNetStep(N, vol, ch, ws, xd, labels, lr=5e-4, swap=False, optimizer="adam", norm=True)
+    ms_n = timed(normed)
+    out["instance_norm"] = {"workload": "same step with instance normalisation after every 3x3x3 convolution, Adam", "ms_per_step": ms_n,
+                            "conv_tflops": flops / ms_n / 1e9, "loss": float(normed.loss.item())}
+    del normed
+    torch.cuda.empty_cache()
     probe = unet.UNetStep(N, vol, ch, ws, xd, labels, swap=True)
     peak = probe.engine.stats()["unswapped_peak_bytes"]
     probe.close()

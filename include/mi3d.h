@@ -192,6 +192,23 @@ int mi3d_dice_loss(const void *logits, const uint8_t *labels, size_t voxels, int
 int mi3d_dice_grad(const void *logits, const uint8_t *labels, size_t voxels, int classes, float eps,
                    const float *sums, void *dlogits, void *stream);
 
+/* Instance normalisation (Section 4.1: every convolution of the network is followed by an instance normalisation
+ * and a LeakyReLU), without learnable scale and shift.  Tensors are bf16 NDHWC with `voxels` voxels per sample and C
+ * channels (C % 8 == 0, C <= 512); stats is N x C x 2 floats (mean, 1 / sqrt(var + eps), biased variance over the
+ * voxels of one sample and channel); ws needs mi3d_instnorm_workspace_bytes(N, C) bytes.  The reductions use a fixed
+ * partition and order (bit-reproducible).
+ *   _stats      statistics of the convolution output z.
+ *   _lrelu_fwd  z <- a = lrelu((z - mean) * rstd), in place.
+ *   _lrelu_bwd  da <- dz, in place, from the gradient da with respect to a, the activated tensor a itself (the
+ *               normalised value is taken back from it: a positive slope makes LeakyReLU invertible) and stats:
+ *               g = da * lrelu'(xhat), dz = rstd * (g - mean(g) - xhat * mean(g * xhat)).  0 < slope <= 1. */
+size_t mi3d_instnorm_workspace_bytes(int N, int C);
+int mi3d_instnorm_stats(const void *z, int N, size_t voxels, int C, float eps, float *stats, void *ws, size_t ws_bytes,
+                        void *stream);
+int mi3d_instnorm_lrelu_fwd(void *z, const float *stats, int N, size_t voxels, int C, float slope, void *stream);
+int mi3d_instnorm_lrelu_bwd(void *da, const void *a, const float *stats, int N, size_t voxels, int C, float slope,
+                            void *ws, size_t ws_bytes, void *stream);
+
 /* w[i] <- w[i] - lr * dw[i] on the fp32 master weights; w_bf16[i] <- the
  * updated value rounded to bf16 (the copy the convolutions read). */
 int mi3d_sgd_update(float *w, const float *dw, void *w_bf16, size_t n, float lr, void *stream);

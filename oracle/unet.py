@@ -45,11 +45,40 @@ def _lrelu_grad(z, da):
     return np.where(z > 0, da, SLOPE * da)
 
 
-def forward(x, weights, channels, q=exact):
+IN_EPS = 1e-5
+
+
+def instnorm(z, eps=IN_EPS):
+    """Instance normalisation without scale and shift (Section 4.1): per sample and channel, over the voxels,
+    xhat = (z - mean) / sqrt(var + eps) with the biased variance.  Returns (xhat, mean, rstd), the last two [N, C]."""
+    ax = (1, 2, 3)
+    mean = z.mean(axis=ax)
+    var = ((z - mean[:, None, None, None, :]) ** 2).mean(axis=ax)
+    rstd = 1.0 / np.sqrt(var + eps)
+    return (z - mean[:, None, None, None, :]) * rstd[:, None, None, None, :], mean, rstd
+
+
+def lrelu_inverse(a):
+    """The argument of the LeakyReLU that produced a (its slope is positive, so it is one to one)."""
+    return np.where(a > 0, a, a / SLOPE)
+
+
+def instnorm_lrelu_bwd(xhat, rstd, da):
+    """Gradient with respect to z of a = lrelu(instnorm(z)), given da, xhat = instnorm(z) and rstd [N, C]:
+    g = da * lrelu'(xhat);  dz = rstd * (g - mean_v(g) - xhat * mean_v(g * xhat))."""
+    ax = (1, 2, 3)
+    g = np.where(xhat > 0, da, SLOPE * da)
+    m1 = g.mean(axis=ax)[:, None, None, None, :]
+    m2 = (g * xhat).mean(axis=ax)[:, None, None, None, :]
+    return rstd[:, None, None, None, :] * (g - m1 - xhat * m2)
+
+
+def forward(x, weights, channels, q=exact, norm=False):
     """x [N, V, V, V, Cin] float64; weights in the order of
     synth_inputs.unet_weight_shapes; q: rounding applied to every tensor the
-    step stores (exact = none).  Returns (logits, saved) where saved holds what
-    the backward pass needs."""
+    step stores (exact = none); norm: instance normalisation between every
+    3x3x3 convolution and its LeakyReLU.  Returns (logits, saved) where saved
+    holds what the backward pass needs."""
     L = len(channels)
     N, V = x.shape[0], x.shape[1]
     it = iter(weights)
@@ -60,6 +89,10 @@ def forward(x, weights, channels, q=exact):
         cout, cin = w.shape[0], w.shape[4]
         g = oc.shape(N, vol, vol, vol, cin, cout, 3, s, 1)
         z = q(oc.fwd(g, a, w))
+        if norm:
+            xhat, _, rstd = instnorm(z)
+            out = q(_lrelu(xhat))
+            return out, (g, a, w, out, rstd)      # the activated tensor and the statistics are what is kept
         return q(_lrelu(z)), (g, a, w, z)
 
     for l in range(L):
@@ -110,8 +143,12 @@ def backward(saved, dlogits, channels, q=exact, trace=None):
     dw = {}
 
     def conv_bwd(rec, da, name, need_dx=True):
-        g, a, w, z = rec
-        dz = q(_lrelu_grad(z, da))
+        if len(rec) == 5:       # with instance normalisation: (geometry, input, weights, activated output, rstd)
+            g, a, w, out, rstd = rec
+            dz = q(instnorm_lrelu_bwd(lrelu_inverse(out), rstd, da))
+        else:
+            g, a, w, z = rec
+            dz = q(_lrelu_grad(z, da))
         if trace is not None:
             trace[name + ".dz"] = dz
         dw[name] = oc.wgrad(g, a, dz)
@@ -146,10 +183,10 @@ def backward(saved, dlogits, channels, q=exact, trace=None):
     return [dw[k] for k in order]
 
 
-def train_step(x, labels, weights, channels, lr, q=exact):
+def train_step(x, labels, weights, channels, lr, q=exact, norm=False):
     """One SGD step: (loss, weight gradients, updated weights)."""
     w64 = [np.asarray(w, dtype=np.float64) for w in weights]
-    logits, saved = forward(x, w64, channels, q)
+    logits, saved = forward(x, w64, channels, q, norm)
     loss, dlogits = dice_loss(logits, labels)
     grads = backward(saved, dlogits, channels, q)
     return loss, grads, [w - lr * g for w, g in zip(w64, grads)]

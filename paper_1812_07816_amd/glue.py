@@ -86,3 +86,29 @@ def sgd_update(w32, dw32, w16, lr):
 def adam_update(w32, dw32, m32, v32, w16, lr, step, beta1=0.9, beta2=0.999, eps=1e-8):
     assert w32.numel() == dw32.numel() == m32.numel() == v32.numel() == w16.numel()
     check(lib().mi3d_adam_update(_p(w32), _p(dw32), _p(m32), _p(v32), _p(w16), w32.numel(), lr, beta1, beta2, eps, int(step), _stream()), "adam_update")
+
+
+IN_EPS = 1e-5
+
+
+def instnorm_workspace(N, C):
+    return torch.empty(lib().mi3d_instnorm_workspace_bytes(N, C), dtype=torch.uint8, device="cuda")
+
+
+def instnorm_stats(z, stats, ws, eps=IN_EPS):
+    """stats[n, c] = (mean, 1 / sqrt(var + eps)) of z[n, ..., c]."""
+    N, C = z.shape[0], z.shape[-1]
+    vox = z.numel() // (N * C)
+    assert tuple(stats.shape) == (N, C, 2) and stats.dtype == torch.float32
+    check(lib().mi3d_instnorm_stats(_p(z), N, vox, C, eps, _p(stats), _p(ws), ws.numel(), _stream()), "instnorm_stats")
+
+
+def instnorm_lrelu_fwd(z, stats, slope=0.01):
+    N, C = z.shape[0], z.shape[-1]
+    check(lib().mi3d_instnorm_lrelu_fwd(_p(z), _p(stats), N, z.numel() // (N * C), C, slope, _stream()), "instnorm_lrelu_fwd")
+
+
+def instnorm_lrelu_bwd(da, a, stats, ws, slope=0.01):
+    N, C = a.shape[0], a.shape[-1]
+    assert da.numel() == a.numel()
+    check(lib().mi3d_instnorm_lrelu_bwd(_p(da), _p(a), _p(stats), N, a.numel() // (N * C), C, slope, _p(ws), ws.numel(), _stream()), "instnorm_lrelu_bwd")

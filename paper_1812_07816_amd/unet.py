@@ -10,7 +10,8 @@ arena and are moved to pinned host memory and back according to its plan.
 Network: L encoder levels of two 3x3x3 convolutions (the first of each level
 but the top with stride 2), decoder levels of up-sampling, concatenation
 [upsampled, skip] and two 3x3x3 convolutions, a 1x1x1 head; LeakyReLU after
-every 3x3x3 convolution; no bias, no normalisation.
+every 3x3x3 convolution, optionally behind an instance normalisation
+(norm=True); no bias.
 
 Op timeline for the planner: forward ops in program order, then one backward
 op per forward op in reverse order (backward op of forward op f is
@@ -46,7 +47,7 @@ class _Saved:
 class UNetStep:
     def __init__(self, N, vol, channels, weights, x, labels, lr=1e-2, in_ch=4, classes=3, swap=True,
                  budget_bytes=None, lookahead=2, policy=sw.POLICY_BUDGET, n_tensors=-1, exclude_tags=0,
-                 eviction=sw.EVICT_SWAP, optimizer="sgd"):
+                 eviction=sw.EVICT_SWAP, optimizer="sgd", norm=False):
         """weights: list of float32 CPU tensors/arrays (bf16-exact start values) in the order enc convs,
         (dec up, conv1, conv2) from the deepest decoder level up, head; x: bf16 CUDA [N,vol,vol,vol,in_ch];
         labels: uint8 CUDA [N,vol,vol,vol,classes]."""
@@ -60,6 +61,8 @@ class UNetStep:
             offs.append(total)
             total += (_numel(w.shape) + 63) // 64 * 64
         assert optimizer in ("sgd", "adam")
+        self._trace = None
+        self.norm = bool(norm)     # instance normalisation between every 3x3x3 convolution and its LeakyReLU (Section 4.1)
         self.optimizer, self.opt_step = optimizer, 0
         self.w32 = torch.zeros(total, dtype=torch.float32, device="cuda")
         self.dw32 = torch.zeros(total, dtype=torch.float32, device="cuda")
@@ -135,7 +138,8 @@ class UNetStep:
         for f, op in enumerate(self.ops):
             if op["kind"] == "conv":
                 prev = self.ops[f - 1]
-                op["through_act"] = prev["kind"] == "conv" and prev["out"] is op["src"] and op["src"].id not in skip_ids
+                op["through_act"] = (not self.norm and prev["kind"] == "conv" and prev["out"] is op["src"]
+                                     and op["src"].id not in skip_ids)
         # backward readers: conv f reads its input (weight gradient; LeakyReLU derivative of the layer below where the
         # data gradient applies it) and, unless the layer above has applied it already, its output (LeakyReLU
         # derivative); up and head read their input (weight gradient); the loss reads the logits
@@ -157,6 +161,11 @@ class UNetStep:
                 ws_bytes = max(ws_bytes, max(mc.workspace_bytes(op["desc"], p) for p in range(3)) + 256)
         self.ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
         self.dice_ws = glue.dice_workspace(classes)
+        if self.norm:     # statistics of every normalised convolution output (kept for the backward pass) and the reduction scratch
+            self.in_ws = glue.instnorm_workspace(N, max(ch))
+            for op in self.ops:
+                if op["kind"] == "conv":
+                    op["stats"] = torch.zeros((N, op["out"].shape[-1], 2), dtype=torch.float32, device="cuda")
         self.sums = torch.zeros(3 * classes, dtype=torch.float32, device="cuda")
         self.loss = torch.zeros(1, dtype=torch.float32, device="cuda")
         # ---- swap engine
@@ -205,6 +214,8 @@ class UNetStep:
         """Device bytes an op holds besides saved tensors: parameters, workspace, labels, and the gradient tensors
         alive during it (the gradient pair of the layer, plus the skip gradients waiting for the encoder)."""
         fixed = self.w32.numel() * (18 if self.optimizer == "adam" else 10) + self.ws.numel() + self.labels.numel()
+        if self.norm:
+            fixed += self.in_ws.numel()
         if op < self.n_fwd:
             o = self.ops[op]
             return fixed + (_numel(o["shape"]) * 2 if o["kind"] == "up" and not o["in_place"] else 0)
@@ -275,7 +286,13 @@ class UNetStep:
 
     def _forward_conv(self, op):
         out = self._produce(op["out"])
-        if op["kind"] == "conv":
+        if op["kind"] == "conv" and self.norm:
+            mc.conv3d_fwd(op["desc"], op["src"].view, self.w[op["w"]], out, self.ws)
+            if self._trace is not None:
+                self._trace[op["name"] + ".z"] = out.clone()
+            glue.instnorm_stats(out, op["stats"], self.in_ws)
+            glue.instnorm_lrelu_fwd(out, op["stats"], SLOPE)
+        elif op["kind"] == "conv":
             mc.conv3d_fwd_lrelu(op["desc"], op["src"].view, self.w[op["w"]], SLOPE, out, self.ws)
         else:
             mc.conv3d_fwd(op["desc"], op["src"].view, self.w[op["w"]], out, self.ws)
@@ -303,6 +320,7 @@ class UNetStep:
                 timeline.append((name, phase, ev))
 
         mark("start", "fwd")
+        self._trace = trace
         self.n_recomputed = 0
         if e is not None:
             e.reset_step()
@@ -364,12 +382,17 @@ class UNetStep:
                 a = self._need(op["src"])
                 mc.conv3d_wgrad(op["desc"], a, da, self.dw[op["w"]], self.ws)
                 nxt = torch.empty(op["src"].shape, dtype=bf, device="cuda")
-                # its input is the last convolution's activation: the data gradient applies that derivative as well
-                mc.conv3d_dgrad_lrelu(op["desc"], da, self.w[op["w"]], a, SLOPE, nxt, self.ws)
-                premasked = True
+                if self.norm:
+                    mc.conv3d_dgrad(op["desc"], da, self.w[op["w"]], nxt, self.ws)
+                else:
+                    # its input is the last convolution's activation: the data gradient applies that derivative as well
+                    mc.conv3d_dgrad_lrelu(op["desc"], da, self.w[op["w"]], a, SLOPE, nxt, self.ws)
+                    premasked = True
                 da = nxt
             elif k == "conv":
-                if not premasked:
+                if self.norm:      # through the LeakyReLU and the normalisation, in place
+                    glue.instnorm_lrelu_bwd(da, self._need(op["out"]), op["stats"], self.in_ws, SLOPE)
+                elif not premasked:
                     glue.leaky_relu_bwd(da, self._need(op["out"]), SLOPE)
                 premasked = False
                 if trace is not None:
@@ -393,8 +416,9 @@ class UNetStep:
                         if trace is not None:
                             trace[op["name"] + ".dgrad"] = da.clone()
                         dcat, c_off = dskip.pop(op["src"].id)
-                        glue.skip_grad(da, dcat, c_off, self._need(op["src"]), SLOPE)
-                        premasked = True
+                        # (with normalisation the derivative is not a factor: the pass only adds, slope 1)
+                        glue.skip_grad(da, dcat, c_off, self._need(op["src"]), 1.0 if self.norm else SLOPE)
+                        premasked = not self.norm
             elif k == "cat":
                 c = op["c"]
                 dskip[op["skip"].id] = (da, c)      # the skip half stays where it is until the encoder reads it

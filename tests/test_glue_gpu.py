@@ -131,3 +131,33 @@ def test_adam_update_over_several_steps(glue):
     g1 = torch.from_numpy(np.where(np.arange(n) % 2 == 0, 3e-3, -7.0).astype(np.float32)).cuda()
     glue.adam_update(w1, g1, torch.zeros(n, device="cuda"), torch.zeros(n, device="cuda"), w16, 0.25, 1)
     assert np.allclose(w1.cpu().numpy() - w, np.where(np.arange(n) % 2 == 0, -0.25, 0.25), rtol=1e-4)
+
+
+@pytest.mark.parametrize("shape", [(2, 5, 6, 7, 32), (1, 4, 4, 6, 320), (2, 3, 3, 3, 8), (1, 16, 16, 24, 64)])
+def test_instance_norm_forward_and_backward(glue, shape):
+    N, C = shape[0], shape[-1]
+    idx = [(2, 5, 6, 7, 32), (1, 4, 4, 6, 320), (2, 3, 3, 3, 8), (1, 16, 16, 24, 64)].index(shape)
+    scale = np.linspace(0.05, 20.0, C)                         # channels of very different spread and offset
+    z = si.bf16_round((si.normal(51, 10 * idx, shape) * scale + np.linspace(-3, 3, C)).astype(np.float32))
+    da = si.normal(51, 10 * idx + 1, shape, bf16=True)
+    z64 = z.astype(np.float64)
+    xhat, mean, rstd = ou.instnorm(z64)
+    ws = glue.instnorm_workspace(N, C)
+    stats = torch.zeros((N, C, 2), dtype=torch.float32, device="cuda")
+    a = dev(z)
+    glue.instnorm_stats(a, stats, ws)
+    st = stats.cpu().numpy().astype(np.float64)
+    assert np.allclose(st[..., 0], mean, rtol=1e-5, atol=1e-5 * np.abs(z64).max()) and np.allclose(st[..., 1], rstd, rtol=1e-4)
+    glue.instnorm_lrelu_fwd(a, stats)
+    ref = ou._lrelu(xhat)
+    assert np.max(np.abs(host(a) - ref)) <= 2 ** -8 * np.max(np.abs(ref))
+    # backward from the stored (bf16) activation: the oracle gets the normalised value back from the same tensor
+    g = dev(da)
+    glue.instnorm_lrelu_bwd(g, a, stats, ws)
+    refd = ou.instnorm_lrelu_bwd(ou.lrelu_inverse(host(a)), rstd, da.astype(np.float64))
+    err = np.max(np.abs(host(g) - refd), axis=(0, 1, 2, 3)) / np.max(np.abs(refd), axis=(0, 1, 2, 3))     # per channel: the scales differ by 400x
+    assert err.max() <= 1e-2, err.max()
+    # reductions in a fixed order: the same bits every time
+    g2 = dev(da)
+    glue.instnorm_lrelu_bwd(g2, a, stats, ws)
+    assert torch.equal(g.view(torch.int16), g2.view(torch.int16))

@@ -126,3 +126,74 @@ def test_adam_step_against_closed_forms():
     mhat = (0.9 * 0.1 - 0.1) / (1 - 0.81)
     vhat = (0.999 * 0.001 + 0.001) / (1 - 0.999 ** 2)
     assert abs(w - (-1.0 - mhat / np.sqrt(vhat))) < 1e-9
+
+
+# ---- instance normalisation (Section 4.1) ------------------------------------------------------------------------
+def test_instnorm_output_statistics_and_invariances():
+    rng = np.random.default_rng(5)
+    z = rng.standard_normal((2, 3, 4, 5, 6)) * rng.uniform(0.1, 30.0, size=6) + rng.uniform(-5, 5, size=6)
+    xhat, mean, rstd = ou.instnorm(z)
+    ax = (1, 2, 3)
+    assert np.allclose(xhat.mean(axis=ax), 0.0, atol=1e-12)
+    var = z.var(axis=ax)
+    assert np.allclose(xhat.var(axis=ax), var / (var + ou.IN_EPS), rtol=1e-12)
+    assert np.allclose(mean, z.mean(axis=ax)) and np.allclose(rstd, 1.0 / np.sqrt(var + ou.IN_EPS))
+    # a shift per (sample, channel) changes nothing; a scale changes nothing up to eps
+    shift = rng.standard_normal((2, 1, 1, 1, 6)) * 100
+    assert np.allclose(ou.instnorm(z + shift)[0], xhat, atol=1e-9)
+    assert np.allclose(ou.instnorm(z * 1e3)[0], xhat, atol=1e-6)
+    # a single sample and channel by hand: values 1, 2, 3, 6 -> mean 3, variance 3.5
+    z1 = np.array([1.0, 2.0, 3.0, 6.0]).reshape(1, 1, 2, 2, 1)
+    assert np.allclose(ou.instnorm(z1, eps=0.5)[0].ravel(), (np.array([1.0, 2.0, 3.0, 6.0]) - 3.0) / 2.0)
+
+
+def test_instnorm_lrelu_backward_matches_finite_differences_and_is_orthogonal():
+    rng = np.random.default_rng(6)
+    z = rng.standard_normal((2, 3, 3, 4, 5)) * 2.0 + 0.7
+    da = rng.standard_normal(z.shape)
+
+    def f(z_):
+        return float((ou._lrelu(ou.instnorm(z_)[0]) * da).sum())
+
+    xhat, _, rstd = ou.instnorm(z)
+    dz = ou.instnorm_lrelu_bwd(xhat, rstd, da)
+    h = 1e-6
+    for _ in range(12):
+        idx = tuple(int(rng.integers(0, n)) for n in z.shape)
+        zp, zm = z.copy(), z.copy()
+        zp[idx] += h; zm[idx] -= h
+        fd = (f(zp) - f(zm)) / (2 * h)
+        assert abs(fd - dz[idx]) <= 1e-7 + 1e-5 * abs(fd), (idx, fd, dz[idx])
+    # the output does not depend on the mean or (up to eps) the scale of z: the gradient has no component along 1,
+    # and along xhat only the part eps / (var + eps) of rstd * sum(g xhat)
+    ax = (1, 2, 3)
+    assert np.allclose(dz.sum(axis=ax), 0.0, atol=1e-10)
+    g = np.where(xhat > 0, da, ou.SLOPE * da)
+    along = (dz * xhat).sum(axis=ax)
+    assert np.allclose(along, rstd * (g * xhat).sum(axis=ax) * (1.0 - (xhat ** 2).mean(axis=ax)), rtol=1e-9, atol=1e-12)
+    assert np.all(np.abs(along) < 1e-4)
+    # the kept activation gives the normalised value back
+    assert np.allclose(ou.lrelu_inverse(ou._lrelu(xhat)), xhat, rtol=1e-12)
+
+
+def test_backward_with_instance_normalisation_matches_finite_differences():
+    channels = [2, 3, 4]
+    V = 8
+    rng = np.random.default_rng(8)
+    shapes = si.unet_weight_shapes(channels, in_ch=2, classes=3)
+    ws = [rng.standard_normal(shp) * 0.4 for _, shp in shapes]
+    x = rng.standard_normal((2, V, V, V, 2))
+    t = (rng.random((2, V, V, V, 3)) < 0.4).astype(np.uint8)
+    loss, grads, _ = ou.train_step(x, t, ws, channels, lr=0.0, norm=True)
+
+    def f(ws_):
+        return ou.dice_loss(ou.forward(x, ws_, channels, norm=True)[0], t)[0]
+
+    h = 1e-5
+    for k, (name, shp) in enumerate(shapes):
+        for _ in range(2):
+            idx = tuple(int(rng.integers(0, n)) for n in shp)
+            wp = [w.copy() for w in ws]; wm = [w.copy() for w in ws]
+            wp[k][idx] += h; wm[k][idx] -= h
+            fd = (f(wp) - f(wm)) / (2 * h)
+            assert abs(fd - grads[k][idx]) <= 1e-8 + 5e-4 * abs(fd), (name, idx, fd, grads[k][idx])
