@@ -408,6 +408,11 @@ def main():
     for r in per:
         r["roofline"] = {k: (round(v, 4) if isinstance(v, float) else v) for k, v in roofline_of(r).items()}
         r["roofline"]["traffic"] = measured_traffic(r["kernel"])
+    # what the matrix cores sustain in a bare MFMA loop on this machine (the rate is power-limited and depends on the
+    # operands): context for the MFMA-bound fractions above, which stay relative to the published peak
+    mfma_bare = {"zero_operands_tflops": mc.probe_mfma_tflops(0), "random_operands_tflops": mc.probe_mfma_tflops(1)}
+    if roof["bound"] == "mfma":
+        roof["frac_of_bare_mfma_loop_random_operands"] = roof["achieved"] / mfma_bare["random_operands_tflops"]
 
     value = flops / ms_step / 1e9
     out = {
@@ -424,6 +429,7 @@ def main():
         "swap_budget_sweep": sweep,
         "kernels": [{k: (round(v, 4) if isinstance(v, float) else v) for k, v in r.items() if k not in ("flop", "bytes")} for r in per],
         "roofline": roof,
+        "mfma_bare_loop": mfma_bare,
     }
     if not args.no_unet_step:
         torch.cuda.empty_cache()

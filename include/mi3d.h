@@ -219,6 +219,14 @@ int mi3d_sgd_update(float *w, const float *dw, void *w_bf16, size_t n, float lr,
 int mi3d_adam_update(float *w, const float *dw, float *m, float *v, void *w_bf16, size_t n, float lr, float beta1,
                      float beta2, float eps, int step, void *stream);
 
+/* Diagnostic for the measurement side: enqueues a bare loop of bf16 32x32x16 MFMA instructions with operands in
+ * registers (one workgroup of four waves per CU, 12 x iters instructions per wave) and stores in *flop the floating
+ * point operations it performs; the caller times the stream.  random_operands = 0: all-zero operands; 1: a fixed
+ * pseudo-random pattern in (-2, 2).  The matrix cores' sustained rate depends on the operands (power), which is why
+ * the convolution kernels are compared with both.  ws: device scratch of mi3d_probe_mfma_workspace_bytes() bytes. */
+size_t mi3d_probe_mfma_workspace_bytes(void);
+int mi3d_probe_mfma(int random_operands, int iters, void *ws, size_t ws_bytes, double *flop, void *stream);
+
 /* ------------------------------------------------------------------------ */
 /* Data-swapping engine                                                     */
 /* ------------------------------------------------------------------------ */

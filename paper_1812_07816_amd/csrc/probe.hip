@@ -1,0 +1,72 @@
+// Diagnostic: the rate of a bare v_mfma_f32_32x32x16_bf16 loop on this device, with operands held in registers.
+// The MFMA-bound convolution kernels are limited by power, and the power of an MFMA depends on its operands: with
+// all-zero operands the loop reaches the published dense peak, with random operands about 70 % of it.  bench.py
+// reports both next to the convolution kernels' rates, so that their distance from what the matrix cores sustain
+// on real data can be told from their distance from the published peak.
+#include "mi3d_internal.h"
+
+namespace mi3d {
+namespace {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+
+// 4 waves per workgroup, one workgroup per CU; each wave keeps 12 independent accumulators (as the plane-streaming
+// convolution does) and four A and four B fragments loaded once from `in` (4096 16-byte pieces).
+__global__ void __launch_bounds__(256, 1) mfma_rate_kernel(const uint4* __restrict__ in, float* __restrict__ out, int iters) {
+    bf16x8 a[4], b[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        a[i] = __builtin_bit_cast(bf16x8, in[(threadIdx.x * 8 + i) & 4095]);
+        b[i] = __builtin_bit_cast(bf16x8, in[(threadIdx.x * 8 + 4 + i) & 4095]);
+    }
+    f32x16 acc[12];
+#pragma unroll
+    for (int k = 0; k < 12; ++k)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) acc[k][j] = 0.f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int k = 0; k < 12; ++k) acc[k] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[k & 3], b[(k + 1) & 3], acc[k], 0, 0, 0);
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int k = 0; k < 12; ++k)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) s += acc[k][j];
+    out[blockIdx.x * 256 + threadIdx.x] = s;
+}
+
+// bf16 operands: zeros, or a fixed pseudo-random pattern of values in (-2, 2) (an LCG over the piece index)
+__global__ void __launch_bounds__(256) mfma_fill_kernel(uint16_t* __restrict__ in, int random_operands) {
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    uint32_t x = (uint32_t)i * 1664525u + 1013904223u;
+    x ^= x >> 15; x *= 2246822519u; x ^= x >> 13;
+    const float f = ((int)(x % 4001u) - 2000) / 1000.f;
+    in[i] = random_operands ? (uint16_t)(__float_as_uint(f) >> 16) : (uint16_t)0;
+}
+
+}  // namespace
+}  // namespace mi3d
+
+using namespace mi3d;
+
+extern "C" {
+
+size_t mi3d_probe_mfma_workspace_bytes(void) { return 65536 + 1024 * 256 * sizeof(float); }
+
+int mi3d_probe_mfma(int random_operands, int iters, void* ws, size_t ws_bytes, double* flop, void* stream) {
+    if (!ws || !flop || iters <= 0 || ((uintptr_t)ws & 15)) return MI3D_ERR_INVALID_ARG;
+    if (ws_bytes < mi3d_probe_mfma_workspace_bytes()) return MI3D_ERR_WORKSPACE;
+    int dev = 0, cus = 256;
+    if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+    if (cus > 1024) cus = 1024;
+    mfma_fill_kernel<<<128, 256, 0, (hipStream_t)stream>>>((uint16_t*)ws, random_operands ? 1 : 0);
+    int st = check_launch();
+    if (st) return st;
+    mfma_rate_kernel<<<cus, 256, 0, (hipStream_t)stream>>>((const uint4*)ws, (float*)((char*)ws + 65536), iters);
+    *flop = 2.0 * 32 * 32 * 16 * 12.0 * (double)iters * 4.0 * cus;
+    return check_launch();
+}
+
+}  // extern "C"
