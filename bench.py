@@ -260,6 +260,9 @@ def main():
                     help="first run three 256 MiB device-to-device copies: dispatches of known size against which "
                          "rocprofv3's FETCH_SIZE / WRITE_SIZE readings are scaled")
     ap.add_argument("--no-unet-step", action="store_true", help="skip the full N=2 U-Net training step (adds ~40 s)")
+    ap.add_argument("--unet-step-only", action="store_true",
+                    help="run only the plain (unswapped, SGD) N=2 U-Net training step --steps times after --warmup and print its "
+                         "time: the command the per-kernel profile of the whole step is taken with")
     ap.add_argument("--unet-layers", action="store_true",
                     help="also time fwd/dgrad/wgrad of every Conv3D layer of the 5-level U-Net at 192^3 (adds ~20 s)")
     args = ap.parse_args()
@@ -275,6 +278,24 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
+    if args.unet_step_only:
+        from paper_1812_07816_amd import unet
+        ch = [32, 64, 128, 256, 320]
+        x = si.normal(5, 0, (2, 192, 192, 192, 4), bf16=True)
+        labels = torch.from_numpy(si.ellipsoid_labels(5, 1, 2, 192)).cuda()
+        xd = torch.from_numpy(si.bf16_bits(x).view(np.int16)).cuda().view(torch.bfloat16).reshape(x.shape)
+        step = unet.UNetStep(2, 192, ch, si.unet_weights(5, ch), xd, labels, swap=False)
+        for _ in range(args.warmup):
+            step.run()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step.run()
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / args.steps
+        print(json.dumps({"metric": "5-level 3D U-Net training step at 192^3, N=2 (unswapped, SGD)", "ms_per_step": ms, "steps": args.steps,
+                          "warmup": args.warmup, "conv_tflops": step.flops / ms / 1e9, "loss": float(step.loss.item())}))
+        return
     vol, N = args.vol, 1
     if args.copy_calibration:
         src = torch.full((64 << 20,), 1.0, dtype=torch.float32, device="cuda")

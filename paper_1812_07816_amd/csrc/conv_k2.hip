@@ -368,8 +368,7 @@ static int k2_wgrad(const Geom& g, const void* x, const void* dy, float* dw, voi
     int st = check_launch();
     if (st) return st;
     const long long n = g.w_elems();
-    reduce_partials_kernel<<<(unsigned)((n + 15) / 16), 256, 0, s>>>((const float*)ws, dw, n, P.slots);
-    return check_launch();
+    return reduce_partials((const float*)ws, dw, n, P.slots, s);
 }
 
 int k2_conv(const Geom& g, int pass, const void* a, const void* w, void* out, void* ws, size_t ws_bytes, hipStream_t s) {

@@ -156,8 +156,7 @@ static int pw_run(const Geom& g, int pass, const void* a, const void* b, void* o
     int st = check_launch();
     if (st) return st;
     const long long n = (long long)g.Cout * g.Cin;
-    reduce_partials_kernel<<<(unsigned)((n + 15) / 16), 256, 0, s>>>((const float*)ws, (float*)out, n, blocks);
-    return check_launch();
+    return reduce_partials((const float*)ws, (float*)out, n, blocks, s);
 }
 
 // fwd: a = x, b = w, out = y.  dgrad: a = dy, b = w, out = dx.  wgrad: a = x, b = dy, out = dw.

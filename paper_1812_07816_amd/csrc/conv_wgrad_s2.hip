@@ -346,8 +346,7 @@ int wgrad_s2(const Geom& g, const void* x, const void* dy, float* dw, void* ws, 
     int st = check_launch();
     if (st) return st;
     long long n = g.w_elems();
-    reduce_partials_kernel<<<(unsigned)((n + 15) / 16), 256, 0, s>>>((const float*)ws, dw, n, P.slots);
-    return check_launch();
+    return reduce_partials((const float*)ws, dw, n, P.slots, s);
 }
 
 }  // namespace mi3d

@@ -56,6 +56,8 @@ int direct_wgrad(const Geom& g, const void* x, const void* dy, float* dw, void* 
 __global__ void sum_chunks_bf16_kernel(const float* __restrict__ part, uint16_t* __restrict__ y, long long n8, long long n, int nch,
                                        float slope, const uint16_t* __restrict__ ref);
 __global__ void reduce_partials_kernel(const float* __restrict__ part, float* __restrict__ out, long long n, int parts);
+// out[i] = sum_p part[p * n + i] in an order fixed by (n, parts); picks the kernel by the number of parts
+int reduce_partials(const float* part, float* out, long long n, int parts, hipStream_t s);
 
 
 // plane-streaming MFMA kernel: bf16, 3x3x3, stride 1 (forward and data gradient)
