@@ -118,6 +118,23 @@ int mi3d_conv3d_dgrad_view(const mi3d_conv_desc *desc, const void *dy, const voi
 int mi3d_conv3d_wgrad_view(const mi3d_conv_desc *desc, const void *x, const mi3d_view *xv, const void *dy, float *dw,
                            void *ws, size_t ws_bytes, void *stream);
 
+/* Virtual concatenation for the decoder's first convolution of a level (Section 4.1: the up-sampled map is
+ * concatenated with the skip connection and convolved).  The tensor of x's shape is given as two tensors of
+ * Cin / 2 channels each, [x_lo | x_hi] along the channels, and is never materialised: the forward pass and the
+ * weight gradient read the two halves, the data gradient writes the two halves of dx (both fully overwritten).
+ * The results are those of the plain calls on the concatenated tensor, bit for bit.  `slope` of the forward call:
+ * LeakyReLU applied to y as in mi3d_conv3d_fwd_lrelu, 1 = none.  Only the bf16 3x3x3 stride-1 MFMA kernels take
+ * halves (Cin % 64 == 0, Cout % 32 == 0, pads <= 2); any other geometry returns MI3D_ERR_UNSUPPORTED, and
+ * mi3d_conv3d_pair_supported tells beforehand (1 / 0).  Workspace as for the plain call of the same pass; all
+ * pointers device, 16-byte aligned. */
+int mi3d_conv3d_pair_supported(const mi3d_conv_desc *desc, int pass);
+int mi3d_conv3d_fwd_pair(const mi3d_conv_desc *desc, const void *x_lo, const void *x_hi, const void *w, void *y,
+                         float slope, void *ws, size_t ws_bytes, void *stream);
+int mi3d_conv3d_dgrad_pair(const mi3d_conv_desc *desc, const void *dy, const void *w, void *dx_lo, void *dx_hi,
+                           void *ws, size_t ws_bytes, void *stream);
+int mi3d_conv3d_wgrad_pair(const mi3d_conv_desc *desc, const void *x_lo, const void *x_hi, const void *dy, float *dw,
+                           void *ws, size_t ws_bytes, void *stream);
+
 /* Convolution followed by the network's LeakyReLU (Section 4.1) in one call:
  * y = lrelu(conv(x, w)), lrelu(v) = v > 0 ? v : slope * v, applied to the fp32
  * accumulator before the single rounding to bf16.  bf16 only, 0 <= slope < 1

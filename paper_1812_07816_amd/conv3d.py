@@ -158,6 +158,60 @@ def conv3d_wgrad_view(desc, x_wide, offset, dy, dw=None, ws=None):
     return dw
 
 
+def pair_supported(desc, pass_):
+    """True if the pass takes the tensor of x's shape as two halves along the channels (conv3d_*_pair)."""
+    return bool(lib().mi3d_conv3d_pair_supported(ctypes.byref(desc), int(pass_)))
+
+
+def _half(desc):
+    xs, _, _ = _shapes(desc)
+    return xs[:-1] + (desc.Cin // 2,)
+
+
+def conv3d_fwd_pair(desc, x_lo, x_hi, w, slope=1.0, y=None, ws=None):
+    """conv3d_fwd over the channel concatenation [x_lo | x_hi] (never materialised); slope != 1: LeakyReLU on y."""
+    _, wsh, ys = _shapes(desc)
+    dt = _tdtype(desc)
+    _chk(x_lo, _half(desc), dt, "x_lo"); _chk(x_hi, _half(desc), dt, "x_hi"); _chk(w, wsh, dt, "w")
+    if y is None:
+        y = torch.empty(ys, dtype=dt, device=x_lo.device)
+    _chk(y, ys, dt, "y")
+    ws, p, n = _ws(desc, PASS_FWD, ws)
+    check(lib().mi3d_conv3d_fwd_pair(ctypes.byref(desc), x_lo.data_ptr(), x_hi.data_ptr(), w.data_ptr(), y.data_ptr(),
+                                     ctypes.c_float(slope), p, n, _stream()), "conv3d_fwd_pair")
+    return y
+
+
+def conv3d_dgrad_pair(desc, dy, w, dx_lo=None, dx_hi=None, ws=None):
+    """conv3d_dgrad that writes the two channel halves of dx to separate tensors."""
+    _, wsh, ys = _shapes(desc)
+    dt = _tdtype(desc)
+    _chk(dy, ys, dt, "dy"); _chk(w, wsh, dt, "w")
+    if dx_lo is None:
+        dx_lo = torch.empty(_half(desc), dtype=dt, device=dy.device)
+    if dx_hi is None:
+        dx_hi = torch.empty(_half(desc), dtype=dt, device=dy.device)
+    _chk(dx_lo, _half(desc), dt, "dx_lo"); _chk(dx_hi, _half(desc), dt, "dx_hi")
+    ws, p, n = _ws(desc, PASS_DGRAD, ws)
+    check(lib().mi3d_conv3d_dgrad_pair(ctypes.byref(desc), dy.data_ptr(), w.data_ptr(), dx_lo.data_ptr(), dx_hi.data_ptr(),
+                                       p, n, _stream()), "conv3d_dgrad_pair")
+    return dx_lo, dx_hi
+
+
+def conv3d_wgrad_pair(desc, x_lo, x_hi, dy, dw=None, ws=None):
+    """conv3d_wgrad whose x is the channel concatenation [x_lo | x_hi] (never materialised)."""
+    _, wsh, ys = _shapes(desc)
+    dt = _tdtype(desc)
+    _chk(x_lo, _half(desc), dt, "x_lo"); _chk(x_hi, _half(desc), dt, "x_hi"); _chk(dy, ys, dt, "dy")
+    if dw is None:
+        dw = torch.empty(wsh, dtype=torch.float32, device=dy.device)
+    _chk(dw, wsh, torch.float32, "dw")
+    ws, p, n = _ws(desc, PASS_WGRAD, ws)
+    check(lib().mi3d_conv3d_wgrad_pair(ctypes.byref(desc), x_lo.data_ptr(), x_hi.data_ptr(), dy.data_ptr(), dw.data_ptr(),
+                                       p, n, _stream()), "conv3d_wgrad_pair")
+    return dw
+
+
 def conv3d_fwd_lrelu(desc, x, w, slope, y=None, ws=None):
     """y = LeakyReLU(conv(x, w)) in one call."""
     xs, wsh, ys = _shapes(desc)

@@ -136,6 +136,13 @@ static bool fuses_epilogue(Kernel k, const Geom& g, int pass) {
     return false;
 }
 
+// the kernels that take the tensor of x's shape as two halves along the channels
+static bool pair_supported(const Geom& g, int pass) {
+    if (g_family.load() == 1 || g.Cin % 64) return false;
+    const Kernel k = choose(g, pass);
+    return pass == MI3D_PASS_WGRAD ? k == K_WGRAD_MFMA : k == K_SP;
+}
+
 // automatic choice for a geometry, used by the entry points and by fallbacks that re-enter with a derived geometry
 size_t auto_workspace_bytes(const Geom& g, int pass) { return kernel_workspace(choose(g, pass), g, pass); }
 int auto_conv(const Geom& g, int pass, const void* a, const void* b, void* out, void* ws, size_t ws_bytes, hipStream_t s) {
@@ -198,10 +205,15 @@ size_t mi3d_conv3d_workspace_bytes(const mi3d_conv_desc* desc, int pass) {
 
 // slope / ref: optional LeakyReLU epilogue (forward: on y; data gradient: derivative factor from ref), 1 / null = none
 static int conv_entry(const mi3d_conv_desc* desc, int pass, const void* a, const void* b, void* out, void* ws, size_t ws_bytes, void* stream,
-                      float slope = 1.f, const void* ref = nullptr, const mi3d_view* xv = nullptr) {
+                      float slope = 1.f, const void* ref = nullptr, const mi3d_view* xv = nullptr, const void* hi = nullptr, bool pair = false) {
     Geom g;
     int st = make_geom(desc, &g);
     if (st) return st;
+    if (pair) {   // the tensor of x's shape comes as two halves along the channels
+        if (!hi || !aligned16(hi)) return MI3D_ERR_INVALID_ARG;
+        if (!pair_supported(g, pass)) return MI3D_ERR_UNSUPPORTED;
+        g.hi = hi;
+    }
     if (xv && xv->pitch) {   // the tensor of x's shape is a channel range of a wider tensor
         if (xv->pitch < 0 || xv->offset < 0 || xv->offset + g.Cin > xv->pitch || xv->pitch % 8 || xv->offset % 8) return MI3D_ERR_INVALID_ARG;
         if (g_family.load() == 1 || choose(g, pass) != K_K2) return MI3D_ERR_UNSUPPORTED;
@@ -250,6 +262,27 @@ int mi3d_conv3d_dgrad_view(const mi3d_conv_desc* desc, const void* dy, const voi
 
 int mi3d_conv3d_wgrad_view(const mi3d_conv_desc* desc, const void* x, const mi3d_view* xv, const void* dy, float* dw, void* ws, size_t ws_bytes, void* stream) {
     return conv_entry(desc, MI3D_PASS_WGRAD, x, dy, dw, ws, ws_bytes, stream, 1.f, nullptr, xv);
+}
+
+int mi3d_conv3d_pair_supported(const mi3d_conv_desc* desc, int pass) {
+    Geom g;
+    if (make_geom(desc, &g) || pass < 0 || pass > 2) return 0;
+    return pair_supported(g, pass) ? 1 : 0;
+}
+
+int mi3d_conv3d_fwd_pair(const mi3d_conv_desc* desc, const void* x_lo, const void* x_hi, const void* w, void* y, float slope,
+                         void* ws, size_t ws_bytes, void* stream) {
+    return conv_entry(desc, MI3D_PASS_FWD, x_lo, w, y, ws, ws_bytes, stream, slope, nullptr, nullptr, x_hi, true);
+}
+
+int mi3d_conv3d_dgrad_pair(const mi3d_conv_desc* desc, const void* dy, const void* w, void* dx_lo, void* dx_hi,
+                           void* ws, size_t ws_bytes, void* stream) {
+    return conv_entry(desc, MI3D_PASS_DGRAD, dy, w, dx_lo, ws, ws_bytes, stream, 1.f, nullptr, nullptr, dx_hi, true);
+}
+
+int mi3d_conv3d_wgrad_pair(const mi3d_conv_desc* desc, const void* x_lo, const void* x_hi, const void* dy, float* dw,
+                           void* ws, size_t ws_bytes, void* stream) {
+    return conv_entry(desc, MI3D_PASS_WGRAD, x_lo, dy, dw, ws, ws_bytes, stream, 1.f, nullptr, nullptr, x_hi, true);
 }
 
 int mi3d_conv3d_fwd_lrelu(const mi3d_conv_desc* desc, const void* x, const void* w, void* y, float slope, void* ws, size_t ws_bytes, void* stream) {

@@ -57,8 +57,8 @@ __global__ void __launch_bounds__(256, 2) c4_fwd_kernel(C4Params P) {
     char* stg = lds + SLOTS * PLANE * 8 + 1024 + wave * RH * 2048;  // this wave's store staging: RH rows x 32 voxels x 64 B
     // Work split.  With at least as many workgroups as patch columns, workgroup g takes column g % columns and
     // the g / columns-th of S equal D segments: workgroups that run side by side then write neighbouring patches of
-    // the same few planes (one workgroup per contiguous range of tiles, each in a plane of its own, measured 25 %
-    // slower: the stores of the whole chip were spread over 500 distant 2 KB rows).  Otherwise contiguous ranges.
+    // the same few planes, and every workgroup streams along D for its whole range so the ring of staged planes is
+    // primed once.  Otherwise contiguous ranges of tiles.
     long long u, u1;
     const long long columns = P.tiles / P.Do;
     if (P.nwg >= columns) {

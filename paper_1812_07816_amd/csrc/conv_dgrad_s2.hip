@@ -380,7 +380,7 @@ int dgrad_s2(const Geom& g, const void* dy, const void* w, void* dx, void* ws, s
     const long long n = (long long)g.in_voxels() * g.Cin;
     long long blocks = (n / 8 + 255) / 256;
     if (blocks > 8192) blocks = 8192;
-    sum_chunks_bf16_kernel<<<(unsigned)blocks, 256, 0, s>>>(G.part, (uint16_t*)dx, n / 8, n, G.NCO, g.slope, (const uint16_t*)g.ref);
+    sum_chunks_bf16_kernel<<<(unsigned)blocks, 256, 0, s>>>(G.part, (uint16_t*)dx, n / 8, n, G.NCO, g.slope, (const uint16_t*)g.ref, nullptr, 0);
     return check_launch();
 }
 

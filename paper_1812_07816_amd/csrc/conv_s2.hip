@@ -320,7 +320,7 @@ __global__ void __launch_bounds__(256) s2_pack_weights_kernel(const uint16_t* __
 // act: LeakyReLU with `slope` (1 = none) if ref is null; otherwise the factor of element i is 1 where
 // ref[i] > 0 and `slope` elsewhere (LeakyReLU derivative taken from the activated tensor ref).
 __global__ void __launch_bounds__(256) sum_chunks_bf16_kernel(const float* __restrict__ part, uint16_t* __restrict__ y, long long n8, long long n, int nch,
-                                                              float slope, const uint16_t* __restrict__ ref) {
+                                                              float slope, const uint16_t* __restrict__ ref, uint16_t* __restrict__ y_hi, int cout) {
     typedef __attribute__((__vector_size__(2 * sizeof(float)))) float f32x2_;
     typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2_;
     for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < n8; i += (long long)gridDim.x * 256) {
@@ -349,7 +349,13 @@ __global__ void __launch_bounds__(256) sum_chunks_bf16_kernel(const float* __res
             f32x2_ v = {a[2 * j], a[2 * j + 1]};
             o[j] = __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_));
         }
-        *(uint4*)(y + 8 * i) = uint4{o[0], o[1], o[2], o[3]};
+        uint16_t* dst = y + 8 * i;
+        if (y_hi) {   // output in two halves of cout / 2 channels per voxel
+            const long long vox = 8 * i / cout;
+            const int c = (int)(8 * i - vox * cout), half = cout >> 1;
+            dst = (c >= half ? y_hi - half : y) + vox * half + c;
+        }
+        *(uint4*)dst = uint4{o[0], o[1], o[2], o[3]};
     }
 }
 
@@ -413,7 +419,7 @@ int s2_fwd(const Geom& g, const void* x, const void* w, void* y, void* ws, size_
     const long long n = (long long)g.out_voxels() * g.Cout;   // Cout % 32 == 0: a multiple of 8
     long long blocks = (n / 8 + 255) / 256;
     if (blocks > 8192) blocks = 8192;
-    sum_chunks_bf16_kernel<<<(unsigned)blocks, 256, 0, s>>>(P.part, (uint16_t*)y, n / 8, n, P.NCH, g.slope, nullptr);
+    sum_chunks_bf16_kernel<<<(unsigned)blocks, 256, 0, s>>>(P.part, (uint16_t*)y, n / 8, n, P.NCH, g.slope, nullptr, nullptr, 0);
     return check_launch();
 }
 

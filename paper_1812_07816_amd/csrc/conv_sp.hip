@@ -45,6 +45,12 @@ struct SpParams {
     const uint16_t* ref;    // MASK variant: tensor of the output's shape whose sign selects the factor 1 or slope
     int N, D, H, W, Cin, Cout, Do, Ho, Wo, pD, pH, pW;
     int HT, WT, CT;         // tiles per plane, cout tiles
+    // Tensors given as two halves along the channels (virtual concatenation): chunks >= xsplit of the input come
+    // from x2, cout tiles >= ysplit of the output go to y2; xpitch / ypitch are the channels per voxel of the
+    // tensors in memory (Cin, Cout when not split; then the split indices lie beyond the last chunk / tile).
+    const uint16_t* x2;
+    uint16_t* y2;
+    int xpitch, ypitch, xsplit, ysplit;
     long long units;        // N*CT*HT*WT*Do
     int nwg;
 };
@@ -320,13 +326,16 @@ __global__ void __launch_bounds__(256, 1) sp_conv_kernel(SpParams P) {
             }
             const int gh = h0 - P.pH + row, gw = w0 - P.pW + col;
             ok = ok && gh >= 0 && gh < P.H && gw >= 0 && gw < P.W;
-            if (DMA) goff[i] = ok ? ((gh * P.W + gw) * P.Cin + c * 8) * 2 : (int)OOB;
-            else goff[i] = ok ? (gh * P.W + gw) * P.Cin + c * 8 : 0;
+            if (DMA) goff[i] = ok ? ((gh * P.W + gw) * P.xpitch + c * 8) * 2 : (int)OOB;
+            else goff[i] = ok ? (gh * P.W + gw) * P.xpitch + c * 8 : 0;
             valid |= (ok ? 1u : 0u) << i;
         }
-        const long long plane_elems = (long long)P.H * P.W * P.Cin;
+        const long long plane_elems = (long long)P.H * P.W * P.xpitch;
         const uint16_t* xn = P.x + (long long)n * P.D * plane_elems;
-        uint16_t* yn = P.y + (long long)n * P.Do * P.Ho * P.Wo * P.Cout;
+        const uint16_t* xn2 = P.x2 + (long long)n * P.D * plane_elems;
+        const int ct_local = ct >= P.ysplit ? ct - P.ysplit : ct;
+        uint16_t* yn = (ct >= P.ysplit ? P.y2 : P.y) + (long long)n * P.Do * P.Ho * P.Wo * P.ypitch;
+        const int opitch = PART ? P.Cout : P.ypitch;   // the fp32 partial outputs are dense
         const int nJ = od_end - od_start + 2;
         uint4 pre[DMA ? 1 : NLOAD];
 
@@ -339,7 +348,9 @@ __global__ void __launch_bounds__(256, 1) sp_conv_kernel(SpParams P) {
         auto begin_stage = [&](int ip, int chunk) {
             const bool inside = ip >= 0 && ip < P.D;
             chunk += chunk0;
-            pre_base = xn + (long long)(inside ? ip : 0) * plane_elems + chunk * 32;
+            const bool high = chunk >= P.xsplit;
+            if (high) chunk -= P.xsplit;
+            pre_base = (high ? xn2 : xn) + (long long)(inside ? ip : 0) * plane_elems + chunk * 32;
             pre_mask = inside ? valid : 0u;
             if (DMA) rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)pre_base, 0, inside ? (int)(plane_elems * 2) - chunk * 64 : 0, 0x00020000);
         };
@@ -374,7 +385,7 @@ __global__ void __launch_bounds__(256, 1) sp_conv_kernel(SpParams P) {
         float* partn = PART ? P.part + ((long long)chunk0 * P.N + n) * P.Do * P.Ho * P.Wo * P.Cout : nullptr;
         bool st_pending = false;
         const int ow_ = w0 + (lane & 31);
-        const long long row_pitch = (long long)P.Wo * P.Cout;
+        const long long row_pitch = (long long)P.Wo * opitch;
         uint4 mk[MASK ? RH : 1][2];   // MASK: the pieces of ref at the addresses of the pending stores
         const uint16_t* refn = MASK ? P.ref + (long long)n * P.Do * P.Ho * P.Wo * P.Cout : nullptr;
         auto load_mask = [&](int r) {     // unconditional, like the stores: masked lanes read the dump area
@@ -446,7 +457,7 @@ __global__ void __launch_bounds__(256, 1) sp_conv_kernel(SpParams P) {
             write_stage(NBUF == 2 ? ((sq + 1) & 1) : 0);                                        \
             if (LAST) {                                                                         \
                 st_pending = jj >= 2;                                                           \
-                st_off = (((long long)(j_ - 2) * P.Ho + h0 + wave * RH) * P.Wo + ow_) * P.Cout + ct * 32;  \
+                st_off = (((long long)(j_ - 2) * P.Ho + h0 + wave * RH) * P.Wo + ow_) * opitch + (PART ? ct : ct_local) * 32;  \
             }                                                                                   \
             ++sq;                                                                               \
             /* the ten loads into the next stage are complete; the eight stores issued after them may still fly */ \
@@ -583,6 +594,13 @@ int sp_conv(const Geom& g, int pass, const void* in, const void* w, void* out, v
     P.HT = (P.Ho + TH - 1) / TH;
     P.WT = (P.Wo + TW - 1) / TW;
     P.CT = P.Cout / 32;
+    // halves along the channels of the tensor of x's shape: the input of the forward pass, the output of the data gradient
+    P.x2 = P.x; P.y2 = P.y; P.xpitch = P.Cin; P.ypitch = P.Cout; P.xsplit = P.Cin; P.ysplit = P.Cout;
+    if (g.hi) {
+        if (g.Cin % 64) return MI3D_ERR_UNSUPPORTED;
+        if (!flip) { P.x2 = (const uint16_t*)g.hi; P.xpitch = g.Cin / 2; P.xsplit = g.Cin / 64; }
+        else { P.y2 = (uint16_t*)g.hi; P.ypitch = g.Cin / 2; P.ysplit = g.Cin / 64; }
+    }
     const bool chunks = sp_use_chunks(g, pass);
     P.NCH = chunks ? P.Cin / 32 : 1;
     const bool mask = pass == MI3D_PASS_DGRAD && g.ref && g.slope != 1.f && !chunks && P.Cin == 32;
@@ -611,7 +629,8 @@ int sp_conv(const Geom& g, int pass, const void* in, const void* w, void* out, v
         const long long n = (long long)P.N * P.Do * P.Ho * P.Wo * P.Cout;   // a multiple of 32
         long long blocks = (n / 8 + 255) / 256;
         if (blocks > 8192) blocks = 8192;
-        sum_chunks_bf16_kernel<<<(unsigned)blocks, 256, 0, s>>>(P.part, (uint16_t*)out, n / 8, n, P.NCH, g.slope, pass == MI3D_PASS_DGRAD ? (const uint16_t*)g.ref : nullptr);
+        sum_chunks_bf16_kernel<<<(unsigned)blocks, 256, 0, s>>>(P.part, (uint16_t*)out, n / 8, n, P.NCH, g.slope, pass == MI3D_PASS_DGRAD ? (const uint16_t*)g.ref : nullptr,
+                                                                flip && g.hi ? (uint16_t*)g.hi : nullptr, P.Cout);
         return check_launch();
     }
     if (mask) sp_conv_kernel<1, false, true><<<(unsigned)nwg, 256, lds1, s>>>(P);

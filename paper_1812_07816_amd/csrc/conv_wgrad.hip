@@ -48,6 +48,10 @@ struct WgParams {
     int HT, WT, CiT, CoT;
     long long units;        // per pair: N*HT*WT*D
     int slots;              // workgroups per pair
+    // x given as two halves along the channels (virtual concatenation): cin tiles >= xsplit come from x2; xpitch is
+    // the channels per voxel of x in memory (Cin when not split; then xsplit lies beyond the last tile)
+    const uint16_t* x2;
+    int xpitch, xsplit;
 };
 
 __device__ __forceinline__ bf16x8 tr_frag(const char* p) {
@@ -147,7 +151,9 @@ __global__ void __launch_bounds__(256, 1) wgrad_kernel(WgParams P) {
 #pragma unroll
             for (int c = 0; c < 3; ++c) acc[a][b][c] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    const long long x_plane = (long long)P.H * P.W * P.Cin;
+    const long long x_plane = (long long)P.H * P.W * P.xpitch;
+    const bool x_high = cit >= P.xsplit;
+    const int cit_local = x_high ? cit - P.xsplit : cit;
     const long long dy_plane = (long long)P.Ho * P.Wo * P.Cout;
 
     while (u0 < u1) {
@@ -170,7 +176,7 @@ __global__ void __launch_bounds__(256, 1) wgrad_kernel(WgParams P) {
             int row = (v * 241) >> 13, col = v - row * XC;  // v / 34
             int gh = h0 - P.pH + row, gw = w0 - P.pW + col;
             bool ok = q < XPIECES && gh >= 0 && gh < P.H && gw >= 0 && gw < P.W;
-            gx[i] = ok ? (gh * P.W + gw) * P.Cin + cit * 32 + c * 8 : 0;
+            gx[i] = ok ? (gh * P.W + gw) * P.xpitch + cit_local * 32 + c * 8 : 0;
             vx |= (ok ? 1u : 0u) << i;
         }
 #pragma unroll
@@ -182,7 +188,7 @@ __global__ void __launch_bounds__(256, 1) wgrad_kernel(WgParams P) {
             gdy[i] = ok ? (gh * P.Wo + gw) * P.Cout + cot * 32 + c * 8 : 0;
             vdy |= (ok ? 1u : 0u) << i;
         }
-        const uint16_t* xn = P.x + (long long)n * P.D * x_plane;
+        const uint16_t* xn = (x_high ? P.x2 : P.x) + (long long)n * P.D * x_plane;
         const uint16_t* dyn = P.dy + (long long)n * P.Do * dy_plane;
 
         uint4 px[NX], pdy[NDY];
@@ -317,6 +323,11 @@ int wgrad_mfma(const Geom& g, const void* x, const void* dy, float* dw, void* ws
     P.CoT = g.Cout / 32;
     P.units = (long long)g.N * P.HT * P.WT * g.D;
     P.slots = wgrad_slots(g);
+    P.x2 = P.x; P.xpitch = g.Cin; P.xsplit = P.CiT;
+    if (g.hi) {
+        if (g.Cin % 64) return MI3D_ERR_UNSUPPORTED;
+        P.x2 = (const uint16_t*)g.hi; P.xpitch = g.Cin / 2; P.xsplit = P.CiT / 2;
+    }
     const int pairs = P.CiT * P.CoT;
     if (pairs > 65535) return MI3D_ERR_UNSUPPORTED;
     size_t lds = X_BYTES + 3 * DY_BYTES;

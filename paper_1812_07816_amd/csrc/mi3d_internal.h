@@ -24,6 +24,10 @@ struct Geom {
     // the data gradient): it lives in a tensor with x_pitch channels per voxel, starting at channel x_off
     // (x_pitch = 0: dense).  Set by the dispatcher only for kernels that implement it.
     int x_pitch = 0, x_off = 0;
+    // Optional virtual concatenation: the tensor of x's shape is given as two tensors of Cin / 2 channels each, the
+    // pointer of the call being the low half and `hi` the high half.  Set by the dispatcher only for kernels that
+    // implement it.
+    const void* hi = nullptr;
     __host__ __device__ long long in_voxels() const { return (long long)N * D * H * W; }
     __host__ __device__ long long out_voxels() const { return (long long)N * Do * Ho * Wo; }
     __host__ __device__ long long taps() const { return (long long)kD * kH * kW; }
@@ -52,9 +56,10 @@ int direct_dgrad(const Geom& g, const void* dy, const void* w, void* dx, hipStre
 int direct_wgrad(const Geom& g, const void* x, const void* dy, float* dw, void* ws, size_t ws_bytes, hipStream_t s);
 // out[i] = sum_p part[p*n + i] in a fixed order (bit-reproducible); launch with (n + 15) / 16 blocks of 256
 // y[i] = bf16(act(sum_c part[c * n + i])), chunks added in index order; n8 = n / 8 outputs of 8; act = LeakyReLU with
-// `slope` (ref null) or the factor (ref[i] > 0 ? 1 : slope)
+// `slope` (ref null) or the factor (ref[i] > 0 ? 1 : slope).  y_hi non-null: the output, `cout` channels per voxel, is
+// written as two tensors of cout / 2 channels per voxel (y the low half, y_hi the high half); cout / 2 % 8 == 0
 __global__ void sum_chunks_bf16_kernel(const float* __restrict__ part, uint16_t* __restrict__ y, long long n8, long long n, int nch,
-                                       float slope, const uint16_t* __restrict__ ref);
+                                       float slope, const uint16_t* __restrict__ ref, uint16_t* __restrict__ y_hi, int cout);
 __global__ void reduce_partials_kernel(const float* __restrict__ part, float* __restrict__ out, long long n, int parts);
 // out[i] = sum_p part[p * n + i] in an order fixed by (n, parts); picks the kernel by the number of parts
 int reduce_partials(const float* part, float* out, long long n, int parts, hipStream_t s);

@@ -1,0 +1,88 @@
+"""GPU-vs-oracle parity of the virtual-concatenation entry points (conv3d_fwd_pair, conv3d_dgrad_pair,
+conv3d_wgrad_pair): the decoder's first convolution of a level reads [up-sampled | skip] as two tensors.  The oracle
+side concatenates with numpy and runs the plain fp64 passes; the plain GPU calls on the materialised concatenation
+must give the same bits."""
+import ctypes
+
+import numpy as np
+import pytest
+import torch
+
+import synth_inputs as si
+from oracle import conv3d as oc
+from paper_1812_07816_amd import conv3d as mc
+from paper_1812_07816_amd._lib import Mi3dError, lib
+from tests import parity
+
+pytestmark = pytest.mark.gpu
+
+CASES = [
+    # N, D, H, W, Cin (both halves together), Cout, pad
+    (1, 6, 20, 40, 64, 32, 1),      # two resident weight chunks forward; one-chunk data gradient, two cout tiles
+    (2, 5, 18, 34, 128, 64, 1),     # streamed weights forward; ragged patch tails
+    (1, 7, 16, 32, 64, 64, 1),
+    (1, 12, 12, 12, 256, 128, 1),   # few units: chunked variants with fp32 partial sums in both passes
+    (1, 6, 10, 12, 512, 256, 1),
+    (1, 5, 17, 33, 64, 32, 0),      # no padding
+]
+
+
+@pytest.mark.parametrize("case", CASES)
+def test_pair_passes_match_oracle_on_the_concatenated_tensor(device, case):
+    N, D, H, W, Cin, Cout, p = case
+    seed = 10 * CASES.index(case)
+    x, w, dy = si.conv_case(95, seed, N, D, H, W, Cin, Cout, 3, 1, p, True)
+    g = oc.shape(N, D, H, W, Cin, Cout, 3, 1, p)
+    desc = mc.make_desc(N, D, H, W, Cin, Cout, 3, 1, p, torch.bfloat16)
+    for q in range(3):
+        assert mc.pair_supported(desc, q)
+    h = Cin // 2
+    xd, wd, dyd = parity.to_device(x, True), parity.to_device(w, True), parity.to_device(dy, True)
+    lo, hi = xd[..., :h].contiguous(), xd[..., h:].contiguous()
+    tol = parity.TOL["bf16"]
+
+    y = mc.conv3d_fwd_pair(desc, lo, hi, wd)
+    e_f = oc.rel_err(parity.to_host(y), oc.fwd(g, x, w))
+    assert torch.equal(y, mc.conv3d_fwd(desc, xd, wd))
+    ya = mc.conv3d_fwd_pair(desc, lo, hi, wd, slope=0.01)
+    assert torch.equal(ya, mc.conv3d_fwd_lrelu(desc, xd, wd, 0.01))
+
+    dw = mc.conv3d_wgrad_pair(desc, lo, hi, dyd)
+    e_w = oc.rel_err(parity.to_host(dw), oc.wgrad(g, x, dy))
+    assert torch.equal(dw, mc.conv3d_wgrad(desc, xd, dyd))
+
+    dlo = torch.full_like(lo, 7.0)
+    dhi = torch.full_like(hi, 7.0)
+    mc.conv3d_dgrad_pair(desc, dyd, wd, dlo, dhi)
+    dx = torch.cat([dlo, dhi], dim=-1)
+    e_d = oc.rel_err(parity.to_host(dx), oc.dgrad(g, dy, w))
+    assert torch.equal(dx, mc.conv3d_dgrad(desc, dyd, wd))
+    print(case, f"fwd {e_f:.2e} dgrad {e_d:.2e} wgrad {e_w:.2e}", flush=True)
+    assert e_f <= tol and e_d <= tol and e_w <= tol
+
+
+def test_pairs_are_refused_where_no_kernel_takes_them(device):
+    bf = torch.bfloat16
+    for args in ((1, 8, 8, 8, 96, 32, 3, 1, 1),       # halves of 48 channels
+                 (1, 8, 8, 8, 64, 32, 3, 2, 1),       # stride 2
+                 (1, 8, 8, 8, 64, 64, 2, 2, 0),       # up-sampling layer
+                 (1, 8, 8, 8, 64, 3, 1, 1, 0)):       # head
+        d = mc.make_desc(*args, bf)
+        assert not any(mc.pair_supported(d, q) for q in range(3)), args
+        N, D, H, W, Cin, Cout, k = args[:7]
+        lo = torch.zeros((N, D, H, W, Cin // 2), dtype=bf, device="cuda")
+        w = torch.zeros((Cout, k, k, k, Cin), dtype=bf, device="cuda")
+        with pytest.raises(Mi3dError):
+            mc.conv3d_fwd_pair(d, lo, lo, w)
+    d32 = mc.make_desc(1, 8, 8, 8, 64, 32, 3, 1, 1, torch.float32)
+    assert not mc.pair_supported(d32, 0)
+    # a missing or misaligned high half is an invalid argument
+    d = mc.make_desc(1, 8, 8, 8, 64, 32, 3, 1, 1, bf)
+    lo = torch.zeros((1, 8, 8, 8, 32), dtype=bf, device="cuda")
+    w = torch.zeros((32, 3, 3, 3, 64), dtype=bf, device="cuda")
+    y = torch.zeros((1, 8, 8, 8, 32), dtype=bf, device="cuda")
+    ws = torch.empty(mc.workspace_bytes(d, 0) + 16, dtype=torch.uint8, device="cuda")
+    for hi_ptr in (None, lo.data_ptr() + 2):
+        st = lib().mi3d_conv3d_fwd_pair(ctypes.byref(d), lo.data_ptr(), hi_ptr, w.data_ptr(), y.data_ptr(), ctypes.c_float(1.0),
+                                        ws.data_ptr(), ws.numel(), None)
+        assert st == -1, st
