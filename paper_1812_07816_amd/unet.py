@@ -47,7 +47,7 @@ class _Saved:
 class UNetStep:
     def __init__(self, N, vol, channels, weights, x, labels, lr=1e-2, in_ch=4, classes=3, swap=True,
                  budget_bytes=None, lookahead=2, policy=sw.POLICY_BUDGET, n_tensors=-1, exclude_tags=0,
-                 eviction=sw.EVICT_SWAP, optimizer="sgd", norm=False):
+                 eviction=sw.EVICT_SWAP, optimizer="sgd", norm=False, virtual_cat=True):
         """weights: list of float32 CPU tensors/arrays (bf16-exact start values) in the order enc convs,
         (dec up, conv1, conv2) from the deepest decoder level up, head; x: bf16 CUDA [N,vol,vol,vol,in_ch];
         labels: uint8 CUDA [N,vol,vol,vol,classes]."""
@@ -88,12 +88,14 @@ class UNetStep:
             self.saved.append(s)
             return s
 
-        def conv_op(name, src, vol_in, cin, cout, s, widx, tag, first=False):
+        def conv_op(name, src, vol_in, cin, cout, s, widx, tag, first=False, src2=None):
             d = mc.make_desc(N, vol_in, vol_in, vol_in, cin, cout, 3, s, 1, torch.bfloat16)
             vo = vol_in // s
             out = new_saved((N, vo, vo, vo, cout), tag)
             src.last_fwd = len(self.ops)
-            self.ops.append(dict(kind="conv", name=name, desc=d, src=src, out=out, w=widx, first=first))
+            if src2 is not None:     # the input is [src | src2] along the channels, never materialised
+                src2.last_fwd = len(self.ops)
+            self.ops.append(dict(kind="conv", name=name, desc=d, src=src, src2=src2, out=out, w=widx, first=first))
             fl = 2.0 * N * vo ** 3 * 27 * cin * cout
             self.flops += fl * (2 if first else 3)
             return out, vo
@@ -115,13 +117,26 @@ class UNetStep:
             # the up-sampling writes straight into its half of the concatenated tensor, and its backward passes read
             # their half of that tensor's gradient in place, where the library has the kernels for it
             in_place = all(mc.kernel_name(d, p) == "mfma_k2s2_panel_gemm" for p in range(3))
-            self.ops.append(dict(kind="up", name=f"dec{l}.up", desc=d, src=a, w=wi, shape=(N, v, v, v, ch[l]), in_place=in_place)); wi += 1
+            # Virtual concatenation: where the library's kernels take the two halves as separate tensors, the
+            # concatenated tensor and its gradient never exist; the up-sampled map is a saved tensor of its own and the
+            # skip tensor is read a second time by the decoder (forward and weight gradient).
+            d1 = mc.make_desc(N, v, v, v, 2 * ch[l], ch[l], 3, 1, 1, torch.bfloat16)
+            virtual = virtual_cat and all(mc.pair_supported(d1, p) for p in range(3))
+            in_place = in_place and not virtual
+            u = new_saved((N, v, v, v, ch[l]), sw.TAG_DECODER) if virtual else None
+            self.ops.append(dict(kind="up", name=f"dec{l}.up", desc=d, src=a, w=wi, shape=(N, v, v, v, ch[l]), in_place=in_place,
+                                 virtual=virtual, out=u)); wi += 1
             self.flops += 3 * 2.0 * N * (v // 2) ** 3 * 8 * ch[l] * ch[l + 1]
+            if virtual:
+                self.ops.append(dict(kind="cat", name=f"dec{l}.cat", skip=skips[l], up=u, c=ch[l], virtual=True))
+                a, _ = conv_op(f"dec{l}.conv1", u, v, 2 * ch[l], ch[l], 1, wi, sw.TAG_DECODER, src2=skips[l]); wi += 1
+                a, _ = conv_op(f"dec{l}.conv2", a, v, ch[l], ch[l], 1, wi, sw.TAG_DECODER); wi += 1
+                continue
             cat = new_saved((N, v, v, v, 2 * ch[l]), sw.TAG_DECODER)
             if in_place:
                 cat.produce = len(self.ops) - 1      # allocated and half filled by the up-sampling, completed by the next op
             skips[l].last_fwd = len(self.ops)
-            self.ops.append(dict(kind="cat", name=f"dec{l}.cat", skip=skips[l], out=cat, c=ch[l]))
+            self.ops.append(dict(kind="cat", name=f"dec{l}.cat", skip=skips[l], out=cat, c=ch[l], virtual=False))
             a, _ = conv_op(f"dec{l}.conv1", cat, v, 2 * ch[l], ch[l], 1, wi, sw.TAG_DECODER); wi += 1
             a, _ = conv_op(f"dec{l}.conv2", a, v, ch[l], ch[l], 1, wi, sw.TAG_DECODER); wi += 1
         d = mc.make_desc(N, v, v, v, ch[0], classes, 1, 1, 0, torch.bfloat16)
@@ -147,6 +162,8 @@ class UNetStep:
             b = self.bwd_op(f)
             if op["kind"] == "conv":
                 op["src"].bwd_ops.append(b)
+                if op["src2"] is not None:
+                    op["src2"].bwd_ops.append(b)
                 nxt = self.ops[f + 1]
                 if not (nxt["kind"] == "conv" and nxt["through_act"]):
                     op["out"].bwd_ops.append(b)
@@ -154,6 +171,12 @@ class UNetStep:
                 op["src"].bwd_ops.append(b)
             elif op["kind"] == "loss":
                 op["src"].bwd_ops.append(b)
+        # the backward op of the encoder convolution that reads a skip tensor (conv1 of the next level down) is the
+        # one that consumes the skip half of the concatenated tensor's gradient
+        for op in self.ops:
+            if op["kind"] == "cat":
+                op["enc_reader"] = next(self.bwd_op(f) for f, o in enumerate(self.ops)
+                                        if o["kind"] == "conv" and o["src"] is op["skip"])
         # ---- workspaces and small buffers
         ws_bytes = 256
         for op in self.ops:
@@ -189,7 +212,10 @@ class UNetStep:
                     d = op["desc"]
                     fl = 2.0 * _numel(op["out"].shape) * d.kD * d.kH * d.kW * d.Cin
                     ms = max(fl / 8e14, (op["src"].bytes + op["out"].bytes) / 4e12) * 1e3
-                    e.set_recompute(op["out"].id, ms, op["src"].id)
+                    if op.get("src2") is not None:
+                        e.set_recompute(op["out"].id, ms, op["src"].id, op["src2"].id)
+                    else:
+                        e.set_recompute(op["out"].id, ms, op["src"].id)
             for op in range(self.n_ops):
                 e.set_transient(op, self._transient(op))
             self._read_plan(e.plan(allow_over_budget=True))
@@ -218,21 +244,22 @@ class UNetStep:
             fixed += self.in_ws.numel()
         if op < self.n_fwd:
             o = self.ops[op]
-            return fixed + (_numel(o["shape"]) * 2 if o["kind"] == "up" and not o["in_place"] else 0)
+            return fixed + (_numel(o["shape"]) * 2 if o["kind"] == "up" and not o["in_place"] and not o["virtual"] else 0)
         f = self.n_fwd - 1 - (op - self.n_fwd)
         o = self.ops[f]
         live = 0
-        if "out" in o:
+        if o.get("out") is not None:
             live += o["out"].bytes
-        if "src" in o:
+        if o.get("src") is not None:
             live += o["src"].bytes
+        if o.get("src2") is not None:
+            live += o["src2"].bytes
         # gradients of concatenated tensors (their skip halves) of decoder levels already walked back and not yet
         # consumed by the encoder
         for g, oo in enumerate(self.ops):
             if oo["kind"] == "cat" and g >= f:
-                enc_reader = min(oo["skip"].bwd_ops)   # conv1 of the next encoder level reads the skip tensor
-                if enc_reader >= op:
-                    live += oo["out"].bytes
+                if oo["enc_reader"] >= op:       # (virtual concatenation: only the skip half of the gradient exists)
+                    live += oo["skip"].bytes if oo["virtual"] else oo["out"].bytes
         return fixed + live
 
     # ---- storage of saved tensors
@@ -280,14 +307,23 @@ class UNetStep:
         if s.view is None and self.recomputed[s.id]:
             op = self.producer[s.id]
             self._need(op["src"])
+            if op.get("src2") is not None:
+                self._need(op["src2"])
             self._forward_conv(op)
             self.n_recomputed += 1
         return s.view
 
     def _forward_conv(self, op):
         out = self._produce(op["out"])
-        if op["kind"] == "conv" and self.norm:
+        pair = op.get("src2") is not None
+        if pair and self.norm:
+            mc.conv3d_fwd_pair(op["desc"], op["src"].view, op["src2"].view, self.w[op["w"]], 1.0, out, self.ws)
+        elif pair:
+            mc.conv3d_fwd_pair(op["desc"], op["src"].view, op["src2"].view, self.w[op["w"]], SLOPE, out, self.ws)
+            return out
+        elif op["kind"] == "conv" and self.norm:
             mc.conv3d_fwd(op["desc"], op["src"].view, self.w[op["w"]], out, self.ws)
+        if op["kind"] == "conv" and self.norm:
             if self._trace is not None:
                 self._trace[op["name"] + ".z"] = out.clone()
             glue.instnorm_stats(out, op["stats"], self.in_ws)
@@ -337,7 +373,12 @@ class UNetStep:
                 if trace is not None:
                     trace[op["name"] + ".a"] = out.clone()
             elif k == "up":
-                if op["in_place"]:
+                if op["virtual"]:
+                    u = self._produce(op["out"])
+                    mc.conv3d_dgrad(op["desc"], op["src"].view, self.w[op["w"]], u, self.ws)
+                    if trace is not None:
+                        trace[op["name"] + ".a"] = u.clone()
+                elif op["in_place"]:
                     cat = self._produce(self.ops[f + 1]["out"])
                     mc.conv3d_dgrad_view(op["desc"], op["src"].view, self.w[op["w"]], cat, 0, self.ws)
                     if trace is not None:
@@ -349,12 +390,15 @@ class UNetStep:
                         trace[op["name"] + ".a"] = op["u"].clone()
             elif k == "cat":
                 up = self.ops[f - 1]
-                if up["in_place"]:
+                if op["virtual"]:
+                    if trace is not None:
+                        trace[op["name"] + ".a"] = torch.cat([op["up"].view, op["skip"].view], dim=-1)
+                elif up["in_place"]:
                     glue.place_channels(op["skip"].view, op["out"].view, op["c"])
                 else:
                     glue.concat_channels(up["u"], op["skip"].view, self._produce(op["out"]))
                     up["u"] = None
-                if trace is not None:
+                if trace is not None and not op["virtual"]:
                     trace[op["name"] + ".a"] = op["out"].view.clone()
             elif k == "head":
                 self._forward_conv(op)
@@ -368,6 +412,7 @@ class UNetStep:
         da = None              # gradient with respect to the output of the op being walked back
         premasked = False      # da already carries the LeakyReLU derivative of the op being walked back
         dskip = {}
+        d_pair = None          # skip half of the gradient of a virtual concatenation, between its convolution and its cat op
         for f in range(self.n_fwd - 1, -1, -1):
             op, b = self.ops[f], self.bwd_op(f)
             self._before_bwd_op(b)
@@ -397,9 +442,21 @@ class UNetStep:
                 premasked = False
                 if trace is not None:
                     trace[op["name"] + ".dz"] = da.clone()
-                mc.conv3d_wgrad(op["desc"], self._need(op["src"]), da, self.dw[op["w"]], self.ws)
+                din_trace = None
+                if op["src2"] is not None:
+                    mc.conv3d_wgrad_pair(op["desc"], self._need(op["src"]), self._need(op["src2"]), da, self.dw[op["w"]], self.ws)
+                else:
+                    mc.conv3d_wgrad(op["desc"], self._need(op["src"]), da, self.dw[op["w"]], self.ws)
                 if op["first"]:
                     da = None      # the network input needs no gradient
+                elif op["src2"] is not None:
+                    # the two halves of the gradient go where they are needed: the up-sampling layer's and the skip's
+                    d_lo = torch.empty(op["src"].shape, dtype=bf, device="cuda")
+                    d_hi = torch.empty(op["src2"].shape, dtype=bf, device="cuda")
+                    mc.conv3d_dgrad_pair(op["desc"], da, self.w[op["w"]], d_lo, d_hi, self.ws)
+                    da, d_pair = d_lo, d_hi
+                    if trace is not None:
+                        din_trace = torch.cat([d_lo, d_hi], dim=-1)
                 else:
                     nxt = torch.empty(op["src"].shape, dtype=bf, device="cuda")
                     if op["through_act"]:
@@ -419,6 +476,12 @@ class UNetStep:
                         # (with normalisation the derivative is not a factor: the pass only adds, slope 1)
                         glue.skip_grad(da, dcat, c_off, self._need(op["src"]), 1.0 if self.norm else SLOPE)
                         premasked = not self.norm
+            elif k == "cat" and op["virtual"]:
+                dskip[op["skip"].id] = (d_pair, 0)  # da is the up-sampling layer's half already
+                if trace is not None:
+                    trace[op["name"] + ".dout"] = torch.cat([da, d_pair], dim=-1)
+                    trace[op["name"] + ".dskip"] = d_pair.clone()
+                d_pair = None
             elif k == "cat":
                 c = op["c"]
                 dskip[op["skip"].id] = (da, c)      # the skip half stays where it is until the encoder reads it
@@ -440,7 +503,10 @@ class UNetStep:
                     mc.conv3d_fwd(op["desc"], da, self.w[op["w"]], nxt, self.ws)
                 da = nxt
             if trace is not None and da is not None:
-                trace[op["name"] + ".din"] = da[..., :op["c"]].clone() if k == "cat" else da.clone()
+                if k == "conv" and din_trace is not None:
+                    trace[op["name"] + ".din"] = din_trace
+                else:
+                    trace[op["name"] + ".din"] = da[..., :op["c"]].clone() if k == "cat" else da.clone()
             self._after_bwd_op(b)
             mark(op["name"], "bwd")
         if update:
@@ -472,7 +538,10 @@ class UNetStep:
         e.set_op_times(ms, link_gbs)
         for f, op in enumerate(self.ops):
             if op["kind"] in ("conv", "head"):
-                e.set_recompute(op["out"].id, ms[f], op["src"].id)
+                if op.get("src2") is not None:
+                    e.set_recompute(op["out"].id, ms[f], op["src"].id, op["src2"].id)
+                else:
+                    e.set_recompute(op["out"].id, ms[f], op["src"].id)
         self._read_plan(e.plan(allow_over_budget=True))
         self.op_ms = ms
 

@@ -53,11 +53,13 @@ def _h(t):
 
 
 # 48 = 16 x 3: odd extents at the two deepest levels, as in the 208^3 volume (16 x 13)
-@pytest.mark.parametrize("N,vol,channels", [(2, 32, CH), (1, 16, CH[:4]), (1, 48, CH)])
-def test_every_op_matches_oracle_on_the_steps_own_tensors(unet, N, vol, channels):
+# (last flag: the decoder reads [up-sampled | skip] as two tensors / materialises the concatenation)
+@pytest.mark.parametrize("N,vol,channels,virtual_cat", [(2, 32, CH, True), (1, 16, CH[:4], True), (1, 48, CH, True), (2, 32, CH, False)])
+def test_every_op_matches_oracle_on_the_steps_own_tensors(unet, N, vol, channels, virtual_cat):
     x, labels, ws, xd, ld = _inputs(N, vol, channels, 5)
     L = len(channels)
-    step = unet.UNetStep(N, vol, channels, ws, xd, ld, swap=False)
+    step = unet.UNetStep(N, vol, channels, ws, xd, ld, swap=False, virtual_cat=virtual_cat)
+    assert all(op["virtual"] == virtual_cat for op in step.ops if op["kind"] == "cat")
     tr = {}
     step.run(update=False, trace=tr)
     torch.cuda.synchronize()
@@ -162,6 +164,23 @@ def test_step_end_to_end_against_oracle_step(unet):
         # SGD on the fp32 master weights with the GPU's own gradient
         expect = w0.astype(np.float32) - np.float32(lr) * g.cpu().numpy()
         assert np.allclose(wm.cpu().numpy(), expect, rtol=1e-6, atol=1e-8), name
+
+
+def test_virtual_concatenation_gives_the_bits_of_the_materialised_one_and_needs_less_memory(unet):
+    N, vol = 2, 32
+    _, _, ws, xd, ld = _inputs(N, vol, CH, 5)
+    out = {}
+    for virtual in (False, True):
+        st = unet.UNetStep(N, vol, CH, ws, xd, ld, swap=True, virtual_cat=virtual)
+        st.run(update=False)
+        torch.cuda.synchronize()
+        out[virtual] = (st.dw32.clone(), st.loss.clone(), st.engine.stats()["unswapped_peak_bytes"], sum(s.bytes for s in st.saved))
+        st.close()
+    assert torch.equal(out[True][0], out[False][0]) and torch.equal(out[True][1], out[False][1])
+    # one tensor of C channels per decoder level is no longer kept
+    dropped = sum(N * (vol >> l) ** 3 * CH[l] * 2 for l in range(len(CH) - 1))
+    assert out[False][3] - out[True][3] == dropped
+    assert out[True][2] < out[False][2]
 
 
 def test_swapped_step_is_bit_identical(unet):
