@@ -132,11 +132,26 @@ def unet_train_step(steps=3, warmup=1):
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) * 1e3 / steps
 
+    def op_times(step):
+        """Per-op durations (ms) on the compute stream, forward ops then backward ops, from events between the ops:
+        a stall (waiting for a swap-in, a swap-out or arena space) shows up in the op that waits."""
+        step.run(update=False)
+        best = None
+        for _ in range(3):      # per-op minimum of three steps: a hiccup of the host thread is not a stall
+            tl = []
+            step.run(update=False, timeline=tl)
+            torch.cuda.synchronize()
+            t = [tl[0][2].elapsed_time(ev) for _, _, ev in tl]
+            ops = [(tl[i + 1][0], tl[i + 1][1], t[i + 1] - t[i]) for i in range(len(t) - 1)]
+            best = ops if best is None else [(a[0], a[1], min(a[2], b[2])) for a, b in zip(ops, best)]
+        return best
+
     plain = unet.UNetStep(N, vol, ch, ws, xd, labels, swap=False)
     plain.run(update=False)          # gradients at the start weights: reference bits for the swapped runs
     torch.cuda.synchronize()
     ref = plain.dw32.clone()
     ms0 = timed(plain)
+    ops0 = op_times(plain)
     flops = plain.flops
     out = {"workload": "5-level 3D U-Net at 192^3, N=2, bf16: forward, sigmoid + soft Dice, backward, SGD; 23 convolution layers",
            "ms_per_step_no_swap": ms0, "conv_tflops_no_swap": flops / ms0 / 1e9, "conv_flop_per_step": flops,
@@ -222,9 +237,20 @@ def unet_train_step(steps=3, warmup=1):
         torch.cuda.synchronize()
         same = bool(torch.equal(st.dw32, ref))
         ms = timed(st)
+        # where the compute stream waits (Fig. 2): per-op time minus the unswapped op's time.  The first backward op
+        # (the loss gradient) waits until the swap-outs still queued at the end of the forward pass have drained and
+        # its own tensor is back; later backward ops wait for swap-ins that were not issued early enough.
+        ops1 = op_times(st)
+        assert [o[:2] for o in ops1] == [o[:2] for o in ops0]
+        stall = [(a[0], a[1], max(0.0, a[2] - b[2])) for a, b in zip(ops1, ops0)]
+        first_bwd = next(i for i, o in enumerate(stall) if o[1] == "bwd")
+        worst = sorted(stall[first_bwd + 1:], key=lambda o: -o[2])[:3]
         s = st.engine.stats()
         exposed = max(0.0, ms - ms0)
         table.append({"configuration": name, "ms_per_step": ms, "n_saved": n_saved, "n_swapped": s["n_planned"], "bytes_out": s["bytes_out"],
+                      "stall_ms": {"forward_ops": sum(o[2] for o in stall[:first_bwd]), "forward_to_backward_turn": stall[first_bwd][2],
+                                   "later_backward_ops": sum(o[2] for o in stall[first_bwd + 1:]),
+                                   "largest_backward": [{"op": o[0], "ms": o[2]} for o in worst]},
                       "planned_peak_bytes": s["planned_peak_bytes"], "transfer_ms": s["busy_ms"], "exposed_ms": exposed,
                       "hidden_frac": (1.0 - exposed / s["busy_ms"]) if s["busy_ms"] > 0 else None, "bit_identical_to_unswapped": same})
         st.close()
