@@ -18,9 +18,15 @@
 // them, leaving four finished output rows in the four lane groups.
 //
 // Work decomposition as in the plane-streaming kernel: persistent workgroups
-// walk (16 x 32 patch, plane) units along D, one dy plane patch with halo is
-// staged in LDS at a time (double buffered) and feeds three output planes
-// whose accumulators stay in registers.
+// walk (16 x 32 patch, plane) units along D; each dy plane patch with halo is
+// staged in LDS once and feeds three output planes whose accumulators stay in
+// registers.  The pass is bound by its reads of dy, so the staging runs two
+// planes ahead of the compute: direct-to-LDS buffer loads fill a ring of three
+// stages, and a plane's data has a whole plane step more than the memory
+// latency to arrive before anybody waits for it.  LDS holds a patch voxel-major
+// (64 bytes per voxel): one load instruction moves 16 neighbouring voxels, 1 KB
+// contiguous in memory and in LDS, and a B fragment (16 voxels x 32 couts) is
+// again 1 KB contiguous, free of bank conflicts.
 #include "mi3d_internal.h"
 
 namespace mi3d {
@@ -35,11 +41,14 @@ typedef __attribute__((ext_vector_type(2))) unsigned u32x2;
 constexpr int TH = 16, TW = 32;
 constexpr int WR = 8, UR = WR + 2;                 // output rows per wave, dy rows they meet
 constexpr int IN_ROWS = TH + 2, IN_COLS = TW + 2;  // staged patch with halo
-constexpr int COLS = 35;                           // row pitch (voxels) in LDS
-constexpr int NV = IN_ROWS * COLS;                 // voxels per 8-channel slab
-constexpr int STAGE_BYTES = 4 * NV * 16;           // [8-channel slab][row][col] x 16 B
-constexpr int NPIECE = IN_ROWS * IN_COLS * 4;      // 16-byte pieces per plane patch
-constexpr int NLOAD = (NPIECE + 255) / 256;        // 10 per thread
+constexpr int VB = 64;                             // bytes per staged voxel (32 couts)
+constexpr int ROWB = IN_COLS * VB;                 // row pitch in LDS: the patch is a flat list of 18 x 34 voxels
+constexpr int NVOX = IN_ROWS * IN_COLS;            // 612
+constexpr int NINSTR = (NVOX + 15) / 16;           // load instructions per plane patch, 16 voxels each (39)
+constexpr int NLOAD = (NINSTR + 3) / 4;            // per wave (10); instruction k = 4 i + wave
+constexpr int STAGE_BYTES = 4 * NLOAD * 1024;      // 40 KB: the last instruction slot is padding
+constexpr int NSTAGE = 3;
+constexpr unsigned OOB = 0x80000000u;              // buffer offset of a piece that must read as zero
 static_assert(NLOAD == UR, "one global load per dy row step");
 
 struct C4DgParams {
@@ -56,6 +65,11 @@ struct C4DgParams {
 };
 
 #define C4D_FENCE() __builtin_amdgcn_sched_barrier(0)
+// Waits until at most N of this wave's vector-memory operations are outstanding (they complete in issue order) and
+// all its LDS reads have returned, then the workgroup barrier.  One asm statement with a memory clobber: the compiler
+// moves no LDS access across it.  __syncthreads() would not do here: its workgroup-scope fence makes every
+// direct-to-LDS load issued so far complete, including those of the plane two steps ahead.
+#define C4D_WAIT_AND_BARRIER(N) asm volatile("s_waitcnt vmcnt(" N ") lgkmcnt(0)\n\ts_barrier" ::: "memory")
 
 // The MFMAs of one staged dy plane for this wave: 10 rows x 3 kw' x 3 kd'.
 // kd' = 0 starts a new output plane (its first product accumulates onto zero).
@@ -64,12 +78,12 @@ template <int PH, class Hook>
 __device__ __forceinline__ void plane_compute(f32x4 (&acc)[3][UR], const char* in_lane, const bf16x8 (&wf)[3][3], int kdmask, Hook&& hook) {
     bf16x8 xf[2][3];
 #pragma unroll
-    for (int kw = 0; kw < 3; ++kw) xf[0][kw] = *(const bf16x8*)(in_lane + kw * 16);
+    for (int kw = 0; kw < 3; ++kw) xf[0][kw] = *(const bf16x8*)(in_lane + kw * VB);
 #pragma unroll
     for (int r = 0; r < UR; ++r) {
         if (r + 1 < UR) {
 #pragma unroll
-            for (int kw = 0; kw < 3; ++kw) xf[(r + 1) & 1][kw] = *(const bf16x8*)(in_lane + ((r + 1) * COLS + kw) * 16);
+            for (int kw = 0; kw < 3; ++kw) xf[(r + 1) & 1][kw] = *(const bf16x8*)(in_lane + (r + 1) * ROWB + kw * VB);
         }
 #pragma unroll
         for (int kd = 2; kd >= 0; --kd) {
@@ -140,7 +154,7 @@ __device__ __forceinline__ void store_plane(const f32x4 (&U)[UR], uint16_t* p, l
 }
 
 __global__ void __launch_bounds__(256, 1) c4_dgrad_kernel(C4DgParams P) {
-    extern __shared__ __attribute__((aligned(16))) char in_lds[];  // 2 stages
+    extern __shared__ __attribute__((aligned(16))) char in_lds[];  // ring of NSTAGE stages
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     const int rh = wave >> 1, ch = wave & 1;  // half of the patch rows, half of its columns
     int gidx = blockIdx.x;
@@ -154,16 +168,9 @@ __global__ void __launch_bounds__(256, 1) c4_dgrad_kernel(C4DgParams P) {
 #pragma unroll
         for (int kw = 0; kw < 3; ++kw) wf[kd][kw] = *((const bf16x8*)P.wpack + (kd * 3 + kw) * 64 + lane);
 
-    int lds_off[NLOAD];
-#pragma unroll
-    for (int i = 0; i < NLOAD; ++i) {
-        const int q = t + 256 * i;
-        const int v = q >> 2, c = q & 3;
-        const int row = (v * 241) >> 13, col = v - row * IN_COLS;  // v / 34 for v < 700
-        lds_off[i] = (c * NV + row * COLS + col) * 16;
-    }
     // lane (n, g): channels 8g..8g+7 of the voxel in column 16 ch + n (+ kw') of row 8 rh (+ r)
-    const int lane_in_off = ((lane >> 4) * NV + rh * WR * COLS + ch * 16 + (lane & 15)) * 16;
+    const int lane_in_off = ((rh * WR) * IN_COLS + ch * 16 + (lane & 15)) * VB + (lane >> 4) * 16;
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
     f32x4 acc[3][UR];
 
     while (u0 < u1) {
@@ -176,46 +183,34 @@ __global__ void __launch_bounds__(256, 1) c4_dgrad_kernel(C4DgParams P) {
         const int n = (int)(column / P.HT);
         const int h0 = ht * TH, w0 = wt * TW;
 
+        // staging plan: load i of this wave is instruction 4 i + wave, lane l its 16-byte piece l % 4 of patch voxel
+        // 16 (4 i + wave) + l / 4 (row-major over 18 x 34); byte offsets from the plane base, OOB for zero padding
         int goff[NLOAD];
-        unsigned valid = 0;
 #pragma unroll
         for (int i = 0; i < NLOAD; ++i) {
-            const int q = t + 256 * i;
-            const int v = q >> 2, c = q & 3;
-            const int row = (v * 241) >> 13, col = v - row * IN_COLS;
+            const int v = 16 * (4 * i + wave) + (lane >> 2), c = lane & 3;
+            const int row = (v * 241) >> 13, col = v - row * IN_COLS;  // v / 34 for v < 700
             const int gh = h0 - P.pH + row, gw = w0 - P.pW + col;
-            const bool ok = q < NPIECE && gh >= 0 && gh < P.H && gw >= 0 && gw < P.W;
-            goff[i] = ok ? (gh * P.W + gw) * 32 + c * 8 : 0;
-            valid |= (ok ? 1u : 0u) << i;
+            const bool ok = v < NVOX && gh >= 0 && gh < P.H && gw >= 0 && gw < P.W;
+            goff[i] = ok ? ((gh * P.W + gw) * 32 + c * 8) * 2 : (int)OOB;
         }
         const long long plane_elems = (long long)P.H * P.W * 32;
         const uint16_t* dyn = P.dy + (long long)n * P.D * plane_elems;
         uint16_t* dxn = P.dx + (long long)n * P.Do * P.Ho * P.Wo * 4;
         const int nJ = od_end - od_start + 2;
 
-        // loads are unconditional (masked pieces read element 0 of a valid plane) and zeroed when
-        // they are written to LDS, so nothing waits for them before the MFMA work
-        uint4 pre[NLOAD];
-        unsigned pre_mask = 0;
-        const uint16_t* pre_base = dyn;
+        // A plane outside [0, D) is zero padding: its buffer has zero records, so every piece reads 0 and nothing is
+        // fetched; so does a plane past the end of the segment, which nobody reads.  The loads are unconditional.
+        __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)dyn, 0, 0, 0x00020000);
+        const int ip_end = od_start - P.pD + nJ;   // first plane the segment does not read
         auto begin_stage = [&](int ip) {
-            const bool inside = ip >= 0 && ip < P.D;
-            pre_base = dyn + (long long)(inside ? ip : 0) * plane_elems;
-            pre_mask = inside ? valid : 0u;
+            const bool inside = ip >= 0 && ip < P.D && ip < ip_end;
+            rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)(dyn + (long long)(inside ? ip : 0) * plane_elems), 0,
+                                                     inside ? (int)(plane_elems * 2) : 0, 0x00020000);
         };
-        auto load_piece = [&](int i) { pre[i] = *(const uint4*)(pre_base + goff[i]); };
-        auto write_stage = [&](int buf) {
-            char* dst = in_lds + buf * STAGE_BYTES;
-#pragma unroll
-            for (int i = 0; i < NLOAD; ++i) {
-                const bool ok = (pre_mask >> i) & 1;
-                uint4 v;
-                v.x = ok ? pre[i].x : 0u;
-                v.y = ok ? pre[i].y : 0u;
-                v.z = ok ? pre[i].z : 0u;
-                v.w = ok ? pre[i].w : 0u;
-                if (t + 256 * i < NPIECE) *(uint4*)(dst + lds_off[i]) = v;
-            }
+        auto load_piece = [&](int i, int buf) {
+            typedef __attribute__((address_space(3))) void* lds_ptr;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_ptr)(in_lds + buf * STAGE_BYTES + (4 * i + wave_u) * 1024), 16, goff[i], 0, 0, 0);
         };
 
         const int oh0 = h0 + rh * WR, ow = w0 + ch * 16 + (lane & 15);
@@ -226,27 +221,33 @@ __global__ void __launch_bounds__(256, 1) c4_dgrad_kernel(C4DgParams P) {
 #pragma unroll
             for (int r = 0; r < UR; ++r) acc[s][r] = f32x4{0.f, 0.f, 0.f, 0.f};
 
+        // the first two planes of the segment; the first one must have arrived, the second may still fly
         begin_stage(od_start - P.pD);
 #pragma unroll
-        for (int i = 0; i < NLOAD; ++i) load_piece(i);
-        write_stage(0);
-        __syncthreads();
+        for (int i = 0; i < NLOAD; ++i) load_piece(i, 0);
+        begin_stage(od_start + 1 - P.pD);
+#pragma unroll
+        for (int i = 0; i < NLOAD; ++i) load_piece(i, 1);
+        C4D_WAIT_AND_BARRIER("10");
 
-        // plane step jj stages dy plane od_start + jj - pD and completes output plane od_start + jj - 2
+        // Plane step jj computes on dy plane od_start + jj - pD (stage sq % 3), completes output plane
+        // od_start + jj - 2 and issues the loads of the plane two steps ahead into the stage that was read one
+        // step ago (every wave has passed the barrier behind that step).  At the end of the step the loads issued
+        // one step ago must be complete; younger than they are at most this step's ten loads and two stores.
 #define C4D_STAGE(PHASE)                                                                        \
         {                                                                                       \
             const int j_ = od_start + jj;                                                       \
-            begin_stage(j_ + 1 - P.pD);                                                         \
+            begin_stage(j_ + 2 - P.pD);                                                         \
+            const int cur_ = sq % NSTAGE, fill_ = (sq + 2) % NSTAGE;                            \
             int kdmask_ = 0;                                                                    \
             for (int kd_ = 0; kd_ < 3; ++kd_)                                                   \
                 if (jj - kd_ >= 0 && jj - kd_ < nJ - 2) kdmask_ |= 1 << kd_;                    \
-            plane_compute<PHASE>(acc, in_lds + (sq & 1) * STAGE_BYTES + lane_in_off, wf, kdmask_, \
-                                 [&](int r) { load_piece(r); });                                \
+            plane_compute<PHASE>(acc, in_lds + cur_ * STAGE_BYTES + lane_in_off, wf, kdmask_,   \
+                                 [&](int r) { load_piece(r, fill_); });                         \
             store_plane(acc[(PHASE + 1) % 3], dxn + (((long long)(j_ - 2) * P.Ho + oh0) * P.Wo + ow) * 4, \
                         row_pitch, lane, jj >= 2 && ow < P.Wo, P.Ho - oh0, P.dump + lane * 4);  \
-            write_stage((sq + 1) & 1);                                                          \
             ++sq;                                                                               \
-            __syncthreads();                                                                    \
+            C4D_WAIT_AND_BARRIER("12");                                                         \
         }
         int sq = 0;
         for (int jj = 0;;) {
@@ -279,6 +280,8 @@ bool c4_dgrad_supported(const Geom& g) {
     if (g.dtype != MI3D_BF16 || g.kD != 3 || g.kH != 3 || g.kW != 3) return false;
     if (g.sD != 1 || g.sH != 1 || g.sW != 1) return false;
     if (g.pD > 2 || g.pH > 2 || g.pW > 2) return false;
+    // a staged plane is addressed through a buffer resource with 32-bit byte offsets; 2^31 marks padding
+    if ((long long)g.Ho * g.Wo * 64 >= (1ll << 31)) return false;
     return g.Cin == 4 && g.Cout == 32;
 }
 
@@ -306,11 +309,11 @@ int c4_dgrad(const Geom& g, const void* dy, const void* w, void* dx, void* ws, s
     P.nwg = (int)nwg;
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void*)c4_dgrad_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 2 * STAGE_BYTES);
+        hipError_t e = hipFuncSetAttribute((const void*)c4_dgrad_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, NSTAGE * STAGE_BYTES);
         if (e != hipSuccess) { note_hip_error(e); return MI3D_ERR_HIP; }
         attr_set = true;
     }
-    c4_dgrad_kernel<<<(unsigned)nwg, 256, 2 * STAGE_BYTES, s>>>(P);
+    c4_dgrad_kernel<<<(unsigned)nwg, 256, NSTAGE * STAGE_BYTES, s>>>(P);
     return check_launch();
 }
 
