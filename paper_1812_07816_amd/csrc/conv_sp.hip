@@ -230,7 +230,7 @@ __device__ __forceinline__ void store_row(const uint32_t (&o)[8], uint16_t* p, b
 // PART (with NC = 1): the 32-channel chunks of Cin are separate work units whose weights (54 KB) stay resident; each
 // writes fp32 partial outputs and a second kernel adds the chunks in index order.  For the deep, small layers this is
 // two to three times faster than streaming the weights of all chunks through LDS for every staged plane.
-// MASK (with NC = 1, data gradient): every output element is multiplied by 1 where P.ref is > 0 and by P.slope
+// MASK (data gradient, not with PART): every output element is multiplied by 1 where P.ref is > 0 and by P.slope
 // elsewhere (LeakyReLU derivative of the layer below) after its rounding to bf16 and rounded again: the bits of the
 // plain kernel followed by an elementwise pass, without that pass's read and write of the gradient.
 template <int NC, bool PART = false, bool MASK = false>
@@ -551,10 +551,8 @@ static bool sp_use_chunks(const Geom& g, int pass) {
 }
 
 // the chunked variant applies the optional derivative factor of the geometry while it sums the chunks
-// ... and so does the one-chunk kernel (contraction over 32 channels), in its store path
-bool sp_fuses_dgrad_factor(const Geom& g) {
-    return sp_supported(g, MI3D_PASS_DGRAD) && (sp_use_chunks(g, MI3D_PASS_DGRAD) || g.Cout == 32);
-}
+// ... and the other variants do in their store path
+bool sp_fuses_dgrad_factor(const Geom& g) { return sp_supported(g, MI3D_PASS_DGRAD); }
 
 static size_t sp_part_offset(const Geom& g) { return (((size_t)g.w_elems() * 2 + 255) & ~(size_t)255) + 8192; }
 
@@ -603,7 +601,7 @@ int sp_conv(const Geom& g, int pass, const void* in, const void* w, void* out, v
     }
     const bool chunks = sp_use_chunks(g, pass);
     P.NCH = chunks ? P.Cin / 32 : 1;
-    const bool mask = pass == MI3D_PASS_DGRAD && g.ref && g.slope != 1.f && !chunks && P.Cin == 32;
+    const bool mask = pass == MI3D_PASS_DGRAD && g.ref && g.slope != 1.f && !chunks;
     P.slope = (pass == MI3D_PASS_FWD || mask) ? g.slope : 1.f;
     P.ref = mask ? (const uint16_t*)g.ref : nullptr;
     P.units = (long long)P.N * P.CT * P.NCH * P.HT * P.WT * P.Do;
@@ -619,6 +617,8 @@ int sp_conv(const Geom& g, int pass, const void* in, const void* w, void* out, v
         if (e == hipSuccess) e = hipFuncSetAttribute((const void*)sp_conv_kernel<0>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds1);
         if (e == hipSuccess) e = hipFuncSetAttribute((const void*)sp_conv_kernel<1, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds1);
         if (e == hipSuccess) e = hipFuncSetAttribute((const void*)sp_conv_kernel<1, false, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds1);
+        if (e == hipSuccess) e = hipFuncSetAttribute((const void*)sp_conv_kernel<2, false, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds2);
+        if (e == hipSuccess) e = hipFuncSetAttribute((const void*)sp_conv_kernel<0, false, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds1);
         if (e != hipSuccess) { note_hip_error(e); return MI3D_ERR_HIP; }
         attr_set = true;
     }
@@ -633,7 +633,9 @@ int sp_conv(const Geom& g, int pass, const void* in, const void* w, void* out, v
                                                                 flip && g.hi ? (uint16_t*)g.hi : nullptr, P.Cout);
         return check_launch();
     }
-    if (mask) sp_conv_kernel<1, false, true><<<(unsigned)nwg, 256, lds1, s>>>(P);
+    if (mask && nc == 1) sp_conv_kernel<1, false, true><<<(unsigned)nwg, 256, lds1, s>>>(P);
+    else if (mask && nc == 2) sp_conv_kernel<2, false, true><<<(unsigned)nwg, 256, lds2, s>>>(P);
+    else if (mask) sp_conv_kernel<0, false, true><<<(unsigned)nwg, 256, lds1, s>>>(P);
     else if (nc == 1) sp_conv_kernel<1><<<(unsigned)nwg, 256, lds1, s>>>(P);
     else if (nc == 2) sp_conv_kernel<2><<<(unsigned)nwg, 256, lds2, s>>>(P);
     else sp_conv_kernel<0><<<(unsigned)nwg, 256, lds1, s>>>(P);
