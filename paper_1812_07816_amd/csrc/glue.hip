@@ -179,20 +179,31 @@ __global__ void __launch_bounds__(256) dice_partial_kernel(const uint4* __restri
     if (threadIdx.x < 3 * C) part[blockIdx.x * 3 * C + threadIdx.x] = red[threadIdx.x][0];
 }
 
-// second pass: partials added in index order in double; sums[3C] and the loss 1 - mean_c (2 I + eps) / (P + T + eps)
+// second pass: thread t adds partials t, t + 256, ... in double, then a fixed binary tree over the threads
+// (bit-reproducible); sums[3C] and the loss 1 - mean_c (2 I + eps) / (P + T + eps)
 template <int C>
-__global__ void dice_final_kernel(const float* __restrict__ part, int nblocks, float eps, float* __restrict__ sums, float* __restrict__ loss) {
-    __shared__ double tot[3 * C];
-    if (threadIdx.x < 3 * C) {
-        double a = 0.0;
-        for (int b = 0; b < nblocks; ++b) a += (double)part[b * 3 * C + threadIdx.x];
-        tot[threadIdx.x] = a;
-        sums[threadIdx.x] = (float)a;
-    }
+__global__ void __launch_bounds__(256) dice_final_kernel(const float* __restrict__ part, int nblocks, float eps, float* __restrict__ sums, float* __restrict__ loss) {
+    __shared__ double red[3 * C][256];
+    const int t = threadIdx.x;
+    double a[3 * C];
+#pragma unroll
+    for (int q = 0; q < 3 * C; ++q) a[q] = 0.0;
+    for (int b = t; b < nblocks; b += 256)
+#pragma unroll
+        for (int q = 0; q < 3 * C; ++q) a[q] += (double)part[b * 3 * C + q];
+#pragma unroll
+    for (int q = 0; q < 3 * C; ++q) red[q][t] = a[q];
     __syncthreads();
-    if (threadIdx.x == 0) {
+    for (int s = 128; s > 0; s >>= 1) {
+        if (t < s)
+#pragma unroll
+            for (int q = 0; q < 3 * C; ++q) red[q][t] += red[q][t + s];
+        __syncthreads();
+    }
+    if (t < 3 * C) sums[t] = (float)red[t][0];
+    if (t == 0) {
         double d = 0.0;
-        for (int c = 0; c < C; ++c) d += (2.0 * tot[c] + eps) / (tot[C + c] + tot[2 * C + c] + eps);
+        for (int c = 0; c < C; ++c) d += (2.0 * red[c][0] + eps) / (red[C + c][0] + red[2 * C + c][0] + eps);
         *loss = (float)(1.0 - d / C);
     }
 }
@@ -344,7 +355,7 @@ int mi3d_dice_loss(const void* logits, const uint8_t* labels, size_t voxels, int
     dice_partial_kernel<3><<<blocks, 256, 0, (hipStream_t)stream>>>((const uint4*)logits, (const uint2*)labels, groups, (float*)ws);
     int st = check_launch();
     if (st) return st;
-    dice_final_kernel<3><<<1, 64, 0, (hipStream_t)stream>>>((const float*)ws, blocks, eps, sums, loss);
+    dice_final_kernel<3><<<1, 256, 0, (hipStream_t)stream>>>((const float*)ws, blocks, eps, sums, loss);
     return check_launch();
 }
 
