@@ -135,6 +135,18 @@ int mi3d_conv3d_dgrad_pair(const mi3d_conv_desc *desc, const void *dy, const voi
 int mi3d_conv3d_wgrad_pair(const mi3d_conv_desc *desc, const void *x_lo, const void *x_hi, const void *dy, float *dw,
                            void *ws, size_t ws_bytes, void *stream);
 
+/* Data gradient of the convolution that reads a skip connection (the stride-2 convolution that leaves a U-Net level,
+ * Section 4.1), finished in one call: the skip tensor has a second reader, the decoder, whose gradient `add` (the skip
+ * half of the decoder convolution's data gradient, of dx's shape) is added, and the LeakyReLU derivative of the layer
+ * that produced the skip tensor a_in is applied:
+ *   dx = (bf16(dgrad(dy, w)) + add) * (a_in > 0 ? 1 : slope),
+ * fp32 arithmetic on the bf16-rounded data gradient, one more rounding: the bits of mi3d_conv3d_dgrad followed by
+ * mi3d_skip_grad.  bf16 only, 0 <= slope <= 1 (1: the sum alone).  The stride-2 MFMA data-gradient kernels do it in
+ * their store path or while they add their fp32 partial gradients; other geometries run the two passes.  Same
+ * workspace as mi3d_conv3d_dgrad; add and a_in must not overlap dx. */
+int mi3d_conv3d_dgrad_skip(const mi3d_conv_desc *desc, const void *dy, const void *w, const void *add, const void *a_in,
+                           float slope, void *dx, void *ws, size_t ws_bytes, void *stream);
+
 /* Convolution followed by the network's LeakyReLU (Section 4.1) in one call:
  * y = lrelu(conv(x, w)), lrelu(v) = v > 0 ? v : slope * v, applied to the fp32
  * accumulator before the single rounding to bf16.  bf16 only, 0 <= slope < 1

@@ -158,6 +158,20 @@ def conv3d_wgrad_view(desc, x_wide, offset, dy, dw=None, ws=None):
     return dw
 
 
+def conv3d_dgrad_skip(desc, dy, w, add, a_in, slope, dx=None, ws=None):
+    """dx = (bf16(dgrad(dy, w)) + add) * (a_in > 0 ? 1 : slope): the gradient that reaches the producer of a skip tensor."""
+    xs, wsh, ys = _shapes(desc)
+    dt = _tdtype(desc)
+    _chk(dy, ys, dt, "dy"); _chk(w, wsh, dt, "w"); _chk(add, xs, dt, "add"); _chk(a_in, xs, dt, "a_in")
+    if dx is None:
+        dx = torch.empty(xs, dtype=dt, device=dy.device)
+    _chk(dx, xs, dt, "dx")
+    ws, p, n = _ws(desc, PASS_DGRAD, ws)
+    check(lib().mi3d_conv3d_dgrad_skip(ctypes.byref(desc), dy.data_ptr(), w.data_ptr(), add.data_ptr(), a_in.data_ptr(), ctypes.c_float(slope),
+                                       dx.data_ptr(), p, n, _stream()), "conv3d_dgrad_skip")
+    return dx
+
+
 def pair_supported(desc, pass_):
     """True if the pass takes the tensor of x's shape as two halves along the channels (conv3d_*_pair)."""
     return bool(lib().mi3d_conv3d_pair_supported(ctypes.byref(desc), int(pass_)))

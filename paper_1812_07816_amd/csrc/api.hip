@@ -264,6 +264,27 @@ int mi3d_conv3d_wgrad_view(const mi3d_conv_desc* desc, const void* x, const mi3d
     return conv_entry(desc, MI3D_PASS_WGRAD, x, dy, dw, ws, ws_bytes, stream, 1.f, nullptr, xv);
 }
 
+int mi3d_conv3d_dgrad_skip(const mi3d_conv_desc* desc, const void* dy, const void* w, const void* add, const void* a_in, float slope, void* dx,
+                           void* ws, size_t ws_bytes, void* stream) {
+    Geom g;
+    int st = make_geom(desc, &g);
+    if (st) return st;
+    if (!dy || !w || !add || !a_in || !dx || !aligned16(dy) || !aligned16(w) || !aligned16(add) || !aligned16(a_in) || !aligned16(dx) || !aligned16(ws))
+        return MI3D_ERR_INVALID_ARG;
+    if (g.dtype != MI3D_BF16 || !(slope >= 0.f && slope <= 1.f) || (ws_bytes && !ws)) return MI3D_ERR_INVALID_ARG;
+    if (ws_bytes < mi3d_conv3d_workspace_bytes(desc, MI3D_PASS_DGRAD)) return MI3D_ERR_WORKSPACE;
+    const Kernel k = g_family.load() == 1 ? K_DIRECT : choose(g, MI3D_PASS_DGRAD);
+    if (k == K_DGRAD_S2 && dgrad_s2_fuses_skip(g)) {
+        Geom ge = g;
+        ge.add = add; ge.ref = a_in; ge.slope = slope;
+        return run_kernel(k, ge, MI3D_PASS_DGRAD, dy, w, dx, ws, ws_bytes, (hipStream_t)stream);
+    }
+    st = run_kernel(k, g, MI3D_PASS_DGRAD, dy, w, dx, ws, ws_bytes, (hipStream_t)stream);
+    if (st) return st;
+    if (g.Cin % 8) return MI3D_ERR_UNSUPPORTED;
+    return mi3d_skip_grad(dx, add, g.Cin, 0, a_in, g.Cin, (size_t)g.in_voxels(), slope, stream);
+}
+
 int mi3d_conv3d_pair_supported(const mi3d_conv_desc* desc, int pass) {
     Geom g;
     if (make_geom(desc, &g) || pass < 0 || pass > 2) return 0;

@@ -36,6 +36,9 @@ struct Dg2Params {
     uint16_t* dx;
     uint16_t* dump;         // 8 KB that masked store lanes write to instead of dx
     float* part;            // [cout chunk][voxel][Cin] fp32 partial gradients (Cout > 64)
+    const uint16_t* add;    // FUSE: second gradient of dx's shape, added to the rounded result
+    const uint16_t* ref;    // FUSE: tensor of dx's shape whose sign selects the factor 1 or slope
+    float slope;
     int N, D, H, W, Cin, Cout, Do, Ho, Wo, p;
     int QD, HT, WT, CiT, NCO;   // ..., cin tiles, cout chunks (of 64 when Cout > 64)
     long long units;
@@ -102,12 +105,27 @@ __device__ __forceinline__ void pack_block(const f32x16& a, uint4 (&c)[2]) {
     }
 }
 
+// (v + a) * (m > 0 ? 1 : slope) on packed bf16 pairs: fp32 sum and product, one rounding to nearest even
+__device__ __forceinline__ uint32_t fuse_pair(uint32_t v, uint32_t a, uint32_t m, float slope) {
+    float lo = __builtin_bit_cast(float, v << 16) + __builtin_bit_cast(float, a << 16);
+    float hi = __builtin_bit_cast(float, v & 0xffff0000u) + __builtin_bit_cast(float, a & 0xffff0000u);
+    lo = (int)(m << 16) > 0 ? lo : slope * lo;
+    hi = (int)(m & 0xffff0000u) > 0 ? hi : slope * hi;
+    f32x2 f = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2));
+}
+__device__ __forceinline__ uint4 fuse4(uint4 v, uint4 a, uint4 m, float slope) {
+    return uint4{fuse_pair(v.x, a.x, m.x, slope), fuse_pair(v.y, a.y, m.y, slope), fuse_pair(v.z, a.z, m.z, slope), fuse_pair(v.w, a.w, m.w, slope)};
+}
+
 // KK = Cout / 16 k16 steps.  Every MFMA needs its own 1 KB weight fragment from LDS (a tap is used once
 // per wave and step), so the kernel runs at the LDS rate: the fragment reads are issued two groups of
 // three MFMAs ahead of their use from a ring of three register groups.
 // PART: Cout > 64 is contracted in chunks of 64 that are separate work units writing fp32 partial gradients; a second
 // kernel adds the chunks in index order and rounds to bf16.
-template <int P, int KK, bool PART>
+// FUSE (not with PART): the gradient of a skip connection.  The pieces of G.add and G.ref at the addresses of the
+// plane pair's 16 stores are requested before its MFMA work and applied to the rounded result in the store path.
+template <int P, int KK, bool PART, bool FUSE = false>
 __global__ void __launch_bounds__(256, 1) dgrad_s2_kernel(Dg2Params G) {
     extern __shared__ __attribute__((aligned(16))) char lds[];
     constexpr int SLABS = 2 * KK;
@@ -201,6 +219,35 @@ __global__ void __launch_bounds__(256, 1) dgrad_s2_kernel(Dg2Params G) {
             load_plane(mB + 1);  // unconditional (after the last pair: a plane nobody reads), so that its wait sits at the LDS write
             const char* plane_base[2] = {in_lds + (mA & 1) * STAGE + lane_in, in_lds + (mB & 1) * STAGE + lane_in};
 
+            // element offsets of this lane's even and odd voxel for block row (cd, ch), -1 outside the tensor
+            auto store_offsets = [&](int cd, int ch, long long& oe, long long& oo) {
+                const int id_ = 2 * q + (cd == 0 ? G.p : 1 - G.p);
+                const int ih_ = 2 * (rq0 + wave) + (ch == 0 ? G.p : 1 - G.p);
+                const int iw_ = 2 * (cq0 + (lane & 31));
+                const bool row_ok = id_ < G.D && ih_ < G.H;
+                const long long o = (((long long)id_ * G.H + ih_) * G.W + iw_) * G.Cin + cit * 32 + 16 * (lane >> 5);
+                oe = (row_ok && iw_ < G.W) ? o : -1;
+                oo = (row_ok && iw_ + 1 < G.W) ? o + G.Cin : -1;
+            };
+            uint4 fa[FUSE ? 4 : 1][4], fm[FUSE ? 4 : 1][4];   // [cd * 2 + ch][even 0, even 1, odd 0, odd 1]
+            if constexpr (FUSE) {
+                const long long nbase = (long long)n * G.D * G.H * G.W * G.Cin;
+#pragma unroll
+                for (int b = 0; b < 4; ++b) {
+                    long long oe, oo;
+                    store_offsets(b >> 1, b & 1, oe, oo);
+                    // unconditional loads: masked lanes read the dump area
+                    const uint16_t* ae = oe >= 0 ? G.add + nbase + oe : G.dump + lane * 16;
+                    const uint16_t* ao = oo >= 0 ? G.add + nbase + oo : G.dump + lane * 16;
+                    const uint16_t* me = oe >= 0 ? G.ref + nbase + oe : G.dump + lane * 16;
+                    const uint16_t* mo = oo >= 0 ? G.ref + nbase + oo : G.dump + lane * 16;
+                    fa[b][0] = *(const uint4*)ae; fa[b][1] = *(const uint4*)(ae + 8);
+                    fa[b][2] = *(const uint4*)ao; fa[b][3] = *(const uint4*)(ao + 8);
+                    fm[b][0] = *(const uint4*)me; fm[b][1] = *(const uint4*)(me + 8);
+                    fm[b][2] = *(const uint4*)mo; fm[b][3] = *(const uint4*)(mo + 8);
+                }
+            }
+
             f32x16 acc[2][2][2];
 #pragma unroll
             for (int a = 0; a < 2; ++a)
@@ -278,6 +325,11 @@ __global__ void __launch_bounds__(256, 1) dgrad_s2_kernel(Dg2Params G) {
                     uint16_t* ptr = dxn + (((long long)id_ * G.H + ih_) * G.W + iw_) * G.Cin + cit * 32 + 16 * (lane >> 5);
                     uint16_t* pe = (row_ok && iw_ < G.W) ? ptr : G.dump + lane * 16;
                     uint16_t* po = (row_ok && iw_ + 1 < G.W) ? ptr + G.Cin : G.dump + lane * 16;
+                    if constexpr (FUSE) {
+                        const int b = cd * 2 + ch;
+                        ev[0] = fuse4(ev[0], fa[b][0], fm[b][0], G.slope); ev[1] = fuse4(ev[1], fa[b][1], fm[b][1], G.slope);
+                        od[0] = fuse4(od[0], fa[b][2], fm[b][2], G.slope); od[1] = fuse4(od[1], fa[b][3], fm[b][3], G.slope);
+                    }
                     *(uint4*)(pe) = ev[0];
                     *(uint4*)(pe + 8) = ev[1];
                     *(uint4*)(po) = od[0];
@@ -324,6 +376,7 @@ bool dgrad_s2_supported(const Geom& g) {
 
 // the chunked variant applies the optional derivative factor of the geometry while it sums the chunks
 bool dgrad_s2_fuses_factor(const Geom& g) { return dgrad_s2_supported(g) && g.Cout > 64; }
+bool dgrad_s2_fuses_skip(const Geom& g) { return dgrad_s2_supported(g) && g.Cout >= 64; }
 
 size_t dgrad_s2_workspace_bytes(const Geom& g) {
     if (!dgrad_s2_supported(g)) return 0;
@@ -343,6 +396,7 @@ int dgrad_s2(const Geom& g, const void* dy, const void* w, void* dx, void* ws, s
     G.dy = (const uint16_t*)dy; G.wpack = (const uint16_t*)ws; G.dx = (uint16_t*)dx;
     G.dump = (uint16_t*)((char*)ws + (((size_t)g.w_elems() * 2 + 255) & ~(size_t)255));
     G.part = (float*)((char*)ws + dg2_part_offset(g));
+    G.add = (const uint16_t*)g.add; G.ref = (const uint16_t*)g.ref; G.slope = g.slope;
     G.N = g.N; G.D = g.D; G.H = g.H; G.W = g.W; G.Cin = g.Cin; G.Cout = g.Cout;
     G.Do = g.Do; G.Ho = g.Ho; G.Wo = g.Wo; G.p = g.pD;
     G.QD = (g.D + 1) / 2;
@@ -359,9 +413,10 @@ int dgrad_s2(const Geom& g, const void* dy, const void* w, void* dx, void* ws, s
     static bool attr_set = false;
     if (!attr_set) {
         const int max_lds = 27 * 4 * 1024 + 2 * 8 * SLABV * 16;
-        const void* fns[6] = {(const void*)dgrad_s2_kernel<0, 2, false>, (const void*)dgrad_s2_kernel<1, 2, false>,
+        const void* fns[8] = {(const void*)dgrad_s2_kernel<0, 2, false>, (const void*)dgrad_s2_kernel<1, 2, false>,
                               (const void*)dgrad_s2_kernel<0, 4, false>, (const void*)dgrad_s2_kernel<1, 4, false>,
-                              (const void*)dgrad_s2_kernel<0, 4, true>, (const void*)dgrad_s2_kernel<1, 4, true>};
+                              (const void*)dgrad_s2_kernel<0, 4, true>, (const void*)dgrad_s2_kernel<1, 4, true>,
+                              (const void*)dgrad_s2_kernel<0, 4, false, true>, (const void*)dgrad_s2_kernel<1, 4, false, true>};
         for (const void* f : fns) {
             hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, max_lds);
             if (e != hipSuccess) { note_hip_error(e); return MI3D_ERR_HIP; }
@@ -369,7 +424,11 @@ int dgrad_s2(const Geom& g, const void* dy, const void* w, void* dx, void* ws, s
         attr_set = true;
     }
     const bool part = G.NCO > 1;
-    if (part && g.pD == 0) dgrad_s2_kernel<0, 4, true><<<(unsigned)nwg, 256, lds, s>>>(G);
+    const bool fuse = g.add && !part;    // (Cout == 64: the only unchunked shape with an added gradient)
+    if (g.add && !dgrad_s2_fuses_skip(g)) return MI3D_ERR_UNSUPPORTED;
+    if (fuse && g.pD == 0) dgrad_s2_kernel<0, 4, false, true><<<(unsigned)nwg, 256, lds, s>>>(G);
+    else if (fuse) dgrad_s2_kernel<1, 4, false, true><<<(unsigned)nwg, 256, lds, s>>>(G);
+    else if (part && g.pD == 0) dgrad_s2_kernel<0, 4, true><<<(unsigned)nwg, 256, lds, s>>>(G);
     else if (part) dgrad_s2_kernel<1, 4, true><<<(unsigned)nwg, 256, lds, s>>>(G);
     else if (g.pD == 0 && KK == 2) dgrad_s2_kernel<0, 2, false><<<(unsigned)nwg, 256, lds, s>>>(G);
     else if (g.pD == 0) dgrad_s2_kernel<0, 4, false><<<(unsigned)nwg, 256, lds, s>>>(G);
@@ -380,7 +439,8 @@ int dgrad_s2(const Geom& g, const void* dy, const void* w, void* dx, void* ws, s
     const long long n = (long long)g.in_voxels() * g.Cin;
     long long blocks = (n / 8 + 255) / 256;
     if (blocks > 8192) blocks = 8192;
-    sum_chunks_bf16_kernel<<<(unsigned)blocks, 256, 0, s>>>(G.part, (uint16_t*)dx, n / 8, n, G.NCO, g.slope, (const uint16_t*)g.ref, nullptr, 0);
+    sum_chunks_bf16_kernel<<<(unsigned)blocks, 256, 0, s>>>(G.part, (uint16_t*)dx, n / 8, n, G.NCO, g.slope, (const uint16_t*)g.ref, nullptr, 0,
+                                                            (const uint16_t*)g.add);
     return check_launch();
 }
 

@@ -320,7 +320,8 @@ __global__ void __launch_bounds__(256) s2_pack_weights_kernel(const uint16_t* __
 // act: LeakyReLU with `slope` (1 = none) if ref is null; otherwise the factor of element i is 1 where
 // ref[i] > 0 and `slope` elsewhere (LeakyReLU derivative taken from the activated tensor ref).
 __global__ void __launch_bounds__(256) sum_chunks_bf16_kernel(const float* __restrict__ part, uint16_t* __restrict__ y, long long n8, long long n, int nch,
-                                                              float slope, const uint16_t* __restrict__ ref, uint16_t* __restrict__ y_hi, int cout) {
+                                                              float slope, const uint16_t* __restrict__ ref, uint16_t* __restrict__ y_hi, int cout,
+                                                              const uint16_t* __restrict__ add) {
     typedef __attribute__((__vector_size__(2 * sizeof(float)))) float f32x2_;
     typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2_;
     for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < n8; i += (long long)gridDim.x * 256) {
@@ -330,6 +331,17 @@ __global__ void __launch_bounds__(256) sum_chunks_bf16_kernel(const float* __res
         for (int c = 0; c < nch; ++c) {
             const float4 lo = *(const float4*)(part + c * n + 8 * i), hi = *(const float4*)(part + c * n + 8 * i + 4);
             a[0] += lo.x; a[1] += lo.y; a[2] += lo.z; a[3] += lo.w; a[4] += hi.x; a[5] += hi.y; a[6] += hi.z; a[7] += hi.w;
+        }
+        if (add) {   // skip connection: the sum as the plain pass would store it (bf16), plus the second gradient
+            const uint4 a4 = *(const uint4*)(add + 8 * i);
+            const uint32_t aw[4] = {a4.x, a4.y, a4.z, a4.w};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                f32x2_ v = {a[2 * j], a[2 * j + 1]};
+                const uint32_t r = __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_));
+                a[2 * j] = __builtin_bit_cast(float, r << 16) + __builtin_bit_cast(float, aw[j] << 16);
+                a[2 * j + 1] = __builtin_bit_cast(float, r & 0xFFFF0000u) + __builtin_bit_cast(float, aw[j] & 0xFFFF0000u);
+            }
         }
         if (ref) {
             const uint4 m4 = *(const uint4*)(ref + 8 * i);
@@ -419,7 +431,7 @@ int s2_fwd(const Geom& g, const void* x, const void* w, void* y, void* ws, size_
     const long long n = (long long)g.out_voxels() * g.Cout;   // Cout % 32 == 0: a multiple of 8
     long long blocks = (n / 8 + 255) / 256;
     if (blocks > 8192) blocks = 8192;
-    sum_chunks_bf16_kernel<<<(unsigned)blocks, 256, 0, s>>>(P.part, (uint16_t*)y, n / 8, n, P.NCH, g.slope, nullptr, nullptr, 0);
+    sum_chunks_bf16_kernel<<<(unsigned)blocks, 256, 0, s>>>(P.part, (uint16_t*)y, n / 8, n, P.NCH, g.slope, nullptr, nullptr, 0, nullptr);
     return check_launch();
 }
 

@@ -630,7 +630,7 @@ int sp_conv(const Geom& g, int pass, const void* in, const void* w, void* out, v
         long long blocks = (n / 8 + 255) / 256;
         if (blocks > 8192) blocks = 8192;
         sum_chunks_bf16_kernel<<<(unsigned)blocks, 256, 0, s>>>(P.part, (uint16_t*)out, n / 8, n, P.NCH, g.slope, pass == MI3D_PASS_DGRAD ? (const uint16_t*)g.ref : nullptr,
-                                                                flip && g.hi ? (uint16_t*)g.hi : nullptr, P.Cout);
+                                                                flip && g.hi ? (uint16_t*)g.hi : nullptr, P.Cout, nullptr);
         return check_launch();
     }
     if (mask && nc == 1) sp_conv_kernel<1, false, true><<<(unsigned)nwg, 256, lds1, s>>>(P);

@@ -28,6 +28,9 @@ struct Geom {
     // pointer of the call being the low half and `hi` the high half.  Set by the dispatcher only for kernels that
     // implement it.
     const void* hi = nullptr;
+    // Optional second gradient of dx's shape added to the bf16-rounded data gradient before the factor of `ref` /
+    // `slope` is applied (skip connection).  Set by the dispatcher only for kernels that implement it.
+    const void* add = nullptr;
     __host__ __device__ long long in_voxels() const { return (long long)N * D * H * W; }
     __host__ __device__ long long out_voxels() const { return (long long)N * Do * Ho * Wo; }
     __host__ __device__ long long taps() const { return (long long)kD * kH * kW; }
@@ -57,9 +60,11 @@ int direct_wgrad(const Geom& g, const void* x, const void* dy, float* dw, void* 
 // out[i] = sum_p part[p*n + i] in a fixed order (bit-reproducible); launch with (n + 15) / 16 blocks of 256
 // y[i] = bf16(act(sum_c part[c * n + i])), chunks added in index order; n8 = n / 8 outputs of 8; act = LeakyReLU with
 // `slope` (ref null) or the factor (ref[i] > 0 ? 1 : slope).  y_hi non-null: the output, `cout` channels per voxel, is
-// written as two tensors of cout / 2 channels per voxel (y the low half, y_hi the high half); cout / 2 % 8 == 0
+// written as two tensors of cout / 2 channels per voxel (y the low half, y_hi the high half); cout / 2 % 8 == 0.
+// add non-null (with ref): the sum is rounded to bf16, add[i] is added and the factor applied, then rounded again.
 __global__ void sum_chunks_bf16_kernel(const float* __restrict__ part, uint16_t* __restrict__ y, long long n8, long long n, int nch,
-                                       float slope, const uint16_t* __restrict__ ref, uint16_t* __restrict__ y_hi, int cout);
+                                       float slope, const uint16_t* __restrict__ ref, uint16_t* __restrict__ y_hi, int cout,
+                                       const uint16_t* __restrict__ add);
 __global__ void reduce_partials_kernel(const float* __restrict__ part, float* __restrict__ out, long long n, int parts);
 // out[i] = sum_p part[p * n + i] in an order fixed by (n, parts); picks the kernel by the number of parts
 int reduce_partials(const float* part, float* out, long long n, int parts, hipStream_t s);
@@ -120,6 +125,7 @@ bool dgrad_s2_supported(const Geom& g);
 size_t dgrad_s2_workspace_bytes(const Geom& g);
 int dgrad_s2(const Geom& g, const void* dy, const void* w, void* dx, void* ws, size_t ws_bytes, hipStream_t s);
 bool dgrad_s2_fuses_factor(const Geom& g);
+bool dgrad_s2_fuses_skip(const Geom& g);   // the added second gradient of a skip connection
 
 
 // 1x1x1 convolution to <= 4 output channels (segmentation head), all passes

@@ -464,6 +464,14 @@ class UNetStep:
                         # the data gradient applies that LeakyReLU's derivative as well
                         mc.conv3d_dgrad_lrelu(op["desc"], da, self.w[op["w"]], self._need(op["src"]), SLOPE, nxt, self.ws)
                         premasked = True
+                    elif op["src"].id in dskip and dskip[op["src"].id][1] == 0 and trace is None:
+                        # the input is also a skip connection whose second gradient is a tensor of its own: the
+                        # data gradient adds it and applies the derivative of the producing layer in the same call
+                        # (with normalisation the derivative is not a factor: the call only adds, slope 1)
+                        d_skip, _ = dskip.pop(op["src"].id)
+                        mc.conv3d_dgrad_skip(op["desc"], da, self.w[op["w"]], d_skip, self._need(op["src"]),
+                                             1.0 if self.norm else SLOPE, nxt, self.ws)
+                        premasked = not self.norm
                     else:
                         mc.conv3d_dgrad(op["desc"], da, self.w[op["w"]], nxt, self.ws)
                     da = nxt

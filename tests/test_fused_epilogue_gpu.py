@@ -69,6 +69,46 @@ def test_fwd_lrelu_and_dgrad_lrelu(device, case):
     assert e_f <= tol and e_neg <= tol and e_d <= tol
 
 
+SKIP_CASES = [
+    # N, D, H, W, Cin, Cout, k, s, p
+    (1, 12, 14, 34, 32, 64, 3, 2, 1),     # stride-2 data gradient, sum and factor in the store path; ragged patch tails
+    (1, 11, 13, 35, 32, 64, 3, 2, 1),     # odd extents: the last plane, row and column pair are half outside
+    (1, 8, 10, 12, 32, 64, 3, 2, 0),      # no padding
+    (1, 12, 12, 12, 64, 128, 3, 2, 1),    # chunked data gradient: sum and factor while the chunks are added
+    (1, 4, 6, 6, 256, 320, 3, 2, 1),
+    (1, 9, 21, 37, 32, 32, 3, 2, 1),      # Cout 32: two passes
+    (1, 8, 16, 32, 32, 32, 3, 1, 1),      # stride 1: two passes
+]
+
+
+@pytest.mark.parametrize("case", SKIP_CASES)
+@pytest.mark.parametrize("slope", [ou.SLOPE, 1.0])
+def test_dgrad_skip_is_the_data_gradient_plus_the_skip_gradient_through_the_activation(device, case, slope):
+    from paper_1812_07816_amd import glue
+    N, D, H, W, Cin, Cout, k, s, p = case
+    x, w, dy = si.conv_case(96, 10 * SKIP_CASES.index(case), N, D, H, W, Cin, Cout, k, s, p, True)
+    add = si.normal(96, 10 * SKIP_CASES.index(case) + 5, x.shape, bf16=True)
+    g = oc.shape(N, D, H, W, Cin, Cout, k, s, p)
+    desc = mc.make_desc(N, D, H, W, Cin, Cout, k, s, p, torch.bfloat16)
+    xd, wd, dyd, addd = (parity.to_device(t, True) for t in (x, w, dy, add))
+    # x doubles as the activated skip tensor (mixed signs)
+    out = torch.full_like(xd, 7.0)
+    mc.conv3d_dgrad_skip(desc, dyd, wd, addd, xd, slope, out)
+    # the bits of the two separate passes
+    two = mc.conv3d_dgrad(desc, dyd, wd)
+    glue.skip_grad(two, addd, 0, xd, slope)
+    assert torch.equal(out, two)
+    total = oc.dgrad(g, dy, w) + add.astype(np.float64)
+    ref = np.where(x > 0, total, slope * total)
+    e = oc.rel_err(parity.to_host(out), ref)
+    print(case, slope, f"{e:.2e}", flush=True)
+    # Two roundings: the data gradient is rounded to bf16 before the second gradient is added, so the first error
+    # (2^-9 of the data gradient) is measured against the sum, which can be several times smaller; the second is the
+    # usual 2^-9.  Twice the tolerance of a plain pass covers both; the elementwise pass itself is pinned bit for bit
+    # against numpy in the glue tests.
+    assert e <= 2 * parity.TOL["bf16"]
+
+
 def test_epilogue_argument_checks(device):
     desc = mc.make_desc(1, 4, 4, 4, 32, 32, 3, 1, 1, torch.bfloat16)
     x = torch.zeros((1, 4, 4, 4, 32), dtype=torch.bfloat16, device="cuda")
