@@ -294,9 +294,12 @@ int c4_fwd(const Geom& g, const void* x, const void* w, void* y, void* ws, size_
 // covers 16 couts x 32 voxels.  Both operands come from transposing LDS reads;
 // for x each lane passes the address of the voxel shifted by its own kw, so
 // the staged rows need no rearrangement.  A workgroup walks a contiguous range
-// of 16 x 32 dy patches, keeps its 9 accumulators per wave in registers, and
-// writes one partial-sum slot per wave pair; a second kernel adds the slots in
-// index order (bit-reproducible) and drops the padding columns.
+// of 16 x 32 dy patches, plane after plane along D for one patch position, and
+// keeps the three x planes of a patch as a ring in LDS: from one patch to the
+// next along D only one new x plane is fetched.  It keeps its 9 accumulators
+// per wave in registers and writes one partial-sum slot per wave pair; a second
+// kernel adds the slots in index order (bit-reproducible) and drops the padding
+// columns.
 namespace mi3d {
 namespace {
 
@@ -316,9 +319,11 @@ struct C4WgParams {
     const uint16_t* dy;
     float* part;   // [slot][Cout][9][16]
     int N, D, H, W, Cout, Do, Ho, Wo, pD, pH, pW, HT, WT;
-    long long tiles;  // N*Do*HT*WT
+    long long tiles;  // N*HT*WT*Do, the plane index running fastest
     int nwg;
 };
+
+__device__ __forceinline__ int c4_mod3(int v) { return ((v % 3) + 3) % 3; }
 
 __device__ __forceinline__ bf16x8 tr8(const char* p0, const char* p1) {
     typedef __attribute__((address_space(3))) s16x4* lptr;
@@ -352,13 +357,17 @@ __global__ void __launch_bounds__(256, 2) c4_wgrad_kernel(C4WgParams P) {
     // patch loads of one tile into registers (zero outside the volume)
     uint2 px[NLOAD3];
     uint4 pdy[WNDY];
+    // A tile that continues the previous one along D (same patch position, next plane) needs only the x plane of
+    // tap kd = 2; the other two are in the ring already.
+    auto continues = [&](long long tile) { return tile > t0 && tile % P.Do != 0; };
     auto load_tile = [&](long long tile) {
         long long b = tile;
+        const int od = (int)(b % P.Do); b /= P.Do;
         const int wt = (int)(b % P.WT); b /= P.WT;
-        const int ht = (int)(b % P.HT); b /= P.HT;
-        const int od = (int)(b % P.Do);
-        const int n = (int)(b / P.Do);
+        const int ht = (int)(b % P.HT);
+        const int n = (int)(b / P.HT);
         const int h0 = ht * TH, w0 = wt * TW;
+        const int first_pl = continues(tile) ? 2 : 0;
 #pragma unroll
         for (int i = 0; i < NLOAD3; ++i) {
             const int q = t + 256 * i;
@@ -366,7 +375,7 @@ __global__ void __launch_bounds__(256, 2) c4_wgrad_kernel(C4WgParams P) {
             const int row = rem / PCOLS, col = rem - row * PCOLS;
             const int gd = od - P.pD + pl, gh = h0 - P.pH + row, gw = w0 - P.pW + col;
             px[i] = uint2{0u, 0u};
-            if (q < NVOX3 && gd >= 0 && gd < P.D && gh >= 0 && gh < P.H && gw >= 0 && gw < P.W)
+            if (q < NVOX3 && pl >= first_pl && gd >= 0 && gd < P.D && gh >= 0 && gh < P.H && gw >= 0 && gw < P.W)
                 px[i] = *(const uint2*)(P.x + ((((long long)n * P.D + gd) * P.H + gh) * P.W + gw) * 4);
         }
 #pragma unroll
@@ -378,13 +387,16 @@ __global__ void __launch_bounds__(256, 2) c4_wgrad_kernel(C4WgParams P) {
                 pdy[i] = *(const uint4*)(P.dy + ((((long long)n * P.Do + od) * P.Ho + gh) * P.Wo + gw) * P.Cout + cot * 32 + c * 8);
         }
     };
-    auto write_tile = [&]() {
+    // x plane ip of a patch lives in ring slot ip mod 3
+    auto write_tile = [&](long long tile) {
+        const int ip0 = (int)(tile % P.Do) - P.pD;
+        const int first_pl = continues(tile) ? 2 : 0;
 #pragma unroll
         for (int i = 0; i < NLOAD3; ++i) {
             const int q = t + 256 * i;
             const int pl = q / (PR * PCOLS), rem = q - pl * (PR * PCOLS);
             const int row = rem / PCOLS, col = rem - row * PCOLS;
-            if (q < NVOX3) *(uint2*)(x_lds + (pl * PLANE + row * PITCH + col) * 8) = px[i];
+            if (q < NVOX3 && pl >= first_pl) *(uint2*)(x_lds + (c4_mod3(ip0 + pl) * PLANE + row * PITCH + col) * 8) = px[i];
         }
 #pragma unroll
         for (int i = 0; i < WNDY; ++i) {
@@ -396,11 +408,12 @@ __global__ void __launch_bounds__(256, 2) c4_wgrad_kernel(C4WgParams P) {
     if (t0 < t1) load_tile(t0);
     for (long long tile = t0; tile < t1; ++tile) {
         __syncthreads();  // readers of the previous tile are done
-        write_tile();
+        write_tile(tile);
         __syncthreads();
         if (tile + 1 < t1) load_tile(tile + 1);  // in flight during the MFMA work below
 
         // this wave's 8 dy rows, then every x row that meets them
+        const int ip0 = (int)(tile % P.Do) - P.pD;
         bf16x8 dyf[TH / 2];
 #pragma unroll
         for (int r = 0; r < TH / 2; ++r) {
@@ -411,7 +424,7 @@ __global__ void __launch_bounds__(256, 2) c4_wgrad_kernel(C4WgParams P) {
         for (int kd = 0; kd < 3; ++kd)
 #pragma unroll
             for (int rr = 0; rr < TH / 2 + 2; ++rr) {
-                const char* p = x_lane + (kd * PLANE + (rh * (TH / 2) + rr) * PITCH) * 8;
+                const char* p = x_lane + (c4_mod3(ip0 + kd) * PLANE + (rh * (TH / 2) + rr) * PITCH) * 8;
                 const bf16x8 xf = tr8(p, p + 16 * 8);
 #pragma unroll
                 for (int kh = 0; kh < 3; ++kh) {
