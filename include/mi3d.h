@@ -147,6 +147,18 @@ int mi3d_conv3d_wgrad_pair(const mi3d_conv_desc *desc, const void *x_lo, const v
 int mi3d_conv3d_dgrad_skip(const mi3d_conv_desc *desc, const void *dy, const void *w, const void *add, const void *a_in,
                            float slope, void *dx, void *ws, size_t ws_bytes, void *stream);
 
+/* Convolution whose kernel also produces the statistics of its output for the instance normalisation that follows it
+ * (Section 4.1: convolution, instance normalisation, LeakyReLU): y as mi3d_conv3d_fwd (or mi3d_conv3d_fwd_pair when
+ * x_hi is not null: x then is the low half), and stats[n][c] = (mean, 1 / sqrt(var + eps)) of the stored bf16 values of
+ * y over the voxels of sample n, biased variance, as mi3d_instnorm_stats computes them in a pass of its own (same
+ * values up to the order of the fp32 partial sums; the order is fixed, so repeated calls give identical bits).
+ * stats: N * Cout * 2 floats, device.  Only the unchunked bf16 3x3x3 stride-1 MFMA forward kernels do this
+ * (mi3d_conv3d_fwd_stats_supported tells, 1 / 0); other geometries return MI3D_ERR_UNSUPPORTED and the caller runs
+ * the two passes.  Workspace as for mi3d_conv3d_fwd. */
+int mi3d_conv3d_fwd_stats_supported(const mi3d_conv_desc *desc);
+int mi3d_conv3d_fwd_stats(const mi3d_conv_desc *desc, const void *x, const void *x_hi, const void *w, void *y,
+                          float eps, float *stats, void *ws, size_t ws_bytes, void *stream);
+
 /* Convolution followed by the network's LeakyReLU (Section 4.1) in one call:
  * y = lrelu(conv(x, w)), lrelu(v) = v > 0 ? v : slope * v, applied to the fp32
  * accumulator before the single rounding to bf16.  bf16 only, 0 <= slope < 1

@@ -172,6 +172,30 @@ def conv3d_dgrad_skip(desc, dy, w, add, a_in, slope, dx=None, ws=None):
     return dx
 
 
+def fwd_stats_supported(desc):
+    """True if the forward kernel of this geometry can produce the instance-normalisation statistics of its output."""
+    return bool(lib().mi3d_conv3d_fwd_stats_supported(ctypes.byref(desc)))
+
+
+def conv3d_fwd_stats(desc, x, w, stats, eps=1e-5, y=None, ws=None, x_hi=None):
+    """y = conv(x, w) (x = [x | x_hi] when x_hi is given) and stats[n][c] = (mean, rstd) of y, in one kernel."""
+    xs, wsh, ys = _shapes(desc)
+    dt = _tdtype(desc)
+    if x_hi is None:
+        _chk(x, xs, dt, "x")
+    else:
+        _chk(x, _half(desc), dt, "x_lo"); _chk(x_hi, _half(desc), dt, "x_hi")
+    _chk(w, wsh, dt, "w")
+    _chk(stats, (desc.N, desc.Cout, 2), torch.float32, "stats")
+    if y is None:
+        y = torch.empty(ys, dtype=dt, device=x.device)
+    _chk(y, ys, dt, "y")
+    ws, p, n = _ws(desc, PASS_FWD, ws)
+    check(lib().mi3d_conv3d_fwd_stats(ctypes.byref(desc), x.data_ptr(), None if x_hi is None else x_hi.data_ptr(), w.data_ptr(), y.data_ptr(),
+                                      ctypes.c_float(eps), stats.data_ptr(), p, n, _stream()), "conv3d_fwd_stats")
+    return y
+
+
 def pair_supported(desc, pass_):
     """True if the pass takes the tensor of x's shape as two halves along the channels (conv3d_*_pair)."""
     return bool(lib().mi3d_conv3d_pair_supported(ctypes.byref(desc), int(pass_)))

@@ -285,6 +285,28 @@ int mi3d_conv3d_dgrad_skip(const mi3d_conv_desc* desc, const void* dy, const voi
     return mi3d_skip_grad(dx, add, g.Cin, 0, a_in, g.Cin, (size_t)g.in_voxels(), slope, stream);
 }
 
+int mi3d_conv3d_fwd_stats_supported(const mi3d_conv_desc* desc) {
+    Geom g;
+    if (make_geom(desc, &g) || g_family.load() == 1) return 0;
+    return choose(g, MI3D_PASS_FWD) == K_SP && sp_fuses_stats(g) ? 1 : 0;
+}
+
+int mi3d_conv3d_fwd_stats(const mi3d_conv_desc* desc, const void* x, const void* x_hi, const void* w, void* y, float eps, float* stats,
+                          void* ws, size_t ws_bytes, void* stream) {
+    Geom g;
+    int st = make_geom(desc, &g);
+    if (st) return st;
+    if (!x || !w || !y || !stats || !aligned16(x) || !aligned16(x_hi) || !aligned16(w) || !aligned16(y) || !aligned16(ws) || !(eps > 0.f))
+        return MI3D_ERR_INVALID_ARG;
+    if (ws_bytes && !ws) return MI3D_ERR_INVALID_ARG;
+    if (!mi3d_conv3d_fwd_stats_supported(desc) || (x_hi && !pair_supported(g, MI3D_PASS_FWD))) return MI3D_ERR_UNSUPPORTED;
+    if (ws_bytes < mi3d_conv3d_workspace_bytes(desc, MI3D_PASS_FWD)) return MI3D_ERR_WORKSPACE;
+    g.hi = x_hi;
+    g.stats = stats;
+    g.stats_eps = eps;
+    return run_kernel(K_SP, g, MI3D_PASS_FWD, x, w, y, ws, ws_bytes, (hipStream_t)stream);
+}
+
 int mi3d_conv3d_pair_supported(const mi3d_conv_desc* desc, int pass) {
     Geom g;
     if (make_geom(desc, &g) || pass < 0 || pass > 2) return 0;

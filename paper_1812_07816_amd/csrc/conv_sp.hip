@@ -51,6 +51,11 @@ struct SpParams {
     const uint16_t* x2;
     uint16_t* y2;
     int xpitch, ypitch, xsplit, ysplit;
+    // STATS variant: per-(workgroup, segment, wave) sums of y and y^2 over the voxels, 32 couts each:
+    // [logical workgroup][segment of its unit range][wave][sum, sum of squares][32 couts]
+    float* stat_part;
+    int* stat_key;          // [logical workgroup][segment]: sample * CT + cout tile of the partial, -1 = unused
+    int max_seg;
     long long units;        // N*CT*HT*WT*Do
     int nwg;
 };
@@ -230,10 +235,15 @@ __device__ __forceinline__ void store_row(const uint32_t (&o)[8], uint16_t* p, b
 // PART (with NC = 1): the 32-channel chunks of Cin are separate work units whose weights (54 KB) stay resident; each
 // writes fp32 partial outputs and a second kernel adds the chunks in index order.  For the deep, small layers this is
 // two to three times faster than streaming the weights of all chunks through LDS for every staged plane.
+// STATS (forward, not with PART or MASK): the kernel also adds up y and y^2 per output channel (of the bf16 values it
+// stores) for the instance normalisation that follows the convolution (Section 4.1).  Every lane keeps the sums of its
+// 16 couts over the rows and planes of a segment; at the end of the segment they are added over the 32 voxel lanes in
+// a fixed butterfly and written as one partial per (workgroup, segment, wave).  A second kernel adds the partials of a
+// (sample, channel) in index order in double.
 // MASK (data gradient, not with PART): every output element is multiplied by 1 where P.ref is > 0 and by P.slope
 // elsewhere (LeakyReLU derivative of the layer below) after its rounding to bf16 and rounded again: the bits of the
 // plain kernel followed by an elementwise pass, without that pass's read and write of the gradient.
-template <int NC, bool PART = false, bool MASK = false>
+template <int NC, bool PART = false, bool MASK = false, bool STATS = false>
 __global__ void __launch_bounds__(256, 1) sp_conv_kernel(SpParams P) {
     extern __shared__ __attribute__((aligned(16))) char lds[];
     constexpr bool STREAM = NC == 0;
@@ -275,6 +285,7 @@ __global__ void __launch_bounds__(256, 1) sp_conv_kernel(SpParams P) {
     const char* w_lane = w_lds + lane * 16;
 
     int cur_ct = -1;
+    int seg = 0;   // STATS: index of the segment within this workgroup's unit range
     while (u0 < u1) {
         long long column = u0 / P.Do;
         int od_start = (int)(u0 - column * P.Do);
@@ -396,8 +407,22 @@ __global__ void __launch_bounds__(256, 1) sp_conv_kernel(SpParams P) {
                 mk[r][1] = *(const uint4*)(q + 8);
             }
         };
+        float st1[STATS ? 16 : 1], st2[STATS ? 16 : 1];   // STATS: this lane's sums over the segment (its 16 couts)
+        if constexpr (STATS) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) st1[i] = st2[i] = 0.f;
+        }
         auto store_piece = [&](int r) {
             const bool ok = st_pending && ow_ < P.Wo && h0 + wave * RH + r < P.Ho;
+            if (STATS && st_pending) {   // (uniform: stages with nothing to store skip the arithmetic)
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    const uint32_t v = ok ? outp[r][i] : 0u;
+                    const float lo = __builtin_bit_cast(float, v << 16), hi = __builtin_bit_cast(float, v & 0xffff0000u);
+                    st1[2 * i] += lo; st2[2 * i] = fmaf(lo, lo, st2[2 * i]);
+                    st1[2 * i + 1] += hi; st2[2 * i + 1] = fmaf(hi, hi, st2[2 * i + 1]);
+                }
+            }
             if constexpr (PART) store_row(outp[r], partn + st_off + r * row_pitch + 4 * (lane >> 5), ok, (float*)P.dump + lane * 32);
             else store_row<MASK>(outp[r], yn + st_off + r * row_pitch + 16 * (lane >> 5), ok, P.dump + lane * 16, mk[MASK ? r : 0], P.slope);
         };
@@ -487,6 +512,61 @@ __global__ void __launch_bounds__(256, 1) sp_conv_kernel(SpParams P) {
         for (int r = 0; r < RH; ++r) load_mask(r);
 #pragma unroll
         for (int r = 0; r < RH; ++r) store_piece(r);  // the last plane of the segment
+        if constexpr (STATS) {
+            // sums over the 32 voxel lanes of each lane half (fixed butterfly), then lane 0 of each half writes its 16
+            // couts: accumulator register j of half h is cout 8 (j / 4) + 4 h + j % 4 of the tile
+#pragma unroll
+            for (int i = 0; i < 16; ++i)
+#pragma unroll
+                for (int off = 16; off > 0; off >>= 1) {
+                    st1[i] += __shfl_xor(st1[i], off, 64);
+                    st2[i] += __shfl_xor(st2[i], off, 64);
+                }
+            if (t == 0) P.stat_key[g * P.max_seg + seg] = n * P.CT + ct;   // whose sums these are
+            if ((lane & 31) == 0) {
+                float* out = P.stat_part + (((long long)g * P.max_seg + seg) * 4 + wave) * 64;
+#pragma unroll
+                for (int j = 0; j < 16; ++j) {
+                    const int c = 8 * (j >> 2) + 4 * (lane >> 5) + (j & 3);
+                    out[c] = st1[j];
+                    out[32 + c] = st2[j];
+                }
+            }
+            ++seg;
+        }
+    }
+    if constexpr (STATS) {
+        if (t == 0)
+            for (; seg < P.max_seg; ++seg) P.stat_key[g * P.max_seg + seg] = -1;   // unused slots of this workgroup
+    }
+}
+
+// stats[n][c] = (mean, 1 / sqrt(var + eps)) of y over the voxels from the partial sums of the STATS variant.  A block
+// per (sample, cout tile); thread (slice s, sum q, cout c) adds the partials of every fourth workgroup in index order in
+// double (key: which (sample, cout tile) a partial belongs to), then the four slices are added in order.
+__global__ void __launch_bounds__(256) sp_stats_finish_kernel(const float* __restrict__ part, const int* __restrict__ key, int Cout, int CT,
+                                                              int nwg, int max_seg, double inv_v, float eps, float* __restrict__ stats) {
+    __shared__ double red[4][64];
+    const int t = threadIdx.x, sl = t >> 6, qc = t & 63;     // qc = 32 q + c
+    const int mine = blockIdx.x;                             // n * CT + ct
+    double a = 0.0;
+    for (int g = sl; g < nwg; g += 4)
+        for (int seg = 0; seg < max_seg; ++seg)
+            if (key[g * max_seg + seg] == mine) {
+                const float* p = part + (((long long)g * max_seg + seg) * 4) * 64;
+                for (int w = 0; w < 4; ++w) a += (double)p[w * 64 + qc];
+            }
+    red[sl][qc] = a;
+    __syncthreads();
+    if (t < 32) {
+        const double s1 = ((red[0][t] + red[1][t]) + red[2][t]) + red[3][t];
+        const double s2 = ((red[0][32 + t] + red[1][32 + t]) + red[2][32 + t]) + red[3][32 + t];
+        const double mean = s1 * inv_v;
+        double var = s2 * inv_v - mean * mean;
+        if (var < 0.0) var = 0.0;
+        const int n = mine / CT, c = (mine % CT) * 32 + t;
+        stats[2 * ((long long)n * Cout + c)] = (float)mean;
+        stats[2 * ((long long)n * Cout + c) + 1] = (float)(1.0 / sqrt(var + (double)eps));
     }
 }
 
@@ -556,6 +636,22 @@ bool sp_fuses_dgrad_factor(const Geom& g) { return sp_supported(g, MI3D_PASS_DGR
 
 static size_t sp_part_offset(const Geom& g) { return (((size_t)g.w_elems() * 2 + 255) & ~(size_t)255) + 8192; }
 
+// STATS variant (forward, unchunked): workgroups, most segments of a workgroup's unit range, bytes of the partial sums
+static void sp_stat_layout(const Geom& g, long long* units, int* nwg, int* max_seg) {
+    *units = (long long)g.N * (g.Cout / 32) * ((g.Ho + TH - 1) / TH) * ((g.Wo + TW - 1) / TW) * g.Do;
+    long long n = sp_cu_count();
+    if (n > *units) n = *units;
+    *nwg = (int)n;
+    const long long per_wg = (*units + n - 1) / n;
+    *max_seg = (int)((per_wg + g.Do - 1) / g.Do) + 1;
+}
+static size_t sp_stat_bytes(const Geom& g) {
+    long long units; int nwg, max_seg;
+    sp_stat_layout(g, &units, &nwg, &max_seg);
+    return (size_t)nwg * max_seg * (4 * 64 * sizeof(float) + sizeof(int)) + 256;
+}
+bool sp_fuses_stats(const Geom& g) { return sp_supported(g, MI3D_PASS_FWD) && !sp_use_chunks(g, MI3D_PASS_FWD); }
+
 size_t sp_workspace_bytes(const Geom& g, int pass) {
     if (!sp_supported(g, pass)) return 0;
     size_t b = sp_part_offset(g);  // packed weights + store dump area
@@ -563,6 +659,8 @@ size_t sp_workspace_bytes(const Geom& g, int pass) {
         const int cin = pass == MI3D_PASS_DGRAD ? g.Cout : g.Cin;
         const size_t out_elems = pass == MI3D_PASS_DGRAD ? (size_t)g.in_voxels() * g.Cin : (size_t)g.out_voxels() * g.Cout;
         b += (size_t)(cin / 32) * out_elems * sizeof(float);
+    } else if (pass == MI3D_PASS_FWD) {
+        b += sp_stat_bytes(g);   // partial sums of the STATS variant
     }
     return b;
 }
@@ -608,6 +706,16 @@ int sp_conv(const Geom& g, int pass, const void* in, const void* w, void* out, v
     long long nwg = sp_cu_count();
     if (nwg > P.units) nwg = P.units;
     P.nwg = (int)nwg;
+    const bool stat = pass == MI3D_PASS_FWD && g.stats;
+    if (stat && chunks) return MI3D_ERR_UNSUPPORTED;
+    P.stat_part = P.part;   // same place in the workspace as the chunked variant's partial outputs
+    P.max_seg = 1;
+    P.stat_key = nullptr;
+    if (stat) {
+        long long units; int n2;
+        sp_stat_layout(g, &units, &n2, &P.max_seg);
+        P.stat_key = (int*)(P.stat_part + (size_t)n2 * P.max_seg * 4 * 64);
+    }
     const int nc = P.Cin / 32;
     const size_t lds1 = W_BYTES + 2 * STAGE_BYTES, lds2 = 2 * W_BYTES + STAGE_BYTES;
     static bool attr_set = false;
@@ -619,6 +727,9 @@ int sp_conv(const Geom& g, int pass, const void* in, const void* w, void* out, v
         if (e == hipSuccess) e = hipFuncSetAttribute((const void*)sp_conv_kernel<1, false, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds1);
         if (e == hipSuccess) e = hipFuncSetAttribute((const void*)sp_conv_kernel<2, false, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds2);
         if (e == hipSuccess) e = hipFuncSetAttribute((const void*)sp_conv_kernel<0, false, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds1);
+        if (e == hipSuccess) e = hipFuncSetAttribute((const void*)sp_conv_kernel<1, false, false, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds1);
+        if (e == hipSuccess) e = hipFuncSetAttribute((const void*)sp_conv_kernel<2, false, false, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds2);
+        if (e == hipSuccess) e = hipFuncSetAttribute((const void*)sp_conv_kernel<0, false, false, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds1);
         if (e != hipSuccess) { note_hip_error(e); return MI3D_ERR_HIP; }
         attr_set = true;
     }
@@ -631,6 +742,16 @@ int sp_conv(const Geom& g, int pass, const void* in, const void* w, void* out, v
         if (blocks > 8192) blocks = 8192;
         sum_chunks_bf16_kernel<<<(unsigned)blocks, 256, 0, s>>>(P.part, (uint16_t*)out, n / 8, n, P.NCH, g.slope, pass == MI3D_PASS_DGRAD ? (const uint16_t*)g.ref : nullptr,
                                                                 flip && g.hi ? (uint16_t*)g.hi : nullptr, P.Cout, nullptr);
+        return check_launch();
+    }
+    if (stat) {
+        if (nc == 1) sp_conv_kernel<1, false, false, true><<<(unsigned)nwg, 256, lds1, s>>>(P);
+        else if (nc == 2) sp_conv_kernel<2, false, false, true><<<(unsigned)nwg, 256, lds2, s>>>(P);
+        else sp_conv_kernel<0, false, false, true><<<(unsigned)nwg, 256, lds1, s>>>(P);
+        st = check_launch();
+        if (st) return st;
+        sp_stats_finish_kernel<<<P.N * P.CT, 256, 0, s>>>(P.stat_part, P.stat_key, P.Cout, P.CT, P.nwg, P.max_seg,
+                                                          1.0 / ((double)P.Do * P.Ho * P.Wo), g.stats_eps, g.stats);
         return check_launch();
     }
     if (mask && nc == 1) sp_conv_kernel<1, false, true><<<(unsigned)nwg, 256, lds1, s>>>(P);

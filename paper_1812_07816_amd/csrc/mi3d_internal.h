@@ -31,6 +31,10 @@ struct Geom {
     // Optional second gradient of dx's shape added to the bf16-rounded data gradient before the factor of `ref` /
     // `slope` is applied (skip connection).  Set by the dispatcher only for kernels that implement it.
     const void* add = nullptr;
+    // Optional statistics of the forward output for the instance normalisation that follows: stats[n][c] =
+    // (mean, 1 / sqrt(var + stats_eps)) over the voxels.  Set by the dispatcher only for kernels that implement it.
+    float* stats = nullptr;
+    float stats_eps = 0.f;
     __host__ __device__ long long in_voxels() const { return (long long)N * D * H * W; }
     __host__ __device__ long long out_voxels() const { return (long long)N * Do * Ho * Wo; }
     __host__ __device__ long long taps() const { return (long long)kD * kH * kW; }
@@ -75,6 +79,7 @@ bool sp_supported(const Geom& g, int pass);
 size_t sp_workspace_bytes(const Geom& g, int pass);
 int sp_conv(const Geom& g, int pass, const void* in, const void* w, void* out, void* ws, size_t ws_bytes, hipStream_t s);
 bool sp_fuses_dgrad_factor(const Geom& g);  // the forward LeakyReLU is always fused
+bool sp_fuses_stats(const Geom& g);         // instance-normalisation statistics of the forward output
 
 
 // MFMA weight gradient: bf16, 3x3x3, stride 1, channels in multiples of 32

@@ -47,7 +47,7 @@ class _Saved:
 class UNetStep:
     def __init__(self, N, vol, channels, weights, x, labels, lr=1e-2, in_ch=4, classes=3, swap=True,
                  budget_bytes=None, lookahead=2, policy=sw.POLICY_BUDGET, n_tensors=-1, exclude_tags=0,
-                 eviction=sw.EVICT_SWAP, optimizer="sgd", norm=False, virtual_cat=True):
+                 eviction=sw.EVICT_SWAP, optimizer="sgd", norm=False, virtual_cat=True, fused_stats=True):
         """weights: list of float32 CPU tensors/arrays (bf16-exact start values) in the order enc convs,
         (dec up, conv1, conv2) from the deepest decoder level up, head; x: bf16 CUDA [N,vol,vol,vol,in_ch];
         labels: uint8 CUDA [N,vol,vol,vol,classes]."""
@@ -189,6 +189,7 @@ class UNetStep:
             for op in self.ops:
                 if op["kind"] == "conv":
                     op["stats"] = torch.zeros((N, op["out"].shape[-1], 2), dtype=torch.float32, device="cuda")
+                    op["fused_stats"] = fused_stats and mc.fwd_stats_supported(op["desc"])
         self.sums = torch.zeros(3 * classes, dtype=torch.float32, device="cuda")
         self.loss = torch.zeros(1, dtype=torch.float32, device="cuda")
         # ---- swap engine
@@ -315,23 +316,29 @@ class UNetStep:
 
     def _forward_conv(self, op):
         out = self._produce(op["out"])
-        pair = op.get("src2") is not None
-        if pair and self.norm:
-            mc.conv3d_fwd_pair(op["desc"], op["src"].view, op["src2"].view, self.w[op["w"]], 1.0, out, self.ws)
-        elif pair:
-            mc.conv3d_fwd_pair(op["desc"], op["src"].view, op["src2"].view, self.w[op["w"]], SLOPE, out, self.ws)
-            return out
-        elif op["kind"] == "conv" and self.norm:
-            mc.conv3d_fwd(op["desc"], op["src"].view, self.w[op["w"]], out, self.ws)
+        d, w = op["desc"], self.w[op["w"]]
+        x, x_hi = op["src"].view, (op["src2"].view if op.get("src2") is not None else None)
         if op["kind"] == "conv" and self.norm:
+            # convolution -> instance normalisation -> LeakyReLU; the statistics come out of the convolution kernel
+            # where it can produce them, else from a pass of their own
+            if op["fused_stats"]:
+                mc.conv3d_fwd_stats(d, x, w, op["stats"], glue.IN_EPS, out, self.ws, x_hi=x_hi)
+            else:
+                if x_hi is not None:
+                    mc.conv3d_fwd_pair(d, x, x_hi, w, 1.0, out, self.ws)
+                else:
+                    mc.conv3d_fwd(d, x, w, out, self.ws)
+                glue.instnorm_stats(out, op["stats"], self.in_ws)
             if self._trace is not None:
                 self._trace[op["name"] + ".z"] = out.clone()
-            glue.instnorm_stats(out, op["stats"], self.in_ws)
+                self._trace[op["name"] + ".stats"] = op["stats"].clone()
             glue.instnorm_lrelu_fwd(out, op["stats"], SLOPE)
+        elif op["kind"] == "conv" and x_hi is not None:
+            mc.conv3d_fwd_pair(d, x, x_hi, w, SLOPE, out, self.ws)
         elif op["kind"] == "conv":
-            mc.conv3d_fwd_lrelu(op["desc"], op["src"].view, self.w[op["w"]], SLOPE, out, self.ws)
+            mc.conv3d_fwd_lrelu(d, x, w, SLOPE, out, self.ws)
         else:
-            mc.conv3d_fwd(op["desc"], op["src"].view, self.w[op["w"]], out, self.ws)
+            mc.conv3d_fwd(d, x, w, out, self.ws)
         return out
 
     def _after_bwd_op(self, op):

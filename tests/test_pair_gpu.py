@@ -1,7 +1,8 @@
 """GPU-vs-oracle parity of the virtual-concatenation entry points (conv3d_fwd_pair, conv3d_dgrad_pair,
 conv3d_wgrad_pair): the decoder's first convolution of a level reads [up-sampled | skip] as two tensors.  The oracle
 side concatenates with numpy and runs the plain fp64 passes; the plain GPU calls on the materialised concatenation
-must give the same bits."""
+must give the same bits.  Also here: conv3d_fwd_stats, the forward pass that hands out the instance-normalisation
+statistics of its output (plain and two-tensor input)."""
 import ctypes
 
 import numpy as np
@@ -86,3 +87,63 @@ def test_pairs_are_refused_where_no_kernel_takes_them(device):
         st = lib().mi3d_conv3d_fwd_pair(ctypes.byref(d), lo.data_ptr(), hi_ptr, w.data_ptr(), y.data_ptr(), ctypes.c_float(1.0),
                                         ws.data_ptr(), ws.numel(), None)
         assert st == -1, st
+
+
+STATS_CASES = [
+    # N, D, H, W, Cin, Cout, pad, two-tensor input
+    (2, 6, 20, 40, 32, 32, 1, False),    # one chunk; two samples
+    (1, 9, 17, 33, 32, 64, 1, False),    # two cout tiles, ragged patches
+    (2, 5, 18, 34, 64, 32, 1, True),     # two resident chunks, halves
+    (2, 33, 33, 66, 128, 32, 1, True),   # streamed weights (enough units to stay unchunked), halves
+    (3, 4, 9, 70, 64, 96, 2, False),     # three samples, pad 2, three cout tiles
+]
+
+
+@pytest.mark.parametrize("case", STATS_CASES)
+def test_forward_statistics_match_the_separate_pass_and_the_oracle(device, case):
+    from oracle import unet as ou
+    from paper_1812_07816_amd import glue
+    N, D, H, W, Cin, Cout, p, pair = case
+    x, w, _ = si.conv_case(98, 10 * STATS_CASES.index(case), N, D, H, W, Cin, Cout, 3, 1, p, True)
+    desc = mc.make_desc(N, D, H, W, Cin, Cout, 3, 1, p, torch.bfloat16)
+    assert mc.fwd_stats_supported(desc)
+    xd, wd = parity.to_device(x, True), parity.to_device(w, True)
+    stats = torch.full((N, Cout, 2), 7.0, device="cuda")
+    if pair:
+        h = Cin // 2
+        y = mc.conv3d_fwd_stats(desc, xd[..., :h].contiguous(), wd, stats, x_hi=xd[..., h:].contiguous())
+    else:
+        y = mc.conv3d_fwd_stats(desc, xd, wd, stats)
+    assert torch.equal(y, mc.conv3d_fwd(desc, xd, wd))           # the convolution itself is unchanged
+    again = torch.zeros_like(stats)
+    mc.conv3d_fwd_stats(desc, xd, wd, again) if not pair else mc.conv3d_fwd_stats(
+        desc, xd[..., :Cin // 2].contiguous(), wd, again, x_hi=xd[..., Cin // 2:].contiguous())
+    assert torch.equal(stats, again)                             # fixed summation order
+    # the separate pass over the stored tensor
+    ref = torch.zeros_like(stats)
+    glue.instnorm_stats(y, ref, glue.instnorm_workspace(N, Cout))
+    got, sep = stats.cpu().numpy().astype(np.float64), ref.cpu().numpy().astype(np.float64)
+    # the oracle's statistics of the same stored values (fp64)
+    yh = parity.to_host(y).astype(np.float64)
+    mean = yh.mean(axis=(1, 2, 3))
+    rstd = 1.0 / np.sqrt(yh.var(axis=(1, 2, 3)) + ou.IN_EPS)
+    scale = np.sqrt(yh.var(axis=(1, 2, 3)))                      # a mean is as good as its size against the spread
+    e_mean = np.abs(got[..., 0] - mean).max() / scale.max()
+    e_rstd = np.abs(got[..., 1] / rstd - 1).max()
+    e_sep = max(np.abs(got[..., 0] - sep[..., 0]).max() / scale.max(), np.abs(got[..., 1] / sep[..., 1] - 1).max())
+    print(case, f"mean {e_mean:.2e} rstd {e_rstd:.2e} vs separate pass {e_sep:.2e}", flush=True)
+    assert e_mean <= 1e-6 and e_rstd <= 1e-6 and e_sep <= 1e-6
+
+
+def test_forward_statistics_are_refused_where_the_kernel_cannot_produce_them(device):
+    bf = torch.bfloat16
+    for args in ((1, 12, 12, 12, 320, 320, 3, 1, 1),   # chunked variant
+                 (1, 8, 8, 8, 32, 64, 3, 2, 1),        # stride 2
+                 (1, 8, 8, 8, 4, 32, 3, 1, 1)):        # first layer
+        d = mc.make_desc(*args, bf)
+        assert not mc.fwd_stats_supported(d), args
+        N, D, H, W, Cin, Cout, k = args[:7]
+        x = torch.zeros((N, D, H, W, Cin), dtype=bf, device="cuda")
+        w = torch.zeros((Cout, k, k, k, Cin), dtype=bf, device="cuda")
+        with pytest.raises(Mi3dError):
+            mc.conv3d_fwd_stats(d, x, w, torch.zeros((N, Cout, 2), device="cuda"))
