@@ -12,7 +12,7 @@
 namespace mi3d {
 namespace {
 
-constexpr int IN_BLOCKS = 256;   // voxel ranges per sample
+constexpr int IN_BLOCKS = 512;   // voxel ranges per sample
 constexpr int MAXC = 512;
 
 __device__ __forceinline__ void unpack8(const uint4& v, float (&f)[8]) {
@@ -51,26 +51,44 @@ __global__ void __launch_bounds__(256) in_reduce_kernel(const uint16_t* __restri
 #pragma unroll
     for (int j = 0; j < 8; ++j) s1[j] = s2[j] = 0.f;
     const float inv_slope = 1.f / slope;
-    if (lane < VPB)
-        for (long long v = v0 + lane; v < v1; v += VPB) {
-            const long long off = ((long long)n * voxels + v) * C + p * 8;
-            float x[8];
-            unpack8(*(const uint4*)(a + off), x);
-            if (MODE == 0) {
+    // one voxel's contribution; the loop below requests four voxels ahead of the arithmetic (the sums are added in
+    // voxel order either way)
+    auto add_voxel = [&](const uint4& av, const uint4& gv) {
+        float x[8];
+        unpack8(av, x);
+        if (MODE == 0) {
 #pragma unroll
-                for (int j = 0; j < 8; ++j) { s1[j] += x[j]; s2[j] = fmaf(x[j], x[j], s2[j]); }
-            } else {
-                float g[8];
-                unpack8(*(const uint4*)(da + off), g);
+            for (int j = 0; j < 8; ++j) { s1[j] += x[j]; s2[j] = fmaf(x[j], x[j], s2[j]); }
+        } else {
+            float g[8];
+            unpack8(gv, g);
 #pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    const float gg = x[j] > 0.f ? g[j] : slope * g[j];
-                    const float xh = x[j] > 0.f ? x[j] : x[j] * inv_slope;
-                    s1[j] += gg;
-                    s2[j] = fmaf(gg, xh, s2[j]);
-                }
+            for (int j = 0; j < 8; ++j) {
+                const float gg = x[j] > 0.f ? g[j] : slope * g[j];
+                const float xh = x[j] > 0.f ? x[j] : x[j] * inv_slope;
+                s1[j] += gg;
+                s2[j] = fmaf(gg, xh, s2[j]);
             }
         }
+    };
+    if (lane < VPB) {
+        const long long base = (long long)n * voxels * C + p * 8;
+        long long v = v0 + lane;
+        for (; v + 3 * VPB < v1; v += 4 * VPB) {
+            uint4 av[4], gv[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                av[u] = *(const uint4*)(a + base + (v + u * VPB) * C);
+                gv[u] = MODE == 0 ? av[u] : *(const uint4*)(da + base + (v + u * VPB) * C);
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) add_voxel(av[u], gv[u]);
+        }
+        for (; v < v1; v += VPB) {
+            const uint4 av = *(const uint4*)(a + base + v * C);
+            add_voxel(av, MODE == 0 ? av : *(const uint4*)(da + base + v * C));
+        }
+    }
     float* out = part + ((long long)n * gridDim.x + blockIdx.x) * 2 * C;
     for (int q = 0; q < 2; ++q) {
         __syncthreads();
@@ -87,18 +105,28 @@ __global__ void __launch_bounds__(256) in_reduce_kernel(const uint16_t* __restri
 }
 
 // MODE 0: stats[n][c] = (mean, rstd) from the block sums of (z, z^2).  MODE 1: stats2[n][c] = (mean g, mean g xhat).
+// A workgroup serves 16 (n, c) pairs; thread (slice s, pair i) adds blocks s, s + 16, ... in double and the 16 slice
+// sums are added in order (bit-reproducible).
 template <int MODE>
 __global__ void __launch_bounds__(256) in_finish_kernel(const float* __restrict__ part, int blocks, int C, int total, double inv_v, float eps,
                                                         float* __restrict__ out) {
-    const int i = blockIdx.x * 256 + threadIdx.x;     // (n, c)
-    if (i >= total) return;
-    const int n = i / C, c = i - n * C;
+    __shared__ double r1[16][17], r2[16][17];
+    const int il = threadIdx.x & 15, sl = threadIdx.x >> 4;
+    const int i = blockIdx.x * 16 + il;     // (n, c)
     double s1 = 0.0, s2 = 0.0;
-    for (int b = 0; b < blocks; ++b) {
-        const float* pb = part + ((long long)n * blocks + b) * 2 * C;
-        s1 += (double)pb[c];
-        s2 += (double)pb[C + c];
+    if (i < total) {
+        const int n = i / C, c = i - n * C;
+        for (int b = sl; b < blocks; b += 16) {
+            const float* pb = part + ((long long)n * blocks + b) * 2 * C;
+            s1 += (double)pb[c];
+            s2 += (double)pb[C + c];
+        }
     }
+    r1[sl][il] = s1; r2[sl][il] = s2;
+    __syncthreads();
+    if (sl != 0 || i >= total) return;
+    s1 = 0.0; s2 = 0.0;
+    for (int k = 0; k < 16; ++k) { s1 += r1[k][il]; s2 += r2[k][il]; }
     if (MODE == 0) {
         const double mean = s1 * inv_v;
         double var = s2 * inv_v - mean * mean;
@@ -195,7 +223,7 @@ int mi3d_instnorm_stats(const void* z, int N, size_t voxels, int C, float eps, f
     in_reduce_kernel<0><<<dim3(blocks, N), 256, 0, (hipStream_t)stream>>>((const uint16_t*)z, nullptr, (long long)voxels, C, 1.f, (float*)ws);
     int st = check_launch();
     if (st) return st;
-    in_finish_kernel<0><<<(N * C + 255) / 256, 256, 0, (hipStream_t)stream>>>((const float*)ws, blocks, C, N * C, 1.0 / (double)voxels, eps, stats);
+    in_finish_kernel<0><<<(N * C + 15) / 16, 256, 0, (hipStream_t)stream>>>((const float*)ws, blocks, C, N * C, 1.0 / (double)voxels, eps, stats);
     return check_launch();
 }
 
@@ -216,7 +244,7 @@ int mi3d_instnorm_lrelu_bwd(void* da, const void* a, const float* stats, int N, 
     in_reduce_kernel<1><<<dim3(blocks, N), 256, 0, (hipStream_t)stream>>>((const uint16_t*)a, (const uint16_t*)da, (long long)voxels, C, slope, part);
     int st = check_launch();
     if (st) return st;
-    in_finish_kernel<1><<<(N * C + 255) / 256, 256, 0, (hipStream_t)stream>>>(part, blocks, C, N * C, 1.0 / (double)voxels, 0.f, sums);
+    in_finish_kernel<1><<<(N * C + 15) / 16, 256, 0, (hipStream_t)stream>>>(part, blocks, C, N * C, 1.0 / (double)voxels, 0.f, sums);
     if ((st = check_launch())) return st;
     const long long pieces = (long long)voxels * (C / 8);
     in_bwd_kernel<<<dim3(in_grid(pieces), N), 256, 0, (hipStream_t)stream>>>((uint4*)da, (const uint4*)a, stats, sums, pieces, C, slope);
