@@ -26,7 +26,9 @@
 // latency to arrive before anybody waits for it.  LDS holds a patch voxel-major
 // (64 bytes per voxel): one load instruction moves 16 neighbouring voxels, 1 KB
 // contiguous in memory and in LDS, and a B fragment (16 voxels x 32 couts) is
-// again 1 KB contiguous, free of bank conflicts.
+// again 1 KB contiguous.  (The eight lanes a 16-byte LDS read serves together
+// are 64 bytes apart in it, a two-way bank conflict; the pass waits for HBM, not
+// for LDS.)
 #include "mi3d_internal.h"
 
 namespace mi3d {
