@@ -121,6 +121,32 @@ def test_epilogue_argument_checks(device):
         mc.conv3d_fwd_lrelu(d32, torch.zeros((1, 4, 4, 4, 4), device="cuda"), torch.zeros((4, 3, 3, 3, 4), device="cuda"), 0.01)
 
 
+def test_dgrad_skip_argument_checks(device):
+    import ctypes
+    from paper_1812_07816_amd._lib import lib
+    bf = torch.bfloat16
+    desc = mc.make_desc(1, 8, 8, 8, 32, 64, 3, 2, 1, bf)
+    dy = torch.zeros((1, 4, 4, 4, 64), dtype=bf, device="cuda")
+    w = torch.zeros((64, 3, 3, 3, 32), dtype=bf, device="cuda")
+    t = torch.zeros((1, 8, 8, 8, 32), dtype=bf, device="cuda")
+    ws = torch.empty(mc.workspace_bytes(desc, 1) + 16, dtype=torch.uint8, device="cuda")
+
+    def call(add, a_in, slope, ws_bytes=ws.numel(), d=desc):
+        return lib().mi3d_conv3d_dgrad_skip(ctypes.byref(d), dy.data_ptr(), w.data_ptr(), add, a_in, ctypes.c_float(slope),
+                                            t.data_ptr(), ws.data_ptr(), ws_bytes, None)
+
+    other = torch.zeros_like(t)
+    assert call(other.data_ptr(), other.data_ptr(), 0.01) == 0
+    assert call(None, other.data_ptr(), 0.01) == -1                  # no second gradient
+    assert call(other.data_ptr(), None, 0.01) == -1                  # no skip tensor
+    assert call(other.data_ptr() + 2, other.data_ptr(), 0.01) == -1  # misaligned
+    assert call(other.data_ptr(), other.data_ptr(), 1.5) == -1       # slope out of range
+    assert call(other.data_ptr(), other.data_ptr(), 0.01, ws_bytes=16) == -3
+    d32 = mc.make_desc(1, 8, 8, 8, 32, 64, 3, 2, 1, torch.float32)
+    assert call(other.data_ptr(), other.data_ptr(), 0.01, d=d32) == -1   # bf16 only
+    torch.cuda.synchronize()
+
+
 def test_bare_mfma_loop_diagnostic_runs_and_checks_its_arguments(device):
     import ctypes
     from paper_1812_07816_amd._lib import lib
