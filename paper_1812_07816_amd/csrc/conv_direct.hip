@@ -140,6 +140,32 @@ __global__ void __launch_bounds__(256) reduce_partials_kernel(const float* __res
     }
 }
 
+// The same sums in the same order, four consecutive elements per thread: a block handles 64 elements and each of its
+// loads covers 256 contiguous bytes per group instead of 64.
+__global__ void __launch_bounds__(256) reduce_partials4_kernel(const float* __restrict__ part, float* __restrict__ out,
+                                                               long long n4, long long n, int parts) {
+    __shared__ float4 sm[16][17];
+    const int e = threadIdx.x & 15, g = threadIdx.x >> 4;
+    const long long i = (long long)blockIdx.x * 16 + e;
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (i < n4)
+        for (int p = g; p < parts; p += 16) {
+            const float4 b = *(const float4*)(part + (long long)p * n + 4 * i);
+            acc.x += b.x; acc.y += b.y; acc.z += b.z; acc.w += b.w;
+        }
+    sm[g][e] = acc;
+    __syncthreads();
+    if (g == 0 && i < n4) {
+        float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+        for (int k = 0; k < 16; ++k) {
+            const float4 b = sm[k][e];
+            a.x += b.x; a.y += b.y; a.z += b.z; a.w += b.w;
+        }
+        *(float4*)(out + 4 * i) = a;
+    }
+}
+
 // Few partial tensors of many elements (the deep layers: two to sixteen slots of millions of weights): one thread
 // per four consecutive elements adds the parts in index order.  The 16-groups kernel above would launch a block per
 // 16 elements with most of its threads idle (71 us for 2 x 3.5 M floats against 12 us here).
@@ -159,6 +185,8 @@ __global__ void __launch_bounds__(256) reduce_few_partials_kernel(const float* _
 int reduce_partials(const float* part, float* out, long long n, int parts, hipStream_t s) {
     if (parts <= 16 && n % 4 == 0 && n >= (1 << 16) && (((uintptr_t)part | (uintptr_t)out) & 15) == 0)
         reduce_few_partials_kernel<<<(unsigned)((n / 4 + 255) / 256), 256, 0, s>>>(part, out, n / 4, n, parts);
+    else if (n % 4 == 0 && n >= 4096 && (((uintptr_t)part | (uintptr_t)out) & 15) == 0)
+        reduce_partials4_kernel<<<(unsigned)((n / 4 + 15) / 16), 256, 0, s>>>(part, out, n / 4, n, parts);
     else
         reduce_partials_kernel<<<(unsigned)((n + 15) / 16), 256, 0, s>>>(part, out, n, parts);
     return check_launch();
