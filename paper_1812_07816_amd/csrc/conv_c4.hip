@@ -456,28 +456,33 @@ __global__ void __launch_bounds__(256, 2) c4_wgrad_kernel(C4WgParams P) {
     }
 }
 
-// dw[co][kd][kh][kw][ci] = sum over slots of part[slot][co][kd*3+kh][4 kw + ci]; a block handles 16
-// elements, thread (g, e) adds slots g, g + 16, ...; the 16 group sums are added in index order
+// dw[co][kd][kh][kw][0..3] = sum over slots of part[slot][co][kd*3+kh][4 kw + 0..3]; a block handles four
+// (co, kd, kh, kw) positions, thread (g, e) adds the four channels of slots g, g + 64, ... of position e; the 64 group
+// sums are then added in index order (a fixed order: bit-reproducible)
 __global__ void __launch_bounds__(256) c4_wgrad_reduce_kernel(const float* __restrict__ part, float* __restrict__ dw, int Cout, int slots) {
-    __shared__ float sm[16][17];
-    const int e = threadIdx.x & 15, g = threadIdx.x >> 4;
-    const int idx = blockIdx.x * 16 + e;
-    const bool ok = idx < Cout * 108;
-    const int ci = idx & 3;
-    int r = idx >> 2;
+    __shared__ float4 sm[64][4];
+    const int e = threadIdx.x & 3, g = threadIdx.x >> 2;
+    const int idx = blockIdx.x * 4 + e;            // (co, kdh, kw)
+    const bool ok = idx < Cout * 27;
+    int r = idx;
     const int kw = r % 3; r /= 3;
     const int kdh = r % 9;
     const int co = r / 9;
-    float a = 0.f;
+    float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
     if (ok)
-        for (int sl = g; sl < slots; sl += 16) a += part[(((long long)sl * Cout + co) * 9 + kdh) * 16 + 4 * kw + ci];
+        for (int sl = g; sl < slots; sl += 64) {
+            const float4 b = *(const float4*)(part + (((long long)sl * Cout + co) * 9 + kdh) * 16 + 4 * kw);
+            a.x += b.x; a.y += b.y; a.z += b.z; a.w += b.w;
+        }
     sm[g][e] = a;
     __syncthreads();
     if (g == 0 && ok) {
-        float b = 0.f;
-#pragma unroll
-        for (int k = 0; k < 16; ++k) b += sm[k][e];
-        dw[idx] = b;
+        float4 b = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int k = 0; k < 64; ++k) {
+            const float4 c = sm[k][e];
+            b.x += c.x; b.y += c.y; b.z += c.z; b.w += c.w;
+        }
+        *(float4*)(dw + 4 * (long long)idx) = b;
     }
 }
 
@@ -509,7 +514,7 @@ int c4_wgrad(const Geom& g, const void* x, const void* dy, float* dw, void* ws, 
     c4_wgrad_kernel<<<dim3((unsigned)P.nwg, (unsigned)(g.Cout / 32)), 256, 0, s>>>(P);
     int st = check_launch();
     if (st) return st;
-    c4_wgrad_reduce_kernel<<<(unsigned)((g.Cout * 108 + 15) / 16), 256, 0, s>>>((const float*)ws, dw, g.Cout, P.nwg);
+    c4_wgrad_reduce_kernel<<<(unsigned)((g.Cout * 27 + 3) / 4), 256, 0, s>>>((const float*)ws, dw, g.Cout, P.nwg);
     return check_launch();
 }
 
