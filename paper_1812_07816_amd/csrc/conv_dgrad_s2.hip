@@ -371,6 +371,7 @@ bool dgrad_s2_supported(const Geom& g) {
     if (g.dtype != MI3D_BF16 || g.kD != 3 || g.kH != 3 || g.kW != 3) return false;
     if (g.sD != 2 || g.sH != 2 || g.sW != 2) return false;
     if (g.pD != g.pH || g.pD != g.pW || g.pD > 1) return false;
+    if (!g.planes_fit_32bit()) return false;
     return g.Cin % 32 == 0 && (g.Cout == 32 || g.Cout % 64 == 0);
 }
 

@@ -292,6 +292,7 @@ bool wgrad_mfma_supported(const Geom& g) {
     if (g.dtype != MI3D_BF16 || g.kD != 3 || g.kH != 3 || g.kW != 3) return false;
     if (g.sD != 1 || g.sH != 1 || g.sW != 1) return false;
     if (g.pD > 2 || g.pH > 2 || g.pW > 2) return false;
+    if (!g.planes_fit_32bit()) return false;
     return g.Cin % 32 == 0 && g.Cout % 32 == 0;
 }
 

@@ -39,6 +39,11 @@ struct Geom {
     __host__ __device__ long long out_voxels() const { return (long long)N * Do * Ho * Wo; }
     __host__ __device__ long long taps() const { return (long long)kD * kH * kW; }
     __host__ __device__ long long w_elems() const { return taps() * Cin * Cout; }
+    // One D-plane of either activation tensor stays below 2 GiB in bf16: the tiled kernels address inside a plane
+    // with 32-bit offsets (the plane base is a 64-bit pointer).
+    bool planes_fit_32bit() const {
+        return (long long)H * W * (x_pitch ? x_pitch : Cin) * 2 < (1ll << 31) && (long long)Ho * Wo * Cout * 2 < (1ll << 31);
+    }
     __host__ __device__ size_t esize() const { return dtype == MI3D_BF16 ? 2 : 4; }
 };
 
