@@ -59,7 +59,13 @@ def cpu_baseline(seconds_target=15.0):
     vol -= vol % 4
     dt, fl = run(vol)
     threads = int(os.environ.get("OMP_NUM_THREADS", cores))
-    return {"value": fl / dt / 1e12, "unit": "TFLOP/s", "cores": min(threads, cores), "kind": "oracle",
+    model = "unknown"
+    try:
+        with open("/proc/cpuinfo") as f:
+            model = next((ln.split(":", 1)[1].strip() for ln in f if ln.startswith("model name")), model)
+    except OSError:
+        pass
+    return {"value": fl / dt / 1e12, "unit": "TFLOP/s", "cores": min(threads, cores), "cpu_model": model, "kind": "oracle",
             "sample": f"fp64 direct-loop fwd+dgrad+wgrad of one 32->32 3x3x3 layer on a {vol}^3 sub-volume of the "
                       f"workload ({dt:.1f} s)", "seconds": dt}
 
