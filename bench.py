@@ -35,6 +35,30 @@ def measured_traffic(kernel):
     return None
 
 
+def probe_mfma_tflops(random_operands, iters=100000):
+    """Rate of a bare bf16 MFMA loop with all-zero or pseudo-random operands (TFLOP/s), timed with events on the
+    current stream.  The loop lives in libbench_probe.so (bench_probe.hip, built by __graft_entry__.build())."""
+    import ctypes
+    import torch
+    path = os.path.join(ROOT, "libbench_probe.so")
+    if not os.path.exists(path):
+        return None
+    l = ctypes.CDLL(path)
+    l.bench_probe_mfma_workspace_bytes.restype = ctypes.c_size_t
+    l.bench_probe_mfma.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t, ctypes.POINTER(ctypes.c_double), ctypes.c_void_p]
+    ws = torch.empty(l.bench_probe_mfma_workspace_bytes(), dtype=torch.uint8, device="cuda")
+    fl = ctypes.c_double()
+    s = torch.cuda.current_stream()
+    sp = ctypes.c_void_p(s.cuda_stream)
+    assert l.bench_probe_mfma(int(random_operands), 2000, ws.data_ptr(), ws.numel(), ctypes.byref(fl), sp) == 0   # warm-up
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(s)
+    assert l.bench_probe_mfma(int(random_operands), int(iters), ws.data_ptr(), ws.numel(), ctypes.byref(fl), sp) == 0
+    e1.record(s)
+    torch.cuda.synchronize()
+    return fl.value / e0.elapsed_time(e1) / 1e9
+
+
 def cpu_baseline(seconds_target=15.0):
     """The fp64 oracle as it stands, timed on this host: fwd + dgrad + wgrad of
     a 32->32 3x3x3 layer on a cube sized for roughly `seconds_target` of work."""
@@ -463,8 +487,8 @@ def main():
         r["roofline"]["traffic"] = measured_traffic(r["kernel"])
     # what the matrix cores sustain in a bare MFMA loop on this machine (the rate is power-limited and depends on the
     # operands): context for the MFMA-bound fractions above, which stay relative to the published peak
-    mfma_bare = {"zero_operands_tflops": mc.probe_mfma_tflops(0), "random_operands_tflops": mc.probe_mfma_tflops(1)}
-    if roof["bound"] == "mfma":
+    mfma_bare = {"zero_operands_tflops": probe_mfma_tflops(0), "random_operands_tflops": probe_mfma_tflops(1)}
+    if roof["bound"] == "mfma" and mfma_bare["random_operands_tflops"]:
         roof["frac_of_bare_mfma_loop_random_operands"] = roof["achieved"] / mfma_bare["random_operands_tflops"]
 
     value = flops / ms_step / 1e9

@@ -3,9 +3,11 @@
 // all-zero operands the loop reaches the published dense peak, with random operands about 70 % of it.  bench.py
 // reports both next to the convolution kernels' rates, so that their distance from what the matrix cores sustain
 // on real data can be told from their distance from the published peak.
-#include "mi3d_internal.h"
+// Measurement-side helper: built into libbench_probe.so next to bench.py, not part of libmi3d.so or its C ABI.
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
 
-namespace mi3d {
 namespace {
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
@@ -47,26 +49,26 @@ __global__ void __launch_bounds__(256) mfma_fill_kernel(uint16_t* __restrict__ i
 }
 
 }  // namespace
-}  // namespace mi3d
-
-using namespace mi3d;
 
 extern "C" {
 
-size_t mi3d_probe_mfma_workspace_bytes(void) { return 65536 + 1024 * 256 * sizeof(float); }
+// Enqueues the loop (one workgroup of four waves per CU, 12 x iters MFMA instructions per wave) on `stream` and stores
+// in *flop the floating point operations it performs; the caller times the stream.  random_operands = 0: all-zero
+// operands; 1: a fixed pseudo-random pattern in (-2, 2).  ws: device scratch of bench_probe_mfma_workspace_bytes()
+// bytes, 16-byte aligned.  Returns 0, -1 (bad argument), -3 (scratch too small) or -4 (launch failed).
+size_t bench_probe_mfma_workspace_bytes(void) { return 65536 + 1024 * 256 * sizeof(float); }
 
-int mi3d_probe_mfma(int random_operands, int iters, void* ws, size_t ws_bytes, double* flop, void* stream) {
-    if (!ws || !flop || iters <= 0 || ((uintptr_t)ws & 15)) return MI3D_ERR_INVALID_ARG;
-    if (ws_bytes < mi3d_probe_mfma_workspace_bytes()) return MI3D_ERR_WORKSPACE;
+int bench_probe_mfma(int random_operands, int iters, void* ws, size_t ws_bytes, double* flop, void* stream) {
+    if (!ws || !flop || iters <= 0 || ((uintptr_t)ws & 15)) return -1;
+    if (ws_bytes < bench_probe_mfma_workspace_bytes()) return -3;
     int dev = 0, cus = 256;
     if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
     if (cus > 1024) cus = 1024;
     mfma_fill_kernel<<<128, 256, 0, (hipStream_t)stream>>>((uint16_t*)ws, random_operands ? 1 : 0);
-    int st = check_launch();
-    if (st) return st;
+    if (hipGetLastError() != hipSuccess) return -4;
     mfma_rate_kernel<<<cus, 256, 0, (hipStream_t)stream>>>((const uint4*)ws, (float*)((char*)ws + 65536), iters);
     *flop = 2.0 * 32 * 32 * 16 * 12.0 * (double)iters * 4.0 * cus;
-    return check_launch();
+    return hipGetLastError() == hipSuccess ? 0 : -4;
 }
 
 }  // extern "C"

@@ -178,11 +178,7 @@ int mi3d_conv3d_fwd_lrelu(const mi3d_conv_desc *desc, const void *x, const void 
 int mi3d_conv3d_dgrad_lrelu(const mi3d_conv_desc *desc, const void *dy, const void *w, const void *a_in, float slope,
                             void *dx, void *ws, size_t ws_bytes, void *stream);
 
-/* Kernel family used for a pass: 0 = automatic choice, 1 = force the plain
- * one-thread-per-output kernels (slow; for debugging and cross-checks).
- * Process-wide; returns the previous value. */
-int mi3d_conv3d_set_kernel_family(int family);
-/* Writes the name of the kernel the automatic choice picks (for reports). */
+/* Writes the name of the kernel family the dispatcher routes this geometry and pass to (for reports and tests). */
 int mi3d_conv3d_kernel_name(const mi3d_conv_desc *desc, int pass, char *buf, size_t buf_len);
 
 /* ------------------------------------------------------------------------
@@ -260,14 +256,6 @@ int mi3d_sgd_update(float *w, const float *dw, void *w_bf16, size_t n, float lr,
 int mi3d_adam_update(float *w, const float *dw, float *m, float *v, void *w_bf16, size_t n, float lr, float beta1,
                      float beta2, float eps, int step, void *stream);
 
-/* Diagnostic for the measurement side: enqueues a bare loop of bf16 32x32x16 MFMA instructions with operands in
- * registers (one workgroup of four waves per CU, 12 x iters instructions per wave) and stores in *flop the floating
- * point operations it performs; the caller times the stream.  random_operands = 0: all-zero operands; 1: a fixed
- * pseudo-random pattern in (-2, 2).  The matrix cores' sustained rate depends on the operands (power), which is why
- * the convolution kernels are compared with both.  ws: device scratch of mi3d_probe_mfma_workspace_bytes() bytes. */
-size_t mi3d_probe_mfma_workspace_bytes(void);
-int mi3d_probe_mfma(int random_operands, int iters, void *ws, size_t ws_bytes, double *flop, void *stream);
-
 /* ------------------------------------------------------------------------ */
 /* Data-swapping engine                                                     */
 /* ------------------------------------------------------------------------ */
@@ -325,7 +313,12 @@ typedef struct {
     uint64_t bytes_out, bytes_in;        /* bytes copied device->host / host->device since create or reset */
     double   copy_ms_out, copy_ms_in;    /* summed event-timed copy durations per direction (completed copies) */
     double   busy_ms;                    /* length of the union of the copy intervals of both side streams */
-    uint64_t peak_arena_bytes;           /* high-water mark of mi3d_swap_alloc()ed bytes */
+    uint64_t peak_arena_bytes;           /* peak of the arena bytes in use: handed out by mi3d_swap_alloc(), or freed
+                                            but still read by a swap-out in flight (since create or reset) */
+    uint64_t arena_high_water_bytes;     /* highest end offset of such a block: the arena the step really needed */
+    uint64_t planned_arena_bytes;        /* bytes of saved tensors at the peak of the planner's model (256-byte
+                                            units); mi3d_swap_alloc stays below this offset while it can */
+    int      n_arena_overflow;           /* allocations that fragmentation pushed above planned_arena_bytes */
     uint64_t planned_peak_bytes;         /* peak of the planner's residency model with the chosen swap set */
     uint64_t unswapped_peak_bytes;       /* same model with nothing swapped */
     int      n_registered, n_planned;    /* tensors known / chosen for swapping */
@@ -379,8 +372,9 @@ int mi3d_swap_first_use_op(mi3d_swap_engine *e, int id);
 
 /* Host-only: chooses the swap set.  MI3D_ERR_OVER_BUDGET if even the chosen
  * policy's full set leaves the modelled peak above budget_bytes (the plan is
- * still filled in, so callers may inspect it), MI3D_ERR_HOST_POOL if the set
- * does not fit the pinned pool. */
+ * still filled in, so callers may inspect and run it), MI3D_ERR_HOST_POOL if
+ * the set does not fit the pinned pool (then there is no plan: the queries
+ * below and mi3d_swap_out return MI3D_ERR_BAD_STATE until a plan succeeds). */
 int mi3d_swap_plan(mi3d_swap_engine *e);
 /* 1 if the tensor is in the swap set, 0 if not, <0 on error. */
 int mi3d_swap_is_planned(mi3d_swap_engine *e, int id);
@@ -393,7 +387,10 @@ int mi3d_swap_planned_bytes_at(mi3d_swap_engine *e, int op, uint64_t *bytes);
 /* Sub-allocates `bytes` (rounded up to 256) from dev_arena for work on
  * `stream`.  A block that was released while copies or kernels were still
  * using it is handed out again only together with a stream wait on those
- * events, so the caller may use it on `stream` at once.
+ * events, so the caller may use it on `stream` at once.  With a plan the
+ * allocation stays below planned_arena_bytes (the saved bytes the budget
+ * leaves room for) as long as a block there fits, even if `stream` then has
+ * to wait for a swap-out that still reads that block.
  * MI3D_ERR_OVER_BUDGET when no block is large enough. */
 int mi3d_swap_alloc(mi3d_swap_engine *e, size_t bytes, void *stream, void **dev_ptr);
 /* Returns a block; it becomes reusable once the work enqueued on `stream` so
@@ -423,7 +420,9 @@ int mi3d_swap_done(mi3d_swap_engine *e, int id);
 /* Blocks the host until every copy issued so far has finished. */
 int mi3d_swap_sync(mi3d_swap_engine *e);
 /* Forgets per-step state (tensor residency, host slots, counters) but keeps
- * registrations and the plan, so the same step can run again. */
+ * registrations and the plan, so the same step can run again.  Blocks of
+ * mi3d_swap_alloc that were never returned (a step that ended early) go back to
+ * the arena after a device synchronisation; their pointers become invalid. */
 int mi3d_swap_reset_step(mi3d_swap_engine *e);
 /* Collects counters; synchronises with the side streams to time the copies. */
 int mi3d_swap_stats(mi3d_swap_engine *e, mi3d_swap_stats_t *out);

@@ -27,7 +27,9 @@ class SwapStats(ctypes.Structure):
     _fields_ = [("bytes_out", ctypes.c_uint64), ("bytes_in", ctypes.c_uint64),
                 ("copy_ms_out", ctypes.c_double), ("copy_ms_in", ctypes.c_double),
                 ("busy_ms", ctypes.c_double),
-                ("peak_arena_bytes", ctypes.c_uint64), ("planned_peak_bytes", ctypes.c_uint64),
+                ("peak_arena_bytes", ctypes.c_uint64), ("arena_high_water_bytes", ctypes.c_uint64),
+                ("planned_arena_bytes", ctypes.c_uint64), ("n_arena_overflow", ctypes.c_int),
+                ("planned_peak_bytes", ctypes.c_uint64),
                 ("unswapped_peak_bytes", ctypes.c_uint64),
                 ("n_registered", ctypes.c_int), ("n_planned", ctypes.c_int),
                 ("n_swapped_out", ctypes.c_int), ("n_swapped_in", ctypes.c_int),
@@ -59,8 +61,6 @@ SIGNATURES = {
     "mi3d_instnorm_stats": (_i, [_vp, _i, _sz, _i, ctypes.c_float, _vp, _vp, _sz, _vp]),
     "mi3d_instnorm_lrelu_fwd": (_i, [_vp, _vp, _i, _sz, _i, ctypes.c_float, _vp]),
     "mi3d_instnorm_lrelu_bwd": (_i, [_vp, _vp, _vp, _i, _sz, _i, ctypes.c_float, _vp, _sz, _vp]),
-    "mi3d_probe_mfma_workspace_bytes": (_sz, []),
-    "mi3d_probe_mfma": (_i, [_i, _i, _vp, _sz, ctypes.POINTER(ctypes.c_double), _vp]),
     "mi3d_adam_update": (_i, [_vp, _vp, _vp, _vp, _vp, _sz, ctypes.c_float, ctypes.c_float, ctypes.c_float, ctypes.c_float, _i, _vp]),
     "mi3d_conv3d_workspace_bytes": (_sz, [_pd, _i]),
     "mi3d_conv3d_fwd": (_i, [_pd, _vp, _vp, _vp, _vp, _sz, _vp]),
@@ -78,7 +78,6 @@ SIGNATURES = {
     "mi3d_conv3d_wgrad_pair": (_i, [_pd, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "mi3d_conv3d_fwd_lrelu": (_i, [_pd, _vp, _vp, _vp, ctypes.c_float, _vp, _sz, _vp]),
     "mi3d_conv3d_dgrad_lrelu": (_i, [_pd, _vp, _vp, _vp, ctypes.c_float, _vp, _vp, _sz, _vp]),
-    "mi3d_conv3d_set_kernel_family": (_i, [_i]),
     "mi3d_conv3d_kernel_name": (_i, [_pd, _i, ctypes.c_char_p, _sz]),
     "mi3d_swap_create": (_i, [ctypes.POINTER(SwapConfig), ctypes.POINTER(_vp)]),
     "mi3d_swap_destroy": (_i, [_vp]),

@@ -41,25 +41,6 @@ def kernel_name(desc, pass_):
     return buf.value.decode()
 
 
-def probe_mfma_tflops(random_operands, iters=100000):
-    """Rate of a bare bf16 MFMA loop with all-zero or pseudo-random operands (TFLOP/s), timed with events on the
-    current stream."""
-    ws = torch.empty(lib().mi3d_probe_mfma_workspace_bytes(), dtype=torch.uint8, device="cuda")
-    fl = ctypes.c_double()
-    s = torch.cuda.current_stream()
-    check(lib().mi3d_probe_mfma(int(random_operands), 2000, ws.data_ptr(), ws.numel(), ctypes.byref(fl), _stream()), "probe_mfma")   # warm-up
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record(s)
-    check(lib().mi3d_probe_mfma(int(random_operands), int(iters), ws.data_ptr(), ws.numel(), ctypes.byref(fl), _stream()), "probe_mfma")
-    e1.record(s)
-    torch.cuda.synchronize()
-    return fl.value / e0.elapsed_time(e1) / 1e9
-
-
-def set_kernel_family(family):
-    return lib().mi3d_conv3d_set_kernel_family(int(family))
-
-
 def _stream():
     return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
 

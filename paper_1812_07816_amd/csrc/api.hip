@@ -1,5 +1,4 @@
 // C ABI of the convolution passes: descriptor validation and kernel choice.
-#include <atomic>
 #include <cstdio>
 #include <cstring>
 
@@ -8,7 +7,6 @@
 namespace mi3d {
 
 static thread_local int g_last_hip_error = 0;
-static std::atomic<int> g_family{0};
 
 void note_hip_error(hipError_t e) { g_last_hip_error = (int)e; }
 
@@ -138,7 +136,7 @@ static bool fuses_epilogue(Kernel k, const Geom& g, int pass) {
 
 // the kernels that take the tensor of x's shape as two halves along the channels
 static bool pair_supported(const Geom& g, int pass) {
-    if (g_family.load() == 1 || g.Cin % 64) return false;
+    if (g.Cin % 64) return false;
     const Kernel k = choose(g, pass);
     return pass == MI3D_PASS_WGRAD ? k == K_WGRAD_MFMA : k == K_SP;
 }
@@ -180,17 +178,12 @@ int mi3d_conv3d_out_dims(const mi3d_conv_desc* desc, int* Do, int* Ho, int* Wo) 
     return MI3D_OK;
 }
 
-int mi3d_conv3d_set_kernel_family(int family) {
-    if (family < 0 || family > 1) return MI3D_ERR_INVALID_ARG;
-    return g_family.exchange(family);
-}
-
 int mi3d_conv3d_kernel_name(const mi3d_conv_desc* desc, int pass, char* buf, size_t buf_len) {
     Geom g;
     int st = make_geom(desc, &g);
     if (st) return st;
     if (!buf || buf_len == 0 || pass < 0 || pass > 2) return MI3D_ERR_INVALID_ARG;
-    Kernel k = g_family.load() == 1 ? K_DIRECT : choose(g, pass);
+    Kernel k = choose(g, pass);
     snprintf(buf, buf_len, "%s", kernel_name(k));
     return MI3D_OK;
 }
@@ -198,9 +191,7 @@ int mi3d_conv3d_kernel_name(const mi3d_conv_desc* desc, int pass, char* buf, siz
 size_t mi3d_conv3d_workspace_bytes(const mi3d_conv_desc* desc, int pass) {
     Geom g;
     if (make_geom(desc, &g) || pass < 0 || pass > 2) return 0;
-    // the plain kernels must stay runnable (kernel family 1), so report the larger of the two
-    size_t plain = direct_workspace_bytes(g, pass), chosen = auto_workspace_bytes(g, pass);
-    return plain > chosen ? plain : chosen;
+    return auto_workspace_bytes(g, pass);
 }
 
 // slope / ref: optional LeakyReLU epilogue (forward: on y; data gradient: derivative factor from ref), 1 / null = none
@@ -216,14 +207,14 @@ static int conv_entry(const mi3d_conv_desc* desc, int pass, const void* a, const
     }
     if (xv && xv->pitch) {   // the tensor of x's shape is a channel range of a wider tensor
         if (xv->pitch < 0 || xv->offset < 0 || xv->offset + g.Cin > xv->pitch || xv->pitch % 8 || xv->offset % 8) return MI3D_ERR_INVALID_ARG;
-        if (g_family.load() == 1 || choose(g, pass) != K_K2) return MI3D_ERR_UNSUPPORTED;
+        if (choose(g, pass) != K_K2) return MI3D_ERR_UNSUPPORTED;
         g.x_pitch = xv->pitch;
         g.x_off = xv->offset;
     }
     if (!a || !b || !out || !aligned16(a) || !aligned16(b) || !aligned16(out) || !aligned16(ws)) return MI3D_ERR_INVALID_ARG;
     if (ws_bytes && !ws) return MI3D_ERR_INVALID_ARG;
     if (ws_bytes < mi3d_conv3d_workspace_bytes(desc, pass)) return MI3D_ERR_WORKSPACE;
-    Kernel k = g_family.load() == 1 ? K_DIRECT : choose(g, pass);
+    Kernel k = choose(g, pass);
     const bool epilogue = slope != 1.f;
     if (!epilogue) return run_kernel(k, g, pass, a, b, out, ws, ws_bytes, (hipStream_t)stream);
     if (!(slope >= 0.f && slope < 1.f) || g.dtype != MI3D_BF16 || pass == MI3D_PASS_WGRAD) return MI3D_ERR_INVALID_ARG;
@@ -273,7 +264,7 @@ int mi3d_conv3d_dgrad_skip(const mi3d_conv_desc* desc, const void* dy, const voi
         return MI3D_ERR_INVALID_ARG;
     if (g.dtype != MI3D_BF16 || !(slope >= 0.f && slope <= 1.f) || (ws_bytes && !ws)) return MI3D_ERR_INVALID_ARG;
     if (ws_bytes < mi3d_conv3d_workspace_bytes(desc, MI3D_PASS_DGRAD)) return MI3D_ERR_WORKSPACE;
-    const Kernel k = g_family.load() == 1 ? K_DIRECT : choose(g, MI3D_PASS_DGRAD);
+    const Kernel k = choose(g, MI3D_PASS_DGRAD);
     if (k == K_DGRAD_S2 && dgrad_s2_fuses_skip(g)) {
         Geom ge = g;
         ge.add = add; ge.ref = a_in; ge.slope = slope;
@@ -287,7 +278,7 @@ int mi3d_conv3d_dgrad_skip(const mi3d_conv_desc* desc, const void* dy, const voi
 
 int mi3d_conv3d_fwd_stats_supported(const mi3d_conv_desc* desc) {
     Geom g;
-    if (make_geom(desc, &g) || g_family.load() == 1) return 0;
+    if (make_geom(desc, &g)) return 0;
     return choose(g, MI3D_PASS_FWD) == K_SP && sp_fuses_stats(g) ? 1 : 0;
 }
 

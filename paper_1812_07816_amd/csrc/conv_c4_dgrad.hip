@@ -309,7 +309,7 @@ int c4_dgrad(const Geom& g, const void* dy, const void* w, void* dx, void* ws, s
     long long nwg = cus;
     if (nwg > P.units) nwg = P.units;
     P.nwg = (int)nwg;
-    static bool attr_set = false;
+    static std::atomic<bool> attr_set{false};   // set once per process; a second thread racing here repeats an idempotent call
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void*)c4_dgrad_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, NSTAGE * STAGE_BYTES);
         if (e != hipSuccess) { note_hip_error(e); return MI3D_ERR_HIP; }

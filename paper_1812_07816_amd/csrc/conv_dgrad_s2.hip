@@ -411,7 +411,7 @@ int dgrad_s2(const Geom& g, const void* dy, const void* w, void* dx, void* ws, s
     const long long nwg = cus < G.units ? cus : G.units;
     G.nwg = (int)nwg;
     const size_t lds = (size_t)27 * KK * 1024 + 2 * (size_t)(2 * KK) * SLABV * 16;
-    static bool attr_set = false;
+    static std::atomic<bool> attr_set{false};   // set once per process; a second thread racing here repeats an idempotent call
     if (!attr_set) {
         const int max_lds = 27 * 4 * 1024 + 2 * 8 * SLABV * 16;
         const void* fns[8] = {(const void*)dgrad_s2_kernel<0, 2, false>, (const void*)dgrad_s2_kernel<1, 2, false>,

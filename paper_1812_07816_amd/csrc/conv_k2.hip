@@ -358,7 +358,7 @@ static int k2_wgrad(const Geom& g, const void* x, const void* dy, float* dw, voi
     P.vox = (int)((long long)g.N * g.Do * g.Ho * g.Wo);
     P.CiT = g.Cin / WCI;
     P.slots = k2_wgrad_slots(g);
-    static bool attr_set = false;
+    static std::atomic<bool> attr_set{false};   // set once per process; a second thread racing here repeats an idempotent call
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void*)k2_wgrad_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 2 * W_STAGE);
         if (e != hipSuccess) { note_hip_error(e); return MI3D_ERR_HIP; }
@@ -399,7 +399,7 @@ int k2_conv(const Geom& g, int pass, const void* a, const void* w, void* out, vo
     if (per_group > tiles) per_group = tiles;
     P.nwg = (int)(per_group * P.NG);
     const size_t lds = (size_t)G * P.K16 * 1024;
-    static bool attr_set = false;
+    static std::atomic<bool> attr_set{false};   // set once per process; a second thread racing here repeats an idempotent call
     if (!attr_set) {
         hipError_t e = hipSuccess;
         const void* fns0[3] = {(const void*)k2_kernel<0, 1>, (const void*)k2_kernel<0, 2>, (const void*)k2_kernel<0, 4>};

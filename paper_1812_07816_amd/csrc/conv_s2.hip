@@ -413,7 +413,7 @@ int s2_fwd(const Geom& g, const void* x, const void* w, void* y, void* ws, size_
     P.nwg = (int)nwg;
     P.slope = g.slope;
     const size_t lds2 = 2 * WB_BYTES + 4 * (2 * TH + 1) * PITCH * 16, lds1 = WB_BYTES + 4 * (4 * TH + 1) * PITCH * 16;
-    static bool attr_set = false;
+    static std::atomic<bool> attr_set{false};   // set once per process; a second thread racing here repeats an idempotent call
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void*)s2_fwd_kernel<2, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds2);
         if (e == hipSuccess) e = hipFuncSetAttribute((const void*)s2_fwd_kernel<1, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds1);

@@ -718,7 +718,7 @@ int sp_conv(const Geom& g, int pass, const void* in, const void* w, void* out, v
     }
     const int nc = P.Cin / 32;
     const size_t lds1 = W_BYTES + 2 * STAGE_BYTES, lds2 = 2 * W_BYTES + STAGE_BYTES;
-    static bool attr_set = false;
+    static std::atomic<bool> attr_set{false};   // set once per process; a second thread racing here repeats an idempotent call
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void*)sp_conv_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds1);
         if (e == hipSuccess) e = hipFuncSetAttribute((const void*)sp_conv_kernel<2>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds2);

@@ -332,7 +332,7 @@ int wgrad_mfma(const Geom& g, const void* x, const void* dy, float* dw, void* ws
     const int pairs = P.CiT * P.CoT;
     if (pairs > 65535) return MI3D_ERR_UNSUPPORTED;
     size_t lds = X_BYTES + 3 * DY_BYTES;
-    static bool attr_set = false;
+    static std::atomic<bool> attr_set{false};   // set once per process; a second thread racing here repeats an idempotent call
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void*)wgrad_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) { note_hip_error(e); return MI3D_ERR_HIP; }

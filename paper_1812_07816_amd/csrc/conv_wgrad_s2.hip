@@ -325,7 +325,7 @@ int wgrad_s2(const Geom& g, const void* x, const void* dy, float* dw, void* ws, 
     const int pairs = P.CiT * P.CoT;
     if (pairs > 65535) return MI3D_ERR_UNSUPPORTED;
     const size_t lds = XSTAGES * X_BYTES + 2 * (size_t)(2 * mb * DY_SLAB);
-    static bool attr_set = false;
+    static std::atomic<bool> attr_set{false};   // set once per process; a second thread racing here repeats an idempotent call
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void*)wgrad_s2_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize, XSTAGES * X_BYTES + 4 * DY_SLAB);
         if (e == hipSuccess) e = hipFuncSetAttribute((const void*)wgrad_s2_kernel<2>, hipFuncAttributeMaxDynamicSharedMemorySize, XSTAGES * X_BYTES + 8 * DY_SLAB);

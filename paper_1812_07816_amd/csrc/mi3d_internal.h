@@ -1,6 +1,7 @@
 // Internal declarations shared by the translation units of libmi3d.so.
 #pragma once
 #include <hip/hip_runtime.h>
+#include <atomic>
 #include <stddef.h>
 #include <stdint.h>
 
@@ -66,7 +67,6 @@ size_t direct_workspace_bytes(const Geom& g, int pass);
 int direct_fwd(const Geom& g, const void* x, const void* w, void* y, hipStream_t s);
 int direct_dgrad(const Geom& g, const void* dy, const void* w, void* dx, hipStream_t s);
 int direct_wgrad(const Geom& g, const void* x, const void* dy, float* dw, void* ws, size_t ws_bytes, hipStream_t s);
-// out[i] = sum_p part[p*n + i] in a fixed order (bit-reproducible); launch with (n + 15) / 16 blocks of 256
 // y[i] = bf16(act(sum_c part[c * n + i])), chunks added in index order; n8 = n / 8 outputs of 8; act = LeakyReLU with
 // `slope` (ref null) or the factor (ref[i] > 0 ? 1 : slope).  y_hi non-null: the output, `cout` channels per voxel, is
 // written as two tensors of cout / 2 channels per voxel (y the low half, y_hi the high half); cout / 2 % 8 == 0.
@@ -74,6 +74,7 @@ int direct_wgrad(const Geom& g, const void* x, const void* dy, float* dw, void* 
 __global__ void sum_chunks_bf16_kernel(const float* __restrict__ part, uint16_t* __restrict__ y, long long n8, long long n, int nch,
                                        float slope, const uint16_t* __restrict__ ref, uint16_t* __restrict__ y_hi, int cout,
                                        const uint16_t* __restrict__ add);
+// out[i] = sum_p part[p*n + i] in a fixed order (bit-reproducible); launch with (n + 15) / 16 blocks of 256
 __global__ void reduce_partials_kernel(const float* __restrict__ part, float* __restrict__ out, long long n, int parts);
 // out[i] = sum_p part[p * n + i] in an order fixed by (n, parts); picks the kernel by the number of parts
 int reduce_partials(const float* part, float* out, long long n, int parts, hipStream_t s);

@@ -64,7 +64,12 @@ struct mi3d_swap_engine {
     std::vector<hipEvent_t> free_events_timed, free_events_plain;
 
     std::vector<ArenaBlock> blocks;
-    size_t arena_used = 0, arena_peak = 0;
+    // arena_used: bytes handed out.  arena_occupied_peak / arena_hwm: peak of the bytes, and highest end offset, of
+    // blocks that are handed out OR freed but still read by a swap-out in flight (that memory is not yet reusable).
+    // arena_cap: bytes the saved tensors occupy at the peak of the plan's residency model; allocations stay below
+    // this offset as long as any block there can serve them (arena_overflow counts those that could not).
+    size_t arena_used = 0, arena_occupied_peak = 0, arena_hwm = 0, arena_cap = 0;
+    int arena_overflow = 0;
 
     uint64_t bytes_out = 0, bytes_in = 0;
     int n_out = 0, n_in = 0;
@@ -148,6 +153,18 @@ int arena_free(mi3d_swap_engine* e, const void* ptr, std::vector<Pending> pendin
     return MI3D_ERR_BAD_STATE;
 }
 
+// blocks whose memory is in use: handed out, or freed behind a copy that has not finished
+void note_occupancy(mi3d_swap_engine* e) {
+    size_t occ = 0, hwm = 0;
+    for (const ArenaBlock& b : e->blocks)
+        if (!b.free || waits_for_copy(b)) {
+            occ += b.size;
+            hwm = std::max(hwm, b.off + b.size);
+        }
+    e->arena_occupied_peak = std::max(e->arena_occupied_peak, occ);
+    e->arena_hwm = std::max(e->arena_hwm, hwm);
+}
+
 void reset_step_state(mi3d_swap_engine* e) {
     for (auto& kv : e->tensors) {
         Tensor& t = kv.second;
@@ -161,6 +178,8 @@ void reset_step_state(mi3d_swap_engine* e) {
     }
     e->bytes_out = e->bytes_in = 0;
     e->n_out = e->n_in = 0;
+    e->arena_occupied_peak = e->arena_hwm = 0;
+    e->arena_overflow = 0;
 }
 
 }  // namespace
@@ -285,7 +304,16 @@ int mi3d_swap_plan(mi3d_swap_engine* e) {
     int st = plan_swaps(ts, e->transient, p, &e->plan_res);
     if (st == MI3D_ERR_INVALID_ARG) return st;
     for (const PlanTensor& t : ts) e->tensors[t.id].plan = t;
-    e->have_plan = true;
+    // a swap set that does not fit the pinned pool is not executable: its host slots lie beyond the pool
+    e->have_plan = st != MI3D_ERR_HOST_POOL;
+    // bytes of saved tensors at the peak of the residency model, each rounded up as the arena rounds them
+    e->arena_cap = 0;
+    if (e->have_plan) {
+        std::vector<PlanTensor> rounded = ts;
+        for (PlanTensor& t : rounded) t.bytes = (t.bytes + 255) & ~(size_t)255;
+        const std::vector<size_t> none;
+        for (int op = 0; op < p.n_ops; ++op) e->arena_cap = std::max<size_t>(e->arena_cap, plan_bytes_at(rounded, none, op, false));
+    }
     return st;
 }
 
@@ -357,16 +385,25 @@ int mi3d_swap_alloc(mi3d_swap_engine* e, size_t bytes, void* stream, void** dev_
         pv.erase(std::remove_if(pv.begin(), pv.end(), [](const Pending& p) { return hipEventQuery((hipEvent_t)p.ev.get()) == hipSuccess; }), pv.end());
     }
     coalesce(e);
-    // first fit among blocks that do not wait for a copy (the host runs ahead of the device, so most freed
-    // blocks still carry an unfired compute-stream event: that wait costs nothing); a block behind a swap-out
-    // in flight is the last resort, since the allocating stream would stall for the rest of that transfer
+    // First fit, in this order: (0) below the plan's peak of saved bytes, among blocks that do not wait for a copy
+    // (the host runs ahead of the device, so most freed blocks still carry an unfired compute-stream event: that
+    // wait costs nothing); (1) below that peak, a block behind a swap-out in flight: the allocating stream stalls
+    // for the rest of that transfer, which is what a device of the budget's size would have to do; (2) anywhere:
+    // only when fragmentation leaves no block below the peak (counted as an overflow).  Without a plan the whole
+    // arena is fair game.
+    const size_t cap = e->have_plan && e->arena_cap ? e->arena_cap : e->cfg.arena_bytes;
     int pick = -1;
-    for (int pass = 0; pass < 2 && pick < 0; ++pass)
+    for (int pass = 0; pass < 4 && pick < 0; ++pass)
         for (int i = 0; i < (int)e->blocks.size(); ++i) {
             const ArenaBlock& b = e->blocks[i];
-            if (b.free && b.size >= need && (pass == 1 || !waits_for_copy(b))) { pick = i; break; }
+            if (!b.free || b.size < need) continue;
+            if (pass < 2 && b.off + need > cap) continue;
+            if ((pass == 0 || pass == 2) && waits_for_copy(b)) continue;
+            pick = i;
+            break;
         }
     if (pick < 0) return MI3D_ERR_OVER_BUDGET;
+    if (e->blocks[pick].off + need > cap) e->arena_overflow++;
     for (auto& p : e->blocks[pick].pending) HIP_TRY(hipStreamWaitEvent((hipStream_t)stream, (hipEvent_t)p.ev.get(), 0));
     ArenaBlock& b = e->blocks[pick];
     if (b.size > need) {
@@ -378,7 +415,7 @@ int mi3d_swap_alloc(mi3d_swap_engine* e, size_t bytes, void* stream, void** dev_
     a.free = false;
     a.pending.clear();
     e->arena_used += need;
-    e->arena_peak = std::max(e->arena_peak, e->arena_used);
+    note_occupancy(e);
     *dev_ptr = (char*)e->cfg.dev_arena + a.off;
     return MI3D_OK;
 }
@@ -396,6 +433,7 @@ int mi3d_swap_out(mi3d_swap_engine* e, int id, const void* dev_src, void* produc
     if (!e || !dev_src) return MI3D_ERR_INVALID_ARG;
     Tensor* t = find(e, id);
     if (!t || !e->have_plan || !t->plan.planned || t->state != ST_NEW || !e->live) return MI3D_ERR_BAD_STATE;
+    if (t->plan.host_offset + t->plan.bytes > e->cfg.host_pool_bytes) return MI3D_ERR_HOST_POOL;
     hipEvent_t dep;
     int st = get_event(e, false, &dep);
     if (st) return st;
@@ -436,6 +474,7 @@ int mi3d_swap_in(mi3d_swap_engine* e, int id, void* dev_dst, void* consumer_stre
     if (!e || !dev_dst) return MI3D_ERR_INVALID_ARG;
     Tensor* t = find(e, id);
     if (!t || t->state != ST_HOST || !e->live) return MI3D_ERR_BAD_STATE;
+    if (t->plan.host_offset + t->plan.bytes > e->cfg.host_pool_bytes) return MI3D_ERR_HOST_POOL;
     hipEvent_t dep;
     int st = get_event(e, false, &dep);
     if (st) return st;
@@ -483,6 +522,20 @@ int mi3d_swap_reset_step(mi3d_swap_engine* e) {
     if (!e) return MI3D_ERR_INVALID_ARG;
     int st = mi3d_swap_sync(e);
     if (st) return st;
+    // blocks a step that ended early never returned: nothing says which stream still uses them, so the device is
+    // drained before they go back (a step that ran to its end has freed everything and pays nothing here)
+    bool leaked = false;
+    for (const ArenaBlock& b : e->blocks) leaked = leaked || !b.free;
+    if (leaked) {
+        HIP_TRY(hipDeviceSynchronize());
+        for (ArenaBlock& b : e->blocks) {
+            if (b.free) continue;
+            b.free = true;
+            b.pending.clear();
+            e->arena_used -= b.size;
+        }
+        coalesce(e);
+    }
     reset_step_state(e);
     if (e->live) HIP_TRY(hipEventRecord(e->base, e->s_out));
     return MI3D_OK;
@@ -493,7 +546,10 @@ int mi3d_swap_stats(mi3d_swap_engine* e, mi3d_swap_stats_t* out) {
     *out = mi3d_swap_stats_t();
     out->bytes_out = e->bytes_out;
     out->bytes_in = e->bytes_in;
-    out->peak_arena_bytes = e->arena_peak;
+    out->peak_arena_bytes = e->arena_occupied_peak;
+    out->arena_high_water_bytes = e->arena_hwm;
+    out->planned_arena_bytes = e->have_plan ? e->arena_cap : 0;
+    out->n_arena_overflow = e->arena_overflow;
     out->planned_peak_bytes = e->have_plan ? e->plan_res.planned_peak : 0;
     out->unswapped_peak_bytes = e->have_plan ? e->plan_res.unswapped_peak : 0;
     out->n_registered = (int)e->tensors.size();

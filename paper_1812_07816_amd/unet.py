@@ -352,7 +352,9 @@ class UNetStep:
 
     # ---- the step
     def run(self, update=True, trace=None, timeline=None):
-        """trace: optional dict that receives copies of intermediate tensors (tests).  timeline: optional list that
+        """trace: optional dict that receives copies of intermediate tensors (tests); the step then takes the skip
+        gradient in a pass of its own, so that the data gradient before it can be recorded, unless the dict has an
+        attribute keep_fused = True (then `<conv>.skip_add` is recorded instead).  timeline: optional list that
         receives (op name, "fwd" | "bwd", event recorded on the compute stream after the op) for a per-op time line."""
         e = self.engine
 
@@ -471,11 +473,13 @@ class UNetStep:
                         # the data gradient applies that LeakyReLU's derivative as well
                         mc.conv3d_dgrad_lrelu(op["desc"], da, self.w[op["w"]], self._need(op["src"]), SLOPE, nxt, self.ws)
                         premasked = True
-                    elif op["src"].id in dskip and dskip[op["src"].id][1] == 0 and trace is None:
+                    elif op["src"].id in dskip and dskip[op["src"].id][1] == 0 and (trace is None or getattr(trace, "keep_fused", False)):
                         # the input is also a skip connection whose second gradient is a tensor of its own: the
                         # data gradient adds it and applies the derivative of the producing layer in the same call
                         # (with normalisation the derivative is not a factor: the call only adds, slope 1)
                         d_skip, _ = dskip.pop(op["src"].id)
+                        if trace is not None:
+                            trace[op["name"] + ".skip_add"] = d_skip.clone()
                         mc.conv3d_dgrad_skip(op["desc"], da, self.w[op["w"]], d_skip, self._need(op["src"]),
                                              1.0 if self.norm else SLOPE, nxt, self.ws)
                         premasked = not self.norm

@@ -35,12 +35,37 @@ def bf16_bits(a):
     return (a.view(np.uint32) >> 16).astype(np.uint16)
 
 
+CHUNK = 1 << 24   # elements per independently generated piece of a large tensor
+
+
 def normal(config, tensor_index, shape, std=1.0, bf16=False):
-    g = rng(config, tensor_index)
-    a = g.standard_normal(size=shape, dtype=np.float32)
-    if std != 1.0:
-        a *= np.float32(std)
-    return bf16_round(a) if bf16 else a
+    """N(0, std^2) float32 values (bf16-exact if bf16).  Tensors of up to CHUNK elements come from one Philox stream;
+    larger ones are filled in pieces of CHUNK elements, piece i from the tensor's stream jumped i + 1 times, on a few
+    threads (the values depend on the seed and the shape only, not on the number of threads)."""
+    n = int(np.prod(shape))
+    if n <= CHUNK:
+        a = rng(config, tensor_index).standard_normal(size=shape, dtype=np.float32)
+        if std != 1.0:
+            a *= np.float32(std)
+        return bf16_round(a) if bf16 else a
+    import concurrent.futures
+    import os
+    out = np.empty(n, dtype=np.float32)
+    seed = BASE_SEED + 1000 * int(config) + int(tensor_index)
+
+    def fill(i):
+        piece = out[i * CHUNK:(i + 1) * CHUNK]
+        g = np.random.Generator(np.random.Philox(seed).jumped(i + 1))
+        g.standard_normal(size=piece.shape, dtype=np.float32, out=piece)
+        if std != 1.0:
+            piece *= np.float32(std)
+        if bf16:
+            piece[:] = bf16_round(piece)
+
+    workers = max(1, min(16, len(os.sched_getaffinity(0))))
+    with concurrent.futures.ThreadPoolExecutor(max_workers=workers) as ex:
+        list(ex.map(fill, range((n + CHUNK - 1) // CHUNK)))
+    return out.reshape(shape)
 
 
 def he_normal_weight(config, tensor_index, Cout, k, Cin, bf16=False):

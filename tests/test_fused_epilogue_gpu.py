@@ -145,15 +145,3 @@ def test_dgrad_skip_argument_checks(device):
     d32 = mc.make_desc(1, 8, 8, 8, 32, 64, 3, 2, 1, torch.float32)
     assert call(other.data_ptr(), other.data_ptr(), 0.01, d=d32) == -1   # bf16 only
     torch.cuda.synchronize()
-
-
-def test_bare_mfma_loop_diagnostic_runs_and_checks_its_arguments(device):
-    import ctypes
-    from paper_1812_07816_amd._lib import lib
-    t0, t1 = mc.probe_mfma_tflops(0, iters=2000), mc.probe_mfma_tflops(1, iters=2000)
-    assert 100.0 < t0 < 3000.0 and 100.0 < t1 < 3000.0, (t0, t1)
-    ws = torch.empty(lib().mi3d_probe_mfma_workspace_bytes(), dtype=torch.uint8, device="cuda")
-    fl = ctypes.c_double()
-    assert lib().mi3d_probe_mfma(0, 0, ws.data_ptr(), ws.numel(), ctypes.byref(fl), None) == -1      # iters must be positive
-    assert lib().mi3d_probe_mfma(0, 10, ws.data_ptr(), 1024, ctypes.byref(fl), None) == -3           # workspace too small
-    torch.cuda.synchronize()
