@@ -67,10 +67,9 @@ _cache = {}
 
 
 def _step(vol):
-    """One traced step per volume, kept for the tests of this module (tensors stay on the GPU)."""
+    """One traced step per volume, kept for the tests of this module (about 15 GB of traced tensors per volume stay
+    on the GPU until the last test of the module lets go of them)."""
     if vol not in _cache:
-        _cache.clear()
-        torch.cuda.empty_cache()
         from paper_1812_07816_amd import unet
         config = 5 if vol == 192 else 6
         x = si.normal(config, 0, (N, vol, vol, vol, 4), bf16=True)
@@ -105,8 +104,8 @@ def _check(what, got, ref):
     assert e <= TOL, (what, e)
 
 
-@pytest.mark.parametrize("vol", [192, 208])
 @pytest.mark.parametrize("name", list(CONVS))
+@pytest.mark.parametrize("vol", [192, 208])       # (the volume varies slowest: one traced step per volume)
 def test_convolution_ops_of_the_full_size_step(device, vol, name):
     from paper_1812_07816_amd import conv3d as mc
     c = _step(vol)
@@ -137,6 +136,9 @@ def test_convolution_ops_of_the_full_size_step(device, vol, name):
         ref = ref * np.where(src_a > 0, 1.0, SLOPE)
     if name + ".skip_add" in tr:             # the skip connection's second gradient joins in the same call
         assert name in SKIP_READERS
+        # (the call is defined as the stored, i.e. bf16-rounded, data gradient plus the second gradient, times the
+        # derivative: the reference takes the same storage rounding of the intermediate)
+        ref = si.bf16_round(ref.astype(np.float32)).astype(np.float64)
         ref = (ref + _pick(tr[name + ".skip_add"], idx)) * np.where(src_a > 0, 1.0, SLOPE)
     else:
         assert name not in SKIP_READERS
