@@ -99,6 +99,19 @@ int mi3d_conv3d_dgrad(const mi3d_conv_desc *desc, const void *dy, const void *w,
 int mi3d_conv3d_wgrad(const mi3d_conv_desc *desc, const void *x, const void *dy, float *dw,
                       void *ws, size_t ws_bytes, void *stream);
 
+/* mi3d_conv3d_wgrad for callers that cannot allocate device memory or pass a workspace: code under HIP graph
+ * capture, tight serving or training loops, harnesses that forbid hipMalloc.  Same result as mi3d_conv3d_wgrad, bit
+ * for bit (same kernels); the scratch the kernels need (per-workgroup partial sums, packed operands) is a static
+ * device array of MI3D_STATIC_SCRATCH_BYTES inside the library, which every GPU the library runs on holds from the
+ * first call until the process ends.  The call allocates nothing and frees nothing.  A geometry whose weight gradient
+ * needs more scratch than that (mi3d_conv3d_workspace_bytes(desc, MI3D_PASS_WGRAD) > MI3D_STATIC_SCRATCH_BYTES)
+ * returns MI3D_ERR_WORKSPACE and launches nothing; every layer of the 5-level U-Net at 192^3 and 208^3 fits.  All
+ * calls on one GPU share the one array: calls that overlap in time on the same GPU (two streams, two threads) race
+ * on it and must be serialised by the caller.  x, dy, dw: device pointers as for mi3d_conv3d_wgrad. */
+#define MI3D_STATIC_SCRATCH_BYTES (64u << 20)
+size_t mi3d_static_scratch_bytes(void);
+int mi3d_conv3d_wgrad_static(const mi3d_conv_desc *desc, const void *x, const void *dy, float *dw, void *stream);
+
 /* Channel-range operands for the decoder's 2x2x2 stride-2 up-sampling layers (Section 4.1: up-sampling,
  * then concatenation with the skip connection).  The tensor of x's shape (x of the forward pass and of the weight
  * gradient, dx of the data gradient) may be `Cin` channels starting at channel `offset` of a tensor that holds

@@ -66,6 +66,8 @@ SIGNATURES = {
     "mi3d_conv3d_fwd": (_i, [_pd, _vp, _vp, _vp, _vp, _sz, _vp]),
     "mi3d_conv3d_dgrad": (_i, [_pd, _vp, _vp, _vp, _vp, _sz, _vp]),
     "mi3d_conv3d_wgrad": (_i, [_pd, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "mi3d_static_scratch_bytes": (_sz, []),
+    "mi3d_conv3d_wgrad_static": (_i, [_pd, _vp, _vp, _vp, _vp]),
     "mi3d_conv3d_fwd_view": (_i, [_pd, _vp, ctypes.POINTER(View), _vp, _vp, _vp, _sz, _vp]),
     "mi3d_conv3d_dgrad_view": (_i, [_pd, _vp, _vp, _vp, ctypes.POINTER(View), _vp, _sz, _vp]),
     "mi3d_conv3d_wgrad_view": (_i, [_pd, _vp, ctypes.POINTER(View), _vp, _vp, _vp, _sz, _vp]),

@@ -268,3 +268,17 @@ def conv3d_wgrad(desc, x, dy, dw=None, ws=None):
     ws, p, n = _ws(desc, PASS_WGRAD, ws)
     check(lib().mi3d_conv3d_wgrad(ctypes.byref(desc), x.data_ptr(), dy.data_ptr(), dw.data_ptr(), p, n, _stream()), "conv3d_wgrad")
     return dw
+
+
+def static_scratch_bytes():
+    return int(lib().mi3d_static_scratch_bytes())
+
+
+def conv3d_wgrad_static(desc, x, dy, dw):
+    """conv3d_wgrad without a workspace argument and without any allocation: dw must be given; the scratch is the
+    library's static device array."""
+    xs, wsh, ys = _shapes(desc)
+    dt = _tdtype(desc)
+    _chk(x, xs, dt, "x"); _chk(dy, ys, dt, "dy"); _chk(dw, wsh, torch.float32, "dw")
+    check(lib().mi3d_conv3d_wgrad_static(ctypes.byref(desc), x.data_ptr(), dy.data_ptr(), dw.data_ptr(), _stream()), "conv3d_wgrad_static")
+    return dw

@@ -1,6 +1,7 @@
 // C ABI of the convolution passes: descriptor validation and kernel choice.
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 
 #include "mi3d_internal.h"
 
@@ -241,6 +242,45 @@ int mi3d_conv3d_dgrad(const mi3d_conv_desc* desc, const void* dy, const void* w,
 
 int mi3d_conv3d_wgrad(const mi3d_conv_desc* desc, const void* x, const void* dy, float* dw, void* ws, size_t ws_bytes, void* stream) {
     return conv_entry(desc, MI3D_PASS_WGRAD, x, dy, dw, ws, ws_bytes, stream);
+}
+
+// ---- weight gradient for callers that cannot allocate -------------------------------------------------------------
+// The per-workgroup partial sums of the weight-gradient kernels (and their packed operands) go to a file-scope device
+// array instead of a caller-provided workspace.  The array's name is only a host-side handle: its device address is
+// looked up once per device with hipGetSymbolAddress and that pointer is what the kernels get.
+static __device__ __align__(256) unsigned char scratch[MI3D_STATIC_SCRATCH_BYTES];
+static std::mutex g_scratch_mutex;
+static void* g_scratch_ptr[64] = {};   // per device; each device holds its own copy of the array at its own address
+
+static int scratch_of_current_device(void** out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) { note_hip_error(e); return MI3D_ERR_HIP; }
+    if (dev < 0 || dev >= 64) return MI3D_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) { note_hip_error(e); return MI3D_ERR_HIP; }
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return MI3D_OK;
+}
+
+size_t mi3d_static_scratch_bytes(void) { return MI3D_STATIC_SCRATCH_BYTES; }
+
+int mi3d_conv3d_wgrad_static(const mi3d_conv_desc* desc, const void* x, const void* dy, float* dw, void* stream) {
+    Geom g;
+    int st = make_geom(desc, &g);
+    if (st) return st;
+    // sizes beyond the array are refused before anything is looked up or launched
+    if (mi3d_conv3d_workspace_bytes(desc, MI3D_PASS_WGRAD) > (size_t)MI3D_STATIC_SCRATCH_BYTES) return MI3D_ERR_WORKSPACE;
+    void* ws = nullptr;
+    st = scratch_of_current_device(&ws);
+    if (st) return st;
+    // every kernel of the pass writes the part of the scratch it later reads, so nothing has to be cleared between calls
+    return conv_entry(desc, MI3D_PASS_WGRAD, x, dy, dw, ws, (size_t)MI3D_STATIC_SCRATCH_BYTES, stream);
 }
 
 int mi3d_conv3d_fwd_view(const mi3d_conv_desc* desc, const void* x, const mi3d_view* xv, const void* w, void* y, void* ws, size_t ws_bytes, void* stream) {
