@@ -44,10 +44,11 @@ static bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
 
 enum Kernel {
     K_DIRECT = 0, K_SP, K_WGRAD_MFMA, K_S2_FWD, K_WGRAD_S2, K_DGRAD_S2, K_C4_FWD, K_C4_DGRAD, K_C4_WGRAD, K_POINTWISE,
-    K_EMBED_C, K_EMBED_S, K_EMBED_K2, K_K2
+    K_EMBED_C, K_EMBED_S, K_EMBED_K2, K_K2, K_F32
 };
 
 static Kernel choose(const Geom& g, int pass) {
+    if (f32_supported(g, pass)) return K_F32;
     if (pointwise_supported(g)) return K_POINTWISE;
     if (pass == MI3D_PASS_WGRAD && wgrad_mfma_supported(g)) return K_WGRAD_MFMA;
     if (pass == MI3D_PASS_WGRAD && wgrad_s2_supported(g)) return K_WGRAD_S2;
@@ -80,6 +81,7 @@ static const char* kernel_name(Kernel k) {
         case K_EMBED_S: return "mfma_via_unit_stride";
         case K_EMBED_K2: return "mfma_via_k3s2_embedding";
         case K_K2: return "mfma_k2s2_panel_gemm";
+        case K_F32: return "mfma_f32_gather";
         default: return "none";
     }
 }
@@ -100,6 +102,7 @@ static size_t kernel_workspace(Kernel k, const Geom& g, int pass) {
         case K_EMBED_S: return embed_s_workspace_bytes(g, pass);
         case K_EMBED_K2: return embed_k2_workspace_bytes(g, pass);
         case K_K2: return k2_workspace_bytes(g, pass);
+        case K_F32: return f32_workspace_bytes(g, pass);
     }
     return 0;
 }
@@ -124,12 +127,16 @@ static int run_kernel(Kernel k, const Geom& g, int pass, const void* a, const vo
         case K_EMBED_S: return embed_s_conv(g, pass, a, b, out, ws, ws_bytes, s);
         case K_EMBED_K2: return embed_k2_conv(g, pass, a, b, out, ws, ws_bytes, s);
         case K_K2: return k2_conv(g, pass, a, b, out, ws, ws_bytes, s);
+        case K_F32:
+            if (pass == MI3D_PASS_WGRAD) return f32_wgrad(g, a, b, (float*)out, ws, ws_bytes, s);
+            return f32_conv(g, pass, a, b, out, ws, ws_bytes, s);
     }
     return MI3D_ERR_UNSUPPORTED;
 }
 
 // Kernels that apply the optional epilogue of the geometry themselves (the others are followed by one elementwise pass)
 static bool fuses_epilogue(Kernel k, const Geom& g, int pass) {
+    if (k == K_F32) return pass != MI3D_PASS_WGRAD;
     if (pass == MI3D_PASS_FWD) return k == K_SP || k == K_S2_FWD || k == K_C4_FWD;
     if (pass == MI3D_PASS_DGRAD) return (k == K_SP && sp_fuses_dgrad_factor(g)) || (k == K_DGRAD_S2 && dgrad_s2_fuses_factor(g)) || k == K_POINTWISE;
     return false;
@@ -139,6 +146,7 @@ static bool fuses_epilogue(Kernel k, const Geom& g, int pass) {
 static bool pair_supported(const Geom& g, int pass) {
     if (g.Cin % 64) return false;
     const Kernel k = choose(g, pass);
+    if (k == K_F32) return f32_takes_halves(g, pass);
     return pass == MI3D_PASS_WGRAD ? k == K_WGRAD_MFMA : k == K_SP;
 }
 
@@ -218,7 +226,7 @@ static int conv_entry(const mi3d_conv_desc* desc, int pass, const void* a, const
     Kernel k = choose(g, pass);
     const bool epilogue = slope != 1.f;
     if (!epilogue) return run_kernel(k, g, pass, a, b, out, ws, ws_bytes, (hipStream_t)stream);
-    if (!(slope >= 0.f && slope < 1.f) || g.dtype != MI3D_BF16 || pass == MI3D_PASS_WGRAD) return MI3D_ERR_INVALID_ARG;
+    if (!(slope >= 0.f && slope < 1.f) || (g.dtype != MI3D_BF16 && k != K_F32) || pass == MI3D_PASS_WGRAD) return MI3D_ERR_INVALID_ARG;
     if (pass == MI3D_PASS_DGRAD && (!ref || !aligned16(ref))) return MI3D_ERR_INVALID_ARG;
     Geom ge = g;
     ge.slope = slope;
@@ -302,10 +310,10 @@ int mi3d_conv3d_dgrad_skip(const mi3d_conv_desc* desc, const void* dy, const voi
     if (st) return st;
     if (!dy || !w || !add || !a_in || !dx || !aligned16(dy) || !aligned16(w) || !aligned16(add) || !aligned16(a_in) || !aligned16(dx) || !aligned16(ws))
         return MI3D_ERR_INVALID_ARG;
-    if (g.dtype != MI3D_BF16 || !(slope >= 0.f && slope <= 1.f) || (ws_bytes && !ws)) return MI3D_ERR_INVALID_ARG;
-    if (ws_bytes < mi3d_conv3d_workspace_bytes(desc, MI3D_PASS_DGRAD)) return MI3D_ERR_WORKSPACE;
     const Kernel k = choose(g, MI3D_PASS_DGRAD);
-    if (k == K_DGRAD_S2 && dgrad_s2_fuses_skip(g)) {
+    if ((g.dtype != MI3D_BF16 && k != K_F32) || !(slope >= 0.f && slope <= 1.f) || (ws_bytes && !ws)) return MI3D_ERR_INVALID_ARG;
+    if (ws_bytes < mi3d_conv3d_workspace_bytes(desc, MI3D_PASS_DGRAD)) return MI3D_ERR_WORKSPACE;
+    if (k == K_F32 || (k == K_DGRAD_S2 && dgrad_s2_fuses_skip(g))) {
         Geom ge = g;
         ge.add = add; ge.ref = a_in; ge.slope = slope;
         return run_kernel(k, ge, MI3D_PASS_DGRAD, dy, w, dx, ws, ws_bytes, (hipStream_t)stream);

@@ -1,0 +1,508 @@
+// fp32 convolution on the fp32 matrix cores (v_mfma_f32_32x32x2_f32): forward, data gradient and weight gradient of
+// the feature-map layers of Section 3.1 for any kernel extent up to 3 and stride up to 2, the precision the paper's
+// own runs presumably used (Section 4.1 names none).
+//
+// Forward pass and data gradient are one kernel, a "gather convolution" over an iteration space j:
+//     out[n, os * j + oo, m] = sum over taps t and channels k of  in[n, is * j + delta_t, k] * wt[t][k][m]
+// per axis.  The forward pass has is = stride, os = 1, delta_t = t - pad.  The stride-1 data gradient reads dy with
+// delta_t = pad - t and the weights with their channel roles swapped.  The stride-2 data gradient is split into the 8
+// parity classes of the output position: class pi writes positions 2 j + pi and sees the taps t with pi + pad - t
+// even, at delta_t = (pi + pad - t) / 2, so no product with a structural zero is formed.  The 2x2x2 stride-2
+// up-sampling layers (run as the data gradient of a 2x2x2 / stride-2 convolution) are the same thing with one tap per
+// class.
+// MFMA roles: A = weights (M = 32 output channels, K = 2 contracted channels), B = input (N = 32 positions along W),
+// so a lane ends with 16 output channels of one position.  A workgroup (4 waves) owns 8 rows x 32 columns of one j
+// plane for 32 or 64 output channels and stages, per group of taps that share an input plane and per chunk of the
+// contracted channels, the input patch with halo and the group's weights in LDS.  An fp32 MFMA takes 64 cycles and
+// needs 8 bytes of operands per lane, so plain 4-byte LDS reads keep it fed.
+//
+// Weight gradient: contraction over positions, A = dy (M = 32 output channels, K = 2 neighbouring positions along W),
+// B = x at the tap's shift (N = 32 input channels); a workgroup owns one 32 x 32 block of (cout, cin) for all taps
+// (dealt round-robin to its 4 waves) over a range of position tiles; per-workgroup partial sums are added in index
+// order by reduce_partials (bit-reproducible).
+#include "mi3d_internal.h"
+
+namespace mi3d {
+namespace {
+
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+
+constexpr int TJH = 8, TJW = 32;     // j tile of a workgroup (rows, columns); 2 rows per wave
+constexpr int MAX_TAPS = 27;
+constexpr int LDS_SOFT = 64 * 1024;  // two workgroups per CU while the tiles fit this
+
+struct GcParams {
+    const float* in; const float* in2;     // input (second half of the channels of a virtually concatenated input)
+    float* out; float* out2;               // output (second half of the channels of an output written as two tensors)
+    const float* wpack;                    // [tap][K][Mpad] weights, M fastest, zero beyond M
+    const float* ref; const float* add;    // optional epilogue operands of the output's shape (see GcEpilogue)
+    float slope;
+    int N, Di, Hi, Wi, K;                  // input extents, contracted channels
+    int Do, Ho, Wo, M, Mpad;               // output extents, output channels (padded to 32)
+    int in_pitch, in_split;                // channels per voxel of each input tensor; first channel that lives in in2
+    int out_pitch, out_split;              // same for the output
+    int Jd, Jh, Jw, JHT, JWT, MT;          // iteration space, tiles
+    int isd, ish, isw, osd, osh, osw, ood, ooh, oow;
+    int ntaps, ngroups;
+    int gstart[4];                         // taps of group g: gstart[g] .. gstart[g + 1] - 1 (sorted by plane offset)
+    int gd[3];                             // input plane offset of each group
+    signed char th[MAX_TAPS], tw[MAX_TAPS];  // row / column offsets of each tap
+    signed char tapidx[MAX_TAPS];            // its index in the layer's own tap order (slot in wpack)
+    int hmin, wmin, prows, pcols;          // smallest offsets; patch extent in LDS
+    int CK;                                // contracted channels per stage (even)
+};
+
+__device__ __forceinline__ f32x16 mfma2(float a, float b, f32x16 c) { return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0); }
+
+// CB = 32-wide blocks of output channels per workgroup
+template <int CB>
+__global__ void __launch_bounds__(256, 2) f32_gconv_kernel(GcParams P) {
+    extern __shared__ __attribute__((aligned(16))) float lds_f[];
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const int ln = lane & 31, half = lane >> 5;
+    const int xp = P.CK + 1;                                   // channel pitch of a staged voxel (odd: no bank conflicts)
+    float* xs = lds_f;                                         // [prows][pcols][CK + 1]
+    float* ws = lds_f + ((P.prows * P.pcols * xp + 3) & ~3);   // [taps of the group][CK][32 CB]
+
+    long long u = blockIdx.x;
+    const int mt = (int)(u % P.MT); u /= P.MT;
+    const int jwt = (int)(u % P.JWT); u /= P.JWT;
+    const int jht = (int)(u % P.JHT); u /= P.JHT;
+    const int jd = (int)(u % P.Jd);
+    const int n = (int)(u / P.Jd);
+    const int jh0 = jht * TJH, jw0 = jwt * TJW, m0 = mt * 32 * CB;
+
+    f32x16 acc[2][CB];
+#pragma unroll
+    for (int r = 0; r < 2; ++r)
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[r][cb][i] = 0.f;
+
+    const long long in_plane = (long long)P.Hi * P.Wi * P.in_pitch;
+    const int row0 = 2 * wave;   // first of this wave's two rows inside the tile
+    for (int c0 = 0; c0 < P.K; c0 += P.CK) {
+        const bool hi_in = c0 >= P.in_split;
+        const float* src = (hi_in ? P.in2 : P.in) + (long long)n * P.Di * in_plane + (hi_in ? c0 - P.in_split : c0);
+        for (int g = 0; g < P.ngroups; ++g) {
+            const int id = P.isd * jd + P.gd[g];
+            const int t0 = P.gstart[g], nt = P.gstart[g + 1] - t0;
+            __syncthreads();   // the previous stage's readers are done
+            // ---- input patch: rows ish * jh0 + hmin .., columns isw * jw0 + wmin .., channels c0 .. c0 + CK - 1
+            const bool plane_ok = id >= 0 && id < P.Di;
+            const int nvox = P.prows * P.pcols;
+            if ((P.CK & 3) == 0 && (P.in_pitch & 3) == 0) {
+                const int q4 = P.CK >> 2;
+                for (int e = t; e < nvox * q4; e += 256) {
+                    const int v = e / q4, q = e - v * q4;
+                    const int pr = v / P.pcols, pc = v - pr * P.pcols;
+                    const int ih = P.ish * jh0 + P.hmin + pr, iw = P.isw * jw0 + P.wmin + pc;
+                    float4 val = make_float4(0.f, 0.f, 0.f, 0.f);
+                    if (plane_ok && ih >= 0 && ih < P.Hi && iw >= 0 && iw < P.Wi)
+                        val = *(const float4*)(src + (long long)id * in_plane + ((long long)ih * P.Wi + iw) * P.in_pitch + 4 * q);
+                    float* d = xs + v * xp + 4 * q;
+                    d[0] = val.x; d[1] = val.y; d[2] = val.z; d[3] = val.w;
+                }
+            } else {   // ragged channel counts: element by element, zero beyond K
+                for (int e = t; e < nvox * P.CK; e += 256) {
+                    const int v = e / P.CK, q = e - v * P.CK;
+                    const int pr = v / P.pcols, pc = v - pr * P.pcols;
+                    const int ih = P.ish * jh0 + P.hmin + pr, iw = P.isw * jw0 + P.wmin + pc;
+                    float val = 0.f;
+                    if (plane_ok && c0 + q < P.K && ih >= 0 && ih < P.Hi && iw >= 0 && iw < P.Wi)
+                        val = src[(long long)id * in_plane + ((long long)ih * P.Wi + iw) * P.in_pitch + q];
+                    xs[v * xp + q] = val;
+                }
+            }
+            // ---- weights of the group's taps: ws[tap][k][m] for m in this workgroup's blocks
+            const int wrow = 32 * CB;
+            for (int e = t; e < nt * P.CK * (wrow >> 2); e += 256) {
+                const int m4 = e % (wrow >> 2);
+                const int k = (e / (wrow >> 2)) % P.CK;
+                const int tp = e / ((wrow >> 2) * P.CK);
+                float4 val = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (c0 + k < P.K && m0 + 4 * m4 < P.Mpad)
+                    val = *(const float4*)(P.wpack + ((long long)P.tapidx[t0 + tp] * P.K + c0 + k) * P.Mpad + m0 + 4 * m4);
+                *(float4*)(ws + (tp * P.CK + k) * wrow + 4 * m4) = val;
+            }
+            __syncthreads();
+            if (!plane_ok) continue;   // zero padding plane: nothing to add (uniform over the workgroup)
+            // ---- MFMAs: per tap and pair of contracted channels, 2 rows x CB blocks
+            for (int tp = 0; tp < nt; ++tp) {
+                const int dh = P.th[t0 + tp] - P.hmin, dw = P.tw[t0 + tp] - P.wmin;
+                const float* b0 = xs + (((row0 + 0) * P.ish + dh) * P.pcols + ln * P.isw + dw) * xp + half;
+                const float* b1 = xs + (((row0 + 1) * P.ish + dh) * P.pcols + ln * P.isw + dw) * xp + half;
+                const float* a = ws + (tp * P.CK + half) * wrow + ln;
+#pragma unroll 4
+                for (int kk = 0; kk < P.CK; kk += 2) {
+                    const float x0 = b0[kk], x1 = b1[kk];
+#pragma unroll
+                    for (int cb = 0; cb < CB; ++cb) {
+                        const float wv = a[kk * wrow + 32 * cb];
+                        acc[0][cb] = mfma2(wv, x0, acc[0][cb]);
+                        acc[1][cb] = mfma2(wv, x1, acc[1][cb]);
+                    }
+                }
+            }
+        }
+    }
+    // ---- epilogue: lane (position ln, half) holds output channels 8 (i / 4) + 4 half + i % 4 of each block
+    const bool vec = (P.out_pitch & 3) == 0;
+#pragma unroll
+    for (int r = 0; r < 2; ++r) {
+        const int jh = jh0 + row0 + r, jw = jw0 + ln;
+        if (jh >= P.Jh || jw >= P.Jw) continue;
+        const int od = P.osd * jd + P.ood, oh = P.osh * jh + P.ooh, ow = P.osw * jw + P.oow;
+        const long long vox = (((long long)n * P.Do + od) * P.Ho + oh) * P.Wo + ow;
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+            for (int g4 = 0; g4 < 4; ++g4) {
+                int c = m0 + 32 * cb + 8 * g4 + 4 * half;
+                if (c >= P.M) continue;
+                float v[4] = {acc[r][cb][4 * g4], acc[r][cb][4 * g4 + 1], acc[r][cb][4 * g4 + 2], acc[r][cb][4 * g4 + 3]};
+                const bool hi_out = c >= P.out_split;
+                float* dst = (hi_out ? P.out2 : P.out) + vox * P.out_pitch + (hi_out ? c - P.out_split : c);
+                const long long eoff = vox * P.out_pitch + (hi_out ? c - P.out_split : c);   // same offset in ref / add (never split)
+                const int nv = P.M - c < 4 ? P.M - c : 4;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    if (i >= nv) break;
+                    float x = v[i];
+                    if (P.add) x += P.add[eoff + i];
+                    if (P.ref) x = P.ref[eoff + i] > 0.f ? x : P.slope * x;
+                    else x = x > 0.f ? x : P.slope * x;
+                    v[i] = x;
+                }
+                if (vec && nv == 4) *(float4*)dst = make_float4(v[0], v[1], v[2], v[3]);
+                else
+                    for (int i = 0; i < nv; ++i) dst[i] = v[i];
+            }
+    }
+}
+
+// wpack[t][k][m] (m padded to Mpad with zeros) from w[co][t][ci]; swap = 0: (k, m) = (ci, co); swap = 1: (k, m) = (co, ci)
+__global__ void __launch_bounds__(256) f32_pack_kernel(const float* __restrict__ w, float* __restrict__ wpack, int Cout, int Cin, int T, int Mpad, int swap) {
+    const int K = swap ? Cout : Cin, M = swap ? Cin : Cout;
+    const long long total = (long long)T * K * Mpad;
+    const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= total) return;
+    const int m = (int)(idx % Mpad);
+    const int k = (int)((idx / Mpad) % K);
+    const int t = (int)(idx / ((long long)Mpad * K));
+    float v = 0.f;
+    if (m < M) {
+        const int co = swap ? k : m, ci = swap ? m : k;
+        v = w[((long long)co * T + t) * Cin + ci];
+    }
+    wpack[idx] = v;
+}
+
+// ---- weight gradient ------------------------------------------------------------------------------------------------
+struct WgParams {
+    const float* x; const float* x2;   // input (second half of the channels of a virtually concatenated input)
+    const float* dy;
+    float* part;                       // [split][Cout][T][Cin]
+    int N, D, H, W, Cin, Cout, Do, Ho, Wo;
+    int kD, kH, kW, sD, sH, sW, pD, pH, pW, T;
+    int x_pitch, x_split;
+    int TR, TW;                        // output tile: rows, columns (16 or 32)
+    int HT, WT, CIT, COT, S;           // tiles per plane, channel blocks, splits
+    long long units;                   // N * Do * HT * WT
+    int prows, pcols;                  // staged x patch per plane
+};
+
+__global__ void __launch_bounds__(256, 2) f32_wgrad_kernel(WgParams P) {
+    extern __shared__ __attribute__((aligned(16))) float lds_f[];
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const int ln = lane & 31, half = lane >> 5;
+    constexpr int CP = 33;                                     // channel pitch of a staged voxel
+    float* dys = lds_f;                                        // [TR][TW][33]
+    float* xs = lds_f + P.TR * P.TW * CP;                      // [kD][prows][pcols][33]
+    int b = blockIdx.x;
+    const int split = b % P.S; b /= P.S;
+    const int cit = b % P.CIT;
+    const int cot = b / P.CIT;
+    const int ci0 = cit * 32, co0 = cot * 32;
+    const bool hi_x = ci0 >= P.x_split;
+    const float* xsrc = (hi_x ? P.x2 : P.x) + (hi_x ? ci0 - P.x_split : ci0);
+
+    constexpr int MAXA = 7;   // taps per wave: 27 taps dealt round-robin to 4 waves
+    f32x16 acc[MAXA];
+#pragma unroll
+    for (int a = 0; a < MAXA; ++a)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[a][i] = 0.f;
+
+    const long long u0 = P.units * split / P.S, u1 = P.units * (split + 1) / P.S;
+    const long long x_plane = (long long)P.H * P.W * P.x_pitch;
+    for (long long u = u0; u < u1; ++u) {
+        long long r = u;
+        const int wt = (int)(r % P.WT); r /= P.WT;
+        const int ht = (int)(r % P.HT); r /= P.HT;
+        const int od = (int)(r % P.Do);
+        const int n = (int)(r / P.Do);
+        const int oh0 = ht * P.TR, ow0 = wt * P.TW;
+        __syncthreads();
+        // ---- dy tile: TR rows x TW columns x 32 output channels (zero outside the tensor)
+        for (int e = t; e < P.TR * P.TW * 32; e += 256) {
+            const int c = e & 31, v = e >> 5;
+            const int tr = v / P.TW, tc = v - tr * P.TW;
+            const int oh = oh0 + tr, ow = ow0 + tc;
+            float val = 0.f;
+            if (oh < P.Ho && ow < P.Wo && co0 + c < P.Cout)
+                val = P.dy[((((long long)n * P.Do + od) * P.Ho + oh) * P.Wo + ow) * P.Cout + co0 + c];
+            dys[v * CP + c] = val;
+        }
+        // ---- x patches of the kD input planes: rows oh0 sH - pH .., columns ow0 sW - pW .., 32 input channels
+        const int pv = P.prows * P.pcols;
+        for (int e = t; e < P.kD * pv * 32; e += 256) {
+            const int c = e & 31, v = e >> 5;
+            const int kd = v / pv, q = v - kd * pv;
+            const int pr = q / P.pcols, pc = q - pr * P.pcols;
+            const int id = od * P.sD - P.pD + kd, ih = oh0 * P.sH - P.pH + pr, iw = ow0 * P.sW - P.pW + pc;
+            float val = 0.f;
+            if (id >= 0 && id < P.D && ih >= 0 && ih < P.H && iw >= 0 && iw < P.W && ci0 + c < P.Cin)
+                val = xsrc[((long long)n * P.D + id) * x_plane + ((long long)ih * P.W + iw) * P.x_pitch + c];
+            xs[v * CP + c] = val;
+        }
+        __syncthreads();
+        // ---- this wave's taps: K runs over pairs of neighbouring output columns
+#pragma unroll
+        for (int a = 0; a < MAXA; ++a) {
+            const int tap = wave + 4 * a;
+            if (tap >= P.T) break;
+            const int kw = tap % P.kW, kh = (tap / P.kW) % P.kH, kd = tap / (P.kW * P.kH);
+            for (int tr = 0; tr < P.TR; ++tr) {
+                const float* ap = dys + (tr * P.TW + half) * CP + ln;
+                const float* bp = xs + ((kd * P.prows + tr * P.sH + kh) * P.pcols + half * P.sW + kw) * CP + ln;
+#pragma unroll 4
+                for (int c2 = 0; c2 < P.TW; c2 += 2)
+                    acc[a] = mfma2(ap[c2 * CP], bp[c2 * P.sW * CP], acc[a]);
+            }
+        }
+    }
+    // ---- partial sums: lane holds input channel ci0 + ln, output channels co0 + 8 (i / 4) + 4 half + i % 4
+    float* part = P.part + (long long)split * P.Cout * P.T * P.Cin;
+#pragma unroll
+    for (int a = 0; a < MAXA; ++a) {
+        const int tap = wave + 4 * a;
+        if (tap >= P.T) break;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int co = co0 + 8 * (i >> 2) + 4 * half + (i & 3), ci = ci0 + ln;
+            if (co < P.Cout && ci < P.Cin) part[((long long)co * P.T + tap) * P.Cin + ci] = acc[a][i];
+        }
+    }
+}
+
+int cu_count() {
+    int dev = 0, cus = 256;
+    if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+    return cus;
+}
+
+// one axis of the gather convolution: valid taps of a class and their input offsets
+struct AxisTaps { int n; int t[3]; int d[3]; };
+
+// forward: every tap, delta = t - p.  data gradient, stride 1: every tap, delta = p - t.  data gradient, stride 2,
+// class pi: taps with pi + p - t even, delta = (pi + p - t) / 2 (floor division is exact here, also for negatives)
+AxisTaps axis_taps(int k, int s, int p, bool dgrad, int pi) {
+    AxisTaps a{0, {0, 0, 0}, {0, 0, 0}};
+    for (int t = 0; t < k; ++t) {
+        if (!dgrad) { a.t[a.n] = t; a.d[a.n++] = t - p; continue; }
+        const int v = pi + p - t;
+        if (v % s) continue;
+        a.t[a.n] = t; a.d[a.n++] = v / s;
+    }
+    return a;
+}
+
+size_t pack_bytes(const Geom& g, int pass) {
+    const int K = pass == MI3D_PASS_DGRAD ? g.Cout : g.Cin, M = pass == MI3D_PASS_DGRAD ? g.Cin : g.Cout;
+    const int Mpad = (M + 31) / 32 * 32;
+    return ((size_t)g.taps() * K * Mpad * sizeof(float) + 255) & ~(size_t)255;
+}
+
+void wgrad_layout(const Geom& g, WgParams* P) {
+    P->TR = 2;
+    P->TW = (g.sW == 1) ? 32 : 16;
+    P->prows = (P->TR - 1) * g.sH + g.kH;
+    P->pcols = (P->TW - 1) * g.sW + g.kW;
+    P->HT = (g.Ho + P->TR - 1) / P->TR;
+    P->WT = (g.Wo + P->TW - 1) / P->TW;
+    P->CIT = (g.Cin + 31) / 32;
+    P->COT = (g.Cout + 31) / 32;
+    P->units = (long long)g.N * g.Do * P->HT * P->WT;
+    long long s = 2ll * cu_count() / ((long long)P->CIT * P->COT);
+    if (s < 1) s = 1;
+    if (s > P->units) s = P->units;
+    if (s > 256) s = 256;
+    P->S = (int)s;
+}
+
+}  // namespace
+
+bool f32_supported(const Geom& g, int pass) {
+    if (g.dtype != MI3D_F32) return false;
+    if (g.kD > 3 || g.kH > 3 || g.kW > 3 || g.sD > 2 || g.sH > 2 || g.sW > 2) return false;
+    if (g.pD > 2 || g.pH > 2 || g.pW > 2) return false;
+    // 32-bit offsets inside one sample's plane and sane grids
+    if ((long long)g.H * g.W * g.Cin >= (1ll << 30) || (long long)g.Ho * g.Wo * g.Cout >= (1ll << 30)) return false;
+    if (g.w_elems() >= (1ll << 28)) return false;
+    if (pass == MI3D_PASS_WGRAD) {
+        WgParams P;
+        wgrad_layout(g, &P);
+        const size_t lds = ((size_t)P.TR * P.TW + (size_t)g.kD * P.prows * P.pcols) * 33 * sizeof(float);
+        return lds <= 160 * 1024 && (long long)P.CIT * P.COT * P.S < (1ll << 30);
+    }
+    return true;
+}
+
+size_t f32_workspace_bytes(const Geom& g, int pass) {
+    if (!f32_supported(g, pass)) return 0;
+    if (pass == MI3D_PASS_WGRAD) {
+        WgParams P;
+        wgrad_layout(g, &P);
+        return (size_t)P.S * g.w_elems() * sizeof(float);
+    }
+    return pack_bytes(g, pass);
+}
+
+bool f32_takes_halves(const Geom& g, int pass) {   // virtual concatenation: halves of Cin in multiples of 32 channels
+    return f32_supported(g, pass) && g.Cin % 64 == 0;
+}
+
+static int launch_gconv(GcParams& P, hipStream_t s) {
+    // contracted channels per stage: the largest even chunk that keeps the tiles of a stage within LDS_SOFT
+    const int CB = P.M > 32 ? 2 : 1;
+    P.MT = (P.Mpad + 32 * CB - 1) / (32 * CB);
+    int max_group = 1;
+    for (int g = 0; g < P.ngroups; ++g) max_group = max_group > P.gstart[g + 1] - P.gstart[g] ? max_group : P.gstart[g + 1] - P.gstart[g];
+    auto lds_bytes = [&](int ck) {
+        return (size_t)(((P.prows * P.pcols * (ck + 1) + 3) & ~3) + max_group * ck * 32 * CB) * sizeof(float);
+    };
+    int ck = 32;
+    const int kpad = (P.K + 1) & ~1;
+    if (ck > kpad) ck = kpad;
+    while (ck > 2 && (lds_bytes(ck) > (size_t)LDS_SOFT || (kpad % ck && ck > 4))) ck >>= 1;
+    if (ck < 2) ck = 2;
+    if (lds_bytes(ck) > 160 * 1024) return MI3D_ERR_UNSUPPORTED;
+    P.CK = ck;
+    P.JHT = (P.Jh + TJH - 1) / TJH;
+    P.JWT = (P.Jw + TJW - 1) / TJW;
+    const long long blocks = (long long)P.N * P.Jd * P.JHT * P.JWT * P.MT;
+    if (blocks <= 0) return MI3D_OK;
+    if (blocks > 0x7fffffffll) return MI3D_ERR_UNSUPPORTED;
+    const size_t lds = lds_bytes(ck);
+    static std::atomic<bool> attr_set{false};   // set once per process; a second thread racing here repeats an idempotent call
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void*)f32_gconv_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e == hipSuccess) e = hipFuncSetAttribute((const void*)f32_gconv_kernel<2>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e == hipSuccess) e = hipFuncSetAttribute((const void*)f32_wgrad_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e != hipSuccess) { note_hip_error(e); return MI3D_ERR_HIP; }
+        attr_set = true;
+    }
+    if (CB == 2) f32_gconv_kernel<2><<<(unsigned)blocks, 256, lds, s>>>(P);
+    else f32_gconv_kernel<1><<<(unsigned)blocks, 256, lds, s>>>(P);
+    return check_launch();
+}
+
+// forward (in = x, out = y) and data gradient (in = dy, out = dx)
+int f32_conv(const Geom& g, int pass, const void* in, const void* w, void* out, void* ws, size_t ws_bytes, hipStream_t s) {
+    if (ws_bytes < f32_workspace_bytes(g, pass)) return MI3D_ERR_WORKSPACE;
+    const bool dgrad = pass == MI3D_PASS_DGRAD;
+    const int T = (int)g.taps();
+    const int K = dgrad ? g.Cout : g.Cin, M = dgrad ? g.Cin : g.Cout, Mpad = (M + 31) / 32 * 32;
+    const long long total = (long long)T * K * Mpad;
+    f32_pack_kernel<<<(unsigned)((total + 255) / 256), 256, 0, s>>>((const float*)w, (float*)ws, g.Cout, g.Cin, T, Mpad, dgrad ? 1 : 0);
+    int st = check_launch();
+    if (st) return st;
+    GcParams B;
+    B.in = B.in2 = (const float*)in;
+    B.out = B.out2 = (float*)out;
+    B.ref = (const float*)g.ref;
+    B.add = (const float*)g.add;
+    B.slope = g.slope;
+    B.N = g.N; B.K = K; B.M = M; B.Mpad = Mpad;
+    B.in_pitch = K; B.in_split = 1 << 30; B.out_pitch = M; B.out_split = 1 << 30;
+    if (!dgrad) {
+        B.Di = g.D; B.Hi = g.H; B.Wi = g.W; B.Do = g.Do; B.Ho = g.Ho; B.Wo = g.Wo;
+        if (g.hi) { B.in2 = (const float*)g.hi; B.in_pitch = K / 2; B.in_split = K / 2; }
+    } else {
+        B.Di = g.Do; B.Hi = g.Ho; B.Wi = g.Wo; B.Do = g.D; B.Ho = g.H; B.Wo = g.W;
+        if (g.hi) { B.out2 = (float*)g.hi; B.out_pitch = M / 2; B.out_split = M / 2; }
+    }
+    const int sD = dgrad ? g.sD : 1, sH = dgrad ? g.sH : 1, sW = dgrad ? g.sW : 1;   // number of classes per axis
+    for (int pd = 0; pd < sD; ++pd)
+        for (int ph = 0; ph < sH; ++ph)
+            for (int pw = 0; pw < sW; ++pw) {
+                GcParams P = B;
+                const AxisTaps ad = axis_taps(g.kD, g.sD, g.pD, dgrad, pd), ah = axis_taps(g.kH, g.sH, g.pH, dgrad, ph),
+                               aw = axis_taps(g.kW, g.sW, g.pW, dgrad, pw);
+                if (!dgrad) {
+                    P.Jd = g.Do; P.Jh = g.Ho; P.Jw = g.Wo;
+                    P.isd = g.sD; P.ish = g.sH; P.isw = g.sW;
+                    P.osd = P.osh = P.osw = 1; P.ood = P.ooh = P.oow = 0;
+                } else {
+                    P.Jd = (g.D - pd + g.sD - 1) / g.sD; P.Jh = (g.H - ph + g.sH - 1) / g.sH; P.Jw = (g.W - pw + g.sW - 1) / g.sW;
+                    P.isd = P.ish = P.isw = 1;
+                    P.osd = g.sD; P.osh = g.sH; P.osw = g.sW; P.ood = pd; P.ooh = ph; P.oow = pw;
+                }
+                if (P.Jd <= 0 || P.Jh <= 0 || P.Jw <= 0) continue;
+                // taps grouped by input plane offset (the kd axis is the outer one)
+                P.ntaps = 0; P.ngroups = 0;
+                int hmin = 1 << 20, hmax = -(1 << 20), wmin = 1 << 20, wmax = -(1 << 20);
+                for (int a = 0; a < ad.n; ++a) {
+                    P.gstart[P.ngroups] = P.ntaps;
+                    P.gd[P.ngroups] = ad.d[a];
+                    for (int bq = 0; bq < ah.n; ++bq)
+                        for (int c = 0; c < aw.n; ++c) {
+                            P.th[P.ntaps] = (signed char)ah.d[bq];
+                            P.tw[P.ntaps] = (signed char)aw.d[c];
+                            P.tapidx[P.ntaps] = (signed char)((ad.t[a] * g.kH + ah.t[bq]) * g.kW + aw.t[c]);
+                            hmin = hmin < ah.d[bq] ? hmin : ah.d[bq]; hmax = hmax > ah.d[bq] ? hmax : ah.d[bq];
+                            wmin = wmin < aw.d[c] ? wmin : aw.d[c]; wmax = wmax > aw.d[c] ? wmax : aw.d[c];
+                            ++P.ntaps;
+                        }
+                    if (P.ntaps > P.gstart[P.ngroups]) ++P.ngroups;
+                }
+                P.gstart[P.ngroups] = P.ntaps;
+                if (P.ntaps == 0) { hmin = hmax = wmin = wmax = 0; }   // a class no tap reaches: zeros (plus the epilogue)
+                P.hmin = hmin; P.wmin = wmin;
+                P.prows = (TJH - 1) * P.ish + (hmax - hmin) + 1;
+                P.pcols = (TJW - 1) * P.isw + (wmax - wmin) + 1;
+                P.wpack = (const float*)ws;
+                st = launch_gconv(P, s);
+                if (st) return st;
+            }
+    return MI3D_OK;
+}
+
+int f32_wgrad(const Geom& g, const void* x, const void* dy, float* dw, void* ws, size_t ws_bytes, hipStream_t s) {
+    if (ws_bytes < f32_workspace_bytes(g, MI3D_PASS_WGRAD)) return MI3D_ERR_WORKSPACE;
+    WgParams P;
+    wgrad_layout(g, &P);
+    P.x = P.x2 = (const float*)x;
+    P.dy = (const float*)dy;
+    P.part = (float*)ws;
+    P.N = g.N; P.D = g.D; P.H = g.H; P.W = g.W; P.Cin = g.Cin; P.Cout = g.Cout; P.Do = g.Do; P.Ho = g.Ho; P.Wo = g.Wo;
+    P.kD = g.kD; P.kH = g.kH; P.kW = g.kW; P.sD = g.sD; P.sH = g.sH; P.sW = g.sW; P.pD = g.pD; P.pH = g.pH; P.pW = g.pW;
+    P.T = (int)g.taps();
+    P.x_pitch = g.Cin; P.x_split = 1 << 30;
+    if (g.hi) { P.x2 = (const float*)g.hi; P.x_pitch = g.Cin / 2; P.x_split = g.Cin / 2; }
+    const size_t lds = ((size_t)P.TR * P.TW + (size_t)g.kD * P.prows * P.pcols) * 33 * sizeof(float);
+    static std::atomic<bool> attr_set{false};   // set once per process; a second thread racing here repeats an idempotent call
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void*)f32_wgrad_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e != hipSuccess) { note_hip_error(e); return MI3D_ERR_HIP; }
+        attr_set = true;
+    }
+    f32_wgrad_kernel<<<(unsigned)(P.CIT * P.COT * P.S), 256, lds, s>>>(P);
+    int st = check_launch();
+    if (st) return st;
+    return reduce_partials((const float*)ws, dw, g.w_elems(), P.S, s);
+}
+
+}  // namespace mi3d

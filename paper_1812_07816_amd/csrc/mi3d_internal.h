@@ -151,6 +151,13 @@ bool embed_k2_supported(const Geom& g, int pass);
 size_t embed_k2_workspace_bytes(const Geom& g, int pass);
 int embed_k2_conv(const Geom& g, int pass, const void* a, const void* b, void* out, void* ws, size_t ws_bytes, hipStream_t s);
 
+// fp32 MFMA kernels: any kernel extent up to 3 and stride up to 2 (forward, data gradient, weight gradient)
+bool f32_supported(const Geom& g, int pass);
+size_t f32_workspace_bytes(const Geom& g, int pass);
+int f32_conv(const Geom& g, int pass, const void* in, const void* w, void* out, void* ws, size_t ws_bytes, hipStream_t s);
+int f32_wgrad(const Geom& g, const void* x, const void* dy, float* dw, void* ws, size_t ws_bytes, hipStream_t s);
+bool f32_takes_halves(const Geom& g, int pass);   // the tensor of x's shape as two halves along the channels
+
 // automatic kernel choice for a geometry (a, b, out per pass: fwd (x, w, y), dgrad (dy, w, dx), wgrad (x, dy, dw))
 size_t auto_workspace_bytes(const Geom& g, int pass);
 int auto_conv(const Geom& g, int pass, const void* a, const void* b, void* out, void* ws, size_t ws_bytes, hipStream_t s);

@@ -79,6 +79,35 @@ def test_mid_shapes_bf16_full(device, case):
     _check(parity.run_case(91, 10 * MID.index(case), *case, bf16=True, full=True), True, f"mid{case}")
 
 
+# ---- the fp32 path on the fp32 matrix cores: every kind of layer of the network, full oracle, 1e-4
+MID_F32 = [
+    (1, 10, 20, 40, 32, 32, 3, 1, 1),
+    (2, 6, 18, 70, 32, 32, 3, 1, 1),
+    (1, 9, 17, 33, 4, 32, 3, 1, 1),
+    (1, 8, 16, 32, 64, 32, 3, 1, 1),
+    (1, 12, 14, 34, 32, 64, 3, 2, 1),
+    (1, 9, 21, 37, 32, 32, 3, 2, 1),
+    (1, 8, 10, 12, 32, 96, 3, 2, 0),
+    (1, 6, 6, 12, 128, 64, 3, 1, 1),
+    (1, 4, 4, 6, 320, 320, 3, 1, 1),
+    (1, 4, 6, 6, 256, 320, 3, 2, 1),
+    (1, 5, 19, 45, 4, 32, 3, 1, 0),
+    (1, 4, 16, 33, 4, 32, 3, 1, 2),
+    (1, 6, 10, 40, 32, 3, 1, 1, 0),
+    (1, 8, 8, 16, 32, 64, 2, 2, 0),
+    (2, 6, 10, 14, 64, 128, 2, 2, 0),
+    (1, 7, 9, 11, 6, 10, 3, 2, 1),
+    (1, 6, 7, 9, 34, 36, (3, 2, 3), (1, 2, 1), (1, 0, 2)),
+]
+
+
+@pytest.mark.parametrize("case", MID_F32)
+def test_mid_shapes_fp32_full(device, case):
+    desc = mc.make_desc(*case, torch.float32)
+    assert all(mc.kernel_name(desc, q) == "mfma_f32_gather" for q in range(3))
+    _check(parity.run_case(96, 10 * MID_F32.index(case), *case, bf16=False, full=True), False, f"mid fp32 {case}")
+
+
 # ---- config 2: 128^3 first level ------------------------------------------
 @pytest.mark.parametrize("cin", [4, 32])
 def test_config2_128cube(device, cin):
