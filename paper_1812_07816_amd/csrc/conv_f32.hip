@@ -209,17 +209,22 @@ struct WgParams {
     int x_pitch, x_split;
     int TR, TW;                        // output tile: rows, columns (16 or 32)
     int HT, WT, CIT, COT, S;           // tiles per plane, channel blocks, splits
-    long long units;                   // N * Do * HT * WT
+    long long units;                   // N * HT * WT * Do, Do fastest: a workgroup walks along D
     int prows, pcols;                  // staged x patch per plane
+    unsigned pcols_magic;              // q / pcols == (q * pcols_magic) >> 16 for every q < prows * pcols (checked on the host)
 };
 
+// A workgroup walks a contiguous range of (sample, tile, output plane) units with the output plane running fastest, so
+// consecutive units share input planes: the kD planes a unit needs live in a ring of kD LDS slots (plane id in slot
+// id mod kD) and only the planes that were not there for the previous unit are fetched.
 __global__ void __launch_bounds__(256, 2) f32_wgrad_kernel(WgParams P) {
     extern __shared__ __attribute__((aligned(16))) float lds_f[];
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     const int ln = lane & 31, half = lane >> 5;
-    constexpr int CP = 33;                                     // channel pitch of a staged voxel
-    float* dys = lds_f;                                        // [TR][TW][33]
-    float* xs = lds_f + P.TR * P.TW * CP;                      // [kD][prows][pcols][33]
+    constexpr int CP = 32;                                     // channels per staged voxel (reads run along the channels)
+    float* dys = lds_f;                                        // [TR][TW][32]
+    float* xs = lds_f + P.TR * P.TW * CP;                      // [kD ring][prows][pcols][32]
+    const int pv = P.prows * P.pcols;
     int b = blockIdx.x;
     const int split = b % P.S; b /= P.S;
     const int cit = b % P.CIT;
@@ -227,6 +232,7 @@ __global__ void __launch_bounds__(256, 2) f32_wgrad_kernel(WgParams P) {
     const int ci0 = cit * 32, co0 = cot * 32;
     const bool hi_x = ci0 >= P.x_split;
     const float* xsrc = (hi_x ? P.x2 : P.x) + (hi_x ? ci0 - P.x_split : ci0);
+    const bool vec_x = (P.x_pitch & 3) == 0 && (P.Cin & 3) == 0, vec_dy = (P.Cout & 3) == 0;
 
     constexpr int MAXA = 7;   // taps per wave: 27 taps dealt round-robin to 4 waves
     f32x16 acc[MAXA];
@@ -237,36 +243,69 @@ __global__ void __launch_bounds__(256, 2) f32_wgrad_kernel(WgParams P) {
 
     const long long u0 = P.units * split / P.S, u1 = P.units * (split + 1) / P.S;
     const long long x_plane = (long long)P.H * P.W * P.x_pitch;
+    const int c4 = t & 7, vslot = t >> 3;   // staging: 8 threads x 16 bytes per voxel, 32 voxels per pass
+    long long cur_col = -1;
+    int have_lo = 1, have_hi = 0;           // input planes resident in the ring (none)
     for (long long u = u0; u < u1; ++u) {
-        long long r = u;
+        const long long col = u / P.Do;
+        const int od = (int)(u - col * P.Do);
+        long long r = col;
         const int wt = (int)(r % P.WT); r /= P.WT;
-        const int ht = (int)(r % P.HT); r /= P.HT;
-        const int od = (int)(r % P.Do);
-        const int n = (int)(r / P.Do);
+        const int ht = (int)(r % P.HT);
+        const int n = (int)(r / P.HT);
         const int oh0 = ht * P.TR, ow0 = wt * P.TW;
-        __syncthreads();
+        if (col != cur_col) { cur_col = col; have_lo = 1; have_hi = 0; }
+        const int need_lo = od * P.sD - P.pD, need_hi = need_lo + P.kD - 1;
+        __syncthreads();   // every wave is done with the previous unit's tiles
         // ---- dy tile: TR rows x TW columns x 32 output channels (zero outside the tensor)
-        for (int e = t; e < P.TR * P.TW * 32; e += 256) {
-            const int c = e & 31, v = e >> 5;
-            const int tr = v / P.TW, tc = v - tr * P.TW;
-            const int oh = oh0 + tr, ow = ow0 + tc;
-            float val = 0.f;
-            if (oh < P.Ho && ow < P.Wo && co0 + c < P.Cout)
-                val = P.dy[((((long long)n * P.Do + od) * P.Ho + oh) * P.Wo + ow) * P.Cout + co0 + c];
-            dys[v * CP + c] = val;
+        if (vec_dy) {
+            for (int v = vslot; v < P.TR * P.TW; v += 32) {
+                const int tr = v / P.TW, tc = v - tr * P.TW;
+                const int oh = oh0 + tr, ow = ow0 + tc;
+                float4 val = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (oh < P.Ho && ow < P.Wo && co0 + 4 * c4 < P.Cout)
+                    val = *(const float4*)(P.dy + ((((long long)n * P.Do + od) * P.Ho + oh) * P.Wo + ow) * P.Cout + co0 + 4 * c4);
+                *(float4*)(dys + v * CP + 4 * c4) = val;
+            }
+        } else {
+            for (int e = t; e < P.TR * P.TW * 32; e += 256) {
+                const int c = e & 31, v = e >> 5;
+                const int tr = v / P.TW, tc = v - tr * P.TW;
+                const int oh = oh0 + tr, ow = ow0 + tc;
+                float val = 0.f;
+                if (oh < P.Ho && ow < P.Wo && co0 + c < P.Cout)
+                    val = P.dy[((((long long)n * P.Do + od) * P.Ho + oh) * P.Wo + ow) * P.Cout + co0 + c];
+                dys[v * CP + c] = val;
+            }
         }
-        // ---- x patches of the kD input planes: rows oh0 sH - pH .., columns ow0 sW - pW .., 32 input channels
-        const int pv = P.prows * P.pcols;
-        for (int e = t; e < P.kD * pv * 32; e += 256) {
-            const int c = e & 31, v = e >> 5;
-            const int kd = v / pv, q = v - kd * pv;
-            const int pr = q / P.pcols, pc = q - pr * P.pcols;
-            const int id = od * P.sD - P.pD + kd, ih = oh0 * P.sH - P.pH + pr, iw = ow0 * P.sW - P.pW + pc;
-            float val = 0.f;
-            if (id >= 0 && id < P.D && ih >= 0 && ih < P.H && iw >= 0 && iw < P.W && ci0 + c < P.Cin)
-                val = xsrc[((long long)n * P.D + id) * x_plane + ((long long)ih * P.W + iw) * P.x_pitch + c];
-            xs[v * CP + c] = val;
+        // ---- x patches: rows oh0 sH - pH .., columns ow0 sW - pW .., 32 input channels, of the planes not yet in the ring
+        for (int id = need_lo; id <= need_hi; ++id) {
+            if (id >= have_lo && id <= have_hi) continue;
+            float* dst = xs + (((id % P.kD) + P.kD) % P.kD) * pv * CP;
+            const bool plane_ok = id >= 0 && id < P.D;
+            const float* src = xsrc + ((long long)n * P.D + (plane_ok ? id : 0)) * x_plane;
+            if (vec_x) {
+                for (int q = vslot; q < pv; q += 32) {
+                    const int pr = (int)(((unsigned)q * P.pcols_magic) >> 16), pc = q - pr * P.pcols;
+                    const int ih = oh0 * P.sH - P.pH + pr, iw = ow0 * P.sW - P.pW + pc;
+                    float4 val = make_float4(0.f, 0.f, 0.f, 0.f);
+                    if (plane_ok && ih >= 0 && ih < P.H && iw >= 0 && iw < P.W && ci0 + 4 * c4 < P.Cin)
+                        val = *(const float4*)(src + ((long long)ih * P.W + iw) * P.x_pitch + 4 * c4);
+                    *(float4*)(dst + q * CP + 4 * c4) = val;
+                }
+            } else {
+                for (int e = t; e < pv * 32; e += 256) {
+                    const int c = e & 31, q = e >> 5;
+                    const int pr = (int)(((unsigned)q * P.pcols_magic) >> 16), pc = q - pr * P.pcols;
+                    const int ih = oh0 * P.sH - P.pH + pr, iw = ow0 * P.sW - P.pW + pc;
+                    float val = 0.f;
+                    if (plane_ok && ih >= 0 && ih < P.H && iw >= 0 && iw < P.W && ci0 + c < P.Cin)
+                        val = src[((long long)ih * P.W + iw) * P.x_pitch + c];
+                    dst[q * CP + c] = val;
+                }
+            }
         }
+        have_lo = need_lo; have_hi = need_hi;
         __syncthreads();
         // ---- this wave's taps: K runs over pairs of neighbouring output columns
 #pragma unroll
@@ -274,9 +313,11 @@ __global__ void __launch_bounds__(256, 2) f32_wgrad_kernel(WgParams P) {
             const int tap = wave + 4 * a;
             if (tap >= P.T) break;
             const int kw = tap % P.kW, kh = (tap / P.kW) % P.kH, kd = tap / (P.kW * P.kH);
+            const int id = need_lo + kd;
+            const float* plane = xs + (((id % P.kD) + P.kD) % P.kD) * pv * CP;
             for (int tr = 0; tr < P.TR; ++tr) {
                 const float* ap = dys + (tr * P.TW + half) * CP + ln;
-                const float* bp = xs + ((kd * P.prows + tr * P.sH + kh) * P.pcols + half * P.sW + kw) * CP + ln;
+                const float* bp = plane + ((tr * P.sH + kh) * P.pcols + half * P.sW + kw) * CP + ln;
 #pragma unroll 4
                 for (int c2 = 0; c2 < P.TW; c2 += 2)
                     acc[a] = mfma2(ap[c2 * CP], bp[c2 * P.sW * CP], acc[a]);
@@ -330,16 +371,24 @@ void wgrad_layout(const Geom& g, WgParams* P) {
     P->TW = (g.sW == 1) ? 32 : 16;
     P->prows = (P->TR - 1) * g.sH + g.kH;
     P->pcols = (P->TW - 1) * g.sW + g.kW;
+    P->pcols_magic = 65536u / (unsigned)P->pcols + 1u;
     P->HT = (g.Ho + P->TR - 1) / P->TR;
     P->WT = (g.Wo + P->TW - 1) / P->TW;
     P->CIT = (g.Cin + 31) / 32;
     P->COT = (g.Cout + 31) / 32;
     P->units = (long long)g.N * g.Do * P->HT * P->WT;
-    long long s = 2ll * cu_count() / ((long long)P->CIT * P->COT);
+    // about four workgroups per CU in all, each with at least a few units to walk
+    long long s = 4ll * cu_count() / ((long long)P->CIT * P->COT);
+    if (s > P->units / 4) s = P->units / 4;
+    if (s > 1024) s = 1024;
     if (s < 1) s = 1;
-    if (s > P->units) s = P->units;
-    if (s > 256) s = 256;
     P->S = (int)s;
+}
+
+bool wgrad_magic_ok(const WgParams& P) {
+    for (unsigned q = 0; q < (unsigned)(P.prows * P.pcols); ++q)
+        if (((q * P.pcols_magic) >> 16) != q / (unsigned)P.pcols) return false;
+    return true;
 }
 
 }  // namespace
@@ -354,8 +403,8 @@ bool f32_supported(const Geom& g, int pass) {
     if (pass == MI3D_PASS_WGRAD) {
         WgParams P;
         wgrad_layout(g, &P);
-        const size_t lds = ((size_t)P.TR * P.TW + (size_t)g.kD * P.prows * P.pcols) * 33 * sizeof(float);
-        return lds <= 160 * 1024 && (long long)P.CIT * P.COT * P.S < (1ll << 30);
+        const size_t lds = ((size_t)P.TR * P.TW + (size_t)g.kD * P.prows * P.pcols) * 32 * sizeof(float);
+        return lds <= 160 * 1024 && (long long)P.CIT * P.COT * P.S < (1ll << 30) && wgrad_magic_ok(P);
     }
     return true;
 }
@@ -492,7 +541,7 @@ int f32_wgrad(const Geom& g, const void* x, const void* dy, float* dw, void* ws,
     P.T = (int)g.taps();
     P.x_pitch = g.Cin; P.x_split = 1 << 30;
     if (g.hi) { P.x2 = (const float*)g.hi; P.x_pitch = g.Cin / 2; P.x_split = g.Cin / 2; }
-    const size_t lds = ((size_t)P.TR * P.TW + (size_t)g.kD * P.prows * P.pcols) * 33 * sizeof(float);
+    const size_t lds = ((size_t)P.TR * P.TW + (size_t)g.kD * P.prows * P.pcols) * 32 * sizeof(float);
     static std::atomic<bool> attr_set{false};   // set once per process; a second thread racing here repeats an idempotent call
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void*)f32_wgrad_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
