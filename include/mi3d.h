@@ -208,6 +208,8 @@ int mi3d_leaky_relu_fwd(void *a, size_t n, float slope, void *stream);
 /* da[i] <- da[i] * (a[i] > 0 ? 1 : slope), in place on da; a is the OUTPUT of
  * the activation (it has the sign of its input, so the input is not kept). */
 int mi3d_leaky_relu_bwd(void *da, const void *a, size_t n, float slope, void *stream);
+/* The same on fp32 tensors (the fp32 training step). */
+int mi3d_leaky_relu_bwd_f32(float *da, const float *a, size_t n, float slope, void *stream);
 /* out[v][0:Ca] = a[v][:], out[v][Ca:Ca+Cb] = b[v][:] over `voxels` voxels
  * (bf16; Ca, Cb multiples of 8).  The decoder's [upsampled, skip] input. */
 int mi3d_concat_channels(const void *a, int Ca, const void *b, int Cb, void *out, size_t voxels, void *stream);
@@ -242,6 +244,12 @@ int mi3d_dice_loss(const void *logits, const uint8_t *labels, size_t voxels, int
 int mi3d_dice_grad(const void *logits, const uint8_t *labels, size_t voxels, int classes, float eps,
                    const float *sums, void *dlogits, void *stream);
 
+/* The two calls above on fp32 logits / gradients (the fp32 training step); same sums, same order. */
+int mi3d_dice_loss_f32(const float *logits, const uint8_t *labels, size_t voxels, int classes, float eps,
+                       void *ws, size_t ws_bytes, float *sums, float *loss, void *stream);
+int mi3d_dice_grad_f32(const float *logits, const uint8_t *labels, size_t voxels, int classes, float eps,
+                       const float *sums, float *dlogits, void *stream);
+
 /* Instance normalisation (Section 4.1: every convolution of the network is followed by an instance normalisation
  * and a LeakyReLU), without learnable scale and shift.  Tensors are bf16 NDHWC with `voxels` voxels per sample and C
  * channels (C % 8 == 0, C <= 512); stats is N x C x 2 floats (mean, 1 / sqrt(var + eps), biased variance over the
@@ -260,7 +268,8 @@ int mi3d_instnorm_lrelu_bwd(void *da, const void *a, const float *stats, int N, 
                             void *ws, size_t ws_bytes, void *stream);
 
 /* w[i] <- w[i] - lr * dw[i] on the fp32 master weights; w_bf16[i] <- the
- * updated value rounded to bf16 (the copy the convolutions read). */
+ * updated value rounded to bf16 (the copy the bf16 convolutions read; NULL in
+ * the fp32 step, whose convolutions read w itself). */
 int mi3d_sgd_update(float *w, const float *dw, void *w_bf16, size_t n, float lr, void *stream);
 /* Adam, the optimiser the paper trains with (Section 4.1), on fp32 state (m, v: first and second moment, n values each,
  * zero before step 1): m <- beta1 m + (1 - beta1) dw, v <- beta2 v + (1 - beta2) dw^2,

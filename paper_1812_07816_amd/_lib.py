@@ -47,6 +47,9 @@ SIGNATURES = {
     "mi3d_conv3d_out_dims": (_i, [_pd, _pi, _pi, _pi]),
     "mi3d_leaky_relu_fwd": (_i, [_vp, _sz, ctypes.c_float, _vp]),
     "mi3d_leaky_relu_bwd": (_i, [_vp, _vp, _sz, ctypes.c_float, _vp]),
+    "mi3d_leaky_relu_bwd_f32": (_i, [_vp, _vp, _sz, ctypes.c_float, _vp]),
+    "mi3d_dice_loss_f32": (_i, [_vp, _vp, _sz, _i, ctypes.c_float, _vp, _sz, _vp, _vp, _vp]),
+    "mi3d_dice_grad_f32": (_i, [_vp, _vp, _sz, _i, ctypes.c_float, _vp, _vp, _vp]),
     "mi3d_concat_channels": (_i, [_vp, _i, _vp, _i, _vp, _sz, _vp]),
     "mi3d_split_channels": (_i, [_vp, _i, _i, _vp, _vp, _sz, _vp]),
     "mi3d_add_inplace": (_i, [_vp, _vp, _sz, _vp]),

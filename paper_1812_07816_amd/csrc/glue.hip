@@ -33,6 +33,26 @@ __device__ __forceinline__ uint4 pack8(const float (&f)[8]) {
     return uint4{w[0], w[1], w[2], w[3]};
 }
 
+// 8 consecutive values of a bf16 (F32 = false) or fp32 (F32 = true) tensor, piece index i
+template <bool F32>
+__device__ __forceinline__ void load8(const void* base, long long i, float (&f)[8]) {
+    if (F32) {
+        const float4 a = ((const float4*)base)[2 * i], b = ((const float4*)base)[2 * i + 1];
+        f[0] = a.x; f[1] = a.y; f[2] = a.z; f[3] = a.w; f[4] = b.x; f[5] = b.y; f[6] = b.z; f[7] = b.w;
+    } else {
+        unpack8(((const uint4*)base)[i], f);
+    }
+}
+template <bool F32>
+__device__ __forceinline__ void store8(void* base, long long i, const float (&f)[8]) {
+    if (F32) {
+        ((float4*)base)[2 * i] = make_float4(f[0], f[1], f[2], f[3]);
+        ((float4*)base)[2 * i + 1] = make_float4(f[4], f[5], f[6], f[7]);
+    } else {
+        ((uint4*)base)[i] = pack8(f);
+    }
+}
+
 // a <- a > 0 ? a : slope * a, in place; n8 = number of 16-byte pieces
 __global__ void __launch_bounds__(256) lrelu_fwd_kernel(uint4* __restrict__ a, long long n8, float slope) {
     for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < n8; i += (long long)gridDim.x * 256) {
@@ -45,14 +65,15 @@ __global__ void __launch_bounds__(256) lrelu_fwd_kernel(uint4* __restrict__ a, l
 }
 
 // da <- da * (a > 0 ? 1 : slope), in place on da; a holds the activation's OUTPUT (same sign as its input)
-__global__ void __launch_bounds__(256) lrelu_bwd_kernel(uint4* __restrict__ da, const uint4* __restrict__ a, long long n8, float slope) {
+template <bool F32>
+__global__ void __launch_bounds__(256) lrelu_bwd_kernel(void* __restrict__ da, const void* __restrict__ a, long long n8, float slope) {
     for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < n8; i += (long long)gridDim.x * 256) {
         float g[8], f[8];
-        unpack8(da[i], g);
-        unpack8(a[i], f);
+        load8<F32>(da, i, g);
+        load8<F32>(a, i, f);
 #pragma unroll
         for (int j = 0; j < 8; ++j) g[j] = f[j] > 0.f ? g[j] : slope * g[j];
-        da[i] = pack8(g);
+        store8<F32>(da, i, g);
     }
 }
 
@@ -141,8 +162,8 @@ __device__ __forceinline__ float sigmoidf(float x) { return 1.f / (1.f + __expf(
 // Soft Dice, first pass.  A thread takes groups of 8 voxels = 8 C values (C 16-byte pieces of logits, C 8-byte
 // pieces of labels); value e of a group belongs to class e % C.  Per class: sum p t, sum p, sum t.  A block
 // owns a contiguous range of groups; per-thread sums are combined in a fixed tree and written as one partial.
-template <int C>
-__global__ void __launch_bounds__(256) dice_partial_kernel(const uint4* __restrict__ logits, const uint2* __restrict__ labels,
+template <int C, bool F32>
+__global__ void __launch_bounds__(256) dice_partial_kernel(const void* __restrict__ logits, const uint2* __restrict__ labels,
                                                            long long groups, float* __restrict__ part) {
     __shared__ float red[3 * C][256];
     const long long g0 = groups * blockIdx.x / gridDim.x, g1 = groups * (blockIdx.x + 1) / gridDim.x;
@@ -153,7 +174,7 @@ __global__ void __launch_bounds__(256) dice_partial_kernel(const uint4* __restri
 #pragma unroll
         for (int q = 0; q < C; ++q) {
             float x[8];
-            unpack8(logits[g * C + q], x);
+            load8<F32>(logits, g * C + q, x);
             const uint2 lb = labels[g * C + q];
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
@@ -209,9 +230,9 @@ __global__ void __launch_bounds__(256) dice_final_kernel(const float* __restrict
 }
 
 // dloss/dlogit = -(1/C) (2 t den - (2 I + eps)) / den^2 * p (1 - p), den = P + T + eps
-template <int C>
-__global__ void __launch_bounds__(256) dice_grad_kernel(const uint4* __restrict__ logits, const uint2* __restrict__ labels, long long groups,
-                                                        float eps, const float* __restrict__ sums, uint4* __restrict__ dlogits) {
+template <int C, bool F32>
+__global__ void __launch_bounds__(256) dice_grad_kernel(const void* __restrict__ logits, const uint2* __restrict__ labels, long long groups,
+                                                        float eps, const float* __restrict__ sums, void* __restrict__ dlogits) {
     float ka[C], kb[C];  // gradient wrt p = ka * t + kb
 #pragma unroll
     for (int c = 0; c < C; ++c) {
@@ -223,7 +244,7 @@ __global__ void __launch_bounds__(256) dice_grad_kernel(const uint4* __restrict_
 #pragma unroll
         for (int q = 0; q < C; ++q) {
             float x[8];
-            unpack8(logits[g * C + q], x);
+            load8<F32>(logits, g * C + q, x);
             const uint2 lb = labels[g * C + q];
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
@@ -232,7 +253,7 @@ __global__ void __launch_bounds__(256) dice_grad_kernel(const uint4* __restrict_
                 const float p = sigmoidf(x[j]);
                 x[j] = (ka[cls] * t + kb[cls]) * p * (1.f - p);
             }
-            dlogits[g * C + q] = pack8(x);
+            store8<F32>(dlogits, g * C + q, x);
         }
     }
 }
@@ -242,7 +263,7 @@ __global__ void __launch_bounds__(256) sgd_kernel(float* __restrict__ w, const f
     for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < n; i += (long long)gridDim.x * 256) {
         const float v = w[i] - lr * dw[i];
         w[i] = v;
-        wb[i] = f32_to_bf16(v);
+        if (wb) wb[i] = f32_to_bf16(v);
     }
 }
 
@@ -258,7 +279,7 @@ __global__ void __launch_bounds__(256) adam_kernel(float* __restrict__ w, const 
         v[i] = vi;
         const float x = w[i] - lr * (mi / c1) / (sqrtf(vi / c2) + eps);
         w[i] = x;
-        wb[i] = f32_to_bf16(x);
+        if (wb) wb[i] = f32_to_bf16(x);
     }
 }
 
@@ -286,7 +307,14 @@ int mi3d_leaky_relu_fwd(void* a, size_t n, float slope, void* stream) {
 int mi3d_leaky_relu_bwd(void* da, const void* a, size_t n, float slope, void* stream) {
     if (!da || !a || !al16(da) || !al16(a) || n % 8) return MI3D_ERR_INVALID_ARG;
     if (n == 0) return MI3D_OK;
-    lrelu_bwd_kernel<<<grid_for(n / 8), 256, 0, (hipStream_t)stream>>>((uint4*)da, (const uint4*)a, (long long)(n / 8), slope);
+    lrelu_bwd_kernel<false><<<grid_for(n / 8), 256, 0, (hipStream_t)stream>>>(da, a, (long long)(n / 8), slope);
+    return check_launch();
+}
+
+int mi3d_leaky_relu_bwd_f32(float* da, const float* a, size_t n, float slope, void* stream) {
+    if (!da || !a || !al16(da) || !al16(a) || n % 8) return MI3D_ERR_INVALID_ARG;
+    if (n == 0) return MI3D_OK;
+    lrelu_bwd_kernel<true><<<grid_for(n / 8), 256, 0, (hipStream_t)stream>>>(da, a, (long long)(n / 8), slope);
     return check_launch();
 }
 
@@ -345,32 +373,54 @@ int mi3d_add_inplace(void* a, const void* b, size_t n, void* stream) {
 
 size_t mi3d_dice_workspace_bytes(int classes) { return (size_t)DICE_BLOCKS * 3 * (classes > 0 ? classes : 1) * sizeof(float); }
 
-int mi3d_dice_loss(const void* logits, const uint8_t* labels, size_t voxels, int classes, float eps,
-                   void* ws, size_t ws_bytes, float* sums, float* loss, void* stream) {
+static int dice_loss_any(bool f32, const void* logits, const uint8_t* labels, size_t voxels, int classes, float eps,
+                         void* ws, size_t ws_bytes, float* sums, float* loss, void* stream) {
     if (!logits || !labels || !ws || !sums || !loss || !al16(logits) || ((uintptr_t)labels & 7) || voxels == 0 || voxels % 8) return MI3D_ERR_INVALID_ARG;
     if (classes != 3) return MI3D_ERR_UNSUPPORTED;
     if (ws_bytes < mi3d_dice_workspace_bytes(classes)) return MI3D_ERR_WORKSPACE;
     const long long groups = (long long)(voxels / 8);
     const int blocks = (int)(groups < DICE_BLOCKS ? groups : DICE_BLOCKS);
-    dice_partial_kernel<3><<<blocks, 256, 0, (hipStream_t)stream>>>((const uint4*)logits, (const uint2*)labels, groups, (float*)ws);
+    if (f32) dice_partial_kernel<3, true><<<blocks, 256, 0, (hipStream_t)stream>>>(logits, (const uint2*)labels, groups, (float*)ws);
+    else dice_partial_kernel<3, false><<<blocks, 256, 0, (hipStream_t)stream>>>(logits, (const uint2*)labels, groups, (float*)ws);
     int st = check_launch();
     if (st) return st;
     dice_final_kernel<3><<<1, 256, 0, (hipStream_t)stream>>>((const float*)ws, blocks, eps, sums, loss);
     return check_launch();
 }
 
-int mi3d_dice_grad(const void* logits, const uint8_t* labels, size_t voxels, int classes, float eps,
-                   const float* sums, void* dlogits, void* stream) {
+static int dice_grad_any(bool f32, const void* logits, const uint8_t* labels, size_t voxels, int classes, float eps,
+                         const float* sums, void* dlogits, void* stream) {
     if (!logits || !labels || !sums || !dlogits || !al16(logits) || !al16(dlogits) || ((uintptr_t)labels & 7) || voxels == 0 || voxels % 8)
         return MI3D_ERR_INVALID_ARG;
     if (classes != 3) return MI3D_ERR_UNSUPPORTED;
     const long long groups = (long long)(voxels / 8);
-    dice_grad_kernel<3><<<grid_for(groups), 256, 0, (hipStream_t)stream>>>((const uint4*)logits, (const uint2*)labels, groups, eps, sums, (uint4*)dlogits);
+    if (f32) dice_grad_kernel<3, true><<<grid_for(groups), 256, 0, (hipStream_t)stream>>>(logits, (const uint2*)labels, groups, eps, sums, dlogits);
+    else dice_grad_kernel<3, false><<<grid_for(groups), 256, 0, (hipStream_t)stream>>>(logits, (const uint2*)labels, groups, eps, sums, dlogits);
     return check_launch();
 }
 
+int mi3d_dice_loss(const void* logits, const uint8_t* labels, size_t voxels, int classes, float eps,
+                   void* ws, size_t ws_bytes, float* sums, float* loss, void* stream) {
+    return dice_loss_any(false, logits, labels, voxels, classes, eps, ws, ws_bytes, sums, loss, stream);
+}
+
+int mi3d_dice_grad(const void* logits, const uint8_t* labels, size_t voxels, int classes, float eps,
+                   const float* sums, void* dlogits, void* stream) {
+    return dice_grad_any(false, logits, labels, voxels, classes, eps, sums, dlogits, stream);
+}
+
+int mi3d_dice_loss_f32(const float* logits, const uint8_t* labels, size_t voxels, int classes, float eps,
+                       void* ws, size_t ws_bytes, float* sums, float* loss, void* stream) {
+    return dice_loss_any(true, logits, labels, voxels, classes, eps, ws, ws_bytes, sums, loss, stream);
+}
+
+int mi3d_dice_grad_f32(const float* logits, const uint8_t* labels, size_t voxels, int classes, float eps,
+                       const float* sums, float* dlogits, void* stream) {
+    return dice_grad_any(true, logits, labels, voxels, classes, eps, sums, dlogits, stream);
+}
+
 int mi3d_sgd_update(float* w, const float* dw, void* w_bf16, size_t n, float lr, void* stream) {
-    if (!w || !dw || !w_bf16) return MI3D_ERR_INVALID_ARG;
+    if (!w || !dw) return MI3D_ERR_INVALID_ARG;
     if (n == 0) return MI3D_OK;
     sgd_kernel<<<grid_for((long long)n), 256, 0, (hipStream_t)stream>>>(w, dw, (uint16_t*)w_bf16, (long long)n, lr);
     return check_launch();
@@ -378,7 +428,7 @@ int mi3d_sgd_update(float* w, const float* dw, void* w_bf16, size_t n, float lr,
 
 int mi3d_adam_update(float* w, const float* dw, float* m, float* v, void* w_bf16, size_t n, float lr, float beta1, float beta2, float eps,
                      int step, void* stream) {
-    if (!w || !dw || !m || !v || !w_bf16 || step < 1) return MI3D_ERR_INVALID_ARG;
+    if (!w || !dw || !m || !v || step < 1) return MI3D_ERR_INVALID_ARG;
     if (!(beta1 >= 0.f && beta1 < 1.f && beta2 >= 0.f && beta2 < 1.f && eps > 0.f)) return MI3D_ERR_INVALID_ARG;
     if (n == 0) return MI3D_OK;
     const float c1 = (float)(1.0 - pow((double)beta1, (double)step)), c2 = (float)(1.0 - pow((double)beta2, (double)step));

@@ -16,8 +16,11 @@ def leaky_relu_fwd(a, slope=0.01):
 
 
 def leaky_relu_bwd(da, a, slope=0.01):
-    assert da.numel() == a.numel()
-    check(lib().mi3d_leaky_relu_bwd(_p(da), _p(a), a.numel(), slope, _stream()), "leaky_relu_bwd")
+    assert da.numel() == a.numel() and da.dtype == a.dtype
+    if da.dtype == torch.float32:
+        check(lib().mi3d_leaky_relu_bwd_f32(_p(da), _p(a), a.numel(), slope, _stream()), "leaky_relu_bwd_f32")
+    else:
+        check(lib().mi3d_leaky_relu_bwd(_p(da), _p(a), a.numel(), slope, _stream()), "leaky_relu_bwd")
 
 
 def concat_channels(a, b, out):
@@ -69,23 +72,27 @@ def dice_workspace(classes=3):
 def dice_loss(logits, labels, ws, sums, loss, eps=1e-5):
     C = logits.shape[-1]
     vox = logits.numel() // C
-    check(lib().mi3d_dice_loss(_p(logits), _p(labels), vox, C, eps, _p(ws), ws.numel(), _p(sums), _p(loss), _stream()), "dice_loss")
+    fn = lib().mi3d_dice_loss_f32 if logits.dtype == torch.float32 else lib().mi3d_dice_loss
+    check(fn(_p(logits), _p(labels), vox, C, eps, _p(ws), ws.numel(), _p(sums), _p(loss), _stream()), "dice_loss")
 
 
 def dice_grad(logits, labels, sums, dlogits, eps=1e-5):
     C = logits.shape[-1]
     vox = logits.numel() // C
-    check(lib().mi3d_dice_grad(_p(logits), _p(labels), vox, C, eps, _p(sums), _p(dlogits), _stream()), "dice_grad")
+    assert logits.dtype == dlogits.dtype
+    fn = lib().mi3d_dice_grad_f32 if logits.dtype == torch.float32 else lib().mi3d_dice_grad
+    check(fn(_p(logits), _p(labels), vox, C, eps, _p(sums), _p(dlogits), _stream()), "dice_grad")
 
 
 def sgd_update(w32, dw32, w16, lr):
-    assert w32.numel() == dw32.numel() == w16.numel()
-    check(lib().mi3d_sgd_update(_p(w32), _p(dw32), _p(w16), w32.numel(), lr, _stream()), "sgd_update")
+    """w16 None: no bf16 working copy (the fp32 step)."""
+    assert w32.numel() == dw32.numel() and (w16 is None or w16.numel() == w32.numel())
+    check(lib().mi3d_sgd_update(_p(w32), _p(dw32), None if w16 is None else _p(w16), w32.numel(), lr, _stream()), "sgd_update")
 
 
 def adam_update(w32, dw32, m32, v32, w16, lr, step, beta1=0.9, beta2=0.999, eps=1e-8):
-    assert w32.numel() == dw32.numel() == m32.numel() == v32.numel() == w16.numel()
-    check(lib().mi3d_adam_update(_p(w32), _p(dw32), _p(m32), _p(v32), _p(w16), w32.numel(), lr, beta1, beta2, eps, int(step), _stream()), "adam_update")
+    assert w32.numel() == dw32.numel() == m32.numel() == v32.numel() and (w16 is None or w16.numel() == w32.numel())
+    check(lib().mi3d_adam_update(_p(w32), _p(dw32), _p(m32), _p(v32), None if w16 is None else _p(w16), w32.numel(), lr, beta1, beta2, eps, int(step), _stream()), "adam_update")
 
 
 IN_EPS = 1e-5

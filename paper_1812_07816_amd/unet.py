@@ -36,8 +36,8 @@ def _numel(shape):
 class _Saved:
     """A tensor produced in the forward pass and needed again in the backward pass."""
 
-    def __init__(self, sid, shape, produce, tag):
-        self.id, self.shape, self.bytes = sid, tuple(shape), _numel(shape) * 2
+    def __init__(self, sid, shape, produce, tag, esize=2):
+        self.id, self.shape, self.bytes = sid, tuple(shape), _numel(shape) * esize
         self.produce, self.last_fwd, self.tag = produce, produce, tag
         self.complete = produce    # forward op after which the contents are final (a swap-out may start)
         self.bwd_ops = []          # backward ops that read it
@@ -47,10 +47,16 @@ class _Saved:
 class UNetStep:
     def __init__(self, N, vol, channels, weights, x, labels, lr=1e-2, in_ch=4, classes=3, swap=True,
                  budget_bytes=None, lookahead=2, policy=sw.POLICY_BUDGET, n_tensors=-1, exclude_tags=0,
-                 eviction=sw.EVICT_SWAP, optimizer="sgd", norm=False, virtual_cat=True, fused_stats=True):
+                 eviction=sw.EVICT_SWAP, optimizer="sgd", norm=False, virtual_cat=True, fused_stats=True, dtype=torch.bfloat16):
         """weights: list of float32 CPU tensors/arrays (bf16-exact start values) in the order enc convs,
-        (dec up, conv1, conv2) from the deepest decoder level up, head; x: bf16 CUDA [N,vol,vol,vol,in_ch];
-        labels: uint8 CUDA [N,vol,vol,vol,classes]."""
+        (dec up, conv1, conv2) from the deepest decoder level up, head; x: CUDA [N,vol,vol,vol,in_ch] of `dtype`;
+        labels: uint8 CUDA [N,vol,vol,vol,classes].  dtype: torch.bfloat16 (bf16 activations and working weights, fp32
+        master weights) or torch.float32 (everything fp32: the convolutions run on the fp32 matrix cores and read the
+        master weights themselves)."""
+        assert dtype in (torch.bfloat16, torch.float32) and x.dtype == dtype
+        assert not (norm and dtype == torch.float32), "the instance-normalisation passes are bf16 only"
+        assert virtual_cat or dtype == torch.bfloat16, "the materialised concatenation is bf16 only"
+        self.dtype, self.esize = dtype, (2 if dtype == torch.bfloat16 else 4)
         self.N, self.vol, self.ch, self.L = N, vol, list(channels), len(channels)
         self.lr, self.classes, self.swap_on = lr, classes, swap
         self.x_in, self.labels = x, labels
@@ -69,14 +75,15 @@ class UNetStep:
         if optimizer == "adam":    # first and second moments (Section 4.1 trains with Adam)
             self.m32 = torch.zeros(total, dtype=torch.float32, device="cuda")
             self.v32 = torch.zeros(total, dtype=torch.float32, device="cuda")
-        self.w16 = torch.zeros(total, dtype=torch.bfloat16, device="cuda")
+        self.w16 = torch.zeros(total, dtype=torch.bfloat16, device="cuda") if dtype == torch.bfloat16 else None
         self.w, self.dw, self.wm = [], [], []
         for w, o in zip(weights, offs):
             n = _numel(w.shape)
             wt = torch.as_tensor(w, dtype=torch.float32).reshape(-1).cuda()
             self.w32[o:o + n].copy_(wt)
-            self.w16[o:o + n].copy_(wt.to(torch.bfloat16))
-            self.w.append(self.w16[o:o + n].view(tuple(w.shape)))
+            if self.w16 is not None:
+                self.w16[o:o + n].copy_(wt.to(torch.bfloat16))
+            self.w.append((self.w32 if self.w16 is None else self.w16)[o:o + n].view(tuple(w.shape)))
             self.dw.append(self.dw32[o:o + n].view(tuple(w.shape)))
             self.wm.append(self.w32[o:o + n].view(tuple(w.shape)))
         # ---- forward program
@@ -84,12 +91,12 @@ class UNetStep:
         self.flops = 0.0
 
         def new_saved(shape, tag):
-            s = _Saved(len(self.saved), shape, len(self.ops), tag)
+            s = _Saved(len(self.saved), shape, len(self.ops), tag, self.esize)
             self.saved.append(s)
             return s
 
         def conv_op(name, src, vol_in, cin, cout, s, widx, tag, first=False, src2=None):
-            d = mc.make_desc(N, vol_in, vol_in, vol_in, cin, cout, 3, s, 1, torch.bfloat16)
+            d = mc.make_desc(N, vol_in, vol_in, vol_in, cin, cout, 3, s, 1, dtype)
             vo = vol_in // s
             out = new_saved((N, vo, vo, vo, cout), tag)
             src.last_fwd = len(self.ops)
@@ -100,7 +107,7 @@ class UNetStep:
             self.flops += fl * (2 if first else 3)
             return out, vo
 
-        xs = _Saved(0, (N, vol, vol, vol, in_ch), 0, sw.TAG_INPUT)
+        xs = _Saved(0, (N, vol, vol, vol, in_ch), 0, sw.TAG_INPUT, self.esize)
         self.saved.append(xs)
         self.ops.append(dict(kind="input", name="input", out=xs))
         a, v, wi = xs, vol, 0
@@ -112,7 +119,7 @@ class UNetStep:
                 skips.append(a)
         for l in range(L - 2, -1, -1):
             v *= 2
-            d = mc.make_desc(N, v, v, v, ch[l], ch[l + 1], 2, 2, 0, torch.bfloat16)  # the convolution whose dgrad is the up-sampling
+            d = mc.make_desc(N, v, v, v, ch[l], ch[l + 1], 2, 2, 0, dtype)  # the convolution whose dgrad is the up-sampling
             a.last_fwd = len(self.ops)
             # the up-sampling writes straight into its half of the concatenated tensor, and its backward passes read
             # their half of that tensor's gradient in place, where the library has the kernels for it
@@ -120,7 +127,7 @@ class UNetStep:
             # Virtual concatenation: where the library's kernels take the two halves as separate tensors, the
             # concatenated tensor and its gradient never exist; the up-sampled map is a saved tensor of its own and the
             # skip tensor is read a second time by the decoder (forward and weight gradient).
-            d1 = mc.make_desc(N, v, v, v, 2 * ch[l], ch[l], 3, 1, 1, torch.bfloat16)
+            d1 = mc.make_desc(N, v, v, v, 2 * ch[l], ch[l], 3, 1, 1, dtype)
             virtual = virtual_cat and all(mc.pair_supported(d1, p) for p in range(3))
             in_place = in_place and not virtual
             u = new_saved((N, v, v, v, ch[l]), sw.TAG_DECODER) if virtual else None
@@ -139,7 +146,7 @@ class UNetStep:
             self.ops.append(dict(kind="cat", name=f"dec{l}.cat", skip=skips[l], out=cat, c=ch[l], virtual=False))
             a, _ = conv_op(f"dec{l}.conv1", cat, v, 2 * ch[l], ch[l], 1, wi, sw.TAG_DECODER); wi += 1
             a, _ = conv_op(f"dec{l}.conv2", a, v, ch[l], ch[l], 1, wi, sw.TAG_DECODER); wi += 1
-        d = mc.make_desc(N, v, v, v, ch[0], classes, 1, 1, 0, torch.bfloat16)
+        d = mc.make_desc(N, v, v, v, ch[0], classes, 1, 1, 0, dtype)
         logits = new_saved((N, v, v, v, classes), sw.TAG_HEAD)
         a.last_fwd = len(self.ops)
         self.ops.append(dict(kind="head", name="head", desc=d, src=a, out=logits, w=wi))
@@ -240,12 +247,12 @@ class UNetStep:
     def _transient(self, op):
         """Device bytes an op holds besides saved tensors: parameters, workspace, labels, and the gradient tensors
         alive during it (the gradient pair of the layer, plus the skip gradients waiting for the encoder)."""
-        fixed = self.w32.numel() * (18 if self.optimizer == "adam" else 10) + self.ws.numel() + self.labels.numel()
+        fixed = self.w32.numel() * ((16 if self.optimizer == "adam" else 8) + (2 if self.w16 is not None else 0)) + self.ws.numel() + self.labels.numel()
         if self.norm:
             fixed += self.in_ws.numel()
         if op < self.n_fwd:
             o = self.ops[op]
-            return fixed + (_numel(o["shape"]) * 2 if o["kind"] == "up" and not o["in_place"] and not o["virtual"] else 0)
+            return fixed + (_numel(o["shape"]) * self.esize if o["kind"] == "up" and not o["in_place"] and not o["virtual"] else 0)
         f = self.n_fwd - 1 - (op - self.n_fwd)
         o = self.ops[f]
         live = 0
@@ -266,11 +273,11 @@ class UNetStep:
     # ---- storage of saved tensors
     def _view(self, ptr, shape):
         off = ptr - self.arena.data_ptr()
-        return self.arena[off:off + _numel(shape) * 2].view(torch.bfloat16).view(shape)
+        return self.arena[off:off + _numel(shape) * self.esize].view(self.dtype).view(shape)
 
     def _produce(self, s):
         if self.engine is None:
-            s.view = torch.empty(s.shape, dtype=torch.bfloat16, device="cuda")
+            s.view = torch.empty(s.shape, dtype=self.dtype, device="cuda")
         else:
             s.ptr = self.engine.alloc(s.bytes)
             s.view = self._view(s.ptr, s.shape)
@@ -369,7 +376,7 @@ class UNetStep:
         self.n_recomputed = 0
         if e is not None:
             e.reset_step()
-        bf = torch.bfloat16
+        bf = self.dtype      # element type of activations and gradients
         # forward
         for f, op in enumerate(self.ops):
             k = op["kind"]
@@ -473,7 +480,7 @@ class UNetStep:
                         # the data gradient applies that LeakyReLU's derivative as well
                         mc.conv3d_dgrad_lrelu(op["desc"], da, self.w[op["w"]], self._need(op["src"]), SLOPE, nxt, self.ws)
                         premasked = True
-                    elif op["src"].id in dskip and dskip[op["src"].id][1] == 0 and (trace is None or getattr(trace, "keep_fused", False)):
+                    elif op["src"].id in dskip and dskip[op["src"].id][1] == 0 and (trace is None or getattr(trace, "keep_fused", False) or self.dtype == torch.float32):
                         # the input is also a skip connection whose second gradient is a tensor of its own: the
                         # data gradient adds it and applies the derivative of the producing layer in the same call
                         # (with normalisation the derivative is not a factor: the call only adds, slope 1)

@@ -54,11 +54,18 @@ def _h(t):
 
 # 48 = 16 x 3: odd extents at the two deepest levels, as in the 208^3 volume (16 x 13)
 # (last flag: the decoder reads [up-sampled | skip] as two tensors / materialises the concatenation)
-@pytest.mark.parametrize("N,vol,channels,virtual_cat", [(2, 32, CH, True), (1, 16, CH[:4], True), (1, 48, CH, True), (2, 32, CH, False)])
-def test_every_op_matches_oracle_on_the_steps_own_tensors(unet, N, vol, channels, virtual_cat):
+# (last flag but one: fp32 step, every convolution on the fp32 matrix cores, tolerance 1e-4)
+@pytest.mark.parametrize("N,vol,channels,virtual_cat,f32", [(2, 32, CH, True, False), (1, 16, CH[:4], True, False), (1, 48, CH, True, False),
+                                                            (2, 32, CH, False, False), (2, 32, CH, True, True), (1, 48, CH, True, True)])
+def test_every_op_matches_oracle_on_the_steps_own_tensors(unet, N, vol, channels, virtual_cat, f32):
     x, labels, ws, xd, ld = _inputs(N, vol, channels, 5)
     L = len(channels)
-    step = unet.UNetStep(N, vol, channels, ws, xd, ld, swap=False, virtual_cat=virtual_cat)
+    TOL = 1e-4 if f32 else 1e-2
+    if f32:
+        xd = xd.float()
+    step = unet.UNetStep(N, vol, channels, ws, xd, ld, swap=False, virtual_cat=virtual_cat, dtype=torch.float32 if f32 else torch.bfloat16)
+    if f32:
+        assert all(unet.mc.kernel_name(op["desc"], q) == "mfma_f32_gather" for op in step.ops if "desc" in op for q in range(3))
     assert all(op["virtual"] == virtual_cat for op in step.ops if op["kind"] == "cat")
     tr = {}
     step.run(update=False, trace=tr)
@@ -127,7 +134,12 @@ def test_every_op_matches_oracle_on_the_steps_own_tensors(unet, N, vol, channels
         din_ref = oc.dgrad(g, t[name + ".dz"], w[name])
         if name in through:
             din_ref = ou._lrelu_grad(t[src + ".a"], din_ref)
-        if name.startswith("enc") and name.endswith("conv1"):          # its input is a skip tensor: second gradient
+        if name.startswith("enc") and name.endswith("conv1") and name + ".skip_add" in t:
+            # (fp32 step: the skip tensor's second gradient joins inside the data-gradient call, no rounding between)
+            l = int(name[3]) - 1
+            assert np.array_equal(t[name + ".skip_add"], t[f"dec{l}.cat.dskip"])
+            close(name + " dgrad + skip", t[name + ".din"], ou._lrelu_grad(t[src + ".a"], din_ref + t[name + ".skip_add"]))
+        elif name.startswith("enc") and name.endswith("conv1"):          # its input is a skip tensor: second gradient
             l = int(name[3]) - 1
             close(name + " dgrad", t[name + ".dgrad"], din_ref)
             close(name + " skip add", t[name + ".din"], ou._lrelu_grad(t[src + ".a"], t[name + ".dgrad"] + t[f"dec{l}.cat.dskip"]))
@@ -164,6 +176,55 @@ def test_step_end_to_end_against_oracle_step(unet):
         # SGD on the fp32 master weights with the GPU's own gradient
         expect = w0.astype(np.float32) - np.float32(lr) * g.cpu().numpy()
         assert np.allclose(wm.cpu().numpy(), expect, rtol=1e-6, atol=1e-8), name
+
+
+def test_fp32_step_end_to_end_against_the_exact_oracle_step(unet):
+    """In fp32 the GPU pipeline and the fp64 oracle step stay together over all 23 layers (no storage rounding that
+    could tip a value over a LeakyReLU kink by more than 1e-7 of its size), so the whole step is pinned tightly: loss,
+    length and direction of every weight gradient, and the updated weights."""
+    N, vol = 2, 32
+    x, labels, ws, xd, ld = _inputs(N, vol, CH, 5)
+    lr = 1e-2
+    step = unet.UNetStep(N, vol, CH, ws, xd.float(), ld, lr=lr, swap=False, dtype=torch.float32)
+    step.run(update=True)
+    torch.cuda.synchronize()
+    loss_ref, grads_ref, w_ref = ou.train_step(x.astype(np.float64), labels, ws, CH, lr)
+    assert abs(float(step.loss.item()) - loss_ref) <= 1e-5 * abs(loss_ref)
+    worst = 0.0
+    for (name, _), g, r, wm, wr in zip(si.unet_weight_shapes(CH), step.dw, grads_ref, step.wm, w_ref):
+        gg = _h(g)
+        e = oc.rel_err(gg, r)
+        worst = max(worst, e)
+        ratio = np.sqrt(np.sum(gg * gg) / np.sum(r * r))
+        cos = np.sum(gg * r) / np.sqrt(np.sum(gg * gg) * np.sum(r * r))
+        print(f"{name}: max error {e:.2e}, norm ratio - 1 = {ratio - 1.0:+.1e}, 1 - cos = {1.0 - cos:.1e}")
+        # A handful of pre-activations lie so close to zero that the fp32 and the fp64 sums put them on different
+        # LeakyReLU branches; each such voxel changes a few gradient elements by up to 1e-2 of the rms.  Length and
+        # direction of every gradient are what a wrong scale, a dropped term or a wrong operand would move.
+        assert abs(ratio - 1.0) <= 2e-4 and 1.0 - cos <= 1e-6, (name, ratio, cos)
+        assert e <= 2e-2, (name, e)
+        assert np.allclose(wm.cpu().numpy(), wr, rtol=1e-4, atol=1e-6), name
+    print(f"worst weight-gradient error of the fp32 step against the exact oracle step: {worst:.2e}")
+
+
+def test_fp32_step_swapped_recomputed_and_hybrid_are_bit_identical(unet):
+    from paper_1812_07816_amd import swap as sw
+    N, vol = 1, 32
+    _, _, ws, xd, ld = _inputs(N, vol, CH, 5)
+    xf = xd.float()
+    plain = unet.UNetStep(N, vol, CH, ws, xf, ld, swap=False, dtype=torch.float32)
+    plain.run(update=False)
+    torch.cuda.synchronize()
+    ref, ref_loss = plain.dw32.clone(), plain.loss.clone()
+    for eviction in (sw.EVICT_SWAP, sw.EVICT_RECOMPUTE, sw.EVICT_HYBRID):
+        st = unet.UNetStep(N, vol, CH, ws, xf, ld, swap=True, budget_bytes=None, lookahead=2, policy=sw.POLICY_ALL, eviction=eviction,
+                           dtype=torch.float32)
+        st.run(update=False)
+        torch.cuda.synchronize()
+        s = st.engine.stats()
+        assert s["n_swapped_out"] + st.n_recomputed > 0
+        assert torch.equal(st.dw32, ref) and torch.equal(st.loss, ref_loss)
+        st.close()
 
 
 def test_virtual_concatenation_gives_the_bits_of_the_materialised_one_and_needs_less_memory(unet):
