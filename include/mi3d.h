@@ -347,6 +347,8 @@ typedef struct {
     int      n_swapped_out, n_swapped_in;/* copies actually issued */
     int      n_recompute;                /* tensors the plan re-computes */
     double   recompute_ms;               /* sum of their stated costs */
+    int      n_checksummed;              /* checksum mode: tensors that went out and came back ... */
+    int      n_checksum_mismatch;        /* ... and those whose checksum after the swap-in differs from the one before the swap-out */
 } mi3d_swap_stats_t;
 
 typedef struct mi3d_swap_engine mi3d_swap_engine;
@@ -439,6 +441,16 @@ int mi3d_swap_in(mi3d_swap_engine *e, int id, void *dev_dst, void *consumer_stre
 int mi3d_swap_wait_in(mi3d_swap_engine *e, int id, void *consumer_stream);
 /* The backward pass is done with `id`: its host slot is recycled. */
 int mi3d_swap_done(mi3d_swap_engine *e, int id);
+/* Checksum mode (a safety net for the event ordering the engine rests on: Section 5 takes for granted that swapping
+ * does not change a value).  While on, every swap-out is preceded by a 64-bit checksum of the device block it reads,
+ * and every swap-in is followed by one of the block it wrote, both on the side streams; mi3d_swap_stats compares
+ * them (n_checksummed, n_checksum_mismatch).  Switch it on after the tensors are registered and before the step;
+ * costs two small kernels and one pass over the tensor per copy.  Needs an engine with a pinned pool.
+ * mi3d_checksum64 is the same function on any device buffer (8-byte aligned): sum over its 8-byte words of
+ * word * (2 * index + 1) modulo 2^64, a trailing piece of fewer than 8 bytes zero-extended; synchronises `stream`
+ * and allocates a few KB of device scratch for the call; *value is a host pointer. */
+int mi3d_swap_set_verify(mi3d_swap_engine *e, int on);
+int mi3d_checksum64(const void *dev, size_t bytes, uint64_t *value, void *stream);
 /* Blocks the host until every copy issued so far has finished. */
 int mi3d_swap_sync(mi3d_swap_engine *e);
 /* Forgets per-step state (tensor residency, host slots, counters) but keeps

@@ -33,7 +33,8 @@ class SwapStats(ctypes.Structure):
                 ("unswapped_peak_bytes", ctypes.c_uint64),
                 ("n_registered", ctypes.c_int), ("n_planned", ctypes.c_int),
                 ("n_swapped_out", ctypes.c_int), ("n_swapped_in", ctypes.c_int),
-                ("n_recompute", ctypes.c_int), ("recompute_ms", ctypes.c_double)]
+                ("n_recompute", ctypes.c_int), ("recompute_ms", ctypes.c_double),
+                ("n_checksummed", ctypes.c_int), ("n_checksum_mismatch", ctypes.c_int)]
 
 
 _vp, _sz, _i, _u = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int, ctypes.c_uint
@@ -105,6 +106,8 @@ SIGNATURES = {
     "mi3d_swap_in": (_i, [_vp, _i, _vp, _vp]),
     "mi3d_swap_wait_in": (_i, [_vp, _i, _vp]),
     "mi3d_swap_done": (_i, [_vp, _i]),
+    "mi3d_swap_set_verify": (_i, [_vp, _i]),
+    "mi3d_checksum64": (_i, [_vp, _sz, ctypes.POINTER(ctypes.c_uint64), _vp]),
     "mi3d_swap_sync": (_i, [_vp]),
     "mi3d_swap_reset_step": (_i, [_vp]),
     "mi3d_swap_stats": (_i, [_vp, ctypes.POINTER(SwapStats)]),

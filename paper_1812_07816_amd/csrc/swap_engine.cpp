@@ -43,6 +43,48 @@ struct ArenaBlock {
     std::vector<Pending> pending;  // events that must fire before reuse
 };
 
+#if defined(__HIPCC__)
+// 64-bit checksum of a device buffer: sum over its 8-byte words of word * (2 * index + 1) mod 2^64 (a trailing piece of
+// fewer than 8 bytes counts as a zero-extended word).  Integer arithmetic: the value does not depend on the order of
+// the additions, so any grid gives the same bits; the odd, position-dependent factor makes it notice flipped bits as
+// well as words that changed places.
+constexpr int CK_BLOCKS = 256;
+__global__ void __launch_bounds__(256) checksum_partial_kernel(const unsigned char* __restrict__ p, size_t bytes, unsigned long long* __restrict__ part) {
+    __shared__ unsigned long long red[256];
+    const size_t words = bytes / 8;
+    unsigned long long acc = 0;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < words; i += (size_t)gridDim.x * 256)
+        acc += ((const unsigned long long*)p)[i] * (2ull * i + 1ull);
+    if (blockIdx.x == 0 && threadIdx.x == 0 && (bytes & 7)) {
+        unsigned long long last = 0;
+        for (size_t b = 0; b < (bytes & 7); ++b) last |= (unsigned long long)p[words * 8 + b] << (8 * b);
+        acc += last * (2ull * words + 1ull);
+    }
+    red[threadIdx.x] = acc;
+    __syncthreads();
+    for (int w = 128; w > 0; w >>= 1) {
+        if ((int)threadIdx.x < w) red[threadIdx.x] += red[threadIdx.x + w];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) part[blockIdx.x] = red[0];
+}
+__global__ void __launch_bounds__(64) checksum_final_kernel(const unsigned long long* __restrict__ part, int n, unsigned long long* __restrict__ out) {
+    if (threadIdx.x == 0) {
+        unsigned long long a = 0;
+        for (int i = 0; i < n; ++i) a += part[i];
+        *out = a;
+    }
+}
+// enqueues the checksum of [p, p + bytes) on `s`; scratch: CK_BLOCKS words of device memory; out: device-writable
+int enqueue_checksum(const void* p, size_t bytes, unsigned long long* scratch, unsigned long long* out, hipStream_t s) {
+    checksum_partial_kernel<<<CK_BLOCKS, 256, 0, s>>>((const unsigned char*)p, bytes, scratch);
+    int st = check_launch();
+    if (st) return st;
+    checksum_final_kernel<<<1, 64, 0, s>>>(scratch, CK_BLOCKS, out);
+    return check_launch();
+}
+#endif
+
 }  // namespace
 
 struct mi3d_swap_engine {
@@ -73,6 +115,14 @@ struct mi3d_swap_engine {
 
     uint64_t bytes_out = 0, bytes_in = 0;
     int n_out = 0, n_in = 0;
+
+    // checksum mode: per tensor slot two words in pinned host memory (before the swap-out, after the swap-in) and
+    // CK_BLOCKS words of device scratch per copy direction
+    bool verify = false;
+    unsigned long long* sums_host = nullptr;     // [slot][2]
+    unsigned long long* sums_scratch = nullptr;  // device, [2][CK_BLOCKS]
+    int sums_slots = 0;
+    std::map<int, int> sum_slot;                 // tensor id -> slot (assigned at its swap-out)
 };
 
 namespace {
@@ -139,6 +189,21 @@ void coalesce(mi3d_swap_engine* e) {
     }
 }
 
+// Merges every run of neighbouring free blocks, also across blocks that wait for a copy (the merged block then
+// waits for it as a whole).  Used when nothing fits without such a wait.
+void coalesce_all(mi3d_swap_engine* e) {
+    std::vector<ArenaBlock>& bl = e->blocks;
+    for (size_t i = 0; i + 1 < bl.size();) {
+        if (bl[i].free && bl[i + 1].free) {
+            bl[i].size += bl[i + 1].size;
+            for (auto& ev : bl[i + 1].pending) bl[i].pending.push_back(ev);
+            bl.erase(bl.begin() + i + 1);
+        } else {
+            ++i;
+        }
+    }
+}
+
 int arena_free(mi3d_swap_engine* e, const void* ptr, std::vector<Pending> pending) {
     size_t off = (const char*)ptr - (const char*)e->cfg.dev_arena;
     for (ArenaBlock& b : e->blocks) {
@@ -180,6 +245,7 @@ void reset_step_state(mi3d_swap_engine* e) {
     e->n_out = e->n_in = 0;
     e->arena_occupied_peak = e->arena_hwm = 0;
     e->arena_overflow = 0;
+    e->sum_slot.clear();
 }
 
 }  // namespace
@@ -225,10 +291,17 @@ int mi3d_swap_destroy(mi3d_swap_engine* e) {
     if (e->live) {
         if (hipStreamSynchronize(e->s_out) != hipSuccess) st = MI3D_ERR_HIP;
         if (hipStreamSynchronize(e->s_in) != hipSuccess) st = MI3D_ERR_HIP;
-        e->blocks.clear();  // drops shared events into the free lists
-        reset_step_state(e);
-        for (hipEvent_t ev : e->free_events_timed) (void)hipEventDestroy(ev);
-        for (hipEvent_t ev : e->free_events_plain) (void)hipEventDestroy(ev);
+    }
+    // (an engine without a pinned pool still records events when its arena is used)
+    e->blocks.clear();  // drops shared events into the free lists
+    reset_step_state(e);
+    for (hipEvent_t ev : e->free_events_timed) (void)hipEventDestroy(ev);
+    for (hipEvent_t ev : e->free_events_plain) (void)hipEventDestroy(ev);
+#if defined(__HIPCC__)
+    if (e->sums_host) (void)hipHostFree(e->sums_host);
+    if (e->sums_scratch) (void)hipFree(e->sums_scratch);
+#endif
+    if (e->live) {
         (void)hipEventDestroy(e->base);
         (void)hipStreamDestroy(e->s_out);
         (void)hipStreamDestroy(e->s_in);
@@ -392,28 +465,51 @@ int mi3d_swap_alloc(mi3d_swap_engine* e, size_t bytes, void* stream, void** dev_
     // only when fragmentation leaves no block below the peak (counted as an overflow).  Without a plan the whole
     // arena is fair game.
     const size_t cap = e->have_plan && e->arena_cap ? e->arena_cap : e->cfg.arena_bytes;
+    // Small tensors (under an eighth of the largest registered one) are packed downwards from the top of that range,
+    // large ones upwards from the bottom, so that the holes the small ones leave never split the space the level-0
+    // maps need in one piece.
+    size_t largest = 0;
+    for (const auto& kv : e->tensors) largest = std::max(largest, kv.second.plan.bytes);
+    const bool from_top = need * 8 <= largest;
     int pick = -1;
-    for (int pass = 0; pass < 4 && pick < 0; ++pass)
-        for (int i = 0; i < (int)e->blocks.size(); ++i) {
+    size_t at = 0;   // offset of the allocation inside the picked block
+    for (int pass = 0; pass < 4 && pick < 0; ++pass) {
+        if (pass == 1) coalesce_all(e);   // from here on a wait for a copy is accepted: free space counts as one piece
+        const int n = (int)e->blocks.size();
+        for (int k = 0; k < n; ++k) {
+            const int i = from_top ? n - 1 - k : k;
             const ArenaBlock& b = e->blocks[i];
             if (!b.free || b.size < need) continue;
-            if (pass < 2 && b.off + need > cap) continue;
             if ((pass == 0 || pass == 2) && waits_for_copy(b)) continue;
+            size_t off = 0;
+            if (from_top) {   // the highest position inside the block that stays below the cap (passes 0, 1)
+                size_t end = b.off + b.size;
+                if (pass < 2 && end > cap) end = cap;
+                if (end < b.off + need) continue;
+                off = end - need - b.off;
+            } else if (pass < 2 && b.off + need > cap) {
+                continue;
+            }
             pick = i;
+            at = off;
             break;
         }
+    }
     if (pick < 0) return MI3D_ERR_OVER_BUDGET;
-    if (e->blocks[pick].off + need > cap) e->arena_overflow++;
+    if (e->blocks[pick].off + at + need > cap) e->arena_overflow++;
     for (auto& p : e->blocks[pick].pending) HIP_TRY(hipStreamWaitEvent((hipStream_t)stream, (hipEvent_t)p.ev.get(), 0));
-    ArenaBlock& b = e->blocks[pick];
-    if (b.size > need) {
-        ArenaBlock rest{b.off + need, b.size - need, true, b.pending};
-        b.size = need;
-        e->blocks.insert(e->blocks.begin() + pick + 1, rest);
+    {
+        // split the picked block into [before | allocation | after]; the free parts keep the pending events
+        ArenaBlock b = e->blocks[pick];
+        std::vector<ArenaBlock> parts;
+        if (at > 0) parts.push_back(ArenaBlock{b.off, at, true, b.pending});
+        parts.push_back(ArenaBlock{b.off + at, need, false, {}});
+        if (at + need < b.size) parts.push_back(ArenaBlock{b.off + at + need, b.size - at - need, true, b.pending});
+        e->blocks.erase(e->blocks.begin() + pick);
+        e->blocks.insert(e->blocks.begin() + pick, parts.begin(), parts.end());
+        if (at > 0) ++pick;
     }
     ArenaBlock& a = e->blocks[pick];
-    a.free = false;
-    a.pending.clear();
     e->arena_used += need;
     note_occupancy(e);
     *dev_ptr = (char*)e->cfg.dev_arena + a.off;
@@ -441,6 +537,16 @@ int mi3d_swap_out(mi3d_swap_engine* e, int id, const void* dev_src, void* produc
     HIP_TRY(hipStreamWaitEvent(e->s_out, dep, 0));
     e->free_events_plain.push_back(dep);  // the enqueued wait refers to the record above; the handle may be re-recorded
     if ((st = get_event(e, true, &t->out.start)) || (st = get_event(e, true, &t->out.done))) return st;
+#if defined(__HIPCC__)
+    if (e->verify) {   // what leaves the device (the side stream is already behind the producer)
+        if ((int)e->sum_slot.size() >= e->sums_slots) return MI3D_ERR_BAD_STATE;
+        const int slot = (int)e->sum_slot.size();
+        e->sum_slot[id] = slot;
+        e->sums_host[2 * slot] = 0;
+        e->sums_host[2 * slot + 1] = 1;   // differs from the first word until the swap-in has been checked
+        if ((st = enqueue_checksum(dev_src, t->plan.bytes, e->sums_scratch, e->sums_host + 2 * slot, e->s_out))) return st;
+    }
+#endif
     HIP_TRY(hipEventRecord(t->out.start, e->s_out));
     HIP_TRY(hipMemcpyAsync(e->host_pool + t->plan.host_offset, dev_src, t->plan.bytes, hipMemcpyDeviceToHost, e->s_out));
     HIP_TRY(hipEventRecord(t->out.done, e->s_out));
@@ -486,6 +592,13 @@ int mi3d_swap_in(mi3d_swap_engine* e, int id, void* dev_dst, void* consumer_stre
     HIP_TRY(hipEventRecord(t->in.start, e->s_in));
     HIP_TRY(hipMemcpyAsync(dev_dst, e->host_pool + t->plan.host_offset, t->plan.bytes, hipMemcpyHostToDevice, e->s_in));
     HIP_TRY(hipEventRecord(t->in.done, e->s_in));
+#if defined(__HIPCC__)
+    if (e->verify) {   // what arrived back on the device (behind the done event: the consumer does not wait for it)
+        auto it = e->sum_slot.find(id);
+        if (it == e->sum_slot.end()) return MI3D_ERR_BAD_STATE;
+        if ((st = enqueue_checksum(dev_dst, t->plan.bytes, e->sums_scratch + CK_BLOCKS, e->sums_host + 2 * it->second + 1, e->s_in))) return st;
+    }
+#endif
     t->in.issued = true;
     t->state = ST_IN_ISSUED;
     e->bytes_in += t->plan.bytes;
@@ -508,6 +621,44 @@ int mi3d_swap_done(mi3d_swap_engine* e, int id) {
     if (!t || t->state != ST_BACK) return MI3D_ERR_BAD_STATE;
     t->state = ST_DONE;
     return MI3D_OK;
+}
+
+int mi3d_swap_set_verify(mi3d_swap_engine* e, int on) {
+    if (!e) return MI3D_ERR_INVALID_ARG;
+#if defined(__HIPCC__)
+    if (!e->live) return MI3D_ERR_BAD_STATE;
+    if (on && !e->sums_host) {
+        const int slots = (int)e->tensors.size() > 0 ? (int)e->tensors.size() : 1;
+        HIP_TRY(hipHostMalloc((void**)&e->sums_host, (size_t)slots * 2 * sizeof(unsigned long long), hipHostMallocDefault));
+        HIP_TRY(hipMalloc((void**)&e->sums_scratch, 2 * CK_BLOCKS * sizeof(unsigned long long)));
+        e->sums_slots = slots;
+    } else if (on && (int)e->tensors.size() > e->sums_slots) {
+        return MI3D_ERR_BAD_STATE;   // tensors were registered after the mode was switched on
+    }
+    e->verify = on != 0;
+    return MI3D_OK;
+#else
+    (void)on;
+    return MI3D_ERR_UNSUPPORTED;
+#endif
+}
+
+int mi3d_checksum64(const void* dev, size_t bytes, uint64_t* value, void* stream) {
+    if (!dev || !value || ((uintptr_t)dev & 7)) return MI3D_ERR_INVALID_ARG;
+#if defined(__HIPCC__)
+    unsigned long long* scratch = nullptr;
+    HIP_TRY(hipMalloc((void**)&scratch, (CK_BLOCKS + 1) * sizeof(unsigned long long)));
+    int st = enqueue_checksum(dev, bytes, scratch, scratch + CK_BLOCKS, (hipStream_t)stream);
+    hipError_t err = hipSuccess;
+    if (!st) err = hipMemcpyAsync(value, scratch + CK_BLOCKS, sizeof(unsigned long long), hipMemcpyDeviceToHost, (hipStream_t)stream);
+    if (!st && err == hipSuccess) err = hipStreamSynchronize((hipStream_t)stream);
+    (void)hipFree(scratch);
+    if (err != hipSuccess) { note_hip_error(err); return MI3D_ERR_HIP; }
+    return st;
+#else
+    (void)bytes; (void)stream;
+    return MI3D_ERR_UNSUPPORTED;
+#endif
 }
 
 int mi3d_swap_sync(mi3d_swap_engine* e) {
@@ -573,6 +724,12 @@ int mi3d_swap_stats(mi3d_swap_engine* e, mi3d_swap_stats_t* out) {
             (dir ? out->copy_ms_in : out->copy_ms_out) += (double)(t1 - t0);
             iv.emplace_back(t0, t1);
         }
+    }
+    for (auto& kv : e->sum_slot) {   // (both side streams are idle here)
+        Tensor* t = find(e, kv.first);
+        if (!t || !t->in.issued) continue;
+        out->n_checksummed++;
+        if (e->sums_host[2 * kv.second] != e->sums_host[2 * kv.second + 1]) out->n_checksum_mismatch++;
     }
     std::sort(iv.begin(), iv.end());
     double busy = 0.0;

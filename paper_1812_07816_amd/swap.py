@@ -120,6 +120,10 @@ class SwapEngine:
     def done(self, id):
         check(lib().mi3d_swap_done(self._h, id), "swap_done")
 
+    def set_verify(self, on=True):
+        """Checksum mode: every swapped tensor is summed before it leaves and after it is back; see stats()."""
+        check(lib().mi3d_swap_set_verify(self._h, int(bool(on))), "swap_set_verify")
+
     def sync(self):
         check(lib().mi3d_swap_sync(self._h), "swap_sync")
 
@@ -130,3 +134,10 @@ class SwapEngine:
         s = SwapStats()
         check(lib().mi3d_swap_stats(self._h, ctypes.byref(s)), "swap_stats")
         return {k: getattr(s, k) for k, _ in SwapStats._fields_}
+
+
+def checksum64(t, stream=None):
+    """64-bit checksum of a CUDA tensor's bytes (the function of the engine's checksum mode)."""
+    v = ctypes.c_uint64()
+    check(lib().mi3d_checksum64(t.data_ptr(), t.numel() * t.element_size(), ctypes.byref(v), _stream(stream)), "checksum64")
+    return v.value

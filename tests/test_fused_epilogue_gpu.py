@@ -116,9 +116,11 @@ def test_epilogue_argument_checks(device):
     for bad in (1.0, 1.5, -0.1):
         with pytest.raises(RuntimeError):
             mc.conv3d_fwd_lrelu(desc, x, w, bad)
-    d32 = mc.make_desc(1, 4, 4, 4, 4, 4, 3, 1, 1, torch.float32)
+    # an fp32 geometry no tiled kernel takes (5 taps per axis runs through the plain kernels) has no epilogue
+    d32 = mc.make_desc(1, 6, 6, 6, 4, 4, 5, 1, 2, torch.float32)
+    assert mc.kernel_name(d32, 0) == "direct"
     with pytest.raises(RuntimeError):
-        mc.conv3d_fwd_lrelu(d32, torch.zeros((1, 4, 4, 4, 4), device="cuda"), torch.zeros((4, 3, 3, 3, 4), device="cuda"), 0.01)
+        mc.conv3d_fwd_lrelu(d32, torch.zeros((1, 6, 6, 6, 4), device="cuda"), torch.zeros((4, 5, 5, 5, 4), device="cuda"), 0.01)
 
 
 def test_dgrad_skip_argument_checks(device):
@@ -142,6 +144,9 @@ def test_dgrad_skip_argument_checks(device):
     assert call(other.data_ptr() + 2, other.data_ptr(), 0.01) == -1  # misaligned
     assert call(other.data_ptr(), other.data_ptr(), 1.5) == -1       # slope out of range
     assert call(other.data_ptr(), other.data_ptr(), 0.01, ws_bytes=16) == -3
-    d32 = mc.make_desc(1, 8, 8, 8, 32, 64, 3, 2, 1, torch.float32)
-    assert call(other.data_ptr(), other.data_ptr(), 0.01, d=d32) == -1   # bf16 only
+    # fp32 geometries outside the tiled fp32 kernels are refused (5 taps per axis; same element counts as above,
+    # so the buffers would be large enough for any kernel that ran)
+    d32 = mc.make_desc(1, 4, 4, 4, 16, 32, 5, 1, 2, torch.float32)
+    assert mc.kernel_name(d32, 1) == "direct"
+    assert call(other.data_ptr(), other.data_ptr(), 0.01, d=d32) == -1
     torch.cuda.synchronize()

@@ -75,8 +75,9 @@ def test_pairs_are_refused_where_no_kernel_takes_them(device):
         w = torch.zeros((Cout, k, k, k, Cin), dtype=bf, device="cuda")
         with pytest.raises(Mi3dError):
             mc.conv3d_fwd_pair(d, lo, lo, w)
-    d32 = mc.make_desc(1, 8, 8, 8, 64, 32, 3, 1, 1, torch.float32)
-    assert not mc.pair_supported(d32, 0)
+    # the fp32 kernels take halves of 32-channel multiples as well, and nothing narrower
+    assert all(mc.pair_supported(mc.make_desc(1, 8, 8, 8, 64, 32, 3, 1, 1, torch.float32), q) for q in range(3))
+    assert not any(mc.pair_supported(mc.make_desc(1, 8, 8, 8, 32, 32, 3, 1, 1, torch.float32), q) for q in range(3))
     # a missing or misaligned high half is an invalid argument
     d = mc.make_desc(1, 8, 8, 8, 64, 32, 3, 1, 1, bf)
     lo = torch.zeros((1, 8, 8, 8, 32), dtype=bf, device="cuda")

@@ -134,3 +134,55 @@ def test_pool_too_small_is_reported(device):
         e.plan()
     assert ei.value.status == -5
     e.close()
+
+
+def _checksum_ref(raw):
+    """The documented function, written out with numpy: sum of word_i * (2 i + 1) modulo 2^64 over the 8-byte
+    little-endian words, the tail zero-extended."""
+    b = np.frombuffer(raw, dtype=np.uint8)
+    pad = (-b.size) % 8
+    w = np.concatenate([b, np.zeros(pad, dtype=np.uint8)]).view("<u8")
+    with np.errstate(over="ignore"):
+        return int(np.sum(w * (2 * np.arange(w.size, dtype=np.uint64) + np.uint64(1)), dtype=np.uint64))
+
+
+@pytest.mark.parametrize("nbytes", [8, 13, 4096, 3 * MiB + 5])
+def test_checksum_function_and_what_it_notices(device, nbytes):
+    g = torch.Generator(device="cuda").manual_seed(nbytes)
+    t = torch.randint(0, 256, (nbytes,), dtype=torch.uint8, device="cuda", generator=g)
+    c0 = sw.checksum64(t)
+    assert c0 == _checksum_ref(t.cpu().numpy().tobytes())
+    u = t.clone()
+    u[nbytes // 2] ^= 1                                  # one flipped bit
+    assert sw.checksum64(u) != c0
+    if nbytes >= 24:                                     # two words that changed places
+        v = t.clone().view(-1)[: nbytes // 8 * 8].view(torch.int64)
+        if int(v[0]) != int(v[1]):
+            a, b = int(v[0]), int(v[1])
+            v[0], v[1] = b, a
+            full = t.clone()
+            full[: v.numel() * 8] = v.view(torch.uint8)
+            assert sw.checksum64(full) != c0
+
+
+def test_checksum_mode_confirms_every_round_trip(device):
+    sizes = [6 * MiB + 24, 2 * MiB, 4096, 10]
+    e = _engine(sizes, budget=1 << 40)
+    e.set_verify(True)
+    g = torch.Generator(device="cuda").manual_seed(11)
+    src = [torch.randint(0, 256, (s,), dtype=torch.uint8, device="cuda", generator=g) for s in sizes]
+    keep = [t.clone() for t in src]
+    for step in range(2):                                # the second step reuses the checksum slots
+        e.reset_step()
+        for i, t in enumerate(src):
+            e.swap_out(i, t.data_ptr())
+            e.release(i)
+        dst = [torch.zeros_like(t) for t in src]
+        for i in reversed(range(len(sizes))):
+            e.swap_in(i, dst[i].data_ptr())
+            e.wait_in(i)
+            e.done(i)
+        st = e.stats()
+        assert st["n_checksummed"] == len(sizes) and st["n_checksum_mismatch"] == 0, st
+        assert all(torch.equal(a, b) for a, b in zip(dst, keep))
+    e.close()

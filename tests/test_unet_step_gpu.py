@@ -255,14 +255,22 @@ def test_swapped_step_is_bit_identical(unet):
     ref_loss = plain.loss.clone()
     probe = unet.UNetStep(N, vol, CH, ws, xd, ld, swap=True)
     peak = probe.engine.stats()["unswapped_peak_bytes"]
+    probe_fixed = probe._transient(0)     # weights, workspace, labels
     probe.close()
     for policy, budget in ((sw.POLICY_BUDGET, int(peak * 0.8)), (sw.POLICY_ALL, None)):
         st = unet.UNetStep(N, vol, CH, ws, xd, ld, swap=True, budget_bytes=budget, lookahead=2, policy=policy)
+        st.engine.set_verify(True)
         st.run(update=False)
         torch.cuda.synchronize()
         s = st.engine.stats()
         assert s["n_swapped_out"] > 0 and s["n_swapped_out"] == s["n_swapped_in"], s
         assert torch.equal(st.dw32, ref) and torch.equal(st.loss, ref_loss)
+        assert s["n_checksummed"] == s["n_swapped_in"] and s["n_checksum_mismatch"] == 0, s
+        # the arena the step really needed, counting blocks a swap-out was still reading, against the plan's share
+        print("policy", policy, "arena high water", s["arena_high_water_bytes"], "planned", s["planned_arena_bytes"], "overflows", s["n_arena_overflow"])
+        if st.plan_status == 0:
+            assert s["n_arena_overflow"] == 0 and s["arena_high_water_bytes"] <= s["planned_arena_bytes"], s
+            assert budget is None or s["arena_high_water_bytes"] + probe_fixed <= budget, s
         st.run(update=False)          # a second step reuses the arena and the host pool
         torch.cuda.synchronize()
         assert torch.equal(st.dw32, ref)
