@@ -465,12 +465,7 @@ int mi3d_swap_alloc(mi3d_swap_engine* e, size_t bytes, void* stream, void** dev_
     // only when fragmentation leaves no block below the peak (counted as an overflow).  Without a plan the whole
     // arena is fair game.
     const size_t cap = e->have_plan && e->arena_cap ? e->arena_cap : e->cfg.arena_bytes;
-    // Small tensors (under an eighth of the largest registered one) are packed downwards from the top of that range,
-    // large ones upwards from the bottom, so that the holes the small ones leave never split the space the level-0
-    // maps need in one piece.
-    size_t largest = 0;
-    for (const auto& kv : e->tensors) largest = std::max(largest, kv.second.plan.bytes);
-    const bool from_top = need * 8 <= largest;
+    const bool from_top = false;   // (placement runs upwards from the bottom of the arena)
     int pick = -1;
     size_t at = 0;   // offset of the allocation inside the picked block
     for (int pass = 0; pass < 4 && pick < 0; ++pass) {

@@ -146,25 +146,25 @@ static void test_a_block_behind_a_copy_counts_as_occupied() {
     CHECK(mi3d_swap_destroy(e) == MI3D_OK);
 }
 
-static void test_small_tensors_pack_from_the_top() {
-    alignas(256) static unsigned char arena[64 * 1024];
-    mi3d_swap_engine* e = make(1 << 20, arena, sizeof arena, 0);
-    chain(e, {16384, 256, 16384, 256});
+static void test_free_space_behind_a_copy_merges_when_nothing_else_fits() {
+    // [1 KiB free][1 KiB behind a copy][1 KiB free]: a 3 KiB request takes all of it and waits for the copy
+    alignas(256) static unsigned char arena[3 * 1024];
+    mi3d_swap_engine* e = make(1 << 20, arena, sizeof arena, 3 * 4096 + 4096, MI3D_SWAP_ALL);
+    chain(e, {1024, 1024, 1024});
     CHECK(mi3d_swap_plan(e) == MI3D_OK);
-    mi3d_swap_stats_t st;
-    CHECK(mi3d_swap_stats(e, &st) == MI3D_OK);
-    const size_t cap = st.planned_arena_bytes;
-    CHECK(cap == 2 * 16384 + 2 * 256);
-    void *big0 = nullptr, *s0 = nullptr, *big1 = nullptr, *s1 = nullptr;
-    CHECK(mi3d_swap_alloc(e, 16384, nullptr, &big0) == MI3D_OK);
-    CHECK(mi3d_swap_alloc(e, 256, nullptr, &s0) == MI3D_OK);
-    CHECK(mi3d_swap_alloc(e, 16384, nullptr, &big1) == MI3D_OK);
-    CHECK(mi3d_swap_alloc(e, 256, nullptr, &s1) == MI3D_OK);
-    CHECK(big0 == arena && big1 == arena + 16384);                          // large ones upwards from the bottom
-    CHECK(s0 == arena + cap - 256 && s1 == arena + cap - 512);              // small ones downwards from the plan's top
-    CHECK(mi3d_swap_stats(e, &st) == MI3D_OK);
-    CHECK(st.n_arena_overflow == 0 && st.arena_high_water_bytes == cap);
-    for (void* p : {big0, s0, big1, s1}) CHECK(mi3d_swap_free(e, p, nullptr) == MI3D_OK);
+    void *a = nullptr, *b = nullptr, *c = nullptr, *all = nullptr;
+    CHECK(mi3d_swap_alloc(e, 1024, nullptr, &a) == MI3D_OK);
+    CHECK(mi3d_swap_alloc(e, 1024, nullptr, &b) == MI3D_OK);
+    CHECK(mi3d_swap_alloc(e, 1024, nullptr, &c) == MI3D_OK);
+    hipstub_hold_events() = true;
+    CHECK(mi3d_swap_out(e, 1, b, nullptr) == MI3D_OK);
+    CHECK(mi3d_swap_release(e, 1, nullptr) == MI3D_OK);
+    CHECK(mi3d_swap_free(e, a, nullptr) == MI3D_OK);
+    CHECK(mi3d_swap_free(e, c, nullptr) == MI3D_OK);
+    CHECK(mi3d_swap_alloc(e, 3 * 1024, nullptr, &all) == MI3D_OK);
+    CHECK(all == arena);
+    hipstub_hold_events() = false;
+    CHECK(mi3d_swap_free(e, all, nullptr) == MI3D_OK);
     CHECK(mi3d_swap_destroy(e) == MI3D_OK);
 }
 
@@ -214,7 +214,7 @@ int main() {
     test_round_trip_states_and_bounds();
     test_arena_counts_blocks_behind_a_copy_and_stays_under_the_plan();
     test_a_block_behind_a_copy_counts_as_occupied();
-    test_small_tensors_pack_from_the_top();
+    test_free_space_behind_a_copy_merges_when_nothing_else_fits();
     test_reset_returns_blocks_of_a_step_that_ended_early();
     test_argument_checks();
     CHECK(hipstub_live_objects() == 0);   // every stream, event and pinned allocation was given back
