@@ -25,13 +25,19 @@ typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 
 constexpr int TH = 16, TW = 32, RH = 4;            // output patch per workgroup, rows per wave
+// Waves and threads per workgroup.  RH = 2 gives eight waves, two per SIMD, so that one wave's LDS reads, conversions
+// and waits run in the shadow of the other's MFMAs (the counters show that a wave issues nothing else while its own
+// MFMA runs).  Measured: 9 % fewer cycles for the 32-channel kernel and the same run time (that kernel is limited by
+// power, the clock drops by as much), and register spills in the 64-channel and streamed-weight variants, which need
+// about 280 registers against the 256 a wave has with two per SIMD: four waves of four rows it stays.
+constexpr int NW = TH / RH, NT = 64 * NW;
 constexpr int IN_ROWS = TH + 2, IN_COLS = TW + 2;  // with halo
 constexpr int COLS = 35;                           // padded row pitch (voxels) in LDS
 constexpr int NV = 646;                            // 16-byte positions per 8-channel slab: 18 x 35 = 630 used, room for
                                                    // ten 64-position loads, slab pitch = 96 bytes mod 256
 constexpr int STAGE_BYTES = 4 * NV * 16;           // 4 slabs of 8 channels, 16 B per voxel
 constexpr int W_BYTES = 27 * 2 * 64 * 16;          // 27 taps x 2 k16 steps x 1 KB fragments
-constexpr int NLOAD = 10;                          // 16-byte loads per thread per plane
+constexpr int NLOAD = 40 / NW;                     // 16-byte loads per thread per plane
 constexpr unsigned OOB = 0x80000000u;              // buffer offset of a piece that must read as zero
 
 struct SpParams {
@@ -244,14 +250,14 @@ __device__ __forceinline__ void store_row(const uint32_t (&o)[8], uint16_t* p, b
 // elsewhere (LeakyReLU derivative of the layer below) after its rounding to bf16 and rounded again: the bits of the
 // plain kernel followed by an elementwise pass, without that pass's read and write of the gradient.
 template <int NC, bool PART = false, bool MASK = false, bool STATS = false>
-__global__ void __launch_bounds__(256, 1) sp_conv_kernel(SpParams P) {
+__global__ void __launch_bounds__(NT, NW / 4) sp_conv_kernel(SpParams P) {
     extern __shared__ __attribute__((aligned(16))) char lds[];
     constexpr bool STREAM = NC == 0;
     constexpr int NBUF = NC == 2 ? 1 : 2;
     const int nc = STREAM ? P.Cin / 32 : NC;
     char* w_lds = lds;
     char* in_lds = lds + (STREAM ? 1 : NC) * W_BYTES;
-    constexpr int WSLOT = W_BYTES / 3, WPIECES = WSLOT / 16, NWL = (WPIECES + 255) / 256;  // 18 KB, 1152, 5
+    constexpr int WSLOT = W_BYTES / 3, WPIECES = WSLOT / 16, NWL = (WPIECES + NT - 1) / NT;  // 18 KB, 1152 pieces
 
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     // XCD-aware placement: hardware deals consecutive workgroup ids round-robin
@@ -275,7 +281,7 @@ __global__ void __launch_bounds__(256, 1) sp_conv_kernel(SpParams P) {
     if (!DMA) {
 #pragma unroll
         for (int i = 0; i < NLOAD; ++i) {
-            int v = 16 * (4 * i + wave) + (lane & 15), c = lane >> 4;
+            int v = 16 * (NW * i + wave) + (lane & 15), c = lane >> 4;
             int row = (v * 241) >> 13, col = v - row * IN_COLS;  // v / 34 for v < 700
             lds_off[i] = (c * NV + row * COLS + col) * 16;
         }
@@ -302,20 +308,20 @@ __global__ void __launch_bounds__(256, 1) sp_conv_kernel(SpParams P) {
         // packed weights of this cout tile (chunked variant: of this cin chunk of it)
         const char* wct = (const char*)P.wpack + ((long long)ct * (PART ? P.NCH : nc) + chunk0) * W_BYTES;
         if (STREAM) {  // slots kw = 0, 1 of chunk 0; slot 2 follows during the first phase
-            for (int i = t; i < 2 * WPIECES; i += 256) ((uint4*)w_lds)[i] = ((const uint4*)wct)[i];
+            for (int i = t; i < 2 * WPIECES; i += NT) ((uint4*)w_lds)[i] = ((const uint4*)wct)[i];
         } else if (ct * (PART ? P.NCH : 1) + chunk0 != cur_ct) {  // (re)load the weights; previous readers passed a barrier
-            for (int i = t; i < NC * W_BYTES / 16; i += 256) ((uint4*)w_lds)[i] = ((const uint4*)wct)[i];
+            for (int i = t; i < NC * W_BYTES / 16; i += NT) ((uint4*)w_lds)[i] = ((const uint4*)wct)[i];
             cur_ct = ct * (PART ? P.NCH : 1) + chunk0;
         }
         // (vector type and no pointer table: with a struct type or an indexed table of sources the pieces were kept
         // in scratch memory, whose loads and stores share the counter of the global loads)
         typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
         u32x4 wreg[NWL];
-        const int wlast = t + 1024 < WPIECES ? t + 1024 : WPIECES - 1;
+        const int wlast = t + NT * (NWL - 1) < WPIECES ? t + NT * (NWL - 1) : WPIECES - 1;
         auto write_wslot = [&](int slot) {
 #pragma unroll
             for (int i = 0; i < NWL; ++i)
-                if (t + 256 * i < WPIECES) *(u32x4*)(w_lds + slot * WSLOT + (t + 256 * i) * 16) = wreg[i];
+                if (t + NT * i < WPIECES) *(u32x4*)(w_lds + slot * WSLOT + (t + NT * i) * 16) = wreg[i];
         };
         // offsets of this thread's pieces relative to the plane base: bytes (DMA) or elements (register path)
         int goff[NLOAD];
@@ -325,12 +331,12 @@ __global__ void __launch_bounds__(256, 1) sp_conv_kernel(SpParams P) {
             int row, col, c;
             bool ok;
             if (DMA) {
-                const int pos = 64 * i + lane;
+                const int pos = 64 * (i + NLOAD * (wave >> 2)) + lane;   // the NW / 4 waves of a slab share its ten loads
                 row = (pos * 1873) >> 16; col = pos - row * COLS;  // pos / 35 for pos < 640
-                c = wave;
+                c = wave & 3;
                 ok = row < IN_ROWS && col < IN_COLS;
             } else {
-                const int v = 16 * (4 * i + wave) + (lane & 15);
+                const int v = 16 * (NW * i + wave) + (lane & 15);
                 row = (v * 241) >> 13; col = v - row * IN_COLS;
                 c = lane >> 4;
                 ok = v < NVOX;
@@ -369,7 +375,7 @@ __global__ void __launch_bounds__(256, 1) sp_conv_kernel(SpParams P) {
         auto load_piece = [&](int i, int buf) {
             if (DMA) {
                 typedef __attribute__((address_space(3))) void* lds_ptr;
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_ptr)(in_lds + buf * STAGE_BYTES + (wave_u * NV + 64 * i) * 16), 16, goff[i], 0, 0, 0);
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_ptr)(in_lds + buf * STAGE_BYTES + ((wave_u & 3) * NV + 64 * (i + NLOAD * (wave_u >> 2))) * 16), 16, goff[i], 0, 0, 0);
             } else {
                 pre[i] = *(const uint4*)(pre_base + goff[i]);
             }
@@ -387,7 +393,7 @@ __global__ void __launch_bounds__(256, 1) sp_conv_kernel(SpParams P) {
                 v.y = ok ? pre[i].y : 0u;
                 v.z = ok ? pre[i].z : 0u;
                 v.w = ok ? pre[i].w : 0u;
-                if (16 * (4 * i + wave) + (lane & 15) < NVOX) *(uint4*)(dst + lds_off[i]) = v;
+                if (16 * (NW * i + wave) + (lane & 15) < NVOX) *(uint4*)(dst + lds_off[i]) = v;
             }
         };
         // finished rows wait in outp[] and are stored during the next stage
@@ -465,7 +471,7 @@ __global__ void __launch_bounds__(256, 1) sp_conv_kernel(SpParams P) {
                                              w_lane + (STREAM ? 0 : (CHUNK) * W_BYTES), outp, MASK ? 1.f : P.slope, kdmask_, [&](int k) { \
                 if (STREAM && k % 6 == 0) { /* all pieces of the slot at the start of its phase: a full phase of cover */ \
                     const char* ws_ = k / 6 == 0 ? wsrc0_ : k / 6 == 1 ? wsrc1_ : wsrc2_;       \
-                    _Pragma("unroll") for (int i_ = 0; i_ < NWL; ++i_) wreg[i_] = *(const u32x4*)(ws_ + (i_ < NWL - 1 ? t + 256 * i_ : wlast) * 16); \
+                    _Pragma("unroll") for (int i_ = 0; i_ < NWL; ++i_) wreg[i_] = *(const u32x4*)(ws_ + (i_ < NWL - 1 ? t + NT * i_ : wlast) * 16); \
                 }                                                                               \
                 if (k < NLOAD) load_piece(k, NBUF == 2 ? ((sq + 1) & 1) : 0);                   \
                 if (MASK && k >= NLOAD - RH && k < NLOAD) load_mask(k - (NLOAD - RH));          \
@@ -485,8 +491,8 @@ __global__ void __launch_bounds__(256, 1) sp_conv_kernel(SpParams P) {
                 st_off = (((long long)(j_ - 2) * P.Ho + h0 + wave * RH) * P.Wo + ow_) * opitch + (PART ? ct : ct_local) * 32;  \
             }                                                                                   \
             ++sq;                                                                               \
-            /* the ten loads into the next stage are complete; the eight stores issued after them may still fly */ \
-            if (DMA) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");                           \
+            /* the loads into the next stage are complete; the 2 RH stores issued after them may still fly */ \
+            if (DMA) { if (RH == 4) asm volatile("s_waitcnt vmcnt(8)" ::: "memory"); else asm volatile("s_waitcnt vmcnt(4)" ::: "memory"); } \
             __syncthreads();                                                                    \
         }
 #define SP_STEP(PHASE)                                                                          \
@@ -524,7 +530,7 @@ __global__ void __launch_bounds__(256, 1) sp_conv_kernel(SpParams P) {
                 }
             if (t == 0) P.stat_key[g * P.max_seg + seg] = n * P.CT + ct;   // whose sums these are
             if ((lane & 31) == 0) {
-                float* out = P.stat_part + (((long long)g * P.max_seg + seg) * 4 + wave) * 64;
+                float* out = P.stat_part + (((long long)g * P.max_seg + seg) * NW + wave) * 64;
 #pragma unroll
                 for (int j = 0; j < 16; ++j) {
                     const int c = 8 * (j >> 2) + 4 * (lane >> 5) + (j & 3);
@@ -553,8 +559,8 @@ __global__ void __launch_bounds__(256) sp_stats_finish_kernel(const float* __res
     for (int g = sl; g < nwg; g += 4)
         for (int seg = 0; seg < max_seg; ++seg)
             if (key[g * max_seg + seg] == mine) {
-                const float* p = part + (((long long)g * max_seg + seg) * 4) * 64;
-                for (int w = 0; w < 4; ++w) a += (double)p[w * 64 + qc];
+                const float* p = part + (((long long)g * max_seg + seg) * NW) * 64;
+                for (int w = 0; w < NW; ++w) a += (double)p[w * 64 + qc];
             }
     red[sl][qc] = a;
     __syncthreads();
@@ -648,7 +654,7 @@ static void sp_stat_layout(const Geom& g, long long* units, int* nwg, int* max_s
 static size_t sp_stat_bytes(const Geom& g) {
     long long units; int nwg, max_seg;
     sp_stat_layout(g, &units, &nwg, &max_seg);
-    return (size_t)nwg * max_seg * (4 * 64 * sizeof(float) + sizeof(int)) + 256;
+    return (size_t)nwg * max_seg * (NW * 64 * sizeof(float) + sizeof(int)) + 256;
 }
 bool sp_fuses_stats(const Geom& g) { return sp_supported(g, MI3D_PASS_FWD) && !sp_use_chunks(g, MI3D_PASS_FWD); }
 
@@ -714,7 +720,7 @@ int sp_conv(const Geom& g, int pass, const void* in, const void* w, void* out, v
     if (stat) {
         long long units; int n2;
         sp_stat_layout(g, &units, &n2, &P.max_seg);
-        P.stat_key = (int*)(P.stat_part + (size_t)n2 * P.max_seg * 4 * 64);
+        P.stat_key = (int*)(P.stat_part + (size_t)n2 * P.max_seg * NW * 64);
     }
     const int nc = P.Cin / 32;
     const size_t lds1 = W_BYTES + 2 * STAGE_BYTES, lds2 = 2 * W_BYTES + STAGE_BYTES;
@@ -734,7 +740,7 @@ int sp_conv(const Geom& g, int pass, const void* in, const void* w, void* out, v
         attr_set = true;
     }
     if (chunks) {
-        sp_conv_kernel<1, true><<<(unsigned)nwg, 256, lds1, s>>>(P);
+        sp_conv_kernel<1, true><<<(unsigned)nwg, NT, lds1, s>>>(P);
         st = check_launch();
         if (st) return st;
         const long long n = (long long)P.N * P.Do * P.Ho * P.Wo * P.Cout;   // a multiple of 32
@@ -745,21 +751,21 @@ int sp_conv(const Geom& g, int pass, const void* in, const void* w, void* out, v
         return check_launch();
     }
     if (stat) {
-        if (nc == 1) sp_conv_kernel<1, false, false, true><<<(unsigned)nwg, 256, lds1, s>>>(P);
-        else if (nc == 2) sp_conv_kernel<2, false, false, true><<<(unsigned)nwg, 256, lds2, s>>>(P);
-        else sp_conv_kernel<0, false, false, true><<<(unsigned)nwg, 256, lds1, s>>>(P);
+        if (nc == 1) sp_conv_kernel<1, false, false, true><<<(unsigned)nwg, NT, lds1, s>>>(P);
+        else if (nc == 2) sp_conv_kernel<2, false, false, true><<<(unsigned)nwg, NT, lds2, s>>>(P);
+        else sp_conv_kernel<0, false, false, true><<<(unsigned)nwg, NT, lds1, s>>>(P);
         st = check_launch();
         if (st) return st;
         sp_stats_finish_kernel<<<P.N * P.CT, 256, 0, s>>>(P.stat_part, P.stat_key, P.Cout, P.CT, P.nwg, P.max_seg,
                                                           1.0 / ((double)P.Do * P.Ho * P.Wo), g.stats_eps, g.stats);
         return check_launch();
     }
-    if (mask && nc == 1) sp_conv_kernel<1, false, true><<<(unsigned)nwg, 256, lds1, s>>>(P);
-    else if (mask && nc == 2) sp_conv_kernel<2, false, true><<<(unsigned)nwg, 256, lds2, s>>>(P);
-    else if (mask) sp_conv_kernel<0, false, true><<<(unsigned)nwg, 256, lds1, s>>>(P);
-    else if (nc == 1) sp_conv_kernel<1><<<(unsigned)nwg, 256, lds1, s>>>(P);
-    else if (nc == 2) sp_conv_kernel<2><<<(unsigned)nwg, 256, lds2, s>>>(P);
-    else sp_conv_kernel<0><<<(unsigned)nwg, 256, lds1, s>>>(P);
+    if (mask && nc == 1) sp_conv_kernel<1, false, true><<<(unsigned)nwg, NT, lds1, s>>>(P);
+    else if (mask && nc == 2) sp_conv_kernel<2, false, true><<<(unsigned)nwg, NT, lds2, s>>>(P);
+    else if (mask) sp_conv_kernel<0, false, true><<<(unsigned)nwg, NT, lds1, s>>>(P);
+    else if (nc == 1) sp_conv_kernel<1><<<(unsigned)nwg, NT, lds1, s>>>(P);
+    else if (nc == 2) sp_conv_kernel<2><<<(unsigned)nwg, NT, lds2, s>>>(P);
+    else sp_conv_kernel<0><<<(unsigned)nwg, NT, lds1, s>>>(P);
     return check_launch();
 }
 
