@@ -607,6 +607,8 @@ def main():
     ap.add_argument("--headline-only", action="store_true",
                     help="only the timed U-Net step and its per-kernel figures (the command the profiles are taken with)")
     ap.add_argument("--no-norm", action="store_true", help="headline step without the instance normalisation")
+    ap.add_argument("--level0-only", action="store_true",
+                    help="only the first U-Net level at 192^3, N=1 (config 3), every pass alone: the command its profiles are taken with")
     ap.add_argument("--unet-layers", action="store_true",
                     help="also time fwd/dgrad/wgrad of every Conv3D layer of the 5-level U-Net at 192^3, N=1, each alone (adds ~20 s)")
     args = ap.parse_args()
@@ -630,6 +632,9 @@ def main():
         del src, dst
         torch.cuda.empty_cache()
 
+    if args.level0_only:
+        print(json.dumps({"level0_192": level0_chain(args)}))
+        return
     # ---- the headline: config 5, the whole training step of the 5-level U-Net at 192^3, N = 2, bf16, with the block
     # of Section 4.1 (convolution -> instance normalisation -> LeakyReLU), soft Dice, SGD, and the swap engine under
     # the 16 GiB budget.  A step is one pass of the whole hot path: every convolution's forward, data-gradient and
