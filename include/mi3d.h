@@ -340,7 +340,9 @@ typedef struct {
     uint64_t arena_high_water_bytes;     /* highest end offset of such a block: the arena the step really needed */
     uint64_t planned_arena_bytes;        /* bytes of saved tensors at the peak of the planner's model (256-byte
                                             units); mi3d_swap_alloc stays below this offset while it can */
-    int      n_arena_overflow;           /* allocations that fragmentation pushed above planned_arena_bytes */
+    uint64_t static_arena_bytes;         /* extent of the plan's static placement: the arena mi3d_swap_alloc_tensor needs */
+    int      n_arena_overflow;           /* allocations that fragmentation pushed above planned_arena_bytes, or that
+                                            mi3d_swap_alloc_tensor could not put at their planned place */
     uint64_t planned_peak_bytes;         /* peak of the planner's residency model with the chosen swap set */
     uint64_t unswapped_peak_bytes;       /* same model with nothing swapped */
     int      n_registered, n_planned;    /* tensors known / chosen for swapping */
@@ -417,6 +419,24 @@ int mi3d_swap_planned_bytes_at(mi3d_swap_engine *e, int op, uint64_t *bytes);
  * to wait for a swap-out that still reads that block.
  * MI3D_ERR_OVER_BUDGET when no block is large enough. */
 int mi3d_swap_alloc(mi3d_swap_engine *e, size_t bytes, void *stream, void **dev_ptr);
+/* Static placement.  mi3d_swap_plan also lays the saved tensors out in one arena from their lifetimes under the plan:
+ * every stay of a tensor on the device gets a fixed offset (largest tensors first, lowest free offset among the stays it
+ * shares an op with; the first stay of a swapped tensor lasts until its modelled copy-out has finished).
+ * mi3d_swap_static_arena_bytes returns the extent of that layout: an arena of this size holds the whole step, so a
+ * caller that allocates exactly this much (mi3d_swap_set_arena, any time no block is handed out) has a device
+ * footprint that is fixed by the plan.  mi3d_swap_alloc_tensor hands out the planned range of tensor `id` (first call
+ * in a step: its first stay; second call, for a tensor that is swapped or re-computed: its second stay) with the
+ * stream waits of mi3d_swap_alloc; if the range is not free (the caller's order of allocations and frees differs
+ * from the registered lifetimes) it falls back to mi3d_swap_alloc and counts an overflow.  Freed with mi3d_swap_free /
+ * mi3d_swap_release as any block. */
+int mi3d_swap_set_arena(mi3d_swap_engine *e, void *dev_arena, size_t arena_bytes);
+/* Changes budget_bytes of the configuration (a caller that measures its real footprint tightens the planner's budget by
+ * what the measurement exceeds the budget it was given).  Invalidates the plan. */
+int mi3d_swap_set_budget(mi3d_swap_engine *e, size_t budget_bytes);
+int mi3d_swap_static_arena_bytes(mi3d_swap_engine *e, uint64_t *bytes);
+int mi3d_swap_alloc_tensor(mi3d_swap_engine *e, int id, void *stream, void **dev_ptr);
+/* Offset of stay 0 or 1 of tensor `id` in the static placement (stay 1 only for tensors that leave the device). */
+int mi3d_swap_planned_offset(mi3d_swap_engine *e, int id, int stay, uint64_t *offset);
 /* Returns a block; it becomes reusable once the work enqueued on `stream` so
  * far has finished (and, for a tensor being swapped out, once its copy has). */
 int mi3d_swap_free(mi3d_swap_engine *e, void *dev_ptr, void *stream);

@@ -28,7 +28,7 @@ class SwapStats(ctypes.Structure):
                 ("copy_ms_out", ctypes.c_double), ("copy_ms_in", ctypes.c_double),
                 ("busy_ms", ctypes.c_double),
                 ("peak_arena_bytes", ctypes.c_uint64), ("arena_high_water_bytes", ctypes.c_uint64),
-                ("planned_arena_bytes", ctypes.c_uint64), ("n_arena_overflow", ctypes.c_int),
+                ("planned_arena_bytes", ctypes.c_uint64), ("static_arena_bytes", ctypes.c_uint64), ("n_arena_overflow", ctypes.c_int),
                 ("planned_peak_bytes", ctypes.c_uint64),
                 ("unswapped_peak_bytes", ctypes.c_uint64),
                 ("n_registered", ctypes.c_int), ("n_planned", ctypes.c_int),
@@ -101,6 +101,11 @@ SIGNATURES = {
     "mi3d_swap_planned_bytes_at": (_i, [_vp, _i, ctypes.POINTER(ctypes.c_uint64)]),
     "mi3d_swap_alloc": (_i, [_vp, _sz, _vp, ctypes.POINTER(_vp)]),
     "mi3d_swap_free": (_i, [_vp, _vp, _vp]),
+    "mi3d_swap_set_arena": (_i, [_vp, _vp, _sz]),
+    "mi3d_swap_set_budget": (_i, [_vp, _sz]),
+    "mi3d_swap_planned_offset": (_i, [_vp, _i, _i, ctypes.POINTER(ctypes.c_uint64)]),
+    "mi3d_swap_static_arena_bytes": (_i, [_vp, ctypes.POINTER(ctypes.c_uint64)]),
+    "mi3d_swap_alloc_tensor": (_i, [_vp, _i, _vp, ctypes.POINTER(_vp)]),
     "mi3d_swap_out": (_i, [_vp, _i, _vp, _vp]),
     "mi3d_swap_release": (_i, [_vp, _i, _vp]),
     "mi3d_swap_in": (_i, [_vp, _i, _vp, _vp]),

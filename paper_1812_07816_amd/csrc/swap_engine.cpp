@@ -24,6 +24,7 @@ struct Copy {
 
 struct Tensor {
     PlanTensor plan;
+    int allocs = 0;     // placements handed out by mi3d_swap_alloc_tensor in this step (0: first stay, 1: second)
     State state = ST_NEW;
     const void* dev_src = nullptr;
     Copy out, in;
@@ -240,6 +241,7 @@ void reset_step_state(mi3d_swap_engine* e) {
         }
         t.state = ST_NEW;
         t.dev_src = nullptr;
+        t.allocs = 0;
     }
     e->bytes_out = e->bytes_in = 0;
     e->n_out = e->n_in = 0;
@@ -379,7 +381,8 @@ int mi3d_swap_plan(mi3d_swap_engine* e) {
     for (const PlanTensor& t : ts) e->tensors[t.id].plan = t;
     // a swap set that does not fit the pinned pool is not executable: its host slots lie beyond the pool
     e->have_plan = st != MI3D_ERR_HOST_POOL;
-    // bytes of saved tensors at the peak of the residency model, each rounded up as the arena rounds them
+    // bytes of saved tensors at the peak of the residency model, each rounded up as the arena rounds them (the limit
+    // mi3d_swap_alloc tries to stay under; mi3d_swap_alloc_tensor uses the static placement instead)
     e->arena_cap = 0;
     if (e->have_plan) {
         std::vector<PlanTensor> rounded = ts;
@@ -508,6 +511,79 @@ int mi3d_swap_alloc(mi3d_swap_engine* e, size_t bytes, void* stream, void** dev_
     e->arena_used += need;
     note_occupancy(e);
     *dev_ptr = (char*)e->cfg.dev_arena + a.off;
+    return MI3D_OK;
+}
+
+int mi3d_swap_set_budget(mi3d_swap_engine* e, size_t budget_bytes) {
+    if (!e) return MI3D_ERR_INVALID_ARG;
+    e->cfg.budget_bytes = budget_bytes;
+    e->have_plan = false;
+    return MI3D_OK;
+}
+
+int mi3d_swap_set_arena(mi3d_swap_engine* e, void* dev_arena, size_t arena_bytes) {
+    if (!e || (dev_arena == nullptr) != (arena_bytes == 0) || ((uintptr_t)dev_arena & 255)) return MI3D_ERR_INVALID_ARG;
+    for (const ArenaBlock& b : e->blocks)
+        if (!b.free) return MI3D_ERR_BAD_STATE;   // blocks of the old arena are still handed out
+    e->blocks.clear();
+    e->cfg.dev_arena = dev_arena;
+    e->cfg.arena_bytes = arena_bytes;
+    e->arena_used = 0;
+    if (arena_bytes) e->blocks.push_back(ArenaBlock{0, arena_bytes & ~(size_t)255, true, {}});
+    return MI3D_OK;
+}
+
+int mi3d_swap_static_arena_bytes(mi3d_swap_engine* e, uint64_t* bytes) {
+    if (!e || !bytes) return MI3D_ERR_INVALID_ARG;
+    if (!e->have_plan) return MI3D_ERR_BAD_STATE;
+    *bytes = e->plan_res.static_arena_bytes;
+    return MI3D_OK;
+}
+
+int mi3d_swap_planned_offset(mi3d_swap_engine* e, int id, int stay, uint64_t* offset) {
+    if (!e || !offset || stay < 0 || stay > 1) return MI3D_ERR_INVALID_ARG;
+    Tensor* t = find(e, id);
+    if (!t || !e->have_plan) return MI3D_ERR_BAD_STATE;
+    if (stay == 1 && !t->plan.planned && !t->plan.recompute) return MI3D_ERR_BAD_STATE;   // a kept tensor stays once
+    *offset = t->plan.arena_off[stay];
+    return MI3D_OK;
+}
+
+int mi3d_swap_alloc_tensor(mi3d_swap_engine* e, int id, void* stream, void** dev_ptr) {
+    if (!e || !dev_ptr) return MI3D_ERR_INVALID_ARG;
+    Tensor* t = find(e, id);
+    if (!t || !e->have_plan || !e->cfg.dev_arena) return MI3D_ERR_BAD_STATE;
+    const size_t need = (t->plan.bytes + 255) & ~(size_t)255;
+    const bool leaves = t->plan.planned || t->plan.recompute;
+    const int stay = leaves && t->allocs > 0 ? 1 : 0;
+    const size_t off = t->plan.arena_off[stay];
+    t->allocs++;
+    // every block the planned range touches must be free; the range then waits for whatever still uses those blocks
+    bool fits = off + need <= (e->cfg.arena_bytes & ~(size_t)255);
+    for (const ArenaBlock& b : e->blocks)
+        if (fits && b.off < off + need && off < b.off + b.size && !b.free) fits = false;
+    if (!fits) {   // the step did not follow the plan's lifetimes (or the arena is smaller than the placement): any free block
+        e->arena_overflow++;
+        return mi3d_swap_alloc(e, t->plan.bytes, stream, dev_ptr);
+    }
+    for (ArenaBlock& b : e->blocks) {   // drop events that have fired
+        if (!b.free) continue;
+        auto& pv = b.pending;
+        pv.erase(std::remove_if(pv.begin(), pv.end(), [](const Pending& p) { return hipEventQuery((hipEvent_t)p.ev.get()) == hipSuccess; }), pv.end());
+    }
+    std::vector<ArenaBlock> out;
+    bool placed = false;
+    for (const ArenaBlock& b : e->blocks) {
+        if (!(b.off < off + need && off < b.off + b.size)) { out.push_back(b); continue; }
+        for (const Pending& p : b.pending) HIP_TRY(hipStreamWaitEvent((hipStream_t)stream, (hipEvent_t)p.ev.get(), 0));
+        if (b.off < off) out.push_back(ArenaBlock{b.off, off - b.off, true, b.pending});
+        if (!placed) { out.push_back(ArenaBlock{off, need, false, {}}); placed = true; }
+        if (b.off + b.size > off + need) out.push_back(ArenaBlock{off + need, b.off + b.size - (off + need), true, b.pending});
+    }
+    e->blocks.swap(out);
+    e->arena_used += need;
+    note_occupancy(e);
+    *dev_ptr = (char*)e->cfg.dev_arena + off;
     return MI3D_OK;
 }
 
@@ -695,6 +771,7 @@ int mi3d_swap_stats(mi3d_swap_engine* e, mi3d_swap_stats_t* out) {
     out->peak_arena_bytes = e->arena_occupied_peak;
     out->arena_high_water_bytes = e->arena_hwm;
     out->planned_arena_bytes = e->have_plan ? e->arena_cap : 0;
+    out->static_arena_bytes = e->have_plan ? e->plan_res.static_arena_bytes : 0;
     out->n_arena_overflow = e->arena_overflow;
     out->planned_peak_bytes = e->have_plan ? e->plan_res.planned_peak : 0;
     out->unswapped_peak_bytes = e->have_plan ? e->plan_res.unswapped_peak : 0;

@@ -94,6 +94,73 @@ static void apply_deps(std::vector<PlanTensor>& ts, const PlanParams& p) {
     for (PlanTensor& t : ts) t.prefetch_op = prefetch_by_ops(t, p);
 }
 
+uint64_t place_static(std::vector<PlanTensor>& ts, const PlanParams& p) {
+    int n_ops = p.n_ops;
+    for (const PlanTensor& t : ts) n_ops = std::max(n_ops, t.bwd_last_use_op + 1);
+    const bool timed = p.op_ms && !p.op_ms->empty() && p.link_gbs > 0.f;
+    // start time of every op (ms) for the copy model
+    std::vector<double> start(n_ops + 1, 0.0);
+    if (timed)
+        for (int op = 0; op < n_ops; ++op) start[op + 1] = start[op] + (op < (int)p.op_ms->size() ? (double)(*p.op_ms)[op] : 0.0);
+    // end of the first stay of the swapped tensors: the copies share one stream and leave in production order
+    std::vector<int> fwd_end(ts.size());
+    std::vector<int> order(ts.size());
+    for (size_t i = 0; i < ts.size(); ++i) order[i] = (int)i;
+    std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return ts[a].produce_op < ts[b].produce_op; });
+    double link_free = 0.0;
+    for (int i : order) {
+        const PlanTensor& t = ts[i];
+        fwd_end[i] = t.last_fwd_use_op;
+        if (!t.planned) continue;
+        if (!timed) { fwd_end[i] = std::min(t.last_fwd_use_op + 1, std::max(t.prefetch_op - 1, t.last_fwd_use_op)); continue; }
+        const double begin = std::max(start[std::min(t.produce_op + 1, n_ops)], link_free);
+        const double finish = begin + (double)t.bytes / ((double)p.link_gbs * 1e6) * 1.15 + 0.05;
+        link_free = finish;
+        int e = t.last_fwd_use_op;
+        while (e + 1 < t.prefetch_op && start[e + 1] < finish) ++e;   // ops that start while the copy still reads the block
+        fwd_end[i] = e;
+    }
+    struct Stay { int tensor, which, from, to; size_t size, off; };
+    std::vector<Stay> stays;
+    for (size_t i = 0; i < ts.size(); ++i) {
+        const PlanTensor& t = ts[i];
+        const size_t sz = (t.bytes + 255) & ~(size_t)255;
+        if (!t.planned && !t.recompute) {
+            stays.push_back({(int)i, 0, t.produce_op, t.bwd_last_use_op, sz, 0});
+        } else {
+            stays.push_back({(int)i, 0, t.produce_op, fwd_end[i], sz, 0});
+            stays.push_back({(int)i, 1, t.recompute ? t.bwd_first_use_op : t.prefetch_op, t.bwd_last_use_op, sz, 0});
+        }
+    }
+    std::vector<int> by_size(stays.size());
+    for (size_t i = 0; i < stays.size(); ++i) by_size[i] = (int)i;
+    std::stable_sort(by_size.begin(), by_size.end(), [&](int a, int b) {
+        return stays[a].size != stays[b].size ? stays[a].size > stays[b].size : stays[a].from < stays[b].from;
+    });
+    std::vector<int> placed;
+    uint64_t extent = 0;
+    for (int si : by_size) {
+        Stay& s = stays[si];
+        // the stays already placed that share an op with this one, by offset
+        std::vector<std::pair<size_t, size_t>> busy;
+        for (int pi : placed) {
+            const Stay& q = stays[pi];
+            if (q.from <= s.to && s.from <= q.to) busy.emplace_back(q.off, q.off + q.size);
+        }
+        std::sort(busy.begin(), busy.end());
+        size_t off = 0;
+        for (const auto& b : busy) {
+            if (off + s.size <= b.first) break;
+            off = std::max(off, b.second);
+        }
+        s.off = off;
+        extent = std::max<uint64_t>(extent, off + s.size);
+        placed.push_back(si);
+    }
+    for (const Stay& s : stays) ts[s.tensor].arena_off[s.which] = s.off;
+    return extent;
+}
+
 int plan_swaps(std::vector<PlanTensor>& ts, const std::vector<size_t>& transient, const PlanParams& p, PlanResult* res) {
     int n_ops = p.n_ops;
     for (const PlanTensor& t : ts) n_ops = std::max(n_ops, t.bwd_last_use_op + 1);
@@ -254,6 +321,7 @@ int plan_swaps(std::vector<PlanTensor>& ts, const std::vector<size_t>& transient
             res->recompute_ms += t.recompute_ms;
         }
     res->planned_peak = peak(ts, transient, n_ops, false, nullptr);
+    res->static_arena_bytes = place_static(ts, p);
     if (p.host_pool_bytes && off > p.host_pool_bytes) return MI3D_ERR_HOST_POOL;
     if (res->planned_peak > p.budget_bytes) return MI3D_ERR_OVER_BUDGET;
     return MI3D_OK;

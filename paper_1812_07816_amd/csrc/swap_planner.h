@@ -27,6 +27,9 @@ struct PlanTensor {
     int dep[2] = {-1, -1};
     bool recompute = false;      // dropped after its last forward use, produced again at bwd_first_use_op
     int bwd_first_use_reg = -1;  // bwd_first_use_op as registered (the plan lowers it for tensors a re-computation reads)
+    // static placement in the device arena: offset of the tensor's first stay on the device (from its production) and,
+    // for a tensor that leaves and comes back, of its second stay (from its swap-in or re-computation)
+    size_t arena_off[2] = {0, 0};
 };
 
 struct PlanParams {
@@ -50,6 +53,7 @@ struct PlanResult {
     size_t host_bytes = 0;
     int n_recompute = 0;
     double recompute_ms = 0.0;   // sum of the costs of the chosen re-computations
+    uint64_t static_arena_bytes = 0;   // extent of the static placement (place_static)
 };
 
 // Resident bytes at `op`: transients plus every tensor that is on the device
@@ -58,6 +62,14 @@ struct PlanResult {
 // from prefetch_op to bwd_last_use_op; a re-computed one from produce_op to
 // last_fwd_use_op and again from bwd_first_use_op to bwd_last_use_op.
 uint64_t plan_bytes_at(const std::vector<PlanTensor>& ts, const std::vector<size_t>& transient, int op, bool ignore_plan);
+
+// Static placement of the saved tensors in one arena, from their lifetimes under the current plan: every stay of a tensor on
+// the device (one for a tensor that is kept, two for one that is swapped or re-computed) is an interval of ops and gets a
+// fixed offset, largest tensors first, each at the lowest offset where it overlaps no stay already placed that it shares an
+// op with.  The first stay of a swapped tensor lasts until its copy to the host has finished: with op times that is
+// modelled (the copies leave one after the other in production order at the link rate), else one op of grace is added.
+// Sizes count in units of 256 bytes.  Fills arena_off and returns the extent of the arena.
+uint64_t place_static(std::vector<PlanTensor>& ts, const PlanParams& p);
 
 // Fills planned / prefetch_op / host_offset.  Returns 0, MI3D_ERR_OVER_BUDGET
 // or MI3D_ERR_HOST_POOL (the plan is filled in either way), or

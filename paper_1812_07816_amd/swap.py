@@ -102,6 +102,31 @@ class SwapEngine:
         check(lib().mi3d_swap_alloc(self._h, bytes, _stream(stream), ctypes.byref(p)), "swap_alloc")
         return p.value
 
+    def set_arena(self, arena):
+        """Replaces the device arena (a torch uint8 CUDA tensor, or None); no block may be handed out."""
+        check(lib().mi3d_swap_set_arena(self._h, None if arena is None else arena.data_ptr(),
+                                        0 if arena is None else arena.numel() * arena.element_size()), "swap_set_arena")
+        self.arena = arena
+
+    def set_budget(self, budget_bytes):
+        check(lib().mi3d_swap_set_budget(self._h, int(budget_bytes)), "swap_set_budget")
+
+    def static_arena_bytes(self):
+        b = ctypes.c_uint64()
+        check(lib().mi3d_swap_static_arena_bytes(self._h, ctypes.byref(b)), "swap_static_arena_bytes")
+        return b.value
+
+    def planned_offset(self, id, stay=0):
+        b = ctypes.c_uint64()
+        check(lib().mi3d_swap_planned_offset(self._h, id, stay, ctypes.byref(b)), "swap_planned_offset")
+        return b.value
+
+    def alloc_tensor(self, id, stream=None):
+        """The planned place of saved tensor `id` in the arena (its first or second stay, in call order)."""
+        p = ctypes.c_void_p()
+        check(lib().mi3d_swap_alloc_tensor(self._h, id, _stream(stream), ctypes.byref(p)), "swap_alloc_tensor")
+        return p.value
+
     def free(self, ptr, stream=None):
         check(lib().mi3d_swap_free(self._h, ptr, _stream(stream)), "swap_free")
 

@@ -205,9 +205,10 @@ class UNetStep:
             budget = (1 << 62) if budget_bytes is None else int(budget_bytes)
             sizes = [s.bytes for s in self.saved]
             pool = sum((b + 4095) // 4096 * 4096 for b in sizes) + 4096
-            arena_bytes = sum((b + 255) // 256 * 256 for b in sizes) + 4096
-            self.arena = torch.empty(arena_bytes, dtype=torch.uint8, device="cuda")
-            self.engine = e = sw.SwapEngine(budget_bytes=budget, host_pool_bytes=pool, arena=self.arena, lookahead=lookahead,
+            # the arena is sized by the plan's static placement of the saved tensors (see _read_plan): what the step
+            # holds on the device is then fixed by the plan, not by how an allocator happened to fill a large pool
+            self.arena, self.budget = None, budget
+            self.engine = e = sw.SwapEngine(budget_bytes=budget, host_pool_bytes=pool, arena=None, lookahead=lookahead,
                                             policy=policy, n_tensors=n_tensors, exclude_tags=exclude_tags)
             e.set_timeline(self.n_fwd, self.n_ops)
             e.set_eviction(eviction)
@@ -240,6 +241,13 @@ class UNetStep:
         self.planned = [e.is_planned(s.id) for s in self.saved]
         self.recomputed = [e.is_recomputed(s.id) for s in self.saved]
         self.prefetch = [e.prefetch_op(s.id) for s in self.saved]
+        need = e.static_arena_bytes() + 256
+        if self.arena is None or self.arena.numel() != need:
+            e.set_arena(None)
+            self.arena = None
+            torch.cuda.empty_cache()
+            self.arena = torch.empty(need, dtype=torch.uint8, device="cuda")
+            e.set_arena(self.arena)
 
     def bwd_op(self, f):
         return self.n_fwd + (self.n_fwd - 1 - f)
@@ -279,7 +287,7 @@ class UNetStep:
         if self.engine is None:
             s.view = torch.empty(s.shape, dtype=self.dtype, device="cuda")
         else:
-            s.ptr = self.engine.alloc(s.bytes)
+            s.ptr = self.engine.alloc_tensor(s.id)
             s.view = self._view(s.ptr, s.shape)
         return s.view
 
@@ -304,7 +312,7 @@ class UNetStep:
             return
         for s in self.saved:
             if self.planned[s.id] and self.prefetch[s.id] == op:
-                s.ptr = self.engine.alloc(s.bytes)
+                s.ptr = self.engine.alloc_tensor(s.id)
                 self.engine.swap_in(s.id, s.ptr)
                 s.view = self._view(s.ptr, s.shape)
 
@@ -570,6 +578,36 @@ class UNetStep:
                     e.set_recompute(op["out"].id, ms[f], op["src"].id)
         self._read_plan(e.plan(allow_over_budget=True))
         self.op_ms = ms
+
+    def fit_budget(self, rounds=4):
+        """Makes the step's measured device footprint meet its budget: runs a step, reads the peak of the torch
+        allocator (arena, gradients, weights, workspaces, labels: every device byte this process holds) and, where
+        that exceeds the budget, takes the excess off the planner's budget and plans again.  Returns the measured
+        peak of the last step (bytes)."""
+        if self.engine is None:
+            return None
+        internal = self.budget
+        peak = None
+        self.fit_log = []     # per round: planner budget, plan status, tensors swapped, re-computed, measured peak
+        for _ in range(rounds):
+            torch.cuda.synchronize()
+            torch.cuda.reset_peak_memory_stats()
+            self.run(update=False)
+            torch.cuda.synchronize()
+            peak = torch.cuda.max_memory_allocated()
+            self.fit_log.append((internal, self.plan_status, sum(self.planned), sum(self.recomputed), peak))
+            if peak <= self.budget or self.budget >= (1 << 60):
+                break
+            # the planner's model has to come down by what the measurement exceeds the budget (the model knows nothing
+            # of what else the process holds, so the correction is relative to the model's own peak)
+            modelled = self.engine.stats()["planned_peak_bytes"]
+            internal = min(internal, modelled) - (peak - self.budget) - (4 << 20)
+            if internal <= 0:
+                break
+            self.engine.set_budget(internal)
+            self._read_plan(self.engine.plan(allow_over_budget=True))
+        self.measured_peak_bytes = peak
+        return peak
 
     def close(self):
         if self.engine is not None:

