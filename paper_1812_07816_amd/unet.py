@@ -579,7 +579,7 @@ class UNetStep:
         self._read_plan(e.plan(allow_over_budget=True))
         self.op_ms = ms
 
-    def fit_budget(self, rounds=4):
+    def fit_budget(self, rounds=6):
         """Makes the step's measured device footprint meet its budget: runs a step, reads the peak of the torch
         allocator (arena, gradients, weights, workspaces, labels: every device byte this process holds) and, where
         that exceeds the budget, takes the excess off the planner's budget and plans again.  Returns the measured
