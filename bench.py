@@ -35,11 +35,11 @@ def _profile_lookup(files, kernel, ncols):
     return None
 
 
-def measured_traffic(kernel):
-    """HBM bytes per launch of `kernel` as counted by rocprofv3 (FETCH_SIZE and WRITE_SIZE runs of this same
-    command, scaled by a copy kernel of known size); the figures are kept, with the commands that produced them,
-    under profiles/ as lines `<kernel> <read bytes> <write bytes>`.  None if not recorded."""
-    v = _profile_lookup(("hbm_traffic_unet_step_192_N2.txt", "hbm_traffic_192_level0.txt"), kernel, 2)
+def measured_traffic(kernel, workload="unet_step_192_N2"):
+    """HBM bytes per launch of `kernel` in the given workload as counted by rocprofv3 (FETCH_SIZE and WRITE_SIZE runs of
+    the bench command of that workload, scaled by a copy kernel of known size); the figures are kept, with the commands
+    that produced them, under profiles/ as lines `<kernel> <read bytes> <write bytes>`.  None if not recorded."""
+    v = _profile_lookup(("hbm_traffic_%s.txt" % workload,), kernel, 2)
     return None if v is None else v[0] + v[1]
 
 
@@ -583,11 +583,11 @@ def level0_chain(args):
         return {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS}
 
     roof = roofline_of(dom)
-    roof.update({"traffic": measured_traffic(dom_name), "kernel": dom_name, "launches": dom["launches"],
+    roof.update({"traffic": measured_traffic(dom_name, "192_level0"), "kernel": dom_name, "launches": dom["launches"],
                  "ms_per_launch": dom["ms"] / len(dom["launches"]), "share_of_kernel_time": dom["ms"] / sum(r["ms"] for r in per)})
     for r in per:
         r["roofline"] = {k: (round(v, 4) if isinstance(v, float) else v) for k, v in roofline_of(r).items()}
-        r["roofline"]["traffic"] = measured_traffic(r["kernel"])
+        r["roofline"]["traffic"] = measured_traffic(r["kernel"], "192_level0")
     # what the matrix cores sustain in a bare MFMA loop on this machine (the rate is power-limited and depends on the
     # operands): context for the MFMA-bound fractions above, which stay relative to the published peak
     

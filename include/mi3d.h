@@ -172,6 +172,21 @@ int mi3d_conv3d_fwd_stats_supported(const mi3d_conv_desc *desc);
 int mi3d_conv3d_fwd_stats(const mi3d_conv_desc *desc, const void *x, const void *x_hi, const void *w, void *y,
                           float eps, float *stats, void *ws, size_t ws_bytes, void *stream);
 
+/* Data gradient whose kernel also produces the two means the backward pass of the instance normalisation of the layer
+ * below needs (Section 4.1: that layer is convolution, instance normalisation, LeakyReLU, and a_in is its activated
+ * output, the input of this convolution): dx as mi3d_conv3d_dgrad, and with g = dx * lrelu'(a_in) (of the stored bf16
+ * values of dx) and xhat = a_in > 0 ? a_in : a_in / slope,
+ *   sums[n][c] = (mean over the voxels of g, mean over the voxels of g * xhat),
+ * which is what mi3d_instnorm_lrelu_bwd computes in a reduction pass of its own (same values up to the order of the
+ * fp32 partial sums; the order is fixed).  mi3d_instnorm_lrelu_bwd_sums then finishes the backward pass without that
+ * reduction.  sums: N * Cin * 2 floats, device; 0 < slope <= 1.  Only the unchunked bf16 3x3x3 stride-1 MFMA
+ * data-gradient kernels do this (mi3d_conv3d_dgrad_insums_supported tells, 1 / 0); other geometries return
+ * MI3D_ERR_UNSUPPORTED and the caller runs mi3d_conv3d_dgrad and mi3d_instnorm_lrelu_bwd.  Workspace as for
+ * mi3d_conv3d_dgrad; a_in must not overlap dx. */
+int mi3d_conv3d_dgrad_insums_supported(const mi3d_conv_desc *desc);
+int mi3d_conv3d_dgrad_insums(const mi3d_conv_desc *desc, const void *dy, const void *w, const void *a_in, float slope,
+                             void *dx, float *sums, void *ws, size_t ws_bytes, void *stream);
+
 /* Convolution followed by the network's LeakyReLU (Section 4.1) in one call:
  * y = lrelu(conv(x, w)), lrelu(v) = v > 0 ? v : slope * v, applied to the fp32
  * accumulator before the single rounding to bf16.  bf16 only, 0 <= slope < 1
@@ -259,13 +274,17 @@ int mi3d_dice_grad_f32(const float *logits, const uint8_t *labels, size_t voxels
  *   _lrelu_fwd  z <- a = lrelu((z - mean) * rstd), in place.
  *   _lrelu_bwd  da <- dz, in place, from the gradient da with respect to a, the activated tensor a itself (the
  *               normalised value is taken back from it: a positive slope makes LeakyReLU invertible) and stats:
- *               g = da * lrelu'(xhat), dz = rstd * (g - mean(g) - xhat * mean(g * xhat)).  0 < slope <= 1. */
+ *               g = da * lrelu'(xhat), dz = rstd * (g - mean(g) - xhat * mean(g * xhat)).  0 < slope <= 1.
+ *   _lrelu_bwd_sums  the same with the two means given (sums: N x C x 2 floats, device, (mean g, mean g xhat), as
+ *               mi3d_conv3d_dgrad_insums delivers them): the elementwise pass alone, no workspace. */
 size_t mi3d_instnorm_workspace_bytes(int N, int C);
 int mi3d_instnorm_stats(const void *z, int N, size_t voxels, int C, float eps, float *stats, void *ws, size_t ws_bytes,
                         void *stream);
 int mi3d_instnorm_lrelu_fwd(void *z, const float *stats, int N, size_t voxels, int C, float slope, void *stream);
 int mi3d_instnorm_lrelu_bwd(void *da, const void *a, const float *stats, int N, size_t voxels, int C, float slope,
                             void *ws, size_t ws_bytes, void *stream);
+int mi3d_instnorm_lrelu_bwd_sums(void *da, const void *a, const float *stats, const float *sums, int N, size_t voxels,
+                                 int C, float slope, void *stream);
 
 /* w[i] <- w[i] - lr * dw[i] on the fp32 master weights; w_bf16[i] <- the
  * updated value rounded to bf16 (the copy the bf16 convolutions read; NULL in

@@ -57,7 +57,8 @@ struct SpParams {
     const uint16_t* x2;
     uint16_t* y2;
     int xpitch, ypitch, xsplit, ysplit;
-    // STATS variant: per-(workgroup, segment, wave) sums of y and y^2 over the voxels, 32 couts each:
+    float stat_slope;       // STATS = 2: slope of the LeakyReLU whose derivative and inverse enter the sums
+    // STATS variants: per-(workgroup, segment, wave) sums of two quantities over the voxels, 32 couts each:
     // [logical workgroup][segment of its unit range][wave][sum, sum of squares][32 couts]
     float* stat_part;
     int* stat_key;          // [logical workgroup][segment]: sample * CT + cout tile of the partial, -1 = unused
@@ -208,18 +209,37 @@ __device__ __forceinline__ uint32_t scale_pair(uint32_t v, uint32_t m, float slo
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2));
 }
 
-template <bool MASK>
-__device__ __forceinline__ void store_row(const uint32_t (&o)[8], uint16_t* p, bool ok, uint16_t* dump, const uint4 (&m)[2], float slope) {
+// BSUM: the lane also adds, for each of its 16 consecutive couts, g = v * lrelu'(a) to s1 and g * xhat to s2, where v
+// is the stored bf16 value, a the value of m at the same place and xhat = a > 0 ? a : a / slope (the inverse of the
+// LeakyReLU); lanes with nothing to store add zeros.
+template <bool MASK, bool BSUM = false>
+__device__ __forceinline__ void store_row(const uint32_t (&o)[8], uint16_t* p, bool ok, uint16_t* dump, const uint4 (&m)[2], float slope,
+                                          float* s1 = nullptr, float* s2 = nullptr, float bslope = 1.f, bool sum = false) {
     typedef __attribute__((ext_vector_type(2))) unsigned u32x2;
     uint4 c[2];
 #pragma unroll
     for (int k = 0; k < 2; ++k) {  // k = 0: cout groups 0 and 2, k = 1: groups 1 and 3
         u32x2 s0 = __builtin_amdgcn_permlane32_swap(o[2 * k], o[2 * k + 4], false, false);
-        u32x2 s1 = __builtin_amdgcn_permlane32_swap(o[2 * k + 1], o[2 * k + 5], false, false);
-        c[k].x = s0[0]; c[k].y = s1[0]; c[k].z = s0[1]; c[k].w = s1[1];
+        u32x2 s1_ = __builtin_amdgcn_permlane32_swap(o[2 * k + 1], o[2 * k + 5], false, false);
+        c[k].x = s0[0]; c[k].y = s1_[0]; c[k].z = s0[1]; c[k].w = s1_[1];
         if (MASK) {
             c[k].x = scale_pair(c[k].x, m[k].x, slope); c[k].y = scale_pair(c[k].y, m[k].y, slope);
             c[k].z = scale_pair(c[k].z, m[k].z, slope); c[k].w = scale_pair(c[k].w, m[k].w, slope);
+        }
+    }
+    if (BSUM && sum) {   // (uniform)
+        const uint32_t cw[8] = {c[0].x, c[0].y, c[0].z, c[0].w, c[1].x, c[1].y, c[1].z, c[1].w};
+        const uint32_t mw[8] = {m[0].x, m[0].y, m[0].z, m[0].w, m[1].x, m[1].y, m[1].z, m[1].w};
+        const float inv = 1.f / bslope;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const uint32_t v = ok ? cw[i] : 0u, a = ok ? mw[i] : 0u;
+            const float vlo = __builtin_bit_cast(float, v << 16), vhi = __builtin_bit_cast(float, v & 0xffff0000u);
+            const float alo = __builtin_bit_cast(float, a << 16), ahi = __builtin_bit_cast(float, a & 0xffff0000u);
+            const float glo = alo > 0.f ? vlo : bslope * vlo, ghi = ahi > 0.f ? vhi : bslope * vhi;
+            const float xlo = alo > 0.f ? alo : alo * inv, xhi = ahi > 0.f ? ahi : ahi * inv;
+            s1[2 * i] += glo; s2[2 * i] = fmaf(glo, xlo, s2[2 * i]);
+            s1[2 * i + 1] += ghi; s2[2 * i + 1] = fmaf(ghi, xhi, s2[2 * i + 1]);
         }
     }
     // Unconditional stores: lanes outside the tensor (or with nothing pending) write to the dump area.
@@ -241,18 +261,22 @@ __device__ __forceinline__ void store_row(const uint32_t (&o)[8], uint16_t* p, b
 // PART (with NC = 1): the 32-channel chunks of Cin are separate work units whose weights (54 KB) stay resident; each
 // writes fp32 partial outputs and a second kernel adds the chunks in index order.  For the deep, small layers this is
 // two to three times faster than streaming the weights of all chunks through LDS for every staged plane.
-// STATS (forward, not with PART or MASK): the kernel also adds up y and y^2 per output channel (of the bf16 values it
+// STATS = 1 (forward, not with PART or MASK): the kernel also adds up y and y^2 per output channel (of the bf16 values it
 // stores) for the instance normalisation that follows the convolution (Section 4.1).  Every lane keeps the sums of its
 // 16 couts over the rows and planes of a segment; at the end of the segment they are added over the 32 voxel lanes in
 // a fixed butterfly and written as one partial per (workgroup, segment, wave).  A second kernel adds the partials of a
 // (sample, channel) in index order in double.
+// STATS = 2 (data gradient, not with PART or MASK): the same machinery adds up the two sums the backward pass of the
+// instance normalisation of the layer below needs: with a = P.ref (that layer's activated output), g = dx * lrelu'(a)
+// and xhat = lrelu^-1(a), the sums of g and of g * xhat per channel.  dx itself is stored unchanged.
 // MASK (data gradient, not with PART): every output element is multiplied by 1 where P.ref is > 0 and by P.slope
 // elsewhere (LeakyReLU derivative of the layer below) after its rounding to bf16 and rounded again: the bits of the
 // plain kernel followed by an elementwise pass, without that pass's read and write of the gradient.
-template <int NC, bool PART = false, bool MASK = false, bool STATS = false>
+template <int NC, bool PART = false, bool MASK = false, int STATS = 0>
 __global__ void __launch_bounds__(NT, NW / 4) sp_conv_kernel(SpParams P) {
     extern __shared__ __attribute__((aligned(16))) char lds[];
     constexpr bool STREAM = NC == 0;
+    constexpr bool REF = MASK || STATS == 2;   // the kernel reads P.ref at the store addresses
     constexpr int NBUF = NC == 2 ? 1 : 2;
     const int nc = STREAM ? P.Cin / 32 : NC;
     char* w_lds = lds;
@@ -403,10 +427,10 @@ __global__ void __launch_bounds__(NT, NW / 4) sp_conv_kernel(SpParams P) {
         bool st_pending = false;
         const int ow_ = w0 + (lane & 31);
         const long long row_pitch = (long long)P.Wo * opitch;
-        uint4 mk[MASK ? RH : 1][2];   // MASK: the pieces of ref at the addresses of the pending stores
-        const uint16_t* refn = MASK ? P.ref + (long long)n * P.Do * P.Ho * P.Wo * P.Cout : nullptr;
+        uint4 mk[REF ? RH : 1][2];   // the pieces of ref at the addresses of the pending stores
+        const uint16_t* refn = REF ? P.ref + (long long)n * P.Do * P.Ho * P.Wo * P.Cout : nullptr;
         auto load_mask = [&](int r) {     // unconditional, like the stores: masked lanes read the dump area
-            if constexpr (MASK) {
+            if constexpr (REF) {
                 const bool ok = st_pending && ow_ < P.Wo && h0 + wave * RH + r < P.Ho;
                 const uint16_t* q = ok ? refn + st_off + r * row_pitch + 16 * (lane >> 5) : P.dump + lane * 16;
                 mk[r][0] = *(const uint4*)q;
@@ -420,7 +444,7 @@ __global__ void __launch_bounds__(NT, NW / 4) sp_conv_kernel(SpParams P) {
         }
         auto store_piece = [&](int r) {
             const bool ok = st_pending && ow_ < P.Wo && h0 + wave * RH + r < P.Ho;
-            if (STATS && st_pending) {   // (uniform: stages with nothing to store skip the arithmetic)
+            if (STATS == 1 && st_pending) {   // (uniform: stages with nothing to store skip the arithmetic)
 #pragma unroll
                 for (int i = 0; i < 8; ++i) {
                     const uint32_t v = ok ? outp[r][i] : 0u;
@@ -430,7 +454,8 @@ __global__ void __launch_bounds__(NT, NW / 4) sp_conv_kernel(SpParams P) {
                 }
             }
             if constexpr (PART) store_row(outp[r], partn + st_off + r * row_pitch + 4 * (lane >> 5), ok, (float*)P.dump + lane * 32);
-            else store_row<MASK>(outp[r], yn + st_off + r * row_pitch + 16 * (lane >> 5), ok, P.dump + lane * 16, mk[MASK ? r : 0], P.slope);
+            else store_row<MASK, STATS == 2>(outp[r], yn + st_off + r * row_pitch + 16 * (lane >> 5), ok, P.dump + lane * 16, mk[REF ? r : 0], P.slope,
+                                             st1, st2, P.stat_slope, st_pending);
         };
 
         // every segment starts from cleared accumulators (keeps them dead across segments)
@@ -474,7 +499,7 @@ __global__ void __launch_bounds__(NT, NW / 4) sp_conv_kernel(SpParams P) {
                     _Pragma("unroll") for (int i_ = 0; i_ < NWL; ++i_) wreg[i_] = *(const u32x4*)(ws_ + (i_ < NWL - 1 ? t + NT * i_ : wlast) * 16); \
                 }                                                                               \
                 if (k < NLOAD) load_piece(k, NBUF == 2 ? ((sq + 1) & 1) : 0);                   \
-                if (MASK && k >= NLOAD - RH && k < NLOAD) load_mask(k - (NLOAD - RH));          \
+                if (REF && k >= NLOAD - RH && k < NLOAD) load_mask(k - (NLOAD - RH));           \
                 if (k < NLOAD) {}                                                               \
                 else if (k < NLOAD + RH) {                                                      \
                     store_piece(k - NLOAD);                                                     \
@@ -520,7 +545,8 @@ __global__ void __launch_bounds__(NT, NW / 4) sp_conv_kernel(SpParams P) {
         for (int r = 0; r < RH; ++r) store_piece(r);  // the last plane of the segment
         if constexpr (STATS) {
             // sums over the 32 voxel lanes of each lane half (fixed butterfly), then lane 0 of each half writes its 16
-            // couts: accumulator register j of half h is cout 8 (j / 4) + 4 h + j % 4 of the tile
+            // couts: accumulator register j of half h is cout 8 (j / 4) + 4 h + j % 4 of the tile (STATS = 1: sums taken
+            // before the exchange between the lane halves), cout 16 h + j after it (STATS = 2)
 #pragma unroll
             for (int i = 0; i < 16; ++i)
 #pragma unroll
@@ -533,7 +559,7 @@ __global__ void __launch_bounds__(NT, NW / 4) sp_conv_kernel(SpParams P) {
                 float* out = P.stat_part + (((long long)g * P.max_seg + seg) * NW + wave) * 64;
 #pragma unroll
                 for (int j = 0; j < 16; ++j) {
-                    const int c = 8 * (j >> 2) + 4 * (lane >> 5) + (j & 3);
+                    const int c = STATS == 1 ? 8 * (j >> 2) + 4 * (lane >> 5) + (j & 3) : 16 * (lane >> 5) + j;
                     out[c] = st1[j];
                     out[32 + c] = st2[j];
                 }
@@ -547,11 +573,12 @@ __global__ void __launch_bounds__(NT, NW / 4) sp_conv_kernel(SpParams P) {
     }
 }
 
-// stats[n][c] = (mean, 1 / sqrt(var + eps)) of y over the voxels from the partial sums of the STATS variant.  A block
+// stats[n][c] = (mean, 1 / sqrt(var + eps)) of y over the voxels from the partial sums of the STATS = 1 variant, or
+// (means = 1) the plain means of the two sums of the STATS = 2 variant.  A block
 // per (sample, cout tile); thread (slice s, sum q, cout c) adds the partials of every fourth workgroup in index order in
 // double (key: which (sample, cout tile) a partial belongs to), then the four slices are added in order.
 __global__ void __launch_bounds__(256) sp_stats_finish_kernel(const float* __restrict__ part, const int* __restrict__ key, int Cout, int CT,
-                                                              int nwg, int max_seg, double inv_v, float eps, float* __restrict__ stats) {
+                                                              int nwg, int max_seg, double inv_v, float eps, int means, float* __restrict__ stats) {
     __shared__ double red[4][64];
     const int t = threadIdx.x, sl = t >> 6, qc = t & 63;     // qc = 32 q + c
     const int mine = blockIdx.x;                             // n * CT + ct
@@ -572,7 +599,7 @@ __global__ void __launch_bounds__(256) sp_stats_finish_kernel(const float* __res
         if (var < 0.0) var = 0.0;
         const int n = mine / CT, c = (mine % CT) * 32 + t;
         stats[2 * ((long long)n * Cout + c)] = (float)mean;
-        stats[2 * ((long long)n * Cout + c) + 1] = (float)(1.0 / sqrt(var + (double)eps));
+        stats[2 * ((long long)n * Cout + c) + 1] = means ? (float)(s2 * inv_v) : (float)(1.0 / sqrt(var + (double)eps));
     }
 }
 
@@ -642,21 +669,25 @@ bool sp_fuses_dgrad_factor(const Geom& g) { return sp_supported(g, MI3D_PASS_DGR
 
 static size_t sp_part_offset(const Geom& g) { return (((size_t)g.w_elems() * 2 + 255) & ~(size_t)255) + 8192; }
 
-// STATS variant (forward, unchunked): workgroups, most segments of a workgroup's unit range, bytes of the partial sums
-static void sp_stat_layout(const Geom& g, long long* units, int* nwg, int* max_seg) {
-    *units = (long long)g.N * (g.Cout / 32) * ((g.Ho + TH - 1) / TH) * ((g.Wo + TW - 1) / TW) * g.Do;
+// STATS variants (unchunked): workgroups, most segments of a workgroup's unit range, bytes of the partial sums
+static void sp_stat_layout(const Geom& g, int pass, long long* units, int* nwg, int* max_seg) {
+    const bool flip = pass == MI3D_PASS_DGRAD;
+    const int cout = flip ? g.Cin : g.Cout, Do = flip ? g.D : g.Do, Ho = flip ? g.H : g.Ho, Wo = flip ? g.W : g.Wo;
+    *units = (long long)g.N * (cout / 32) * ((Ho + TH - 1) / TH) * ((Wo + TW - 1) / TW) * Do;
     long long n = sp_cu_count();
     if (n > *units) n = *units;
     *nwg = (int)n;
     const long long per_wg = (*units + n - 1) / n;
-    *max_seg = (int)((per_wg + g.Do - 1) / g.Do) + 1;
+    *max_seg = (int)((per_wg + Do - 1) / Do) + 1;
 }
-static size_t sp_stat_bytes(const Geom& g) {
+static size_t sp_stat_bytes(const Geom& g, int pass) {
     long long units; int nwg, max_seg;
-    sp_stat_layout(g, &units, &nwg, &max_seg);
+    sp_stat_layout(g, pass, &units, &nwg, &max_seg);
     return (size_t)nwg * max_seg * (NW * 64 * sizeof(float) + sizeof(int)) + 256;
 }
 bool sp_fuses_stats(const Geom& g) { return sp_supported(g, MI3D_PASS_FWD) && !sp_use_chunks(g, MI3D_PASS_FWD); }
+// the data gradient that also delivers the sums of the instance-normalisation backward pass of the layer below
+bool sp_fuses_bwd_sums(const Geom& g) { return sp_supported(g, MI3D_PASS_DGRAD) && !sp_use_chunks(g, MI3D_PASS_DGRAD); }
 
 size_t sp_workspace_bytes(const Geom& g, int pass) {
     if (!sp_supported(g, pass)) return 0;
@@ -665,8 +696,8 @@ size_t sp_workspace_bytes(const Geom& g, int pass) {
         const int cin = pass == MI3D_PASS_DGRAD ? g.Cout : g.Cin;
         const size_t out_elems = pass == MI3D_PASS_DGRAD ? (size_t)g.in_voxels() * g.Cin : (size_t)g.out_voxels() * g.Cout;
         b += (size_t)(cin / 32) * out_elems * sizeof(float);
-    } else if (pass == MI3D_PASS_FWD) {
-        b += sp_stat_bytes(g);   // partial sums of the STATS variant
+    } else {
+        b += sp_stat_bytes(g, pass);   // partial sums of the STATS variants
     }
     return b;
 }
@@ -705,9 +736,12 @@ int sp_conv(const Geom& g, int pass, const void* in, const void* w, void* out, v
     }
     const bool chunks = sp_use_chunks(g, pass);
     P.NCH = chunks ? P.Cin / 32 : 1;
-    const bool mask = pass == MI3D_PASS_DGRAD && g.ref && g.slope != 1.f && !chunks;
+    const bool bstat = pass == MI3D_PASS_DGRAD && g.stats;   // sums for the normalisation below; dx itself stays unmasked
+    if (bstat && (chunks || !g.ref || g.hi || !(g.slope > 0.f))) return MI3D_ERR_UNSUPPORTED;
+    const bool mask = pass == MI3D_PASS_DGRAD && g.ref && g.slope != 1.f && !chunks && !bstat;
     P.slope = (pass == MI3D_PASS_FWD || mask) ? g.slope : 1.f;
-    P.ref = mask ? (const uint16_t*)g.ref : nullptr;
+    P.ref = mask || bstat ? (const uint16_t*)g.ref : nullptr;
+    P.stat_slope = bstat ? g.slope : 1.f;
     P.units = (long long)P.N * P.CT * P.NCH * P.HT * P.WT * P.Do;
     long long nwg = sp_cu_count();
     if (nwg > P.units) nwg = P.units;
@@ -717,9 +751,9 @@ int sp_conv(const Geom& g, int pass, const void* in, const void* w, void* out, v
     P.stat_part = P.part;   // same place in the workspace as the chunked variant's partial outputs
     P.max_seg = 1;
     P.stat_key = nullptr;
-    if (stat) {
+    if (stat || bstat) {
         long long units; int n2;
-        sp_stat_layout(g, &units, &n2, &P.max_seg);
+        sp_stat_layout(g, pass, &units, &n2, &P.max_seg);
         P.stat_key = (int*)(P.stat_part + (size_t)n2 * P.max_seg * NW * 64);
     }
     const int nc = P.Cin / 32;
@@ -733,9 +767,12 @@ int sp_conv(const Geom& g, int pass, const void* in, const void* w, void* out, v
         if (e == hipSuccess) e = hipFuncSetAttribute((const void*)sp_conv_kernel<1, false, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds1);
         if (e == hipSuccess) e = hipFuncSetAttribute((const void*)sp_conv_kernel<2, false, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds2);
         if (e == hipSuccess) e = hipFuncSetAttribute((const void*)sp_conv_kernel<0, false, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds1);
-        if (e == hipSuccess) e = hipFuncSetAttribute((const void*)sp_conv_kernel<1, false, false, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds1);
-        if (e == hipSuccess) e = hipFuncSetAttribute((const void*)sp_conv_kernel<2, false, false, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds2);
-        if (e == hipSuccess) e = hipFuncSetAttribute((const void*)sp_conv_kernel<0, false, false, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds1);
+        if (e == hipSuccess) e = hipFuncSetAttribute((const void*)sp_conv_kernel<1, false, false, 1>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds1);
+        if (e == hipSuccess) e = hipFuncSetAttribute((const void*)sp_conv_kernel<2, false, false, 1>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds2);
+        if (e == hipSuccess) e = hipFuncSetAttribute((const void*)sp_conv_kernel<0, false, false, 1>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds1);
+        if (e == hipSuccess) e = hipFuncSetAttribute((const void*)sp_conv_kernel<1, false, false, 2>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds1);
+        if (e == hipSuccess) e = hipFuncSetAttribute((const void*)sp_conv_kernel<2, false, false, 2>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds2);
+        if (e == hipSuccess) e = hipFuncSetAttribute((const void*)sp_conv_kernel<0, false, false, 2>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds1);
         if (e != hipSuccess) { note_hip_error(e); return MI3D_ERR_HIP; }
         attr_set = true;
     }
@@ -750,14 +787,17 @@ int sp_conv(const Geom& g, int pass, const void* in, const void* w, void* out, v
                                                                 flip && g.hi ? (uint16_t*)g.hi : nullptr, P.Cout, nullptr);
         return check_launch();
     }
-    if (stat) {
-        if (nc == 1) sp_conv_kernel<1, false, false, true><<<(unsigned)nwg, NT, lds1, s>>>(P);
-        else if (nc == 2) sp_conv_kernel<2, false, false, true><<<(unsigned)nwg, NT, lds2, s>>>(P);
-        else sp_conv_kernel<0, false, false, true><<<(unsigned)nwg, NT, lds1, s>>>(P);
+    if (stat || bstat) {
+        if (stat && nc == 1) sp_conv_kernel<1, false, false, 1><<<(unsigned)nwg, NT, lds1, s>>>(P);
+        else if (stat && nc == 2) sp_conv_kernel<2, false, false, 1><<<(unsigned)nwg, NT, lds2, s>>>(P);
+        else if (stat) sp_conv_kernel<0, false, false, 1><<<(unsigned)nwg, NT, lds1, s>>>(P);
+        else if (nc == 1) sp_conv_kernel<1, false, false, 2><<<(unsigned)nwg, NT, lds1, s>>>(P);
+        else if (nc == 2) sp_conv_kernel<2, false, false, 2><<<(unsigned)nwg, NT, lds2, s>>>(P);
+        else sp_conv_kernel<0, false, false, 2><<<(unsigned)nwg, NT, lds1, s>>>(P);
         st = check_launch();
         if (st) return st;
         sp_stats_finish_kernel<<<P.N * P.CT, 256, 0, s>>>(P.stat_part, P.stat_key, P.Cout, P.CT, P.nwg, P.max_seg,
-                                                          1.0 / ((double)P.Do * P.Ho * P.Wo), g.stats_eps, g.stats);
+                                                          1.0 / ((double)P.Do * P.Ho * P.Wo), g.stats_eps, bstat ? 1 : 0, g.stats);
         return check_launch();
     }
     if (mask && nc == 1) sp_conv_kernel<1, false, true><<<(unsigned)nwg, NT, lds1, s>>>(P);

@@ -251,4 +251,12 @@ int mi3d_instnorm_lrelu_bwd(void* da, const void* a, const float* stats, int N, 
     return check_launch();
 }
 
+int mi3d_instnorm_lrelu_bwd_sums(void* da, const void* a, const float* stats, const float* sums, int N, size_t voxels, int C, float slope,
+                                 void* stream) {
+    if (!da || !a || !stats || !sums || !a16(da) || !a16(a) || !in_args_ok(N, voxels, C) || !(slope > 0.f && slope <= 1.f)) return MI3D_ERR_INVALID_ARG;
+    const long long pieces = (long long)voxels * (C / 8);
+    in_bwd_kernel<<<dim3(in_grid(pieces), N), 256, 0, (hipStream_t)stream>>>((uint4*)da, (const uint4*)a, stats, sums, pieces, C, slope);
+    return check_launch();
+}
+
 }  // extern "C"

@@ -33,7 +33,9 @@ struct Geom {
     // `slope` is applied (skip connection).  Set by the dispatcher only for kernels that implement it.
     const void* add = nullptr;
     // Optional statistics of the forward output for the instance normalisation that follows: stats[n][c] =
-    // (mean, 1 / sqrt(var + stats_eps)) over the voxels.  Set by the dispatcher only for kernels that implement it.
+    // (mean, 1 / sqrt(var + stats_eps)) over the voxels.  In a data-gradient pass: the two means the backward pass of
+    // the instance normalisation of the layer below needs, (mean g, mean g xhat) with g = dx lrelu'(ref) and
+    // xhat = lrelu^-1(ref) (slope = the LeakyReLU's).  Set by the dispatcher only for kernels that implement it.
     float* stats = nullptr;
     float stats_eps = 0.f;
     __host__ __device__ long long in_voxels() const { return (long long)N * D * H * W; }
@@ -86,6 +88,7 @@ size_t sp_workspace_bytes(const Geom& g, int pass);
 int sp_conv(const Geom& g, int pass, const void* in, const void* w, void* out, void* ws, size_t ws_bytes, hipStream_t s);
 bool sp_fuses_dgrad_factor(const Geom& g);  // the forward LeakyReLU is always fused
 bool sp_fuses_stats(const Geom& g);         // instance-normalisation statistics of the forward output
+bool sp_fuses_bwd_sums(const Geom& g);      // sums of the instance-normalisation backward pass from the data gradient
 
 
 // MFMA weight gradient: bf16, 3x3x3, stride 1, channels in multiples of 32

@@ -115,6 +115,13 @@ def instnorm_lrelu_fwd(z, stats, slope=0.01):
     check(lib().mi3d_instnorm_lrelu_fwd(_p(z), _p(stats), N, z.numel() // (N * C), C, slope, _stream()), "instnorm_lrelu_fwd")
 
 
+def instnorm_lrelu_bwd_sums(da, a, stats, sums, slope=0.01):
+    """da <- dz given the two means (mean g, mean g * xhat) per (sample, channel)."""
+    N, C = a.shape[0], a.shape[-1]
+    assert da.numel() == a.numel() and tuple(sums.shape) == (N, C, 2) and sums.dtype == torch.float32
+    check(lib().mi3d_instnorm_lrelu_bwd_sums(_p(da), _p(a), _p(stats), _p(sums), N, a.numel() // (N * C), C, slope, _stream()), "instnorm_lrelu_bwd_sums")
+
+
 def instnorm_lrelu_bwd(da, a, stats, ws, slope=0.01):
     N, C = a.shape[0], a.shape[-1]
     assert da.numel() == a.numel()

@@ -47,7 +47,7 @@ class _Saved:
 class UNetStep:
     def __init__(self, N, vol, channels, weights, x, labels, lr=1e-2, in_ch=4, classes=3, swap=True,
                  budget_bytes=None, lookahead=2, policy=sw.POLICY_BUDGET, n_tensors=-1, exclude_tags=0,
-                 eviction=sw.EVICT_SWAP, optimizer="sgd", norm=False, virtual_cat=True, fused_stats=True, dtype=torch.bfloat16):
+                 eviction=sw.EVICT_SWAP, optimizer="sgd", norm=False, virtual_cat=True, fused_stats=True, fused_bwd_sums=True, dtype=torch.bfloat16):
         """weights: list of float32 CPU tensors/arrays (bf16-exact start values) in the order enc convs,
         (dec up, conv1, conv2) from the deepest decoder level up, head; x: CUDA [N,vol,vol,vol,in_ch] of `dtype`;
         labels: uint8 CUDA [N,vol,vol,vol,classes].  dtype: torch.bfloat16 (bf16 activations and working weights, fp32
@@ -160,8 +160,15 @@ class UNetStep:
         for f, op in enumerate(self.ops):
             if op["kind"] == "conv":
                 prev = self.ops[f - 1]
-                op["through_act"] = (not self.norm and prev["kind"] == "conv" and prev["out"] is op["src"]
-                                     and op["src"].id not in skip_ids)
+                alone = prev["kind"] == "conv" and prev["out"] is op["src"] and op["src"].id not in skip_ids
+                op["through_act"] = not self.norm and alone
+                # with the normalisation in between, the data gradient can still take the two sums of that
+                # normalisation's backward pass on its way out
+                # (taken where it pays: with 32 contracted channels the kernel has registers to spare and the tensors
+                # are the large ones, 1.78 -> 1.52 ms for data gradient + backward pass at 192^3, N = 2; the variants for
+                # more channels spill and the reduction they save runs from the caches: 0.57 -> 0.58 ms at 96^3)
+                op["through_norm"] = bool(self.norm and alone and fused_bwd_sums and op["desc"].Cout == 32
+                                          and mc.dgrad_insums_supported(op["desc"]))
         # backward readers: conv f reads its input (weight gradient; LeakyReLU derivative of the layer below where the
         # data gradient applies it) and, unless the layer above has applied it already, its output (LeakyReLU
         # derivative); up and head read their input (weight gradient); the loss reads the logits
@@ -196,6 +203,7 @@ class UNetStep:
             for op in self.ops:
                 if op["kind"] == "conv":
                     op["stats"] = torch.zeros((N, op["out"].shape[-1], 2), dtype=torch.float32, device="cuda")
+                    op["bwd_sums"] = torch.zeros((N, op["out"].shape[-1], 2), dtype=torch.float32, device="cuda")
                     op["fused_stats"] = fused_stats and mc.fwd_stats_supported(op["desc"])
         self.sums = torch.zeros(3 * classes, dtype=torch.float32, device="cuda")
         self.loss = torch.zeros(1, dtype=torch.float32, device="cuda")
@@ -435,6 +443,7 @@ class UNetStep:
         # backward
         da = None              # gradient with respect to the output of the op being walked back
         premasked = False      # da already carries the LeakyReLU derivative of the op being walked back
+        have_sums = False      # the sums of the normalisation's backward pass came with da (op["bwd_sums"])
         dskip = {}
         d_pair = None          # skip half of the gradient of a virtual concatenation, between its convolution and its cat op
         for f in range(self.n_fwd - 1, -1, -1):
@@ -459,11 +468,14 @@ class UNetStep:
                     premasked = True
                 da = nxt
             elif k == "conv":
-                if self.norm:      # through the LeakyReLU and the normalisation, in place
+                if self.norm and have_sums:
+                    glue.instnorm_lrelu_bwd_sums(da, self._need(op["out"]), op["stats"], op["bwd_sums"], SLOPE)
+                elif self.norm:    # through the LeakyReLU and the normalisation, in place
                     glue.instnorm_lrelu_bwd(da, self._need(op["out"]), op["stats"], self.in_ws, SLOPE)
                 elif not premasked:
                     glue.leaky_relu_bwd(da, self._need(op["out"]), SLOPE)
                 premasked = False
+                have_sums = False
                 if trace is not None:
                     trace[op["name"] + ".dz"] = da.clone()
                 din_trace = None
@@ -488,6 +500,12 @@ class UNetStep:
                         # the data gradient applies that LeakyReLU's derivative as well
                         mc.conv3d_dgrad_lrelu(op["desc"], da, self.w[op["w"]], self._need(op["src"]), SLOPE, nxt, self.ws)
                         premasked = True
+                    elif op["through_norm"]:
+                        # the same situation with a normalisation in between: the data gradient also adds up what
+                        # that normalisation's backward pass needs
+                        mc.conv3d_dgrad_insums(op["desc"], da, self.w[op["w"]], self._need(op["src"]), SLOPE,
+                                               self.ops[f - 1]["bwd_sums"], nxt, self.ws)
+                        have_sums = True
                     elif op["src"].id in dskip and dskip[op["src"].id][1] == 0 and (trace is None or getattr(trace, "keep_fused", False) or self.dtype == torch.float32):
                         # the input is also a skip connection whose second gradient is a tensor of its own: the
                         # data gradient adds it and applies the derivative of the producing layer in the same call

@@ -2,7 +2,8 @@
 conv3d_wgrad_pair): the decoder's first convolution of a level reads [up-sampled | skip] as two tensors.  The oracle
 side concatenates with numpy and runs the plain fp64 passes; the plain GPU calls on the materialised concatenation
 must give the same bits.  Also here: conv3d_fwd_stats, the forward pass that hands out the instance-normalisation
-statistics of its output (plain and two-tensor input)."""
+statistics of its output (plain and two-tensor input), and conv3d_dgrad_insums, the data gradient that hands out the
+two means of the instance-normalisation backward pass of the layer below."""
 import ctypes
 
 import numpy as np
@@ -148,3 +149,78 @@ def test_forward_statistics_are_refused_where_the_kernel_cannot_produce_them(dev
         w = torch.zeros((Cout, k, k, k, Cin), dtype=bf, device="cuda")
         with pytest.raises(Mi3dError):
             mc.conv3d_fwd_stats(d, x, w, torch.zeros((N, Cout, 2), device="cuda"))
+
+
+BSUM_CASES = [
+    # N, D, H, W, Cin, Cout, pad
+    (2, 6, 20, 40, 32, 32, 1),     # one chunk; two samples
+    (1, 9, 17, 33, 64, 32, 1),     # one chunk contracted, two tiles of output channels, ragged patches
+    (2, 5, 18, 34, 64, 64, 1),     # two resident chunks
+    (2, 33, 33, 66, 32, 128, 1),   # streamed weights (enough units to stay unchunked)
+    (3, 4, 9, 70, 96, 64, 2),      # three samples, pad 2, three tiles of output channels
+]
+
+
+@pytest.mark.parametrize("case", BSUM_CASES)
+def test_data_gradient_with_the_sums_of_the_normalisation_backward_pass(device, case):
+    from oracle import unet as ou
+    from paper_1812_07816_amd import glue
+    N, D, H, W, Cin, Cout, p = case
+    seed = 10 * BSUM_CASES.index(case)
+    x, w, dy = si.conv_case(99, seed, N, D, H, W, Cin, Cout, 3, 1, p, True)
+    # x doubles as the activated output of the layer below (mixed signs); channels of different spread
+    a = si.bf16_round((x * np.linspace(0.2, 3.0, Cin)).astype(np.float32))
+    desc = mc.make_desc(N, D, H, W, Cin, Cout, 3, 1, p, torch.bfloat16)
+    assert mc.dgrad_insums_supported(desc)
+    ad, wd, dyd = parity.to_device(a, True), parity.to_device(w, True), parity.to_device(dy, True)
+    sums = torch.full((N, Cin, 2), 7.0, device="cuda")
+    dx = mc.conv3d_dgrad_insums(desc, dyd, wd, ad, ou.SLOPE, sums)
+    assert torch.equal(dx, mc.conv3d_dgrad(desc, dyd, wd))        # the data gradient itself is unchanged
+    again = torch.zeros_like(sums)
+    mc.conv3d_dgrad_insums(desc, dyd, wd, ad, ou.SLOPE, again)
+    assert torch.equal(sums, again)                               # fixed summation order
+    # the oracle's means of the same stored values (fp64)
+    dxh = parity.to_host(dx).astype(np.float64)
+    xhat = ou.lrelu_inverse(a.astype(np.float64))
+    g = np.where(xhat > 0, dxh, ou.SLOPE * dxh)
+    m1, m2 = g.mean(axis=(1, 2, 3)), (g * xhat).mean(axis=(1, 2, 3))
+    got = sums.cpu().numpy().astype(np.float64)
+    # a mean is as good as its size against the spread of what is averaged
+    s1, s2 = g.std(axis=(1, 2, 3)), (g * xhat).std(axis=(1, 2, 3))
+    e1, e2 = (np.abs(got[..., 0] - m1) / s1).max(), (np.abs(got[..., 1] - m2) / s2).max()
+    print(case, f"mean g {e1:.2e} mean g xhat {e2:.2e}", flush=True)
+    assert e1 <= 1e-6 and e2 <= 1e-6
+    # the backward pass finished from these means against the one that takes its sums in a pass of its own
+    stats = torch.zeros((N, Cin, 2), device="cuda")
+    zst = torch.from_numpy(np.stack([np.zeros((N, Cin)), np.linspace(0.5, 2.0, Cin)[None].repeat(N, 0)], axis=-1).astype(np.float32)).cuda()
+    stats.copy_(zst)
+    d1, d2 = dx.clone(), dx.clone()
+    glue.instnorm_lrelu_bwd_sums(d1, ad, stats, sums)
+    glue.instnorm_lrelu_bwd(d2, ad, stats, glue.instnorm_workspace(N, Cin))
+    ref = ou.instnorm_lrelu_bwd(xhat, zst[..., 1].cpu().numpy().astype(np.float64), dxh)
+    e_f = np.max(np.abs(parity.to_host(d1) - ref), axis=(0, 1, 2, 3)) / np.max(np.abs(ref), axis=(0, 1, 2, 3))
+    e_s = np.max(np.abs(parity.to_host(d2) - ref), axis=(0, 1, 2, 3)) / np.max(np.abs(ref), axis=(0, 1, 2, 3))
+    print(case, f"dz: with the kernel's means {e_f.max():.2e}, with a pass of its own {e_s.max():.2e}", flush=True)
+    assert e_f.max() <= 1e-2 and e_s.max() <= 1e-2
+
+
+def test_backward_sums_are_refused_where_the_kernel_cannot_produce_them(device):
+    bf = torch.bfloat16
+    for args in ((1, 12, 12, 12, 320, 320, 3, 1, 1),   # chunked variant
+                 (1, 8, 8, 8, 32, 64, 3, 2, 1),        # stride 2
+                 (1, 8, 8, 8, 4, 32, 3, 1, 1)):        # first layer
+        d = mc.make_desc(*args, bf)
+        assert not mc.dgrad_insums_supported(d), args
+        N, D, H, W, Cin, Cout, k, s_ = args[:8]
+        Do = (D + 2 - k) // s_ + 1
+        dy = torch.zeros((N, Do, Do, Do, Cout), dtype=bf, device="cuda")
+        w = torch.zeros((Cout, k, k, k, Cin), dtype=bf, device="cuda")
+        a = torch.zeros((N, D, H, W, Cin), dtype=bf, device="cuda")
+        with pytest.raises(Mi3dError):
+            mc.conv3d_dgrad_insums(d, dy, w, a, 0.01, torch.zeros((N, Cin, 2), device="cuda"))
+    d = mc.make_desc(1, 8, 16, 32, 32, 32, 3, 1, 1, bf)
+    t = torch.zeros((1, 8, 16, 32, 32), dtype=bf, device="cuda")
+    w = torch.zeros((32, 3, 3, 3, 32), dtype=bf, device="cuda")
+    for bad in (0.0, 1.5, -0.1):                        # the inverse of the activation needs a positive slope
+        with pytest.raises(Mi3dError):
+            mc.conv3d_dgrad_insums(d, t, w, t.clone(), bad, torch.zeros((1, 32, 2), device="cuda"))

@@ -432,6 +432,33 @@ def test_every_op_with_instance_normalisation_matches_oracle(unet, N, vol, chann
     print(f"worst op error {worst[0]:.2e} ({worst[1]})")
 
 
+def test_backward_sums_from_the_data_gradient_give_the_step_of_the_separate_reductions(unet):
+    """The data gradients that also deliver the sums of the normalisation's backward pass against the step that takes
+    them in reduction passes of its own: same sums up to the order of fp32 additions, so the weight gradients agree to
+    bf16 rounding noise (not bit for bit: a sum that differs in its last bits rounds a few stored values the other
+    way, and the layers below inherit that)."""
+    N, vol = 2, 32
+    x, labels, ws, xd, ld = _inputs(N, vol, CH, 5)
+    a = unet.UNetStep(N, vol, CH, ws, xd, ld, swap=False, norm=True)
+    b = unet.UNetStep(N, vol, CH, ws, xd, ld, swap=False, norm=True, fused_bwd_sums=False)
+    assert sum(1 for op in a.ops if op.get("through_norm")) == 2 and not any(op.get("through_norm") for op in b.ops)
+    a.run(update=False); b.run(update=False)
+    torch.cuda.synchronize()
+    assert torch.equal(a.loss, b.loss)
+    worst = {}
+    for (name, _), ga, gb in zip(si.unet_weight_shapes(CH), a.dw, b.dw):
+        ga, gb = _h(ga), _h(gb)
+        e = np.max(np.abs(ga - gb)) / np.max(np.abs(gb))
+        l2 = np.sqrt(np.sum((ga - gb) ** 2) / np.sum(gb * gb))
+        print(f"{name}: max {e:.1e}, l2 {l2:.1e}")
+        worst[name] = max(e, l2)
+    # Layers whose gradients are formed before the first such data gradient see the same bits.  From there on a
+    # stored bf16 value that rounds the other way is a relative step of 2^-8, and every layer further down the
+    # backward pass inherits the noise of those above it: the first layer's gradient (formed last) the most.
+    assert worst["head"] == 0.0 and worst["dec0.conv2"] == 0.0
+    assert max(worst.values()) <= 3e-2, worst
+
+
 def test_normalised_step_end_to_end_and_under_eviction(unet):
     from paper_1812_07816_amd import swap as sw
     N, vol = 2, 32
