@@ -103,9 +103,26 @@ def cpu_baseline(seconds_target=15.0):
             model = next((ln.split(":", 1)[1].strip() for ln in f if ln.startswith("model name")), model)
     except OSError:
         pass
+    # full passes of the two small configurations (fp32 16^3 4->8; 128^3 4->32), timed as they are; the larger ones
+    # are extrapolated from the sample's rate by their FLOP counts and labelled so
+    def full(vol, cin, cout, bf16):
+        x, w, dy = si.conv_case(1, 0, 1, vol, vol, vol, cin, cout, 3, 1, 1, bf16)
+        g = oc.shape(1, vol, vol, vol, cin, cout, 3, 1, 1)
+        x, w, dy = (a.astype(np.float64) for a in (x, w, dy))
+        t0 = time.perf_counter()
+        oc.fwd(g, x, w); oc.dgrad(g, dy, w); oc.wgrad(g, x, dy)
+        return time.perf_counter() - t0
+    rate = fl / dt
+    per_config = {
+        "config1_16^3_4->8_fwd+dgrad+wgrad_s": full(16, 4, 8, False),
+        "config2a_128^3_4->32_fwd+dgrad+wgrad_s": full(128, 4, 32, True),
+        "extrapolated_from_the_sample_rate_s": {
+            "config2b_128^3_32->32": 3 * 2.0 * 128 ** 3 * 27 * 32 * 32 / rate,
+            "config3b_192^3_32->32": 3 * 2.0 * 192 ** 3 * 27 * 32 * 32 / rate,
+            "config5_whole_step_conv_work": 19.264454e12 / rate}}
     return {"value": fl / dt / 1e12, "unit": "TFLOP/s", "cores": min(threads, cores), "cpu_model": model, "kind": "oracle",
             "sample": f"fp64 direct-loop fwd+dgrad+wgrad of one 32->32 3x3x3 layer on a {vol}^3 sub-volume of the "
-                      f"workload ({dt:.1f} s)", "seconds": dt}
+                      f"workload ({dt:.1f} s)", "seconds": dt, "per_config": per_config}
 
 
 def unet_layer_table(N):

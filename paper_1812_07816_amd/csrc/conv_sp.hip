@@ -574,16 +574,17 @@ __global__ void __launch_bounds__(NT, NW / 4) sp_conv_kernel(SpParams P) {
 }
 
 // stats[n][c] = (mean, 1 / sqrt(var + eps)) of y over the voxels from the partial sums of the STATS = 1 variant, or
-// (means = 1) the plain means of the two sums of the STATS = 2 variant.  A block
-// per (sample, cout tile); thread (slice s, sum q, cout c) adds the partials of every fourth workgroup in index order in
-// double (key: which (sample, cout tile) a partial belongs to), then the four slices are added in order.
-__global__ void __launch_bounds__(256) sp_stats_finish_kernel(const float* __restrict__ part, const int* __restrict__ key, int Cout, int CT,
-                                                              int nwg, int max_seg, double inv_v, float eps, int means, float* __restrict__ stats) {
-    __shared__ double red[4][64];
+// (means = 1) the plain means of the two sums of the STATS = 2 variant.  A block of 1024 threads per (sample, cout
+// tile); thread (slice s of 16, sum q, cout c) adds the partials of every sixteenth workgroup in index order in double
+// (key: which (sample, cout tile) a partial belongs to), then the sixteen slices are added in order.
+constexpr int FIN_SLICES = 16;
+__global__ void __launch_bounds__(64 * FIN_SLICES) sp_stats_finish_kernel(const float* __restrict__ part, const int* __restrict__ key, int Cout, int CT,
+                                                                          int nwg, int max_seg, double inv_v, float eps, int means, float* __restrict__ stats) {
+    __shared__ double red[FIN_SLICES][64];
     const int t = threadIdx.x, sl = t >> 6, qc = t & 63;     // qc = 32 q + c
     const int mine = blockIdx.x;                             // n * CT + ct
     double a = 0.0;
-    for (int g = sl; g < nwg; g += 4)
+    for (int g = sl; g < nwg; g += FIN_SLICES)
         for (int seg = 0; seg < max_seg; ++seg)
             if (key[g * max_seg + seg] == mine) {
                 const float* p = part + (((long long)g * max_seg + seg) * NW) * 64;
@@ -592,8 +593,8 @@ __global__ void __launch_bounds__(256) sp_stats_finish_kernel(const float* __res
     red[sl][qc] = a;
     __syncthreads();
     if (t < 32) {
-        const double s1 = ((red[0][t] + red[1][t]) + red[2][t]) + red[3][t];
-        const double s2 = ((red[0][32 + t] + red[1][32 + t]) + red[2][32 + t]) + red[3][32 + t];
+        double s1 = 0.0, s2 = 0.0;
+        for (int k = 0; k < FIN_SLICES; ++k) { s1 += red[k][t]; s2 += red[k][32 + t]; }
         const double mean = s1 * inv_v;
         double var = s2 * inv_v - mean * mean;
         if (var < 0.0) var = 0.0;
@@ -796,7 +797,7 @@ int sp_conv(const Geom& g, int pass, const void* in, const void* w, void* out, v
         else sp_conv_kernel<0, false, false, 2><<<(unsigned)nwg, NT, lds1, s>>>(P);
         st = check_launch();
         if (st) return st;
-        sp_stats_finish_kernel<<<P.N * P.CT, 256, 0, s>>>(P.stat_part, P.stat_key, P.Cout, P.CT, P.nwg, P.max_seg,
+        sp_stats_finish_kernel<<<P.N * P.CT, 64 * FIN_SLICES, 0, s>>>(P.stat_part, P.stat_key, P.Cout, P.CT, P.nwg, P.max_seg,
                                                           1.0 / ((double)P.Do * P.Ho * P.Wo), g.stats_eps, bstat ? 1 : 0, g.stats);
         return check_launch();
     }
