@@ -339,6 +339,7 @@ class CallRecorder:
     current stream) by wrapping the binding's entry points while it is active; the product code is untouched."""
     NAMES = {"conv3d_fwd": 0, "conv3d_fwd_lrelu": 0, "conv3d_fwd_pair": 0, "conv3d_fwd_stats": 0, "conv3d_fwd_view": 0,
              "conv3d_dgrad": 1, "conv3d_dgrad_lrelu": 1, "conv3d_dgrad_pair": 1, "conv3d_dgrad_skip": 1, "conv3d_dgrad_view": 1,
+             "conv3d_dgrad_insums": 1,
              "conv3d_wgrad": 2, "conv3d_wgrad_pair": 2, "conv3d_wgrad_view": 2}
 
     def __init__(self, mc):
@@ -351,7 +352,7 @@ class CallRecorder:
             self.saved[name] = fn
 
             # tensors of dx's shape a fused data-gradient call reads besides dy and w (they are part of its work)
-            extra = {"conv3d_dgrad_lrelu": 1, "conv3d_dgrad_skip": 2}.get(name, 0)
+            extra = {"conv3d_dgrad_lrelu": 1, "conv3d_dgrad_skip": 2, "conv3d_dgrad_insums": 1}.get(name, 0)
 
             def wrapped(desc, *a, _fn=fn, _pass=pass_, _extra=extra, **kw):
                 e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)

@@ -398,6 +398,9 @@ int dgrad_s2(const Geom& g, const void* dy, const void* w, void* dx, void* ws, s
     G.dump = (uint16_t*)((char*)ws + (((size_t)g.w_elems() * 2 + 255) & ~(size_t)255));
     G.part = (float*)((char*)ws + dg2_part_offset(g));
     G.add = (const uint16_t*)g.add; G.ref = (const uint16_t*)g.ref; G.slope = g.slope;
+    // a factor of 1 on both sides of the sign test needs no sign: the store path then reads the added tensor a second
+    // time (from the cache) instead of streaming a third tensor of dx's size from memory
+    if (g.add && g.slope == 1.f) G.ref = G.add;
     G.N = g.N; G.D = g.D; G.H = g.H; G.W = g.W; G.Cin = g.Cin; G.Cout = g.Cout;
     G.Do = g.Do; G.Ho = g.Ho; G.Wo = g.Wo; G.p = g.pD;
     G.QD = (g.D + 1) / 2;

@@ -2,8 +2,8 @@
 // 32 -> 3 classes).  All three passes are bound by streaming the 32-channel
 // tensor once (3 flop/byte), so they are plain vector-ALU kernels built around
 // 16-byte loads and stores:
-//   fwd    y[v,co]  = sum_ci x[v,ci] w[co,ci]      one thread per voxel
-//   dgrad  dx[v,ci] = sum_co dy[v,co] w[co,ci]     one thread per 8 input channels of a voxel
+//   fwd    y[v,co]  = sum_ci x[v,ci] w[co,ci]      a thread per 8 input channels of a voxel, lanes of a voxel summed
+//   dgrad  dx[v,ci] = sum_co dy[v,co] w[co,ci]     a thread per 8 input channels of a voxel, grid-stride
 //   wgrad  dw[co,ci]= sum_v dy[v,co] x[v,ci]       per-thread partial sums over a strided voxel range,
 //                                                  block tree reduction, slots added in fixed order
 // Supported: k = 1, s = 1, p = 0, Cin % 8 == 0, Cin <= 64, Cout <= 4, bf16.
@@ -23,29 +23,51 @@ __device__ __forceinline__ void unpack8(const uint4& v, float (&f)[8]) {
     }
 }
 
+// Thread t of the grid handles the 16-byte pieces t, t + T, ... of x (8 input channels of one voxel), four at a time;
+// the Cin / 8 neighbouring lanes that share a voxel add their partial sums in a fixed butterfly and the first of
+// them stores the voxel's outputs.
 template <int CO>
 __global__ void __launch_bounds__(256) pw_fwd_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ w,
                                                      uint16_t* __restrict__ y, long long voxels, int Cin) {
     __shared__ float ws[MAXCO * MAXCI];
     for (int i = threadIdx.x; i < CO * Cin; i += 256) ws[i] = bf16_to_f32(w[i]);
     __syncthreads();
-    const long long v = (long long)blockIdx.x * 256 + threadIdx.x;
-    if (v >= voxels) return;
-    float acc[CO];
+    const int per = Cin / 8;                      // a power of two that divides 64: a voxel never straddles waves
+    const long long pieces = voxels * per, T = (long long)gridDim.x * 256;
+    const int c0 = (threadIdx.x % per) * 8;       // T is a multiple of per: the same channels in every round
+    constexpr int U = 4;
+    for (long long i0 = (long long)blockIdx.x * 256 + threadIdx.x; i0 < pieces; i0 += U * T) {   // (uniform over the lanes of a voxel)
+        uint4 xv[U];
 #pragma unroll
-    for (int co = 0; co < CO; ++co) acc[co] = 0.f;
-    for (int c8 = 0; c8 < Cin / 8; ++c8) {
-        float f[8];
-        unpack8(*(const uint4*)(x + v * Cin + c8 * 8), f);
+        for (int u = 0; u < U; ++u) {
+            const long long i = i0 + u * T;
+            xv[u] = *(const uint4*)(x + (i < pieces ? i : pieces - 1) * 8);   // clamped: loaded, never stored
+        }
 #pragma unroll
-        for (int co = 0; co < CO; ++co)
+        for (int u = 0; u < U; ++u) {
+            const long long i = i0 + u * T;
+            float f[8], acc[CO];
+            unpack8(xv[u], f);
 #pragma unroll
-            for (int j = 0; j < 8; ++j) acc[co] = fmaf(f[j], ws[co * Cin + c8 * 8 + j], acc[co]);
+            for (int co = 0; co < CO; ++co) {
+                acc[co] = 0.f;
+#pragma unroll
+                for (int j = 0; j < 8; ++j) acc[co] = fmaf(f[j], ws[co * Cin + c0 + j], acc[co]);
+            }
+            for (int off = per >> 1; off > 0; off >>= 1)
+#pragma unroll
+                for (int co = 0; co < CO; ++co) acc[co] += __shfl_xor(acc[co], off, 64);
+            if (c0 == 0 && i < pieces) {
+                const long long v = i / per;
+#pragma unroll
+                for (int co = 0; co < CO; ++co) y[v * CO + co] = f32_to_bf16_rne(acc[co]);
+            }
+        }
     }
-#pragma unroll
-    for (int co = 0; co < CO; ++co) y[v * CO + co] = f32_to_bf16_rne(acc[co]);
 }
 
+// Thread t of the grid handles the 16-byte pieces t, t + T, t + 2 T, ... of dx (T = threads in the grid), four at a time
+// so that their loads are in flight together; a piece is 8 input channels of one voxel.
 template <int CO>
 __global__ void __launch_bounds__(256) pw_dgrad_kernel(const uint16_t* __restrict__ dy, const uint16_t* __restrict__ w,
                                                        uint16_t* __restrict__ dx, long long voxels, int Cin,
@@ -54,31 +76,44 @@ __global__ void __launch_bounds__(256) pw_dgrad_kernel(const uint16_t* __restric
     for (int i = threadIdx.x; i < CO * Cin; i += 256) ws[i] = bf16_to_f32(w[i]);
     __syncthreads();
     const int per = Cin / 8;
-    const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
-    if (idx >= voxels * per) return;
-    const long long v = idx / per;
-    const int c0 = (int)(idx % per) * 8;
-    float g[CO];
+    const long long pieces = voxels * per, T = (long long)gridDim.x * 256;
+    constexpr int U = 4;
+    for (long long i0 = (long long)blockIdx.x * 256 + threadIdx.x; i0 < pieces; i0 += U * T) {
+        float g[U][CO];
+        uint4 m4[U];
+        long long idx[U];
 #pragma unroll
-    for (int co = 0; co < CO; ++co) g[co] = bf16_to_f32(dy[v * CO + co]);
-    // optional LeakyReLU derivative of the layer below: factor 1 where its activated output ref is > 0, slope elsewhere
-    uint4 m4 = uint4{0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};
-    if (ref) m4 = *(const uint4*)(ref + v * Cin + c0);
-    const uint32_t m[4] = {m4.x, m4.y, m4.z, m4.w};
-    uint32_t o[4];
+        for (int u = 0; u < U; ++u) {
+            idx[u] = i0 + u * T;
+            const long long ic = idx[u] < pieces ? idx[u] : pieces - 1;   // clamped: loaded, never stored
+            const long long v = ic / per;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        float a = 0.f, b = 0.f;
-#pragma unroll
-        for (int co = 0; co < CO; ++co) {
-            a = fmaf(g[co], ws[co * Cin + c0 + 2 * j], a);
-            b = fmaf(g[co], ws[co * Cin + c0 + 2 * j + 1], b);
+            for (int co = 0; co < CO; ++co) g[u][co] = bf16_to_f32(dy[v * CO + co]);
+            // optional LeakyReLU derivative of the layer below: factor 1 where its activated output ref is > 0, slope elsewhere
+            m4[u] = uint4{0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};
+            if (ref) m4[u] = *(const uint4*)(ref + ic * 8);
         }
-        if (!((int)(m[j] << 16) > 0)) a *= slope;
-        if (!((int)(m[j] & 0xffff0000u) > 0)) b *= slope;
-        o[j] = (uint32_t)f32_to_bf16_rne(a) | ((uint32_t)f32_to_bf16_rne(b) << 16);
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            if (idx[u] >= pieces) continue;
+            const int c0 = (int)(idx[u] % per) * 8;
+            const uint32_t m[4] = {m4[u].x, m4[u].y, m4[u].z, m4[u].w};
+            uint32_t o[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                float a = 0.f, b = 0.f;
+#pragma unroll
+                for (int co = 0; co < CO; ++co) {
+                    a = fmaf(g[u][co], ws[co * Cin + c0 + 2 * j], a);
+                    b = fmaf(g[u][co], ws[co * Cin + c0 + 2 * j + 1], b);
+                }
+                if (!((int)(m[j] << 16) > 0)) a *= slope;
+                if (!((int)(m[j] & 0xffff0000u) > 0)) b *= slope;
+                o[j] = (uint32_t)f32_to_bf16_rne(a) | ((uint32_t)f32_to_bf16_rne(b) << 16);
+            }
+            *(uint4*)(dx + idx[u] * 8) = uint4{o[0], o[1], o[2], o[3]};
+        }
     }
-    *(uint4*)(dx + v * Cin + c0) = uint4{o[0], o[1], o[2], o[3]};
 }
 
 // block b handles voxels b, b + gridDim.x, ... in chunks; thread (g = t / per, c8 = t % per): voxel lane g
@@ -142,12 +177,16 @@ template <int CO>
 static int pw_run(const Geom& g, int pass, const void* a, const void* b, void* out, void* ws, hipStream_t s) {
     const long long vox = g.in_voxels();
     if (pass == MI3D_PASS_FWD) {
-        pw_fwd_kernel<CO><<<(unsigned)((vox + 255) / 256), 256, 0, s>>>((const uint16_t*)a, (const uint16_t*)b, (uint16_t*)out, vox, g.Cin);
+        long long blocks = (vox * (g.Cin / 8) + 4 * 256 - 1) / (4 * 256);
+        if (blocks > 8192) blocks = 8192;
+        pw_fwd_kernel<CO><<<(unsigned)blocks, 256, 0, s>>>((const uint16_t*)a, (const uint16_t*)b, (uint16_t*)out, vox, g.Cin);
         return check_launch();
     }
     if (pass == MI3D_PASS_DGRAD) {
         const long long n = vox * (g.Cin / 8);
-        pw_dgrad_kernel<CO><<<(unsigned)((n + 255) / 256), 256, 0, s>>>((const uint16_t*)a, (const uint16_t*)b, (uint16_t*)out, vox, g.Cin,
+        long long blocks = (n + 4 * 256 - 1) / (4 * 256);
+        if (blocks > 8192) blocks = 8192;
+        pw_dgrad_kernel<CO><<<(unsigned)blocks, 256, 0, s>>>((const uint16_t*)a, (const uint16_t*)b, (uint16_t*)out, vox, g.Cin,
                                                                              (const uint16_t*)g.ref, g.slope);
         return check_launch();
     }
