@@ -18,13 +18,24 @@
 
 #include "mi3d_internal.h"
 
+// The file is compiled twice: as it is (16-row patches, 4 rows per wave, namespace th16) and from conv_sp12.hip with
+// 12-row patches of 3 rows per wave (namespace th12) for planes whose height 16-row patches cover badly (24 and 12
+// rows: a quarter of the MFMA work would fall on rows outside the tensor).  The entry points at the end of the
+// 16-row build choose between the two.
+#ifndef SP_TH
+#define SP_TH 16
+#define SP_RH 4
+#define SP_NS th16
+#endif
+
 namespace mi3d {
+namespace SP_NS {
 namespace {
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 
-constexpr int TH = 16, TW = 32, RH = 4;            // output patch per workgroup, rows per wave
+constexpr int TH = SP_TH, TW = 32, RH = SP_RH;     // output patch per workgroup, rows per wave
 // Waves and threads per workgroup.  RH = 2 gives eight waves, two per SIMD, so that one wave's LDS reads, conversions
 // and waits run in the shadow of the other's MFMAs (the counters show that a wave issues nothing else while its own
 // MFMA runs).  Measured: 9 % fewer cycles for the 32-channel kernel and the same run time (that kernel is limited by
@@ -33,11 +44,13 @@ constexpr int TH = 16, TW = 32, RH = 4;            // output patch per workgroup
 constexpr int NW = TH / RH, NT = 64 * NW;
 constexpr int IN_ROWS = TH + 2, IN_COLS = TW + 2;  // with halo
 constexpr int COLS = 35;                           // padded row pitch (voxels) in LDS
-constexpr int NV = 646;                            // 16-byte positions per 8-channel slab: 18 x 35 = 630 used, room for
-                                                   // ten 64-position loads, slab pitch = 96 bytes mod 256
+constexpr int NLOAD = (IN_ROWS * COLS + 64 * (NW / 4) - 1) / (64 * (NW / 4));   // 16-byte loads per thread per plane (10)
+// 16-byte positions per 8-channel slab: IN_ROWS x 35 used (630), room for NLOAD 64-position loads per slab (640),
+// slab pitch = 96 bytes mod 256 (646 positions)
+constexpr int NV = ((64 * NLOAD * (NW / 4) + 15) / 16) * 16 + 6;
 constexpr int STAGE_BYTES = 4 * NV * 16;           // 4 slabs of 8 channels, 16 B per voxel
 constexpr int W_BYTES = 27 * 2 * 64 * 16;          // 27 taps x 2 k16 steps x 1 KB fragments
-constexpr int NLOAD = 40 / NW;                     // 16-byte loads per thread per plane
+static_assert(NW % 4 == 0 && NLOAD * NW * 16 >= IN_ROWS * IN_COLS && (NV * 16) % 256 == 96, "staging plan");
 constexpr unsigned OOB = 0x80000000u;              // buffer offset of a piece that must read as zero
 
 struct SpParams {
@@ -517,7 +530,7 @@ __global__ void __launch_bounds__(NT, NW / 4) sp_conv_kernel(SpParams P) {
             }                                                                                   \
             ++sq;                                                                               \
             /* the loads into the next stage are complete; the 2 RH stores issued after them may still fly */ \
-            if (DMA) { if (RH == 4) asm volatile("s_waitcnt vmcnt(8)" ::: "memory"); else asm volatile("s_waitcnt vmcnt(4)" ::: "memory"); } \
+            if (DMA) { if (RH == 4) asm volatile("s_waitcnt vmcnt(8)" ::: "memory"); else if (RH == 3) asm volatile("s_waitcnt vmcnt(6)" ::: "memory"); else asm volatile("s_waitcnt vmcnt(4)" ::: "memory"); } \
             __syncthreads();                                                                    \
         }
 #define SP_STEP(PHASE)                                                                          \
@@ -634,7 +647,7 @@ __global__ void __launch_bounds__(256) sp_pack_weights_kernel(const uint16_t* __
 
 }  // namespace
 
-bool sp_supported(const Geom& g, int pass) {
+bool supported(const Geom& g, int pass) {
     if (g.dtype != MI3D_BF16 || g.kD != 3 || g.kH != 3 || g.kW != 3) return false;
     if (g.sD != 1 || g.sH != 1 || g.sW != 1) return false;
     if (g.pD > 2 || g.pH > 2 || g.pW > 2) return false;
@@ -664,9 +677,6 @@ static bool sp_use_chunks(const Geom& g, int pass) {
     return cin >= 96 && units < 2ll * sp_cu_count();
 }
 
-// the chunked variant applies the optional derivative factor of the geometry while it sums the chunks
-// ... and the other variants do in their store path
-bool sp_fuses_dgrad_factor(const Geom& g) { return sp_supported(g, MI3D_PASS_DGRAD); }
 
 static size_t sp_part_offset(const Geom& g) { return (((size_t)g.w_elems() * 2 + 255) & ~(size_t)255) + 8192; }
 
@@ -686,12 +696,12 @@ static size_t sp_stat_bytes(const Geom& g, int pass) {
     sp_stat_layout(g, pass, &units, &nwg, &max_seg);
     return (size_t)nwg * max_seg * (NW * 64 * sizeof(float) + sizeof(int)) + 256;
 }
-bool sp_fuses_stats(const Geom& g) { return sp_supported(g, MI3D_PASS_FWD) && !sp_use_chunks(g, MI3D_PASS_FWD); }
+bool fuses_stats(const Geom& g) { return supported(g, MI3D_PASS_FWD) && !sp_use_chunks(g, MI3D_PASS_FWD); }
 // the data gradient that also delivers the sums of the instance-normalisation backward pass of the layer below
-bool sp_fuses_bwd_sums(const Geom& g) { return sp_supported(g, MI3D_PASS_DGRAD) && !sp_use_chunks(g, MI3D_PASS_DGRAD); }
+bool fuses_bwd_sums(const Geom& g) { return supported(g, MI3D_PASS_DGRAD) && !sp_use_chunks(g, MI3D_PASS_DGRAD); }
 
-size_t sp_workspace_bytes(const Geom& g, int pass) {
-    if (!sp_supported(g, pass)) return 0;
+size_t workspace_bytes(const Geom& g, int pass) {
+    if (!supported(g, pass)) return 0;
     size_t b = sp_part_offset(g);  // packed weights + store dump area
     if (sp_use_chunks(g, pass)) {
         const int cin = pass == MI3D_PASS_DGRAD ? g.Cout : g.Cin;
@@ -704,8 +714,8 @@ size_t sp_workspace_bytes(const Geom& g, int pass) {
 }
 
 // in: activations read (x for fwd, dy for dgrad); out: y or dx
-int sp_conv(const Geom& g, int pass, const void* in, const void* w, void* out, void* ws, size_t ws_bytes, hipStream_t s) {
-    if (ws_bytes < sp_workspace_bytes(g, pass)) return MI3D_ERR_WORKSPACE;
+int conv(const Geom& g, int pass, const void* in, const void* w, void* out, void* ws, size_t ws_bytes, hipStream_t s) {
+    if (ws_bytes < workspace_bytes(g, pass)) return MI3D_ERR_WORKSPACE;
     const bool flip = pass == MI3D_PASS_DGRAD;
     long long total = g.w_elems();
     sp_pack_weights_kernel<<<(unsigned)((total + 255) / 256), 256, 0, s>>>((const uint16_t*)w, (uint16_t*)ws, g.Cin, g.Cout, flip ? 1 : 0);
@@ -809,5 +819,45 @@ int sp_conv(const Geom& g, int pass, const void* in, const void* w, void* out, v
     else sp_conv_kernel<0><<<(unsigned)nwg, NT, lds1, s>>>(P);
     return check_launch();
 }
+
+}  // namespace SP_NS
+
+#if SP_TH == 16
+namespace th12 {
+size_t workspace_bytes(const Geom& g, int pass);
+int conv(const Geom& g, int pass, const void* in, const void* w, void* out, void* ws, size_t ws_bytes, hipStream_t s);
+bool fuses_stats(const Geom& g);
+bool fuses_bwd_sums(const Geom& g);
+}  // namespace th12
+
+// 12-row patches where they cover the output plane with fewer rows than 16-row patches do (heights 12, 24, 36, ...),
+// and on a tie where 16-row patches would give a CU fewer than six units (more, smaller units balance better).
+// Measured, 16 / 12 rows: 256->256 at 24^3 0.119 / 0.100 ms (N = 1), 0.158 / 0.138 (N = 2); 320->320 at 12^3
+// 0.083 / 0.070; 128->128 at 48^3, N = 1, 0.152 / 0.130; the large layers lose 1-3 % with 12 rows.
+static bool sp_rows12(const Geom& g, int pass) {
+    const bool flip = pass == MI3D_PASS_DGRAD;
+    const int cout = flip ? g.Cin : g.Cout, Do = flip ? g.D : g.Do, Ho = flip ? g.H : g.Ho, Wo = flip ? g.W : g.Wo;
+    const int r16 = (Ho + 15) / 16 * 16, r12 = (Ho + 11) / 12 * 12;
+    if (r12 != r16) return r12 < r16;
+    int dev = 0, cus = 256;
+    if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+    const long long units16 = (long long)g.N * (cout / 32) * (r16 / 16) * ((Wo + 31) / 32) * Do;
+    return units16 < 6ll * cus;
+}
+
+bool sp_supported(const Geom& g, int pass) { return th16::supported(g, pass); }
+// the chunked variant applies the optional derivative factor of the geometry while it sums the chunks, the other
+// variants do in their store path
+bool sp_fuses_dgrad_factor(const Geom& g) { return th16::supported(g, MI3D_PASS_DGRAD); }
+bool sp_fuses_stats(const Geom& g) { return sp_rows12(g, MI3D_PASS_FWD) ? th12::fuses_stats(g) : th16::fuses_stats(g); }
+bool sp_fuses_bwd_sums(const Geom& g) { return sp_rows12(g, MI3D_PASS_DGRAD) ? th12::fuses_bwd_sums(g) : th16::fuses_bwd_sums(g); }
+size_t sp_workspace_bytes(const Geom& g, int pass) {
+    if (!th16::supported(g, pass)) return 0;
+    return sp_rows12(g, pass) ? th12::workspace_bytes(g, pass) : th16::workspace_bytes(g, pass);
+}
+int sp_conv(const Geom& g, int pass, const void* in, const void* w, void* out, void* ws, size_t ws_bytes, hipStream_t s) {
+    return sp_rows12(g, pass) ? th12::conv(g, pass, in, w, out, ws, ws_bytes, s) : th16::conv(g, pass, in, w, out, ws, ws_bytes, s);
+}
+#endif
 
 }  // namespace mi3d

@@ -22,7 +22,16 @@
 //   bit-reproducible.
 #include "mi3d_internal.h"
 
+// The file is compiled twice: as it is (16-row patches, namespace th16) and from conv_wgrad12.hip with 12-row patches
+// (namespace th12) for planes whose height 16-row patches cover badly (24 and 12 rows: a quarter of the MFMA work
+// would fall on rows outside the tensor).  The entry points at the end of the 16-row build choose between the two.
+#ifndef WG_TH
+#define WG_TH 16
+#define WG_NS th16
+#endif
+
 namespace mi3d {
+namespace WG_NS {
 namespace {
 
 typedef __attribute__((__vector_size__(4 * sizeof(short)))) short s16x4;
@@ -30,7 +39,7 @@ typedef __attribute__((__vector_size__(8 * sizeof(short)))) short s16x8;
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
 
-constexpr int TH = 16, TW = 32;
+constexpr int TH = WG_TH, TW = 32;
 constexpr int XR = TH + 2, XC = TW + 2;          // x patch with halo
 constexpr int X_SLAB = XR * XC * 32;             // bytes of one 16-channel slab of the x patch
 constexpr int X_BYTES = 2 * X_SLAB;
@@ -39,6 +48,7 @@ constexpr int DY_BYTES = 2 * DY_SLAB;
 constexpr int NX = (XR * XC * 4 + 255) / 256;    // 16-byte pieces per thread: x patch (10)
 constexpr int NDY = TH * TW * 4 / 256;           // dy patch (8)
 constexpr int XPIECES = XR * XC * 4;
+static_assert(NX + NDY <= XR && NDY * 256 == TH * TW * 4, "one global load per x row covers both patches");
 
 struct WgParams {
     const uint16_t* x;
@@ -97,6 +107,16 @@ __device__ __forceinline__ void row_step(f32x4 (&acc)[3][3][3], bf16x8 (&dyw)[3]
     WG_FENCE();
 }
 
+// rows R, R + 1, ... of the x patch; xf holds the fragments of row R, the other set receives those of row R + 1
+template <int R, class Hook>
+__device__ __forceinline__ void rows_from(f32x4 (&acc)[3][3][3], bf16x8 (&dyw)[3][4], bf16x8 (&xf)[3], bf16x8 (&xn)[3],
+                                          const char* x_lane, const char* const (&dy_lane)[3], Hook&& hook) {
+    if constexpr (R < XR) {
+        row_step<R>(acc, dyw, xf, xn, x_lane, dy_lane, hook);
+        rows_from<R + 1>(acc, dyw, xn, xf, x_lane, dy_lane, hook);
+    }
+}
+
 template <class Hook>
 __device__ __forceinline__ void plane_step(f32x4 (&acc)[3][3][3], const char* x_lane, const char* const (&dy_lane)[3], Hook&& hook) {
     bf16x8 dyw[3][4], xa[3], xb[3];
@@ -104,24 +124,7 @@ __device__ __forceinline__ void plane_step(f32x4 (&acc)[3][3][3], const char* x_
     for (int kd = 0; kd < 3; ++kd) dyw[kd][0] = tr_frag(dy_lane[kd]);
 #pragma unroll
     for (int kw = 0; kw < 3; ++kw) xa[kw] = tr_frag(x_lane + kw * 32);
-    row_step<0>(acc, dyw, xa, xb, x_lane, dy_lane, hook);
-    row_step<1>(acc, dyw, xb, xa, x_lane, dy_lane, hook);
-    row_step<2>(acc, dyw, xa, xb, x_lane, dy_lane, hook);
-    row_step<3>(acc, dyw, xb, xa, x_lane, dy_lane, hook);
-    row_step<4>(acc, dyw, xa, xb, x_lane, dy_lane, hook);
-    row_step<5>(acc, dyw, xb, xa, x_lane, dy_lane, hook);
-    row_step<6>(acc, dyw, xa, xb, x_lane, dy_lane, hook);
-    row_step<7>(acc, dyw, xb, xa, x_lane, dy_lane, hook);
-    row_step<8>(acc, dyw, xa, xb, x_lane, dy_lane, hook);
-    row_step<9>(acc, dyw, xb, xa, x_lane, dy_lane, hook);
-    row_step<10>(acc, dyw, xa, xb, x_lane, dy_lane, hook);
-    row_step<11>(acc, dyw, xb, xa, x_lane, dy_lane, hook);
-    row_step<12>(acc, dyw, xa, xb, x_lane, dy_lane, hook);
-    row_step<13>(acc, dyw, xb, xa, x_lane, dy_lane, hook);
-    row_step<14>(acc, dyw, xa, xb, x_lane, dy_lane, hook);
-    row_step<15>(acc, dyw, xb, xa, x_lane, dy_lane, hook);
-    row_step<16>(acc, dyw, xa, xb, x_lane, dy_lane, hook);
-    row_step<17>(acc, dyw, xb, xa, x_lane, dy_lane, hook);
+    rows_from<0>(acc, dyw, xa, xb, x_lane, dy_lane, hook);
 }
 
 __device__ __forceinline__ int mod3(int v) { return ((v % 3) + 3) % 3; }
@@ -251,7 +254,7 @@ __global__ void __launch_bounds__(256, 1) wgrad_kernel(WgParams P) {
             for (int kd = 0; kd < 3; ++kd)
                 dyl[kd] = dy_lds + mod3(id + P.pD - kd) * DY_BYTES + coh * DY_SLAB + lane_off;
             const char* const dy_lane[3] = {dyl[0], dyl[1], dyl[2]};
-            // one global load per x row: rows 0..9 fetch the next x patch, rows 10..17 the next dy patch.
+            // one global load per x row: the first NX rows fetch the next x patch, the other NDY the next dy patch.
             // The loads and the LDS writes below are unconditional (the step after the last one of a segment
             // fetches a valid plane that is never used): with a condition the compiler cannot pair each
             // load with its consumer and waits for all outstanding loads before every new one.
@@ -288,7 +291,7 @@ __global__ void __launch_bounds__(256, 1) wgrad_kernel(WgParams P) {
 
 }  // namespace
 
-bool wgrad_mfma_supported(const Geom& g) {
+bool supported(const Geom& g) {
     if (g.dtype != MI3D_BF16 || g.kD != 3 || g.kH != 3 || g.kW != 3) return false;
     if (g.sD != 1 || g.sH != 1 || g.sW != 1) return false;
     if (g.pD > 2 || g.pH > 2 || g.pW > 2) return false;
@@ -305,13 +308,13 @@ static int wgrad_slots(const Geom& g) {
     return (int)slots;
 }
 
-size_t wgrad_mfma_workspace_bytes(const Geom& g) {
-    if (!wgrad_mfma_supported(g)) return 0;
+size_t workspace_bytes(const Geom& g) {
+    if (!supported(g)) return 0;
     return (size_t)wgrad_slots(g) * g.w_elems() * sizeof(float);
 }
 
-int wgrad_mfma(const Geom& g, const void* x, const void* dy, float* dw, void* ws, size_t ws_bytes, hipStream_t s) {
-    if (ws_bytes < wgrad_mfma_workspace_bytes(g)) return MI3D_ERR_WORKSPACE;
+int run(const Geom& g, const void* x, const void* dy, float* dw, void* ws, size_t ws_bytes, hipStream_t s) {
+    if (ws_bytes < workspace_bytes(g)) return MI3D_ERR_WORKSPACE;
     WgParams P;
     P.x = (const uint16_t*)x;
     P.dy = (const uint16_t*)dy;
@@ -344,5 +347,23 @@ int wgrad_mfma(const Geom& g, const void* x, const void* dy, float* dw, void* ws
     long long n = g.w_elems();
     return reduce_partials((const float*)ws, dw, n, P.slots, s);
 }
+
+}  // namespace WG_NS
+
+#if WG_TH == 16
+namespace th12 {
+size_t workspace_bytes(const Geom& g);
+int run(const Geom& g, const void* x, const void* dy, float* dw, void* ws, size_t ws_bytes, hipStream_t s);
+}  // namespace th12
+
+// 12-row patches where they cover the dy plane with fewer rows than 16-row patches do (heights 12, 24, 36, ...)
+static bool wgrad_rows12(const Geom& g) { return (g.Ho + 11) / 12 * 12 < (g.Ho + 15) / 16 * 16; }
+
+bool wgrad_mfma_supported(const Geom& g) { return th16::supported(g); }
+size_t wgrad_mfma_workspace_bytes(const Geom& g) { return wgrad_rows12(g) ? th12::workspace_bytes(g) : th16::workspace_bytes(g); }
+int wgrad_mfma(const Geom& g, const void* x, const void* dy, float* dw, void* ws, size_t ws_bytes, hipStream_t s) {
+    return wgrad_rows12(g) ? th12::run(g, x, dy, dw, ws, ws_bytes, s) : th16::run(g, x, dy, dw, ws, ws_bytes, s);
+}
+#endif
 
 }  // namespace mi3d
