@@ -831,9 +831,10 @@ bool fuses_bwd_sums(const Geom& g);
 }  // namespace th12
 
 // 12-row patches where they cover the output plane with fewer rows than 16-row patches do (heights 12, 24, 36, ...),
-// and on a tie where 16-row patches would give a CU fewer than six units (more, smaller units balance better).
+// and on a tie where 16-row patches would give a CU fewer than twelve units (more, smaller units balance better).
 // Measured, 16 / 12 rows: 256->256 at 24^3 0.119 / 0.100 ms (N = 1), 0.158 / 0.138 (N = 2); 320->320 at 12^3
-// 0.083 / 0.070; 128->128 at 48^3, N = 1, 0.152 / 0.130; the large layers lose 1-3 % with 12 rows.
+// 0.083 / 0.070; 128->128 at 48^3 0.152 / 0.130 (N = 1: 4.5 units per CU), 0.243 / 0.231 (N = 2: 9 per CU); 128->64
+// at 96^3, N = 2 (27 per CU) 0.666 / 0.691: the large layers lose 1-3 % with 12 rows.
 static bool sp_rows12(const Geom& g, int pass) {
     const bool flip = pass == MI3D_PASS_DGRAD;
     const int cout = flip ? g.Cin : g.Cout, Do = flip ? g.D : g.Do, Ho = flip ? g.H : g.Ho, Wo = flip ? g.W : g.Wo;
@@ -842,7 +843,7 @@ static bool sp_rows12(const Geom& g, int pass) {
     int dev = 0, cus = 256;
     if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
     const long long units16 = (long long)g.N * (cout / 32) * (r16 / 16) * ((Wo + 31) / 32) * Do;
-    return units16 < 6ll * cus;
+    return units16 < 12ll * cus;
 }
 
 bool sp_supported(const Geom& g, int pass) { return th16::supported(g, pass); }
