@@ -42,8 +42,14 @@ constexpr int TH = SP_TH, TW = 32, RH = SP_RH;     // output patch per workgroup
 // power, the clock drops by as much), and register spills in the 64-channel and streamed-weight variants, which need
 // about 280 registers against the 256 a wave has with two per SIMD: four waves of four rows it stays.
 constexpr int NW = TH / RH, NT = 64 * NW;
-constexpr int IN_ROWS = TH + 2, IN_COLS = TW + 2;  // with halo
-constexpr int COLS = 35;                           // padded row pitch (voxels) in LDS
+// PAIRED (12-row build): where the last column of patches has at most 16 columns inside the tensor (W = 48: 32 + 16),
+// a workgroup takes that column for two patch rows at once: MFMA columns 0..15 are the 16 columns of patch row 2 i,
+// columns 16..31 the same 16 columns of patch row 2 i + 1, so no MFMA column is spent outside the tensor.  The two
+// input patches (18 columns each with halo) sit side by side in the staged rows.
+constexpr bool PAIRED = TH == 12;
+constexpr int HALF = TW / 2 + 2;                   // staged columns of one half of a paired patch
+constexpr int IN_ROWS = TH + 2, IN_COLS = PAIRED ? 2 * HALF : TW + 2;  // with halo
+constexpr int COLS = IN_COLS + 1;                  // padded row pitch (voxels) in LDS
 constexpr int NLOAD = (IN_ROWS * COLS + 64 * (NW / 4) - 1) / (64 * (NW / 4));   // 16-byte loads per thread per plane (10)
 // 16-byte positions per 8-channel slab: IN_ROWS x 35 used (630), room for NLOAD 64-position loads per slab (640),
 // slab pitch = 96 bytes mod 256 (646 positions)
@@ -64,6 +70,7 @@ struct SpParams {
     const uint16_t* ref;    // MASK variant: tensor of the output's shape whose sign selects the factor 1 or slope
     int N, D, H, W, Cin, Cout, Do, Ho, Wo, pD, pH, pW;
     int HT, WT, CT;         // tiles per plane, cout tiles
+    int WTF, HTP;           // columns of patches taken one patch at a time, paired patch rows of the last column (else 0)
     // Tensors given as two halves along the channels (virtual concatenation): chunks >= xsplit of the input come
     // from x2, cout tiles >= ysplit of the output go to y2; xpitch / ypitch are the channels per voxel of the
     // tensors in memory (Cin, Cout when not split; then the split indices lie beyond the last chunk / tile).
@@ -319,12 +326,11 @@ __global__ void __launch_bounds__(NT, NW / 4) sp_conv_kernel(SpParams P) {
 #pragma unroll
         for (int i = 0; i < NLOAD; ++i) {
             int v = 16 * (NW * i + wave) + (lane & 15), c = lane >> 4;
-            int row = (v * 241) >> 13, col = v - row * IN_COLS;  // v / 34 for v < 700
+            int row = v / IN_COLS, col = v - row * IN_COLS;
             lds_off[i] = (c * NV + row * COLS + col) * 16;
         }
     }
     f32x16 acc[3][RH];
-    const int lane_in_off = ((lane >> 5) * NV + wave * RH * COLS + (lane & 31)) * 16;
     const char* w_lane = w_lds + lane * 16;
 
     int cur_ct = -1;
@@ -334,8 +340,17 @@ __global__ void __launch_bounds__(NT, NW / 4) sp_conv_kernel(SpParams P) {
         int od_start = (int)(u0 - column * P.Do);
         int od_end = od_start + (int)((u1 - u0) < (long long)(P.Do - od_start) ? (u1 - u0) : (long long)(P.Do - od_start));
         u0 += od_end - od_start;
-        int wt = (int)(column % P.WT); column /= P.WT;
-        int ht = (int)(column % P.HT); column /= P.HT;
+        const int tpp = P.HT * P.WTF + P.HTP;                  // patches of a plane
+        const int tsel = (int)(column % tpp); column /= tpp;
+        const bool paired = PAIRED && tsel >= P.HT * P.WTF;    // (uniform)
+        const int wtf1 = P.WTF > 0 ? P.WTF : 1;                // (no unpaired column: every patch is paired)
+        const int wt = paired ? P.WTF : tsel % wtf1;
+        const int ht = paired ? 2 * (tsel - P.HT * P.WTF) : tsel / wtf1;
+        // this lane's column of the patch (before the tap shift) in the staged rows, the rows between its patch and the
+        // first one, and its column in the tensor
+        const int lcol = paired ? (lane & 15) + ((lane & 16) ? HALF : 0) : (lane & 31);
+        const int lrow = paired && (lane & 16) ? TH : 0;
+        const int lane_in_off = ((lane >> 5) * NV + wave * RH * COLS + lcol) * 16;
         const int chunk0 = PART ? (int)(column % P.NCH) : 0;   // chunked variant: this unit's cin chunk
         if (PART) column /= P.NCH;
         int ct = (int)(column % P.CT);
@@ -369,16 +384,17 @@ __global__ void __launch_bounds__(NT, NW / 4) sp_conv_kernel(SpParams P) {
             bool ok;
             if (DMA) {
                 const int pos = 64 * (i + NLOAD * (wave >> 2)) + lane;   // the NW / 4 waves of a slab share its ten loads
-                row = (pos * 1873) >> 16; col = pos - row * COLS;  // pos / 35 for pos < 640
+                row = pos / COLS; col = pos - row * COLS;
                 c = wave & 3;
-                ok = row < IN_ROWS && col < IN_COLS;
+                ok = row < IN_ROWS && col < (paired ? IN_COLS : TW + 2);
             } else {
                 const int v = 16 * (NW * i + wave) + (lane & 15);
-                row = (v * 241) >> 13; col = v - row * IN_COLS;
+                row = v / IN_COLS; col = v - row * IN_COLS;
                 c = lane >> 4;
-                ok = v < NVOX;
+                ok = v < NVOX && col < (paired ? IN_COLS : TW + 2);
             }
-            const int gh = h0 - P.pH + row, gw = w0 - P.pW + col;
+            const bool second = paired && col >= HALF;   // the patch one patch row further down
+            const int gh = h0 + (second ? TH : 0) - P.pH + row, gw = w0 - P.pW + (second ? col - HALF : col);
             ok = ok && gh >= 0 && gh < P.H && gw >= 0 && gw < P.W;
             if (DMA) goff[i] = ok ? ((gh * P.W + gw) * P.xpitch + c * 8) * 2 : (int)OOB;
             else goff[i] = ok ? (gh * P.W + gw) * P.xpitch + c * 8 : 0;
@@ -438,13 +454,13 @@ __global__ void __launch_bounds__(NT, NW / 4) sp_conv_kernel(SpParams P) {
         long long st_off = 0;     // element offset of row 0 of the pending plane for this lane (before the lane half)
         float* partn = PART ? P.part + ((long long)chunk0 * P.N + n) * P.Do * P.Ho * P.Wo * P.Cout : nullptr;
         bool st_pending = false;
-        const int ow_ = w0 + (lane & 31);
+        const int ow_ = w0 + (paired ? (lane & 15) : (lane & 31));
         const long long row_pitch = (long long)P.Wo * opitch;
         uint4 mk[REF ? RH : 1][2];   // the pieces of ref at the addresses of the pending stores
         const uint16_t* refn = REF ? P.ref + (long long)n * P.Do * P.Ho * P.Wo * P.Cout : nullptr;
         auto load_mask = [&](int r) {     // unconditional, like the stores: masked lanes read the dump area
             if constexpr (REF) {
-                const bool ok = st_pending && ow_ < P.Wo && h0 + wave * RH + r < P.Ho;
+                const bool ok = st_pending && ow_ < P.Wo && h0 + lrow + wave * RH + r < P.Ho;
                 const uint16_t* q = ok ? refn + st_off + r * row_pitch + 16 * (lane >> 5) : P.dump + lane * 16;
                 mk[r][0] = *(const uint4*)q;
                 mk[r][1] = *(const uint4*)(q + 8);
@@ -456,7 +472,7 @@ __global__ void __launch_bounds__(NT, NW / 4) sp_conv_kernel(SpParams P) {
             for (int i = 0; i < 16; ++i) st1[i] = st2[i] = 0.f;
         }
         auto store_piece = [&](int r) {
-            const bool ok = st_pending && ow_ < P.Wo && h0 + wave * RH + r < P.Ho;
+            const bool ok = st_pending && ow_ < P.Wo && h0 + lrow + wave * RH + r < P.Ho;
             if (STATS == 1 && st_pending) {   // (uniform: stages with nothing to store skip the arithmetic)
 #pragma unroll
                 for (int i = 0; i < 8; ++i) {
@@ -526,7 +542,7 @@ __global__ void __launch_bounds__(NT, NW / 4) sp_conv_kernel(SpParams P) {
             write_stage(NBUF == 2 ? ((sq + 1) & 1) : 0);                                        \
             if (LAST) {                                                                         \
                 st_pending = jj >= 2;                                                           \
-                st_off = (((long long)(j_ - 2) * P.Ho + h0 + wave * RH) * P.Wo + ow_) * opitch + (PART ? ct : ct_local) * 32;  \
+                st_off = (((long long)(j_ - 2) * P.Ho + h0 + lrow + wave * RH) * P.Wo + ow_) * opitch + (PART ? ct : ct_local) * 32;  \
             }                                                                                   \
             ++sq;                                                                               \
             /* the loads into the next stage are complete; the 2 RH stores issued after them may still fly */ \
@@ -658,6 +674,17 @@ bool supported(const Geom& g, int pass) {
     return false;
 }
 
+// Patches of an output plane of Ho x Wo: wtf columns of patches are taken one patch at a time; where the last column
+// has at most 16 columns inside the tensor and there are at least two patch rows, it is taken two patch rows at a
+// time (htp pairs; 12-row build only).
+static int sp_plane_tiles(int Ho, int Wo, int* wtf, int* htp) {
+    const int HT = (Ho + TH - 1) / TH, WT = (Wo + TW - 1) / TW, tail = Wo - (WT - 1) * TW;
+    const bool pair = PAIRED && tail <= TW / 2 && HT >= 2;
+    *wtf = pair ? WT - 1 : WT;
+    *htp = pair ? (HT + 1) / 2 : 0;
+    return HT * *wtf + *htp;
+}
+
 static int sp_cu_count() {
     int dev = 0, cus = 256;
     if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
@@ -673,7 +700,8 @@ static bool sp_use_chunks(const Geom& g, int pass) {
     const bool flip = pass == MI3D_PASS_DGRAD;
     const int cin = flip ? g.Cout : g.Cin, cout = flip ? g.Cin : g.Cout;
     const int Do = flip ? g.D : g.Do, Ho = flip ? g.H : g.Ho, Wo = flip ? g.W : g.Wo;
-    const long long units = (long long)g.N * (cout / 32) * ((Ho + TH - 1) / TH) * ((Wo + TW - 1) / TW) * Do;
+    int wtf, htp;
+    const long long units = (long long)g.N * (cout / 32) * sp_plane_tiles(Ho, Wo, &wtf, &htp) * Do;
     return cin >= 96 && units < 2ll * sp_cu_count();
 }
 
@@ -684,7 +712,8 @@ static size_t sp_part_offset(const Geom& g) { return (((size_t)g.w_elems() * 2 +
 static void sp_stat_layout(const Geom& g, int pass, long long* units, int* nwg, int* max_seg) {
     const bool flip = pass == MI3D_PASS_DGRAD;
     const int cout = flip ? g.Cin : g.Cout, Do = flip ? g.D : g.Do, Ho = flip ? g.H : g.Ho, Wo = flip ? g.W : g.Wo;
-    *units = (long long)g.N * (cout / 32) * ((Ho + TH - 1) / TH) * ((Wo + TW - 1) / TW) * Do;
+    int wtf, htp;
+    *units = (long long)g.N * (cout / 32) * sp_plane_tiles(Ho, Wo, &wtf, &htp) * Do;
     long long n = sp_cu_count();
     if (n > *units) n = *units;
     *nwg = (int)n;
@@ -753,7 +782,7 @@ int conv(const Geom& g, int pass, const void* in, const void* w, void* out, void
     P.slope = (pass == MI3D_PASS_FWD || mask) ? g.slope : 1.f;
     P.ref = mask || bstat ? (const uint16_t*)g.ref : nullptr;
     P.stat_slope = bstat ? g.slope : 1.f;
-    P.units = (long long)P.N * P.CT * P.NCH * P.HT * P.WT * P.Do;
+    P.units = (long long)P.N * P.CT * P.NCH * sp_plane_tiles(P.Ho, P.Wo, &P.WTF, &P.HTP) * P.Do;
     long long nwg = sp_cu_count();
     if (nwg > P.units) nwg = P.units;
     P.nwg = (int)nwg;
@@ -831,7 +860,8 @@ bool fuses_bwd_sums(const Geom& g);
 }  // namespace th12
 
 // 12-row patches where they cover the output plane with fewer rows than 16-row patches do (heights 12, 24, 36, ...),
-// and on a tie where 16-row patches would give a CU fewer than twelve units (more, smaller units balance better).
+// on a tie where the last column of patches can be paired (widths 48, 16, ...: 128->128 at 48^3, N = 2, 0.231 ->
+// 0.19 ms), and on a tie where 16-row patches would give a CU fewer than twelve units (more, smaller units balance better).
 // Measured, 16 / 12 rows: 256->256 at 24^3 0.119 / 0.100 ms (N = 1), 0.158 / 0.138 (N = 2); 320->320 at 12^3
 // 0.083 / 0.070; 128->128 at 48^3 0.152 / 0.130 (N = 1: 4.5 units per CU), 0.243 / 0.231 (N = 2: 9 per CU); 128->64
 // at 96^3, N = 2 (27 per CU) 0.666 / 0.691: the large layers lose 1-3 % with 12 rows.
@@ -840,6 +870,9 @@ static bool sp_rows12(const Geom& g, int pass) {
     const int cout = flip ? g.Cin : g.Cout, Do = flip ? g.D : g.Do, Ho = flip ? g.H : g.Ho, Wo = flip ? g.W : g.Wo;
     const int r16 = (Ho + 15) / 16 * 16, r12 = (Ho + 11) / 12 * 12;
     if (r12 != r16) return r12 < r16;
+    // the 12-row build takes a last column of patches that is at most half inside the tensor two patch rows at a time
+    const int tail = Wo - (Wo - 1) / 32 * 32;
+    if (tail <= 16 && r12 >= 24) return true;
     int dev = 0, cus = 256;
     if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
     const long long units16 = (long long)g.N * (cout / 32) * (r16 / 16) * ((Wo + 31) / 32) * Do;

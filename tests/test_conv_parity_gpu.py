@@ -71,6 +71,12 @@ MID = [
     (2, 6, 10, 14, 64, 128, 2, 2, 0),
     (1, 4, 6, 6, 256, 320, 2, 2, 0),
     (1, 4, 4, 8, 32, 96, 2, 2, 0),
+    # a last column of patches at most half inside the tensor, taken two patch rows at a time (12-row patches)
+    (1, 5, 24, 48, 32, 32, 3, 1, 1),
+    (2, 4, 36, 16, 64, 64, 3, 1, 1),      # no other column; odd number of patch rows
+    (1, 4, 48, 48, 128, 64, 3, 1, 1),     # streamed weights
+    (1, 5, 26, 50, 32, 32, 3, 1, 0),      # 24 x 48 output without padding
+    (1, 5, 22, 46, 64, 32, 3, 1, 2),      # 24 x 48 output, padding 2
 ]
 
 
