@@ -40,7 +40,13 @@ typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
 
 constexpr int TH = WG_TH, TW = 32;
-constexpr int XR = TH + 2, XC = TW + 2;          // x patch with halo
+// PAIRED (12-row build): where the last column of patches has at most 16 columns inside the tensor (W = 48: 32 + 16),
+// a workgroup takes that column for two patch rows at once: voxels 0..15 of a staged dy row are the 16 columns of
+// patch row 2 i, voxels 16..31 the same columns of patch row 2 i + 1, so no MFMA k-step is spent outside the tensor.
+// The two x patches (18 columns each with halo) sit side by side in the staged rows.
+constexpr bool PAIRED = TH == 12;
+constexpr int HALF = TW / 2 + 2;                 // staged columns of one half of a paired x patch
+constexpr int XR = TH + 2, XC = PAIRED ? 2 * HALF : TW + 2;   // x patch with halo
 constexpr int X_SLAB = XR * XC * 32;             // bytes of one 16-channel slab of the x patch
 constexpr int X_BYTES = 2 * X_SLAB;
 constexpr int DY_SLAB = TH * TW * 32;
@@ -56,6 +62,7 @@ struct WgParams {
     float* part;            // [slots][Cout][27][Cin]
     int N, D, H, W, Cin, Cout, Do, Ho, Wo, pD, pH, pW;
     int HT, WT, CiT, CoT;
+    int WTF, HTP;           // columns of patches taken one patch at a time, paired patch rows of the last column (else 0)
     long long units;        // per pair: N*HT*WT*D
     int slots;              // workgroups per pair
     // x given as two halves along the channels (virtual concatenation): cin tiles >= xsplit come from x2; xpitch is
@@ -72,6 +79,15 @@ __device__ __forceinline__ bf16x8 tr_frag(const char* p) {
     return __builtin_bit_cast(bf16x8, c);
 }
 
+// the same with the second sixteen voxels at an address of their own (paired x patches)
+__device__ __forceinline__ bf16x8 tr_frag2(const char* p, const char* p2) {
+    typedef __attribute__((address_space(3))) s16x4* lptr;
+    s16x4 a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lptr)(p));
+    s16x4 b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lptr)(p2));
+    s16x8 c = __builtin_shufflevector(a, b, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8, c);
+}
+
 __device__ __forceinline__ f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c) {
     return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
 }
@@ -83,7 +99,7 @@ __device__ __forceinline__ f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c) {
 // shifts of the current row, xn receives those of the next row.
 template <int R, class Hook>
 __device__ __forceinline__ void row_step(f32x4 (&acc)[3][3][3], bf16x8 (&dyw)[3][4], bf16x8 (&xf)[3], bf16x8 (&xn)[3],
-                                         const char* x_lane, const char* const (&dy_lane)[3], Hook&& hook) {
+                                         const char* x_lane, const char* x_lane2, const char* const (&dy_lane)[3], Hook&& hook) {
     // prefetch for row R + 1: its dy fragments (one per kd) and x fragments (one per kw)
     if (R + 1 < TH) {
 #pragma unroll
@@ -91,7 +107,7 @@ __device__ __forceinline__ void row_step(f32x4 (&acc)[3][3][3], bf16x8 (&dyw)[3]
     }
     if (R + 1 < XR) {
 #pragma unroll
-        for (int kw = 0; kw < 3; ++kw) xn[kw] = tr_frag(x_lane + ((R + 1) * XC + kw) * 32);
+        for (int kw = 0; kw < 3; ++kw) xn[kw] = tr_frag2(x_lane + ((R + 1) * XC + kw) * 32, x_lane2 + ((R + 1) * XC + kw) * 32);
     }
 #pragma unroll
     for (int kh = 0; kh < 3; ++kh) {
@@ -110,21 +126,21 @@ __device__ __forceinline__ void row_step(f32x4 (&acc)[3][3][3], bf16x8 (&dyw)[3]
 // rows R, R + 1, ... of the x patch; xf holds the fragments of row R, the other set receives those of row R + 1
 template <int R, class Hook>
 __device__ __forceinline__ void rows_from(f32x4 (&acc)[3][3][3], bf16x8 (&dyw)[3][4], bf16x8 (&xf)[3], bf16x8 (&xn)[3],
-                                          const char* x_lane, const char* const (&dy_lane)[3], Hook&& hook) {
+                                          const char* x_lane, const char* x_lane2, const char* const (&dy_lane)[3], Hook&& hook) {
     if constexpr (R < XR) {
-        row_step<R>(acc, dyw, xf, xn, x_lane, dy_lane, hook);
-        rows_from<R + 1>(acc, dyw, xn, xf, x_lane, dy_lane, hook);
+        row_step<R>(acc, dyw, xf, xn, x_lane, x_lane2, dy_lane, hook);
+        rows_from<R + 1>(acc, dyw, xn, xf, x_lane, x_lane2, dy_lane, hook);
     }
 }
 
 template <class Hook>
-__device__ __forceinline__ void plane_step(f32x4 (&acc)[3][3][3], const char* x_lane, const char* const (&dy_lane)[3], Hook&& hook) {
+__device__ __forceinline__ void plane_step(f32x4 (&acc)[3][3][3], const char* x_lane, const char* x_lane2, const char* const (&dy_lane)[3], Hook&& hook) {
     bf16x8 dyw[3][4], xa[3], xb[3];
 #pragma unroll
     for (int kd = 0; kd < 3; ++kd) dyw[kd][0] = tr_frag(dy_lane[kd]);
 #pragma unroll
-    for (int kw = 0; kw < 3; ++kw) xa[kw] = tr_frag(x_lane + kw * 32);
-    rows_from<0>(acc, dyw, xa, xb, x_lane, dy_lane, hook);
+    for (int kw = 0; kw < 3; ++kw) xa[kw] = tr_frag2(x_lane + kw * 32, x_lane2 + kw * 32);
+    rows_from<0>(acc, dyw, xa, xb, x_lane, x_lane2, dy_lane, hook);
 }
 
 __device__ __forceinline__ int mod3(int v) { return ((v % 3) + 3) % 3; }
@@ -165,10 +181,16 @@ __global__ void __launch_bounds__(256, 1) wgrad_kernel(WgParams P) {
         const long long left = u1 - u0;
         const int id_end = id_start + (int)(left < (long long)(P.D - id_start) ? left : (long long)(P.D - id_start));
         u0 += id_end - id_start;
-        const int wt = (int)(column % P.WT); column /= P.WT;
-        const int ht = (int)(column % P.HT);
-        const int n = (int)(column / P.HT);
+        const int tpp = P.HT * P.WTF + P.HTP;                  // patches of a plane
+        const int tsel = (int)(column % tpp);
+        const int n = (int)(column / tpp);
+        const bool paired = PAIRED && tsel >= P.HT * P.WTF;    // (uniform)
+        const int wtf1 = P.WTF > 0 ? P.WTF : 1;                // (no unpaired column: every patch is paired)
+        const int wt = paired ? P.WTF : tsel % wtf1;
+        const int ht = paired ? 2 * (tsel - P.HT * P.WTF) : tsel / wtf1;
         const int h0 = ht * TH, w0 = wt * TW;
+        // the second sixteen voxels of an x fragment: the same staged row, or the second patch's part of it
+        const char* x_lane2 = x_lane + (16 + (paired ? HALF - 16 : 0)) * 32;
 
         // load plans: x piece q = t + 256 i is channels 8c..8c+7 of patch voxel q / 4
         int gx[NX], gdy[NDY];
@@ -176,9 +198,10 @@ __global__ void __launch_bounds__(256, 1) wgrad_kernel(WgParams P) {
 #pragma unroll
         for (int i = 0; i < NX; ++i) {
             int q = t + 256 * i, v = q >> 2, c = q & 3;
-            int row = (v * 241) >> 13, col = v - row * XC;  // v / 34
-            int gh = h0 - P.pH + row, gw = w0 - P.pW + col;
-            bool ok = q < XPIECES && gh >= 0 && gh < P.H && gw >= 0 && gw < P.W;
+            int row = v / XC, col = v - row * XC;
+            const bool second = paired && col >= HALF;   // the patch one patch row further down
+            int gh = h0 + (second ? TH : 0) - P.pH + row, gw = w0 - P.pW + (second ? col - HALF : col);
+            bool ok = q < XPIECES && col < (paired ? XC : TW + 2) && gh >= 0 && gh < P.H && gw >= 0 && gw < P.W;
             gx[i] = ok ? (gh * P.W + gw) * P.xpitch + cit_local * 32 + c * 8 : 0;
             vx |= (ok ? 1u : 0u) << i;
         }
@@ -186,8 +209,9 @@ __global__ void __launch_bounds__(256, 1) wgrad_kernel(WgParams P) {
         for (int i = 0; i < NDY; ++i) {
             int q = t + 256 * i, v = q >> 2, c = q & 3;
             int row = v >> 5, col = v & 31;
-            int gh = h0 + row, gw = w0 + col;
-            bool ok = gh < P.Ho && gw < P.Wo;
+            const bool second = paired && col >= 16;
+            int gh = h0 + (second ? TH : 0) + row, gw = w0 + (second ? col - 16 : col);
+            bool ok = gh < P.Ho && gw < P.Wo && !(paired && !second && col >= 16);
             gdy[i] = ok ? (gh * P.Wo + gw) * P.Cout + cot * 32 + c * 8 : 0;
             vdy |= (ok ? 1u : 0u) << i;
         }
@@ -211,7 +235,7 @@ __global__ void __launch_bounds__(256, 1) wgrad_kernel(WgParams P) {
 #pragma unroll
             for (int i = 0; i < NX; ++i) {
                 int q = t + 256 * i, v = q >> 2, c = q & 3;
-                int row = (v * 241) >> 13, col = v - row * XC;
+                int row = v / XC, col = v - row * XC;
                 const bool ok = (mx >> i) & 1;
                 uint4 w;
                 w.x = ok ? px[i].x : 0u; w.y = ok ? px[i].y : 0u; w.z = ok ? px[i].z : 0u; w.w = ok ? px[i].w : 0u;
@@ -259,7 +283,7 @@ __global__ void __launch_bounds__(256, 1) wgrad_kernel(WgParams P) {
             // fetches a valid plane that is never used): with a condition the compiler cannot pair each
             // load with its consumer and waits for all outstanding loads before every new one.
             (void)more;
-            plane_step(acc, x_lane, dy_lane, [&](int r) {
+            plane_step(acc, x_lane, x_lane2, dy_lane, [&](int r) {
                 if (r < NX) px[r] = *(const uint4*)(bx + gx[r]);
                 else if (r - NX < NDY) pdy[r - NX] = *(const uint4*)(bdy + gdy[r - NX]);
             });
@@ -299,9 +323,21 @@ bool supported(const Geom& g) {
     return g.Cin % 32 == 0 && g.Cout % 32 == 0;
 }
 
+// Patches of a dy plane of Ho x Wo: wtf columns of patches are taken one patch at a time; where the last column has
+// at most 16 columns inside the tensor and there are at least two patch rows, it is taken two patch rows at a time
+// (htp pairs; 12-row build only).
+static int plane_tiles(int Ho, int Wo, int* wtf, int* htp) {
+    const int HT = (Ho + TH - 1) / TH, WT = (Wo + TW - 1) / TW, tail = Wo - (WT - 1) * TW;
+    const bool pair = PAIRED && tail <= TW / 2 && HT >= 2;
+    *wtf = pair ? WT - 1 : WT;
+    *htp = pair ? (HT + 1) / 2 : 0;
+    return HT * *wtf + *htp;
+}
+
 static int wgrad_slots(const Geom& g) {
     long long pairs = (long long)(g.Cin / 32) * (g.Cout / 32);
-    long long units = (long long)g.N * ((g.Ho + TH - 1) / TH) * ((g.Wo + TW - 1) / TW) * g.D;
+    int wtf, htp;
+    long long units = (long long)g.N * plane_tiles(g.Ho, g.Wo, &wtf, &htp) * g.D;
     long long slots = (256 + pairs - 1) / pairs;   // about one workgroup per CU in total
     if (slots > units) slots = units;
     if (slots < 1) slots = 1;
@@ -325,7 +361,7 @@ int run(const Geom& g, const void* x, const void* dy, float* dw, void* ws, size_
     P.WT = (g.Wo + TW - 1) / TW;
     P.CiT = g.Cin / 32;
     P.CoT = g.Cout / 32;
-    P.units = (long long)g.N * P.HT * P.WT * g.D;
+    P.units = (long long)g.N * plane_tiles(g.Ho, g.Wo, &P.WTF, &P.HTP) * g.D;
     P.slots = wgrad_slots(g);
     P.x2 = P.x; P.xpitch = g.Cin; P.xsplit = P.CiT;
     if (g.hi) {
@@ -357,7 +393,13 @@ int run(const Geom& g, const void* x, const void* dy, float* dw, void* ws, size_
 }  // namespace th12
 
 // 12-row patches where they cover the dy plane with fewer rows than 16-row patches do (heights 12, 24, 36, ...)
-static bool wgrad_rows12(const Geom& g) { return (g.Ho + 11) / 12 * 12 < (g.Ho + 15) / 16 * 16; }
+// and on a tie where the last column of patches can be paired (widths 48, 16, ...)
+static bool wgrad_rows12(const Geom& g) {
+    const int r16 = (g.Ho + 15) / 16 * 16, r12 = (g.Ho + 11) / 12 * 12;
+    if (r12 != r16) return r12 < r16;
+    const int tail = g.Wo - (g.Wo - 1) / 32 * 32;
+    return tail <= 16 && r12 >= 24;
+}
 
 bool wgrad_mfma_supported(const Geom& g) { return th16::supported(g); }
 size_t wgrad_mfma_workspace_bytes(const Geom& g) { return wgrad_rows12(g) ? th12::workspace_bytes(g) : th16::workspace_bytes(g); }
