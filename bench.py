@@ -689,7 +689,13 @@ def main():
     roof = roofline_entry(dom, MFMA_BF16_PEAK_TFLOPS, args.steps)
     roof.update({"kernel": dom_name, "share_of_step_time": dom["ms"] / args.steps / ms_step,
                  "traffic": measured_traffic(dom_name), "profiler_avg_us_per_launch": profiled_avg_us(dom_name),
-                 "timing": "HIP events around every call of the kernel inside the timed steps, on the launch stream"})
+                 "timing": "HIP events around every call of the kernel inside the timed steps, on the launch stream (a call's "
+                           "small launches, weight packing or the ordered sum of the partial sums, and the gaps between them are inside)"})
+    if roof["profiler_avg_us_per_launch"]:
+        # the same algorithmic work per launch over the main kernel's own average duration in rocprofv3's trace of this command
+        per_launch = (dom["flop"] if roof["bound"] == "mfma" else dom["bytes"]) / dom["launches"]
+        ach = per_launch / (roof["profiler_avg_us_per_launch"] * 1e-6) / (1e12 if roof["bound"] == "mfma" else 1e9)
+        roof["frac_by_profiler_avg"] = ach / roof["peak"]
     kernels = {k: {q: (round(v, 4) if isinstance(v, float) else v) for q, v in roofline_entry(a, MFMA_BF16_PEAK_TFLOPS, args.steps).items()}
                for k, a in sorted(kern.items(), key=lambda kv: -kv[1]["ms"])}
     value = flops / ms_step / 1e9
