@@ -180,7 +180,7 @@ int mi3d_conv3d_fwd_stats(const mi3d_conv_desc *desc, const void *x, const void 
  * which is what mi3d_instnorm_lrelu_bwd computes in a reduction pass of its own (same values up to the order of the
  * fp32 partial sums; the order is fixed).  mi3d_instnorm_lrelu_bwd_sums then finishes the backward pass without that
  * reduction.  sums: N * Cin * 2 floats, device; 0 < slope <= 1.  Only the unchunked bf16 3x3x3 stride-1 MFMA
- * data-gradient kernels do this (mi3d_conv3d_dgrad_insums_supported tells, 1 / 0); other geometries return
+ * data-gradient kernels and the 1x1x1 head kernel do this (mi3d_conv3d_dgrad_insums_supported tells, 1 / 0); other geometries return
  * MI3D_ERR_UNSUPPORTED and the caller runs mi3d_conv3d_dgrad and mi3d_instnorm_lrelu_bwd.  Workspace as for
  * mi3d_conv3d_dgrad; a_in must not overlap dx. */
 int mi3d_conv3d_dgrad_insums_supported(const mi3d_conv_desc *desc);

@@ -349,7 +349,8 @@ int mi3d_conv3d_fwd_stats(const mi3d_conv_desc* desc, const void* x, const void*
 int mi3d_conv3d_dgrad_insums_supported(const mi3d_conv_desc* desc) {
     Geom g;
     if (make_geom(desc, &g)) return 0;
-    return choose(g, MI3D_PASS_DGRAD) == K_SP && sp_fuses_bwd_sums(g) ? 1 : 0;
+    const Kernel k = choose(g, MI3D_PASS_DGRAD);
+    return (k == K_SP && sp_fuses_bwd_sums(g)) || k == K_POINTWISE ? 1 : 0;
 }
 
 int mi3d_conv3d_dgrad_insums(const mi3d_conv_desc* desc, const void* dy, const void* w, const void* a_in, float slope, void* dx, float* sums,
@@ -366,7 +367,7 @@ int mi3d_conv3d_dgrad_insums(const mi3d_conv_desc* desc, const void* dy, const v
     g.ref = a_in;
     g.slope = slope;
     g.stats = sums;
-    return run_kernel(K_SP, g, MI3D_PASS_DGRAD, dy, w, dx, ws, ws_bytes, (hipStream_t)stream);
+    return run_kernel(choose(g, MI3D_PASS_DGRAD), g, MI3D_PASS_DGRAD, dy, w, dx, ws, ws_bytes, (hipStream_t)stream);
 }
 
 int mi3d_conv3d_pair_supported(const mi3d_conv_desc* desc, int pass) {

@@ -68,16 +68,30 @@ __global__ void __launch_bounds__(256) pw_fwd_kernel(const uint16_t* __restrict_
 
 // Thread t of the grid handles the 16-byte pieces t, t + T, t + 2 T, ... of dx (T = threads in the grid), four at a time
 // so that their loads are in flight together; a piece is 8 input channels of one voxel.
-template <int CO>
+// SUMS: one sample per blockIdx.y; no factor is applied to dx, but with a = ref (the activated output of the
+// normalised layer below), g = dx * lrelu'(a) of the stored values and xhat = lrelu^-1(a), every thread adds up g and
+// g * xhat of its 8 channels (T is a multiple of the pieces per voxel, so they are the same in every round); the block
+// adds its threads' sums in thread order and writes part[n][block][2][Cin].
+template <int CO, bool SUMS>
 __global__ void __launch_bounds__(256) pw_dgrad_kernel(const uint16_t* __restrict__ dy, const uint16_t* __restrict__ w,
                                                        uint16_t* __restrict__ dx, long long voxels, int Cin,
-                                                       const uint16_t* __restrict__ ref, float slope) {
+                                                       const uint16_t* __restrict__ ref, float slope, float* __restrict__ part) {
     __shared__ float ws[MAXCO * MAXCI];
+    __shared__ float red[SUMS ? 256 * 8 : 1];
     for (int i = threadIdx.x; i < CO * Cin; i += 256) ws[i] = bf16_to_f32(w[i]);
     __syncthreads();
     const int per = Cin / 8;
+    if (SUMS) {   // this block's sample
+        dy += (long long)blockIdx.y * voxels * CO;
+        dx += (long long)blockIdx.y * voxels * Cin;
+        ref += (long long)blockIdx.y * voxels * Cin;
+    }
     const long long pieces = voxels * per, T = (long long)gridDim.x * 256;
     constexpr int U = 4;
+    float s1[8], s2[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) s1[j] = s2[j] = 0.f;
+    const float inv_slope = 1.f / slope;
     for (long long i0 = (long long)blockIdx.x * 256 + threadIdx.x; i0 < pieces; i0 += U * T) {
         float g[U][CO];
         uint4 m4[U];
@@ -107,11 +121,36 @@ __global__ void __launch_bounds__(256) pw_dgrad_kernel(const uint16_t* __restric
                     a = fmaf(g[u][co], ws[co * Cin + c0 + 2 * j], a);
                     b = fmaf(g[u][co], ws[co * Cin + c0 + 2 * j + 1], b);
                 }
-                if (!((int)(m[j] << 16) > 0)) a *= slope;
-                if (!((int)(m[j] & 0xffff0000u) > 0)) b *= slope;
+                if (!SUMS) {
+                    if (!((int)(m[j] << 16) > 0)) a *= slope;
+                    if (!((int)(m[j] & 0xffff0000u) > 0)) b *= slope;
+                }
                 o[j] = (uint32_t)f32_to_bf16_rne(a) | ((uint32_t)f32_to_bf16_rne(b) << 16);
+                if (SUMS) {
+                    const float va = __uint_as_float(o[j] << 16), vb = __uint_as_float(o[j] & 0xffff0000u);
+                    const float ra = __uint_as_float(m[j] << 16), rb = __uint_as_float(m[j] & 0xffff0000u);
+                    const float ga = ra > 0.f ? va : slope * va, gb = rb > 0.f ? vb : slope * vb;
+                    s1[2 * j] += ga; s2[2 * j] = fmaf(ga, ra > 0.f ? ra : ra * inv_slope, s2[2 * j]);
+                    s1[2 * j + 1] += gb; s2[2 * j + 1] = fmaf(gb, rb > 0.f ? rb : rb * inv_slope, s2[2 * j + 1]);
+                }
             }
             *(uint4*)(dx + idx[u] * 8) = uint4{o[0], o[1], o[2], o[3]};
+        }
+    }
+    if (SUMS) {
+        const int t = threadIdx.x, groups = 256 / per;    // thread t holds channels 8 (t % per) ..
+        float* out = part + ((long long)blockIdx.y * gridDim.x + blockIdx.x) * 2 * Cin;
+        for (int q = 0; q < 2; ++q) {
+            __syncthreads();
+#pragma unroll
+            for (int j = 0; j < 8; ++j) red[t * 8 + j] = q ? s2[j] : s1[j];
+            __syncthreads();
+            for (int c = t; c < Cin; c += 256) {
+                const int pp = c / 8, j = c % 8;
+                float a = 0.f;
+                for (int l = 0; l < groups; ++l) a += red[(l * per + pp) * 8 + j];
+                out[q * Cin + c] = a;
+            }
         }
     }
 }
@@ -168,8 +207,11 @@ static int pw_wgrad_blocks(const Geom& g) {
     return (int)(b < 1024 ? b : 1024);
 }
 
+constexpr int PW_SUM_BLOCKS = 512;   // blocks per sample of the data gradient that also adds up the normalisation's sums
+
 size_t pointwise_workspace_bytes(const Geom& g, int pass) {
-    if (!pointwise_supported(g) || pass != MI3D_PASS_WGRAD) return 0;
+    if (!pointwise_supported(g) || pass == MI3D_PASS_FWD) return 0;
+    if (pass == MI3D_PASS_DGRAD) return (size_t)g.N * PW_SUM_BLOCKS * 2 * g.Cin * sizeof(float);   // block sums of the variant with sums
     return (size_t)pw_wgrad_blocks(g) * g.Cout * g.Cin * sizeof(float);
 }
 
@@ -182,12 +224,24 @@ static int pw_run(const Geom& g, int pass, const void* a, const void* b, void* o
         pw_fwd_kernel<CO><<<(unsigned)blocks, 256, 0, s>>>((const uint16_t*)a, (const uint16_t*)b, (uint16_t*)out, vox, g.Cin);
         return check_launch();
     }
+    if (pass == MI3D_PASS_DGRAD && g.stats) {
+        // with the two sums of the instance-normalisation backward pass of the layer below (ref = its activated output)
+        if (!g.ref || !(g.slope > 0.f) || g.N > 65535) return MI3D_ERR_UNSUPPORTED;
+        const long long per_sample = vox / g.N;
+        long long blocks = (per_sample * (g.Cin / 8) + 4 * 256 - 1) / (4 * 256);
+        if (blocks > PW_SUM_BLOCKS) blocks = PW_SUM_BLOCKS;
+        pw_dgrad_kernel<CO, true><<<dim3((unsigned)blocks, (unsigned)g.N), 256, 0, s>>>((const uint16_t*)a, (const uint16_t*)b, (uint16_t*)out, per_sample,
+                                                                                        g.Cin, (const uint16_t*)g.ref, g.slope, (float*)ws);
+        int st = check_launch();
+        if (st) return st;
+        return instnorm_finish_means((const float*)ws, (int)blocks, g.Cin, g.N, 1.0 / (double)per_sample, g.stats, s);
+    }
     if (pass == MI3D_PASS_DGRAD) {
         const long long n = vox * (g.Cin / 8);
         long long blocks = (n + 4 * 256 - 1) / (4 * 256);
         if (blocks > 8192) blocks = 8192;
-        pw_dgrad_kernel<CO><<<(unsigned)blocks, 256, 0, s>>>((const uint16_t*)a, (const uint16_t*)b, (uint16_t*)out, vox, g.Cin,
-                                                                             (const uint16_t*)g.ref, g.slope);
+        pw_dgrad_kernel<CO, false><<<(unsigned)blocks, 256, 0, s>>>((const uint16_t*)a, (const uint16_t*)b, (uint16_t*)out, vox, g.Cin,
+                                                                     (const uint16_t*)g.ref, g.slope, nullptr);
         return check_launch();
     }
     const int blocks = pw_wgrad_blocks(g);

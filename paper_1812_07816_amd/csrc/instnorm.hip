@@ -205,6 +205,14 @@ unsigned in_grid(long long pieces) {
 bool a16(const void* p) { return ((uintptr_t)p & 15) == 0; }
 
 }  // namespace
+
+// out[n][c] = (mean of the first quantity, mean of the second) from block sums part[n][block][2][C], added in index order
+// in double: the last step of a reduction whose block sums another kernel has written in in_reduce_kernel's layout
+int instnorm_finish_means(const float* part, int blocks, int C, int N, double inv_v, float* out, hipStream_t s) {
+    in_finish_kernel<1><<<(N * C + 15) / 16, 256, 0, s>>>(part, blocks, C, N * C, inv_v, 0.f, out);
+    return check_launch();
+}
+
 }  // namespace mi3d
 
 using namespace mi3d;

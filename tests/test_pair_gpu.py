@@ -204,6 +204,32 @@ def test_data_gradient_with_the_sums_of_the_normalisation_backward_pass(device, 
     assert e_f.max() <= 1e-2 and e_s.max() <= 1e-2
 
 
+@pytest.mark.parametrize("shape", [(2, 9, 10, 37, 32, 3), (1, 5, 6, 7, 64, 4), (3, 4, 4, 4, 8, 1)])
+def test_head_data_gradient_with_the_sums_of_the_normalisation_backward_pass(device, shape):
+    from oracle import unet as ou
+    N, D, H, W, Cin, Cout = shape
+    x, w, dy = si.conv_case(99, 100 + Cin, N, D, H, W, Cin, Cout, 1, 1, 0, True)
+    a = si.bf16_round((x * np.linspace(0.2, 3.0, Cin)).astype(np.float32))
+    desc = mc.make_desc(N, D, H, W, Cin, Cout, 1, 1, 0, torch.bfloat16)
+    assert mc.dgrad_insums_supported(desc) and mc.kernel_name(desc, 1) == "valu_pointwise_head"
+    ad, wd, dyd = parity.to_device(a, True), parity.to_device(w, True), parity.to_device(dy, True)
+    sums = torch.full((N, Cin, 2), 7.0, device="cuda")
+    dx = mc.conv3d_dgrad_insums(desc, dyd, wd, ad, ou.SLOPE, sums)
+    assert torch.equal(dx, mc.conv3d_dgrad(desc, dyd, wd))
+    again = torch.zeros_like(sums)
+    mc.conv3d_dgrad_insums(desc, dyd, wd, ad, ou.SLOPE, again)
+    assert torch.equal(sums, again)
+    dxh = parity.to_host(dx).astype(np.float64)
+    xhat = ou.lrelu_inverse(a.astype(np.float64))
+    g = np.where(xhat > 0, dxh, ou.SLOPE * dxh)
+    m1, m2 = g.mean(axis=(1, 2, 3)), (g * xhat).mean(axis=(1, 2, 3))
+    got = sums.cpu().numpy().astype(np.float64)
+    s1, s2 = g.std(axis=(1, 2, 3)), (g * xhat).std(axis=(1, 2, 3))
+    e1, e2 = (np.abs(got[..., 0] - m1) / s1).max(), (np.abs(got[..., 1] - m2) / s2).max()
+    print(shape, f"mean g {e1:.2e} mean g xhat {e2:.2e}", flush=True)
+    assert e1 <= 1e-6 and e2 <= 1e-6
+
+
 def test_backward_sums_are_refused_where_the_kernel_cannot_produce_them(device):
     bf = torch.bfloat16
     for args in ((1, 12, 12, 12, 320, 320, 3, 1, 1),   # chunked variant

@@ -441,7 +441,7 @@ def test_backward_sums_from_the_data_gradient_give_the_step_of_the_separate_redu
     x, labels, ws, xd, ld = _inputs(N, vol, CH, 5)
     a = unet.UNetStep(N, vol, CH, ws, xd, ld, swap=False, norm=True)
     b = unet.UNetStep(N, vol, CH, ws, xd, ld, swap=False, norm=True, fused_bwd_sums=False)
-    assert sum(1 for op in a.ops if op.get("through_norm")) == 2 and not any(op.get("through_norm") for op in b.ops)
+    assert sum(1 for op in a.ops if op.get("through_norm")) == 3 and not any(op.get("through_norm") for op in b.ops)
     a.run(update=False); b.run(update=False)
     torch.cuda.synchronize()
     assert torch.equal(a.loss, b.loss)
@@ -452,10 +452,10 @@ def test_backward_sums_from_the_data_gradient_give_the_step_of_the_separate_redu
         l2 = np.sqrt(np.sum((ga - gb) ** 2) / np.sum(gb * gb))
         print(f"{name}: max {e:.1e}, l2 {l2:.1e}")
         worst[name] = max(e, l2)
-    # Layers whose gradients are formed before the first such data gradient see the same bits.  From there on a
+    # The head's gradient is formed before the first such data gradient and sees the same bits.  From there on a
     # stored bf16 value that rounds the other way is a relative step of 2^-8, and every layer further down the
     # backward pass inherits the noise of those above it: the first layer's gradient (formed last) the most.
-    assert worst["head"] == 0.0 and worst["dec0.conv2"] == 0.0
+    assert worst["head"] == 0.0
     assert max(worst.values()) <= 3e-2, worst
 
 
