@@ -165,7 +165,8 @@ int mi3d_conv3d_dgrad_skip(const mi3d_conv_desc *desc, const void *dy, const voi
  * x_hi is not null: x then is the low half), and stats[n][c] = (mean, 1 / sqrt(var + eps)) of the stored bf16 values of
  * y over the voxels of sample n, biased variance, as mi3d_instnorm_stats computes them in a pass of its own (same
  * values up to the order of the fp32 partial sums; the order is fixed, so repeated calls give identical bits).
- * stats: N * Cout * 2 floats, device.  Only the unchunked bf16 3x3x3 stride-1 MFMA forward kernels do this
+ * stats: N * Cout * 2 floats, device.  Only the unchunked bf16 3x3x3 stride-1 MFMA forward kernels (and the 4-channel
+ * first-layer kernel with 32 output channels) do this
  * (mi3d_conv3d_fwd_stats_supported tells, 1 / 0); other geometries return MI3D_ERR_UNSUPPORTED and the caller runs
  * the two passes.  Workspace as for mi3d_conv3d_fwd. */
 int mi3d_conv3d_fwd_stats_supported(const mi3d_conv_desc *desc);

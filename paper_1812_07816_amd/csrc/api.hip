@@ -327,7 +327,8 @@ int mi3d_conv3d_dgrad_skip(const mi3d_conv_desc* desc, const void* dy, const voi
 int mi3d_conv3d_fwd_stats_supported(const mi3d_conv_desc* desc) {
     Geom g;
     if (make_geom(desc, &g)) return 0;
-    return choose(g, MI3D_PASS_FWD) == K_SP && sp_fuses_stats(g) ? 1 : 0;
+    const Kernel k = choose(g, MI3D_PASS_FWD);
+    return (k == K_SP && sp_fuses_stats(g)) || (k == K_C4_FWD && c4_fwd_fuses_stats(g)) ? 1 : 0;
 }
 
 int mi3d_conv3d_fwd_stats(const mi3d_conv_desc* desc, const void* x, const void* x_hi, const void* w, void* y, float eps, float* stats,
@@ -343,7 +344,7 @@ int mi3d_conv3d_fwd_stats(const mi3d_conv_desc* desc, const void* x, const void*
     g.hi = x_hi;
     g.stats = stats;
     g.stats_eps = eps;
-    return run_kernel(K_SP, g, MI3D_PASS_FWD, x, w, y, ws, ws_bytes, (hipStream_t)stream);
+    return run_kernel(choose(g, MI3D_PASS_FWD), g, MI3D_PASS_FWD, x, w, y, ws, ws_bytes, (hipStream_t)stream);
 }
 
 int mi3d_conv3d_dgrad_insums_supported(const mi3d_conv_desc* desc) {

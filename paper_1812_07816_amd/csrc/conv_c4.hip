@@ -36,6 +36,11 @@ struct C4Params {
     long long tiles;        // N*HT*WT*Do, output plane fastest
     int nwg;
     float slope;            // LeakyReLU slope applied to the output (1 = none)
+    // STATS: per-(workgroup, segment, wave) sums of y and y^2 over the voxels, 32 couts each, in the layout of the
+    // plane-streaming kernel's statistics: [workgroup][segment][wave][sum, sum of squares][32]; key = sample, -1 = unused
+    float* stat_part;
+    int* stat_key;
+    int max_seg;
 };
 
 // Persistent workgroups walk a contiguous range of (n, 16-row, 32-col, od) tiles, output plane fastest: a
@@ -44,7 +49,10 @@ struct C4Params {
 // tile, loaded into registers while the current tile is computed and stored).
 // ONE: Cout == 32, the 9 weight fragments stay in registers for the whole kernel (otherwise they are
 // re-read from L2 for every cout block of every tile, a load latency per tile that nothing hides)
-template <bool ONE>
+// STATS (with ONE): the kernel also adds up y and y^2 per output channel (of the bf16 values it stores) for the instance
+// normalisation that follows the layer (Section 4.1): a lane stores the same 8 couts of every voxel it handles, keeps
+// their sums over a segment, and the 16 lanes that share the couts add theirs in a fixed butterfly.
+template <bool ONE, bool STATS = false>
 __global__ void __launch_bounds__(256, 2) c4_fwd_kernel(C4Params P) {
     // ring of planes, 1 KB that threads without a voxel of the plane write to, store staging
     __shared__ __attribute__((aligned(16))) char lds[SLOTS * PLANE * 8 + 1024 + 4 * RH * 2048];
@@ -65,7 +73,11 @@ __global__ void __launch_bounds__(256, 2) c4_fwd_kernel(C4Params P) {
         const int S = (int)(P.nwg / columns);
         const int seg = (int)(blockIdx.x / columns);
         const long long col = blockIdx.x % columns;
-        if (seg >= S) return;
+        if (seg >= S) {
+            if (STATS && t == 0)
+                for (int k = 0; k < P.max_seg; ++k) P.stat_key[blockIdx.x * P.max_seg + k] = -1;
+            return;
+        }
         u = col * P.Do + (long long)P.Do * seg / S;
         u1 = col * P.Do + (long long)P.Do * (seg + 1) / S;
     } else {
@@ -83,6 +95,7 @@ __global__ void __launch_bounds__(256, 2) c4_fwd_kernel(C4Params P) {
         lds_off[i] = q < NVOX ? (prow[i] * PITCH + pcol[i]) * 8 : -1;
     }
 
+    int seg_i = 0;   // STATS: index of the segment within this workgroup's range
     while (u < u1) {
         long long b = u / P.Do;
         const int od0 = (int)(u - b * P.Do);
@@ -143,6 +156,11 @@ __global__ void __launch_bounds__(256, 2) c4_fwd_kernel(C4Params P) {
         u32x4 ov[2 * RH];
 #pragma unroll
         for (int i = 0; i < 2 * RH; ++i) ov[i] = u32x4{0u, 0u, 0u, 0u};
+        float st1[STATS ? 8 : 1], st2[STATS ? 8 : 1];
+        if constexpr (STATS) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) st1[j] = st2[j] = 0.f;
+        }
         for (int od = od0; od < od1; ++od) {
             load_plane(od + 3);  // the plane the next tile adds (after the last tile: fetched, never read)
             __builtin_amdgcn_sched_barrier(0);  // keeps the loads here, a whole tile ahead of the LDS write that uses them
@@ -224,9 +242,19 @@ __global__ void __launch_bounds__(256, 2) c4_fwd_kernel(C4Params P) {
                         const int vox = i * 16 + (lane >> 2);
                         // unconditional (masked lanes write to the dump area): the compiler can then count the stores and
                         // lets them fly while the next plane goes to LDS, instead of waiting for vmcnt(0) every tile
-                        uint16_t* dst = (w0 + vox < P.Wo && oh0 + r < P.Ho) ? ybase + r * row_pitch + (long long)vox * P.Cout + cb * 32 + (lane & 3) * 8
-                                                                            : P.dump + t * 8;
+                        const bool inside = w0 + vox < P.Wo && oh0 + r < P.Ho;
+                        uint16_t* dst = inside ? ybase + r * row_pitch + (long long)vox * P.Cout + cb * 32 + (lane & 3) * 8 : P.dump + t * 8;
                         *(u32x4*)dst = v;
+                        if constexpr (STATS) {
+                            const unsigned wv[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                            for (int j = 0; j < 4; ++j) {
+                                const unsigned q = inside ? wv[j] : 0u;
+                                const float lo = __builtin_bit_cast(float, q << 16), hi = __builtin_bit_cast(float, q & 0xffff0000u);
+                                st1[2 * j] += lo; st2[2 * j] = fmaf(lo, lo, st2[2 * j]);
+                                st1[2 * j + 1] += hi; st2[2 * j + 1] = fmaf(hi, hi, st2[2 * j + 1]);
+                            }
+                        }
                     }
             }
             // the slot of plane od + 3 held plane od - 1, whose readers passed the barrier of the previous tile
@@ -234,6 +262,30 @@ __global__ void __launch_bounds__(256, 2) c4_fwd_kernel(C4Params P) {
             write_plane(od + 3);
             __syncthreads();
         }
+        if constexpr (STATS) {
+            // lanes l, l + 4, l + 8, ... hold the same couts 8 (l % 4) .. 8 (l % 4) + 7
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+#pragma unroll
+                for (int off = 32; off >= 4; off >>= 1) {
+                    st1[j] += __shfl_xor(st1[j], off, 64);
+                    st2[j] += __shfl_xor(st2[j], off, 64);
+                }
+            if (t == 0) P.stat_key[blockIdx.x * P.max_seg + seg_i] = n;
+            if (lane < 4) {
+                float* out = P.stat_part + (((long long)blockIdx.x * P.max_seg + seg_i) * 4 + wave) * 64;
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    out[8 * lane + j] = st1[j];
+                    out[32 + 8 * lane + j] = st2[j];
+                }
+            }
+            ++seg_i;
+        }
+    }
+    if constexpr (STATS) {
+        if (t == 0)
+            for (; seg_i < P.max_seg; ++seg_i) P.stat_key[blockIdx.x * P.max_seg + seg_i] = -1;   // unused slots of this workgroup
     }
 }
 
@@ -263,7 +315,24 @@ bool c4_fwd_supported(const Geom& g) {
     return g.Cin == 4 && g.Cout % 32 == 0;
 }
 
-size_t c4_fwd_workspace_bytes(const Geom& g) { return c4_fwd_supported(g) ? (size_t)(g.Cout / 32) * 9 * 1024 + 4096 : 0; }
+// workgroups and the most segments (runs along D inside one patch column) one of them walks
+static void c4_fwd_layout(const Geom& g, long long* tiles, int* nwg, int* max_seg) {
+    *tiles = (long long)g.N * ((g.Ho + TH - 1) / TH) * ((g.Wo + TW - 1) / TW) * g.Do;
+    *nwg = (int)(*tiles < 512 ? *tiles : 512);
+    const long long columns = *tiles / g.Do;
+    if (*nwg >= columns) *max_seg = 1;
+    else *max_seg = (int)(((*tiles + *nwg - 1) / *nwg + g.Do - 1) / g.Do) + 1;
+}
+
+bool c4_fwd_fuses_stats(const Geom& g) { return c4_fwd_supported(g) && g.Cout == 32; }
+
+size_t c4_fwd_workspace_bytes(const Geom& g) {
+    if (!c4_fwd_supported(g)) return 0;
+    long long tiles; int nwg, max_seg;
+    c4_fwd_layout(g, &tiles, &nwg, &max_seg);
+    // packed weights, store dump area, partial sums and keys of the variant with statistics
+    return (size_t)(g.Cout / 32) * 9 * 1024 + 4096 + (size_t)nwg * max_seg * (4 * 64 * sizeof(float) + sizeof(int)) + 256;
+}
 
 int c4_fwd(const Geom& g, const void* x, const void* w, void* y, void* ws, size_t ws_bytes, hipStream_t s) {
     if (ws_bytes < c4_fwd_workspace_bytes(g)) return MI3D_ERR_WORKSPACE;
@@ -278,9 +347,17 @@ int c4_fwd(const Geom& g, const void* x, const void* w, void* y, void* ws, size_
     P.Do = g.Do; P.Ho = g.Ho; P.Wo = g.Wo; P.pD = g.pD; P.pH = g.pH; P.pW = g.pW;
     P.HT = (g.Ho + TH - 1) / TH;
     P.WT = (g.Wo + TW - 1) / TW;
-    P.tiles = (long long)g.N * P.HT * P.WT * g.Do;
-    P.nwg = (int)(P.tiles < 512 ? P.tiles : 512);
+    c4_fwd_layout(g, &P.tiles, &P.nwg, &P.max_seg);
     P.slope = g.slope;
+    P.stat_part = (float*)((char*)ws + (size_t)(g.Cout / 32) * 9 * 1024 + 4096);
+    P.stat_key = (int*)(P.stat_part + (size_t)P.nwg * P.max_seg * 4 * 64);
+    if (g.stats) {
+        if (!c4_fwd_fuses_stats(g)) return MI3D_ERR_UNSUPPORTED;
+        c4_fwd_kernel<true, true><<<(unsigned)P.nwg, 256, 0, s>>>(P);
+        st = check_launch();
+        if (st) return st;
+        return sp_stats_finish(P.stat_part, P.stat_key, 32, 1, g.N, P.nwg, P.max_seg, 1.0 / ((double)g.Do * g.Ho * g.Wo), g.stats_eps, g.stats, s);
+    }
     if (g.Cout == 32) c4_fwd_kernel<true><<<(unsigned)P.nwg, 256, 0, s>>>(P);
     else c4_fwd_kernel<false><<<(unsigned)P.nwg, 256, 0, s>>>(P);
     return check_launch();

@@ -879,6 +879,14 @@ static bool sp_rows12(const Geom& g, int pass) {
     return units16 < 12ll * cus;
 }
 
+// statistics (mean, 1 / sqrt(var + eps)) from partial sums another kernel has written in the STATS = 1 layout (four
+// waves per workgroup): [workgroup][segment][wave][sum, sum of squares][32 couts], key = sample * CT + cout tile
+int sp_stats_finish(const float* part, const int* key, int Cout, int CT, int N, int nwg, int max_seg, double inv_v, float eps, float* stats,
+                    hipStream_t s) {
+    th16::sp_stats_finish_kernel<<<N * CT, 64 * th16::FIN_SLICES, 0, s>>>(part, key, Cout, CT, nwg, max_seg, inv_v, eps, 0, stats);
+    return check_launch();
+}
+
 bool sp_supported(const Geom& g, int pass) { return th16::supported(g, pass); }
 // the chunked variant applies the optional derivative factor of the geometry while it sums the chunks, the other
 // variants do in their store path

@@ -98,6 +98,9 @@ STATS_CASES = [
     (2, 5, 18, 34, 64, 32, 1, True),     # two resident chunks, halves
     (2, 33, 33, 66, 128, 32, 1, True),   # streamed weights (enough units to stay unchunked), halves
     (3, 4, 9, 70, 64, 96, 2, False),     # three samples, pad 2, three cout tiles
+    (2, 12, 20, 36, 4, 32, 1, False),    # first layer (4 input channels): one segment per workgroup
+    (1, 5, 19, 45, 4, 32, 0, False),
+    (1, 2, 384, 776, 4, 32, 1, False),   # more patch columns than workgroups: several segments per workgroup
 ]
 
 
@@ -141,7 +144,7 @@ def test_forward_statistics_are_refused_where_the_kernel_cannot_produce_them(dev
     bf = torch.bfloat16
     for args in ((1, 12, 12, 12, 320, 320, 3, 1, 1),   # chunked variant
                  (1, 8, 8, 8, 32, 64, 3, 2, 1),        # stride 2
-                 (1, 8, 8, 8, 4, 32, 3, 1, 1)):        # first layer
+                 (1, 8, 8, 8, 4, 64, 3, 1, 1)):        # first layer with more than one block of output channels
         d = mc.make_desc(*args, bf)
         assert not mc.fwd_stats_supported(d), args
         N, D, H, W, Cin, Cout, k = args[:7]
