@@ -175,18 +175,21 @@ int mi3d_conv3d_fwd_stats(const mi3d_conv_desc *desc, const void *x, const void 
 
 /* Data gradient whose kernel also produces the two means the backward pass of the instance normalisation of the layer
  * below needs (Section 4.1: that layer is convolution, instance normalisation, LeakyReLU, and a_in is its activated
- * output, the input of this convolution): dx as mi3d_conv3d_dgrad, and with g = dx * lrelu'(a_in) (of the stored bf16
- * values of dx) and xhat = a_in > 0 ? a_in : a_in / slope,
+ * output, the input of this convolution): dx = dgrad(dy, w) as mi3d_conv3d_dgrad computes it, plus add where add is
+ * not NULL (the second gradient of a skip connection, of dx's shape: the bits of mi3d_conv3d_dgrad_skip with slope 1),
+ * and with g = dx * lrelu'(a_in) (of the stored bf16 values of dx) and xhat = a_in > 0 ? a_in : a_in / slope,
  *   sums[n][c] = (mean over the voxels of g, mean over the voxels of g * xhat),
  * which is what mi3d_instnorm_lrelu_bwd computes in a reduction pass of its own (same values up to the order of the
  * fp32 partial sums; the order is fixed).  mi3d_instnorm_lrelu_bwd_sums then finishes the backward pass without that
- * reduction.  sums: N * Cin * 2 floats, device; 0 < slope <= 1.  Only the unchunked bf16 3x3x3 stride-1 MFMA
- * data-gradient kernels and the 1x1x1 head kernel do this (mi3d_conv3d_dgrad_insums_supported tells, 1 / 0); other geometries return
- * MI3D_ERR_UNSUPPORTED and the caller runs mi3d_conv3d_dgrad and mi3d_instnorm_lrelu_bwd.  Workspace as for
- * mi3d_conv3d_dgrad; a_in must not overlap dx. */
-int mi3d_conv3d_dgrad_insums_supported(const mi3d_conv_desc *desc);
-int mi3d_conv3d_dgrad_insums(const mi3d_conv_desc *desc, const void *dy, const void *w, const void *a_in, float slope,
-                             void *dx, float *sums, void *ws, size_t ws_bytes, void *stream);
+ * reduction.  sums: N * Cin * 2 floats, device; 0 < slope <= 1.  Without add: the unchunked bf16 3x3x3 stride-1 MFMA
+ * data-gradient kernels and the 1x1x1 head kernel do this; with add: the unchunked 3x3x3 stride-2 kernel (Cout = 64)
+ * (mi3d_conv3d_dgrad_insums_supported tells, 1 / 0); other geometries return MI3D_ERR_UNSUPPORTED and the caller runs
+ * mi3d_conv3d_dgrad or mi3d_conv3d_dgrad_skip and mi3d_instnorm_lrelu_bwd.  Workspace as for mi3d_conv3d_dgrad; add and
+ * a_in must not overlap dx. */
+int mi3d_conv3d_dgrad_insums_supported(const mi3d_conv_desc *desc, int with_add);
+int mi3d_conv3d_dgrad_insums(const mi3d_conv_desc *desc, const void *dy, const void *w, const void *add,
+                             const void *a_in, float slope, void *dx, float *sums, void *ws, size_t ws_bytes,
+                             void *stream);
 
 /* Convolution followed by the network's LeakyReLU (Section 4.1) in one call:
  * y = lrelu(conv(x, w)), lrelu(v) = v > 0 ? v : slope * v, applied to the fp32

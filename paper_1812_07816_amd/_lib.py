@@ -76,8 +76,8 @@ SIGNATURES = {
     "mi3d_conv3d_dgrad_view": (_i, [_pd, _vp, _vp, _vp, ctypes.POINTER(View), _vp, _sz, _vp]),
     "mi3d_conv3d_wgrad_view": (_i, [_pd, _vp, ctypes.POINTER(View), _vp, _vp, _vp, _sz, _vp]),
     "mi3d_conv3d_dgrad_skip": (_i, [_pd, _vp, _vp, _vp, _vp, ctypes.c_float, _vp, _vp, _sz, _vp]),
-    "mi3d_conv3d_dgrad_insums_supported": (_i, [_pd]),
-    "mi3d_conv3d_dgrad_insums": (_i, [_pd, _vp, _vp, _vp, ctypes.c_float, _vp, _vp, _vp, _sz, _vp]),
+    "mi3d_conv3d_dgrad_insums_supported": (_i, [_pd, _i]),
+    "mi3d_conv3d_dgrad_insums": (_i, [_pd, _vp, _vp, _vp, _vp, ctypes.c_float, _vp, _vp, _vp, _sz, _vp]),
     "mi3d_instnorm_lrelu_bwd_sums": (_i, [_vp, _vp, _vp, _vp, _i, _sz, _i, ctypes.c_float, _vp]),
     "mi3d_conv3d_fwd_stats_supported": (_i, [_pd]),
     "mi3d_conv3d_fwd_stats": (_i, [_pd, _vp, _vp, _vp, _vp, ctypes.c_float, _vp, _vp, _sz, _vp]),

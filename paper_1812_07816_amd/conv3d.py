@@ -177,24 +177,26 @@ def conv3d_fwd_stats(desc, x, w, stats, eps=1e-5, y=None, ws=None, x_hi=None):
     return y
 
 
-def dgrad_insums_supported(desc):
+def dgrad_insums_supported(desc, with_add=False):
     """True if the data-gradient kernel of this geometry can also produce the two means of the instance-normalisation
-    backward pass of the layer below."""
-    return bool(lib().mi3d_conv3d_dgrad_insums_supported(ctypes.byref(desc)))
+    backward pass of the layer below (with_add: while it adds the second gradient of a skip connection)."""
+    return bool(lib().mi3d_conv3d_dgrad_insums_supported(ctypes.byref(desc), int(bool(with_add))))
 
 
-def conv3d_dgrad_insums(desc, dy, w, a_in, slope, sums, dx=None, ws=None):
-    """dx = dgrad(dy, w) and sums[n][c] = (mean g, mean g * xhat) with g = dx * lrelu'(a_in), xhat = lrelu^-1(a_in)."""
+def conv3d_dgrad_insums(desc, dy, w, a_in, slope, sums, dx=None, ws=None, add=None):
+    """dx = dgrad(dy, w) (+ add) and sums[n][c] = (mean g, mean g * xhat) with g = dx * lrelu'(a_in), xhat = lrelu^-1(a_in)."""
     xs, wsh, ys = _shapes(desc)
     dt = _tdtype(desc)
     _chk(dy, ys, dt, "dy"); _chk(w, wsh, dt, "w"); _chk(a_in, xs, dt, "a_in")
+    if add is not None:
+        _chk(add, xs, dt, "add")
     _chk(sums, (desc.N, desc.Cin, 2), torch.float32, "sums")
     if dx is None:
         dx = torch.empty(xs, dtype=dt, device=dy.device)
     _chk(dx, xs, dt, "dx")
     ws, p, n = _ws(desc, PASS_DGRAD, ws)
-    check(lib().mi3d_conv3d_dgrad_insums(ctypes.byref(desc), dy.data_ptr(), w.data_ptr(), a_in.data_ptr(), ctypes.c_float(slope), dx.data_ptr(),
-                                         sums.data_ptr(), p, n, _stream()), "conv3d_dgrad_insums")
+    check(lib().mi3d_conv3d_dgrad_insums(ctypes.byref(desc), dy.data_ptr(), w.data_ptr(), None if add is None else add.data_ptr(), a_in.data_ptr(),
+                                         ctypes.c_float(slope), dx.data_ptr(), sums.data_ptr(), p, n, _stream()), "conv3d_dgrad_insums")
     return dx
 
 

@@ -347,24 +347,26 @@ int mi3d_conv3d_fwd_stats(const mi3d_conv_desc* desc, const void* x, const void*
     return run_kernel(choose(g, MI3D_PASS_FWD), g, MI3D_PASS_FWD, x, w, y, ws, ws_bytes, (hipStream_t)stream);
 }
 
-int mi3d_conv3d_dgrad_insums_supported(const mi3d_conv_desc* desc) {
+int mi3d_conv3d_dgrad_insums_supported(const mi3d_conv_desc* desc, int with_add) {
     Geom g;
     if (make_geom(desc, &g)) return 0;
     const Kernel k = choose(g, MI3D_PASS_DGRAD);
+    if (with_add) return k == K_DGRAD_S2 && dgrad_s2_fuses_skip_sums(g) ? 1 : 0;
     return (k == K_SP && sp_fuses_bwd_sums(g)) || k == K_POINTWISE ? 1 : 0;
 }
 
-int mi3d_conv3d_dgrad_insums(const mi3d_conv_desc* desc, const void* dy, const void* w, const void* a_in, float slope, void* dx, float* sums,
-                             void* ws, size_t ws_bytes, void* stream) {
+int mi3d_conv3d_dgrad_insums(const mi3d_conv_desc* desc, const void* dy, const void* w, const void* add, const void* a_in, float slope, void* dx,
+                             float* sums, void* ws, size_t ws_bytes, void* stream) {
     Geom g;
     int st = make_geom(desc, &g);
     if (st) return st;
-    if (!dy || !w || !a_in || !dx || !sums || !aligned16(dy) || !aligned16(w) || !aligned16(a_in) || !aligned16(dx) || !aligned16(ws) ||
-        !(slope > 0.f && slope <= 1.f))
+    if (!dy || !w || !a_in || !dx || !sums || !aligned16(dy) || !aligned16(w) || !aligned16(add) || !aligned16(a_in) || !aligned16(dx) ||
+        !aligned16(ws) || !(slope > 0.f && slope <= 1.f))
         return MI3D_ERR_INVALID_ARG;
     if (ws_bytes && !ws) return MI3D_ERR_INVALID_ARG;
-    if (!mi3d_conv3d_dgrad_insums_supported(desc)) return MI3D_ERR_UNSUPPORTED;
+    if (!mi3d_conv3d_dgrad_insums_supported(desc, add ? 1 : 0)) return MI3D_ERR_UNSUPPORTED;
     if (ws_bytes < mi3d_conv3d_workspace_bytes(desc, MI3D_PASS_DGRAD)) return MI3D_ERR_WORKSPACE;
+    g.add = add;
     g.ref = a_in;
     g.slope = slope;
     g.stats = sums;

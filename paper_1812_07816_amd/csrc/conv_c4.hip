@@ -356,7 +356,7 @@ int c4_fwd(const Geom& g, const void* x, const void* w, void* y, void* ws, size_
         c4_fwd_kernel<true, true><<<(unsigned)P.nwg, 256, 0, s>>>(P);
         st = check_launch();
         if (st) return st;
-        return sp_stats_finish(P.stat_part, P.stat_key, 32, 1, g.N, P.nwg, P.max_seg, 1.0 / ((double)g.Do * g.Ho * g.Wo), g.stats_eps, g.stats, s);
+        return sp_stats_finish(P.stat_part, P.stat_key, 32, 1, g.N, P.nwg, P.max_seg, 1.0 / ((double)g.Do * g.Ho * g.Wo), g.stats_eps, 0, g.stats, s);
     }
     if (g.Cout == 32) c4_fwd_kernel<true><<<(unsigned)P.nwg, 256, 0, s>>>(P);
     else c4_fwd_kernel<false><<<(unsigned)P.nwg, 256, 0, s>>>(P);

@@ -43,7 +43,28 @@ struct Dg2Params {
     int QD, HT, WT, CiT, NCO;   // ..., cin tiles, cout chunks (of 64 when Cout > 64)
     long long units;
     int nwg;
+    // FUSE == 2: per-(workgroup, segment, wave) sums of g and g * xhat, 32 cins each, in the layout of the
+    // plane-streaming kernel's statistics; key = sample * CiT + cin tile, -1 = unused
+    float stat_slope;
+    float* stat_part;
+    int* stat_key;
+    int max_seg;
 };
+
+// adds g = v * lrelu'(a) and g * xhat, xhat = lrelu^-1(a), of the 8 packed bf16 values of v (stored gradient) and a
+// (activated output of the normalised layer below) to s1[0..7], s2[0..7]; nothing where the lane stores nothing
+__device__ __forceinline__ void add_sums8(const uint4& v, const uint4& a, bool ok, float slope, float inv, float* s1, float* s2) {
+    const uint32_t vw[4] = {v.x, v.y, v.z, v.w}, aw[4] = {a.x, a.y, a.z, a.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const uint32_t q = ok ? vw[i] : 0u, r = ok ? aw[i] : 0u;
+        const float vlo = __builtin_bit_cast(float, q << 16), vhi = __builtin_bit_cast(float, q & 0xffff0000u);
+        const float alo = __builtin_bit_cast(float, r << 16), ahi = __builtin_bit_cast(float, r & 0xffff0000u);
+        const float glo = alo > 0.f ? vlo : slope * vlo, ghi = ahi > 0.f ? vhi : slope * vhi;
+        s1[2 * i] += glo; s2[2 * i] = fmaf(glo, alo > 0.f ? alo : alo * inv, s2[2 * i]);
+        s1[2 * i + 1] += ghi; s2[2 * i + 1] = fmaf(ghi, ahi > 0.f ? ahi : ahi * inv, s2[2 * i + 1]);
+    }
+}
 
 __device__ __forceinline__ f32x16 mfma(bf16x8 a, bf16x8 b, f32x16 c) {
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
@@ -125,7 +146,10 @@ __device__ __forceinline__ uint4 fuse4(uint4 v, uint4 a, uint4 m, float slope) {
 // kernel adds the chunks in index order and rounds to bf16.
 // FUSE (not with PART): the gradient of a skip connection.  The pieces of G.add and G.ref at the addresses of the
 // plane pair's 16 stores are requested before its MFMA work and applied to the rounded result in the store path.
-template <int P, int KK, bool PART, bool FUSE = false>
+// FUSE == 2: the skip tensor's producer is a normalised layer (Section 4.1), so no factor is applied (G.slope = 1), and
+// the kernel adds up the two sums that layer's normalisation needs for its backward pass, from the stored gradient
+// and G.ref: every lane keeps the sums of its 16 cins over a segment, a fixed butterfly adds the 32 voxel lanes.
+template <int P, int KK, bool PART, int FUSE = 0>
 __global__ void __launch_bounds__(256, 1) dgrad_s2_kernel(Dg2Params G) {
     extern __shared__ __attribute__((aligned(16))) char lds[];
     constexpr int SLABS = 2 * KK;
@@ -143,6 +167,7 @@ __global__ void __launch_bounds__(256, 1) dgrad_s2_kernel(Dg2Params G) {
     const int NPIECE = PR * PC * SLABS;         // 16-byte pieces of a staged plane (<= 1320)
     constexpr int NL = 6;
     int cur_cit = -1;
+    int seg_i = 0;   // FUSE == 2: index of the segment within this workgroup's unit range
 
     while (u0 < u1) {
         long long column = u0 / G.QD;
@@ -181,6 +206,12 @@ __global__ void __launch_bounds__(256, 1) dgrad_s2_kernel(Dg2Params G) {
         const long long dy_plane = (long long)G.Ho * G.Wo * G.Cout;
         const uint16_t* dyn = G.dy + (long long)n * G.Do * dy_plane;
         uint16_t* dxn = G.dx + (long long)n * G.D * G.H * G.W * G.Cin;
+        float st1[FUSE == 2 ? 16 : 1], st2[FUSE == 2 ? 16 : 1];
+        if constexpr (FUSE == 2) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) st1[i] = st2[i] = 0.f;
+        }
+        const float inv_stat_slope = FUSE == 2 ? 1.f / G.stat_slope : 1.f;
         float* pn = PART ? G.part + ((long long)chunk * G.N + n) * G.D * G.H * G.W * G.Cin : nullptr;
 
         uint4 pre[NL];
@@ -229,8 +260,8 @@ __global__ void __launch_bounds__(256, 1) dgrad_s2_kernel(Dg2Params G) {
                 oe = (row_ok && iw_ < G.W) ? o : -1;
                 oo = (row_ok && iw_ + 1 < G.W) ? o + G.Cin : -1;
             };
-            uint4 fa[FUSE ? 4 : 1][4], fm[FUSE ? 4 : 1][4];   // [cd * 2 + ch][even 0, even 1, odd 0, odd 1]
-            if constexpr (FUSE) {
+            uint4 fa[FUSE != 0 ? 4 : 1][4], fm[FUSE != 0 ? 4 : 1][4];   // [cd * 2 + ch][even 0, even 1, odd 0, odd 1]
+            if constexpr (FUSE != 0) {
                 const long long nbase = (long long)n * G.D * G.H * G.W * G.Cin;
 #pragma unroll
                 for (int b = 0; b < 4; ++b) {
@@ -325,10 +356,17 @@ __global__ void __launch_bounds__(256, 1) dgrad_s2_kernel(Dg2Params G) {
                     uint16_t* ptr = dxn + (((long long)id_ * G.H + ih_) * G.W + iw_) * G.Cin + cit * 32 + 16 * (lane >> 5);
                     uint16_t* pe = (row_ok && iw_ < G.W) ? ptr : G.dump + lane * 16;
                     uint16_t* po = (row_ok && iw_ + 1 < G.W) ? ptr + G.Cin : G.dump + lane * 16;
-                    if constexpr (FUSE) {
+                    if constexpr (FUSE != 0) {
                         const int b = cd * 2 + ch;
                         ev[0] = fuse4(ev[0], fa[b][0], fm[b][0], G.slope); ev[1] = fuse4(ev[1], fa[b][1], fm[b][1], G.slope);
                         od[0] = fuse4(od[0], fa[b][2], fm[b][2], G.slope); od[1] = fuse4(od[1], fa[b][3], fm[b][3], G.slope);
+                        if constexpr (FUSE == 2) {
+                            const bool oke = row_ok && iw_ < G.W, oko = row_ok && iw_ + 1 < G.W;
+                            add_sums8(ev[0], fm[b][0], oke, G.stat_slope, inv_stat_slope, st1, st2);
+                            add_sums8(ev[1], fm[b][1], oke, G.stat_slope, inv_stat_slope, st1 + 8, st2 + 8);
+                            add_sums8(od[0], fm[b][2], oko, G.stat_slope, inv_stat_slope, st1, st2);
+                            add_sums8(od[1], fm[b][3], oko, G.stat_slope, inv_stat_slope, st1 + 8, st2 + 8);
+                        }
                     }
                     *(uint4*)(pe) = ev[0];
                     *(uint4*)(pe + 8) = ev[1];
@@ -341,6 +379,30 @@ __global__ void __launch_bounds__(256, 1) dgrad_s2_kernel(Dg2Params G) {
             write_plane((mB + 1) & 1);
             __syncthreads();
         }
+        if constexpr (FUSE == 2) {
+            // sums over the 32 voxel lanes of each lane half; lane 0 of half h writes cins 16 h .. 16 h + 15 of the tile
+#pragma unroll
+            for (int i = 0; i < 16; ++i)
+#pragma unroll
+                for (int off = 16; off > 0; off >>= 1) {
+                    st1[i] += __shfl_xor(st1[i], off, 64);
+                    st2[i] += __shfl_xor(st2[i], off, 64);
+                }
+            if (t == 0) G.stat_key[g * G.max_seg + seg_i] = n * G.CiT + cit;
+            if ((lane & 31) == 0) {
+                float* out = G.stat_part + (((long long)g * G.max_seg + seg_i) * 4 + wave) * 64;
+#pragma unroll
+                for (int j = 0; j < 16; ++j) {
+                    out[16 * (lane >> 5) + j] = st1[j];
+                    out[32 + 16 * (lane >> 5) + j] = st2[j];
+                }
+            }
+            ++seg_i;
+        }
+    }
+    if constexpr (FUSE == 2) {
+        if (t == 0)
+            for (; seg_i < G.max_seg; ++seg_i) G.stat_key[g * G.max_seg + seg_i] = -1;   // unused slots of this workgroup
     }
 }
 
@@ -378,11 +440,28 @@ bool dgrad_s2_supported(const Geom& g) {
 // the chunked variant applies the optional derivative factor of the geometry while it sums the chunks
 bool dgrad_s2_fuses_factor(const Geom& g) { return dgrad_s2_supported(g) && g.Cout > 64; }
 bool dgrad_s2_fuses_skip(const Geom& g) { return dgrad_s2_supported(g) && g.Cout >= 64; }
+// ... and the unchunked kernel also the sums of the instance-normalisation backward pass of the skip tensor's producer
+bool dgrad_s2_fuses_skip_sums(const Geom& g) { return dgrad_s2_supported(g) && g.Cout == 64; }
+
+// workgroups and the most segments (runs along D inside one patch column) one of them walks, for the unchunked kernel
+static void dg2_layout(const Geom& g, long long* units, int* nwg, int* max_seg) {
+    const int QD = (g.D + 1) / 2, HT = ((g.H + 1) / 2 + RP - 1) / RP, WT = ((g.W + 1) / 2 + CP - 1) / CP;
+    *units = (long long)g.N * (g.Cin / 32) * HT * WT * QD;
+    int dev = 0, cus = 256;
+    if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+    *nwg = (int)(cus < *units ? cus : *units);
+    *max_seg = (int)(((*units + *nwg - 1) / *nwg + QD - 1) / QD) + 1;
+}
 
 size_t dgrad_s2_workspace_bytes(const Geom& g) {
     if (!dgrad_s2_supported(g)) return 0;
     size_t b = dg2_part_offset(g);   // packed weights + store dump area
     if (g.Cout > 64) b += (size_t)(g.Cout / 64) * g.in_voxels() * g.Cin * sizeof(float);
+    if (g.Cout == 64) {   // partial sums and keys of the variant with the normalisation's sums
+        long long units; int nwg, max_seg;
+        dg2_layout(g, &units, &nwg, &max_seg);
+        b += (size_t)nwg * max_seg * (4 * 64 * sizeof(float) + sizeof(int)) + 256;
+    }
     return b;
 }
 
@@ -400,7 +479,16 @@ int dgrad_s2(const Geom& g, const void* dy, const void* w, void* dx, void* ws, s
     G.add = (const uint16_t*)g.add; G.ref = (const uint16_t*)g.ref; G.slope = g.slope;
     // a factor of 1 on both sides of the sign test needs no sign: the store path then reads the added tensor a second
     // time (from the cache) instead of streaming a third tensor of dx's size from memory
+    const bool sums = g.add && g.stats;
+    if (sums && (!dgrad_s2_fuses_skip_sums(g) || !g.ref || !(g.slope > 0.f))) return MI3D_ERR_UNSUPPORTED;
     if (g.add && g.slope == 1.f) G.ref = G.add;
+    if (sums) {   // the factor stays 1; the slope is that of the activation whose inverse enters the sums
+        G.ref = (const uint16_t*)g.ref; G.slope = 1.f; G.stat_slope = g.slope;
+        long long units; int n2;
+        dg2_layout(g, &units, &n2, &G.max_seg);
+        G.stat_part = (float*)((char*)ws + dg2_part_offset(g));
+        G.stat_key = (int*)(G.stat_part + (size_t)n2 * G.max_seg * 4 * 64);
+    }
     G.N = g.N; G.D = g.D; G.H = g.H; G.W = g.W; G.Cin = g.Cin; G.Cout = g.Cout;
     G.Do = g.Do; G.Ho = g.Ho; G.Wo = g.Wo; G.p = g.pD;
     G.QD = (g.D + 1) / 2;
@@ -417,10 +505,11 @@ int dgrad_s2(const Geom& g, const void* dy, const void* w, void* dx, void* ws, s
     static std::atomic<bool> attr_set{false};   // set once per process; a second thread racing here repeats an idempotent call
     if (!attr_set) {
         const int max_lds = 27 * 4 * 1024 + 2 * 8 * SLABV * 16;
-        const void* fns[8] = {(const void*)dgrad_s2_kernel<0, 2, false>, (const void*)dgrad_s2_kernel<1, 2, false>,
-                              (const void*)dgrad_s2_kernel<0, 4, false>, (const void*)dgrad_s2_kernel<1, 4, false>,
-                              (const void*)dgrad_s2_kernel<0, 4, true>, (const void*)dgrad_s2_kernel<1, 4, true>,
-                              (const void*)dgrad_s2_kernel<0, 4, false, true>, (const void*)dgrad_s2_kernel<1, 4, false, true>};
+        const void* fns[10] = {(const void*)dgrad_s2_kernel<0, 2, false>, (const void*)dgrad_s2_kernel<1, 2, false>,
+                               (const void*)dgrad_s2_kernel<0, 4, false>, (const void*)dgrad_s2_kernel<1, 4, false>,
+                               (const void*)dgrad_s2_kernel<0, 4, true>, (const void*)dgrad_s2_kernel<1, 4, true>,
+                               (const void*)dgrad_s2_kernel<0, 4, false, 1>, (const void*)dgrad_s2_kernel<1, 4, false, 1>,
+                               (const void*)dgrad_s2_kernel<0, 4, false, 2>, (const void*)dgrad_s2_kernel<1, 4, false, 2>};
         for (const void* f : fns) {
             hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, max_lds);
             if (e != hipSuccess) { note_hip_error(e); return MI3D_ERR_HIP; }
@@ -430,8 +519,15 @@ int dgrad_s2(const Geom& g, const void* dy, const void* w, void* dx, void* ws, s
     const bool part = G.NCO > 1;
     const bool fuse = g.add && !part;    // (Cout == 64: the only unchunked shape with an added gradient)
     if (g.add && !dgrad_s2_fuses_skip(g)) return MI3D_ERR_UNSUPPORTED;
-    if (fuse && g.pD == 0) dgrad_s2_kernel<0, 4, false, true><<<(unsigned)nwg, 256, lds, s>>>(G);
-    else if (fuse) dgrad_s2_kernel<1, 4, false, true><<<(unsigned)nwg, 256, lds, s>>>(G);
+    if (sums) {
+        if (g.pD == 0) dgrad_s2_kernel<0, 4, false, 2><<<(unsigned)nwg, 256, lds, s>>>(G);
+        else dgrad_s2_kernel<1, 4, false, 2><<<(unsigned)nwg, 256, lds, s>>>(G);
+        st = check_launch();
+        if (st) return st;
+        return sp_stats_finish(G.stat_part, G.stat_key, g.Cin, G.CiT, g.N, G.nwg, G.max_seg, 1.0 / ((double)g.D * g.H * g.W), 0.f, 1, g.stats, s);
+    }
+    if (fuse && g.pD == 0) dgrad_s2_kernel<0, 4, false, 1><<<(unsigned)nwg, 256, lds, s>>>(G);
+    else if (fuse) dgrad_s2_kernel<1, 4, false, 1><<<(unsigned)nwg, 256, lds, s>>>(G);
     else if (part && g.pD == 0) dgrad_s2_kernel<0, 4, true><<<(unsigned)nwg, 256, lds, s>>>(G);
     else if (part) dgrad_s2_kernel<1, 4, true><<<(unsigned)nwg, 256, lds, s>>>(G);
     else if (g.pD == 0 && KK == 2) dgrad_s2_kernel<0, 2, false><<<(unsigned)nwg, 256, lds, s>>>(G);

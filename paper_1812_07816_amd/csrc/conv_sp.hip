@@ -879,11 +879,11 @@ static bool sp_rows12(const Geom& g, int pass) {
     return units16 < 12ll * cus;
 }
 
-// statistics (mean, 1 / sqrt(var + eps)) from partial sums another kernel has written in the STATS = 1 layout (four
-// waves per workgroup): [workgroup][segment][wave][sum, sum of squares][32 couts], key = sample * CT + cout tile
-int sp_stats_finish(const float* part, const int* key, int Cout, int CT, int N, int nwg, int max_seg, double inv_v, float eps, float* stats,
-                    hipStream_t s) {
-    th16::sp_stats_finish_kernel<<<N * CT, 64 * th16::FIN_SLICES, 0, s>>>(part, key, Cout, CT, nwg, max_seg, inv_v, eps, 0, stats);
+// statistics (mean, 1 / sqrt(var + eps)), or with means = 1 the plain means of the two sums, from partial sums another
+// kernel has written in the STATS layout (four waves per workgroup): [workgroup][segment][wave][sum, sum of squares][32 couts], key = sample * CT + cout tile
+int sp_stats_finish(const float* part, const int* key, int Cout, int CT, int N, int nwg, int max_seg, double inv_v, float eps, int means,
+                    float* stats, hipStream_t s) {
+    th16::sp_stats_finish_kernel<<<N * CT, 64 * th16::FIN_SLICES, 0, s>>>(part, key, Cout, CT, nwg, max_seg, inv_v, eps, means, stats);
     return check_launch();
 }
 

@@ -89,8 +89,9 @@ int sp_conv(const Geom& g, int pass, const void* in, const void* w, void* out, v
 bool sp_fuses_dgrad_factor(const Geom& g);  // the forward LeakyReLU is always fused
 bool sp_fuses_stats(const Geom& g);         // instance-normalisation statistics of the forward output
 bool sp_fuses_bwd_sums(const Geom& g);      // sums of the instance-normalisation backward pass from the data gradient
-int sp_stats_finish(const float* part, const int* key, int Cout, int CT, int N, int nwg, int max_seg, double inv_v, float eps, float* stats,
-                    hipStream_t s);         // statistics from partial sums in the plane-streaming kernel's layout
+int sp_stats_finish(const float* part, const int* key, int Cout, int CT, int N, int nwg, int max_seg, double inv_v, float eps, int means,
+                    float* stats, hipStream_t s);   // statistics (or plain means) from partial sums in the plane-streaming kernel's layout
+bool dgrad_s2_fuses_skip_sums(const Geom& g);       // stride-2 data gradient with added gradient and the normalisation's backward sums
 bool c4_fwd_fuses_stats(const Geom& g);     // the first layer's forward kernel delivers them too
 // last step of a per-(sample, channel) reduction of two quantities: means from block sums part[n][block][2][C]
 int instnorm_finish_means(const float* part, int blocks, int C, int N, double inv_v, float* out, hipStream_t s);

@@ -174,6 +174,12 @@ class UNetStep:
                 # more channels spill and the reduction they save runs from the caches: 0.57 -> 0.58 ms at 96^3)
                 op["through_norm"] = bool(self.norm and alone and fused_bwd_sums and op["desc"].Cout == 32
                                           and mc.dgrad_insums_supported(op["desc"]))
+                # the stride-2 data gradient that adds the skip connection's second gradient (virtual concatenation):
+                # the gradient of the skip tensor is complete there, so the sums of its producer's normalisation can
+                # be taken there as well (the producer is the convolution right before this one)
+                op["skip_sums"] = bool(self.norm and fused_bwd_sums and virtual_cat and op["src"].id in skip_ids
+                                       and prev["kind"] == "conv" and prev["out"] is op["src"]
+                                       and mc.dgrad_insums_supported(op["desc"], with_add=True))
         # backward readers: conv f reads its input (weight gradient; LeakyReLU derivative of the layer below where the
         # data gradient applies it) and, unless the layer above has applied it already, its output (LeakyReLU
         # derivative); up and head read their input (weight gradient); the loss reads the logits
@@ -522,8 +528,14 @@ class UNetStep:
                         d_skip, _ = dskip.pop(op["src"].id)
                         if trace is not None:
                             trace[op["name"] + ".skip_add"] = d_skip.clone()
-                        mc.conv3d_dgrad_skip(op["desc"], da, self.w[op["w"]], d_skip, self._need(op["src"]),
-                                             1.0 if self.norm else SLOPE, nxt, self.ws)
+                        if op["skip_sums"]:
+                            # ... and the sums of the backward pass of the normalisation that produced the skip tensor
+                            mc.conv3d_dgrad_insums(op["desc"], da, self.w[op["w"]], self._need(op["src"]), SLOPE,
+                                                   self.ops[f - 1]["bwd_sums"], nxt, self.ws, add=d_skip)
+                            have_sums = True
+                        else:
+                            mc.conv3d_dgrad_skip(op["desc"], da, self.w[op["w"]], d_skip, self._need(op["src"]),
+                                                 1.0 if self.norm else SLOPE, nxt, self.ws)
                         premasked = not self.norm
                     else:
                         mc.conv3d_dgrad(op["desc"], da, self.w[op["w"]], nxt, self.ws)

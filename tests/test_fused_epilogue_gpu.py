@@ -78,6 +78,7 @@ SKIP_CASES = [
     (1, 4, 6, 6, 256, 320, 3, 2, 1),
     (1, 9, 21, 37, 32, 32, 3, 2, 1),      # Cout 32: two passes
     (1, 8, 16, 32, 32, 32, 3, 1, 1),      # stride 1: two passes
+    (2, 6, 10, 70, 64, 64, 3, 2, 1),      # two samples, two tiles of input channels, two patch columns
 ]
 
 
@@ -107,6 +108,36 @@ def test_dgrad_skip_is_the_data_gradient_plus_the_skip_gradient_through_the_acti
     # usual 2^-9.  Twice the tolerance of a plain pass covers both; the elementwise pass itself is pinned bit for bit
     # against numpy in the glue tests.
     assert e <= 2 * parity.TOL["bf16"]
+
+
+@pytest.mark.parametrize("case", [c for c in SKIP_CASES if c[5] == 64 and c[7] == 2])
+def test_dgrad_with_the_skip_gradient_and_the_sums_of_the_normalisation_backward_pass(device, case):
+    """conv3d_dgrad_insums with an added gradient: dx is the sum alone (the bits of conv3d_dgrad_skip with slope 1), and
+    the two means are those of the stored sum against the skip tensor (fp64 on the host)."""
+    N, D, H, W, Cin, Cout, k, s, p = case
+    x, w, dy = si.conv_case(96, 10 * SKIP_CASES.index(case), N, D, H, W, Cin, Cout, k, s, p, True)
+    add = si.normal(96, 10 * SKIP_CASES.index(case) + 5, x.shape, bf16=True)
+    a = si.bf16_round((x * np.linspace(0.2, 3.0, Cin)).astype(np.float32))     # the activated skip tensor (mixed signs)
+    desc = mc.make_desc(N, D, H, W, Cin, Cout, k, s, p, torch.bfloat16)
+    assert mc.dgrad_insums_supported(desc, with_add=True)
+    ad, wd, dyd, addd = (parity.to_device(t, True) for t in (a, w, dy, add))
+    sums = torch.full((N, Cin, 2), 7.0, device="cuda")
+    dx = mc.conv3d_dgrad_insums(desc, dyd, wd, ad, ou.SLOPE, sums, add=addd)
+    ref = torch.empty_like(dx)
+    mc.conv3d_dgrad_skip(desc, dyd, wd, addd, ad, 1.0, ref)
+    assert torch.equal(dx, ref)
+    again = torch.zeros_like(sums)
+    mc.conv3d_dgrad_insums(desc, dyd, wd, ad, ou.SLOPE, again, add=addd)
+    assert torch.equal(sums, again)                               # fixed summation order
+    dxh = parity.to_host(dx).astype(np.float64)
+    xhat = ou.lrelu_inverse(a.astype(np.float64))
+    g = np.where(xhat > 0, dxh, ou.SLOPE * dxh)
+    m1, m2 = g.mean(axis=(1, 2, 3)), (g * xhat).mean(axis=(1, 2, 3))
+    got = sums.cpu().numpy().astype(np.float64)
+    s1, s2 = g.std(axis=(1, 2, 3)), (g * xhat).std(axis=(1, 2, 3))
+    e1, e2 = (np.abs(got[..., 0] - m1) / s1).max(), (np.abs(got[..., 1] - m2) / s2).max()
+    print(case, f"mean g {e1:.2e} mean g xhat {e2:.2e}", flush=True)
+    assert e1 <= 1e-6 and e2 <= 1e-6
 
 
 def test_epilogue_argument_checks(device):
