@@ -64,3 +64,29 @@ def test_random_geometry_matches_oracle(device, case):
     print(case, names, {q: f"{v:.2e}" for q, v in errs.items()}, flush=True)
     for q, v in errs.items():
         assert v <= parity.TOL["bf16"], (case, q, v)
+
+
+def _tall_cases():
+    """3x3x3 stride-1 layers on planes of 10 to 60 rows and 9 to 100 columns: one to five patch rows of 16 or 12 rows,
+    last columns of patches that are paired two patch rows at a time (at most 16 columns inside the tensor) or not, few
+    and many units (chunked, streamed and resident weights).  Sampled oracle: every patch seam plus random positions."""
+    r = np.random.RandomState(181207817)
+    out = []
+    for _ in range(16):
+        cin, cout = int(r.choice([32, 64, 128, 256])), int(r.choice([32, 64, 128]))
+        d, h, w = int(r.randint(2, 7)), int(r.randint(10, 61)), int(r.randint(9, 101))
+        out.append((int(r.randint(1, 4)), d, h, w, cin, cout, 3, 1, int(r.choice([0, 1, 1, 2]))))
+    return out
+
+
+TALL = _tall_cases()
+
+
+@pytest.mark.parametrize("case", TALL, ids=[f"s1tall-{i}" for i in range(len(TALL))])
+def test_random_tall_planes_match_oracle(device, case):
+    N, D, H, W, Cin, Cout, k, s, p = case
+    errs = parity.run_case(98, 10 * TALL.index(case), N, D, H, W, Cin, Cout, k, s, p, bf16=True, full=False,
+                           n_samples=30000, n_wgrad_samples=48)
+    print(case, {q: f"{v:.2e}" for q, v in errs.items()}, flush=True)
+    for q, v in errs.items():
+        assert v <= parity.TOL["bf16"], (case, q, v)
