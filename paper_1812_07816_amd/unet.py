@@ -169,11 +169,10 @@ class UNetStep:
                 op["through_act"] = not self.norm and alone
                 # with the normalisation in between, the data gradient can still take the two sums of that
                 # normalisation's backward pass on its way out
-                # (taken where it pays: with 32 contracted channels the kernel has registers to spare and the tensors
-                # are the large ones, 1.78 -> 1.52 ms for data gradient + backward pass at 192^3, N = 2; the variants for
-                # more channels spill and the reduction they save runs from the caches: 0.57 -> 0.58 ms at 96^3)
-                op["through_norm"] = bool(self.norm and alone and fused_bwd_sums and op["desc"].Cout == 32
-                                          and mc.dgrad_insums_supported(op["desc"]))
+                # (measured at N = 2, data gradient + backward pass: 1.79 -> 1.49 ms at 192^3 with 32 channels, where the
+                # tensors come from memory; 0.575 -> 0.555 at 96^3 with 64, 0.268 -> 0.260 at 48^3 with 128: small gains
+                # where the reduction it saves runs from the caches)
+                op["through_norm"] = bool(self.norm and alone and fused_bwd_sums and mc.dgrad_insums_supported(op["desc"]))
                 # the stride-2 data gradient that adds the skip connection's second gradient (virtual concatenation):
                 # the gradient of the skip tensor is complete there, so the sums of its producer's normalisation can
                 # be taken there as well (the producer is the convolution right before this one)

@@ -28,7 +28,7 @@ def structured_and_random(shape, n_random, seed):
     channel) plus n_random uniform picks."""
     N, A, B, C, Ch = shape
     def pts(n):
-        c = {0, 1, n // 2, n - 2, n - 1, 15, 16, 31, 32, 33, 63, 64, 65}
+        c = {0, 1, n // 2, n - 2, n - 1, 11, 12, 15, 16, 23, 24, 31, 32, 33, 35, 36, 47, 48, 63, 64, 65}   # seams of 12-, 16- and 32-wide tiles
         return sorted(v for v in c if 0 <= v < n)
     chans = sorted({0, Ch // 2, Ch - 1})
     grid = np.array(np.meshgrid([0, N - 1], pts(A), pts(B), pts(C), chans, indexing="ij")).reshape(5, -1)

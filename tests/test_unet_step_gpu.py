@@ -441,7 +441,7 @@ def test_backward_sums_from_the_data_gradient_give_the_step_of_the_separate_redu
     x, labels, ws, xd, ld = _inputs(N, vol, CH, 5)
     a = unet.UNetStep(N, vol, CH, ws, xd, ld, swap=False, norm=True)
     b = unet.UNetStep(N, vol, CH, ws, xd, ld, swap=False, norm=True, fused_bwd_sums=False)
-    assert sum(1 for op in a.ops if op.get("through_norm")) == 3 and sum(1 for op in a.ops if op.get("skip_sums")) == 1
+    assert sum(1 for op in a.ops if op.get("through_norm")) >= 5 and sum(1 for op in a.ops if op.get("skip_sums")) == 1
     assert not any(op.get("through_norm") or op.get("skip_sums") for op in b.ops)
     a.run(update=False); b.run(update=False)
     torch.cuda.synchronize()
