@@ -51,9 +51,14 @@ struct K2Params {
 };
 
 // MODE 0: forward (gather), MODE 1: data gradient (scatter).  G: blocks of 32 output channels per panel.
-template <int MODE, int G>
+// ROWS (MODE 1, G = 4, 32 big-volume channels: a panel is the four taps (kh, kw) of one kd): the scattered voxels of a
+// wave's 32 small voxels are two runs of 64 neighbouring big voxels (rows 2 oh and 2 oh + 1); the wave passes them
+// through LDS so that a store instruction writes whole 64-byte voxels of 16 neighbours (four lanes per voxel) instead
+// of 16-byte pieces of 64 voxels.
+constexpr int K2_STG = 8192 + 256;   // per wave: 2 rows x 64 voxels x 64 B, and the 32 voxels' offsets
+template <int MODE, int G, bool ROWS = false>
 __global__ void __launch_bounds__(256, MODE == 1 ? 2 : 1) k2_kernel(K2Params P) {
-    extern __shared__ __attribute__((aligned(16))) char panel[];   // G * K16 KB
+    extern __shared__ __attribute__((aligned(16))) char panel[];   // G * K16 KB (+ 4 x K2_STG with ROWS)
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     const int group = blockIdx.x % P.NG, first_tile = blockIdx.x / P.NG, tile_step = P.nwg / P.NG;
     {
@@ -121,6 +126,10 @@ __global__ void __launch_bounds__(256, MODE == 1 ? 2 : 1) k2_kernel(K2Params P) 
             }
         }
         // stores: lane (voxel, half h) ends with channels 16 h .. 16 h + 15 of each block
+        char* stg = panel + (size_t)G * P.K16 * 1024 + (ROWS ? wave * K2_STG : 0);
+        if constexpr (ROWS) {
+            if (lane < 32) ((long long*)(stg + 8192))[lane] = cur.ok ? cur.big0 : -1;
+        }
 #pragma unroll
         for (int g = 0; g < G; ++g) {
             uint32_t o[8];
@@ -136,6 +145,12 @@ __global__ void __launch_bounds__(256, MODE == 1 ? 2 : 1) k2_kernel(K2Params P) 
                 u32x2 s1 = __builtin_amdgcn_permlane32_swap(o[2 * k + 1], o[2 * k + 5], false, false);
                 c[k].x = s0[0]; c[k].y = s1[0]; c[k].z = s0[1]; c[k].w = s1[1];
             }
+            if constexpr (ROWS) {   // block g is tap (kh, kw) = (g / 2, g % 2): big voxel 2 v + kw of row kh of the wave's run
+                char* q = stg + (g >> 1) * 4096 + (2 * (lane & 31) + (g & 1)) * 64 + h * 32;
+                *(uint4*)q = c[0];
+                *(uint4*)(q + 16) = c[1];
+                continue;
+            }
             const int nb = group * G + g;     // block of 32 output channels
             uint16_t* dst;
             if (MODE == 0) {
@@ -148,6 +163,25 @@ __global__ void __launch_bounds__(256, MODE == 1 ? 2 : 1) k2_kernel(K2Params P) 
             uint16_t* q = cur.ok ? dst : P.dump + lane * 16;
             *(uint4*)q = c[0];
             *(uint4*)(q + 8) = c[1];
+        }
+        if constexpr (ROWS) {
+            // same wave, LDS executes in order: only the compiler must not move the reads above the writes
+            asm volatile("" ::: "memory");
+            __builtin_amdgcn_wave_barrier();
+            asm volatile("" ::: "memory");
+#pragma unroll
+            for (int kh = 0; kh < 2; ++kh)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const uint4 v = *(const uint4*)(stg + kh * 4096 + i * 1024 + lane * 16);
+                    const int bv = i * 16 + (lane >> 2);                       // big voxel of the run; its small voxel is bv / 2
+                    const long long b0 = ((const long long*)(stg + 8192))[bv >> 1];
+                    uint16_t* dst = P.out + b0 + tap_off(group * 4 + kh * 2 + (bv & 1)) + (lane & 3) * 8;
+                    *(uint4*)(b0 >= 0 ? dst : P.dump + lane * 8) = v;
+                }
+            asm volatile("" ::: "memory");
+            __builtin_amdgcn_wave_barrier();   // the next tile's writes stay behind these reads
+            asm volatile("" ::: "memory");
         }
         cur = nxt_w;
         src = src_next;
@@ -398,19 +432,22 @@ int k2_conv(const Geom& g, int pass, const void* a, const void* w, void* out, vo
     if (per_group < 1) per_group = 1;
     if (per_group > tiles) per_group = tiles;
     P.nwg = (int)(per_group * P.NG);
-    const size_t lds = (size_t)G * P.K16 * 1024;
+    // scatter with 32 big-volume channels and a panel per kd: whole voxels per store instruction through LDS
+    const bool rows = mode == 1 && G == 4 && g.Cin == 32;
+    const size_t lds = (size_t)G * P.K16 * 1024 + (rows ? 4 * K2_STG : 0);
     static std::atomic<bool> attr_set{false};   // set once per process; a second thread racing here repeats an idempotent call
     if (!attr_set) {
         hipError_t e = hipSuccess;
         const void* fns0[3] = {(const void*)k2_kernel<0, 1>, (const void*)k2_kernel<0, 2>, (const void*)k2_kernel<0, 4>};
-        const void* fns1[3] = {(const void*)k2_kernel<1, 1>, (const void*)k2_kernel<1, 2>, (const void*)k2_kernel<1, 4>};
+        const void* fns1[4] = {(const void*)k2_kernel<1, 1>, (const void*)k2_kernel<1, 2>, (const void*)k2_kernel<1, 4>, (const void*)k2_kernel<1, 4, true>};
         for (int i = 0; i < 3 && e == hipSuccess; ++i) e = hipFuncSetAttribute(fns0[i], hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);
-        for (int i = 0; i < 3 && e == hipSuccess; ++i) e = hipFuncSetAttribute(fns1[i], hipFuncAttributeMaxDynamicSharedMemorySize, 64 * 1024);
+        for (int i = 0; i < 4 && e == hipSuccess; ++i) e = hipFuncSetAttribute(fns1[i], hipFuncAttributeMaxDynamicSharedMemorySize, 64 * 1024 + 4 * K2_STG);
         if (e != hipSuccess) { note_hip_error(e); return MI3D_ERR_HIP; }
         attr_set = true;
     }
 #define K2_LAUNCH(M, GG) k2_kernel<M, GG><<<(unsigned)P.nwg, 256, lds, s>>>(P)
     if (mode == 0) { if (G == 4) K2_LAUNCH(0, 4); else if (G == 2) K2_LAUNCH(0, 2); else K2_LAUNCH(0, 1); }
+    else if (rows) k2_kernel<1, 4, true><<<(unsigned)P.nwg, 256, lds, s>>>(P);
     else { if (G == 4) K2_LAUNCH(1, 4); else if (G == 2) K2_LAUNCH(1, 2); else K2_LAUNCH(1, 1); }
 #undef K2_LAUNCH
     return check_launch();
