@@ -359,7 +359,7 @@ class CallRecorder:
                 e0.record()
                 r = _fn(desc, *a, **kw)
                 e1.record()
-                self.calls.append((desc, _pass, e0, e1, _extra))
+                self.calls.append((desc, _pass, e0, e1, _extra + (1 if kw.get("add") is not None else 0)))
                 return r
             setattr(self.mc, name, wrapped)
         return self
