@@ -422,16 +422,18 @@ def fp32_steps():
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) * 1e3 / steps
 
-    for vol, config, budgets in ((192, 5, (16.0, 16e9 / 2 ** 30, 12.0)), (208, 6, (16.0,))):
+    # (last row: the paper's block, convolution -> instance normalisation -> LeakyReLU, in fp32)
+    for vol, config, budgets, norm in ((192, 5, (16.0, 16e9 / 2 ** 30, 12.0), False), (208, 6, (16.0,), False), (192, 5, (16.0,), True)):
         x = torch.from_numpy(si.normal(config, 0, (N, vol, vol, vol, 4), bf16=True)).cuda()
         labels = torch.from_numpy(si.ellipsoid_labels(config, 1, N, vol)).cuda()
         ws = si.unet_weights(config, ch)
-        plain = unet.UNetStep(N, vol, ch, ws, x, labels, swap=False, dtype=torch.float32)
+        plain = unet.UNetStep(N, vol, ch, ws, x, labels, swap=False, dtype=torch.float32, norm=norm)
         plain.run(update=False)
         torch.cuda.synchronize()
         ref = plain.dw32.clone()
         ms0 = timed(plain)
-        row = {"workload": f"5-level 3D U-Net training step at {vol}^3, N={N}, fp32 (convolution -> LeakyReLU, soft Dice, SGD)",
+        block = "convolution -> instance normalisation -> LeakyReLU" if norm else "convolution -> LeakyReLU"
+        row = {"workload": f"5-level 3D U-Net training step at {vol}^3, N={N}, fp32 ({block}, soft Dice, SGD)", "instance_norm": norm,
                "ms_per_step_no_swap": ms0, "conv_tflops_no_swap": plain.flops / ms0 / 1e9,
                "frac_of_fp32_mfma_peak": plain.flops / ms0 / 1e9 / MFMA_F32_PEAK_TFLOPS, "loss": float(plain.loss.item()), "budgets": []}
         del plain
@@ -440,7 +442,7 @@ def fp32_steps():
             for ev, name in ((sw.EVICT_SWAP, "swap"), (sw.EVICT_HYBRID, "hybrid")):
                 ref_bytes = ref.numel() * ref.element_size()    # the bench's own copy of the reference gradients is not the step's
                 st = unet.UNetStep(N, vol, ch, ws, x, labels, swap=True, budget_bytes=int(gib * 2 ** 30) + ref_bytes, lookahead=1, eviction=ev,
-                                   dtype=torch.float32)
+                                   dtype=torch.float32, norm=norm)
                 st.calibrate(link_gbs=55.0)
                 measured = st.fit_budget() - ref_bytes     # peak of the device allocator over a step (everything but the reference copy)
                 st.engine.set_verify(True)
@@ -736,7 +738,7 @@ def main():
         out["level0_192"] = level0_chain(args)
         out["fp32"] = fp32_steps()
         # the stated targets, spelled out
-        rows16 = [dict(volume=r["workload"].split(" at ")[1].split(",")[0], eviction=b["eviction"], n_swapped=b["n_swapped"], n_recomputed=b["n_recomputed"],
+        rows16 = [dict(volume=r["workload"].split(" at ")[1].split(",")[0], instance_norm=r["instance_norm"], eviction=b["eviction"], n_swapped=b["n_swapped"], n_recomputed=b["n_recomputed"],
                        bytes_out=b["bytes_out"], hidden_frac=b["hidden_frac"], measured_peak_device_bytes=b["measured_peak_device_bytes"],
                        measured_peak_within_budget=b["measured_peak_within_budget"], slowdown_vs_unswapped=b["ms_per_step"] / r["ms_per_step_no_swap"])
                   for r in out["fp32"]["runs"] for b in r["budgets"] if b["budget_gib"] == 16.0]

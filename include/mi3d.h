@@ -289,6 +289,13 @@ int mi3d_instnorm_lrelu_bwd(void *da, const void *a, const float *stats, int N, 
                             void *ws, size_t ws_bytes, void *stream);
 int mi3d_instnorm_lrelu_bwd_sums(void *da, const void *a, const float *stats, const float *sums, int N, size_t voxels,
                                  int C, float slope, void *stream);
+/* The same three passes on fp32 tensors (the precision Section 4.1's network presumably ran in); statistics,
+ * workspace, order of the sums and error codes as above. */
+int mi3d_instnorm_stats_f32(const void *z, int N, size_t voxels, int C, float eps, float *stats, void *ws,
+                            size_t ws_bytes, void *stream);
+int mi3d_instnorm_lrelu_fwd_f32(void *z, const float *stats, int N, size_t voxels, int C, float slope, void *stream);
+int mi3d_instnorm_lrelu_bwd_f32(void *da, const void *a, const float *stats, int N, size_t voxels, int C, float slope,
+                                void *ws, size_t ws_bytes, void *stream);
 
 /* w[i] <- w[i] - lr * dw[i] on the fp32 master weights; w_bf16[i] <- the
  * updated value rounded to bf16 (the copy the bf16 convolutions read; NULL in

@@ -65,6 +65,9 @@ SIGNATURES = {
     "mi3d_instnorm_stats": (_i, [_vp, _i, _sz, _i, ctypes.c_float, _vp, _vp, _sz, _vp]),
     "mi3d_instnorm_lrelu_fwd": (_i, [_vp, _vp, _i, _sz, _i, ctypes.c_float, _vp]),
     "mi3d_instnorm_lrelu_bwd": (_i, [_vp, _vp, _vp, _i, _sz, _i, ctypes.c_float, _vp, _sz, _vp]),
+    "mi3d_instnorm_stats_f32": (_i, [_vp, _i, _sz, _i, ctypes.c_float, _vp, _vp, _sz, _vp]),
+    "mi3d_instnorm_lrelu_fwd_f32": (_i, [_vp, _vp, _i, _sz, _i, ctypes.c_float, _vp]),
+    "mi3d_instnorm_lrelu_bwd_f32": (_i, [_vp, _vp, _vp, _i, _sz, _i, ctypes.c_float, _vp, _sz, _vp]),
     "mi3d_adam_update": (_i, [_vp, _vp, _vp, _vp, _vp, _sz, ctypes.c_float, ctypes.c_float, ctypes.c_float, ctypes.c_float, _i, _vp]),
     "mi3d_conv3d_workspace_bytes": (_sz, [_pd, _i]),
     "mi3d_conv3d_fwd": (_i, [_pd, _vp, _vp, _vp, _vp, _sz, _vp]),

@@ -193,7 +193,8 @@ int mi3d_conv3d_kernel_name(const mi3d_conv_desc* desc, int pass, char* buf, siz
     if (st) return st;
     if (!buf || buf_len == 0 || pass < 0 || pass > 2) return MI3D_ERR_INVALID_ARG;
     Kernel k = choose(g, pass);
-    snprintf(buf, buf_len, "%s", kernel_name(k));
+    // (the fp32 dispatcher hands 1x1x1 layers with a handful of output channels to VALU kernels of its own)
+    snprintf(buf, buf_len, "%s", k == K_F32 && pointwise_f32_supported(g) ? "valu_pointwise_head_f32" : kernel_name(k));
     return MI3D_OK;
 }
 

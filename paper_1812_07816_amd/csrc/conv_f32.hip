@@ -409,14 +409,23 @@ bool f32_supported(const Geom& g, int pass) {
     return true;
 }
 
+// 1x1x1 layers with a handful of output channels (the segmentation head) run through plain VALU kernels: with 3 of 32
+// MFMA rows in use the matrix cores would do ten times the work (measured at 192^3, N = 2: 0.74 / 1.81 / 3.06 ms for the
+// three passes on the matrix cores).  A call with an added gradient or a two-tensor operand keeps the general kernel.
+static bool f32_head(const Geom& g) { return pointwise_f32_supported(g) && !g.add && !g.hi; }
+
 size_t f32_workspace_bytes(const Geom& g, int pass) {
     if (!f32_supported(g, pass)) return 0;
+    size_t b;
     if (pass == MI3D_PASS_WGRAD) {
         WgParams P;
         wgrad_layout(g, &P);
-        return (size_t)P.S * g.w_elems() * sizeof(float);
+        b = (size_t)P.S * g.w_elems() * sizeof(float);
+    } else {
+        b = pack_bytes(g, pass);
     }
-    return pack_bytes(g, pass);
+    const size_t h = pointwise_f32_workspace_bytes(g, pass);   // (0 where the head kernels do not apply)
+    return b > h ? b : h;
 }
 
 bool f32_takes_halves(const Geom& g, int pass) {   // virtual concatenation: halves of Cin in multiples of 32 channels
@@ -460,6 +469,7 @@ static int launch_gconv(GcParams& P, hipStream_t s) {
 
 // forward (in = x, out = y) and data gradient (in = dy, out = dx)
 int f32_conv(const Geom& g, int pass, const void* in, const void* w, void* out, void* ws, size_t ws_bytes, hipStream_t s) {
+    if (f32_head(g)) return pointwise_f32_conv(g, pass, in, w, out, ws, ws_bytes, s);
     if (ws_bytes < f32_workspace_bytes(g, pass)) return MI3D_ERR_WORKSPACE;
     const bool dgrad = pass == MI3D_PASS_DGRAD;
     const int T = (int)g.taps();
@@ -530,6 +540,7 @@ int f32_conv(const Geom& g, int pass, const void* in, const void* w, void* out, 
 }
 
 int f32_wgrad(const Geom& g, const void* x, const void* dy, float* dw, void* ws, size_t ws_bytes, hipStream_t s) {
+    if (f32_head(g)) return pointwise_f32_conv(g, MI3D_PASS_WGRAD, x, dy, dw, ws, ws_bytes, s);
     if (ws_bytes < f32_workspace_bytes(g, MI3D_PASS_WGRAD)) return MI3D_ERR_WORKSPACE;
     WgParams P;
     wgrad_layout(g, &P);

@@ -193,6 +193,138 @@ __global__ void __launch_bounds__(256) pw_wgrad_kernel(const uint16_t* __restric
     }
 }
 
+// ---- the same three passes for fp32 tensors (a piece is 8 channels = 32 bytes, two 16-byte accesses; a thread keeps
+//      the same channels throughout, so its weights stay in registers) ------------------------------------------------
+__device__ __forceinline__ void load8f(const float* p, float (&f)[8]) {
+    const float4 a = *(const float4*)p, b = *(const float4*)(p + 4);
+    f[0] = a.x; f[1] = a.y; f[2] = a.z; f[3] = a.w; f[4] = b.x; f[5] = b.y; f[6] = b.z; f[7] = b.w;
+}
+
+// y = lrelu(x . w) (slope 1: none); lanes of a voxel summed in a fixed butterfly
+template <int CO>
+__global__ void __launch_bounds__(256) pwf_fwd_kernel(const float* __restrict__ x, const float* __restrict__ w, float* __restrict__ y,
+                                                      long long voxels, int Cin, float slope) {
+    const int per = Cin / 8;
+    const long long pieces = voxels * per, T = (long long)gridDim.x * 256;
+    const int c0 = (threadIdx.x % per) * 8;
+    float wr[CO][8];
+#pragma unroll
+    for (int co = 0; co < CO; ++co) load8f(w + co * Cin + c0, wr[co]);
+    constexpr int U = 4;
+    for (long long i0 = (long long)blockIdx.x * 256 + threadIdx.x; i0 < pieces; i0 += U * T) {   // (uniform over the lanes of a voxel)
+        float f[U][8];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const long long i = i0 + u * T;
+            load8f(x + (i < pieces ? i : pieces - 1) * 8, f[u]);   // clamped: loaded, never stored
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const long long i = i0 + u * T;
+            float acc[CO];
+#pragma unroll
+            for (int co = 0; co < CO; ++co) {
+                acc[co] = 0.f;
+#pragma unroll
+                for (int j = 0; j < 8; ++j) acc[co] = fmaf(f[u][j], wr[co][j], acc[co]);
+            }
+            for (int off = per >> 1; off > 0; off >>= 1)
+#pragma unroll
+                for (int co = 0; co < CO; ++co) acc[co] += __shfl_xor(acc[co], off, 64);
+            if (c0 == 0 && i < pieces) {
+                const long long v = i / per;
+#pragma unroll
+                for (int co = 0; co < CO; ++co) y[v * CO + co] = fmaxf(acc[co], slope * acc[co]);
+            }
+        }
+    }
+}
+
+// dx = (dy . w^T) * (ref > 0 ? 1 : slope) (no ref: no factor)
+template <int CO>
+__global__ void __launch_bounds__(256) pwf_dgrad_kernel(const float* __restrict__ dy, const float* __restrict__ w, float* __restrict__ dx,
+                                                        long long voxels, int Cin, const float* __restrict__ ref, float slope) {
+    const int per = Cin / 8;
+    const long long pieces = voxels * per, T = (long long)gridDim.x * 256;
+    const int c0 = (threadIdx.x % per) * 8;
+    float wr[CO][8];
+#pragma unroll
+    for (int co = 0; co < CO; ++co) load8f(w + co * Cin + c0, wr[co]);
+    constexpr int U = 4;
+    for (long long i0 = (long long)blockIdx.x * 256 + threadIdx.x; i0 < pieces; i0 += U * T) {
+        float g[U][CO], m[U][8];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const long long i = i0 + u * T, ic = i < pieces ? i : pieces - 1;
+            const long long v = ic / per;
+#pragma unroll
+            for (int co = 0; co < CO; ++co) g[u][co] = dy[v * CO + co];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) m[u][j] = 1.f;
+            if (ref) load8f(ref + ic * 8, m[u]);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const long long i = i0 + u * T;
+            if (i >= pieces) continue;
+            float o[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                float a = 0.f;
+#pragma unroll
+                for (int co = 0; co < CO; ++co) a = fmaf(g[u][co], wr[co][j], a);
+                o[j] = m[u][j] > 0.f ? a : slope * a;
+            }
+            *(float4*)(dx + i * 8) = make_float4(o[0], o[1], o[2], o[3]);
+            *(float4*)(dx + i * 8 + 4) = make_float4(o[4], o[5], o[6], o[7]);
+        }
+    }
+}
+
+// per-block partial sums of dw over a strided voxel range, as pw_wgrad_kernel
+template <int CO>
+__global__ void __launch_bounds__(256) pwf_wgrad_kernel(const float* __restrict__ x, const float* __restrict__ dy, float* __restrict__ part,
+                                                        long long voxels, int Cin) {
+    __shared__ float red[256 * 8];
+    const int per = Cin / 8, groups = 256 / per;
+    const int t = threadIdx.x, g = t / per, c8 = t % per;
+    float acc[CO][8];
+#pragma unroll
+    for (int co = 0; co < CO; ++co)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[co][j] = 0.f;
+    const long long V = (long long)gridDim.x * groups;
+    constexpr int U = 2;
+    for (long long v0 = (long long)blockIdx.x * groups + g; v0 < voxels; v0 += U * V) {
+        float f[U][8], gv[U][CO];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const long long v = v0 + u * V, vc = v < voxels ? v : voxels - 1;
+            load8f(x + vc * Cin + c8 * 8, f[u]);
+#pragma unroll
+            for (int co = 0; co < CO; ++co) gv[u][co] = v < voxels ? dy[vc * CO + co] : 0.f;   // past the end: adds zeros
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int co = 0; co < CO; ++co)
+#pragma unroll
+                for (int j = 0; j < 8; ++j) acc[co][j] = fmaf(gv[u][co], f[u][j], acc[co][j]);
+    }
+    for (int co = 0; co < CO; ++co) {
+        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < 8; ++j) red[t * 8 + j] = acc[co][j];
+        __syncthreads();
+        if (t < Cin) {
+            const int cc8 = t / 8, j = t % 8;
+            float a = 0.f;
+            for (int gg = 0; gg < groups; ++gg) a += red[(gg * per + cc8) * 8 + j];
+            part[((long long)blockIdx.x * CO + co) * Cin + t] = a;
+        }
+    }
+}
+
 }  // namespace
 
 bool pointwise_supported(const Geom& g) {
@@ -250,6 +382,56 @@ static int pw_run(const Geom& g, int pass, const void* a, const void* b, void* o
     if (st) return st;
     const long long n = (long long)g.Cout * g.Cin;
     return reduce_partials((const float*)ws, (float*)out, n, blocks, s);
+}
+
+static int pwf_wgrad_blocks(const Geom& g) {
+    long long groups = 256 / (g.Cin / 8);
+    long long b = (g.in_voxels() + groups - 1) / groups;
+    return (int)(b < 2048 ? b : 2048);
+}
+
+bool pointwise_f32_supported(const Geom& g) {
+    if (g.dtype != MI3D_F32 || g.kD != 1 || g.kH != 1 || g.kW != 1) return false;
+    if (g.sD != 1 || g.sH != 1 || g.sW != 1 || g.pD || g.pH || g.pW) return false;
+    // (lanes of a voxel must share a wave: Cin/8 a power of two)
+    return g.Cin % 8 == 0 && g.Cin <= MAXCI && g.Cout <= MAXCO && 64 % (g.Cin / 8) == 0 && g.in_voxels() * (g.Cin / 8) / 256 <= 0x7fffffffll;
+}
+
+size_t pointwise_f32_workspace_bytes(const Geom& g, int pass) {
+    if (!pointwise_f32_supported(g) || pass != MI3D_PASS_WGRAD) return 0;
+    return (size_t)pwf_wgrad_blocks(g) * g.Cout * g.Cin * sizeof(float);
+}
+
+template <int CO>
+static int pwf_run(const Geom& g, int pass, const void* a, const void* b, void* out, void* ws, hipStream_t s) {
+    const long long vox = g.in_voxels();
+    long long blocks = (vox * (g.Cin / 8) + 4 * 256 - 1) / (4 * 256);
+    if (blocks > 8192) blocks = 8192;
+    if (pass == MI3D_PASS_FWD) {
+        pwf_fwd_kernel<CO><<<(unsigned)blocks, 256, 0, s>>>((const float*)a, (const float*)b, (float*)out, vox, g.Cin, g.slope);
+        return check_launch();
+    }
+    if (pass == MI3D_PASS_DGRAD) {
+        pwf_dgrad_kernel<CO><<<(unsigned)blocks, 256, 0, s>>>((const float*)a, (const float*)b, (float*)out, vox, g.Cin, (const float*)g.ref, g.slope);
+        return check_launch();
+    }
+    const int nb = pwf_wgrad_blocks(g);
+    pwf_wgrad_kernel<CO><<<nb, 256, 0, s>>>((const float*)a, (const float*)b, (float*)ws, vox, g.Cin);
+    int st = check_launch();
+    if (st) return st;
+    return reduce_partials((const float*)ws, (float*)out, (long long)g.Cout * g.Cin, nb, s);
+}
+
+// the fp32 head: same arguments as pointwise_conv; applies the optional LeakyReLU (forward) or derivative factor (data gradient)
+int pointwise_f32_conv(const Geom& g, int pass, const void* a, const void* b, void* out, void* ws, size_t ws_bytes, hipStream_t s) {
+    if (!pointwise_f32_supported(g) || g.add || g.hi) return MI3D_ERR_UNSUPPORTED;
+    if (ws_bytes < pointwise_f32_workspace_bytes(g, pass)) return MI3D_ERR_WORKSPACE;
+    switch (g.Cout) {
+        case 1: return pwf_run<1>(g, pass, a, b, out, ws, s);
+        case 2: return pwf_run<2>(g, pass, a, b, out, ws, s);
+        case 3: return pwf_run<3>(g, pass, a, b, out, ws, s);
+        default: return pwf_run<4>(g, pass, a, b, out, ws, s);
+    }
 }
 
 // fwd: a = x, b = w, out = y.  dgrad: a = dy, b = w, out = dx.  wgrad: a = x, b = dy, out = dw.

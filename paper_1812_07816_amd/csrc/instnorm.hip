@@ -5,8 +5,9 @@
 // Only the activated tensor a is kept for the backward pass: LeakyReLU with a positive slope is invertible, so
 // xhat = a > 0 ? a : a / slope is taken back from it, and the statistics (N x C x 2 floats) ride along.  Backward:
 //   g = da * lrelu'(xhat),   dz = rstd * (g - mean_v(g) - xhat * mean_v(g * xhat)).
-// All four steps stream NDHWC bf16 tensors once with 16-byte accesses; the two reductions use a fixed partition of
-// the voxels into blocks and add the block sums in index order in double (bit-reproducible).
+// All four steps stream NDHWC tensors once with 16-byte accesses (bf16, or fp32 in the entry points named _f32:
+// the same kernels on 32-byte pieces); the two reductions use a fixed partition of the voxels into blocks and add
+// the block sums in index order in double (bit-reproducible).
 #include "mi3d_internal.h"
 
 namespace mi3d {
@@ -35,13 +36,32 @@ __device__ __forceinline__ uint4 pack8(const float (&f)[8]) {
     return uint4{w[0], w[1], w[2], w[3]};
 }
 
+// A piece = the 8 channels a thread handles at a time: one 16-byte word of bf16, or two of fp32.
+struct Raw32 { float4 lo, hi; };
+template <typename T> struct Piece;
+template <> struct Piece<uint16_t> {
+    typedef uint4 raw;
+    static __device__ __forceinline__ void unpack(const raw& v, float (&f)[8]) { unpack8(v, f); }
+    static __device__ __forceinline__ raw pack(const float (&f)[8]) { return pack8(f); }
+};
+template <> struct Piece<float> {
+    typedef Raw32 raw;
+    static __device__ __forceinline__ void unpack(const raw& v, float (&f)[8]) {
+        f[0] = v.lo.x; f[1] = v.lo.y; f[2] = v.lo.z; f[3] = v.lo.w; f[4] = v.hi.x; f[5] = v.hi.y; f[6] = v.hi.z; f[7] = v.hi.w;
+    }
+    static __device__ __forceinline__ raw pack(const float (&f)[8]) {
+        return Raw32{float4{f[0], f[1], f[2], f[3]}, float4{f[4], f[5], f[6], f[7]}};
+    }
+};
+
 // Sums of two quantities per channel over the voxel range of block (blockIdx.x, sample blockIdx.y).
 // MODE 0: (z, z^2) of one tensor.  MODE 1: (g, g * xhat) with g = da * lrelu'(xhat), xhat from a.
 // Thread t handles the 8 channels of piece t % P of voxels t / P, t / P + VPB, ...; the per-thread sums of a piece
 // are added over the voxel lanes in lane order.  part: [n][block][2][C].
-template <int MODE>
-__global__ void __launch_bounds__(256) in_reduce_kernel(const uint16_t* __restrict__ a, const uint16_t* __restrict__ da, long long voxels, int C,
+template <int MODE, typename T>
+__global__ void __launch_bounds__(256) in_reduce_kernel(const T* __restrict__ a, const T* __restrict__ da, long long voxels, int C,
                                                         float slope, float* __restrict__ part) {
+    typedef typename Piece<T>::raw raw;
     __shared__ float red[256 * 8];
     const int P = C / 8, VPB = 256 / P;         // pieces per voxel, voxels per pass of the block
     const int t = threadIdx.x, p = t % P, lane = t / P;
@@ -53,15 +73,15 @@ __global__ void __launch_bounds__(256) in_reduce_kernel(const uint16_t* __restri
     const float inv_slope = 1.f / slope;
     // one voxel's contribution; the loop below requests four voxels ahead of the arithmetic (the sums are added in
     // voxel order either way)
-    auto add_voxel = [&](const uint4& av, const uint4& gv) {
+    auto add_voxel = [&](const raw& av, const raw& gv) {
         float x[8];
-        unpack8(av, x);
+        Piece<T>::unpack(av, x);
         if (MODE == 0) {
 #pragma unroll
             for (int j = 0; j < 8; ++j) { s1[j] += x[j]; s2[j] = fmaf(x[j], x[j], s2[j]); }
         } else {
             float g[8];
-            unpack8(gv, g);
+            Piece<T>::unpack(gv, g);
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
                 const float gg = x[j] > 0.f ? g[j] : slope * g[j];
@@ -75,18 +95,18 @@ __global__ void __launch_bounds__(256) in_reduce_kernel(const uint16_t* __restri
         const long long base = (long long)n * voxels * C + p * 8;
         long long v = v0 + lane;
         for (; v + 3 * VPB < v1; v += 4 * VPB) {
-            uint4 av[4], gv[4];
+            raw av[4], gv[4];
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
-                av[u] = *(const uint4*)(a + base + (v + u * VPB) * C);
-                gv[u] = MODE == 0 ? av[u] : *(const uint4*)(da + base + (v + u * VPB) * C);
+                av[u] = *(const raw*)(a + base + (v + u * VPB) * C);
+                gv[u] = MODE == 0 ? av[u] : *(const raw*)(da + base + (v + u * VPB) * C);
             }
 #pragma unroll
             for (int u = 0; u < 4; ++u) add_voxel(av[u], gv[u]);
         }
         for (; v < v1; v += VPB) {
-            const uint4 av = *(const uint4*)(a + base + v * C);
-            add_voxel(av, MODE == 0 ? av : *(const uint4*)(da + base + v * C));
+            const raw av = *(const raw*)(a + base + v * C);
+            add_voxel(av, MODE == 0 ? av : *(const raw*)(da + base + v * C));
         }
     }
     float* out = part + ((long long)n * gridDim.x + blockIdx.x) * 2 * C;
@@ -140,31 +160,37 @@ __global__ void __launch_bounds__(256) in_finish_kernel(const float* __restrict_
 }
 
 // a <- lrelu((z - mean) * rstd), in place.  One sample per blockIdx.y; its statistics sit in LDS.
-__global__ void __launch_bounds__(256) in_fwd_kernel(uint4* __restrict__ z, const float* __restrict__ stats, long long pieces, int C, float slope) {
+template <typename T>
+__global__ void __launch_bounds__(256) in_fwd_kernel(typename Piece<T>::raw* __restrict__ z, const float* __restrict__ stats, long long pieces, int C,
+                                                     float slope) {
+    typedef typename Piece<T>::raw raw;
     __shared__ float st[2 * MAXC];
     const int n = blockIdx.y, P = C / 8;
     for (int i = threadIdx.x; i < 2 * C; i += 256) st[i] = stats[(long long)n * 2 * C + i];
     __syncthreads();
-    uint4* zn = z + (long long)n * pieces;
+    raw* zn = z + (long long)n * pieces;
     const long long i0 = (long long)blockIdx.x * 256 + threadIdx.x;
     int pc = (int)(i0 % P);                                  // piece within the voxel, advanced without a division
     const int pstep = (int)(((long long)gridDim.x * 256) % P);
     for (long long i = i0; i < pieces; i += (long long)gridDim.x * 256, pc = pc + pstep >= P ? pc + pstep - P : pc + pstep) {
         const int c0 = pc * 8;
         float x[8];
-        unpack8(zn[i], x);
+        Piece<T>::unpack(zn[i], x);
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             const float xh = (x[j] - st[2 * (c0 + j)]) * st[2 * (c0 + j) + 1];
             x[j] = fmaxf(xh, slope * xh);
         }
-        zn[i] = pack8(x);
+        zn[i] = Piece<T>::pack(x);
     }
 }
 
 // da <- dz = rstd * (g - mean g - xhat * mean(g xhat)), in place; st: (mean, rstd), s2: (mean g, mean g xhat)
-__global__ void __launch_bounds__(256) in_bwd_kernel(uint4* __restrict__ da, const uint4* __restrict__ a, const float* __restrict__ stats,
-                                                     const float* __restrict__ sums, long long pieces, int C, float slope) {
+template <typename T>
+__global__ void __launch_bounds__(256) in_bwd_kernel(typename Piece<T>::raw* __restrict__ da, const typename Piece<T>::raw* __restrict__ a,
+                                                     const float* __restrict__ stats, const float* __restrict__ sums, long long pieces, int C,
+                                                     float slope) {
+    typedef typename Piece<T>::raw raw;
     __shared__ float rs[MAXC], m1[MAXC], m2[MAXC];
     const int n = blockIdx.y, P = C / 8;
     for (int i = threadIdx.x; i < C; i += 256) {
@@ -173,8 +199,8 @@ __global__ void __launch_bounds__(256) in_bwd_kernel(uint4* __restrict__ da, con
         m2[i] = sums[((long long)n * C + i) * 2 + 1];
     }
     __syncthreads();
-    uint4* dn = da + (long long)n * pieces;
-    const uint4* an = a + (long long)n * pieces;
+    raw* dn = da + (long long)n * pieces;
+    const raw* an = a + (long long)n * pieces;
     const float inv_slope = 1.f / slope;
     const long long i0 = (long long)blockIdx.x * 256 + threadIdx.x;
     int pc = (int)(i0 % P);
@@ -182,15 +208,15 @@ __global__ void __launch_bounds__(256) in_bwd_kernel(uint4* __restrict__ da, con
     for (long long i = i0; i < pieces; i += (long long)gridDim.x * 256, pc = pc + pstep >= P ? pc + pstep - P : pc + pstep) {
         const int c0 = pc * 8;
         float g[8], x[8];
-        unpack8(dn[i], g);
-        unpack8(an[i], x);
+        Piece<T>::unpack(dn[i], g);
+        Piece<T>::unpack(an[i], x);
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             const float gg = x[j] > 0.f ? g[j] : slope * g[j];
             const float xh = x[j] > 0.f ? x[j] : x[j] * inv_slope;
             g[j] = rs[c0 + j] * (gg - m1[c0 + j] - xh * m2[c0 + j]);
         }
-        dn[i] = pack8(g);
+        dn[i] = Piece<T>::pack(g);
     }
 }
 
@@ -213,6 +239,49 @@ int instnorm_finish_means(const float* part, int blocks, int C, int N, double in
     return check_launch();
 }
 
+namespace {
+
+template <typename T>
+int in_stats(const void* z, int N, size_t voxels, int C, float eps, float* stats, void* ws, size_t ws_bytes, void* stream) {
+    if (!z || !stats || !ws || !a16(z) || !in_args_ok(N, voxels, C) || !(eps > 0.f)) return MI3D_ERR_INVALID_ARG;
+    if (ws_bytes < mi3d_instnorm_workspace_bytes(N, C)) return MI3D_ERR_WORKSPACE;
+    const int blocks = in_blocks(voxels);
+    in_reduce_kernel<0, T><<<dim3(blocks, N), 256, 0, (hipStream_t)stream>>>((const T*)z, nullptr, (long long)voxels, C, 1.f, (float*)ws);
+    int st = check_launch();
+    if (st) return st;
+    in_finish_kernel<0><<<(N * C + 15) / 16, 256, 0, (hipStream_t)stream>>>((const float*)ws, blocks, C, N * C, 1.0 / (double)voxels, eps, stats);
+    return check_launch();
+}
+
+template <typename T>
+int in_fwd(void* z, const float* stats, int N, size_t voxels, int C, float slope, void* stream) {
+    typedef typename Piece<T>::raw raw;
+    if (!z || !stats || !a16(z) || !in_args_ok(N, voxels, C) || !(slope > 0.f && slope <= 1.f)) return MI3D_ERR_INVALID_ARG;
+    const long long pieces = (long long)voxels * (C / 8);
+    in_fwd_kernel<T><<<dim3(in_grid(pieces), N), 256, 0, (hipStream_t)stream>>>((raw*)z, stats, pieces, C, slope);
+    return check_launch();
+}
+
+template <typename T>
+int in_bwd(void* da, const void* a, const float* stats, int N, size_t voxels, int C, float slope, void* ws, size_t ws_bytes, void* stream) {
+    typedef typename Piece<T>::raw raw;
+    if (!da || !a || !stats || !ws || !a16(da) || !a16(a) || !in_args_ok(N, voxels, C) || !(slope > 0.f && slope <= 1.f)) return MI3D_ERR_INVALID_ARG;
+    if (ws_bytes < mi3d_instnorm_workspace_bytes(N, C)) return MI3D_ERR_WORKSPACE;
+    const int blocks = in_blocks(voxels);
+    float* part = (float*)ws;
+    float* sums = part + (size_t)N * IN_BLOCKS * 2 * C;
+    in_reduce_kernel<1, T><<<dim3(blocks, N), 256, 0, (hipStream_t)stream>>>((const T*)a, (const T*)da, (long long)voxels, C, slope, part);
+    int st = check_launch();
+    if (st) return st;
+    in_finish_kernel<1><<<(N * C + 15) / 16, 256, 0, (hipStream_t)stream>>>(part, blocks, C, N * C, 1.0 / (double)voxels, 0.f, sums);
+    if ((st = check_launch())) return st;
+    const long long pieces = (long long)voxels * (C / 8);
+    in_bwd_kernel<T><<<dim3(in_grid(pieces), N), 256, 0, (hipStream_t)stream>>>((raw*)da, (const raw*)a, stats, sums, pieces, C, slope);
+    return check_launch();
+}
+
+}  // namespace
+
 }  // namespace mi3d
 
 using namespace mi3d;
@@ -225,45 +294,33 @@ size_t mi3d_instnorm_workspace_bytes(int N, int C) {
 }
 
 int mi3d_instnorm_stats(const void* z, int N, size_t voxels, int C, float eps, float* stats, void* ws, size_t ws_bytes, void* stream) {
-    if (!z || !stats || !ws || !a16(z) || !in_args_ok(N, voxels, C) || !(eps > 0.f)) return MI3D_ERR_INVALID_ARG;
-    if (ws_bytes < mi3d_instnorm_workspace_bytes(N, C)) return MI3D_ERR_WORKSPACE;
-    const int blocks = in_blocks(voxels);
-    in_reduce_kernel<0><<<dim3(blocks, N), 256, 0, (hipStream_t)stream>>>((const uint16_t*)z, nullptr, (long long)voxels, C, 1.f, (float*)ws);
-    int st = check_launch();
-    if (st) return st;
-    in_finish_kernel<0><<<(N * C + 15) / 16, 256, 0, (hipStream_t)stream>>>((const float*)ws, blocks, C, N * C, 1.0 / (double)voxels, eps, stats);
-    return check_launch();
+    return in_stats<uint16_t>(z, N, voxels, C, eps, stats, ws, ws_bytes, stream);
+}
+int mi3d_instnorm_stats_f32(const void* z, int N, size_t voxels, int C, float eps, float* stats, void* ws, size_t ws_bytes, void* stream) {
+    return in_stats<float>(z, N, voxels, C, eps, stats, ws, ws_bytes, stream);
 }
 
 int mi3d_instnorm_lrelu_fwd(void* z, const float* stats, int N, size_t voxels, int C, float slope, void* stream) {
-    if (!z || !stats || !a16(z) || !in_args_ok(N, voxels, C) || !(slope > 0.f && slope <= 1.f)) return MI3D_ERR_INVALID_ARG;
-    const long long pieces = (long long)voxels * (C / 8);
-    in_fwd_kernel<<<dim3(in_grid(pieces), N), 256, 0, (hipStream_t)stream>>>((uint4*)z, stats, pieces, C, slope);
-    return check_launch();
+    return in_fwd<uint16_t>(z, stats, N, voxels, C, slope, stream);
+}
+int mi3d_instnorm_lrelu_fwd_f32(void* z, const float* stats, int N, size_t voxels, int C, float slope, void* stream) {
+    return in_fwd<float>(z, stats, N, voxels, C, slope, stream);
 }
 
 int mi3d_instnorm_lrelu_bwd(void* da, const void* a, const float* stats, int N, size_t voxels, int C, float slope, void* ws, size_t ws_bytes,
                             void* stream) {
-    if (!da || !a || !stats || !ws || !a16(da) || !a16(a) || !in_args_ok(N, voxels, C) || !(slope > 0.f && slope <= 1.f)) return MI3D_ERR_INVALID_ARG;
-    if (ws_bytes < mi3d_instnorm_workspace_bytes(N, C)) return MI3D_ERR_WORKSPACE;
-    const int blocks = in_blocks(voxels);
-    float* part = (float*)ws;
-    float* sums = part + (size_t)N * IN_BLOCKS * 2 * C;
-    in_reduce_kernel<1><<<dim3(blocks, N), 256, 0, (hipStream_t)stream>>>((const uint16_t*)a, (const uint16_t*)da, (long long)voxels, C, slope, part);
-    int st = check_launch();
-    if (st) return st;
-    in_finish_kernel<1><<<(N * C + 15) / 16, 256, 0, (hipStream_t)stream>>>(part, blocks, C, N * C, 1.0 / (double)voxels, 0.f, sums);
-    if ((st = check_launch())) return st;
-    const long long pieces = (long long)voxels * (C / 8);
-    in_bwd_kernel<<<dim3(in_grid(pieces), N), 256, 0, (hipStream_t)stream>>>((uint4*)da, (const uint4*)a, stats, sums, pieces, C, slope);
-    return check_launch();
+    return in_bwd<uint16_t>(da, a, stats, N, voxels, C, slope, ws, ws_bytes, stream);
+}
+int mi3d_instnorm_lrelu_bwd_f32(void* da, const void* a, const float* stats, int N, size_t voxels, int C, float slope, void* ws, size_t ws_bytes,
+                                void* stream) {
+    return in_bwd<float>(da, a, stats, N, voxels, C, slope, ws, ws_bytes, stream);
 }
 
 int mi3d_instnorm_lrelu_bwd_sums(void* da, const void* a, const float* stats, const float* sums, int N, size_t voxels, int C, float slope,
                                  void* stream) {
     if (!da || !a || !stats || !sums || !a16(da) || !a16(a) || !in_args_ok(N, voxels, C) || !(slope > 0.f && slope <= 1.f)) return MI3D_ERR_INVALID_ARG;
     const long long pieces = (long long)voxels * (C / 8);
-    in_bwd_kernel<<<dim3(in_grid(pieces), N), 256, 0, (hipStream_t)stream>>>((uint4*)da, (const uint4*)a, stats, sums, pieces, C, slope);
+    in_bwd_kernel<uint16_t><<<dim3(in_grid(pieces), N), 256, 0, (hipStream_t)stream>>>((uint4*)da, (const uint4*)a, stats, sums, pieces, C, slope);
     return check_launch();
 }
 

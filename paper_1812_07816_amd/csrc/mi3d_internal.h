@@ -152,6 +152,10 @@ bool dgrad_s2_fuses_skip(const Geom& g);   // the added second gradient of a ski
 bool pointwise_supported(const Geom& g);
 size_t pointwise_workspace_bytes(const Geom& g, int pass);
 int pointwise_conv(const Geom& g, int pass, const void* a, const void* b, void* out, void* ws, size_t ws_bytes, hipStream_t s);
+// the same head in fp32 (VALU kernels; the fp32 dispatcher routes 1x1x1 layers with at most 4 output channels here)
+bool pointwise_f32_supported(const Geom& g);
+size_t pointwise_f32_workspace_bytes(const Geom& g, int pass);
+int pointwise_f32_conv(const Geom& g, int pass, const void* a, const void* b, void* out, void* ws, size_t ws_bytes, hipStream_t s);
 
 
 // 2x2x2 stride-2 pad-0 layers (decoder upsampling and its gradients) run as 3x3x3 stride-2 pad-1 layers

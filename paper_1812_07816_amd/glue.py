@@ -107,22 +107,26 @@ def instnorm_stats(z, stats, ws, eps=IN_EPS):
     N, C = z.shape[0], z.shape[-1]
     vox = z.numel() // (N * C)
     assert tuple(stats.shape) == (N, C, 2) and stats.dtype == torch.float32
-    check(lib().mi3d_instnorm_stats(_p(z), N, vox, C, eps, _p(stats), _p(ws), ws.numel(), _stream()), "instnorm_stats")
+    fn = lib().mi3d_instnorm_stats_f32 if z.dtype == torch.float32 else lib().mi3d_instnorm_stats
+    check(fn(_p(z), N, vox, C, eps, _p(stats), _p(ws), ws.numel(), _stream()), "instnorm_stats")
 
 
 def instnorm_lrelu_fwd(z, stats, slope=0.01):
     N, C = z.shape[0], z.shape[-1]
-    check(lib().mi3d_instnorm_lrelu_fwd(_p(z), _p(stats), N, z.numel() // (N * C), C, slope, _stream()), "instnorm_lrelu_fwd")
+    fn = lib().mi3d_instnorm_lrelu_fwd_f32 if z.dtype == torch.float32 else lib().mi3d_instnorm_lrelu_fwd
+    check(fn(_p(z), _p(stats), N, z.numel() // (N * C), C, slope, _stream()), "instnorm_lrelu_fwd")
 
 
 def instnorm_lrelu_bwd_sums(da, a, stats, sums, slope=0.01):
     """da <- dz given the two means (mean g, mean g * xhat) per (sample, channel)."""
     N, C = a.shape[0], a.shape[-1]
     assert da.numel() == a.numel() and tuple(sums.shape) == (N, C, 2) and sums.dtype == torch.float32
+    assert a.dtype == torch.bfloat16 and da.dtype == torch.bfloat16      # (bf16 only: the kernels that deliver the sums are)
     check(lib().mi3d_instnorm_lrelu_bwd_sums(_p(da), _p(a), _p(stats), _p(sums), N, a.numel() // (N * C), C, slope, _stream()), "instnorm_lrelu_bwd_sums")
 
 
 def instnorm_lrelu_bwd(da, a, stats, ws, slope=0.01):
     N, C = a.shape[0], a.shape[-1]
-    assert da.numel() == a.numel()
-    check(lib().mi3d_instnorm_lrelu_bwd(_p(da), _p(a), _p(stats), N, a.numel() // (N * C), C, slope, _p(ws), ws.numel(), _stream()), "instnorm_lrelu_bwd")
+    assert da.numel() == a.numel() and da.dtype == a.dtype
+    fn = lib().mi3d_instnorm_lrelu_bwd_f32 if a.dtype == torch.float32 else lib().mi3d_instnorm_lrelu_bwd
+    check(fn(_p(da), _p(a), _p(stats), N, a.numel() // (N * C), C, slope, _p(ws), ws.numel(), _stream()), "instnorm_lrelu_bwd")

@@ -54,7 +54,6 @@ class UNetStep:
         master weights) or torch.float32 (everything fp32: the convolutions run on the fp32 matrix cores and read the
         master weights themselves)."""
         assert dtype in (torch.bfloat16, torch.float32) and x.dtype == dtype
-        assert not (norm and dtype == torch.float32), "the instance-normalisation passes are bf16 only"
         assert virtual_cat or dtype == torch.bfloat16, "the materialised concatenation is bf16 only"
         self.dtype, self.esize = dtype, (2 if dtype == torch.bfloat16 else 4)
         self.N, self.vol, self.ch, self.L = N, vol, list(channels), len(channels)

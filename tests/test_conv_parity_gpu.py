@@ -100,6 +100,9 @@ MID_F32 = [
     (1, 5, 19, 45, 4, 32, 3, 1, 0),
     (1, 4, 16, 33, 4, 32, 3, 1, 2),
     (1, 6, 10, 40, 32, 3, 1, 1, 0),
+    (2, 5, 9, 13, 64, 4, 1, 1, 0),
+    (3, 4, 5, 7, 8, 1, 1, 1, 0),
+    (1, 3, 5, 9, 16, 2, 1, 1, 0),
     (1, 8, 8, 16, 32, 64, 2, 2, 0),
     (2, 6, 10, 14, 64, 128, 2, 2, 0),
     (1, 7, 9, 11, 6, 10, 3, 2, 1),
@@ -110,7 +113,8 @@ MID_F32 = [
 @pytest.mark.parametrize("case", MID_F32)
 def test_mid_shapes_fp32_full(device, case):
     desc = mc.make_desc(*case, torch.float32)
-    assert all(mc.kernel_name(desc, q) == "mfma_f32_gather" for q in range(3))
+    head = case[6] == 1 and case[5] <= 4     # 1x1x1 to a handful of channels: VALU kernels
+    assert all(mc.kernel_name(desc, q) == ("valu_pointwise_head_f32" if head else "mfma_f32_gather") for q in range(3))
     _check(parity.run_case(96, 10 * MID_F32.index(case), *case, bf16=False, full=True), False, f"mid fp32 {case}")
 
 

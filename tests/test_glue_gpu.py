@@ -161,3 +161,31 @@ def test_instance_norm_forward_and_backward(glue, shape):
     g2 = dev(da)
     glue.instnorm_lrelu_bwd(g2, a, stats, ws)
     assert torch.equal(g.view(torch.int16), g2.view(torch.int16))
+
+
+@pytest.mark.parametrize("shape", [(2, 5, 6, 7, 32), (1, 4, 4, 6, 320), (2, 3, 3, 3, 8), (1, 16, 16, 24, 64)])
+def test_instance_norm_fp32(glue, shape):
+    """The fp32 entry points against the fp64 definition, at fp32 accuracy."""
+    N, C = shape[0], shape[-1]
+    scale = np.linspace(0.05, 20.0, C)
+    z = (si.normal(52, C, shape) * scale + np.linspace(-3, 3, C)).astype(np.float32)
+    da = si.normal(52, C + 1, shape).astype(np.float32)
+    xhat, mean, rstd = ou.instnorm(z.astype(np.float64))
+    ws = glue.instnorm_workspace(N, C)
+    stats = torch.zeros((N, C, 2), dtype=torch.float32, device="cuda")
+    a = torch.from_numpy(z).cuda()
+    glue.instnorm_stats(a, stats, ws)
+    st = stats.cpu().numpy().astype(np.float64)
+    assert np.allclose(st[..., 0], mean, rtol=1e-5, atol=1e-6 * np.abs(z).max()) and np.allclose(st[..., 1], rstd, rtol=1e-4)
+    glue.instnorm_lrelu_fwd(a, stats)
+    ref = ou._lrelu(xhat)
+    # (one-pass variance from fp32 block sums: a channel whose offset is 60 standard deviations loses 1e-4 of rstd)
+    assert np.max(np.abs(a.cpu().numpy() - ref)) <= 2e-4 * np.max(np.abs(ref))
+    g = torch.from_numpy(da).cuda()
+    glue.instnorm_lrelu_bwd(g, a, stats, ws)
+    refd = ou.instnorm_lrelu_bwd(ou.lrelu_inverse(a.cpu().numpy().astype(np.float64)), rstd, da.astype(np.float64))
+    err = np.max(np.abs(g.cpu().numpy() - refd), axis=(0, 1, 2, 3)) / np.max(np.abs(refd), axis=(0, 1, 2, 3))
+    assert err.max() <= 5e-4, err.max()
+    g2 = torch.from_numpy(da).cuda()
+    glue.instnorm_lrelu_bwd(g2, a, stats, ws)
+    assert torch.equal(g, g2)

@@ -65,7 +65,9 @@ def test_every_op_matches_oracle_on_the_steps_own_tensors(unet, N, vol, channels
         xd = xd.float()
     step = unet.UNetStep(N, vol, channels, ws, xd, ld, swap=False, virtual_cat=virtual_cat, dtype=torch.float32 if f32 else torch.bfloat16)
     if f32:
-        assert all(unet.mc.kernel_name(op["desc"], q) == "mfma_f32_gather" for op in step.ops if "desc" in op for q in range(3))
+        # (the head runs through VALU kernels of its own, every other layer on the fp32 matrix cores)
+        assert all(unet.mc.kernel_name(op["desc"], q) == ("valu_pointwise_head_f32" if op["kind"] == "head" else "mfma_f32_gather")
+                   for op in step.ops if "desc" in op for q in range(3))
     assert all(op["virtual"] == virtual_cat for op in step.ops if op["kind"] == "cat")
     tr = {}
     step.run(update=False, trace=tr)
@@ -205,6 +207,25 @@ def test_fp32_step_end_to_end_against_the_exact_oracle_step(unet):
         assert e <= 2e-2, (name, e)
         assert np.allclose(wm.cpu().numpy(), wr, rtol=1e-4, atol=1e-6), name
     print(f"worst weight-gradient error of the fp32 step against the exact oracle step: {worst:.2e}")
+
+
+def test_fp32_normalised_step_end_to_end_against_the_exact_oracle_step(unet):
+    """The paper's block (Section 4.1: convolution -> instance normalisation -> LeakyReLU) in fp32 against the fp64
+    oracle step with the same block: loss, length and direction of every weight gradient."""
+    N, vol = 2, 32
+    x, labels, ws, xd, ld = _inputs(N, vol, CH, 5)
+    step = unet.UNetStep(N, vol, CH, ws, xd.float(), ld, swap=False, norm=True, dtype=torch.float32)
+    step.run(update=False)
+    torch.cuda.synchronize()
+    loss_ref, grads_ref, _ = ou.train_step(x.astype(np.float64), labels, ws, CH, 0.0, norm=True)
+    assert abs(float(step.loss.item()) - loss_ref) <= 1e-5 * abs(loss_ref)
+    for (name, _), g, r in zip(si.unet_weight_shapes(CH), step.dw, grads_ref):
+        gg = _h(g)
+        ratio = np.sqrt(np.sum(gg * gg) / np.sum(r * r))
+        cos = np.sum(gg * r) / np.sqrt(np.sum(gg * gg) * np.sum(r * r))
+        print(f"{name}: max error {oc.rel_err(gg, r):.2e}, norm ratio - 1 = {ratio - 1.0:+.1e}, 1 - cos = {1.0 - cos:.1e}")
+        # (as in the step without normalisation: a few pre-activations next to zero take the other LeakyReLU branch)
+        assert abs(ratio - 1.0) <= 2e-4 and 1.0 - cos <= 5e-6, (name, ratio, cos)
 
 
 def test_fp32_step_swapped_recomputed_and_hybrid_are_bit_identical(unet):
@@ -377,13 +398,16 @@ def test_adam_steps_follow_the_oracle_update_on_the_steps_own_gradients(unet):
     assert float(np.max(np.abs(w - step.w32.cpu().numpy()))) < 1e-6
 
 
-@pytest.mark.parametrize("N,vol,channels", [(2, 32, CH), (1, 16, CH[:4])])
-def test_every_op_with_instance_normalisation_matches_oracle(unet, N, vol, channels):
+@pytest.mark.parametrize("N,vol,channels,f32", [(2, 32, CH, False), (1, 16, CH[:4], False), (2, 32, CH, True), (1, 16, CH[:4], True)])
+def test_every_op_with_instance_normalisation_matches_oracle(unet, N, vol, channels, f32):
     """The network of Section 4.1 proper: convolution -> instance normalisation -> LeakyReLU.  Every op of the GPU
-    step against the oracle's definition of it on the tensors the step itself fed it."""
+    step against the oracle's definition of it on the tensors the step itself fed it (fp32: at fp32 accuracy; the
+    normalisation's one-pass variance from fp32 block sums is the least accurate op)."""
     x, labels, ws, xd, ld = _inputs(N, vol, channels, 5)
     L = len(channels)
-    step = unet.UNetStep(N, vol, channels, ws, xd, ld, swap=False, norm=True)
+    TOL = 2e-4 if f32 else 1e-2
+    step = unet.UNetStep(N, vol, channels, ws, xd.float() if f32 else xd, ld, swap=False, norm=True,
+                         dtype=torch.float32 if f32 else torch.bfloat16)
     tr = {}
     step.run(update=False, trace=tr)
     torch.cuda.synchronize()
@@ -420,7 +444,12 @@ def test_every_op_with_instance_normalisation_matches_oracle(unet, N, vol, chann
         if name == "enc0.conv1":
             continue
         din_ref = oc.dgrad(g, t[name + ".dz"], w[name])
-        if name.startswith("enc") and name.endswith("conv1"):
+        if name.startswith("enc") and name.endswith("conv1") and name + ".skip_add" in t:
+            # (fp32: the data gradient adds the skip connection's second gradient itself)
+            l = int(name[3]) - 1
+            assert np.array_equal(t[name + ".skip_add"], t[f"dec{l}.cat.dskip"])
+            close(name + " dgrad + skip", t[name + ".din"], din_ref + t[name + ".skip_add"])
+        elif name.startswith("enc") and name.endswith("conv1"):
             l = int(name[3]) - 1
             close(name + " dgrad", t[name + ".dgrad"], din_ref)
             close(name + " skip add", t[name + ".din"], t[name + ".dgrad"] + t[f"dec{l}.cat.dskip"])
