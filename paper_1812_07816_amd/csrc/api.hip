@@ -193,8 +193,12 @@ int mi3d_conv3d_kernel_name(const mi3d_conv_desc* desc, int pass, char* buf, siz
     if (st) return st;
     if (!buf || buf_len == 0 || pass < 0 || pass > 2) return MI3D_ERR_INVALID_ARG;
     Kernel k = choose(g, pass);
-    // (the fp32 dispatcher hands 1x1x1 layers with a handful of output channels to VALU kernels of its own)
-    snprintf(buf, buf_len, "%s", k == K_F32 && pointwise_f32_supported(g) ? "valu_pointwise_head_f32" : kernel_name(k));
+    // (the fp32 dispatcher hands 1x1x1 layers with a handful of output channels to VALU kernels of its own, and the
+    // weight gradient of a layer with at most 4 input channels to a kernel that folds the taps into the block's columns)
+    const char* name = kernel_name(k);
+    if (k == K_F32 && pointwise_f32_supported(g)) name = "valu_pointwise_head_f32";
+    else if (k == K_F32 && pass == MI3D_PASS_WGRAD && f32_wgrad_folds_taps(g)) name = "mfma_f32_wgrad_cin4_folded_taps";
+    snprintf(buf, buf_len, "%s", name);
     return MI3D_OK;
 }
 

@@ -338,6 +338,93 @@ __global__ void __launch_bounds__(256, 2) f32_wgrad_kernel(WgParams P) {
     }
 }
 
+// Weight gradient of a 3x3x3 / stride-1 layer with at most 4 input channels (the network's first layer).  The general
+// kernel above would give each tap a 32 x 32 block of which 4 columns are in use; here (tap, input channel) pairs are
+// the columns: four groups of 8 taps x 4 channels, one group and one block per wave (27 taps: the last group has 3).
+// Lane column ln of wave w is tap 8 w + ln / 4, channel ln % 4, so the B operand is a per-lane shifted read of the
+// staged x patch ([plane ring][row][column][4 channels]); units, ring and partial sums as in the general kernel.
+__global__ void __launch_bounds__(256, 2) f32_wgrad_c4_kernel(WgParams P) {
+    extern __shared__ __attribute__((aligned(16))) float lds_f[];
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const int ln = lane & 31, half = lane >> 5;
+    float* dys = lds_f;                                        // [TR][TW][32 output channels]
+    float* xs = lds_f + P.TR * P.TW * 32;                      // [3 ring slots][prows][pcols][4]
+    const int pv = P.prows * P.pcols;
+    const int split = blockIdx.x % P.S, cot = blockIdx.x / P.S;
+    const int co0 = cot * 32;
+    const int tap = 8 * wave + (ln >> 2), ci = ln & 3;
+    const bool col_ok = tap < 27 && ci < P.Cin;
+    const int kd = tap / 9, kh = (tap / 3) % 3, kw = tap % 3;   // (tap >= 27: reads inside the staged patch, value unused)
+    f32x16 acc[2];
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[a][i] = 0.f;
+
+    const long long u0 = P.units * split / P.S, u1 = P.units * (split + 1) / P.S;
+    const long long x_plane = (long long)P.H * P.W * P.Cin;
+    const int c4 = t & 7, vslot = t >> 3;   // dy staging: 8 threads x 16 bytes per voxel, 32 voxels per pass
+    long long cur_col = -1;
+    int have_lo = 1, have_hi = 0;           // input planes resident in the ring (none)
+    for (long long u = u0; u < u1; ++u) {
+        const long long col = u / P.Do;
+        const int od = (int)(u - col * P.Do);
+        long long r = col;
+        const int wt = (int)(r % P.WT); r /= P.WT;
+        const int ht = (int)(r % P.HT);
+        const int n = (int)(r / P.HT);
+        const int oh0 = ht * P.TR, ow0 = wt * P.TW;
+        if (col != cur_col) { cur_col = col; have_lo = 1; have_hi = 0; }
+        const int need_lo = od - P.pD, need_hi = need_lo + 2;
+        __syncthreads();   // every wave is done with the previous unit's tiles
+        for (int v = vslot; v < P.TR * P.TW; v += 32) {
+            const int tr = v / P.TW, tc = v - tr * P.TW;
+            const int oh = oh0 + tr, ow = ow0 + tc;
+            float4 val = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (oh < P.Ho && ow < P.Wo && co0 + 4 * c4 < P.Cout)
+                val = *(const float4*)(P.dy + ((((long long)n * P.Do + od) * P.Ho + oh) * P.Wo + ow) * P.Cout + co0 + 4 * c4);
+            *(float4*)(dys + v * 32 + 4 * c4) = val;
+        }
+        for (int id = need_lo; id <= need_hi; ++id) {
+            if (id >= have_lo && id <= have_hi) continue;
+            float* dst = xs + ((id % 3 + 3) % 3) * pv * 4;
+            const bool plane_ok = id >= 0 && id < P.D;
+            const float* src = P.x + ((long long)n * P.D + (plane_ok ? id : 0)) * x_plane;
+            for (int q = t; q < pv; q += 256) {
+                const int pr = q / P.pcols, pc = q - pr * P.pcols;
+                const int ih = oh0 - P.pH + pr, iw = ow0 - P.pW + pc;
+                float4 val = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (plane_ok && ih >= 0 && ih < P.H && iw >= 0 && iw < P.W) {
+                    const float* px = src + ((long long)ih * P.W + iw) * P.Cin;
+                    if (P.Cin == 4) val = *(const float4*)px;
+                    else { val.x = px[0]; if (P.Cin > 1) val.y = px[1]; if (P.Cin > 2) val.z = px[2]; }
+                }
+                *(float4*)(dst + q * 4) = val;
+            }
+        }
+        have_lo = need_lo; have_hi = need_hi;
+        __syncthreads();
+        const float* plane = xs + (((need_lo + kd) % 3 + 3) % 3) * pv * 4 + ci;
+        for (int tr = 0; tr < P.TR; ++tr) {
+            const float* ap = dys + (tr * P.TW + half) * 32 + ln;
+            const float* bp = plane + ((tr + kh) * P.pcols + half + kw) * 4;
+#pragma unroll 4
+            for (int c2 = 0; c2 < P.TW; c2 += 4) {   // K = pairs of neighbouring output columns, two chains
+                const float b0 = bp[c2 * 4], b1 = bp[(c2 + 2) * 4];
+                acc[0] = mfma2(ap[c2 * 32], col_ok ? b0 : 0.f, acc[0]);
+                acc[1] = mfma2(ap[(c2 + 2) * 32], col_ok ? b1 : 0.f, acc[1]);
+            }
+        }
+    }
+    // partial sums: lane column (tap, ci), rows are the output channels co0 + 8 (i / 4) + 4 half + i % 4
+    float* part = P.part + (long long)split * P.Cout * 27 * P.Cin;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int co = co0 + 8 * (i >> 2) + 4 * half + (i & 3);
+        if (col_ok && co < P.Cout) part[((long long)co * 27 + tap) * P.Cin + ci] = acc[0][i] + acc[1][i];
+    }
+}
+
 int cu_count() {
     int dev = 0, cus = 256;
     if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
@@ -385,6 +472,28 @@ void wgrad_layout(const Geom& g, WgParams* P) {
     P->S = (int)s;
 }
 
+// the folded-tap kernel for at most 4 input channels: 4 x 32 output tiles, two workgroups per CU
+bool wgrad_c4_ok(const Geom& g) {
+    return g.kD == 3 && g.kH == 3 && g.kW == 3 && g.sD == 1 && g.sH == 1 && g.sW == 1 && g.Cin <= 4 && g.Cout % 4 == 0 && !g.hi;
+}
+void wgrad_c4_layout(const Geom& g, WgParams* P) {
+    P->TR = 4;
+    P->TW = 32;
+    P->prows = P->TR + 2;
+    P->pcols = P->TW + 2;
+    P->pcols_magic = 0;
+    P->HT = (g.Ho + P->TR - 1) / P->TR;
+    P->WT = (g.Wo + P->TW - 1) / P->TW;
+    P->CIT = 1;
+    P->COT = (g.Cout + 31) / 32;
+    P->units = (long long)g.N * g.Do * P->HT * P->WT;
+    long long s = 2ll * cu_count() / P->COT;
+    if (s > P->units / 4) s = P->units / 4;
+    if (s > 1024) s = 1024;
+    if (s < 1) s = 1;
+    P->S = (int)s;
+}
+
 bool wgrad_magic_ok(const WgParams& P) {
     for (unsigned q = 0; q < (unsigned)(P.prows * P.pcols); ++q)
         if (((q * P.pcols_magic) >> 16) != q / (unsigned)P.pcols) return false;
@@ -421,12 +530,19 @@ size_t f32_workspace_bytes(const Geom& g, int pass) {
         WgParams P;
         wgrad_layout(g, &P);
         b = (size_t)P.S * g.w_elems() * sizeof(float);
+        if (wgrad_c4_ok(g)) {
+            wgrad_c4_layout(g, &P);
+            const size_t c = (size_t)P.S * g.w_elems() * sizeof(float);
+            b = b > c ? b : c;
+        }
     } else {
         b = pack_bytes(g, pass);
     }
     const size_t h = pointwise_f32_workspace_bytes(g, pass);   // (0 where the head kernels do not apply)
     return b > h ? b : h;
 }
+
+bool f32_wgrad_folds_taps(const Geom& g) { return f32_supported(g, MI3D_PASS_WGRAD) && wgrad_c4_ok(g); }
 
 bool f32_takes_halves(const Geom& g, int pass) {   // virtual concatenation: halves of Cin in multiples of 32 channels
     return f32_supported(g, pass) && g.Cin % 64 == 0;
@@ -552,6 +668,14 @@ int f32_wgrad(const Geom& g, const void* x, const void* dy, float* dw, void* ws,
     P.T = (int)g.taps();
     P.x_pitch = g.Cin; P.x_split = 1 << 30;
     if (g.hi) { P.x2 = (const float*)g.hi; P.x_pitch = g.Cin / 2; P.x_split = g.Cin / 2; }
+    if (wgrad_c4_ok(g)) {
+        wgrad_c4_layout(g, &P);
+        const size_t lds4 = ((size_t)P.TR * P.TW * 32 + (size_t)3 * P.prows * P.pcols * 4) * sizeof(float);   // 26 KB
+        f32_wgrad_c4_kernel<<<(unsigned)(P.COT * P.S), 256, lds4, s>>>(P);
+        int st4 = check_launch();
+        if (st4) return st4;
+        return reduce_partials((const float*)ws, dw, g.w_elems(), P.S, s);
+    }
     const size_t lds = ((size_t)P.TR * P.TW + (size_t)g.kD * P.prows * P.pcols) * 32 * sizeof(float);
     static std::atomic<bool> attr_set{false};   // set once per process; a second thread racing here repeats an idempotent call
     if (!attr_set) {

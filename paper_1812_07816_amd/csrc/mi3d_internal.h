@@ -169,6 +169,7 @@ bool f32_supported(const Geom& g, int pass);
 size_t f32_workspace_bytes(const Geom& g, int pass);
 int f32_conv(const Geom& g, int pass, const void* in, const void* w, void* out, void* ws, size_t ws_bytes, hipStream_t s);
 int f32_wgrad(const Geom& g, const void* x, const void* dy, float* dw, void* ws, size_t ws_bytes, hipStream_t s);
+bool f32_wgrad_folds_taps(const Geom& g);   // at most 4 input channels: (tap, channel) pairs as the columns of the MFMA block
 bool f32_takes_halves(const Geom& g, int pass);   // the tensor of x's shape as two halves along the channels
 
 // automatic kernel choice for a geometry (a, b, out per pass: fwd (x, w, y), dgrad (dy, w, dx), wgrad (x, dy, dw))

@@ -66,6 +66,9 @@ MID = [
     (2, 12, 20, 36, 4, 32, 3, 1, 1),
     (1, 5, 19, 45, 4, 32, 3, 1, 0),
     (1, 4, 16, 33, 4, 32, 3, 1, 2),
+    (2, 7, 11, 70, 4, 32, 3, 1, 1),
+    (1, 5, 6, 35, 3, 40, 3, 1, 1),
+    (2, 3, 9, 31, 1, 8, 3, 1, 0),
     (1, 6, 10, 40, 32, 3, 1, 1, 0),
     (1, 8, 8, 16, 32, 64, 2, 2, 0),
     (2, 6, 10, 14, 64, 128, 2, 2, 0),
@@ -114,7 +117,10 @@ MID_F32 = [
 def test_mid_shapes_fp32_full(device, case):
     desc = mc.make_desc(*case, torch.float32)
     head = case[6] == 1 and case[5] <= 4     # 1x1x1 to a handful of channels: VALU kernels
-    assert all(mc.kernel_name(desc, q) == ("valu_pointwise_head_f32" if head else "mfma_f32_gather") for q in range(3))
+    fold = case[4] <= 4 and case[6] == 3 and case[7] == 1 and case[5] % 4 == 0   # few input channels: taps folded into the weight gradient's columns
+    for q in range(3):
+        want = "valu_pointwise_head_f32" if head else "mfma_f32_wgrad_cin4_folded_taps" if fold and q == 2 else "mfma_f32_gather"
+        assert mc.kernel_name(desc, q) == want
     _check(parity.run_case(96, 10 * MID_F32.index(case), *case, bf16=False, full=True), False, f"mid fp32 {case}")
 
 

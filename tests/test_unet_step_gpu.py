@@ -66,8 +66,11 @@ def test_every_op_matches_oracle_on_the_steps_own_tensors(unet, N, vol, channels
     step = unet.UNetStep(N, vol, channels, ws, xd, ld, swap=False, virtual_cat=virtual_cat, dtype=torch.float32 if f32 else torch.bfloat16)
     if f32:
         # (the head runs through VALU kernels of its own, every other layer on the fp32 matrix cores)
-        assert all(unet.mc.kernel_name(op["desc"], q) == ("valu_pointwise_head_f32" if op["kind"] == "head" else "mfma_f32_gather")
-                   for op in step.ops if "desc" in op for q in range(3))
+        def expected(op, q):
+            if op["kind"] == "head":
+                return "valu_pointwise_head_f32"
+            return "mfma_f32_wgrad_cin4_folded_taps" if q == 2 and op["name"] == "enc0.conv1" else "mfma_f32_gather"
+        assert all(unet.mc.kernel_name(op["desc"], q) == expected(op, q) for op in step.ops if "desc" in op for q in range(3))
     assert all(op["virtual"] == virtual_cat for op in step.ops if op["kind"] == "cat")
     tr = {}
     step.run(update=False, trace=tr)
