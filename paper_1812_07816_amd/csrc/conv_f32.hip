@@ -549,9 +549,24 @@ bool f32_takes_halves(const Geom& g, int pass) {   // virtual concatenation: hal
 }
 
 static int launch_gconv(GcParams& P, hipStream_t s) {
-    // contracted channels per stage: the largest even chunk that keeps the tiles of a stage within LDS_SOFT
-    const int CB = P.M > 32 ? 2 : 1;
+    P.JHT = (P.Jh + TJH - 1) / TJH;
+    P.JWT = (P.Jw + TJW - 1) / TJW;
+    // Output channels per workgroup: 64 where there are that many, unless the grid is so small that its last round
+    // over the 2 x CUs workgroup slots would be mostly empty and 32-channel workgroups fill the rounds better
+    // (24^3, N = 2, 256 output channels: 576 workgroups = 2 rounds of 512 at 56 %; 1152 = 3 rounds at 75 %).
+    // Only where the MFMA work of a workgroup outweighs its staging (taps x contracted channels): a 2x2x2 layer with
+    // 128 channels got slower with the smaller workgroups (0.40 -> 0.61 ms), which stage the same patch twice.
+    int CB = P.M > 32 ? 2 : 1;
+    if (CB == 2 && P.ntaps * P.K >= 27 * 64) {
+        const long long tiles = (long long)P.N * P.Jd * P.JHT * P.JWT, slots = 2ll * cu_count();
+        auto fill = [&](int cb) {
+            const long long b = tiles * ((P.Mpad + 32 * cb - 1) / (32 * cb));
+            return (double)b / (double)(((b + slots - 1) / slots) * slots);
+        };
+        if (fill(1) > 1.15 * fill(2)) CB = 1;
+    }
     P.MT = (P.Mpad + 32 * CB - 1) / (32 * CB);
+    // contracted channels per stage: the largest even chunk that keeps the tiles of a stage within LDS_SOFT
     int max_group = 1;
     for (int g = 0; g < P.ngroups; ++g) max_group = max_group > P.gstart[g + 1] - P.gstart[g] ? max_group : P.gstart[g + 1] - P.gstart[g];
     auto lds_bytes = [&](int ck) {
@@ -564,8 +579,6 @@ static int launch_gconv(GcParams& P, hipStream_t s) {
     if (ck < 2) ck = 2;
     if (lds_bytes(ck) > 160 * 1024) return MI3D_ERR_UNSUPPORTED;
     P.CK = ck;
-    P.JHT = (P.Jh + TJH - 1) / TJH;
-    P.JWT = (P.Jw + TJW - 1) / TJW;
     const long long blocks = (long long)P.N * P.Jd * P.JHT * P.JWT * P.MT;
     if (blocks <= 0) return MI3D_OK;
     if (blocks > 0x7fffffffll) return MI3D_ERR_UNSUPPORTED;
