@@ -54,22 +54,15 @@ struct GcParams {
 
 __device__ __forceinline__ f32x16 mfma2(float a, float b, f32x16 c) { return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0); }
 
+// The work of one workgroup: tile (n, jd, jht, jwt) of the iteration space, output channel block mt.
 // CB = 32-wide blocks of output channels per workgroup
 template <int CB>
-__global__ void __launch_bounds__(256, 2) f32_gconv_kernel(GcParams P) {
-    extern __shared__ __attribute__((aligned(16))) float lds_f[];
+__device__ __forceinline__ void gconv_tile(const GcParams& P, float* lds_f, int n, int jd, int jht, int jwt, int mt) {
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     const int ln = lane & 31, half = lane >> 5;
     const int xp = P.CK + 1;                                   // channel pitch of a staged voxel (odd: no bank conflicts)
     float* xs = lds_f;                                         // [prows][pcols][CK + 1]
     float* ws = lds_f + ((P.prows * P.pcols * xp + 3) & ~3);   // [taps of the group][CK][32 CB]
-
-    long long u = blockIdx.x;
-    const int mt = (int)(u % P.MT); u /= P.MT;
-    const int jwt = (int)(u % P.JWT); u /= P.JWT;
-    const int jht = (int)(u % P.JHT); u /= P.JHT;
-    const int jd = (int)(u % P.Jd);
-    const int n = (int)(u / P.Jd);
     const int jh0 = jht * TJH, jw0 = jwt * TJW, m0 = mt * 32 * CB;
 
     f32x16 acc[2][CB];
@@ -180,6 +173,48 @@ __global__ void __launch_bounds__(256, 2) f32_gconv_kernel(GcParams P) {
                     for (int i = 0; i < nv; ++i) dst[i] = v[i];
             }
     }
+}
+
+template <int CB>
+__global__ void __launch_bounds__(256, 2) f32_gconv_kernel(GcParams P) {
+    extern __shared__ __attribute__((aligned(16))) float lds_f[];
+    long long u = blockIdx.x;
+    const int mt = (int)(u % P.MT); u /= P.MT;
+    const int jwt = (int)(u % P.JWT); u /= P.JWT;
+    const int jht = (int)(u % P.JHT); u /= P.JHT;
+    const int jd = (int)(u % P.Jd);
+    const int n = (int)(u / P.Jd);
+    gconv_tile<CB>(P, lds_f, n, jd, jht, jwt, mt);
+}
+
+// The parity classes of a stride-2 data gradient in one launch.  Workgroups are dealt to the 8 XCDs by index modulo
+// 8, so tile t goes to XCD t % 8 and its classes follow each other there: b = 8 (ncls (t / 8) + class) + t % 8.  The
+// classes of a tile read the same input patch, which then comes from that XCD's L2 for all but the first, and
+// every XCD gets every class (class = b % 8 would hand each XCD one class).  Used where the classes have the same
+// work each.  The grid spans the largest iteration space of the classes; a workgroup whose tile lies
+// outside its class's leaves at once.
+struct GcMulti {
+    GcParams p[8];
+    int ncls, MT, JWT, JHT, Jd;
+    long long tiles;      // N * Jd * JHT * JWT * MT of the spanning grid
+};
+static_assert(sizeof(GcMulti) <= 4096, "kernel arguments");
+
+template <int CB>
+__global__ void __launch_bounds__(256, 2) f32_gconv_classes_kernel(GcMulti Q) {
+    extern __shared__ __attribute__((aligned(16))) float lds_f[];
+    const long long r = blockIdx.x >> 3;
+    const int cls = (int)(r % Q.ncls);
+    long long u = (r / Q.ncls) * 8 + (blockIdx.x & 7);
+    if (u >= Q.tiles) return;
+    const int mt = (int)(u % Q.MT); u /= Q.MT;
+    const int jwt = (int)(u % Q.JWT); u /= Q.JWT;
+    const int jht = (int)(u % Q.JHT); u /= Q.JHT;
+    const int jd = (int)(u % Q.Jd);
+    const int n = (int)(u / Q.Jd);
+    const GcParams& P = Q.p[cls];
+    if (mt >= P.MT || jwt >= P.JWT || jht >= P.JHT || jd >= P.Jd) return;   // (uniform over the workgroup)
+    gconv_tile<CB>(P, lds_f, n, jd, jht, jwt, mt);
 }
 
 // wpack[t][k][m] (m padded to Mpad with zeros) from w[co][t][ci]; swap = 0: (k, m) = (ci, co); swap = 1: (k, m) = (co, ci)
@@ -548,23 +583,42 @@ bool f32_takes_halves(const Geom& g, int pass) {   // virtual concatenation: hal
     return f32_supported(g, pass) && g.Cin % 64 == 0;
 }
 
-static int launch_gconv(GcParams& P, hipStream_t s) {
-    P.JHT = (P.Jh + TJH - 1) / TJH;
-    P.JWT = (P.Jw + TJW - 1) / TJW;
-    // Output channels per workgroup: 64 where there are that many, unless the grid is so small that its last round
-    // over the 2 x CUs workgroup slots would be mostly empty and 32-channel workgroups fill the rounds better
-    // (24^3, N = 2, 256 output channels: 576 workgroups = 2 rounds of 512 at 56 %; 1152 = 3 rounds at 75 %).
-    // Only where the MFMA work of a workgroup outweighs its staging (taps x contracted channels): a 2x2x2 layer with
-    // 128 channels got slower with the smaller workgroups (0.40 -> 0.61 ms), which stage the same patch twice.
+static int gconv_attributes() {
+    static std::atomic<bool> attr_set{false};   // set once per process; a second thread racing here repeats an idempotent call
+    if (!attr_set) {
+        const void* fns[5] = {(const void*)f32_gconv_kernel<1>, (const void*)f32_gconv_kernel<2>, (const void*)f32_gconv_classes_kernel<1>,
+                              (const void*)f32_gconv_classes_kernel<2>, (const void*)f32_wgrad_kernel};
+        for (const void* f : fns) {
+            hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+            if (e != hipSuccess) { note_hip_error(e); return MI3D_ERR_HIP; }
+        }
+        attr_set = true;
+    }
+    return MI3D_OK;
+}
+
+// Output channels per workgroup: 64 where there are that many, unless the grid is so small that its last round
+// over the 2 x CUs workgroup slots would be mostly empty and 32-channel workgroups fill the rounds better
+// (24^3, N = 2, 256 output channels: 576 workgroups = 2 rounds of 512 at 56 %; 1152 = 3 rounds at 75 %).
+// Only where the MFMA work of a workgroup outweighs its staging (taps x contracted channels): a 2x2x2 layer with
+// 128 channels got slower with the smaller workgroups (0.40 -> 0.61 ms), which stage the same patch twice.
+static int gconv_blocks_of_channels(const GcParams& P, long long tiles, int ntaps) {
     int CB = P.M > 32 ? 2 : 1;
-    if (CB == 2 && P.ntaps * P.K >= 27 * 64) {
-        const long long tiles = (long long)P.N * P.Jd * P.JHT * P.JWT, slots = 2ll * cu_count();
+    if (CB == 2 && ntaps * P.K >= 27 * 64) {
+        const long long slots = 2ll * cu_count();
         auto fill = [&](int cb) {
             const long long b = tiles * ((P.Mpad + 32 * cb - 1) / (32 * cb));
             return (double)b / (double)(((b + slots - 1) / slots) * slots);
         };
         if (fill(1) > 1.15 * fill(2)) CB = 1;
     }
+    return CB;
+}
+
+// tiles, channel chunk and LDS bytes of one launch (or one class of a launch) for CB blocks of output channels
+static int gconv_prepare(GcParams& P, int CB, size_t* lds) {
+    P.JHT = (P.Jh + TJH - 1) / TJH;
+    P.JWT = (P.Jw + TJW - 1) / TJW;
     P.MT = (P.Mpad + 32 * CB - 1) / (32 * CB);
     // contracted channels per stage: the largest even chunk that keeps the tiles of a stage within LDS_SOFT
     int max_group = 1;
@@ -579,20 +633,56 @@ static int launch_gconv(GcParams& P, hipStream_t s) {
     if (ck < 2) ck = 2;
     if (lds_bytes(ck) > 160 * 1024) return MI3D_ERR_UNSUPPORTED;
     P.CK = ck;
+    *lds = lds_bytes(ck);
+    return MI3D_OK;
+}
+
+static int launch_gconv(GcParams& P, hipStream_t s) {
+    const int CB = gconv_blocks_of_channels(P, (long long)P.N * P.Jd * ((P.Jh + TJH - 1) / TJH) * ((P.Jw + TJW - 1) / TJW), P.ntaps);
+    size_t lds = 0;
+    int st = gconv_prepare(P, CB, &lds);
+    if (st) return st;
     const long long blocks = (long long)P.N * P.Jd * P.JHT * P.JWT * P.MT;
     if (blocks <= 0) return MI3D_OK;
     if (blocks > 0x7fffffffll) return MI3D_ERR_UNSUPPORTED;
-    const size_t lds = lds_bytes(ck);
-    static std::atomic<bool> attr_set{false};   // set once per process; a second thread racing here repeats an idempotent call
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void*)f32_gconv_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-        if (e == hipSuccess) e = hipFuncSetAttribute((const void*)f32_gconv_kernel<2>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-        if (e == hipSuccess) e = hipFuncSetAttribute((const void*)f32_wgrad_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-        if (e != hipSuccess) { note_hip_error(e); return MI3D_ERR_HIP; }
-        attr_set = true;
-    }
+    if ((st = gconv_attributes())) return st;
     if (CB == 2) f32_gconv_kernel<2><<<(unsigned)blocks, 256, lds, s>>>(P);
     else f32_gconv_kernel<1><<<(unsigned)blocks, 256, lds, s>>>(P);
+    return check_launch();
+}
+
+// all classes of a stride-2 data gradient in one launch (Q.p[0 .. ncls - 1] filled in but for tiles, CK)
+static int launch_gconv_classes(GcMulti& Q, hipStream_t s) {
+    if (Q.ncls == 0) return MI3D_OK;
+    long long tiles = 0;
+    int ntaps = 0;
+    for (int c = 0; c < Q.ncls; ++c) {
+        const GcParams& P = Q.p[c];
+        const long long tc = (long long)P.N * P.Jd * ((P.Jh + TJH - 1) / TJH) * ((P.Jw + TJW - 1) / TJW);
+        tiles += tc;
+        ntaps = ntaps > P.ntaps ? ntaps : P.ntaps;
+    }
+    const int CB = gconv_blocks_of_channels(Q.p[0], tiles, ntaps);
+    size_t lds = 0;
+    Q.MT = Q.JWT = Q.JHT = Q.Jd = 0;
+    for (int c = 0; c < Q.ncls; ++c) {
+        size_t l = 0;
+        int st = gconv_prepare(Q.p[c], CB, &l);
+        if (st) return st;
+        lds = lds > l ? lds : l;
+        Q.MT = Q.MT > Q.p[c].MT ? Q.MT : Q.p[c].MT;
+        Q.JWT = Q.JWT > Q.p[c].JWT ? Q.JWT : Q.p[c].JWT;
+        Q.JHT = Q.JHT > Q.p[c].JHT ? Q.JHT : Q.p[c].JHT;
+        Q.Jd = Q.Jd > Q.p[c].Jd ? Q.Jd : Q.p[c].Jd;
+    }
+    Q.tiles = (long long)Q.p[0].N * Q.Jd * Q.JHT * Q.JWT * Q.MT;
+    const long long blocks = (Q.tiles + 7) / 8 * 8 * Q.ncls;
+    if (blocks <= 0) return MI3D_OK;
+    if (blocks > 0x7fffffffll) return MI3D_ERR_UNSUPPORTED;
+    int st = gconv_attributes();
+    if (st) return st;
+    if (CB == 2) f32_gconv_classes_kernel<2><<<(unsigned)blocks, 256, lds, s>>>(Q);
+    else f32_gconv_classes_kernel<1><<<(unsigned)blocks, 256, lds, s>>>(Q);
     return check_launch();
 }
 
@@ -623,6 +713,12 @@ int f32_conv(const Geom& g, int pass, const void* in, const void* w, void* out, 
         if (g.hi) { B.out2 = (float*)g.hi; B.out_pitch = M / 2; B.out_split = M / 2; }
     }
     const int sD = dgrad ? g.sD : 1, sH = dgrad ? g.sH : 1, sW = dgrad ? g.sW : 1;   // number of classes per axis
+    // Classes with the same work each (2x2x2: one tap per class) go into one launch, where they share their input
+    // patch through the L2 (192^3, N = 2: 1.74 -> 1.58 ms; 48^3: 0.63 -> 0.30).  Classes of 1 to 8 taps (3x3x3) keep a
+    // launch each: merged, their mix left CUs with the eight-tap workgroups behind (6.0 against 5.4 ms).
+    const bool classes = sD * sH * sW > 1 && g.kD <= g.sD && g.kH <= g.sH && g.kW <= g.sW;
+    GcMulti Q;
+    Q.ncls = 0;
     for (int pd = 0; pd < sD; ++pd)
         for (int ph = 0; ph < sH; ++ph)
             for (int pw = 0; pw < sW; ++pw) {
@@ -662,10 +758,11 @@ int f32_conv(const Geom& g, int pass, const void* in, const void* w, void* out, 
                 P.prows = (TJH - 1) * P.ish + (hmax - hmin) + 1;
                 P.pcols = (TJW - 1) * P.isw + (wmax - wmin) + 1;
                 P.wpack = (const float*)ws;
+                if (classes) { Q.p[Q.ncls++] = P; continue; }
                 st = launch_gconv(P, s);
                 if (st) return st;
             }
-    return MI3D_OK;
+    return classes ? launch_gconv_classes(Q, s) : MI3D_OK;
 }
 
 int f32_wgrad(const Geom& g, const void* x, const void* dy, float* dw, void* ws, size_t ws_bytes, hipStream_t s) {
