@@ -27,7 +27,9 @@ namespace {
 
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 
-constexpr int TJH = 8, TJW = 32;     // j tile of a workgroup (rows, columns); 2 rows per wave
+// j tile of a workgroup: 256 positions, 8 rows x 32 columns or 16 x 16 (whichever covers the plane with fewer positions
+// outside it: 48 columns are 3 x 16 but 2 x 32 with a quarter wasted, 12 x 12 fits one 16 x 16 tile).  A wave owns two
+// MFMA blocks of 32 positions; position f of the tile is row f / TJW, column f % TJW.
 constexpr int MAX_TAPS = 27;
 constexpr int LDS_SOFT = 64 * 1024;  // two workgroups per CU while the tiles fit this
 
@@ -49,6 +51,7 @@ struct GcParams {
     signed char th[MAX_TAPS], tw[MAX_TAPS];  // row / column offsets of each tap
     signed char tapidx[MAX_TAPS];            // its index in the layer's own tap order (slot in wpack)
     int hmin, wmin, prows, pcols;          // smallest offsets; patch extent in LDS
+    int TJH, TJW, LW;                      // tile rows, columns (a power of two, 2^LW)
     int CK;                                // contracted channels per stage (even)
 };
 
@@ -63,7 +66,10 @@ __device__ __forceinline__ void gconv_tile(const GcParams& P, float* lds_f, int 
     const int xp = P.CK + 1;                                   // channel pitch of a staged voxel (odd: no bank conflicts)
     float* xs = lds_f;                                         // [prows][pcols][CK + 1]
     float* ws = lds_f + ((P.prows * P.pcols * xp + 3) & ~3);   // [taps of the group][CK][32 CB]
-    const int jh0 = jht * TJH, jw0 = jwt * TJW, m0 = mt * 32 * CB;
+    const int jh0 = jht * P.TJH, jw0 = jwt * P.TJW, m0 = mt * 32 * CB;
+    // this lane's position in each of the wave's two blocks
+    const int f0 = (2 * wave) * 32 + ln, f1 = f0 + 32;
+    const int tr0 = f0 >> P.LW, tc0 = f0 & (P.TJW - 1), tr1 = f1 >> P.LW, tc1 = f1 & (P.TJW - 1);
 
     f32x16 acc[2][CB];
 #pragma unroll
@@ -74,7 +80,6 @@ __device__ __forceinline__ void gconv_tile(const GcParams& P, float* lds_f, int 
             for (int i = 0; i < 16; ++i) acc[r][cb][i] = 0.f;
 
     const long long in_plane = (long long)P.Hi * P.Wi * P.in_pitch;
-    const int row0 = 2 * wave;   // first of this wave's two rows inside the tile
     for (int c0 = 0; c0 < P.K; c0 += P.CK) {
         const bool hi_in = c0 >= P.in_split;
         const float* src = (hi_in ? P.in2 : P.in) + (long long)n * P.Di * in_plane + (hi_in ? c0 - P.in_split : c0);
@@ -124,8 +129,8 @@ __device__ __forceinline__ void gconv_tile(const GcParams& P, float* lds_f, int 
             // ---- MFMAs: per tap and pair of contracted channels, 2 rows x CB blocks
             for (int tp = 0; tp < nt; ++tp) {
                 const int dh = P.th[t0 + tp] - P.hmin, dw = P.tw[t0 + tp] - P.wmin;
-                const float* b0 = xs + (((row0 + 0) * P.ish + dh) * P.pcols + ln * P.isw + dw) * xp + half;
-                const float* b1 = xs + (((row0 + 1) * P.ish + dh) * P.pcols + ln * P.isw + dw) * xp + half;
+                const float* b0 = xs + ((tr0 * P.ish + dh) * P.pcols + tc0 * P.isw + dw) * xp + half;
+                const float* b1 = xs + ((tr1 * P.ish + dh) * P.pcols + tc1 * P.isw + dw) * xp + half;
                 const float* a = ws + (tp * P.CK + half) * wrow + ln;
 #pragma unroll 4
                 for (int kk = 0; kk < P.CK; kk += 2) {
@@ -144,7 +149,7 @@ __device__ __forceinline__ void gconv_tile(const GcParams& P, float* lds_f, int 
     const bool vec = (P.out_pitch & 3) == 0;
 #pragma unroll
     for (int r = 0; r < 2; ++r) {
-        const int jh = jh0 + row0 + r, jw = jw0 + ln;
+        const int jh = jh0 + (r ? tr1 : tr0), jw = jw0 + (r ? tc1 : tc0);
         if (jh >= P.Jh || jw >= P.Jw) continue;
         const int od = P.osd * jd + P.ood, oh = P.osh * jh + P.ooh, ow = P.osw * jw + P.oow;
         const long long vox = (((long long)n * P.Do + od) * P.Ho + oh) * P.Wo + ow;
@@ -491,6 +496,9 @@ size_t pack_bytes(const Geom& g, int pass) {
 void wgrad_layout(const Geom& g, WgParams* P) {
     P->TR = 2;
     P->TW = (g.sW == 1) ? 32 : 16;
+    // (stride 1: 4 rows x 16 columns where that leaves fewer positions outside the plane, e.g. 48 = 3 x 16 columns)
+    auto padded = [&](int tr, int tw) { return (long long)((g.Ho + tr - 1) / tr * tr) * ((g.Wo + tw - 1) / tw * tw); };
+    if (g.sW == 1 && padded(4, 16) < padded(2, 32)) { P->TR = 4; P->TW = 16; }
     P->prows = (P->TR - 1) * g.sH + g.kH;
     P->pcols = (P->TW - 1) * g.sW + g.kW;
     P->pcols_magic = 65536u / (unsigned)P->pcols + 1u;
@@ -583,6 +591,15 @@ bool f32_takes_halves(const Geom& g, int pass) {   // virtual concatenation: hal
     return f32_supported(g, pass) && g.Cin % 64 == 0;
 }
 
+// 8 x 32 unless 16 x 16 covers the iteration plane with fewer positions outside it
+static void gconv_tile_shape(GcParams* P) {
+    auto padded = [&](int th, int tw) { return (long long)((P->Jh + th - 1) / th * th) * ((P->Jw + tw - 1) / tw * tw); };
+    const bool square = padded(16, 16) < padded(8, 32);
+    P->TJH = square ? 16 : 8;
+    P->TJW = square ? 16 : 32;
+    P->LW = square ? 4 : 5;
+}
+
 static int gconv_attributes() {
     static std::atomic<bool> attr_set{false};   // set once per process; a second thread racing here repeats an idempotent call
     if (!attr_set) {
@@ -617,8 +634,8 @@ static int gconv_blocks_of_channels(const GcParams& P, long long tiles, int ntap
 
 // tiles, channel chunk and LDS bytes of one launch (or one class of a launch) for CB blocks of output channels
 static int gconv_prepare(GcParams& P, int CB, size_t* lds) {
-    P.JHT = (P.Jh + TJH - 1) / TJH;
-    P.JWT = (P.Jw + TJW - 1) / TJW;
+    P.JHT = (P.Jh + P.TJH - 1) / P.TJH;
+    P.JWT = (P.Jw + P.TJW - 1) / P.TJW;
     P.MT = (P.Mpad + 32 * CB - 1) / (32 * CB);
     // contracted channels per stage: the largest even chunk that keeps the tiles of a stage within LDS_SOFT
     int max_group = 1;
@@ -638,7 +655,7 @@ static int gconv_prepare(GcParams& P, int CB, size_t* lds) {
 }
 
 static int launch_gconv(GcParams& P, hipStream_t s) {
-    const int CB = gconv_blocks_of_channels(P, (long long)P.N * P.Jd * ((P.Jh + TJH - 1) / TJH) * ((P.Jw + TJW - 1) / TJW), P.ntaps);
+    const int CB = gconv_blocks_of_channels(P, (long long)P.N * P.Jd * ((P.Jh + P.TJH - 1) / P.TJH) * ((P.Jw + P.TJW - 1) / P.TJW), P.ntaps);
     size_t lds = 0;
     int st = gconv_prepare(P, CB, &lds);
     if (st) return st;
@@ -658,7 +675,7 @@ static int launch_gconv_classes(GcMulti& Q, hipStream_t s) {
     int ntaps = 0;
     for (int c = 0; c < Q.ncls; ++c) {
         const GcParams& P = Q.p[c];
-        const long long tc = (long long)P.N * P.Jd * ((P.Jh + TJH - 1) / TJH) * ((P.Jw + TJW - 1) / TJW);
+        const long long tc = (long long)P.N * P.Jd * ((P.Jh + P.TJH - 1) / P.TJH) * ((P.Jw + P.TJW - 1) / P.TJW);
         tiles += tc;
         ntaps = ntaps > P.ntaps ? ntaps : P.ntaps;
     }
@@ -755,8 +772,9 @@ int f32_conv(const Geom& g, int pass, const void* in, const void* w, void* out, 
                 P.gstart[P.ngroups] = P.ntaps;
                 if (P.ntaps == 0) { hmin = hmax = wmin = wmax = 0; }   // a class no tap reaches: zeros (plus the epilogue)
                 P.hmin = hmin; P.wmin = wmin;
-                P.prows = (TJH - 1) * P.ish + (hmax - hmin) + 1;
-                P.pcols = (TJW - 1) * P.isw + (wmax - wmin) + 1;
+                gconv_tile_shape(&P);
+                P.prows = (P.TJH - 1) * P.ish + (hmax - hmin) + 1;
+                P.pcols = (P.TJW - 1) * P.isw + (wmax - wmin) + 1;
                 P.wpack = (const float*)ws;
                 if (classes) { Q.p[Q.ncls++] = P; continue; }
                 st = launch_gconv(P, s);

@@ -110,6 +110,11 @@ MID_F32 = [
     (2, 6, 10, 14, 64, 128, 2, 2, 0),
     (1, 7, 9, 11, 6, 10, 3, 2, 1),
     (1, 6, 7, 9, 34, 36, (3, 2, 3), (1, 2, 1), (1, 0, 2)),
+    # planes that 16 x 16 (weight gradient: 4 x 16) tiles cover better than 8 x 32 (2 x 32)
+    (1, 4, 30, 46, 32, 64, 3, 1, 1),
+    (2, 5, 31, 93, 32, 64, 3, 2, 1),
+    (1, 4, 11, 12, 64, 96, 3, 1, 1),
+    (1, 4, 22, 24, 32, 64, 2, 2, 0),
 ]
 
 
