@@ -474,6 +474,33 @@ def fp32_steps():
         torch.cuda.empty_cache()
     return out
 
+def fp32_step_alone(args):
+    """The unswapped fp32 step at 192^3, N = 2, timed over args.steps steps; every convolution call bracketed by HIP events."""
+    import torch
+    import synth_inputs as si
+    from paper_1812_07816_amd import conv3d as mc, unet
+    N, vol, ch, norm = 2, 192, [32, 64, 128, 256, 320], not args.no_norm
+    x = torch.from_numpy(si.normal(5, 0, (N, vol, vol, vol, 4), bf16=True)).cuda()
+    labels = torch.from_numpy(si.ellipsoid_labels(5, 1, N, vol)).cuda()
+    step = unet.UNetStep(N, vol, ch, si.unet_weights(5, ch), x, labels, swap=False, dtype=torch.float32, norm=norm)
+    for _ in range(args.warmup):
+        step.run()
+    torch.cuda.synchronize()
+    rec = CallRecorder(mc)
+    with rec:
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step.run()
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    kern = rec.by_kernel(4)
+    return {"workload": f"5-level 3D U-Net training step at {vol}^3, N={N}, fp32, " + ("with" if norm else "without") + " instance normalisation, SGD",
+            "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "conv_tflops": step.flops / ms / 1e9,
+            "frac_of_fp32_mfma_peak": step.flops / ms / 1e9 / MFMA_F32_PEAK_TFLOPS,
+            "kernels": {k: {q: (round(v, 4) if isinstance(v, float) else v) for q, v in roofline_entry(a, MFMA_F32_PEAK_TFLOPS, args.steps).items()}
+                        for k, a in sorted(kern.items(), key=lambda kv: -kv[1]["ms"])}}
+
+
 def level0_chain(args):
     """Config 3: the first U-Net level at 192^3, N = 1 (Conv3D 4->32, 32->32, stride-2 32->64; forward, data gradient and
     weight gradient of each), every pass timed alone with HIP events over warm back-to-back launches, with the swap
@@ -633,6 +660,9 @@ def main():
     ap.add_argument("--no-norm", action="store_true", help="headline step without the instance normalisation")
     ap.add_argument("--level0-only", action="store_true",
                     help="only the first U-Net level at 192^3, N=1 (config 3), every pass alone: the command its profiles are taken with")
+    ap.add_argument("--fp32-only", action="store_true",
+                    help="only the fp32 training step at 192^3, N=2, no swapping (with --no-norm: convolution -> LeakyReLU): the command "
+                         "its profile is taken with")
     ap.add_argument("--unet-layers", action="store_true",
                     help="also time fwd/dgrad/wgrad of every Conv3D layer of the 5-level U-Net at 192^3, N=1, each alone (adds ~20 s)")
     args = ap.parse_args()
@@ -658,6 +688,9 @@ def main():
 
     if args.level0_only:
         print(json.dumps({"level0_192": level0_chain(args)}))
+        return
+    if args.fp32_only:
+        print(json.dumps({"fp32_step": fp32_step_alone(args)}))
         return
     # ---- the headline: config 5, the whole training step of the 5-level U-Net at 192^3, N = 2, bf16, with the block
     # of Section 4.1 (convolution -> instance normalisation -> LeakyReLU), soft Dice, SGD, and the swap engine under
