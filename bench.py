@@ -49,9 +49,9 @@ def profiled_avg_us(kernel):
     return None if v is None else v[0]
 
 
-def probe_mfma_tflops(random_operands, iters=100000):
-    """Rate of a bare bf16 MFMA loop with all-zero or pseudo-random operands (TFLOP/s), timed with events on the
-    current stream.  The loop lives in libbench_probe.so (bench_probe.hip, built by __graft_entry__.build())."""
+def probe_mfma_tflops(random_operands, iters=100000, f32=False):
+    """Rate of a bare bf16 (f32: fp32) MFMA loop with all-zero or pseudo-random operands (TFLOP/s), timed with events on
+    the current stream.  The loop lives in libbench_probe.so (bench_probe.hip, built by __graft_entry__.build())."""
     import ctypes
     import torch
     path = os.path.join(ROOT, "libbench_probe.so")
@@ -59,15 +59,16 @@ def probe_mfma_tflops(random_operands, iters=100000):
         return None
     l = ctypes.CDLL(path)
     l.bench_probe_mfma_workspace_bytes.restype = ctypes.c_size_t
-    l.bench_probe_mfma.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t, ctypes.POINTER(ctypes.c_double), ctypes.c_void_p]
+    fn = l.bench_probe_mfma_f32 if f32 else l.bench_probe_mfma
+    fn.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t, ctypes.POINTER(ctypes.c_double), ctypes.c_void_p]
     ws = torch.empty(l.bench_probe_mfma_workspace_bytes(), dtype=torch.uint8, device="cuda")
     fl = ctypes.c_double()
     s = torch.cuda.current_stream()
     sp = ctypes.c_void_p(s.cuda_stream)
-    assert l.bench_probe_mfma(int(random_operands), 2000, ws.data_ptr(), ws.numel(), ctypes.byref(fl), sp) == 0   # warm-up
+    assert fn(int(random_operands), 2000, ws.data_ptr(), ws.numel(), ctypes.byref(fl), sp) == 0   # warm-up
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     e0.record(s)
-    assert l.bench_probe_mfma(int(random_operands), int(iters), ws.data_ptr(), ws.numel(), ctypes.byref(fl), sp) == 0
+    assert fn(int(random_operands), int(iters), ws.data_ptr(), ws.numel(), ctypes.byref(fl), sp) == 0
     e1.record(s)
     torch.cuda.synchronize()
     return fl.value / e0.elapsed_time(e1) / 1e9
@@ -410,7 +411,8 @@ def fp32_steps():
     import synth_inputs as si
     from paper_1812_07816_amd import swap as sw, unet
     N, ch = 2, [32, 64, 128, 256, 320]
-    out = {"dtype": "f32", "peak_tflops": MFMA_F32_PEAK_TFLOPS, "runs": []}
+    out = {"dtype": "f32", "peak_tflops": MFMA_F32_PEAK_TFLOPS, "runs": [],
+           "bare_mfma_loop_tflops": {"zero_operands": probe_mfma_tflops(0, 25000, f32=True), "random_operands": probe_mfma_tflops(1, 25000, f32=True)}}
 
     def timed(step, steps=3, warmup=1):
         for _ in range(warmup):
