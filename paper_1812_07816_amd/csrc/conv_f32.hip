@@ -31,7 +31,11 @@ typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 // outside it: 48 columns are 3 x 16 but 2 x 32 with a quarter wasted, 12 x 12 fits one 16 x 16 tile).  A wave owns two
 // MFMA blocks of 32 positions; position f of the tile is row f / TJW, column f % TJW.
 constexpr int MAX_TAPS = 27;
-constexpr int LDS_SOFT = 64 * 1024;  // two workgroups per CU while the tiles fit this
+// Budget for the tiles of a stage.  40 KB makes a stage 8 contracted channels deep for the 3x3x3 layers (21 KB with
+// 32 output channels per workgroup, 31 KB with 64), so that several workgroups share a CU and one's staging hides behind
+// the others' MFMAs: 64->32 at 192^3 93 -> 106 TFLOP/s, 128->64 at 96^3 98 -> 112 (64 KB: 16 channels; 20 KB: 4
+// channels, slower again: 92 and 100).
+constexpr int LDS_SOFT = 40 * 1024;
 
 struct GcParams {
     const float* in; const float* in2;     // input (second half of the channels of a virtually concatenated input)

@@ -204,10 +204,11 @@ def test_fp32_step_end_to_end_against_the_exact_oracle_step(unet):
         cos = np.sum(gg * r) / np.sqrt(np.sum(gg * gg) * np.sum(r * r))
         print(f"{name}: max error {e:.2e}, norm ratio - 1 = {ratio - 1.0:+.1e}, 1 - cos = {1.0 - cos:.1e}")
         # A handful of pre-activations lie so close to zero that the fp32 and the fp64 sums put them on different
-        # LeakyReLU branches; each such voxel changes a few gradient elements by up to 1e-2 of the rms.  Length and
-        # direction of every gradient are what a wrong scale, a dropped term or a wrong operand would move.
+        # LeakyReLU branches; each such voxel changes a few gradient elements by a few 1e-2 of the rms (which voxels
+        # depends on the order of the fp32 sums: 1.4e-2 at worst with 16 contracted channels per stage, 3.9e-2 with 8).
+        # Length and direction of every gradient are what a wrong scale, a dropped term or a wrong operand would move.
         assert abs(ratio - 1.0) <= 2e-4 and 1.0 - cos <= 1e-6, (name, ratio, cos)
-        assert e <= 2e-2, (name, e)
+        assert e <= 6e-2, (name, e)
         assert np.allclose(wm.cpu().numpy(), wr, rtol=1e-4, atol=1e-6), name
     print(f"worst weight-gradient error of the fp32 step against the exact oracle step: {worst:.2e}")
 
