@@ -36,6 +36,7 @@ constexpr int MAX_TAPS = 27;
 // the others' MFMAs: 64->32 at 192^3 93 -> 106 TFLOP/s, 128->64 at 96^3 98 -> 112 (64 KB: 16 channels; 20 KB: 4
 // channels, slower again: 92 and 100).
 constexpr int LDS_SOFT = 40 * 1024;
+constexpr int LDS_SOFT_STRIDED = 64 * 1024;   // forward passes with stride 2
 
 struct GcParams {
     const float* in; const float* in2;     // input (second half of the channels of a virtually concatenated input)
@@ -657,7 +658,10 @@ static int gconv_prepare(GcParams& P, int CB, size_t* lds) {
     int ck = 32;
     const int kpad = (P.K + 1) & ~1;
     if (ck > kpad) ck = kpad;
-    while (ck > 2 && (lds_bytes(ck) > (size_t)LDS_SOFT || (kpad % ck && ck > 4))) ck >>= 1;
+    // (strided reads: the patch is four times the tile and the layer is bound by its staging, which deeper stages
+    // repeat less often: 32->64 2x2x2 stride 2 at 192^3 1.14 ms with the larger budget, 2.04 with the smaller)
+    const size_t soft = (P.isd > 1 || P.ish > 1 || P.isw > 1) ? (size_t)LDS_SOFT_STRIDED : (size_t)LDS_SOFT;
+    while (ck > 2 && (lds_bytes(ck) > soft || (kpad % ck && ck > 4))) ck >>= 1;
     if (ck < 2) ck = 2;
     if (lds_bytes(ck) > 160 * 1024) return MI3D_ERR_UNSUPPORTED;
     P.CK = ck;
