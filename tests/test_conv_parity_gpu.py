@@ -152,6 +152,19 @@ def test_208cube_layers(device, layer):
                            n_samples=40000, n_wgrad_samples=48), True, f"208 {layer}")
 
 
+# ---- the fp32 step's layers at their own size (N = 2): launch shapes that depend on the size of the grid (32- or
+# 64-channel workgroups, 8 x 32 or 16 x 16 tiles, merged parity classes, folded taps), sampled against the oracle
+FULL_F32 = [(192, 4, 32, 3, 1, 1), (192, 32, 32, 3, 1, 1), (96, 64, 128, 3, 2, 1), (48, 128, 128, 3, 1, 1), (24, 256, 256, 3, 1, 1),
+            (12, 320, 320, 3, 1, 1), (192, 32, 64, 2, 2, 0), (192, 32, 3, 1, 1, 0)]
+
+
+@pytest.mark.parametrize("layer", FULL_F32)
+def test_fp32_layers_at_the_size_of_the_step(device, layer):
+    vol, cin, cout, k, s, p = layer
+    _check(parity.run_case(5, 100 + 10 * FULL_F32.index(layer), 2, vol, vol, vol, cin, cout, k, s, p, bf16=False, full=False,
+                           n_samples=40000, n_wgrad_samples=48), False, f"fp32 N=2 {layer}")
+
+
 # ---- config 4: every layer shape of the 5-level U-Net at 192^3 -------------
 CH = [32, 64, 128, 256, 320]
 VOL = [192, 96, 48, 24, 12]
