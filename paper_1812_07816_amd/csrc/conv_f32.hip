@@ -18,7 +18,7 @@
 //
 // Weight gradient: contraction over positions, A = dy (M = 32 output channels, K = 2 neighbouring positions along W),
 // B = x at the tap's shift (N = 32 input channels); a workgroup owns one 32 x 32 block of (cout, cin) for all taps
-// (dealt round-robin to its 4 waves) over a range of position tiles; per-workgroup partial sums are added in index
+// (dealt round-robin to its 8 waves) over a range of position tiles; per-workgroup partial sums are added in index
 // order by reduce_partials (bit-reproducible).
 #include "mi3d_internal.h"
 
@@ -259,10 +259,16 @@ struct WgParams {
     unsigned pcols_magic;              // q / pcols == (q * pcols_magic) >> 16 for every q < prows * pcols (checked on the host)
 };
 
+// Waves, threads of a weight-gradient workgroup.  Eight waves share the staged tiles and take 3 or 4 taps each (64
+// accumulator registers instead of 112 with four waves), so two workgroups per CU are four waves per SIMD: 91 -> 100
+// TFLOP/s on the 192^3 layers.  Sixteen waves in one workgroup per CU: 88 (no second workgroup to compute while this
+// one stages).
+constexpr int WG_NW = 8, WG_NT = 64 * WG_NW;
+
 // A workgroup walks a contiguous range of (sample, tile, output plane) units with the output plane running fastest, so
 // consecutive units share input planes: the kD planes a unit needs live in a ring of kD LDS slots (plane id in slot
 // id mod kD) and only the planes that were not there for the previous unit are fetched.
-__global__ void __launch_bounds__(256, 2) f32_wgrad_kernel(WgParams P) {
+__global__ void __launch_bounds__(WG_NT, 2) f32_wgrad_kernel(WgParams P) {
     extern __shared__ __attribute__((aligned(16))) float lds_f[];
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     const int ln = lane & 31, half = lane >> 5;
@@ -279,7 +285,7 @@ __global__ void __launch_bounds__(256, 2) f32_wgrad_kernel(WgParams P) {
     const float* xsrc = (hi_x ? P.x2 : P.x) + (hi_x ? ci0 - P.x_split : ci0);
     const bool vec_x = (P.x_pitch & 3) == 0 && (P.Cin & 3) == 0, vec_dy = (P.Cout & 3) == 0;
 
-    constexpr int MAXA = 7;   // taps per wave: 27 taps dealt round-robin to 4 waves
+    constexpr int MAXA = (27 + WG_NW - 1) / WG_NW;   // taps per wave: 27 taps dealt round-robin to the waves
     f32x16 acc[MAXA];
 #pragma unroll
     for (int a = 0; a < MAXA; ++a)
@@ -288,7 +294,7 @@ __global__ void __launch_bounds__(256, 2) f32_wgrad_kernel(WgParams P) {
 
     const long long u0 = P.units * split / P.S, u1 = P.units * (split + 1) / P.S;
     const long long x_plane = (long long)P.H * P.W * P.x_pitch;
-    const int c4 = t & 7, vslot = t >> 3;   // staging: 8 threads x 16 bytes per voxel, 32 voxels per pass
+    const int c4 = t & 7, vslot = t >> 3;   // staging: 8 threads x 16 bytes per voxel, WG_NT / 8 voxels per pass
     long long cur_col = -1;
     int have_lo = 1, have_hi = 0;           // input planes resident in the ring (none)
     for (long long u = u0; u < u1; ++u) {
@@ -304,7 +310,7 @@ __global__ void __launch_bounds__(256, 2) f32_wgrad_kernel(WgParams P) {
         __syncthreads();   // every wave is done with the previous unit's tiles
         // ---- dy tile: TR rows x TW columns x 32 output channels (zero outside the tensor)
         if (vec_dy) {
-            for (int v = vslot; v < P.TR * P.TW; v += 32) {
+            for (int v = vslot; v < P.TR * P.TW; v += WG_NT / 8) {
                 const int tr = v / P.TW, tc = v - tr * P.TW;
                 const int oh = oh0 + tr, ow = ow0 + tc;
                 float4 val = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -313,7 +319,7 @@ __global__ void __launch_bounds__(256, 2) f32_wgrad_kernel(WgParams P) {
                 *(float4*)(dys + v * CP + 4 * c4) = val;
             }
         } else {
-            for (int e = t; e < P.TR * P.TW * 32; e += 256) {
+            for (int e = t; e < P.TR * P.TW * 32; e += WG_NT) {
                 const int c = e & 31, v = e >> 5;
                 const int tr = v / P.TW, tc = v - tr * P.TW;
                 const int oh = oh0 + tr, ow = ow0 + tc;
@@ -330,7 +336,7 @@ __global__ void __launch_bounds__(256, 2) f32_wgrad_kernel(WgParams P) {
             const bool plane_ok = id >= 0 && id < P.D;
             const float* src = xsrc + ((long long)n * P.D + (plane_ok ? id : 0)) * x_plane;
             if (vec_x) {
-                for (int q = vslot; q < pv; q += 32) {
+                for (int q = vslot; q < pv; q += WG_NT / 8) {
                     const int pr = (int)(((unsigned)q * P.pcols_magic) >> 16), pc = q - pr * P.pcols;
                     const int ih = oh0 * P.sH - P.pH + pr, iw = ow0 * P.sW - P.pW + pc;
                     float4 val = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -339,7 +345,7 @@ __global__ void __launch_bounds__(256, 2) f32_wgrad_kernel(WgParams P) {
                     *(float4*)(dst + q * CP + 4 * c4) = val;
                 }
             } else {
-                for (int e = t; e < pv * 32; e += 256) {
+                for (int e = t; e < pv * 32; e += WG_NT) {
                     const int c = e & 31, q = e >> 5;
                     const int pr = (int)(((unsigned)q * P.pcols_magic) >> 16), pc = q - pr * P.pcols;
                     const int ih = oh0 * P.sH - P.pH + pr, iw = ow0 * P.sW - P.pW + pc;
@@ -355,7 +361,7 @@ __global__ void __launch_bounds__(256, 2) f32_wgrad_kernel(WgParams P) {
         // ---- this wave's taps: K runs over pairs of neighbouring output columns
 #pragma unroll
         for (int a = 0; a < MAXA; ++a) {
-            const int tap = wave + 4 * a;
+            const int tap = wave + WG_NW * a;
             if (tap >= P.T) break;
             const int kw = tap % P.kW, kh = (tap / P.kW) % P.kH, kd = tap / (P.kW * P.kH);
             const int id = need_lo + kd;
@@ -373,7 +379,7 @@ __global__ void __launch_bounds__(256, 2) f32_wgrad_kernel(WgParams P) {
     float* part = P.part + (long long)split * P.Cout * P.T * P.Cin;
 #pragma unroll
     for (int a = 0; a < MAXA; ++a) {
-        const int tap = wave + 4 * a;
+        const int tap = wave + WG_NW * a;
         if (tap >= P.T) break;
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
@@ -826,7 +832,7 @@ int f32_wgrad(const Geom& g, const void* x, const void* dy, float* dw, void* ws,
         if (e != hipSuccess) { note_hip_error(e); return MI3D_ERR_HIP; }
         attr_set = true;
     }
-    f32_wgrad_kernel<<<(unsigned)(P.CIT * P.COT * P.S), 256, lds, s>>>(P);
+    f32_wgrad_kernel<<<(unsigned)(P.CIT * P.COT * P.S), WG_NT, lds, s>>>(P);
     int st = check_launch();
     if (st) return st;
     return reduce_partials((const float*)ws, dw, g.w_elems(), P.S, s);
