@@ -31,6 +31,11 @@ typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 // outside it: 48 columns are 3 x 16 but 2 x 32 with a quarter wasted, 12 x 12 fits one 16 x 16 tile).  A wave owns two
 // MFMA blocks of 32 positions; position f of the tile is row f / TJW, column f % TJW.
 constexpr int MAX_TAPS = 27;
+// Waves of a convolution workgroup with 32 / 64 output channels.  With 64 channels eight waves take one block of 32
+// positions each (72 registers instead of 107: six or seven waves per SIMD instead of four; strided forward 2.90 ->
+// 2.44 ms at 192^3, the stride-1 layers 1 % faster); with 32 channels four waves of two blocks stay (eight: 96 instead
+// of 103 TFLOP/s, every weight read then feeds one MFMA instead of two).
+constexpr int GC_NW1 = 4, GC_NW2 = 8;
 // Budget for the tiles of a stage.  40 KB makes a stage 8 contracted channels deep for the 3x3x3 layers (21 KB with
 // 32 output channels per workgroup, 31 KB with 64), so that several workgroups share a CU and one's staging hides behind
 // the others' MFMAs: 64->32 at 192^3 93 -> 106 TFLOP/s, 128->64 at 96^3 98 -> 112 (64 KB: 16 channels; 20 KB: 4
@@ -64,8 +69,9 @@ __device__ __forceinline__ f32x16 mfma2(float a, float b, f32x16 c) { return __b
 
 // The work of one workgroup: tile (n, jd, jht, jwt) of the iteration space, output channel block mt.
 // CB = 32-wide blocks of output channels per workgroup
-template <int CB>
+template <int CB, int NW>
 __device__ __forceinline__ void gconv_tile(const GcParams& P, float* lds_f, int n, int jd, int jht, int jwt, int mt) {
+    constexpr int NB = 8 / NW, NT = 64 * NW;   // blocks of 32 positions per wave, threads
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     const int ln = lane & 31, half = lane >> 5;
     const int xp = P.CK + 1;                                   // channel pitch of a staged voxel (odd: no bank conflicts)
@@ -73,12 +79,12 @@ __device__ __forceinline__ void gconv_tile(const GcParams& P, float* lds_f, int 
     float* ws = lds_f + ((P.prows * P.pcols * xp + 3) & ~3);   // [taps of the group][CK][32 CB]
     const int jh0 = jht * P.TJH, jw0 = jwt * P.TJW, m0 = mt * 32 * CB;
     // this lane's position in each of the wave's two blocks
-    const int f0 = (2 * wave) * 32 + ln, f1 = f0 + 32;
+    const int f0 = (NB * wave) * 32 + ln, f1 = NB == 2 ? f0 + 32 : f0;
     const int tr0 = f0 >> P.LW, tc0 = f0 & (P.TJW - 1), tr1 = f1 >> P.LW, tc1 = f1 & (P.TJW - 1);
 
-    f32x16 acc[2][CB];
+    f32x16 acc[NB][CB];
 #pragma unroll
-    for (int r = 0; r < 2; ++r)
+    for (int r = 0; r < NB; ++r)
 #pragma unroll
         for (int cb = 0; cb < CB; ++cb)
 #pragma unroll
@@ -97,7 +103,7 @@ __device__ __forceinline__ void gconv_tile(const GcParams& P, float* lds_f, int 
             const int nvox = P.prows * P.pcols;
             if ((P.CK & 3) == 0 && (P.in_pitch & 3) == 0) {
                 const int q4 = P.CK >> 2;
-                for (int e = t; e < nvox * q4; e += 256) {
+                for (int e = t; e < nvox * q4; e += NT) {
                     const int v = e / q4, q = e - v * q4;
                     const int pr = v / P.pcols, pc = v - pr * P.pcols;
                     const int ih = P.ish * jh0 + P.hmin + pr, iw = P.isw * jw0 + P.wmin + pc;
@@ -108,7 +114,7 @@ __device__ __forceinline__ void gconv_tile(const GcParams& P, float* lds_f, int 
                     d[0] = val.x; d[1] = val.y; d[2] = val.z; d[3] = val.w;
                 }
             } else {   // ragged channel counts: element by element, zero beyond K
-                for (int e = t; e < nvox * P.CK; e += 256) {
+                for (int e = t; e < nvox * P.CK; e += NT) {
                     const int v = e / P.CK, q = e - v * P.CK;
                     const int pr = v / P.pcols, pc = v - pr * P.pcols;
                     const int ih = P.ish * jh0 + P.hmin + pr, iw = P.isw * jw0 + P.wmin + pc;
@@ -120,7 +126,7 @@ __device__ __forceinline__ void gconv_tile(const GcParams& P, float* lds_f, int 
             }
             // ---- weights of the group's taps: ws[tap][k][m] for m in this workgroup's blocks
             const int wrow = 32 * CB;
-            for (int e = t; e < nt * P.CK * (wrow >> 2); e += 256) {
+            for (int e = t; e < nt * P.CK * (wrow >> 2); e += NT) {
                 const int m4 = e % (wrow >> 2);
                 const int k = (e / (wrow >> 2)) % P.CK;
                 const int tp = e / ((wrow >> 2) * P.CK);
@@ -137,14 +143,23 @@ __device__ __forceinline__ void gconv_tile(const GcParams& P, float* lds_f, int 
                 const float* b0 = xs + ((tr0 * P.ish + dh) * P.pcols + tc0 * P.isw + dw) * xp + half;
                 const float* b1 = xs + ((tr1 * P.ish + dh) * P.pcols + tc1 * P.isw + dw) * xp + half;
                 const float* a = ws + (tp * P.CK + half) * wrow + ln;
+                if constexpr (NB == 2) {
 #pragma unroll 4
-                for (int kk = 0; kk < P.CK; kk += 2) {
-                    const float x0 = b0[kk], x1 = b1[kk];
+                    for (int kk = 0; kk < P.CK; kk += 2) {
+                        const float x0 = b0[kk], x1 = b1[kk];
 #pragma unroll
-                    for (int cb = 0; cb < CB; ++cb) {
-                        const float wv = a[kk * wrow + 32 * cb];
-                        acc[0][cb] = mfma2(wv, x0, acc[0][cb]);
-                        acc[1][cb] = mfma2(wv, x1, acc[1][cb]);
+                        for (int cb = 0; cb < CB; ++cb) {
+                            const float wv = a[kk * wrow + 32 * cb];
+                            acc[0][cb] = mfma2(wv, x0, acc[0][cb]);
+                            acc[1][cb] = mfma2(wv, x1, acc[1][cb]);
+                        }
+                    }
+                } else {
+#pragma unroll 4
+                    for (int kk = 0; kk < P.CK; kk += 2) {
+                        const float x0 = b0[kk];
+#pragma unroll
+                        for (int cb = 0; cb < CB; ++cb) acc[0][cb] = mfma2(a[kk * wrow + 32 * cb], x0, acc[0][cb]);
                     }
                 }
             }
@@ -157,7 +172,7 @@ __device__ __forceinline__ void gconv_tile(const GcParams& P, float* lds_f, int 
     // the lower occupancy, more than it gains.
     const bool vec = (P.out_pitch & 3) == 0;
 #pragma unroll
-    for (int r = 0; r < 2; ++r) {
+    for (int r = 0; r < NB; ++r) {
         const int jh = jh0 + (r ? tr1 : tr0), jw = jw0 + (r ? tc1 : tc0);
         if (jh >= P.Jh || jw >= P.Jw) continue;
         const int od = P.osd * jd + P.ood, oh = P.osh * jh + P.ooh, ow = P.osw * jw + P.oow;
@@ -203,8 +218,8 @@ __device__ __forceinline__ void gconv_tile(const GcParams& P, float* lds_f, int 
     }
 }
 
-template <int CB>
-__global__ void __launch_bounds__(256, 2) f32_gconv_kernel(GcParams P) {
+template <int CB, int NW>
+__global__ void __launch_bounds__(64 * NW, 2) f32_gconv_kernel(GcParams P) {
     extern __shared__ __attribute__((aligned(16))) float lds_f[];
     long long u = blockIdx.x;
     const int mt = (int)(u % P.MT); u /= P.MT;
@@ -212,7 +227,7 @@ __global__ void __launch_bounds__(256, 2) f32_gconv_kernel(GcParams P) {
     const int jht = (int)(u % P.JHT); u /= P.JHT;
     const int jd = (int)(u % P.Jd);
     const int n = (int)(u / P.Jd);
-    gconv_tile<CB>(P, lds_f, n, jd, jht, jwt, mt);
+    gconv_tile<CB, NW>(P, lds_f, n, jd, jht, jwt, mt);
 }
 
 // The parity classes of a stride-2 data gradient in one launch.  Workgroups are dealt to the 8 XCDs by index modulo
@@ -228,8 +243,8 @@ struct GcMulti {
 };
 static_assert(sizeof(GcMulti) <= 4096, "kernel arguments");
 
-template <int CB>
-__global__ void __launch_bounds__(256, 2) f32_gconv_classes_kernel(GcMulti Q) {
+template <int CB, int NW>
+__global__ void __launch_bounds__(64 * NW, 2) f32_gconv_classes_kernel(GcMulti Q) {
     extern __shared__ __attribute__((aligned(16))) float lds_f[];
     const long long r = blockIdx.x >> 3;
     const int cls = (int)(r % Q.ncls);
@@ -242,7 +257,7 @@ __global__ void __launch_bounds__(256, 2) f32_gconv_classes_kernel(GcMulti Q) {
     const int n = (int)(u / Q.Jd);
     const GcParams& P = Q.p[cls];
     if (mt >= P.MT || jwt >= P.JWT || jht >= P.JHT || jd >= P.Jd) return;   // (uniform over the workgroup)
-    gconv_tile<CB>(P, lds_f, n, jd, jht, jwt, mt);
+    gconv_tile<CB, NW>(P, lds_f, n, jd, jht, jwt, mt);
 }
 
 // wpack[t][k][m] (m padded to Mpad with zeros) from w[co][t][ci]; swap = 0: (k, m) = (ci, co); swap = 1: (k, m) = (co, ci)
@@ -639,8 +654,8 @@ static void gconv_tile_shape(GcParams* P) {
 static int gconv_attributes() {
     static std::atomic<bool> attr_set{false};   // set once per process; a second thread racing here repeats an idempotent call
     if (!attr_set) {
-        const void* fns[5] = {(const void*)f32_gconv_kernel<1>, (const void*)f32_gconv_kernel<2>, (const void*)f32_gconv_classes_kernel<1>,
-                              (const void*)f32_gconv_classes_kernel<2>, (const void*)f32_wgrad_kernel};
+        const void* fns[5] = {(const void*)f32_gconv_kernel<1, GC_NW1>, (const void*)f32_gconv_kernel<2, GC_NW2>, (const void*)f32_gconv_classes_kernel<1, GC_NW1>,
+                              (const void*)f32_gconv_classes_kernel<2, GC_NW2>, (const void*)f32_wgrad_kernel};
         for (const void* f : fns) {
             hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
             if (e != hipSuccess) { note_hip_error(e); return MI3D_ERR_HIP; }
@@ -702,8 +717,8 @@ static int launch_gconv(GcParams& P, hipStream_t s) {
     if (blocks <= 0) return MI3D_OK;
     if (blocks > 0x7fffffffll) return MI3D_ERR_UNSUPPORTED;
     if ((st = gconv_attributes())) return st;
-    if (CB == 2) f32_gconv_kernel<2><<<(unsigned)blocks, 256, lds, s>>>(P);
-    else f32_gconv_kernel<1><<<(unsigned)blocks, 256, lds, s>>>(P);
+    if (CB == 2) f32_gconv_kernel<2, GC_NW2><<<(unsigned)blocks, 64 * GC_NW2, lds, s>>>(P);
+    else f32_gconv_kernel<1, GC_NW1><<<(unsigned)blocks, 64 * GC_NW1, lds, s>>>(P);
     return check_launch();
 }
 
@@ -737,8 +752,8 @@ static int launch_gconv_classes(GcMulti& Q, hipStream_t s) {
     if (blocks > 0x7fffffffll) return MI3D_ERR_UNSUPPORTED;
     int st = gconv_attributes();
     if (st) return st;
-    if (CB == 2) f32_gconv_classes_kernel<2><<<(unsigned)blocks, 256, lds, s>>>(Q);
-    else f32_gconv_classes_kernel<1><<<(unsigned)blocks, 256, lds, s>>>(Q);
+    if (CB == 2) f32_gconv_classes_kernel<2, GC_NW2><<<(unsigned)blocks, 64 * GC_NW2, lds, s>>>(Q);
+    else f32_gconv_classes_kernel<1, GC_NW1><<<(unsigned)blocks, 64 * GC_NW1, lds, s>>>(Q);
     return check_launch();
 }
 
