@@ -540,6 +540,9 @@ size_t pack_bytes(const Geom& g, int pass) {
 void wgrad_layout(const Geom& g, WgParams* P) {
     P->TR = 2;
     P->TW = (g.sW == 1) ? 32 : 16;
+    // (2x2x2 stride 2: one tap per wave and 16 MFMAs per tile and wave leave the kernel waiting for its staging; 32 columns
+    // double the work per staged tile, and the x patch of two planes still leaves room for two workgroups per CU)
+    if (g.sW == 2 && g.kD <= 2 && g.kH <= 2 && g.kW <= 2 && g.Wo % 32 == 0) P->TW = 32;   // (1.43 -> 1.27 ms at 192^3)
     // Stride 1: 4 rows x 16 columns where that leaves fewer positions outside the plane (48 = 3 x 16 columns); planes
     // narrower than 32 take their own (even) width and as many rows as make about 64 positions (24 x 2, 12 x 4): the
     // contraction runs over pairs of neighbouring columns, so any even width works (24^3 layers 70 -> 88 TFLOP/s).
