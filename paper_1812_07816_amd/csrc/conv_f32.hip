@@ -62,6 +62,7 @@ struct GcParams {
     signed char tapidx[MAX_TAPS];            // its index in the layer's own tap order (slot in wpack)
     int hmin, wmin, prows, pcols;          // smallest offsets; patch extent in LDS
     int TJH, TJW, LW;                      // tile rows, columns (a power of two, 2^LW)
+    int flat;                              // 1: row-major tiles over the whole width (TJW = Jw, JWT = 1, JHT = tiles of 256 positions)
     int CK;                                // contracted channels per stage (even)
 };
 
@@ -77,10 +78,28 @@ __device__ __forceinline__ void gconv_tile(const GcParams& P, float* lds_f, int 
     const int xp = P.CK + 1;                                   // channel pitch of a staged voxel (odd: no bank conflicts)
     float* xs = lds_f;                                         // [prows][pcols][CK + 1]
     float* ws = lds_f + ((P.prows * P.pcols * xp + 3) & ~3);   // [taps of the group][CK][32 CB]
-    const int jh0 = jht * P.TJH, jw0 = jwt * P.TJW, m0 = mt * 32 * CB;
-    // this lane's position in each of the wave's two blocks
-    const int f0 = (NB * wave) * 32 + ln, f1 = NB == 2 ? f0 + 32 : f0;
-    const int tr0 = f0 >> P.LW, tc0 = f0 & (P.TJW - 1), tr1 = f1 >> P.LW, tc1 = f1 & (P.TJW - 1);
+    const int m0 = mt * 32 * CB;
+    // this lane's position in each of the wave's blocks: row and column inside the tile, inside the plane or not;
+    // active: the wave has a position inside the plane (its first one; waves without one issue no MFMA)
+    int jh0, jw0, tr0, tc0, tr1, tc1;
+    bool ok0, ok1, active;
+    {
+        const int f0 = (NB * wave) * 32 + ln, f1 = NB == 2 ? f0 + 32 : f0;
+        if (P.flat) {
+            const int base = jht * 256, total = P.Jh * P.Jw;
+            jh0 = base / P.Jw; jw0 = 0;
+            const int r0 = (base + f0) / P.Jw, r1 = (base + f1) / P.Jw;
+            ok0 = base + f0 < total; ok1 = base + f1 < total;
+            tr0 = ok0 ? r0 - jh0 : 0; tc0 = ok0 ? base + f0 - r0 * P.Jw : 0;     // (outside: any staged position)
+            tr1 = ok1 ? r1 - jh0 : 0; tc1 = ok1 ? base + f1 - r1 * P.Jw : 0;
+            active = base + (NB * wave) * 32 < total;
+        } else {
+            jh0 = jht * P.TJH; jw0 = jwt * P.TJW;
+            tr0 = f0 >> P.LW; tc0 = f0 & (P.TJW - 1); tr1 = f1 >> P.LW; tc1 = f1 & (P.TJW - 1);
+            ok0 = jh0 + tr0 < P.Jh && jw0 + tc0 < P.Jw; ok1 = jh0 + tr1 < P.Jh && jw0 + tc1 < P.Jw;
+            active = jh0 + (((NB * wave) * 32) >> P.LW) < P.Jh;
+        }
+    }
 
     f32x16 acc[NB][CB];
 #pragma unroll
@@ -137,6 +156,7 @@ __device__ __forceinline__ void gconv_tile(const GcParams& P, float* lds_f, int 
             }
             __syncthreads();
             if (!plane_ok) continue;   // zero padding plane: nothing to add (uniform over the workgroup)
+            if (!active) continue;     // no block of this wave has a position inside the plane (uniform over the wave)
             // ---- MFMAs: per tap and pair of contracted channels, 2 rows x CB blocks
             for (int tp = 0; tp < nt; ++tp) {
                 const int dh = P.th[t0 + tp] - P.hmin, dw = P.tw[t0 + tp] - P.wmin;
@@ -174,7 +194,7 @@ __device__ __forceinline__ void gconv_tile(const GcParams& P, float* lds_f, int 
 #pragma unroll
     for (int r = 0; r < NB; ++r) {
         const int jh = jh0 + (r ? tr1 : tr0), jw = jw0 + (r ? tc1 : tc0);
-        if (jh >= P.Jh || jw >= P.Jw) continue;
+        if (!(r ? ok1 : ok0)) continue;
         const int od = P.osd * jd + P.ood, oh = P.osh * jh + P.ooh, ow = P.osw * jw + P.oow;
         const long long vox = (((long long)n * P.Do + od) * P.Ho + oh) * P.Wo + ow;
 #pragma unroll
@@ -645,14 +665,27 @@ bool f32_takes_halves(const Geom& g, int pass) {   // virtual concatenation: hal
     return f32_supported(g, pass) && g.Cin % 64 == 0;
 }
 
-// 8 x 32 unless 16 x 16 covers the iteration plane with fewer positions outside it
+// 8 x 32 unless 16 x 16 covers the iteration plane with fewer positions outside it; planes narrower than 32 columns in
+// row-major order over their whole width (tile k = positions 256 k .. 256 k + 255 of the plane, whatever rows they fall
+// in: a 24 x 24 plane is 18 full blocks of 32 positions instead of 24 blocks three quarters full; TJH = the most rows 256
+// consecutive positions can touch)
 static void gconv_tile_shape(GcParams* P) {
+    P->flat = P->Jw < 32 ? 1 : 0;
+    if (P->flat) {
+        P->TJW = P->Jw;
+        P->TJH = 255 / P->Jw + 2;
+        if (P->TJH > P->Jh) P->TJH = P->Jh;
+        P->LW = 0;
+        return;
+    }
     auto padded = [&](int th, int tw) { return (long long)((P->Jh + th - 1) / th * th) * ((P->Jw + tw - 1) / tw * tw); };
     const bool square = padded(16, 16) < padded(8, 32);
     P->TJH = square ? 16 : 8;
     P->TJW = square ? 16 : 32;
     P->LW = square ? 4 : 5;
 }
+static int gconv_row_tiles(const GcParams& P) { return P.flat ? (P.Jh * P.Jw + 255) / 256 : (P.Jh + P.TJH - 1) / P.TJH; }
+static int gconv_col_tiles(const GcParams& P) { return P.flat ? 1 : (P.Jw + P.TJW - 1) / P.TJW; }
 
 static int gconv_attributes() {
     static std::atomic<bool> attr_set{false};   // set once per process; a second thread racing here repeats an idempotent call
@@ -688,8 +721,8 @@ static int gconv_blocks_of_channels(const GcParams& P, long long tiles, int ntap
 
 // tiles, channel chunk and LDS bytes of one launch (or one class of a launch) for CB blocks of output channels
 static int gconv_prepare(GcParams& P, int CB, size_t* lds) {
-    P.JHT = (P.Jh + P.TJH - 1) / P.TJH;
-    P.JWT = (P.Jw + P.TJW - 1) / P.TJW;
+    P.JHT = gconv_row_tiles(P);
+    P.JWT = gconv_col_tiles(P);
     P.MT = (P.Mpad + 32 * CB - 1) / (32 * CB);
     // contracted channels per stage: the largest even chunk that keeps the tiles of a stage within LDS_SOFT
     int max_group = 1;
@@ -712,7 +745,7 @@ static int gconv_prepare(GcParams& P, int CB, size_t* lds) {
 }
 
 static int launch_gconv(GcParams& P, hipStream_t s) {
-    const int CB = gconv_blocks_of_channels(P, (long long)P.N * P.Jd * ((P.Jh + P.TJH - 1) / P.TJH) * ((P.Jw + P.TJW - 1) / P.TJW), P.ntaps);
+    const int CB = gconv_blocks_of_channels(P, (long long)P.N * P.Jd * gconv_row_tiles(P) * gconv_col_tiles(P), P.ntaps);
     size_t lds = 0;
     int st = gconv_prepare(P, CB, &lds);
     if (st) return st;
@@ -732,7 +765,7 @@ static int launch_gconv_classes(GcMulti& Q, hipStream_t s) {
     int ntaps = 0;
     for (int c = 0; c < Q.ncls; ++c) {
         const GcParams& P = Q.p[c];
-        const long long tc = (long long)P.N * P.Jd * ((P.Jh + P.TJH - 1) / P.TJH) * ((P.Jw + P.TJW - 1) / P.TJW);
+        const long long tc = (long long)P.N * P.Jd * gconv_row_tiles(P) * gconv_col_tiles(P);
         tiles += tc;
         ntaps = ntaps > P.ntaps ? ntaps : P.ntaps;
     }
