@@ -300,11 +300,24 @@ class UNetStep:
         off = ptr - self.arena.data_ptr()
         return self.arena[off:off + _numel(shape) * self.esize].view(self.dtype).view(shape)
 
+    def _timed_wait(self, call):
+        """Runs an engine call that may make the compute stream wait (for a copy into or out of the arena); while a
+        calibration records, brackets it with events so that the wait can be taken off the op's measured duration."""
+        rec = getattr(self, "_wait_events", None)
+        if rec is None:
+            return call()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        r = call()
+        e1.record()
+        rec.append((self._cur_op, e0, e1))
+        return r
+
     def _produce(self, s):
         if self.engine is None:
             s.view = torch.empty(s.shape, dtype=self.dtype, device="cuda")
         else:
-            s.ptr = self.engine.alloc_tensor(s.id)
+            s.ptr = self._timed_wait(lambda: self.engine.alloc_tensor(s.id))
             s.view = self._view(s.ptr, s.shape)
         return s.view
 
@@ -335,7 +348,7 @@ class UNetStep:
 
     def _need(self, s):
         if self.engine is not None and self.planned[s.id] and not getattr(s, "_waited", False):
-            self.engine.wait_in(s.id)
+            self._timed_wait(lambda: self.engine.wait_in(s.id))
             s._waited = True
         if s.view is None and self.recomputed[s.id]:
             op = self.producer[s.id]
@@ -405,6 +418,7 @@ class UNetStep:
         # forward
         for f, op in enumerate(self.ops):
             k = op["kind"]
+            self._cur_op = f
             if k == "input":
                 self._produce(op["out"]).copy_(self.x_in)
                 if trace is not None:
@@ -457,6 +471,7 @@ class UNetStep:
         d_pair = None          # skip half of the gradient of a virtual concatenation, between its convolution and its cat op
         for f in range(self.n_fwd - 1, -1, -1):
             op, b = self.ops[f], self.bwd_op(f)
+            self._cur_op = b
             self._before_bwd_op(b)
             k = op["kind"]
             if trace is not None and da is not None:
@@ -587,13 +602,13 @@ class UNetStep:
             else:
                 glue.sgd_update(self.w32, self.dw32, self.w16, self.lr)
 
-    def calibrate(self, link_gbs=55.0, passes=2):
+    def calibrate(self, link_gbs=55.0, passes=1):
         """Runs one step with per-op events, hands the measured op durations and the host-link rate to the
-        planner and plans again: the swap-ins are then scheduled by time instead of by op count.  The op durations of
-        the first pass contain the waits of the plan they were measured under (swap-ins issued a fixed number of ops
-        ahead), which makes the time line look longer than it will be and the swap-ins come late; the second pass
-        measures under the first pass's plan, where those waits are gone (fp32, 192^3, 16 GB: one pass left a 28 ms
-        wait for a level-0 tensor, 13 % of the step; two passes none)."""
+        planner and plans again: the swap-ins are then scheduled by time instead of by op count.  What the compute
+        stream spent waiting for copies under the plan it was measured with (swap-ins issued a fixed number of ops
+        ahead, blocks still being copied out) is taken off the op durations: left in, the time line looks longer than
+        it will be and the timed swap-ins come late (fp32, 192^3, 16 GB: a 28 ms wait for a level-0 tensor, 13 % of
+        the step)."""
         if self.engine is None:
             return
         self.link_gbs = link_gbs
@@ -603,11 +618,17 @@ class UNetStep:
     def _calibrate_once(self, link_gbs):
         self.run(update=False)
         tl = []
-        self.run(update=False, timeline=tl)
+        self._wait_events = []
+        try:
+            self.run(update=False, timeline=tl)
+        finally:
+            waits, self._wait_events = self._wait_events, None
         torch.cuda.synchronize()
         t = [tl[0][2].elapsed_time(ev) for _, _, ev in tl]
         ms = [max(t[i + 1] - t[i], 0.0) for i in range(len(t) - 1)]     # forward ops, then backward ops in timeline order
         assert len(ms) == self.n_ops
+        for op_index, e0, e1 in waits:
+            ms[op_index] = max(ms[op_index] - e0.elapsed_time(e1), 0.0)
         e = self.engine
         # a re-computation costs what the forward op took; the backward ops that ran one under the current plan are
         # charged without it (the planner adds the cost of the re-computations it chooses itself)
