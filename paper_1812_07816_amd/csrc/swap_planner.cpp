@@ -193,13 +193,28 @@ int plan_swaps(std::vector<PlanTensor>& ts, const std::vector<size_t>& transient
         recomputable[i] = ok;
     }
     const bool can_swap = p.eviction != MI3D_EVICT_RECOMPUTE;
-    // hybrid: re-compute where that costs less compute time than the swap-in alone would take on the link
+    // hybrid: a copy that hides behind compute costs nothing, a re-computation always costs its compute time.  With
+    // measured op times the plan is first made with swapping alone; it stands if it meets the budget and its copies fit
+    // into the shorter of the two passes (swap-outs ride under the forward pass, swap-ins under the backward pass; 90 %
+    // of it: the copies do not pack perfectly).  Otherwise, and without op times, a tensor is re-computed where that
+    // costs less compute time than its swap-in alone would take on the link.  (Filling the link first and re-computing
+    // only the rest was tried: under tight budgets the swapped tensors, which come back early and leave late, cost
+    // more footprint than the re-computed ones and the plans no longer met the budgets the per-tensor rule meets.)
+    const double link_rate = p.link_gbs > 0.f ? (double)p.link_gbs : 50.0;
+    auto copy_ms = [&](int i) { return (double)ts[i].bytes / (link_rate * 1e6); };
+    double link_room_ms = 0.0;
+    if (timed) {
+        double fwd = 0.0, bwd = 0.0;
+        for (int op = 0; op < n_ops && op < (int)p.op_ms->size(); ++op) (op < p.n_fwd_ops ? fwd : bwd) += (double)(*p.op_ms)[op];
+        link_room_ms = 0.9 * std::min(fwd, bwd);
+    }
+    bool swap_only = false;      // first attempt of the hybrid with op times
     auto wants_recompute = [&](int i) {
-        if (p.eviction == MI3D_EVICT_SWAP || !recomputable[i]) return false;
+        if (p.eviction == MI3D_EVICT_SWAP || !recomputable[i] || swap_only) return false;
         if (!can_swap) return true;
-        const double link = p.link_gbs > 0.f ? (double)p.link_gbs : 50.0;
-        return (double)ts[i].recompute_ms < (double)ts[i].bytes / (link * 1e6);
+        return (double)ts[i].recompute_ms < copy_ms(i);
     };
+    auto plan_swap = [&](int i) { ts[i].planned = true; };
     auto dep_recomputed = [&](int i) {
         for (int d : ts[i].dep)
             for (const PlanTensor& u : ts)
@@ -224,6 +239,16 @@ int plan_swaps(std::vector<PlanTensor>& ts, const std::vector<size_t>& transient
         if (eligible(ts[i])) order.push_back(i);
     std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return ts[a].produce_op < ts[b].produce_op; });
 
+    if (p.policy != MI3D_SWAP_ALL && p.policy != MI3D_SWAP_FIRST_N && p.policy != MI3D_SWAP_BUDGET) return MI3D_ERR_INVALID_ARG;
+    const int attempts = (p.eviction == MI3D_EVICT_HYBRID && timed) ? 2 : 1;
+    for (int attempt = 0; attempt < attempts; ++attempt) {
+    swap_only = attempts == 2 && attempt == 0;
+    for (PlanTensor& t : ts) {
+        t.planned = false;
+        t.recompute = false;
+        t.bwd_first_use_op = t.bwd_first_use_reg;
+        t.prefetch_op = prefetch_by_ops(t, p);
+    }
     if (p.policy == MI3D_SWAP_ALL || p.policy == MI3D_SWAP_FIRST_N) {
         int n = (int)order.size();
         if (p.policy == MI3D_SWAP_FIRST_N && p.n_tensors >= 0) n = std::min<int>(p.n_tensors, n);
@@ -232,7 +257,7 @@ int plan_swaps(std::vector<PlanTensor>& ts, const std::vector<size_t>& transient
             // re-computing a tensor from one that is re-computed itself would bring the whole chain back at
             // once: such a tensor is swapped instead (or kept, where swapping is not allowed)
             if (wants_recompute(i) && !dep_recomputed(i)) ts[i].recompute = true;
-            else if (can_swap) ts[i].planned = true;
+            else if (can_swap) plan_swap(i);
         }
         reschedule();
     } else if (p.policy == MI3D_SWAP_BUDGET) {
@@ -262,7 +287,7 @@ int plan_swaps(std::vector<PlanTensor>& ts, const std::vector<size_t>& transient
             }
             if (best < 0) break;  // nothing more can lower this peak
             if (wants_recompute(best)) ts[best].recompute = true;
-            else ts[best].planned = true;
+            else plan_swap(best);
             apply_deps(ts, p);
             chosen.push_back(best);
         }
@@ -280,8 +305,6 @@ int plan_swaps(std::vector<PlanTensor>& ts, const std::vector<size_t>& transient
                 }
             }
         }
-    } else {
-        return MI3D_ERR_INVALID_ARG;
     }
 
     // The swap set is chosen with the op-count rule (least residency, least traffic); only then are its swap-ins
@@ -302,6 +325,14 @@ int plan_swaps(std::vector<PlanTensor>& ts, const std::vector<size_t>& transient
             ts[pick].prefetch_op = std::min(at + 1, prefetch_by_ops(ts[pick], p));
         }
     }
+    if (swap_only) {
+        // does swapping alone do, hidden?  Else the second attempt decides tensor by tensor.
+        double load = 0.0;
+        for (int i = 0; i < (int)ts.size(); ++i)
+            if (ts[i].planned) load += 1.15 * copy_ms(i);
+        if (load <= link_room_ms && peak(ts, transient, n_ops, false, nullptr) <= p.budget_bytes) break;
+    }
+    }   // attempts
 
     size_t off = 0;
     int n = 0;

@@ -301,8 +301,8 @@ class UNetStep:
         return self.arena[off:off + _numel(shape) * self.esize].view(self.dtype).view(shape)
 
     def _timed_wait(self, call):
-        """Runs an engine call that may make the compute stream wait (for a copy into or out of the arena); while a
-        calibration records, brackets it with events so that the wait can be taken off the op's measured duration."""
+        """Runs an engine call that may make the compute stream wait for a swap-in; while a calibration records,
+        brackets it with events so that the wait can be taken off the op's measured duration."""
         rec = getattr(self, "_wait_events", None)
         if rec is None:
             return call()
@@ -317,7 +317,7 @@ class UNetStep:
         if self.engine is None:
             s.view = torch.empty(s.shape, dtype=self.dtype, device="cuda")
         else:
-            s.ptr = self._timed_wait(lambda: self.engine.alloc_tensor(s.id))
+            s.ptr = self.engine.alloc_tensor(s.id)
             s.view = self._view(s.ptr, s.shape)
         return s.view
 
@@ -340,7 +340,9 @@ class UNetStep:
     def _before_bwd_op(self, op):
         if self.engine is None:
             return
-        for s in self.saved:
+        # (swap-ins that fall on the same op go out in the order of their first use: they share one copy stream, and
+        # under a link-bound plan most of them fall on the first backward op)
+        for s in sorted(self.saved, key=lambda t: min(t.bwd_ops)):
             if self.planned[s.id] and self.prefetch[s.id] == op:
                 s.ptr = self.engine.alloc_tensor(s.id)
                 self.engine.swap_in(s.id, s.ptr)
@@ -605,10 +607,11 @@ class UNetStep:
     def calibrate(self, link_gbs=55.0, passes=1):
         """Runs one step with per-op events, hands the measured op durations and the host-link rate to the
         planner and plans again: the swap-ins are then scheduled by time instead of by op count.  What the compute
-        stream spent waiting for copies under the plan it was measured with (swap-ins issued a fixed number of ops
-        ahead, blocks still being copied out) is taken off the op durations: left in, the time line looks longer than
-        it will be and the timed swap-ins come late (fp32, 192^3, 16 GB: a 28 ms wait for a level-0 tensor, 13 % of
-        the step)."""
+        stream spent waiting for swap-ins under the plan it was measured with (issued a fixed number of ops ahead) is
+        taken off the backward ops' durations: left in, the time line looks longer than it will be and the timed
+        swap-ins come late (fp32, 192^3, 16 GB: a 28 ms wait for a level-0 tensor, 13 % of the step).  The forward
+        ops keep their waits for places in the arena that are still being copied out: the placement model counts on
+        them (taken off as well, the link-bound bf16 plans got 12 % slower)."""
         if self.engine is None:
             return
         self.link_gbs = link_gbs

@@ -339,14 +339,33 @@ def test_hybrid_recomputes_cheap_tensors_and_swaps_dear_ones():
         assert (recomputed, planned) == (({1}, set()) if expect_recompute else (set(), {1}))
         assert e.stats()["planned_peak_bytes"] <= 1600
         e.close()
-    # with a measured link rate the comparison is cost against bytes / rate: 600 bytes at 1e-3 GB/s take 0.6 ms
-    for cost, expect in ((0.5, True), (0.7, False)):
+    # with measured op times and link rate: 600 bytes at 1e-3 GB/s take 0.6 ms.  Where that hides behind the passes
+    # (6 ops of 1 ms each way) the tensor is swapped whatever its re-computation costs; where the passes are too short
+    # to hide it (6 ops of 0.05 ms), the comparison is cost against bytes / rate
+    for op_ms, cost, expect in ((1.0, 0.5, False), (1.0, 0.0, False), (0.05, 0.5, True), (0.05, 0.7, False)):
         e = make(ts, n_fwd, n_ops, budget_bytes=1600, lookahead=1)
         e.set_eviction(sw.EVICT_HYBRID)
-        e.set_op_times([1.0] * n_ops, 1e-3)
+        e.set_op_times([op_ms] * n_ops, 1e-3)
         e.set_recompute(1, cost, 0)
-        e.plan()
-        assert e.is_recomputed(1) == expect and e.is_planned(1) == (not expect)
+        e.plan(allow_over_budget=True)
+        assert e.is_recomputed(1) == expect and e.is_planned(1) == (not expect), (op_ms, cost)
+        e.close()
+
+
+def test_hybrid_swaps_everything_where_the_link_hides_it_and_decides_per_tensor_where_not():
+    """Seven equal tensors that all have to go, all but the first cheaper to re-compute than to copy.  Seven copies
+    of 1.15 x 0.9 ms fit into 90 % of a 14 ms pass: swapping alone stands.  They do not fit into 90 % of a 7 ms pass:
+    every other tensor is re-computed (one whose source is re-computed itself is swapped)."""
+    n_fwd, n_ops, ts = real_chain([900] * 7)
+    for op_ms, want_planned, want_recomputed in ((2.0, {0, 1, 2, 3, 4, 5, 6}, set()), (1.0, {0, 2, 4, 6}, {1, 3, 5})):
+        e = make(ts, n_fwd, n_ops, budget_bytes=900 * 3, lookahead=1, policy=sw.POLICY_ALL)
+        e.set_eviction(sw.EVICT_HYBRID)
+        e.set_op_times([op_ms] * n_ops, 1e-3)
+        for i in range(1, 7):
+            e.set_recompute(i, 0.1, i - 1)
+        e.plan(allow_over_budget=True)
+        planned, recomputed, _, _ = plan_state(e, ts)
+        assert planned == want_planned and recomputed == want_recomputed, (op_ms, planned, recomputed)
         e.close()
 
 

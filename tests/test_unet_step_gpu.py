@@ -349,14 +349,19 @@ def test_recomputed_and_hybrid_steps_are_bit_identical(unet):
     fixed = probe._transient(0)           # weights, workspace, labels: nothing the plan can move
     probe.close()
 
-    def check(st, budget):
+    def check(st, budget, hybrid):
         for calibrated in (False, True):
             if calibrated:
                 st.calibrate()
             st.run(update=False)
             torch.cuda.synchronize()
             s = st.engine.stats()
-            assert s["n_recompute"] > 0 and st.n_recomputed == s["n_recompute"], (s, st.n_recomputed)
+            assert st.n_recomputed == s["n_recompute"], (s, st.n_recomputed)
+            # (with measured op times the hybrid swaps what the link can hide and may need no re-computation at all)
+            if calibrated and hybrid:
+                assert s["n_recompute"] + s["n_planned"] > 0, s
+            else:
+                assert s["n_recompute"] > 0, s
             if budget is not None and st.plan_status == 0:
                 assert s["planned_peak_bytes"] <= budget and s["peak_arena_bytes"] <= s["planned_peak_bytes"] - fixed
                 assert s["n_arena_overflow"] == 0 and s["arena_high_water_bytes"] <= s["static_arena_bytes"]
@@ -372,13 +377,13 @@ def test_recomputed_and_hybrid_steps_are_bit_identical(unet):
                 break
             st.close()
         assert st.plan_status == 0, "no cut of the movable bytes is feasible"
-        s = check(st, budget)
+        s = check(st, budget, eviction == sw.EVICT_HYBRID)
         print("eviction", eviction, "cut", cut, "recomputed", s["n_recompute"], "swapped", s["n_planned"])
         if eviction == sw.EVICT_RECOMPUTE:
             assert s["n_swapped_out"] == 0
         st.close()
         st = unet.UNetStep(N, vol, CH, ws, xd, ld, swap=True, budget_bytes=None, lookahead=2, policy=sw.POLICY_ALL, eviction=eviction)
-        s = check(st, None)
+        s = check(st, None, eviction == sw.EVICT_HYBRID)
         assert (s["n_swapped_out"] == 0) if eviction == sw.EVICT_RECOMPUTE else (s["n_swapped_out"] > 0 and s["n_swapped_out"] == s["n_swapped_in"])
         st.close()
 
