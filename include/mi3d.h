@@ -154,7 +154,9 @@ int mi3d_conv3d_wgrad_pair(const mi3d_conv_desc *desc, const void *x_lo, const v
  * that produced the skip tensor a_in is applied:
  *   dx = (bf16(dgrad(dy, w)) + add) * (a_in > 0 ? 1 : slope),
  * fp32 arithmetic on the bf16-rounded data gradient, one more rounding: the bits of mi3d_conv3d_dgrad followed by
- * mi3d_skip_grad.  bf16 only, 0 <= slope <= 1 (1: the sum alone).  The stride-2 MFMA data-gradient kernels do it in
+ * mi3d_skip_grad.  0 <= slope <= 1 (1: the sum alone).  bf16 descriptors, and fp32 descriptors that run on the fp32
+ * matrix-core kernels (kernel extent <= 3, stride <= 2; all in fp32, no intermediate rounding); other fp32
+ * descriptors: MI3D_ERR_INVALID_ARG.  The stride-2 MFMA data-gradient kernels do it in
  * their store path or while they add their fp32 partial gradients; other geometries run the two passes.  Same
  * workspace as mi3d_conv3d_dgrad; add and a_in must not overlap dx. */
 int mi3d_conv3d_dgrad_skip(const mi3d_conv_desc *desc, const void *dy, const void *w, const void *add, const void *a_in,
@@ -193,7 +195,8 @@ int mi3d_conv3d_dgrad_insums(const mi3d_conv_desc *desc, const void *dy, const v
 
 /* Convolution followed by the network's LeakyReLU (Section 4.1) in one call:
  * y = lrelu(conv(x, w)), lrelu(v) = v > 0 ? v : slope * v, applied to the fp32
- * accumulator before the single rounding to bf16.  bf16 only, 0 <= slope < 1
+ * accumulator before the single rounding to bf16.  0 <= slope < 1; bf16
+ * descriptors, and fp32 descriptors that run on the fp32 matrix-core kernels
  * (else MI3D_ERR_INVALID_ARG).  The MFMA forward kernels apply it in their
  * epilogue; other geometries run the convolution and one elementwise pass.
  * Same workspace as mi3d_conv3d_fwd. */
@@ -205,7 +208,8 @@ int mi3d_conv3d_fwd_lrelu(const mi3d_conv_desc *desc, const void *x, const void 
  * bf16, shape of x) is the activated input of the layer, whose sign is that of
  * the pre-activation.  Kernels that sum fp32 partial gradients apply the factor
  * before the single rounding to bf16; other geometries run mi3d_conv3d_dgrad
- * and mi3d_leaky_relu_bwd (two roundings).  bf16 only, 0 <= slope < 1.  dz_in
+ * and mi3d_leaky_relu_bwd (two roundings).  0 <= slope < 1; bf16 descriptors,
+ * and fp32 descriptors that run on the fp32 matrix-core kernels (a_in fp32).  dz_in
  * must not alias a_in.  Same workspace as mi3d_conv3d_dgrad. */
 int mi3d_conv3d_dgrad_lrelu(const mi3d_conv_desc *desc, const void *dy, const void *w, const void *a_in, float slope,
                             void *dx, void *ws, size_t ws_bytes, void *stream);
