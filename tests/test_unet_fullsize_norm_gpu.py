@@ -158,7 +158,9 @@ def test_normalised_layer_of_the_headline_step(device, f32, name):
     total = dw.numel()
     widx = np.unique(np.concatenate([[0, total - 1], np.random.default_rng(32).integers(0, total, size=16)]))
     # (fp32: an entry is a sum of 1.4e7 products accumulated in fp32, 1.4e4 of them one after the other in a workgroup's
-    # accumulator and the 512 to 1024 partial sums in order; measured 1e-6 to 2e-4 of the entries' size)
+    # accumulator and the 512 to 1024 partial sums in order.  Behind a normalisation the gradient dz sums to zero over
+    # each channel, so the entries are what is left of heavy cancellation: measured 1e-6 to 2e-4 of the entries' size,
+    # the same with the partial sums added in double)
     _check(f"{name} wgrad", _pick(dw, widx), oc.wgrad_at(g, a_in, dz, widx), 1e-3 if f32 else tol)
 
 
