@@ -70,9 +70,9 @@ __device__ __forceinline__ f32x16 mfma2(float a, float b, f32x16 c) { return __b
 
 // The work of one workgroup: tile (n, jd, jht, jwt) of the iteration space, output channel block mt.
 // CB = 32-wide blocks of output channels per workgroup
-template <int CB, int NW>
+template <int CB, int NW, int NB>
 __device__ __forceinline__ void gconv_tile(const GcParams& P, float* lds_f, int n, int jd, int jht, int jwt, int mt) {
-    constexpr int NB = 8 / NW, NT = 64 * NW;   // blocks of 32 positions per wave, threads
+    constexpr int NT = 64 * NW;   // threads; NB = blocks of 32 positions per wave (the tile has NW * NB * 32 positions)
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     const int ln = lane & 31, half = lane >> 5;
     const int xp = P.CK + 1;                                   // channel pitch of a staged voxel (odd: no bank conflicts)
@@ -238,7 +238,7 @@ __device__ __forceinline__ void gconv_tile(const GcParams& P, float* lds_f, int 
     }
 }
 
-template <int CB, int NW>
+template <int CB, int NW, int NB>
 __global__ void __launch_bounds__(64 * NW, 2) f32_gconv_kernel(GcParams P) {
     extern __shared__ __attribute__((aligned(16))) float lds_f[];
     long long u = blockIdx.x;
@@ -247,7 +247,7 @@ __global__ void __launch_bounds__(64 * NW, 2) f32_gconv_kernel(GcParams P) {
     const int jht = (int)(u % P.JHT); u /= P.JHT;
     const int jd = (int)(u % P.Jd);
     const int n = (int)(u / P.Jd);
-    gconv_tile<CB, NW>(P, lds_f, n, jd, jht, jwt, mt);
+    gconv_tile<CB, NW, NB>(P, lds_f, n, jd, jht, jwt, mt);
 }
 
 // The parity classes of a stride-2 data gradient in one launch.  Workgroups are dealt to the 8 XCDs by index modulo
@@ -277,7 +277,7 @@ __global__ void __launch_bounds__(64 * NW, 2) f32_gconv_classes_kernel(GcMulti Q
     const int n = (int)(u / Q.Jd);
     const GcParams& P = Q.p[cls];
     if (mt >= P.MT || jwt >= P.JWT || jht >= P.JHT || jd >= P.Jd) return;   // (uniform over the workgroup)
-    gconv_tile<CB, NW>(P, lds_f, n, jd, jht, jwt, mt);
+    gconv_tile<CB, NW, 8 / NW>(P, lds_f, n, jd, jht, jwt, mt);
 }
 
 // wpack[t][k][m] (m padded to Mpad with zeros) from w[co][t][ci]; swap = 0: (k, m) = (ci, co); swap = 1: (k, m) = (co, ci)
@@ -669,7 +669,7 @@ bool f32_takes_halves(const Geom& g, int pass) {   // virtual concatenation: hal
 // row-major order over their whole width (tile k = positions 256 k .. 256 k + 255 of the plane, whatever rows they fall
 // in: a 24 x 24 plane is 18 full blocks of 32 positions instead of 24 blocks three quarters full; TJH = the most rows 256
 // consecutive positions can touch)
-static void gconv_tile_shape(GcParams* P) {
+static void gconv_tile_shape(GcParams* P, bool big_tiles) {
     P->flat = P->Jw < 32 ? 1 : 0;
     if (P->flat) {
         P->TJW = P->Jw;
@@ -683,6 +683,10 @@ static void gconv_tile_shape(GcParams* P) {
     P->TJH = square ? 16 : 8;
     P->TJW = square ? 16 : 32;
     P->LW = square ? 4 : 5;
+    // Layers with at most 32 output channels (one block per workgroup whatever the grid): 16 x 32 tiles for eight waves
+    // where they cover the plane as well; the weights of a stage then serve 512 positions and the halo rows are 2 in
+    // 18 instead of 2 in 10 (32->32 at 192^3 +2 %).
+    if (!square && big_tiles && P->M <= 32 && padded(16, 32) == padded(8, 32)) P->TJH = 16;
 }
 static int gconv_row_tiles(const GcParams& P) { return P.flat ? (P.Jh * P.Jw + 255) / 256 : (P.Jh + P.TJH - 1) / P.TJH; }
 static int gconv_col_tiles(const GcParams& P) { return P.flat ? 1 : (P.Jw + P.TJW - 1) / P.TJW; }
@@ -690,8 +694,8 @@ static int gconv_col_tiles(const GcParams& P) { return P.flat ? 1 : (P.Jw + P.TJ
 static int gconv_attributes() {
     static std::atomic<bool> attr_set{false};   // set once per process; a second thread racing here repeats an idempotent call
     if (!attr_set) {
-        const void* fns[5] = {(const void*)f32_gconv_kernel<1, GC_NW1>, (const void*)f32_gconv_kernel<2, GC_NW2>, (const void*)f32_gconv_classes_kernel<1, GC_NW1>,
-                              (const void*)f32_gconv_classes_kernel<2, GC_NW2>, (const void*)f32_wgrad_kernel};
+        const void* fns[6] = {(const void*)f32_gconv_kernel<1, GC_NW1, 2>, (const void*)f32_gconv_kernel<2, GC_NW2, 1>, (const void*)f32_gconv_classes_kernel<1, GC_NW1>,
+                              (const void*)f32_gconv_classes_kernel<2, GC_NW2>, (const void*)f32_wgrad_kernel, (const void*)f32_gconv_kernel<1, 8, 2>};
         for (const void* f : fns) {
             hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
             if (e != hipSuccess) { note_hip_error(e); return MI3D_ERR_HIP; }
@@ -753,8 +757,9 @@ static int launch_gconv(GcParams& P, hipStream_t s) {
     if (blocks <= 0) return MI3D_OK;
     if (blocks > 0x7fffffffll) return MI3D_ERR_UNSUPPORTED;
     if ((st = gconv_attributes())) return st;
-    if (CB == 2) f32_gconv_kernel<2, GC_NW2><<<(unsigned)blocks, 64 * GC_NW2, lds, s>>>(P);
-    else f32_gconv_kernel<1, GC_NW1><<<(unsigned)blocks, 64 * GC_NW1, lds, s>>>(P);
+    if (CB == 2) f32_gconv_kernel<2, GC_NW2, 1><<<(unsigned)blocks, 64 * GC_NW2, lds, s>>>(P);
+    else if (P.TJH == 16 && P.TJW == 32) f32_gconv_kernel<1, 8, 2><<<(unsigned)blocks, 512, lds, s>>>(P);   // 512 positions
+    else f32_gconv_kernel<1, GC_NW1, 2><<<(unsigned)blocks, 64 * GC_NW1, lds, s>>>(P);
     return check_launch();
 }
 
@@ -862,7 +867,7 @@ int f32_conv(const Geom& g, int pass, const void* in, const void* w, void* out, 
                 P.gstart[P.ngroups] = P.ntaps;
                 if (P.ntaps == 0) { hmin = hmax = wmin = wmax = 0; }   // a class no tap reaches: zeros (plus the epilogue)
                 P.hmin = hmin; P.wmin = wmin;
-                gconv_tile_shape(&P);
+                gconv_tile_shape(&P, !classes && sD * sH * sW == 1);
                 P.prows = (P.TJH - 1) * P.ish + (hmax - hmin) + 1;
                 P.pcols = (P.TJW - 1) * P.isw + (wmax - wmin) + 1;
                 P.wpack = (const float*)ws;
