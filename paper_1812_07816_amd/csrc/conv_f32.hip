@@ -563,16 +563,22 @@ void wgrad_layout(const Geom& g, WgParams* P) {
     // (2x2x2 stride 2: one tap per wave and 16 MFMAs per tile and wave leave the kernel waiting for its staging; 32 columns
     // double the work per staged tile, and the x patch of two planes still leaves room for two workgroups per CU)
     if (g.sW == 2 && g.kD <= 2 && g.kH <= 2 && g.kW <= 2 && g.Wo % 32 == 0) P->TW = 32;   // (1.43 -> 1.27 ms at 192^3)
-    // Stride 1: 4 rows x 16 columns where that leaves fewer positions outside the plane (48 = 3 x 16 columns); planes
-    // narrower than 32 take their own (even) width and as many rows as make about 64 positions (24 x 2, 12 x 4): the
-    // contraction runs over pairs of neighbouring columns, so any even width works (24^3 layers 70 -> 88 TFLOP/s).
+    // Stride 1.  Width: 32 columns, 16 where that leaves fewer positions outside the plane (48 = 3 x 16 columns); planes
+    // narrower than 32 take their own (even) width: the contraction runs over pairs of neighbouring columns, so any
+    // even width works (24^3 layers 70 -> 88 TFLOP/s).  Rows: as many as make about 96 positions (3 x 32, 6 x 16,
+    // 4 x 24) while the dy tile and the ring of x planes leave room for two workgroups per CU (78 KB each), fewer
+    // where that divides the height better: more MFMAs per staged tile and fewer halo rows per row (2 x 32 -> 3 x 32:
+    // 100 -> 106 TFLOP/s on the 192^3 layers).
     auto padded = [&](int tr, int tw) { return (long long)((g.Ho + tr - 1) / tr * tr) * ((g.Wo + tw - 1) / tw * tw); };
-    if (g.sW == 1 && g.Wo < 32) {
-        P->TW = (g.Wo + 1) & ~1;
-        P->TR = 64 / P->TW > 2 ? 64 / P->TW : 2;
-        if (P->TR > 8) P->TR = 8;
-        while (P->TR > 2 && padded(P->TR, P->TW) > padded(P->TR - 1, P->TW)) --P->TR;   // (fewer rows where they divide the height better)
-    } else if (g.sW == 1 && padded(4, 16) < padded(2, 32)) { P->TR = 4; P->TW = 16; }
+    if (g.sW == 1) {
+        if (g.Wo < 32) P->TW = (g.Wo + 1) & ~1;
+        else if (padded(2, 16) < padded(2, 32)) P->TW = 16;
+        auto lds = [&](int tr) { return ((size_t)tr * P->TW + (size_t)g.kD * ((tr - 1) * g.sH + g.kH) * ((P->TW - 1) * g.sW + g.kW)) * 32 * sizeof(float); };
+        int tr = 96 / P->TW;
+        tr = tr < 2 ? 2 : (tr > 8 ? 8 : tr);
+        while (tr > 2 && (lds(tr) > 78 * 1024 || padded(tr, P->TW) > padded(tr - 1, P->TW))) --tr;
+        P->TR = tr;
+    }
     P->prows = (P->TR - 1) * g.sH + g.kH;
     P->pcols = (P->TW - 1) * g.sW + g.kW;
     P->pcols_magic = 65536u / (unsigned)P->pcols + 1u;
