@@ -659,7 +659,7 @@ class UNetStep:
         internal = self.budget
         peak = None
         self.fit_log = []     # per round: planner budget, plan status, tensors swapped, re-computed, measured peak
-        for _ in range(rounds):
+        for r in range(rounds + 4):
             torch.cuda.synchronize()
             torch.cuda.reset_peak_memory_stats()
             self.run(update=False)
@@ -676,8 +676,11 @@ class UNetStep:
                 break
             self.engine.set_budget(internal)
             self._read_plan(self.engine.plan(allow_over_budget=True))
-            if getattr(self, "link_gbs", None):
-                self._calibrate_once(self.link_gbs)     # op durations under the new plan (other tensors wait now)
+            # op durations under the new plan (other tensors wait now); the last rounds keep the op durations they
+            # have, so that the plan only moves with the budget (a re-measured time line can move a swap-in by an op
+            # and the footprint by some MB, which kept one run from settling within 0.1 % of its budget)
+            if getattr(self, "link_gbs", None) and r < rounds:
+                self._calibrate_once(self.link_gbs)
         self.measured_peak_bytes = peak
         return peak
 
